@@ -1,0 +1,135 @@
+/* rgc.h -- C ABI of the MI355X (gfx950) Residual Gradient Compression library.
+ *
+ * The library implements, on ONE GPU, the per-iteration hot path of RedSync's Residual
+ * Gradient Compression (arXiv 1808.04357):
+ *
+ *   compress   (Algorithm 1, inner loop over layers):  V += G;  Masks = select(V, D);
+ *              message = compress(V . Masks);  V = V . (1 - Masks)
+ *   decompress (Section 2.3, last paragraph before the cost model): the N gathered sparse
+ *              messages are added into a dense array.
+ *
+ * Every function returns an int status (RGC_OK = 0, negative = error) unless stated; no C++
+ * exception crosses this boundary.  All tensor and message pointers are DEVICE pointers into
+ * memory owned by the caller (hipMalloc / a PyTorch-ROCm tensor); descriptor arrays
+ * (rgc_layer[], rgc_msg[], pointer and size arrays) are HOST memory and are copied before
+ * the call returns.  Work is enqueued on the caller's HIP stream; nothing synchronises the
+ * stream or the device.  The context owns only scratch memory and speed hints: results never
+ * depend on what an earlier call left in it.
+ */
+#ifndef RGC_H_
+#define RGC_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- status codes ------------------------------------------------------------------- */
+#define RGC_OK       0
+#define RGC_EINVAL  (-1) /* null pointer, n < 1, n >= 2^31, k < 1, k > n, negative count,
+                            unknown flag bit, too many layers/workers for the context     */
+#define RGC_ENOMEM  (-2) /* scratch sized at rgc_create is too small for this call, or an
+                            allocation failed in rgc_create                                */
+#define RGC_EHIP    (-3) /* a HIP runtime call failed; rgc_strerror gives its text         */
+
+/* ---- flags -------------------------------------------------------------------------- */
+/* rgc_compress_layers */
+#define RGC_NO_MOMENTUM_MASK 0x1u /* keep the velocity u of sent entries (default clears it) */
+#define RGC_NO_HINTS         0x2u /* ignore and do not update the per-layer speed hints:
+                                     every layer takes the hint-free multi-pass path        */
+/* rgc_decompress_accumulate: exactly one of the two */
+#define RGC_OVERWRITE        0x10u /* dense = acc * scale                                   */
+#define RGC_ADD_TO_DST       0x20u /* dense = dense + acc * scale (two roundings, no fma)   */
+
+typedef struct rgc_ctx rgc_ctx; /* opaque */
+
+/* One layer of a compression call (host struct holding device pointers).
+ * Section 2, Algorithm 1: G_j is `grad`, V_j is `residual`; Section 2.5 names the
+ * momentum-corrected variant, whose velocity is `momentum`.  Tensors are flat, contiguous
+ * fp32; only 4-byte alignment is required (16-byte aligned tensors take the fast loads). */
+typedef struct {
+  const float* grad;      /* [n] read only                                                  */
+  float*       residual;  /* [n] in/out: V on entry, masked V + G (or V + u) on return      */
+  float*       momentum;  /* [n] in/out velocity u, or NULL for the plain variant           */
+  int64_t      n;         /* 1 <= n < 2^31                                                  */
+  int32_t      k;         /* 1 <= k <= n, number of entries to send (rgc_k_for_density)     */
+  int32_t*     out_idx;   /* [k] layer-local 0-based indices, strictly ascending            */
+  float*       out_val;   /* [k] out_val[j] = accumulated value at out_idx[j], sign kept    */
+  int32_t*     out_count; /* [1] device word, receives k: the message's length element
+                             (Section 2.3: "an initial element, which indicates the length") */
+} rgc_layer;
+
+/* One (worker, layer) message handed to decompression: `count` entries, `idx` strictly
+ * ascending and < n of that layer (what rgc_compress_layers emits).  count is a host value. */
+typedef struct {
+  const int32_t* idx;
+  const float*   val;
+  int32_t        count;
+} rgc_msg;
+
+/* Create a context on HIP device `device_id` able to handle calls whose layers hold at most
+ * `max_total_elems` elements in total, in at most `max_layers` layers.  Allocates all scratch
+ * once (about 0.15 byte per element plus 24 KiB per layer); later calls allocate nothing for
+ * compression.  Decompression grows its own table on first use and when a call needs more.
+ * Errors: RGC_EINVAL (null out, sizes < 1), RGC_ENOMEM, RGC_EHIP. */
+int rgc_create(rgc_ctx** out, int device_id, int64_t max_total_elems, int32_t max_layers);
+
+/* Free everything the context owns.  The caller must have synchronised the streams it used. */
+int rgc_destroy(rgc_ctx* ctx);
+
+/* k = max(1, ceil(n * density_ppm / 1e6)) clipped to n, in integer arithmetic (Section 2.1
+ * uses density 0.1 % = 1000 ppm; n = 1,048,576 gives 1049).  Returns 0 for n < 1. */
+int32_t rgc_k_for_density(int64_t n, uint32_t density_ppm);
+
+/* Compression step of Algorithm 1 for `num_layers` independent layers, batched.
+ * For each layer:  a = residual + grad            (plain)
+ *              or  u = fma(momentum, u, grad) with one rounding; a = residual + u
+ *   the k entries of largest |a| are selected exactly (order of the IEEE bit pattern with the
+ *   sign cleared; equal magnitudes: lowest index first; NaN above Inf above finite);
+ *   out_idx/out_val/out_count receive them in ascending index order;
+ *   residual = +0.0f at the selected entries and a elsewhere; the velocity is cleared at the
+ *   selected entries too unless RGC_NO_MOMENTUM_MASK.
+ * `momentum` (the factor m) is used only by layers whose momentum pointer is non-NULL.
+ * Tensors of different layers, and the tensors of one layer, must not overlap.
+ * The first call for a layer set (and any call whose cached threshold hint turns out
+ * unusable) takes several passes over the data; later calls take one.  The result is the
+ * same bit for bit either way.
+ * Errors (nothing is enqueued, no buffer is modified): RGC_EINVAL, RGC_ENOMEM, RGC_EHIP. */
+int rgc_compress_layers(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers,
+                        float momentum, uint32_t flags, void* hip_stream);
+
+/* Decompression of Section 2.3 for `num_layers` dense buffers and `num_workers` workers.
+ * msgs is worker-major: msgs[w * num_layers + l] is worker w's message for layer l.
+ * For every layer l and element i:  acc = +0;  for w = 0 .. num_workers-1 in this order:
+ * acc += val (fp32) for the entry of worker w with idx == i, if any;  then
+ *   RGC_OVERWRITE : dense[l][i] = acc * scale        (every element is written)
+ *   RGC_ADD_TO_DST: dense[l][i] = dense[l][i] + acc * scale
+ * The summation order is fixed, so the result does not depend on scheduling.
+ * dense: host array of num_layers device pointers; n: host array of their lengths.
+ * Precondition (not checked): each message's idx strictly ascending and < n[l].
+ * Errors (nothing enqueued): RGC_EINVAL, RGC_ENOMEM, RGC_EHIP. */
+int rgc_decompress_accumulate(rgc_ctx* ctx, const rgc_msg* msgs, int32_t num_workers,
+                              int32_t num_layers, float* const* dense, const int64_t* n,
+                              float scale, uint32_t flags, void* hip_stream);
+
+/* Speed-hint control (never changes results).  rgc_reset_hints forgets every cached
+ * threshold, so the next call behaves like a first call.  rgc_poison_hints overwrites the
+ * cached thresholds with deliberately wrong values (mode 0: far too high, 1: far too low,
+ * 2: pseudo-random) -- a test hook proving that results do not depend on them. */
+int rgc_reset_hints(rgc_ctx* ctx);
+int rgc_poison_hints(rgc_ctx* ctx, int mode, void* hip_stream);
+
+/* Copies per-layer path statistics of the LAST compression call into `out` (host memory,
+ * int32[num_layers]): 0 = one-pass hinted path, 1 = hint-free multi-pass path, 2 = hinted
+ * pass missed and the multi-pass path re-ran on the updated residual.  Synchronises
+ * `hip_stream`.  A diagnostic for tests and benchmarks. */
+int rgc_last_paths(rgc_ctx* ctx, int32_t* out, int32_t num_layers, void* hip_stream);
+
+/* Text for a status code; for RGC_EHIP the text of the last HIP error seen by this thread. */
+const char* rgc_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RGC_H_ */

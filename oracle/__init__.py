@@ -1,0 +1,141 @@
+"""ctypes access to the CPU oracle (``rgc_oracle.cpp``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by the smoke check and by the
+benchmark's ``cpu_baseline`` leg.  The product package never imports this
+module and this module never imports the product package.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "rgc_oracle.cpp")
+_LIB = os.path.join(_HERE, "librgc_oracle.so")
+
+_f32p = ctypes.POINTER(ctypes.c_float)
+_i32p = ctypes.POINTER(ctypes.c_int32)
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with g++ (no fast-math, no contraction)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["g++", "-std=c++17", "-O2", "-ffp-contract=off", "-fPIC", "-shared",
+               "-pthread", "-o", _LIB, _SRC]
+        subprocess.check_call(cmd)
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        L.rgc_oracle_k_for_density.restype = ctypes.c_int32
+        L.rgc_oracle_k_for_density.argtypes = [ctypes.c_int64, ctypes.c_uint32]
+        for name in ("rgc_oracle_compress_layer", "rgc_oracle_compress_layer_bruteforce"):
+            fn = getattr(L, name)
+            fn.restype = ctypes.c_int
+            fn.argtypes = [_f32p, _f32p, _f32p, ctypes.c_int64, ctypes.c_int32, ctypes.c_float,
+                           ctypes.c_int, _i32p, _f32p, _i32p]
+        L.rgc_oracle_compress_layers.restype = ctypes.c_int
+        L.rgc_oracle_compress_layers.argtypes = [
+            ctypes.POINTER(_f32p), ctypes.POINTER(_f32p), ctypes.POINTER(_f32p),
+            ctypes.POINTER(ctypes.c_int64), _i32p, ctypes.c_int32, ctypes.c_float, ctypes.c_int,
+            ctypes.POINTER(_i32p), ctypes.POINTER(_f32p), _i32p, ctypes.c_int32]
+        L.rgc_oracle_decompress.restype = ctypes.c_int
+        L.rgc_oracle_decompress.argtypes = [
+            ctypes.POINTER(_i32p), ctypes.POINTER(_f32p), _i32p, ctypes.c_int32, _f32p,
+            ctypes.c_int64, ctypes.c_float, ctypes.c_int]
+        L.rgc_oracle_hardware_threads.restype = ctypes.c_int32
+        L.rgc_oracle_hardware_threads.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _f32(a: np.ndarray) -> "_f32p":
+    assert a.dtype == np.float32 and a.flags.c_contiguous
+    return a.ctypes.data_as(_f32p)
+
+
+def _i32(a: np.ndarray) -> "_i32p":
+    assert a.dtype == np.int32 and a.flags.c_contiguous
+    return a.ctypes.data_as(_i32p)
+
+
+def k_for_density(n: int, ppm: int = 1000) -> int:
+    return int(lib().rgc_oracle_k_for_density(int(n), int(ppm)))
+
+
+def hardware_threads() -> int:
+    return int(lib().rgc_oracle_hardware_threads())
+
+
+def compress_layer(grad: np.ndarray, residual: np.ndarray, k: int,
+                   momentum: Optional[np.ndarray] = None, m: float = 0.0,
+                   mask_momentum: bool = True, bruteforce: bool = False
+                   ) -> Tuple[np.ndarray, np.ndarray, int]:
+    """Compress one layer IN PLACE (residual, momentum are updated).
+
+    Returns (out_idx int32[k], out_val float32[k], count).
+    """
+    n = grad.size
+    out_idx = np.empty(k, dtype=np.int32)
+    out_val = np.empty(k, dtype=np.float32)
+    out_cnt = np.zeros(1, dtype=np.int32)
+    fn = lib().rgc_oracle_compress_layer_bruteforce if bruteforce else lib().rgc_oracle_compress_layer
+    rc = fn(_f32(grad), _f32(residual), _f32(momentum) if momentum is not None else None,
+            n, int(k), float(m), 1 if mask_momentum else 0, _i32(out_idx), _f32(out_val),
+            _i32(out_cnt))
+    if rc != 0:
+        raise ValueError("oracle rejected the arguments")
+    return out_idx, out_val, int(out_cnt[0])
+
+
+def compress_layers(grads: Sequence[np.ndarray], residuals: Sequence[np.ndarray],
+                    ks: Sequence[int], momenta: Optional[Sequence[np.ndarray]] = None,
+                    m: float = 0.0, mask_momentum: bool = True, threads: int = 1
+                    ) -> List[Tuple[np.ndarray, np.ndarray, int]]:
+    """Compress a whole layer set in place, optionally on several host threads."""
+    L = len(grads)
+    out_idx = [np.empty(int(k), dtype=np.int32) for k in ks]
+    out_val = [np.empty(int(k), dtype=np.float32) for k in ks]
+    out_cnt = np.zeros(L, dtype=np.int32)
+    g = (_f32p * L)(*[_f32(a) for a in grads])
+    r = (_f32p * L)(*[_f32(a) for a in residuals])
+    mo = (_f32p * L)(*[_f32(a) for a in momenta]) if momenta is not None else None
+    oi = (_i32p * L)(*[_i32(a) for a in out_idx])
+    ov = (_f32p * L)(*[_f32(a) for a in out_val])
+    n = (ctypes.c_int64 * L)(*[int(a.size) for a in grads])
+    kk = (ctypes.c_int32 * L)(*[int(k) for k in ks])
+    rc = lib().rgc_oracle_compress_layers(g, r, mo, n, kk, L, float(m),
+                                          1 if mask_momentum else 0, oi, ov, _i32(out_cnt),
+                                          int(threads))
+    if rc != 0:
+        raise ValueError("oracle rejected the arguments")
+    return [(out_idx[l], out_val[l], int(out_cnt[l])) for l in range(L)]
+
+
+def decompress(idx: Sequence[np.ndarray], val: Sequence[np.ndarray], n: int, scale: float,
+               dense: Optional[np.ndarray] = None) -> np.ndarray:
+    """Decompress one layer.  ``dense=None`` overwrites into a fresh buffer, else
+    adds into ``dense`` in place (and returns it)."""
+    N = len(idx)
+    add = dense is not None
+    if dense is None:
+        dense = np.empty(n, dtype=np.float32)
+    ip = (_i32p * max(N, 1))(*[_i32(a) for a in idx])
+    vp = (_f32p * max(N, 1))(*[_f32(a) for a in val])
+    cnt = np.array([a.size for a in idx], dtype=np.int32) if N else np.zeros(1, np.int32)
+    rc = lib().rgc_oracle_decompress(ip, vp, _i32(cnt), N, _f32(dense), int(n), float(scale),
+                                     1 if add else 0)
+    if rc != 0:
+        raise ValueError("oracle rejected the arguments")
+    return dense
