@@ -32,6 +32,7 @@ extern "C" {
 #define RGC_ENOMEM  (-2) /* scratch sized at rgc_create is too small for this call, or an
                             allocation failed in rgc_create                                */
 #define RGC_EHIP    (-3) /* a HIP runtime call failed; rgc_strerror gives its text         */
+#define RGC_EINTERNAL (-4) /* a kernel reported an inconsistency (a bug; results invalid)  */
 
 /* ---- flags -------------------------------------------------------------------------- */
 /* rgc_compress_layers */
@@ -70,8 +71,8 @@ typedef struct {
 
 /* Create a context on HIP device `device_id` able to handle calls whose layers hold at most
  * `max_total_elems` elements in total, in at most `max_layers` layers.  Allocates all scratch
- * once (about 0.15 byte per element plus 24 KiB per layer); later calls allocate nothing for
- * compression.  Decompression grows its own table on first use and when a call needs more.
+ * once (about 0.15 byte per element plus 57 KiB per layer); later compression calls allocate
+ * device memory only when they see a layer list (pointers, sizes) not seen recently.  Decompression grows its own table on first use and when a call needs more.
  * Errors: RGC_EINVAL (null out, sizes < 1), RGC_ENOMEM, RGC_EHIP. */
 int rgc_create(rgc_ctx** out, int device_id, int64_t max_total_elems, int32_t max_layers);
 
@@ -120,10 +121,16 @@ int rgc_decompress_accumulate(rgc_ctx* ctx, const rgc_msg* msgs, int32_t num_wor
 int rgc_reset_hints(rgc_ctx* ctx);
 int rgc_poison_hints(rgc_ctx* ctx, int mode, void* hip_stream);
 
+/* Runs a one-workgroup kernel that checks the wave64 primitives the kernels rely on (DPP
+ * prefix scan, ballot ranks) against values computed on the host.  Synchronises `hip_stream`.
+ * Returns RGC_OK, RGC_EINTERNAL on a mismatch, or RGC_EHIP. */
+int rgc_selftest(rgc_ctx* ctx, void* hip_stream);
+
 /* Copies per-layer path statistics of the LAST compression call into `out` (host memory,
  * int32[num_layers]): 0 = one-pass hinted path, 1 = hint-free multi-pass path, 2 = hinted
  * pass missed and the multi-pass path re-ran on the updated residual.  Synchronises
- * `hip_stream`.  A diagnostic for tests and benchmarks. */
+ * `hip_stream`.  Returns RGC_EINTERNAL if any kernel of an earlier call flagged an internal
+ * inconsistency.  A diagnostic for tests and benchmarks. */
 int rgc_last_paths(rgc_ctx* ctx, int32_t* out, int32_t num_layers, void* hip_stream);
 
 /* Text for a status code; for RGC_EHIP the text of the last HIP error seen by this thread. */

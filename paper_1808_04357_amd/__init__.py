@@ -1,0 +1,12 @@
+"""MI355X-native Residual Gradient Compression hot path (RedSync, arXiv 1808.04357).
+
+The package is a thin ctypes binding over ``librgc.so`` (hand-written HIP for gfx950, C ABI in
+``include/rgc.h``).  It only marshals arguments: every step of the path runs in the library's
+kernels.  PyTorch-ROCm tensors are used for device memory and streams.  There is no CPU
+fallback: if the library is missing, importing the binding's entry points raises.
+"""
+from .binding import (  # noqa: F401
+    RGC_ADD_TO_DST, RGC_NO_HINTS, RGC_NO_MOMENTUM_MASK, RGC_OVERWRITE, Context, LayerList,
+    MessageList, RgcError, library_path, load_library, rgc_compress_layers,
+    rgc_decompress_accumulate, rgc_k_for_density,
+)

@@ -1,0 +1,560 @@
+// Host side of librgc: the C ABI declared in include/rgc.h.  Validates arguments, turns the
+// caller's layer / message lists into device descriptor tables (cached while the lists do not
+// change) and enqueues the kernels.  No kernel arithmetic lives here.
+#include "../../include/rgc.h"
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <memory>
+#include <new>
+#include <numeric>
+#include <string>
+#include <vector>
+
+#include "rgc_internal.h"
+
+using namespace rgc;
+
+namespace {
+
+thread_local std::string g_hip_error = "no HIP error recorded";
+
+int fail_hip(hipError_t e, const char* what) {
+  char buf[256];
+  std::snprintf(buf, sizeof buf, "%s: %s", what, hipGetErrorString(e));
+  g_hip_error = buf;
+  return RGC_EHIP;
+}
+
+#define RGC_HIP(call)                                   \
+  do {                                                  \
+    hipError_t e_ = (call);                             \
+    if (e_ != hipSuccess) return fail_hip(e_, #call);   \
+  } while (0)
+
+constexpr uint32_t kChunk = 8192;          // elements per wave-chunk
+constexpr uint32_t kCap = kChunk / 64;     // candidate slots per wave-chunk
+constexpr int kPlanCache = 8;
+constexpr int kLaunches = 6;               // streaming pass + at most five phase launches
+
+struct DeviceGuard {
+  int prev = -1;
+  bool ok = false;
+  explicit DeviceGuard(int dev) {
+    if (hipGetDevice(&prev) == hipSuccess && hipSetDevice(dev) == hipSuccess) ok = true;
+  }
+  ~DeviceGuard() {
+    if (prev >= 0) (void)hipSetDevice(prev);
+  }
+};
+
+template <typename T>
+struct DevBuf {
+  T* p = nullptr;
+  size_t n = 0;
+  hipError_t alloc(size_t count) {
+    release();
+    if (count == 0) count = 1;
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&p), count * sizeof(T));
+    if (e == hipSuccess) n = count; else p = nullptr;
+    return e;
+  }
+  void release() {
+    if (p) (void)hipFree(p);
+    p = nullptr;
+    n = 0;
+  }
+};
+
+struct PinnedBuf {
+  void* p = nullptr;
+  size_t bytes = 0;
+  hipError_t ensure(size_t b) {
+    if (b <= bytes) return hipSuccess;
+    if (p) (void)hipHostFree(p);
+    p = nullptr;
+    bytes = 0;
+    hipError_t e = hipHostMalloc(&p, b, hipHostMallocDefault);
+    if (e == hipSuccess) bytes = b; else p = nullptr;
+    return e;
+  }
+  void release() {
+    if (p) (void)hipHostFree(p);
+    p = nullptr;
+    bytes = 0;
+  }
+};
+
+// One cached translation of a layer list into device tables.
+struct CompressPlan {
+  std::vector<rgc_layer> key;       // the caller's list this plan was built from
+  DevBuf<LayerDesc> d_layers;
+  DevBuf<uint32_t> d_wg2layer;
+  PinnedBuf staging;
+  hipEvent_t uploaded = nullptr;    // recorded after the uploads
+  uint32_t num_wgs = 0;
+  uint64_t last_use = 0;
+  bool valid = false;
+};
+
+struct DecompressPlan {
+  std::vector<rgc_msg> key_msgs;
+  std::vector<float*> key_dense;
+  std::vector<int64_t> key_n;
+  int32_t workers = 0, layers = 0;
+  DevBuf<unsigned char> d_tables;   // MsgDesc[], TileDesc[], BlockDesc[], layer_tiles[]
+  DevBuf<uint32_t> d_tab;
+  PinnedBuf staging;
+  hipEvent_t uploaded = nullptr;
+  DecompressArgs args{};
+  bool valid = false;
+};
+
+}  // namespace
+
+struct rgc_ctx {
+  int device = 0;
+  int64_t max_total = 0;
+  int32_t max_layers = 0;
+  uint32_t wc_max = 0;
+  DevBuf<LayerState> d_state;
+  DevBuf<uint32_t> d_hist, d_coarse, d_cand_cnt, d_wc_a, d_wc_b, d_err;
+  DevBuf<unsigned long long> d_members;
+  DevBuf<uint2> d_slots;
+  CompressPlan plans[kPlanCache];
+  uint64_t tick = 0;
+  std::vector<std::pair<int64_t, int32_t>> hint_sig;   // (n, k) per layer slot the hints belong to
+  bool hints_reset = true;
+  int32_t last_layers = 0;
+  DecompressPlan dplan;
+};
+
+namespace {
+
+int build_compress_plan(rgc_ctx* ctx, CompressPlan& P, const rgc_layer* layers, int32_t L,
+                        hipStream_t stream) {
+  if (P.uploaded) RGC_HIP(hipEventSynchronize(P.uploaded));   // an older upload may still read staging
+  else RGC_HIP(hipEventCreateWithFlags(&P.uploaded, hipEventDisableTiming));
+  P.valid = false;
+  // workgroups are handed out largest layer first so that the long per-layer tails start early
+  std::vector<int32_t> order(L);
+  std::iota(order.begin(), order.end(), 0);
+  std::stable_sort(order.begin(), order.end(),
+                   [&](int32_t a, int32_t b) { return layers[a].n > layers[b].n; });
+  std::vector<LayerDesc> desc(L);
+  uint32_t wc = 0, wg = 0;
+  for (int32_t o = 0; o < L; ++o) {
+    const int32_t l = order[o];
+    const rgc_layer& in = layers[l];
+    LayerDesc& d = desc[l];
+    d.grad = in.grad;
+    d.resid = in.residual;
+    d.mom = in.momentum;
+    d.out_idx = in.out_idx;
+    d.out_val = in.out_val;
+    d.out_count = in.out_count;
+    d.n = static_cast<uint32_t>(in.n);
+    d.k = static_cast<uint32_t>(in.k);
+    d.wc_first = wc;
+    d.wc_count = static_cast<uint32_t>((in.n + kChunk - 1) / kChunk);
+    d.wg_first = wg;
+    d.wg_count = (d.wc_count + kWavesPerBlock - 1) / kWavesPerBlock;
+    const uintptr_t bits = reinterpret_cast<uintptr_t>(in.grad) | reinterpret_cast<uintptr_t>(in.residual) |
+                           reinterpret_cast<uintptr_t>(in.momentum);
+    d.vec_ok = (bits & 15u) == 0 ? 1u : 0u;
+    // speed-hint policy: aim the threshold at rank 2k + margin of this call, accept up to cmax
+    const uint64_t k = d.k;
+    const uint64_t margin = std::max<uint64_t>(k / 2, 32);
+    const uint64_t span = std::max<uint64_t>(d.n, kChunk);
+    const uint64_t target = 2 * k + margin;   // rank the next threshold is aimed at
+    const uint64_t per_chunk = (target * kChunk + span - 1) / span;         // expected per wave-chunk
+    d.hintable = (2 * per_chunk + 16 <= kCap) ? 1u : 0u;
+    d.margin = static_cast<uint32_t>(margin);
+    const uint64_t cmax = std::min<uint64_t>(2 * target, (kCap / 2) * (span / kChunk));
+    d.cmax = static_cast<uint32_t>(std::min<uint64_t>(cmax, 0x7FFFFFFFu));
+    wc += d.wc_count;
+    wg += d.wg_count;
+  }
+  if (wc > ctx->wc_max) return RGC_ENOMEM;
+  const size_t bytes_layers = sizeof(LayerDesc) * static_cast<size_t>(L);
+  const size_t bytes_map = sizeof(uint32_t) * static_cast<size_t>(wg);
+  RGC_HIP(P.staging.ensure(bytes_layers + bytes_map));
+  if (P.d_layers.n < static_cast<size_t>(L)) RGC_HIP(P.d_layers.alloc(static_cast<size_t>(L)));
+  if (P.d_wg2layer.n < wg) RGC_HIP(P.d_wg2layer.alloc(wg));
+  std::memcpy(P.staging.p, desc.data(), bytes_layers);
+  uint32_t* map = reinterpret_cast<uint32_t*>(static_cast<char*>(P.staging.p) + bytes_layers);
+  for (int32_t o = 0; o < L; ++o) {
+    const int32_t l = order[o];
+    for (uint32_t i = 0; i < desc[l].wg_count; ++i) map[desc[l].wg_first + i] = static_cast<uint32_t>(l);
+  }
+  RGC_HIP(hipMemcpyAsync(P.d_layers.p, P.staging.p, bytes_layers, hipMemcpyHostToDevice, stream));
+  RGC_HIP(hipMemcpyAsync(P.d_wg2layer.p, map, bytes_map, hipMemcpyHostToDevice, stream));
+  RGC_HIP(hipEventRecord(P.uploaded, stream));
+  P.key.assign(layers, layers + L);
+  P.num_wgs = wg;
+  P.valid = true;
+  return RGC_OK;
+}
+
+void destroy_plan(CompressPlan& P) {
+  if (P.uploaded) { (void)hipEventSynchronize(P.uploaded); (void)hipEventDestroy(P.uploaded); }
+  P.uploaded = nullptr;
+  P.d_layers.release();
+  P.d_wg2layer.release();
+  P.staging.release();
+  P.valid = false;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t rgc_k_for_density(int64_t n, uint32_t density_ppm) {
+  if (n < 1) return 0;
+  if (n >= (int64_t(1) << 31)) n = (int64_t(1) << 31) - 1;
+  const unsigned long long num = static_cast<unsigned long long>(n) * density_ppm;
+  unsigned long long k = (num + 999999ull) / 1000000ull;
+  if (k < 1) k = 1;
+  if (k > static_cast<unsigned long long>(n)) k = static_cast<unsigned long long>(n);
+  return static_cast<int32_t>(k);
+}
+
+const char* rgc_strerror(int status) {
+  switch (status) {
+    case RGC_OK: return "ok";
+    case RGC_EINVAL: return "invalid argument";
+    case RGC_ENOMEM: return "scratch too small or allocation failed";
+    case RGC_EHIP: return g_hip_error.c_str();
+    case RGC_EINTERNAL: return "internal inconsistency reported by a kernel";
+    default: return "unknown status";
+  }
+}
+
+int rgc_create(rgc_ctx** out, int device_id, int64_t max_total_elems, int32_t max_layers) {
+  if (!out) return RGC_EINVAL;
+  *out = nullptr;
+  if (max_total_elems < 1 || max_layers < 1 || device_id < 0) return RGC_EINVAL;
+  int ndev = 0;
+  RGC_HIP(hipGetDeviceCount(&ndev));
+  if (device_id >= ndev) return RGC_EINVAL;
+  DeviceGuard guard(device_id);
+  if (!guard.ok) return fail_hip(hipErrorInvalidDevice, "hipSetDevice");
+  std::unique_ptr<rgc_ctx> c(new (std::nothrow) rgc_ctx);
+  if (!c) return RGC_ENOMEM;
+  c->device = device_id;
+  c->max_total = max_total_elems;
+  c->max_layers = max_layers;
+  const uint64_t wc_max = static_cast<uint64_t>((max_total_elems + kChunk - 1) / kChunk) + static_cast<uint64_t>(max_layers);
+  if (wc_max > 0x7FFFFFFFull) return RGC_ENOMEM;
+  c->wc_max = static_cast<uint32_t>(wc_max);
+  const size_t L = static_cast<size_t>(max_layers);
+  hipError_t e = hipSuccess;
+  auto chk = [&](hipError_t r) { if (e == hipSuccess && r != hipSuccess) e = r; };
+  chk(c->d_state.alloc(L));
+  chk(c->d_hist.alloc(L * kHistBins));
+  chk(c->d_coarse.alloc(L * kCoarseBins));
+  chk(c->d_members.alloc(L * kMemberMax));
+  chk(c->d_cand_cnt.alloc(wc_max));
+  chk(c->d_wc_a.alloc(wc_max));
+  chk(c->d_wc_b.alloc(wc_max));
+  chk(c->d_slots.alloc(wc_max * kCap));
+  chk(c->d_err.alloc(1));
+  if (e == hipSuccess) chk(hipMemset(c->d_state.p, 0, sizeof(LayerState) * L));
+  if (e == hipSuccess) chk(hipMemset(c->d_hist.p, 0, sizeof(uint32_t) * L * kHistBins));
+  if (e == hipSuccess) chk(hipMemset(c->d_coarse.p, 0, sizeof(uint32_t) * L * kCoarseBins));
+  if (e == hipSuccess) chk(hipMemset(c->d_cand_cnt.p, 0, sizeof(uint32_t) * wc_max));
+  if (e == hipSuccess) chk(hipMemset(c->d_err.p, 0, sizeof(uint32_t)));
+  if (e == hipSuccess) chk(hipDeviceSynchronize());
+  if (e != hipSuccess) {
+    rgc_ctx* raw = c.release();
+    rgc_destroy(raw);
+    if (e == hipErrorOutOfMemory) { (void)hipGetLastError(); return RGC_ENOMEM; }
+    return fail_hip(e, "rgc_create allocation");
+  }
+  *out = c.release();
+  return RGC_OK;
+}
+
+int rgc_destroy(rgc_ctx* ctx) {
+  if (!ctx) return RGC_EINVAL;
+  DeviceGuard guard(ctx->device);
+  for (auto& P : ctx->plans) destroy_plan(P);
+  if (ctx->dplan.uploaded) { (void)hipEventSynchronize(ctx->dplan.uploaded); (void)hipEventDestroy(ctx->dplan.uploaded); }
+  ctx->dplan.d_tables.release();
+  ctx->dplan.d_tab.release();
+  ctx->dplan.staging.release();
+  ctx->d_state.release();
+  ctx->d_hist.release();
+  ctx->d_coarse.release();
+  ctx->d_members.release();
+  ctx->d_cand_cnt.release();
+  ctx->d_wc_a.release();
+  ctx->d_wc_b.release();
+  ctx->d_slots.release();
+  ctx->d_err.release();
+  delete ctx;
+  return RGC_OK;
+}
+
+int rgc_reset_hints(rgc_ctx* ctx) {
+  if (!ctx) return RGC_EINVAL;
+  ctx->hints_reset = true;
+  return RGC_OK;
+}
+
+int rgc_poison_hints(rgc_ctx* ctx, int mode, void* hip_stream) {
+  if (!ctx || mode < 0 || mode > 2) return RGC_EINVAL;
+  DeviceGuard guard(ctx->device);
+  RGC_HIP(launch_poison(ctx->d_state.p, static_cast<uint32_t>(ctx->max_layers), mode,
+                        static_cast<hipStream_t>(hip_stream)));
+  ctx->hints_reset = false;   // the poisoned values are to be used
+  return RGC_OK;
+}
+
+int rgc_compress_layers(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers, float momentum,
+                        uint32_t flags, void* hip_stream) {
+  if (!ctx || !layers || num_layers < 1 || num_layers > ctx->max_layers) return RGC_EINVAL;
+  if (flags & ~(RGC_NO_MOMENTUM_MASK | RGC_NO_HINTS)) return RGC_EINVAL;
+  int64_t total = 0;
+  for (int32_t l = 0; l < num_layers; ++l) {
+    const rgc_layer& a = layers[l];
+    if (!a.grad || !a.residual || !a.out_idx || !a.out_val || !a.out_count) return RGC_EINVAL;
+    if (a.n < 1 || a.n >= (int64_t(1) << 31) || a.k < 1 || a.k > a.n) return RGC_EINVAL;
+    const uintptr_t bits = reinterpret_cast<uintptr_t>(a.grad) | reinterpret_cast<uintptr_t>(a.residual) |
+                           reinterpret_cast<uintptr_t>(a.momentum) | reinterpret_cast<uintptr_t>(a.out_idx) |
+                           reinterpret_cast<uintptr_t>(a.out_val) | reinterpret_cast<uintptr_t>(a.out_count);
+    if (bits & 3u) return RGC_EINVAL;
+    total += a.n;
+  }
+  if (total > ctx->max_total) return RGC_ENOMEM;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return fail_hip(hipErrorInvalidDevice, "hipSetDevice");
+
+  // ---- find or build the plan for this exact layer list
+  CompressPlan* plan = nullptr;
+  for (auto& P : ctx->plans) {
+    if (P.valid && P.key.size() == static_cast<size_t>(num_layers) &&
+        std::memcmp(P.key.data(), layers, sizeof(rgc_layer) * num_layers) == 0) {
+      plan = &P;
+      break;
+    }
+  }
+  if (!plan) {
+    CompressPlan* victim = &ctx->plans[0];
+    for (auto& P : ctx->plans) {
+      if (!P.valid) { victim = &P; break; }
+      if (P.last_use < victim->last_use) victim = &P;
+    }
+    const int rc = build_compress_plan(ctx, *victim, layers, num_layers, stream);
+    if (rc != RGC_OK) return rc;
+    plan = victim;
+  }
+  plan->last_use = ++ctx->tick;
+
+  // ---- hints belong to a (n, k) sequence; anything else starts hint-free
+  bool sig_same = !ctx->hints_reset && ctx->hint_sig.size() == static_cast<size_t>(num_layers);
+  if (sig_same) {
+    for (int32_t l = 0; l < num_layers; ++l)
+      if (ctx->hint_sig[l].first != layers[l].n || ctx->hint_sig[l].second != layers[l].k) { sig_same = false; break; }
+  }
+  const bool no_hints = (flags & RGC_NO_HINTS) != 0;
+
+  CompressArgs A{};
+  A.layers = plan->d_layers.p;
+  A.state = ctx->d_state.p;
+  A.wg2layer = plan->d_wg2layer.p;
+  A.hist = ctx->d_hist.p;
+  A.coarse = ctx->d_coarse.p;
+  A.members = ctx->d_members.p;
+  A.cand_cnt = ctx->d_cand_cnt.p;
+  A.slots = ctx->d_slots.p;
+  A.wc_a = ctx->d_wc_a.p;
+  A.wc_b = ctx->d_wc_b.p;
+  A.errflag = ctx->d_err.p;
+  A.chunk = kChunk;
+  A.cap = kCap;
+  A.use_hints = (sig_same && !no_hints) ? 1u : 0u;
+  A.update_hints = no_hints ? 0u : 1u;
+  A.mask_momentum = (flags & RGC_NO_MOMENTUM_MASK) ? 0u : 1u;
+  A.m = momentum;
+  A.launch = 1;
+  RGC_HIP(launch_accumulate(A, plan->num_wgs, stream));
+  for (int launch = 2; launch <= kLaunches; ++launch) {
+    A.launch = static_cast<uint32_t>(launch);
+    RGC_HIP(launch_phase(A, plan->num_wgs, stream));
+  }
+  if (!no_hints) {
+    ctx->hint_sig.resize(num_layers);
+    for (int32_t l = 0; l < num_layers; ++l) ctx->hint_sig[l] = {layers[l].n, layers[l].k};
+    ctx->hints_reset = false;
+  }
+  ctx->last_layers = num_layers;
+  return RGC_OK;
+}
+
+int rgc_last_paths(rgc_ctx* ctx, int32_t* out, int32_t num_layers, void* hip_stream) {
+  if (!ctx || !out || num_layers < 1 || num_layers > ctx->max_layers) return RGC_EINVAL;
+  DeviceGuard guard(ctx->device);
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  std::vector<LayerState> st(num_layers);
+  uint32_t err = 0;
+  RGC_HIP(hipMemcpyAsync(st.data(), ctx->d_state.p, sizeof(LayerState) * num_layers, hipMemcpyDeviceToHost, stream));
+  RGC_HIP(hipMemcpyAsync(&err, ctx->d_err.p, sizeof err, hipMemcpyDeviceToHost, stream));
+  RGC_HIP(hipStreamSynchronize(stream));
+  for (int32_t l = 0; l < num_layers; ++l) out[l] = static_cast<int32_t>(st[l].path);
+  return err ? RGC_EINTERNAL : RGC_OK;
+}
+
+int rgc_selftest(rgc_ctx* ctx, void* hip_stream) {
+  if (!ctx) return RGC_EINVAL;
+  DeviceGuard guard(ctx->device);
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  DevBuf<uint32_t> io;
+  RGC_HIP(io.alloc(768));
+  std::vector<uint32_t> h(768, 0), ref(768, 0);
+  uint32_t x = 12345u, sum = 0;
+  for (int i = 0; i < 256; ++i) {
+    x = x * 1664525u + 1013904223u;
+    h[i] = (x >> 20) & 0x3FFu;
+  }
+  for (int i = 0; i < 256; ++i) { ref[i] = sum; sum += h[i]; }
+  ref[256] = sum;
+  for (int w = 0; w < 4; ++w) {
+    uint32_t r = 0;
+    for (int lane = 0; lane < 64; ++lane) { ref[512 + w * 64 + lane] = r; r += h[w * 64 + lane] & 1u; }
+  }
+  hipError_t e = hipMemcpyAsync(io.p, h.data(), 768 * 4, hipMemcpyHostToDevice, stream);
+  if (e == hipSuccess) e = launch_wave_scan_selftest(io.p, stream);
+  if (e == hipSuccess) e = hipMemcpyAsync(h.data(), io.p, 768 * 4, hipMemcpyDeviceToHost, stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(stream);
+  io.release();
+  if (e != hipSuccess) return fail_hip(e, "rgc_selftest");
+  for (int i = 0; i <= 256; ++i) if (h[i] != ref[i]) return RGC_EINTERNAL;
+  for (int i = 512; i < 768; ++i) if (h[i] != ref[i]) return RGC_EINTERNAL;
+  return RGC_OK;
+}
+
+int rgc_decompress_accumulate(rgc_ctx* ctx, const rgc_msg* msgs, int32_t num_workers, int32_t num_layers,
+                              float* const* dense, const int64_t* n, float scale, uint32_t flags,
+                              void* hip_stream) {
+  if (!ctx || !dense || !n || num_layers < 1 || num_workers < 0) return RGC_EINVAL;
+  if (num_workers > 0 && !msgs) return RGC_EINVAL;
+  if (flags != RGC_OVERWRITE && flags != RGC_ADD_TO_DST) return RGC_EINVAL;
+  if (static_cast<int64_t>(num_workers) * num_layers > (int64_t(1) << 24)) return RGC_EINVAL;
+  for (int32_t l = 0; l < num_layers; ++l) {
+    if (!dense[l] || n[l] < 1 || n[l] >= (int64_t(1) << 31)) return RGC_EINVAL;
+    if (reinterpret_cast<uintptr_t>(dense[l]) & 3u) return RGC_EINVAL;
+  }
+  const size_t NM = static_cast<size_t>(num_workers) * num_layers;
+  for (size_t i = 0; i < NM; ++i) {
+    const rgc_msg& m = msgs[i];
+    if (m.count < 0 || m.count > n[i % num_layers]) return RGC_EINVAL;
+    if (m.count > 0 && (!m.idx || !m.val)) return RGC_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(m.idx) | reinterpret_cast<uintptr_t>(m.val)) & 3u) return RGC_EINVAL;
+  }
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return fail_hip(hipErrorInvalidDevice, "hipSetDevice");
+
+  DecompressPlan& P = ctx->dplan;
+  const bool same = P.valid && P.workers == num_workers && P.layers == num_layers &&
+                    (NM == 0 || std::memcmp(P.key_msgs.data(), msgs, sizeof(rgc_msg) * NM) == 0) &&
+                    std::memcmp(P.key_dense.data(), dense, sizeof(float*) * num_layers) == 0 &&
+                    std::memcmp(P.key_n.data(), n, sizeof(int64_t) * num_layers) == 0;
+  if (!same) {
+    if (P.uploaded) RGC_HIP(hipEventSynchronize(P.uploaded));
+    else RGC_HIP(hipEventCreateWithFlags(&P.uploaded, hipEventDisableTiming));
+    P.valid = false;
+    // geometry
+    std::vector<uint32_t> layer_tiles(num_layers), layer_col(num_layers);
+    uint64_t tiles = 0, stride = 0;
+    for (int32_t l = 0; l < num_layers; ++l) {
+      layer_tiles[l] = static_cast<uint32_t>((n[l] + kTile - 1) >> kTileShift);
+      layer_col[l] = static_cast<uint32_t>(stride);
+      tiles += layer_tiles[l];
+      stride += layer_tiles[l] + 1u;
+    }
+    uint64_t blocks = 0;
+    for (size_t i = 0; i < NM; ++i) blocks += std::max<uint64_t>(1, (static_cast<uint64_t>(msgs[i].count) + 1023) / 1024);
+    const uint64_t tab_words = stride * static_cast<uint64_t>(std::max(num_workers, 1));
+    if (tiles > 0x7FFFFFFFull || blocks > 0x7FFFFFFFull || tab_words > 0xFFFFFFFFull) return RGC_ENOMEM;
+    const size_t off_msgs = 0;
+    const size_t off_tiles = off_msgs + sizeof(MsgDesc) * std::max<size_t>(NM, 1);
+    const size_t off_blocks = off_tiles + sizeof(TileDesc) * tiles;
+    const size_t off_lt = off_blocks + sizeof(BlockDesc) * std::max<uint64_t>(blocks, 1);
+    const size_t bytes = off_lt + sizeof(uint32_t) * num_layers;
+    RGC_HIP(P.staging.ensure(bytes));
+    if (P.d_tables.n < bytes) {
+      hipError_t e = P.d_tables.alloc(bytes);
+      if (e == hipErrorOutOfMemory) { (void)hipGetLastError(); return RGC_ENOMEM; }
+      RGC_HIP(e);
+    }
+    if (P.d_tab.n < tab_words) {
+      hipError_t e = P.d_tab.alloc(tab_words);
+      if (e == hipErrorOutOfMemory) { (void)hipGetLastError(); return RGC_ENOMEM; }
+      RGC_HIP(e);
+    }
+    char* base = static_cast<char*>(P.staging.p);
+    MsgDesc* hm = reinterpret_cast<MsgDesc*>(base + off_msgs);
+    TileDesc* ht = reinterpret_cast<TileDesc*>(base + off_tiles);
+    BlockDesc* hb = reinterpret_cast<BlockDesc*>(base + off_blocks);
+    uint32_t* hl = reinterpret_cast<uint32_t*>(base + off_lt);
+    uint64_t nb = 0;
+    for (size_t i = 0; i < NM; ++i) {
+      const uint32_t w = static_cast<uint32_t>(i / num_layers), l = static_cast<uint32_t>(i % num_layers);
+      hm[i].idx = msgs[i].idx;
+      hm[i].val = msgs[i].val;
+      hm[i].count = static_cast<uint32_t>(msgs[i].count);
+      hm[i].tab_base = static_cast<uint32_t>(static_cast<uint64_t>(w) * stride + layer_col[l]);
+      const uint32_t cnt = hm[i].count;
+      uint32_t first = 0;
+      do {
+        hb[nb].msg = static_cast<uint32_t>(i);
+        hb[nb].first = first;
+        ++nb;
+        first += 1024;
+      } while (first < cnt);
+    }
+    uint64_t nt = 0;
+    for (int32_t l = 0; l < num_layers; ++l) {
+      hl[l] = layer_tiles[l];
+      for (uint32_t t = 0; t < layer_tiles[l]; ++t) {
+        TileDesc& td = ht[nt++];
+        td.first = t << kTileShift;
+        td.dense = dense[l] + td.first;
+        td.len = static_cast<uint32_t>(std::min<int64_t>(kTile, n[l] - static_cast<int64_t>(td.first)));
+        td.layer = static_cast<uint32_t>(l);
+        td.tab_col = t;
+      }
+    }
+    RGC_HIP(hipMemcpyAsync(P.d_tables.p, P.staging.p, bytes, hipMemcpyHostToDevice, stream));
+    RGC_HIP(hipEventRecord(P.uploaded, stream));
+    DecompressArgs& A = P.args;
+    A.msgs = reinterpret_cast<const MsgDesc*>(P.d_tables.p + off_msgs);
+    A.tiles = reinterpret_cast<const TileDesc*>(P.d_tables.p + off_tiles);
+    A.blocks = reinterpret_cast<const BlockDesc*>(P.d_tables.p + off_blocks);
+    A.layer_tiles = reinterpret_cast<const uint32_t*>(P.d_tables.p + off_lt);
+    A.tab = P.d_tab.p;
+    A.tab_stride = static_cast<uint32_t>(stride);
+    A.num_workers = static_cast<uint32_t>(num_workers);
+    A.num_layers = static_cast<uint32_t>(num_layers);
+    A.num_tiles = static_cast<uint32_t>(tiles);
+    A.num_blocks = static_cast<uint32_t>(nb);
+    P.key_msgs.assign(msgs, msgs + NM);
+    P.key_dense.assign(dense, dense + num_layers);
+    P.key_n.assign(n, n + num_layers);
+    P.workers = num_workers;
+    P.layers = num_layers;
+    P.valid = true;
+  }
+  DecompressArgs A = P.args;
+  A.add_to_dst = (flags == RGC_ADD_TO_DST) ? 1u : 0u;
+  A.scale = scale;
+  RGC_HIP(launch_decompress_table(A, stream));
+  RGC_HIP(launch_decompress_tiles(A, stream));
+  return RGC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,825 @@
+// gfx950 kernels of the compression step (RedSync, Algorithm 1, inner loop over layers):
+//   V += G (or the momentum-corrected form of Section 2.5), exact top-k selection by
+//   magnitude (Section 2.1 defines the communication-set as the top 0.1 % of each layer),
+//   packing into (index, value) messages (Sections 2.2 / 2.3) and masking of the residual.
+//
+// Work decomposition: a layer is cut into wave-chunks of `chunk` consecutive elements; one
+// wave64 owns one wave-chunk, four waves form a workgroup, all layers of a call share one
+// launch (workgroup -> layer through a table).  A wave keeps everything it emits in ascending
+// index order using ballot + popcount ranks, so every list below is ordered without a sort.
+//
+// Two ways to the same result:
+//  * hinted, one pass over G/V: the streaming pass appends every element whose magnitude key
+//    is >= a cached threshold tau to its wave-chunk's candidate list and counts candidates in
+//    a coarse histogram of (key - tau).  If at least k candidates were seen and no list
+//    overflowed, the exact k-th key is found among the candidates (PH_SEL) and the message is
+//    written from the lists (PH_OUT_C).  tau only decides speed: a bad tau is detected and the
+//    layer falls back to
+//  * multi-pass radix select: three histogram passes over 12+12+7 key bits give the exact
+//    k-th key T and the number r of admitted ties, a counting pass and an ordered-compaction
+//    pass write the message (lowest indices win among keys equal to T).
+// Per layer decisions are taken by the last workgroup of the layer to finish a phase
+// (fence + atomic counter), so no host round trip and no spinning is needed.
+#include "rgc_device.h"
+
+namespace rgc {
+
+namespace {
+
+__device__ __forceinline__ uint32_t fbits(float x) { return __float_as_uint(x); }
+
+typedef float vf4 __attribute__((ext_vector_type(4)));   // one 16-byte access per lane
+
+struct Collector {
+  uint2* slot;       // this wave-chunk's candidate list
+  uint32_t* coarse;  // the layer's coarse histogram
+  uint32_t cap;
+  uint32_t count;    // candidates seen so far (wave-uniform)
+  uint32_t tau;
+  uint32_t shift;
+};
+
+__device__ __forceinline__ uint32_t coarse_bin(uint32_t key, uint32_t tau, uint32_t shift) {
+  const uint32_t b = (key - tau) >> shift;
+  return b < static_cast<uint32_t>(kCoarseBins - 1) ? b : static_cast<uint32_t>(kCoarseBins - 1);
+}
+
+// Consume the four accumulated values a lane holds (elements idx0 .. idx0+3, the first
+// `nvalid` of which exist).  Element order inside the wave is lane-major.
+template <bool kCollect>
+__device__ __forceinline__ void consume(const float (&a)[4], uint32_t nvalid, uint32_t idx0,
+                                        Collector& c, uint32_t* lds_hist, uint32_t& zeros) {
+  uint32_t bits[4], key[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    bits[j] = fbits(a[j]);
+    key[j] = bits[j] & kKeyMask;
+  }
+  if constexpr (kCollect) {
+    bool f[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) f[j] = (static_cast<uint32_t>(j) < nvalid) && (key[j] >= c.tau);
+    const unsigned long long any = __ballot(f[0] | f[1] | f[2] | f[3]);
+    if (any != 0ull) {
+      const unsigned long long m0 = __ballot(f[0]), m1 = __ballot(f[1]), m2 = __ballot(f[2]),
+                               m3 = __ballot(f[3]);
+      uint32_t pos = c.count + rank_below(m0) + rank_below(m1) + rank_below(m2) + rank_below(m3);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (f[j]) {
+          if (pos < c.cap) {
+            c.slot[pos] = make_uint2(bits[j], idx0 + j);
+            atomicAdd(&c.coarse[coarse_bin(key[j], c.tau, c.shift)], 1u);
+          }
+          ++pos;
+        }
+      }
+      c.count += popc64(m0) + popc64(m1) + popc64(m2) + popc64(m3);
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (static_cast<uint32_t>(j) < nvalid) {
+        if (key[j] != 0u) atomicAdd(&lds_hist[key[j] >> 19], 1u);
+        else ++zeros;
+      }
+    }
+  }
+}
+
+template <bool kMom>
+__device__ __forceinline__ void accum4(const float (&g)[4], const float (&v)[4], float (&u)[4],
+                                       float m, float (&a)[4]) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    if constexpr (kMom) {
+      u[j] = __fmaf_rn(m, u[j], g[j]);
+      a[j] = __fadd_rn(v[j], u[j]);
+    } else {
+      a[j] = __fadd_rn(v[j], g[j]);
+    }
+  }
+}
+
+// Streaming pass over one wave-chunk [begin, end) of a layer.
+template <bool kMom, bool kCollect>
+__device__ __forceinline__ void stream_chunk(const LayerDesc& L, uint32_t begin, uint32_t end,
+                                             float m, Collector& c, uint32_t* lds_hist) {
+  const uint32_t lane = lane_id();
+  uint32_t zeros = 0;
+  uint32_t base = begin;
+  if (L.vec_ok) {
+    const uint32_t nfull = (end - begin) / kGroupElems;
+    const vf4* __restrict__ G4 = reinterpret_cast<const vf4*>(L.grad + begin);
+    vf4* __restrict__ V4 = reinterpret_cast<vf4*>(L.resid + begin);
+    vf4* __restrict__ U4 = kMom ? reinterpret_cast<vf4*>(L.mom + begin) : nullptr;
+    constexpr uint32_t kUnroll = 4;
+    uint32_t g = 0;
+    for (; g + kUnroll <= nfull; g += kUnroll) {
+      vf4 gv[kUnroll], vv[kUnroll], uv[kUnroll];
+#pragma unroll
+      for (uint32_t t = 0; t < kUnroll; ++t) {
+        const uint32_t o = (g + t) * kWaveSize + lane;
+        gv[t] = __builtin_nontemporal_load(&G4[o]);
+        vv[t] = V4[o];
+        if constexpr (kMom) uv[t] = U4[o];
+      }
+#pragma unroll
+      for (uint32_t t = 0; t < kUnroll; ++t) {
+        const uint32_t o = (g + t) * kWaveSize + lane;
+        const float gg[4] = {gv[t].x, gv[t].y, gv[t].z, gv[t].w};
+        const float vvv[4] = {vv[t].x, vv[t].y, vv[t].z, vv[t].w};
+        float uu[4] = {0.f, 0.f, 0.f, 0.f};
+        if constexpr (kMom) { uu[0] = uv[t].x; uu[1] = uv[t].y; uu[2] = uv[t].z; uu[3] = uv[t].w; }
+        float a[4];
+        accum4<kMom>(gg, vvv, uu, m, a);
+        V4[o] = vf4{a[0], a[1], a[2], a[3]};
+        if constexpr (kMom) U4[o] = vf4{uu[0], uu[1], uu[2], uu[3]};
+        consume<kCollect>(a, 4u, begin + o * 4u, c, lds_hist, zeros);
+      }
+    }
+    for (; g < nfull; ++g) {
+      const uint32_t o = g * kWaveSize + lane;
+      const vf4 gq = __builtin_nontemporal_load(&G4[o]);
+      const vf4 vq = V4[o];
+      const float gg[4] = {gq.x, gq.y, gq.z, gq.w};
+      const float vvv[4] = {vq.x, vq.y, vq.z, vq.w};
+      float uu[4] = {0.f, 0.f, 0.f, 0.f};
+      if constexpr (kMom) { const vf4 uq = U4[o]; uu[0] = uq.x; uu[1] = uq.y; uu[2] = uq.z; uu[3] = uq.w; }
+      float a[4];
+      accum4<kMom>(gg, vvv, uu, m, a);
+      V4[o] = vf4{a[0], a[1], a[2], a[3]};
+      if constexpr (kMom) U4[o] = vf4{uu[0], uu[1], uu[2], uu[3]};
+      consume<kCollect>(a, 4u, begin + o * 4u, c, lds_hist, zeros);
+    }
+    base = begin + nfull * kGroupElems;
+  }
+  // scalar groups: the ragged tail of an aligned layer, or every group of an unaligned one
+  for (; base < end; base += kGroupElems) {
+    const uint32_t idx0 = base + lane * 4u;
+    const uint32_t nvalid = idx0 < end ? ((end - idx0) < 4u ? (end - idx0) : 4u) : 0u;
+    float gg[4] = {0.f, 0.f, 0.f, 0.f}, vvv[4] = {0.f, 0.f, 0.f, 0.f}, uu[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (static_cast<uint32_t>(j) < nvalid) {
+        gg[j] = L.grad[idx0 + j];
+        vvv[j] = L.resid[idx0 + j];
+        if constexpr (kMom) uu[j] = L.mom[idx0 + j];
+      }
+    }
+    float a[4];
+    accum4<kMom>(gg, vvv, uu, m, a);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (static_cast<uint32_t>(j) < nvalid) {
+        L.resid[idx0 + j] = a[j];
+        if constexpr (kMom) L.mom[idx0 + j] = uu[j];
+      }
+    }
+    consume<kCollect>(a, nvalid, idx0, c, lds_hist, zeros);
+  }
+  if constexpr (!kCollect) {
+    if (zeros) atomicAdd(&lds_hist[0], zeros);
+  }
+}
+
+// Read-only walk over one wave-chunk of the updated residual, four elements per lane per step,
+// same element order as the streaming pass.  f(a[4], nvalid, idx0) must be wave-uniform code.
+template <typename F>
+__device__ __forceinline__ void for_each_group(const float* __restrict__ p, bool vec, uint32_t begin,
+                                               uint32_t end, F&& f) {
+  const uint32_t lane = lane_id();
+  for (uint32_t base = begin; base < end; base += kGroupElems) {
+    const uint32_t idx0 = base + lane * 4u;
+    float a[4] = {0.f, 0.f, 0.f, 0.f};
+    uint32_t nvalid;
+    if (vec && base + kGroupElems <= end) {
+      const vf4 q = *reinterpret_cast<const vf4*>(p + idx0);
+      a[0] = q.x; a[1] = q.y; a[2] = q.z; a[3] = q.w;
+      nvalid = 4u;
+    } else {
+      nvalid = idx0 < end ? ((end - idx0) < 4u ? (end - idx0) : 4u) : 0u;
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (static_cast<uint32_t>(j) < nvalid) a[j] = p[idx0 + j];
+    }
+    f(a, nvalid, idx0);
+  }
+}
+
+__device__ __forceinline__ void flush_hist(const uint32_t* lds_hist, uint32_t* ghist, uint32_t bins) {
+  for (uint32_t b = threadIdx.x; b < bins; b += kBlockThreads) {
+    const uint32_t v = lds_hist[b];
+    if (v) atomicAdd(&ghist[b], v);
+  }
+}
+
+__device__ __forceinline__ uint32_t bit_length(uint32_t x) { return x ? 32u - __clz(x) : 0u; }
+
+// Coarse-bin shift for the next call so that the k-th key lands near bin 512..1023.
+__device__ __forceinline__ uint32_t shift_for(uint32_t T, uint32_t tau) {
+  const uint32_t d = T >= tau ? T - tau : 0u;
+  const uint32_t bl = bit_length(d);
+  return bl > 10u ? bl - 10u : 0u;
+}
+
+struct ResolveShared {
+  uint32_t scan[4];
+  uint32_t flag;
+  uint32_t bin, above, cnt;     // bin holding the k-th key, keys above it, keys in it
+  uint32_t hbin, hcum, hcnt;    // bin where the cumulative count reaches k + margin
+  uint32_t bad;
+};
+
+// Multi-pass path, one radix digit: the layer's histogram of this digit is complete.  Find the
+// bin holding the k_rem-th largest key, update prefix / k_rem, derive the threshold hint for
+// the next call on the way, clear the histogram, schedule the next phase.
+template <int kLevel>
+__device__ void resolve_digit(const CompressArgs& A, uint32_t l, const LayerDesc& L, LayerState* st,
+                              ResolveShared& sh, uint32_t cur_launch) {
+  constexpr uint32_t kBins = (kLevel == 3) ? 128u : static_cast<uint32_t>(kHistBins);
+  constexpr uint32_t kPer = (kLevel == 3) ? 1u : kBins / kBlockThreads;
+  uint32_t* ghist = A.hist + static_cast<size_t>(l) * kHistBins;
+  const uint32_t t = threadIdx.x;
+  const uint32_t k_rem = (kLevel == 1) ? L.k : st->k_rem;
+  const uint32_t above_scope = L.k - k_rem;          // keys above the current scope
+  // The k entries selected now leave the residual, so the next call's top-k come from ranks
+  // k+1.. of this call: aim the next threshold at rank 2k + margin.
+  const uint32_t target = 2u * L.k + L.margin;
+  const uint32_t pending = (kLevel == 1) ? 1u : st->hint_pending;
+  const uint32_t prefix = (kLevel == 1) ? 0u : st->prefix;
+
+  uint32_t h[kPer];
+  uint32_t s = 0;
+  const bool active = t * kPer < kBins;
+#pragma unroll
+  for (uint32_t i = 0; i < kPer; ++i) {
+    h[i] = active ? ld_agent(&ghist[kBins - 1u - (t * kPer + i)]) : 0u;
+    s += h[i];
+  }
+  if (t == 0) { sh.bin = 0xFFFFFFFFu; sh.hbin = 0xFFFFFFFFu; sh.above = 0; sh.cnt = 0; sh.hcum = 0; sh.hcnt = 0; }
+  uint32_t total;
+  const uint32_t ex = block_excl_scan(s, sh.scan, total);   // barriers inside: sh init is visible
+  if (active && ex < k_rem && k_rem <= ex + s) {
+    uint32_t cum = ex;
+#pragma unroll
+    for (uint32_t i = 0; i < kPer; ++i) {
+      if (cum < k_rem && cum + h[i] >= k_rem) {
+        sh.bin = kBins - 1u - (t * kPer + i); sh.above = cum; sh.cnt = h[i];
+      }
+      cum += h[i];
+    }
+  }
+  const uint32_t tgt_local = target - above_scope;   // > 0
+  if (active && ex < tgt_local && tgt_local <= ex + s) {
+    uint32_t cum = ex;
+#pragma unroll
+    for (uint32_t i = 0; i < kPer; ++i) {
+      if (cum < tgt_local && cum + h[i] >= tgt_local) {
+        sh.hbin = kBins - 1u - (t * kPer + i); sh.hcum = above_scope + cum + h[i]; sh.hcnt = h[i];
+      }
+      cum += h[i];
+    }
+  }
+  // clear the bins for the next digit / the next call
+#pragma unroll
+  for (uint32_t i = 0; i < kPer; ++i)
+    if (active) ghist[kBins - 1u - (t * kPer + i)] = 0u;
+  if (kLevel == 3) {   // digits 1 and 2 used all 4096 bins, digit 3 only 128: nothing else is dirty
+  }
+  __syncthreads();
+  if (t == 0) {
+    if (sh.bin == 0xFFFFFFFFu) { atomicOr(A.errflag, 1u); sh.bin = 0; }
+    const uint32_t D = sh.bin;
+    auto edge = [&](uint32_t b) -> uint32_t {
+      if (kLevel == 1) return b << 19;
+      if (kLevel == 2) return (prefix << 19) | (b << 7);
+      return (prefix << 7) | b;
+    };
+    // ---- hint derivation (speed only)
+    uint32_t pend = pending;
+    if (pend == 1u) {
+      if (sh.hbin == 0xFFFFFFFFu) {          // the whole layer holds fewer than k + margin keys
+        st->tau_next = 0u; pend = 2u;
+      } else if (sh.hcum <= L.cmax) {
+        st->tau_next = edge(sh.hbin); pend = 2u;
+      } else if (sh.hbin == D) {
+        pend = (kLevel < 3) ? 1u : 3u;      // refine inside the same bin, or give up (heavy ties)
+      } else {
+        st->tau_next = edge(sh.hbin + 1u); pend = 2u;   // one bin up: count in [k, k + margin)
+      }
+    }
+    const uint32_t new_rem = k_rem - sh.above;
+    st->k_rem = new_rem;
+    if (kLevel == 1) {
+      st->prefix = D;
+      st->next_phase = PH_HIST2;
+    } else if (kLevel == 2) {
+      st->prefix = (prefix << 12) | D;
+      st->next_phase = PH_HIST3;
+    } else {
+      const uint32_t T = (prefix << 7) | D;
+      st->T = T;
+      st->r = new_rem;
+      st->next_phase = PH_COUNT;
+      if (A.update_hints) {
+        if (pend == 2u) {
+          st->tau = st->tau_next; st->shift = shift_for(T, st->tau_next); st->hint_valid = 1u;
+        } else {
+          st->hint_valid = 0u;
+        }
+      }
+    }
+    st->hint_pending = pend;
+    st->next_launch = cur_launch + 1u;
+  }
+}
+
+// Hinted path, end of the streaming pass: validate the candidate lists, locate the coarse bin
+// holding the k-th key, clear the coarse histogram, schedule PH_SEL or fall back.
+__device__ void resolve_collect(const CompressArgs& A, uint32_t l, const LayerDesc& L, LayerState* st,
+                                ResolveShared& sh) {
+  const uint32_t t = threadIdx.x;
+  uint32_t* coarse = A.coarse + static_cast<size_t>(l) * kCoarseBins;
+  uint32_t total = 0, bad = 0;
+  for (uint32_t c = t; c < L.wc_count; c += kBlockThreads) {
+    const uint32_t v = A.cand_cnt[L.wc_first + c];
+    bad |= (v > A.cap) ? 1u : 0u;
+    total += v;
+  }
+  uint32_t cand_total;
+  (void)block_excl_scan(total, sh.scan, cand_total);
+  bad = __syncthreads_or(static_cast<int>(bad)) ? 1u : 0u;
+
+  constexpr uint32_t kPer = kCoarseBins / kBlockThreads;   // 8
+  uint32_t h[kPer];
+  uint32_t s = 0;
+#pragma unroll
+  for (uint32_t i = 0; i < kPer; ++i) {
+    h[i] = ld_agent(&coarse[kCoarseBins - 1u - (t * kPer + i)]);
+    s += h[i];
+  }
+  if (t == 0) { sh.bin = 0xFFFFFFFFu; sh.hbin = 0xFFFFFFFFu; sh.above = 0; sh.cnt = 0; sh.hcum = 0; }
+  uint32_t hist_total;
+  const uint32_t ex = block_excl_scan(s, sh.scan, hist_total);
+  const uint32_t k = L.k, target = 2u * L.k + L.margin;   // see resolve_digit
+  if (ex < k && k <= ex + s) {
+    uint32_t cum = ex;
+#pragma unroll
+    for (uint32_t i = 0; i < kPer; ++i) {
+      if (cum < k && cum + h[i] >= k) { sh.bin = kCoarseBins - 1u - (t * kPer + i); sh.above = cum; sh.cnt = h[i]; }
+      cum += h[i];
+    }
+  }
+  if (ex < target && target <= ex + s) {
+    uint32_t cum = ex;
+#pragma unroll
+    for (uint32_t i = 0; i < kPer; ++i) {
+      if (cum < target && cum + h[i] >= target) { sh.hbin = kCoarseBins - 1u - (t * kPer + i); sh.hcum = cum + h[i]; }
+      cum += h[i];
+    }
+  }
+#pragma unroll
+  for (uint32_t i = 0; i < kPer; ++i) coarse[kCoarseBins - 1u - (t * kPer + i)] = 0u;
+  __syncthreads();
+  if (t == 0) {
+    const bool ok = !bad && cand_total >= k && hist_total == cand_total && sh.bin != 0xFFFFFFFFu &&
+                    sh.cnt <= static_cast<uint32_t>(kMemberMax);
+    if (ok) {
+      const uint32_t tau = st->tau, shift = st->shift;
+      st->bstar = sh.bin;
+      st->k_rem = k - sh.above;
+      st->nmembers = 0u;
+      st->path = 0u;
+      st->next_phase = PH_SEL;
+      unsigned long long tn;
+      if (sh.hbin != 0xFFFFFFFFu) {
+        tn = static_cast<unsigned long long>(tau) + (static_cast<unsigned long long>(sh.hbin) << shift);
+        if (tn > kKeyMask) tn = kKeyMask;
+      } else {
+        // the lists end above rank 2k + margin: extend tau downwards assuming the key density
+        // seen between rank k and the end of the lists (it grows further down, so this errs
+        // towards more candidates)
+        const unsigned long long d = (static_cast<unsigned long long>(sh.bin) + 1ull) << shift;
+        const unsigned long long have = cand_total > k ? cand_total - k : 1u;
+        const unsigned long long need = target - cand_total;
+        const unsigned long long delta = (d * need + have - 1ull) / have + 1ull;
+        tn = delta < tau ? tau - delta : 0ull;
+      }
+      st->tau_next = static_cast<uint32_t>(tn);
+    } else {
+      st->path = 2u;
+      st->next_phase = PH_HIST1;
+    }
+    st->next_launch = 2u;
+  }
+}
+
+// In-place exclusive scan over the per wave-chunk counters of one layer (one workgroup).
+// with_ties: a[] = keys > T, b[] = keys == T  ->  a[] = output offset of the chunk
+//            (= prefix(a) + min(prefix(b), r)), b[] = prefix(b).
+__device__ void scan_chunks(uint32_t* a, uint32_t* b, uint32_t count, uint32_t r, bool with_ties,
+                            uint32_t* lds_scan, uint32_t* out_total) {
+  constexpr uint32_t kItems = 4;
+  uint32_t carry_a = 0, carry_b = 0;
+  for (uint32_t base = 0; base < count; base += kBlockThreads * kItems) {
+    uint32_t va[kItems], vb[kItems];
+    uint32_t sa = 0, sb = 0;
+    const uint32_t i0 = base + threadIdx.x * kItems;
+#pragma unroll
+    for (uint32_t j = 0; j < kItems; ++j) {
+      va[j] = (i0 + j < count) ? ld_agent(&a[i0 + j]) : 0u;
+      vb[j] = (with_ties && i0 + j < count) ? ld_agent(&b[i0 + j]) : 0u;
+      sa += va[j];
+      sb += vb[j];
+    }
+    uint32_t ta, tb = 0;
+    uint32_t ea = block_excl_scan(sa, lds_scan, ta) + carry_a;
+    uint32_t eb = 0;
+    if (with_ties) eb = block_excl_scan(sb, lds_scan, tb) + carry_b;
+#pragma unroll
+    for (uint32_t j = 0; j < kItems; ++j) {
+      if (i0 + j < count) {
+        if (with_ties) {
+          a[i0 + j] = ea + (eb < r ? eb : r);
+          b[i0 + j] = eb;
+        } else {
+          a[i0 + j] = ea;
+        }
+      }
+      ea += va[j];
+      eb += vb[j];
+    }
+    carry_a += ta;
+    carry_b += tb;
+  }
+  if (threadIdx.x == 0) *out_total = carry_a + (with_ties ? (carry_b < r ? carry_b : r) : 0u);
+}
+
+// Descending bitonic sort of n2 (power of two) 64-bit keys in LDS by 256 threads.
+__device__ void bitonic_sort_desc(unsigned long long* s, uint32_t n2) {
+  for (uint32_t size = 2; size <= n2; size <<= 1) {
+    for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
+      __syncthreads();
+      for (uint32_t i = threadIdx.x; i < (n2 >> 1); i += kBlockThreads) {
+        const uint32_t lo = 2u * i - (i & (stride - 1u));
+        const uint32_t hi = lo + stride;
+        const bool desc = ((lo & size) == 0u);
+        const unsigned long long x = s[lo], y = s[hi];
+        if ((x < y) == desc) { s[lo] = y; s[hi] = x; }
+      }
+    }
+  }
+  __syncthreads();
+}
+
+__device__ __forceinline__ unsigned long long composite(uint32_t key, uint32_t idx) {
+  return (static_cast<unsigned long long>(key) << 32) | static_cast<unsigned long long>(0xFFFFFFFFu - idx);
+}
+
+}  // namespace
+
+// =================================================================== launch 1: streaming pass
+__global__ void __launch_bounds__(kBlockThreads) accumulate_kernel(CompressArgs A) {
+  __shared__ uint32_t lds_hist[kHistBins];
+  __shared__ ResolveShared sh;
+  const uint32_t wg = blockIdx.x;
+  const uint32_t l = A.wg2layer[wg];
+  const LayerDesc L = A.layers[l];
+  LayerState* st = A.state + l;
+  const bool collect = A.use_hints && L.hintable && (st->hint_valid != 0u);
+  if (!collect) {
+    for (uint32_t b = threadIdx.x; b < kHistBins; b += kBlockThreads) lds_hist[b] = 0u;
+    __syncthreads();
+  }
+  const uint32_t wave = threadIdx.x >> 6;
+  const uint32_t wc_local = (wg - L.wg_first) * kWavesPerBlock + wave;
+  if (wc_local < L.wc_count) {
+    const uint32_t begin = wc_local * A.chunk;
+    const uint32_t end = (L.n - begin) < A.chunk ? L.n : begin + A.chunk;
+    Collector c;
+    c.slot = A.slots + static_cast<size_t>(L.wc_first + wc_local) * A.cap;
+    c.coarse = A.coarse + static_cast<size_t>(l) * kCoarseBins;
+    c.cap = A.cap;
+    c.count = 0;
+    c.tau = st->tau;
+    c.shift = st->shift;
+    const bool mom = (L.mom != nullptr);
+    if (collect) {
+      if (mom) stream_chunk<true, true>(L, begin, end, A.m, c, lds_hist);
+      else stream_chunk<false, true>(L, begin, end, A.m, c, lds_hist);
+      if (lane_id() == 0) A.cand_cnt[L.wc_first + wc_local] = c.count;
+    } else {
+      if (mom) stream_chunk<true, false>(L, begin, end, A.m, c, lds_hist);
+      else stream_chunk<false, false>(L, begin, end, A.m, c, lds_hist);
+    }
+  }
+  if (!collect) {
+    __syncthreads();
+    flush_hist(lds_hist, A.hist + static_cast<size_t>(l) * kHistBins, kHistBins);
+  }
+  if (last_block_of_layer(&st->done, L.wg_count, &sh.flag)) {
+    if (collect) {
+      resolve_collect(A, l, L, st, sh);
+    } else {
+      if (threadIdx.x == 0) st->path = 1u;
+      resolve_digit<1>(A, l, L, st, sh, 1u);
+    }
+  }
+}
+
+// =================================================================== launches 2..6: phases
+namespace {
+
+template <int kLevel>
+__device__ void phase_hist(const CompressArgs& A, uint32_t l, const LayerDesc& L, LayerState* st,
+                           uint32_t wc_local, uint32_t* lds_hist, ResolveShared& sh) {
+  constexpr uint32_t kBins = (kLevel == 3) ? 128u : static_cast<uint32_t>(kHistBins);
+  for (uint32_t b = threadIdx.x; b < kBins; b += kBlockThreads) lds_hist[b] = 0u;
+  __syncthreads();
+  const uint32_t prefix = st->prefix;
+  if (wc_local < L.wc_count) {
+    const uint32_t begin = wc_local * A.chunk;
+    const uint32_t end = (L.n - begin) < A.chunk ? L.n : begin + A.chunk;
+    uint32_t zeros = 0;
+    for_each_group(L.resid, L.vec_ok != 0u, begin, end,
+                   [&](const float (&a)[4], uint32_t nvalid, uint32_t) {
+#pragma unroll
+                     for (int j = 0; j < 4; ++j) {
+                       if (static_cast<uint32_t>(j) < nvalid) {
+                         const uint32_t key = fbits(a[j]) & kKeyMask;
+                         if (kLevel == 1) {
+                           if (key != 0u) atomicAdd(&lds_hist[key >> 19], 1u);
+                           else ++zeros;
+                         } else if (kLevel == 2) {
+                           if ((key >> 19) == prefix) atomicAdd(&lds_hist[(key >> 7) & 0xFFFu], 1u);
+                         } else {
+                           if ((key >> 7) == prefix) atomicAdd(&lds_hist[key & 0x7Fu], 1u);
+                         }
+                       }
+                     }
+                   });
+    if (kLevel == 1 && zeros) atomicAdd(&lds_hist[0], zeros);
+  }
+  __syncthreads();
+  flush_hist(lds_hist, A.hist + static_cast<size_t>(l) * kHistBins, kBins);
+  if (last_block_of_layer(&st->done, L.wg_count, &sh.flag)) resolve_digit<kLevel>(A, l, L, st, sh, A.launch);
+}
+
+__device__ void phase_count(const CompressArgs& A, uint32_t l, const LayerDesc& L, LayerState* st,
+                            uint32_t wc_local, ResolveShared& sh) {
+  const uint32_t T = st->T;
+  if (wc_local < L.wc_count) {
+    const uint32_t begin = wc_local * A.chunk;
+    const uint32_t end = (L.n - begin) < A.chunk ? L.n : begin + A.chunk;
+    uint32_t gt = 0, eq = 0;
+    for_each_group(L.resid, L.vec_ok != 0u, begin, end,
+                   [&](const float (&a)[4], uint32_t nvalid, uint32_t) {
+#pragma unroll
+                     for (int j = 0; j < 4; ++j) {
+                       if (static_cast<uint32_t>(j) < nvalid) {
+                         const uint32_t key = fbits(a[j]) & kKeyMask;
+                         gt += (key > T) ? 1u : 0u;
+                         eq += (key == T) ? 1u : 0u;
+                       }
+                     }
+                   });
+    const uint32_t gt_all = wave_total(wave_incl_scan(gt));
+    const uint32_t eq_all = wave_total(wave_incl_scan(eq));
+    if (lane_id() == 0) {
+      A.wc_a[L.wc_first + wc_local] = gt_all;
+      A.wc_b[L.wc_first + wc_local] = eq_all;
+    }
+  }
+  if (last_block_of_layer(&st->done, L.wg_count, &sh.flag)) {
+    scan_chunks(A.wc_a + L.wc_first, A.wc_b + L.wc_first, L.wc_count, st->r, true, sh.scan, &sh.cnt);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      if (sh.cnt != L.k) atomicOr(A.errflag, 2u);
+      st->next_phase = PH_OUT_V;
+      st->next_launch = A.launch + 1u;
+    }
+  }
+}
+
+__device__ void phase_out_v(const CompressArgs& A, const LayerDesc& L, LayerState* st, uint32_t wc_local) {
+  if (wc_local >= L.wc_count) return;
+  const uint32_t T = st->T, r = st->r;
+  const uint32_t begin = wc_local * A.chunk;
+  const uint32_t end = (L.n - begin) < A.chunk ? L.n : begin + A.chunk;
+  uint32_t out_pos = A.wc_a[L.wc_first + wc_local];
+  uint32_t eq_seen = A.wc_b[L.wc_first + wc_local];
+  const bool clear_mom = (L.mom != nullptr) && A.mask_momentum;
+  for_each_group(L.resid, L.vec_ok != 0u, begin, end,
+                 [&](const float (&a)[4], uint32_t nvalid, uint32_t idx0) {
+                   bool gt[4], eq[4];
+#pragma unroll
+                   for (int j = 0; j < 4; ++j) {
+                     const uint32_t key = fbits(a[j]) & kKeyMask;
+                     const bool valid = static_cast<uint32_t>(j) < nvalid;
+                     gt[j] = valid && key > T;
+                     eq[j] = valid && key == T;
+                   }
+                   const unsigned long long any =
+                       __ballot(gt[0] | gt[1] | gt[2] | gt[3] | eq[0] | eq[1] | eq[2] | eq[3]);
+                   if (any == 0ull) return;
+                   const unsigned long long e0 = __ballot(eq[0]), e1 = __ballot(eq[1]),
+                                            e2 = __ballot(eq[2]), e3 = __ballot(eq[3]);
+                   uint32_t my_eq = eq_seen + rank_below(e0) + rank_below(e1) + rank_below(e2) + rank_below(e3);
+                   bool sel[4];
+#pragma unroll
+                   for (int j = 0; j < 4; ++j) {
+                     sel[j] = gt[j] || (eq[j] && my_eq < r);
+                     my_eq += eq[j] ? 1u : 0u;
+                   }
+                   eq_seen += popc64(e0) + popc64(e1) + popc64(e2) + popc64(e3);
+                   const unsigned long long s0 = __ballot(sel[0]), s1 = __ballot(sel[1]),
+                                            s2 = __ballot(sel[2]), s3 = __ballot(sel[3]);
+                   uint32_t pos = out_pos + rank_below(s0) + rank_below(s1) + rank_below(s2) + rank_below(s3);
+#pragma unroll
+                   for (int j = 0; j < 4; ++j) {
+                     if (sel[j]) {
+                       if (pos < L.k) {   // always true when the counts are consistent
+                         L.out_idx[pos] = static_cast<int32_t>(idx0 + j);
+                         L.out_val[pos] = a[j];
+                         L.resid[idx0 + j] = 0.0f;
+                         if (clear_mom) L.mom[idx0 + j] = 0.0f;
+                       }
+                       ++pos;
+                     }
+                   }
+                   out_pos += popc64(s0) + popc64(s1) + popc64(s2) + popc64(s3);
+                 });
+  if (wc_local == 0 && lane_id() == 0) *L.out_count = static_cast<int32_t>(L.k);
+}
+
+// Hinted path: every wave looks at its own candidate list; candidates of the coarse bin that
+// holds the k-th key become "members" (ranked exactly by the last workgroup), candidates of
+// higher bins are counted as certainly selected.
+__device__ void phase_sel(const CompressArgs& A, uint32_t l, const LayerDesc& L, LayerState* st,
+                          uint32_t wc_local, unsigned long long* sortbuf, ResolveShared& sh) {
+  const uint32_t tau = st->tau, shift = st->shift, bstar = st->bstar;
+  unsigned long long* members = A.members + static_cast<size_t>(l) * kMemberMax;
+  const uint32_t lane = lane_id();
+  if (wc_local < L.wc_count) {
+    const uint32_t wc = L.wc_first + wc_local;
+    const uint32_t cnt = A.cand_cnt[wc];
+    const uint2* slot = A.slots + static_cast<size_t>(wc) * A.cap;
+    uint32_t hi = 0;
+    for (uint32_t p0 = 0; p0 < cnt; p0 += kWaveSize) {
+      const uint32_t p = p0 + lane;
+      if (p < cnt) {
+        const uint2 e = slot[p];
+        const uint32_t key = e.x & kKeyMask;
+        const uint32_t bin = coarse_bin(key, tau, shift);
+        if (bin > bstar) {
+          ++hi;
+        } else if (bin == bstar) {
+          const uint32_t at = atomicAdd(&st->nmembers, 1u);
+          if (at < static_cast<uint32_t>(kMemberMax)) members[at] = composite(key, e.y);
+        }
+      }
+    }
+    const uint32_t hi_all = wave_total(wave_incl_scan(hi));
+    if (lane == 0) A.wc_a[wc] = hi_all;
+  }
+  if (!last_block_of_layer(&st->done, L.wg_count, &sh.flag)) return;
+
+  const uint32_t m = ld_agent(&st->nmembers);
+  const uint32_t k_rem = st->k_rem;
+  if (m > static_cast<uint32_t>(kMemberMax) || k_rem == 0u || k_rem > m) {
+    if (threadIdx.x == 0) atomicOr(A.errflag, 4u);
+    return;   // cannot happen when the histogram and the lists agree; leave the layer unscheduled
+  }
+  uint32_t n2 = 2;
+  while (n2 < m) n2 <<= 1;
+  for (uint32_t i = threadIdx.x; i < n2; i += kBlockThreads)
+    sortbuf[i] = (i < m) ? __hip_atomic_load(&members[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0ull;
+  bitonic_sort_desc(sortbuf, n2);
+  const unsigned long long thr = sortbuf[k_rem - 1u];
+  // members at sorted positions < k_rem are selected: credit them to their wave-chunks
+  for (uint32_t i = threadIdx.x; i < k_rem; i += kBlockThreads) {
+    const uint32_t idx = 0xFFFFFFFFu - static_cast<uint32_t>(sortbuf[i] & 0xFFFFFFFFull);
+    atomicAdd(&A.wc_a[L.wc_first + idx / A.chunk], 1u);
+  }
+  __threadfence();
+  __syncthreads();
+  scan_chunks(A.wc_a + L.wc_first, nullptr, L.wc_count, 0u, false, sh.scan, &sh.cnt);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    if (sh.cnt != L.k) atomicOr(A.errflag, 8u);
+    const uint32_t T = static_cast<uint32_t>(thr >> 32);
+    st->thr = thr;
+    st->T = T;
+    if (A.update_hints) {
+      const uint32_t tn = st->tau_next <= T ? st->tau_next : T;
+      st->tau = tn;
+      st->shift = shift_for(T, tn);
+    }
+    st->next_phase = PH_OUT_C;
+    st->next_launch = A.launch + 1u;
+  }
+}
+
+__device__ void phase_out_c(const CompressArgs& A, const LayerDesc& L, LayerState* st, uint32_t wc_local) {
+  if (wc_local >= L.wc_count) return;
+  const unsigned long long thr = st->thr;
+  const uint32_t wc = L.wc_first + wc_local;
+  const uint32_t cnt = A.cand_cnt[wc];
+  const uint2* slot = A.slots + static_cast<size_t>(wc) * A.cap;
+  const uint32_t lane = lane_id();
+  uint32_t out_pos = A.wc_a[wc];
+  const bool clear_mom = (L.mom != nullptr) && A.mask_momentum;
+  for (uint32_t p0 = 0; p0 < cnt; p0 += kWaveSize) {
+    const uint32_t p = p0 + lane;
+    uint2 e = make_uint2(0u, 0u);
+    bool sel = false;
+    if (p < cnt) {
+      e = slot[p];
+      sel = composite(e.x & kKeyMask, e.y) >= thr;
+    }
+    const unsigned long long sm = __ballot(sel);
+    const uint32_t pos = out_pos + rank_below(sm);
+    if (sel && pos < L.k && e.y < L.n) {   // the bounds always hold when the counts are consistent
+      L.out_idx[pos] = static_cast<int32_t>(e.y);
+      L.out_val[pos] = __uint_as_float(e.x);
+      L.resid[e.y] = 0.0f;
+      if (clear_mom) L.mom[e.y] = 0.0f;
+    }
+    out_pos += popc64(sm);
+  }
+  if (wc_local == 0 && lane == 0) *L.out_count = static_cast<int32_t>(L.k);
+}
+
+}  // namespace
+
+__global__ void __launch_bounds__(kBlockThreads) phase_kernel(CompressArgs A) {
+  __shared__ union {
+    uint32_t hist[kHistBins];
+    unsigned long long sortbuf[kMemberMax];
+  } sm;
+  __shared__ ResolveShared sh;
+  const uint32_t wg = blockIdx.x;
+  const uint32_t l = A.wg2layer[wg];
+  LayerState* st = A.state + l;
+  if (st->next_launch != A.launch) return;
+  const LayerDesc L = A.layers[l];
+  const uint32_t phase = st->next_phase;
+  const uint32_t wc_local = (wg - L.wg_first) * kWavesPerBlock + (threadIdx.x >> 6);
+  switch (phase) {
+    case PH_SEL:   phase_sel(A, l, L, st, wc_local, sm.sortbuf, sh); break;
+    case PH_OUT_C: phase_out_c(A, L, st, wc_local); break;
+    case PH_HIST1: phase_hist<1>(A, l, L, st, wc_local, sm.hist, sh); break;
+    case PH_HIST2: phase_hist<2>(A, l, L, st, wc_local, sm.hist, sh); break;
+    case PH_HIST3: phase_hist<3>(A, l, L, st, wc_local, sm.hist, sh); break;
+    case PH_COUNT: phase_count(A, l, L, st, wc_local, sh); break;
+    case PH_OUT_V: phase_out_v(A, L, st, wc_local); break;
+    default: break;
+  }
+}
+
+// Overwrite the cached thresholds with wrong values (test hook: results must not change).
+__global__ void poison_kernel(LayerState* st, uint32_t num_layers, int mode) {
+  const uint32_t l = blockIdx.x * blockDim.x + threadIdx.x;
+  if (l >= num_layers) return;
+  uint32_t h = (l + 1u) * 2654435761u;
+  h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+  st[l].hint_valid = 1u;
+  if (mode == 0) { st[l].tau = 0x7F000000u; st[l].shift = 0u; }
+  else if (mode == 1) { st[l].tau = 0u; st[l].shift = 0u; }
+  else { st[l].tau = h & 0x3FFFFFFFu; st[l].shift = (h >> 7) % 24u; }
+}
+
+__global__ void wave_scan_selftest_kernel(uint32_t* io) {
+  // io[0..255] in: values; out: block-exclusive scan.  io[256]: total.
+  __shared__ uint32_t lds[4];
+  uint32_t total;
+  const uint32_t v = io[threadIdx.x];
+  const uint32_t ex = block_excl_scan(v, lds, total);
+  const unsigned long long odd = __ballot((v & 1u) != 0u);
+  io[threadIdx.x] = ex;
+  io[512 + threadIdx.x] = rank_below(odd);
+  if (threadIdx.x == 0) io[256] = total;
+}
+
+hipError_t launch_accumulate(const CompressArgs& a, uint32_t num_wgs, hipStream_t s) {
+  hipLaunchKernelGGL(accumulate_kernel, dim3(num_wgs), dim3(kBlockThreads), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_phase(const CompressArgs& a, uint32_t num_wgs, hipStream_t s) {
+  hipLaunchKernelGGL(phase_kernel, dim3(num_wgs), dim3(kBlockThreads), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_poison(LayerState* st, uint32_t num_layers, int mode, hipStream_t s) {
+  hipLaunchKernelGGL(poison_kernel, dim3((num_layers + 255u) / 256u), dim3(256), 0, s, st, num_layers, mode);
+  return hipGetLastError();
+}
+
+hipError_t launch_wave_scan_selftest(uint32_t* io, hipStream_t s) {
+  hipLaunchKernelGGL(wave_scan_selftest_kernel, dim3(1), dim3(kBlockThreads), 0, s, io);
+  return hipGetLastError();
+}
+
+}  // namespace rgc

@@ -1,0 +1,88 @@
+// Wave64 / workgroup primitives for the gfx950 kernels: ballot-popcount ranks, DPP prefix
+// scans, a 256-thread block scan.  Device code only.
+#pragma once
+
+#include "rgc_internal.h"
+
+namespace rgc {
+
+__device__ __forceinline__ uint32_t lane_id() {
+  return __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+}
+
+// Number of set bits of `mask` that belong to lanes below the calling lane.
+__device__ __forceinline__ uint32_t rank_below(unsigned long long mask) {
+  return __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32),
+                                   __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0u));
+}
+
+__device__ __forceinline__ uint32_t popc64(unsigned long long m) {
+  return static_cast<uint32_t>(__popcll(m));
+}
+
+template <int kCtrl, int kRowMask>
+__device__ __forceinline__ uint32_t dpp_shift_add(uint32_t v) {
+  // lanes without a source (shifted in from outside the row, or rows masked off) add 0
+  uint32_t t = static_cast<uint32_t>(__builtin_amdgcn_update_dpp(
+      0, static_cast<int>(v), kCtrl, kRowMask, 0xF, false));
+  return v + t;
+}
+
+// Inclusive prefix sum over the 64 lanes of a wave using DPP row shifts and row broadcasts.
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v) {
+  v = dpp_shift_add<0x111, 0xF>(v);  // row_shr:1
+  v = dpp_shift_add<0x112, 0xF>(v);  // row_shr:2
+  v = dpp_shift_add<0x114, 0xF>(v);  // row_shr:4
+  v = dpp_shift_add<0x118, 0xF>(v);  // row_shr:8   -> inclusive scan inside each row of 16
+  v = dpp_shift_add<0x142, 0xA>(v);  // row_bcast:15 into rows 1 and 3
+  v = dpp_shift_add<0x143, 0xC>(v);  // row_bcast:31 into rows 2 and 3
+  return v;
+}
+
+__device__ __forceinline__ uint32_t wave_total(uint32_t incl) {
+  return static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(incl), 63));
+}
+
+// Exclusive prefix sum over the 256 threads of a workgroup.  `lds` holds >= 4 words.
+// Contains barriers: every thread of the workgroup must call it.
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* lds, uint32_t& total) {
+  const uint32_t incl = wave_incl_scan(v);
+  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+  __syncthreads();
+  if (lane == 63u) lds[wave] = incl;
+  __syncthreads();
+  uint32_t off = 0, tot = 0;
+#pragma unroll
+  for (uint32_t w = 0; w < kWavesPerBlock; ++w) {
+    const uint32_t t = lds[w];
+    off += (w < wave) ? t : 0u;
+    tot += t;
+  }
+  total = tot;
+  return off + incl - v;
+}
+
+__device__ __forceinline__ uint32_t ld_agent(const uint32_t* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// "Last workgroup of the layer" election.  Every thread has finished its global writes.
+// Returns true in every thread of exactly one workgroup per (layer, phase): the one whose
+// increment completes the count.  That workgroup also resets the counter.
+__device__ __forceinline__ bool last_block_of_layer(uint32_t* done, uint32_t expect,
+                                                    uint32_t* lds_flag) {
+  __threadfence();
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const uint32_t prev = atomicAdd(done, 1u);
+    const bool last = (prev + 1u == expect);
+    if (last) __hip_atomic_store(done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *lds_flag = last ? 1u : 0u;
+  }
+  __syncthreads();
+  const bool last = (*lds_flag != 0u);
+  if (last) __threadfence();
+  return last;
+}
+
+}  // namespace rgc

@@ -1,0 +1,147 @@
+// Internal declarations shared by the host API and the gfx950 kernels of librgc.
+// Nothing here is visible through the C ABI (include/rgc.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rgc {
+
+// ---------------------------------------------------------------- geometry (compile time)
+constexpr int kWaveSize = 64;
+constexpr int kBlockThreads = 256;                 // 4 waves per workgroup
+constexpr int kWavesPerBlock = kBlockThreads / kWaveSize;
+constexpr int kGroupElems = kWaveSize * 4;         // one float4 per lane per step
+constexpr int kHistBins = 4096;                    // radix digit of 12 bits (31-bit key = 12+12+7)
+constexpr int kCoarseBins = 2048;                  // candidate histogram bins (hinted path)
+constexpr int kMemberMax = 4096;                   // candidates of one coarse bin ranked in LDS
+constexpr uint32_t kKeyMask = 0x7FFFFFFFu;
+
+// Phase a layer has to run at a given launch of the phase kernel.
+enum Phase : uint32_t {
+  PH_NONE = 0,
+  PH_SEL = 1,      // hinted: rank the members of the candidate bin holding the k-th key
+  PH_OUT_C = 2,    // hinted: ordered output from the candidate lists
+  PH_HIST1 = 3,    // multi-pass: digit-1 histogram over the updated residual (after a miss)
+  PH_HIST2 = 4,    // multi-pass: digit-2 histogram
+  PH_HIST3 = 5,    // multi-pass: digit-3 histogram
+  PH_COUNT = 6,    // multi-pass: per wave-chunk counts of keys > T and == T
+  PH_OUT_V = 7,    // multi-pass: ordered compaction from the updated residual
+};
+
+// Per call, per layer descriptor (device copy of the caller's rgc_layer plus the tiling).
+struct LayerDesc {
+  const float* grad;
+  float* resid;
+  float* mom;
+  int32_t* out_idx;
+  float* out_val;
+  int32_t* out_count;
+  uint32_t n;
+  uint32_t k;
+  uint32_t wc_first;   // first wave-chunk of this layer in the per-wave-chunk arrays
+  uint32_t wc_count;   // number of wave-chunks = ceil(n / chunk)
+  uint32_t wg_first;   // first workgroup of this layer
+  uint32_t wg_count;   // = ceil(wc_count / 4)
+  uint32_t vec_ok;     // every tensor pointer is 16-byte aligned
+  uint32_t hintable;   // candidate lists are large enough for k + margin at this density
+  uint32_t margin;     // extra candidates aimed for beyond k
+  uint32_t cmax;       // largest candidate total a hint may aim at
+};
+
+// Per layer state living in the context (device memory).  Everything but the hint fields is
+// rewritten by every call before it is read.
+struct LayerState {
+  uint32_t next_phase;   // Phase to run ...
+  uint32_t next_launch;  // ... at this launch number (2..6)
+  uint32_t done;         // workgroups of the layer that finished the current phase
+  uint32_t prefix;       // multi-pass: key bits fixed so far (digits 1 and 2)
+  uint32_t k_rem;        // rank of the k-th key inside the current bin (1-based)
+  uint32_t T;            // threshold key: the k-th largest key of the layer
+  uint32_t r;            // multi-pass: how many keys == T are admitted (lowest indices)
+  uint32_t bstar;        // hinted: coarse bin holding the k-th key
+  uint32_t nmembers;     // hinted: members appended so far
+  uint32_t path;         // 0 hinted one-pass, 1 hint-free multi-pass, 2 miss then multi-pass
+  unsigned long long thr;  // hinted: composite (key<<32 | ~idx) of the k-th entry
+  // speed hints (never influence results)
+  uint32_t hint_valid;
+  uint32_t tau;          // candidate threshold key for the next call
+  uint32_t shift;        // coarse bin = min((key - tau) >> shift, 2047)
+  uint32_t tau_next;     // being derived during this call
+  uint32_t hint_pending; // multi-pass: 0 none found yet / 1 refine in the next digit / 2 final
+  uint32_t pad;
+};
+
+struct CompressArgs {
+  const LayerDesc* layers;
+  LayerState* state;
+  const uint32_t* wg2layer;
+  uint32_t* hist;        // [layers][kHistBins]
+  uint32_t* coarse;      // [layers][kCoarseBins]
+  unsigned long long* members;  // [layers][kMemberMax]
+  uint32_t* cand_cnt;    // [wave-chunks]
+  uint2* slots;          // [wave-chunks][cap] (float bits, index), ascending index per chunk
+  uint32_t* wc_a;        // [wave-chunks] counts, then output offsets
+  uint32_t* wc_b;        // [wave-chunks] tie counts, then tie prefixes
+  uint32_t* errflag;     // set non-zero on an internal inconsistency
+  uint32_t chunk;        // elements per wave-chunk (multiple of 256)
+  uint32_t cap;          // candidate slots per wave-chunk
+  uint32_t use_hints;
+  uint32_t update_hints;
+  uint32_t mask_momentum;
+  float m;
+  uint32_t launch;       // launch number of the phase kernel (2..6)
+};
+
+// ---------------------------------------------------------------- decompress
+constexpr int kTileShift = 12;
+constexpr int kTile = 1 << kTileShift;            // dense positions owned by one workgroup
+constexpr int kEntryCap = 1024;                   // entries staged per worker batch
+constexpr int kBatchWorkers = 128;                // workers per batch (mask of 4 words)
+constexpr int kMaskWords = kBatchWorkers / 32;
+constexpr int kQMax = 128;                        // positions hit more than once per batch
+
+struct MsgDesc {                                   // one (worker, layer) message
+  const int32_t* idx;
+  const float* val;
+  uint32_t count;
+  uint32_t tab_base;    // offset of this message's row segment: w * tab_stride + layer tab base
+};
+
+struct TileDesc {
+  float* dense;         // start of the tile
+  uint32_t len;         // positions in this tile (<= kTile)
+  uint32_t layer;
+  uint32_t tab_col;     // column of this tile inside a message's table row segment
+  uint32_t first;       // layer-local index of the tile's first position
+};
+
+struct BlockDesc {      // one block of the table-building kernel
+  uint32_t msg;         // index into the MsgDesc array
+  uint32_t first;       // first entry handled by the block
+};
+
+struct DecompressArgs {
+  const MsgDesc* msgs;        // [workers][layers]
+  const TileDesc* tiles;
+  const BlockDesc* blocks;
+  const uint32_t* layer_tiles;  // [layers] number of tiles of the layer
+  uint32_t* tab;              // [workers][tab_stride] first entry of each tile, + sentinel per layer
+  uint32_t tab_stride;
+  uint32_t num_workers;
+  uint32_t num_layers;
+  uint32_t num_tiles;
+  uint32_t num_blocks;
+  uint32_t add_to_dst;
+  float scale;
+};
+
+// kernel launchers (defined in the .hip files)
+hipError_t launch_accumulate(const CompressArgs& a, uint32_t num_wgs, hipStream_t s);
+hipError_t launch_phase(const CompressArgs& a, uint32_t num_wgs, hipStream_t s);
+hipError_t launch_poison(LayerState* st, uint32_t num_layers, int mode, hipStream_t s);
+hipError_t launch_decompress_table(const DecompressArgs& a, hipStream_t s);
+hipError_t launch_decompress_tiles(const DecompressArgs& a, hipStream_t s);
+hipError_t launch_wave_scan_selftest(uint32_t* io, hipStream_t s);
+
+}  // namespace rgc

@@ -1,0 +1,224 @@
+"""GPU parity: rgc_compress_layers (through the C ABI) against the CPU oracle, bit for bit on
+indices, values, count, residual and velocity."""
+import numpy as np
+import pytest
+
+from paper_1808_04357_amd import synth
+from rgc_testutil import GpuLayers, assert_layers_equal, check_properties, oracle_step, u32
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def rgc():
+    torch = pytest.importorskip("torch")
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    import paper_1808_04357_amd as pkg
+    pkg.load_library()
+    return pkg
+
+
+def run_iterations(rgc, oracle, V0, G_list, ks, U0=None, m=0.0, flags=0, ctx=None, misalign=0,
+                   poison=None, tag="", threads=4, expect_paths=None):
+    """Runs len(G_list) compression steps on both sides and compares after every step."""
+    total = sum(v.size for v in V0)
+    own = ctx is None
+    if own:
+        ctx = rgc.Context(total, len(V0))
+    dev = GpuLayers(rgc, V0, ks, U0, misalign=misalign)
+    Vh = [v.copy() for v in V0]
+    Uh = [u.copy() for u in U0] if U0 is not None else None
+    paths = []
+    for t, G in enumerate(G_list):
+        print("  %s step %d" % (tag, t), flush=True)
+        if poison is not None and t > 0:
+            ctx.poison_hints(poison[(t - 1) % len(poison)])
+        dev.set_grads(G)
+        dev.step(ctx, m, flags)
+        msgs = oracle_step(oracle, G, Vh, ks, Uh, m, mask_momentum=not (flags & rgc.RGC_NO_MOMENTUM_MASK),
+                           threads=threads)
+        assert_layers_equal("%s step %d" % (tag, t), ks, dev.results(), msgs, Vh, Uh)
+        paths.append(ctx.last_paths(len(V0)))
+    if expect_paths is not None:
+        expect_paths(paths)
+    if own:
+        ctx.close()
+    return paths
+
+
+def test_wave_primitives_selftest(rgc):
+    ctx = rgc.Context(1024, 1)
+    ctx.selftest()
+    ctx.close()
+
+
+def test_config1_single_layer_five_steps(rgc, oracle):
+    cfg = synth.config_single(1 << 20, num_grads=5)
+    ks = [rgc.rgc_k_for_density(1 << 20)]
+    assert ks == [1049]
+
+    def expect(paths):
+        assert paths[0] == [1], "first call has no hint"
+        assert all(p == [0] for p in paths[1:]), "later calls take the one-pass path: %r" % (paths,)
+
+    run_iterations(rgc, oracle, cfg["V"], cfg["G"], ks, tag="C1", expect_paths=expect)
+
+
+@pytest.mark.parametrize("flags_name", ["default", "no_hints"])
+def test_ragged_sizes_batched(rgc, oracle, flags_name):
+    sizes = [1, 2, 3, 63, 64, 65, 255, 256, 257, 1000, 4096, 8191, 8192, 8193, 3 * 8192 + 5,
+             100_003, 4 * 8192, 262_147]
+    g = np.random.default_rng(42)
+    V = [(g.standard_normal(n) * 1e-2).astype(np.float32) for n in sizes]
+    ks = []
+    for i, n in enumerate(sizes):
+        ks.append([1, n, max(1, n // 2), rgc.rgc_k_for_density(n), max(1, n // 10)][i % 5])
+    G_list = [[(g.standard_normal(n) * 1e-3).astype(np.float32) for n in sizes] for _ in range(4)]
+    flags = rgc.RGC_NO_HINTS if flags_name == "no_hints" else 0
+    run_iterations(rgc, oracle, V, G_list, ks, flags=flags, tag="ragged-" + flags_name)
+
+
+def test_unaligned_tensors(rgc, oracle):
+    sizes = [5, 300, 8192 + 7, 50_001]
+    g = np.random.default_rng(43)
+    V = [(g.standard_normal(n)).astype(np.float32) for n in sizes]
+    U = [(g.standard_normal(n)).astype(np.float32) for n in sizes]
+    ks = [2, 3, 9, 51]
+    G_list = [[(g.standard_normal(n) * 0.1).astype(np.float32) for n in sizes] for _ in range(3)]
+    for mis in (1, 2, 3):
+        run_iterations(rgc, oracle, V, G_list, ks, U0=U, m=0.9, misalign=mis, tag="misalign%d" % mis)
+
+
+def test_ties_zeros_and_constant_tensors(rgc, oracle):
+    g = np.random.default_rng(44)
+    n = 70_000
+    quant = (np.round(g.standard_normal(n) * 4) / 4).astype(np.float32)       # ~20 distinct magnitudes
+    V = [quant, np.zeros(n, np.float32), np.full(n, -2.5, np.float32), np.zeros(9000, np.float32),
+         np.where(np.arange(n) % 7 == 0, 1.0, -1.0).astype(np.float32)]
+    ks = [700, 70, 123, 9000, 33]
+    zero = [np.zeros(v.size, np.float32) for v in V]
+    small = [(np.round(g.standard_normal(v.size)) * 0.25).astype(np.float32) for v in V]
+    run_iterations(rgc, oracle, V, [zero, small, zero, small, small], ks, tag="ties")
+
+
+def test_nan_inf_denormal(rgc, oracle):
+    g = np.random.default_rng(45)
+    n = 20_000
+    V = (g.standard_normal(n) * 1e-3).astype(np.float32)
+    V[[5, 77, 9000]] = [np.nan, np.inf, -np.inf]
+    V[100:200] = np.float32(1e-41)       # denormals must survive the add and order correctly
+    V[300:400] = np.float32(-3e-42)
+    G = np.zeros(n, np.float32)
+    G[150] = np.float32(2e-41)
+    G2 = (g.standard_normal(n) * 1e-42).astype(np.float32)
+    run_iterations(rgc, oracle, [V], [[G], [G2], [G2]], [40], tag="special")
+    # a layer of denormals only: selection must order them by magnitude
+    Vd = (g.integers(-2000, 2000, n).astype(np.float64) * 1.4e-45).astype(np.float32)
+    run_iterations(rgc, oracle, [Vd], [[G2], [G2]], [25], tag="denormal")
+
+
+@pytest.mark.parametrize("mask", [True, False])
+def test_momentum_variant(rgc, oracle, mask):
+    g = np.random.default_rng(46)
+    sizes = [40_000, 9000, 130]
+    V = [(g.laplace(0, 5e-3, n)).astype(np.float32) for n in sizes]
+    U = [(g.laplace(0, 1e-3, n)).astype(np.float32) for n in sizes]
+    ks = [rgc.rgc_k_for_density(n) for n in sizes]
+    G_list = [[(g.laplace(0, 1e-3, n)).astype(np.float32) for n in sizes] for _ in range(4)]
+    flags = 0 if mask else rgc.RGC_NO_MOMENTUM_MASK
+    run_iterations(rgc, oracle, V, G_list, ks, U0=U, m=0.9, flags=flags, tag="momentum-mask%d" % mask)
+
+
+def test_results_do_not_depend_on_hints(rgc, oracle):
+    """Poisoned thresholds (too high, too low, random) must only cost time."""
+    cfg = synth.config_single(300_000, num_grads=7)
+    g = np.random.default_rng(47)
+    sizes = [300_000, 50_000, 2048, 64]
+    V = [cfg["V"][0]] + [(g.standard_normal(n) * 1e-2).astype(np.float32) for n in sizes[1:]]
+    G_list = [[cfg["G"][t][0]] + [(g.standard_normal(n) * 1e-3).astype(np.float32) for n in sizes[1:]]
+              for t in range(7)]
+    ks = [rgc.rgc_k_for_density(n) for n in sizes]
+    paths = run_iterations(rgc, oracle, V, G_list, ks, poison=[0, 1, 2, 2, 0, 1], tag="poison")
+    assert any(p != 0 for step in paths[1:] for p in step), "poisoned hints should force fallbacks"
+
+
+def test_hint_signature_change_and_reuse_of_context(rgc, oracle):
+    g = np.random.default_rng(48)
+    ctx = rgc.Context(200_000, 4)
+    for sizes in ([100_000, 777], [90_000, 777, 5000], [100_000, 777]):
+        V = [(g.standard_normal(n) * 1e-2).astype(np.float32) for n in sizes]
+        G_list = [[(g.standard_normal(n) * 1e-3).astype(np.float32) for n in sizes] for _ in range(3)]
+        ks = [rgc.rgc_k_for_density(n) for n in sizes]
+        run_iterations(rgc, oracle, V, G_list, ks, ctx=ctx, tag="reuse%d" % len(sizes))
+    ctx.reset_hints()
+    ctx.close()
+
+
+def test_uniform_distribution_of_the_papers_selection_benchmark(rgc, oracle):
+    cfg = synth.config_uniform(1 << 21, num_grads=3)
+    ks = [rgc.rgc_k_for_density(1 << 21)]
+    run_iterations(rgc, oracle, cfg["V"], cfg["G"], ks, tag="uniform")
+
+
+def test_larger_density(rgc, oracle):
+    """Warm-up densities (Section 2.5 lists 25 % ... 0.1 %) must be correct for any k."""
+    g = np.random.default_rng(49)
+    n = 200_000
+    for ppm in (250_000, 62_500, 15_625, 4_000):
+        V = [(g.standard_normal(n) * 1e-2).astype(np.float32)]
+        G_list = [[(g.standard_normal(n) * 1e-3).astype(np.float32)] for _ in range(2)]
+        run_iterations(rgc, oracle, V, G_list, [rgc.rgc_k_for_density(n, ppm)], tag="ppm%d" % ppm)
+
+
+def test_config2_resnet50_set(rgc, oracle):
+    cfg = synth.config_resnet50(num_grads=3)
+    ks = [rgc.rgc_k_for_density(v.size) for v in cfg["V"]]
+    assert len(ks) == 161 and sum(ks) == 25_670
+    run_iterations(rgc, oracle, cfg["V"], cfg["G"], ks, tag="C2", threads=16)
+
+
+def test_config4_lstm_set_full_size(rgc, oracle):
+    cfg = synth.config_lstm(num_grads=2)
+    ks = [rgc.rgc_k_for_density(v.size) for v in cfg["V"]]
+    assert sum(ks) == 66_024
+    run_iterations(rgc, oracle, cfg["V"], cfg["G"], ks, tag="C4", threads=16)
+
+
+def test_config3_vgg16_set_full_size_momentum(rgc, oracle):
+    cfg = synth.config_vgg16(num_grads=2)
+    ks = [rgc.rgc_k_for_density(v.size) for v in cfg["V"]]
+    assert sum(ks) == 138_351
+    run_iterations(rgc, oracle, cfg["V"], cfg["G"], ks, U0=cfg["U"], m=cfg["momentum"], tag="C3", threads=16)
+
+
+def test_argument_errors(rgc):
+    import torch
+    ctx = rgc.Context(10_000, 2)
+    dev = torch.device("cuda:0")
+    g = torch.zeros(100, device=dev)
+    v = torch.zeros(100, device=dev)
+    oi = torch.zeros(10, dtype=torch.int32, device=dev)
+    ov = torch.zeros(10, device=dev)
+    oc = torch.zeros(4, dtype=torch.int32, device=dev)
+
+    def status(fn):
+        with pytest.raises(rgc.RgcError) as e:
+            fn()
+        return e.value.status
+
+    ok = rgc.LayerList([g], [v], [10], [oi], [ov], oc)
+    rgc.rgc_compress_layers(ctx, ok)
+    assert status(lambda: rgc.rgc_compress_layers(ctx, rgc.LayerList([g], [v], [0], [oi], [ov], oc))) == -1
+    assert status(lambda: rgc.rgc_compress_layers(ctx, rgc.LayerList([g], [v], [101], [oi], [ov], oc))) == -1
+    assert status(lambda: rgc.rgc_compress_layers(ctx, ok, flags=0x80)) == -1
+    three = rgc.LayerList([g, g, g], [v, v, v], [1, 1, 1], [oi, oi, oi], [ov, ov, ov], oc)
+    assert status(lambda: rgc.rgc_compress_layers(ctx, three)) == -1            # more layers than the context
+    big = torch.zeros(20_000, device=dev)
+    assert status(lambda: rgc.rgc_compress_layers(
+        ctx, rgc.LayerList([big], [big.clone()], [1], [oi], [ov], oc))) == -2    # scratch too small
+    bad = rgc.LayerList([g], [v], [10], [oi], [ov], oc)
+    bad.array[0].residual = None
+    assert status(lambda: rgc.rgc_compress_layers(ctx, bad)) == -1
+    torch.cuda.synchronize()
+    ctx.close()
