@@ -1,0 +1,235 @@
+#!/usr/bin/env python3
+"""Benchmark of the RGC hot path on one MI355X.
+
+A step = one pass of the whole hot path over one batch of synthetic input:
+  rgc_compress_layers on the VGG16-shaped layer set (16 tensors, 138.3 M fp32 elements,
+  momentum-corrected variant, density 0.1 %)  followed by
+  rgc_decompress_accumulate of 128 virtual workers' messages (0.1 % each, 80 % from a shared
+  hot set) into a VGG16-shaped dense buffer, averaged by 128.
+All inputs are resident in HBM before the timed region.  The residual and velocity evolve
+from step to step (steady-state RGC) while the gradient rotates through 4 pre-generated sets.
+
+Prints ONE JSON line; see the design doc for the meaning of every field.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+NUM_GRAD_SETS = 4
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def upload(torch, arrays, dev):
+    return [torch.from_numpy(a).to(dev) for a in arrays]
+
+
+class CompressWorkload:
+    def __init__(self, torch, rgc, cfg, dev):
+        self.torch, self.rgc = torch, rgc
+        self.name = cfg["name"]
+        self.m = float(cfg["momentum"])
+        self.sizes = [int(v.size) for v in cfg["V"]]
+        self.total = sum(self.sizes)
+        self.ks = [rgc.rgc_k_for_density(n) for n in self.sizes]
+        self.V = upload(torch, cfg["V"], dev)
+        self.U = upload(torch, cfg["U"], dev) if cfg["U"] is not None else None
+        self.G = [upload(torch, g, dev) for g in cfg["G"]]
+        self.out_idx = [torch.empty(k, dtype=torch.int32, device=dev) for k in self.ks]
+        self.out_val = [torch.empty(k, dtype=torch.float32, device=dev) for k in self.ks]
+        self.out_count = torch.zeros(len(self.ks), dtype=torch.int32, device=dev)
+        self.lists = [rgc.LayerList(g, self.V, self.ks, self.out_idx, self.out_val, self.out_count, self.U)
+                      for g in self.G]
+        per_elem = 20 if self.U is not None else 12      # read G,V(,u); write V(,u)
+        self.alg_bytes_stream = per_elem * self.total
+        self.alg_bytes = per_elem * self.total + (16 if self.U is not None else 12) * sum(self.ks)
+        self.t = 0
+
+    def step(self, ctx, stream, flags=0):
+        self.rgc.rgc_compress_layers(ctx, self.lists[self.t % len(self.lists)], self.m, flags, stream)
+        self.t += 1
+
+
+class DecompressWorkload:
+    def __init__(self, torch, rgc, sizes, workers, dev, synth):
+        self.torch, self.rgc = torch, rgc
+        self.sizes = sizes
+        self.workers = workers
+        idx, val = synth.decompress_messages(sizes, num_workers=workers)
+        self.entries = sum(int(a.size) for row in idx for a in row)
+        self.d_idx = [upload(torch, row, dev) for row in idx]
+        self.d_val = [upload(torch, row, dev) for row in val]
+        self.dense = [torch.empty(n, dtype=torch.float32, device=dev) for n in sizes]
+        self.msgs = rgc.MessageList(self.d_idx, self.d_val, self.dense)
+        self.scale = 1.0 / workers
+        self.alg_bytes = 8 * self.entries + 4 * sum(sizes)
+
+    def step(self, ctx, stream):
+        self.rgc.rgc_decompress_accumulate(ctx, self.msgs, self.scale, self.rgc.RGC_OVERWRITE, stream)
+
+
+def time_loop(torch, fn, steps):
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def measure_compress(torch, rgc, ctx, wl, stream, steps, warmup):
+    """Steady-state ms/iter plus first-call and hint-free timings of one compress workload."""
+    out = {"elements": wl.total, "tensors": len(wl.sizes), "sum_k": sum(wl.ks)}
+    ctx.reset_hints()
+    out["first_call_ms"] = time_loop(torch, lambda: wl.step(ctx, stream), 1)
+    for _ in range(warmup):
+        wl.step(ctx, stream)
+    ms = time_loop(torch, lambda: wl.step(ctx, stream), steps)
+    out["ms_per_iter"] = ms
+    out["gradient_GBps"] = 4.0 * wl.total / ms / 1e6
+    out["alg_bytes"] = wl.alg_bytes
+    out["hbm_frac_algorithmic"] = wl.alg_bytes / (ms * 1e-3) / (HBM_PEAK_GBPS * 1e9)
+    # kernel split and path statistics with the library's event timing switched on
+    ctx.profile_enable(True)
+    slow = 0
+    psteps = min(steps, 20)
+    for _ in range(psteps):
+        wl.step(ctx, stream)
+        slow += sum(1 for p in ctx.last_paths(len(wl.sizes), stream) if p != 0)
+    ms4, calls = ctx.profile_read()
+    ctx.profile_enable(False)
+    out["accumulate_kernel_ms"] = ms4[0] / max(calls[0], 1)
+    out["phase_launches_ms"] = ms4[1] / max(calls[0], 1)
+    out["layers_off_one_pass_path_per_iter"] = slow / psteps
+    out["hint_free_ms"] = time_loop(torch, lambda: wl.step(ctx, stream, rgc.RGC_NO_HINTS), 3)
+    return out
+
+
+def cpu_baseline(torch, wl):
+    """The oracle as it stands, timed on the host on a bounded sample of the same workload: every
+    tensor of the set except the largest one(s), capped at ~40 M elements."""
+    import numpy as np
+    import oracle
+    torch.cuda.synchronize()
+    order = sorted(range(len(wl.sizes)), key=lambda l: wl.sizes[l])
+    pick, tot = [], 0
+    for l in order:
+        if tot + wl.sizes[l] > 40_000_000:
+            break
+        pick.append(l)
+        tot += wl.sizes[l]
+    pick.sort()
+    G = [wl.G[0][l].cpu().numpy() for l in pick]
+    V = [wl.V[l].cpu().numpy().copy() for l in pick]
+    U = [wl.U[l].cpu().numpy().copy() for l in pick] if wl.U is not None else None
+    ks = [wl.ks[l] for l in pick]
+    t0 = time.perf_counter()
+    oracle.compress_layers(G, V, ks, momenta=U, m=wl.m, threads=1)
+    dt = time.perf_counter() - t0
+    return {"value": 4.0 * tot / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": "compress step of %d of the %d %s tensors (%d of %d elements: all but the largest), "
+                      "plain C++ full-sort oracle, 1 thread, %.1f s" % (len(pick), len(wl.sizes), wl.name, tot, wl.total, dt),
+            "host_threads_available": oracle.hardware_threads()}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--skip-others", action="store_true", help="only the headline VGG16 step")
+    ap.add_argument("--skip-cpu", action="store_true", help="leave out the oracle timing")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1")
+
+    import torch
+    import paper_1808_04357_amd as rgc
+    from paper_1808_04357_amd import synth
+    rgc.load_library()             # raises if the HIP library is missing: there is no fallback
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.current_stream()
+
+    log("generating VGG16-shaped inputs (138.3 M elements, %d gradient sets)..." % NUM_GRAD_SETS)
+    t0 = time.perf_counter()
+    vgg = CompressWorkload(torch, rgc, synth.config_vgg16(num_grads=NUM_GRAD_SETS), dev)
+    log("  %.1f s; generating 128 workers' messages..." % (time.perf_counter() - t0))
+    dec = DecompressWorkload(torch, rgc, vgg.sizes, 128, dev, synth)
+    ctx = rgc.Context(vgg.total, 256)
+    log("  done (%.1f s)" % (time.perf_counter() - t0))
+
+    def step():
+        vgg.step(ctx, stream)
+        dec.step(ctx, stream)
+
+    # ---- headline: whole step, inputs resident, W warmup + exactly K timed steps
+    for _ in range(args.warmup):
+        step()
+    ms_step = time_loop(torch, step, args.steps)
+    step_bytes = vgg.alg_bytes + dec.alg_bytes
+    value = 4.0 * vgg.total / ms_step / 1e6          # gradient GB/s through the whole step
+
+    # ---- the two halves and the dominant kernel, measured live with HIP events
+    ms_dec = time_loop(torch, lambda: dec.step(ctx, stream), args.steps)
+    comp = measure_compress(torch, rgc, ctx, vgg, stream, args.steps, args.warmup)
+    ctx.profile_enable(True)
+    for _ in range(min(args.steps, 20)):
+        dec.step(ctx, stream)
+    ms4, calls = ctx.profile_read()
+    ctx.profile_enable(False)
+    dec_info = {"ms_per_iter": ms_dec, "entries": dec.entries, "workers": dec.workers,
+                "alg_bytes": dec.alg_bytes,
+                "hbm_frac_algorithmic": dec.alg_bytes / (ms_dec * 1e-3) / (HBM_PEAK_GBPS * 1e9),
+                "table_kernel_ms": ms4[2] / max(calls[1], 1), "tile_kernel_ms": ms4[3] / max(calls[1], 1)}
+    k_ms = comp["accumulate_kernel_ms"]
+    achieved = vgg.alg_bytes_stream / (k_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "accumulate_kernel (fused residual/momentum accumulate + candidate collect)",
+                "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                "traffic": None, "bytes_per_launch": vgg.alg_bytes_stream, "avg_launch_ms": k_ms}
+
+    others = {}
+    if not args.skip_others:
+        del step
+        for name, make in (("lstm", lambda: synth.config_lstm(num_grads=NUM_GRAD_SETS)),
+                           ("resnet50", lambda: synth.config_resnet50(num_grads=NUM_GRAD_SETS)),
+                           ("single_1Mi", lambda: synth.config_single(1 << 20, num_grads=NUM_GRAD_SETS))):
+            log("workload %s..." % name)
+            wl = CompressWorkload(torch, rgc, make(), dev)
+            others[name] = measure_compress(torch, rgc, ctx, wl, stream, args.steps, args.warmup)
+            del wl
+            torch.cuda.empty_cache()
+
+    cpu = None
+    if not args.skip_cpu:
+        log("timing the CPU oracle on a bounded sample...")
+        cpu = cpu_baseline(torch, vgg)
+
+    line = {
+        "metric": "gradient GB/s through accumulate+top-k+pack (% HBM peak); ms/iter per layer set",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "VGG16-shaped layer set: compress (16 tensors, 138,344,128 elements, momentum 0.9, "
+                               "density 0.1 %) + decompress of 128 virtual workers into the same shape",
+                   "step": "rgc_compress_layers + rgc_decompress_accumulate", "gradient_sets_rotated": NUM_GRAD_SETS},
+        "hbm_frac_step_algorithmic": step_bytes / (ms_step * 1e-3) / (HBM_PEAK_GBPS * 1e9),
+        "compress": comp, "decompress": dec_info, "other_workloads": others,
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -133,6 +133,16 @@ int rgc_selftest(rgc_ctx* ctx, void* hip_stream);
  * inconsistency.  A diagnostic for tests and benchmarks. */
 int rgc_last_paths(rgc_ctx* ctx, int32_t* out, int32_t num_layers, void* hip_stream);
 
+/* Kernel timing for benchmarks.  rgc_profile_enable(ctx, 1) makes every later compression and
+ * decompression call record HIP events on the caller's stream around its kernels (a few extra
+ * microseconds per call); rgc_profile_enable(ctx, 0) stops that.  rgc_profile_read synchronises
+ * the recorded events and returns, summed over the calls since the last read, the milliseconds
+ * spent in  out_ms[0] the streaming accumulate kernel, out_ms[1] the phase launches after it,
+ * out_ms[2] the decompression table kernel, out_ms[3] the decompression tile kernel, and the
+ * number of compression / decompression calls in out_calls[0..1].  The record is then cleared. */
+int rgc_profile_enable(rgc_ctx* ctx, int enable);
+int rgc_profile_read(rgc_ctx* ctx, double* out_ms, int64_t* out_calls);
+
 /* Text for a status code; for RGC_EHIP the text of the last HIP error seen by this thread. */
 const char* rgc_strerror(int status);
 

@@ -25,7 +25,7 @@ _LIB_PATH = os.path.join(_HERE, "librgc.so")
 
 EXPORTS = ["rgc_create", "rgc_destroy", "rgc_k_for_density", "rgc_compress_layers",
            "rgc_decompress_accumulate", "rgc_reset_hints", "rgc_poison_hints", "rgc_selftest",
-           "rgc_last_paths", "rgc_strerror"]
+           "rgc_last_paths", "rgc_profile_enable", "rgc_profile_read", "rgc_strerror"]
 
 
 class RgcError(RuntimeError):
@@ -82,6 +82,10 @@ def load_library() -> ctypes.CDLL:
     L.rgc_selftest.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
     L.rgc_last_paths.restype = ctypes.c_int
     L.rgc_last_paths.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32), ctypes.c_int32, ctypes.c_void_p]
+    L.rgc_profile_enable.restype = ctypes.c_int
+    L.rgc_profile_enable.argtypes = [ctypes.c_void_p, ctypes.c_int]
+    L.rgc_profile_read.restype = ctypes.c_int
+    L.rgc_profile_read.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     L.rgc_strerror.restype = ctypes.c_char_p
     L.rgc_strerror.argtypes = [ctypes.c_int]
     _lib = L
@@ -138,6 +142,16 @@ class Context:
 
     def selftest(self, stream=None) -> None:
         _check(self._lib.rgc_selftest(self._h, _stream(stream)))
+
+    def profile_enable(self, enable: bool) -> None:
+        _check(self._lib.rgc_profile_enable(self._h, 1 if enable else 0))
+
+    def profile_read(self):
+        """-> (ms[4]: accumulate, phases, decompress table, decompress tiles; calls[2])."""
+        ms = (ctypes.c_double * 4)()
+        calls = (ctypes.c_int64 * 2)()
+        _check(self._lib.rgc_profile_read(self._h, ms, calls))
+        return list(ms), list(calls)
 
     def last_paths(self, num_layers: int, stream=None) -> List[int]:
         out = (ctypes.c_int32 * num_layers)()

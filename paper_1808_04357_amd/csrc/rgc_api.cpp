@@ -5,6 +5,7 @@
 
 #include <algorithm>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <memory>
 #include <new>
@@ -33,8 +34,22 @@ int fail_hip(hipError_t e, const char* what) {
     if (e_ != hipSuccess) return fail_hip(e_, #call);   \
   } while (0)
 
-constexpr uint32_t kChunk = 8192;          // elements per wave-chunk
-constexpr uint32_t kCap = kChunk / 64;     // candidate slots per wave-chunk
+constexpr uint32_t kChunkDefault = 8192;   // elements per wave-chunk
+constexpr uint32_t kChunkMin = 1024;
+constexpr uint32_t kCapDiv = 32;           // candidate slots per wave-chunk = chunk / 32
+
+// Elements per wave-chunk; RGC_CHUNK (a power of two >= 1024) overrides the default for tuning.
+uint32_t chunk_elems() {
+  static const uint32_t v = [] {
+    const char* e = std::getenv("RGC_CHUNK");
+    if (e) {
+      const long x = std::atol(e);
+      if (x >= static_cast<long>(kChunkMin) && x <= (1l << 20) && (x & (x - 1)) == 0) return static_cast<uint32_t>(x);
+    }
+    return kChunkDefault;
+  }();
+  return v;
+}
 constexpr int kPlanCache = 8;
 constexpr int kLaunches = 6;               // streaming pass + at most five phase launches
 
@@ -128,6 +143,11 @@ struct rgc_ctx {
   bool hints_reset = true;
   int32_t last_layers = 0;
   DecompressPlan dplan;
+  // benchmark timing: events recorded around the kernels of each call while enabled
+  bool profiling = false;
+  std::vector<hipEvent_t> ev_compress;     // triples: before accumulate, after it, after the phases
+  std::vector<hipEvent_t> ev_decompress;   // triples: before table, after it, after the tiles
+  std::vector<hipEvent_t> ev_pool;
 };
 
 namespace {
@@ -143,6 +163,7 @@ int build_compress_plan(rgc_ctx* ctx, CompressPlan& P, const rgc_layer* layers, 
   std::stable_sort(order.begin(), order.end(),
                    [&](int32_t a, int32_t b) { return layers[a].n > layers[b].n; });
   std::vector<LayerDesc> desc(L);
+  const uint32_t kChunk = chunk_elems(), kCap = kChunk / kCapDiv;
   uint32_t wc = 0, wg = 0;
   for (int32_t o = 0; o < L; ++o) {
     const int32_t l = order[o];
@@ -165,7 +186,8 @@ int build_compress_plan(rgc_ctx* ctx, CompressPlan& P, const rgc_layer* layers, 
     d.vec_ok = (bits & 15u) == 0 ? 1u : 0u;
     // speed-hint policy: aim the threshold at rank 2k + margin of this call, accept up to cmax
     const uint64_t k = d.k;
-    const uint64_t margin = std::max<uint64_t>(k / 2, 32);
+    uint64_t margin = std::max<uint64_t>(k / 2, 32);
+    if (d.n <= kChunk) margin = std::min<uint64_t>(margin, std::max<uint64_t>(kCap / 4, 8));   // one list holds it all
     const uint64_t span = std::max<uint64_t>(d.n, kChunk);
     const uint64_t target = 2 * k + margin;   // rank the next threshold is aimed at
     const uint64_t per_chunk = (target * kChunk + span - 1) / span;         // expected per wave-chunk
@@ -195,6 +217,19 @@ int build_compress_plan(rgc_ctx* ctx, CompressPlan& P, const rgc_layer* layers, 
   P.num_wgs = wg;
   P.valid = true;
   return RGC_OK;
+}
+
+hipError_t take_event(rgc_ctx* ctx, hipStream_t stream, std::vector<hipEvent_t>& into) {
+  hipEvent_t e = nullptr;
+  if (!ctx->ev_pool.empty()) {
+    e = ctx->ev_pool.back();
+    ctx->ev_pool.pop_back();
+  } else {
+    hipError_t r = hipEventCreate(&e);
+    if (r != hipSuccess) return r;
+  }
+  into.push_back(e);
+  return hipEventRecord(e, stream);
 }
 
 void destroy_plan(CompressPlan& P) {
@@ -245,6 +280,7 @@ int rgc_create(rgc_ctx** out, int device_id, int64_t max_total_elems, int32_t ma
   c->device = device_id;
   c->max_total = max_total_elems;
   c->max_layers = max_layers;
+  const uint32_t kChunk = chunk_elems(), kCap = kChunk / kCapDiv;
   const uint64_t wc_max = static_cast<uint64_t>((max_total_elems + kChunk - 1) / kChunk) + static_cast<uint64_t>(max_layers);
   if (wc_max > 0x7FFFFFFFull) return RGC_ENOMEM;
   c->wc_max = static_cast<uint32_t>(wc_max);
@@ -253,7 +289,7 @@ int rgc_create(rgc_ctx** out, int device_id, int64_t max_total_elems, int32_t ma
   auto chk = [&](hipError_t r) { if (e == hipSuccess && r != hipSuccess) e = r; };
   chk(c->d_state.alloc(L));
   chk(c->d_hist.alloc(L * kHistBins));
-  chk(c->d_coarse.alloc(L * kCoarseBins));
+  chk(c->d_coarse.alloc(L * kCoarseRep * kCoarseBins));
   chk(c->d_members.alloc(L * kMemberMax));
   chk(c->d_cand_cnt.alloc(wc_max));
   chk(c->d_wc_a.alloc(wc_max));
@@ -262,7 +298,7 @@ int rgc_create(rgc_ctx** out, int device_id, int64_t max_total_elems, int32_t ma
   chk(c->d_err.alloc(1));
   if (e == hipSuccess) chk(hipMemset(c->d_state.p, 0, sizeof(LayerState) * L));
   if (e == hipSuccess) chk(hipMemset(c->d_hist.p, 0, sizeof(uint32_t) * L * kHistBins));
-  if (e == hipSuccess) chk(hipMemset(c->d_coarse.p, 0, sizeof(uint32_t) * L * kCoarseBins));
+  if (e == hipSuccess) chk(hipMemset(c->d_coarse.p, 0, sizeof(uint32_t) * L * kCoarseRep * kCoarseBins));
   if (e == hipSuccess) chk(hipMemset(c->d_cand_cnt.p, 0, sizeof(uint32_t) * wc_max));
   if (e == hipSuccess) chk(hipMemset(c->d_err.p, 0, sizeof(uint32_t)));
   if (e == hipSuccess) chk(hipDeviceSynchronize());
@@ -293,6 +329,8 @@ int rgc_destroy(rgc_ctx* ctx) {
   ctx->d_wc_b.release();
   ctx->d_slots.release();
   ctx->d_err.release();
+  for (auto* v : {&ctx->ev_compress, &ctx->ev_decompress, &ctx->ev_pool})
+    for (hipEvent_t e : *v) (void)hipEventDestroy(e);
   delete ctx;
   return RGC_OK;
 }
@@ -373,18 +411,21 @@ int rgc_compress_layers(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layer
   A.wc_a = ctx->d_wc_a.p;
   A.wc_b = ctx->d_wc_b.p;
   A.errflag = ctx->d_err.p;
-  A.chunk = kChunk;
-  A.cap = kCap;
+  A.chunk = chunk_elems();
+  A.cap = A.chunk / kCapDiv;
   A.use_hints = (sig_same && !no_hints) ? 1u : 0u;
   A.update_hints = no_hints ? 0u : 1u;
   A.mask_momentum = (flags & RGC_NO_MOMENTUM_MASK) ? 0u : 1u;
   A.m = momentum;
   A.launch = 1;
+  if (ctx->profiling) RGC_HIP(take_event(ctx, stream, ctx->ev_compress));
   RGC_HIP(launch_accumulate(A, plan->num_wgs, stream));
+  if (ctx->profiling) RGC_HIP(take_event(ctx, stream, ctx->ev_compress));
   for (int launch = 2; launch <= kLaunches; ++launch) {
     A.launch = static_cast<uint32_t>(launch);
     RGC_HIP(launch_phase(A, plan->num_wgs, stream));
   }
+  if (ctx->profiling) RGC_HIP(take_event(ctx, stream, ctx->ev_compress));
   if (!no_hints) {
     ctx->hint_sig.resize(num_layers);
     for (int32_t l = 0; l < num_layers; ++l) ctx->hint_sig[l] = {layers[l].n, layers[l].k};
@@ -552,9 +593,41 @@ int rgc_decompress_accumulate(rgc_ctx* ctx, const rgc_msg* msgs, int32_t num_wor
   DecompressArgs A = P.args;
   A.add_to_dst = (flags == RGC_ADD_TO_DST) ? 1u : 0u;
   A.scale = scale;
+  if (ctx->profiling) RGC_HIP(take_event(ctx, stream, ctx->ev_decompress));
   RGC_HIP(launch_decompress_table(A, stream));
+  if (ctx->profiling) RGC_HIP(take_event(ctx, stream, ctx->ev_decompress));
   RGC_HIP(launch_decompress_tiles(A, stream));
+  if (ctx->profiling) RGC_HIP(take_event(ctx, stream, ctx->ev_decompress));
   return RGC_OK;
+}
+
+int rgc_profile_enable(rgc_ctx* ctx, int enable) {
+  if (!ctx) return RGC_EINVAL;
+  ctx->profiling = enable != 0;
+  return RGC_OK;
+}
+
+int rgc_profile_read(rgc_ctx* ctx, double* out_ms, int64_t* out_calls) {
+  if (!ctx || !out_ms || !out_calls) return RGC_EINVAL;
+  DeviceGuard guard(ctx->device);
+  for (int i = 0; i < 4; ++i) out_ms[i] = 0.0;
+  auto drain = [&](std::vector<hipEvent_t>& ev, double* ms, int64_t* calls) -> int {
+    *calls = static_cast<int64_t>(ev.size() / 3);
+    for (size_t i = 0; i + 2 < ev.size(); i += 3) {
+      float a = 0.f, b = 0.f;
+      RGC_HIP(hipEventSynchronize(ev[i + 2]));
+      RGC_HIP(hipEventElapsedTime(&a, ev[i], ev[i + 1]));
+      RGC_HIP(hipEventElapsedTime(&b, ev[i + 1], ev[i + 2]));
+      ms[0] += a;
+      ms[1] += b;
+    }
+    for (hipEvent_t e : ev) ctx->ev_pool.push_back(e);
+    ev.clear();
+    return RGC_OK;
+  };
+  int rc = drain(ctx->ev_compress, out_ms, &out_calls[0]);
+  if (rc != RGC_OK) return rc;
+  return drain(ctx->ev_decompress, out_ms + 2, &out_calls[1]);
 }
 
 }  // extern "C"

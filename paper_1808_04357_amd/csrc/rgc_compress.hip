@@ -216,11 +216,28 @@ __device__ __forceinline__ void flush_hist(const uint32_t* lds_hist, uint32_t* g
 
 __device__ __forceinline__ uint32_t bit_length(uint32_t x) { return x ? 32u - __clz(x) : 0u; }
 
-// Coarse-bin shift for the next call so that the k-th key lands near bin 512..1023.
+// Coarse-bin shift for the next call so that the k-th key lands in the second quarter of the
+// coarse bins (kCoarseBins / 4 .. kCoarseBins / 2).
 __device__ __forceinline__ uint32_t shift_for(uint32_t T, uint32_t tau) {
   const uint32_t d = T >= tau ? T - tau : 0u;
   const uint32_t bl = bit_length(d);
-  return bl > 10u ? bl - 10u : 0u;
+  constexpr uint32_t kKeep = 9u;   // log2(kCoarseBins / 2)
+  static_assert(kCoarseBins == 1024, "kKeep is tied to the number of coarse bins");
+  return bl > kKeep ? bl - kKeep : 0u;
+}
+
+// Threshold for the next call = rank-based estimate from this call + the observed drift of the
+// k-th key between the last two calls (a steadily growing or shrinking residual moves the
+// threshold by about the same amount every call).  Speed only.
+__device__ __forceinline__ uint32_t drifted_tau(uint32_t tau_rank, uint32_t T, uint32_t T_prev, bool has_prev) {
+  long long d = has_prev ? static_cast<long long>(T) - static_cast<long long>(T_prev) : 0ll;
+  const long long lim = 1ll << 22;               // half an octave per call at most
+  d = d > lim ? lim : (d < -lim ? -lim : d);
+  if (d > 0) d -= d >> 3;                        // raising tau is the risky direction
+  long long t = static_cast<long long>(tau_rank) + d;
+  if (t < 0) t = 0;
+  if (t > static_cast<long long>(kKeyMask)) t = kKeyMask;
+  return static_cast<uint32_t>(t);
 }
 
 struct ResolveShared {
@@ -324,10 +341,15 @@ __device__ void resolve_digit(const CompressArgs& A, uint32_t l, const LayerDesc
       st->next_phase = PH_COUNT;
       if (A.update_hints) {
         if (pend == 2u) {
-          st->tau = st->tau_next; st->shift = shift_for(T, st->tau_next); st->hint_valid = 1u;
+          const uint32_t tn = st->tau_next;
+          st->tau = drifted_tau(tn, T, st->T_prev, A.use_hints && st->has_prev);
+          st->shift = shift_for(T, tn);
+          st->hint_valid = 1u;
         } else {
           st->hint_valid = 0u;
         }
+        st->T_prev = T;
+        st->has_prev = 1u;
       }
     }
     st->hint_pending = pend;
@@ -340,12 +362,20 @@ __device__ void resolve_digit(const CompressArgs& A, uint32_t l, const LayerDesc
 __device__ void resolve_collect(const CompressArgs& A, uint32_t l, const LayerDesc& L, LayerState* st,
                                 ResolveShared& sh) {
   const uint32_t t = threadIdx.x;
-  uint32_t* coarse = A.coarse + static_cast<size_t>(l) * kCoarseBins;
+  uint32_t* coarse = A.coarse + static_cast<size_t>(l) * kCoarseRep * kCoarseBins;
   uint32_t total = 0, bad = 0;
-  for (uint32_t c = t; c < L.wc_count; c += kBlockThreads) {
-    const uint32_t v = A.cand_cnt[L.wc_first + c];
-    bad |= (v > A.cap) ? 1u : 0u;
-    total += v;
+  for (uint32_t c0 = 0; c0 < L.wc_count; c0 += 4u * kBlockThreads) {
+    uint32_t v[4];
+#pragma unroll
+    for (uint32_t j = 0; j < 4u; ++j) {
+      const uint32_t c = c0 + j * kBlockThreads + t;
+      v[j] = c < L.wc_count ? ld_agent(&A.cand_cnt[L.wc_first + c]) : 0u;
+    }
+#pragma unroll
+    for (uint32_t j = 0; j < 4u; ++j) {
+      bad |= (v[j] > A.cap) ? 1u : 0u;
+      total += v[j];
+    }
   }
   uint32_t cand_total;
   (void)block_excl_scan(total, sh.scan, cand_total);
@@ -356,7 +386,13 @@ __device__ void resolve_collect(const CompressArgs& A, uint32_t l, const LayerDe
   uint32_t s = 0;
 #pragma unroll
   for (uint32_t i = 0; i < kPer; ++i) {
-    h[i] = ld_agent(&coarse[kCoarseBins - 1u - (t * kPer + i)]);
+    uint32_t part[kCoarseRep];
+#pragma unroll
+    for (uint32_t rep = 0; rep < kCoarseRep; ++rep)
+      part[rep] = ld_agent(&coarse[rep * kCoarseBins + kCoarseBins - 1u - (t * kPer + i)]);
+    h[i] = 0;
+#pragma unroll
+    for (uint32_t rep = 0; rep < kCoarseRep; ++rep) h[i] += part[rep];
     s += h[i];
   }
   if (t == 0) { sh.bin = 0xFFFFFFFFu; sh.hbin = 0xFFFFFFFFu; sh.above = 0; sh.cnt = 0; sh.hcum = 0; }
@@ -380,7 +416,10 @@ __device__ void resolve_collect(const CompressArgs& A, uint32_t l, const LayerDe
     }
   }
 #pragma unroll
-  for (uint32_t i = 0; i < kPer; ++i) coarse[kCoarseBins - 1u - (t * kPer + i)] = 0u;
+  for (uint32_t i = 0; i < kPer; ++i)
+#pragma unroll
+    for (uint32_t rep = 0; rep < kCoarseRep; ++rep)
+      coarse[rep * kCoarseBins + kCoarseBins - 1u - (t * kPer + i)] = 0u;
   __syncthreads();
   if (t == 0) {
     const bool ok = !bad && cand_total >= k && hist_total == cand_total && sh.bin != 0xFFFFFFFFu &&
@@ -499,7 +538,7 @@ __global__ void __launch_bounds__(kBlockThreads) accumulate_kernel(CompressArgs 
     const uint32_t end = (L.n - begin) < A.chunk ? L.n : begin + A.chunk;
     Collector c;
     c.slot = A.slots + static_cast<size_t>(L.wc_first + wc_local) * A.cap;
-    c.coarse = A.coarse + static_cast<size_t>(l) * kCoarseBins;
+    c.coarse = A.coarse + (static_cast<size_t>(l) * kCoarseRep + (wg & (kCoarseRep - 1))) * kCoarseBins;
     c.cap = A.cap;
     c.count = 0;
     c.tau = st->tau;
@@ -508,7 +547,7 @@ __global__ void __launch_bounds__(kBlockThreads) accumulate_kernel(CompressArgs 
     if (collect) {
       if (mom) stream_chunk<true, true>(L, begin, end, A.m, c, lds_hist);
       else stream_chunk<false, true>(L, begin, end, A.m, c, lds_hist);
-      if (lane_id() == 0) A.cand_cnt[L.wc_first + wc_local] = c.count;
+      if (lane_id() == 0) st_agent(&A.cand_cnt[L.wc_first + wc_local], c.count);
     } else {
       if (mom) stream_chunk<true, false>(L, begin, end, A.m, c, lds_hist);
       else stream_chunk<false, false>(L, begin, end, A.m, c, lds_hist);
@@ -587,8 +626,8 @@ __device__ void phase_count(const CompressArgs& A, uint32_t l, const LayerDesc& 
     const uint32_t gt_all = wave_total(wave_incl_scan(gt));
     const uint32_t eq_all = wave_total(wave_incl_scan(eq));
     if (lane_id() == 0) {
-      A.wc_a[L.wc_first + wc_local] = gt_all;
-      A.wc_b[L.wc_first + wc_local] = eq_all;
+      st_agent(&A.wc_a[L.wc_first + wc_local], gt_all);
+      st_agent(&A.wc_b[L.wc_first + wc_local], eq_all);
     }
   }
   if (last_block_of_layer(&st->done, L.wg_count, &sh.flag)) {
@@ -676,12 +715,13 @@ __device__ void phase_sel(const CompressArgs& A, uint32_t l, const LayerDesc& L,
           ++hi;
         } else if (bin == bstar) {
           const uint32_t at = atomicAdd(&st->nmembers, 1u);
-          if (at < static_cast<uint32_t>(kMemberMax)) members[at] = composite(key, e.y);
+          if (at < static_cast<uint32_t>(kMemberMax))
+            __hip_atomic_store(&members[at], composite(key, e.y), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
       }
     }
     const uint32_t hi_all = wave_total(wave_incl_scan(hi));
-    if (lane == 0) A.wc_a[wc] = hi_all;
+    if (lane == 0) st_agent(&A.wc_a[wc], hi_all);
   }
   if (!last_block_of_layer(&st->done, L.wg_count, &sh.flag)) return;
 
@@ -702,7 +742,7 @@ __device__ void phase_sel(const CompressArgs& A, uint32_t l, const LayerDesc& L,
     const uint32_t idx = 0xFFFFFFFFu - static_cast<uint32_t>(sortbuf[i] & 0xFFFFFFFFull);
     atomicAdd(&A.wc_a[L.wc_first + idx / A.chunk], 1u);
   }
-  __threadfence();
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the credits are device-scope atomics
   __syncthreads();
   scan_chunks(A.wc_a + L.wc_first, nullptr, L.wc_count, 0u, false, sh.scan, &sh.cnt);
   __syncthreads();
@@ -713,8 +753,10 @@ __device__ void phase_sel(const CompressArgs& A, uint32_t l, const LayerDesc& L,
     st->T = T;
     if (A.update_hints) {
       const uint32_t tn = st->tau_next <= T ? st->tau_next : T;
-      st->tau = tn;
+      st->tau = drifted_tau(tn, T, st->T_prev, st->has_prev != 0u);
       st->shift = shift_for(T, tn);
+      st->T_prev = T;
+      st->has_prev = 1u;
     }
     st->next_phase = PH_OUT_C;
     st->next_launch = A.launch + 1u;

@@ -66,23 +66,31 @@ __device__ __forceinline__ uint32_t ld_agent(const uint32_t* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// "Last workgroup of the layer" election.  Every thread has finished its global writes.
+__device__ __forceinline__ void st_agent(uint32_t* p, uint32_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// "Last workgroup of the layer" election.  Contract: everything the elected workgroup will
+// read from this phase was written with device-scope atomics or st_agent() (both go to the
+// device's coherence point, unlike plain stores which may sit in one XCD's L2 until the kernel
+// ends), and is read back with ld_agent().  Waiting for the wave's outstanding memory
+// operations before the counter increment is then all the ordering needed; a full
+// __threadfence() here would force an L2 write-back per workgroup and costs several times the
+// streaming pass itself.
 // Returns true in every thread of exactly one workgroup per (layer, phase): the one whose
 // increment completes the count.  That workgroup also resets the counter.
 __device__ __forceinline__ bool last_block_of_layer(uint32_t* done, uint32_t expect,
                                                     uint32_t* lds_flag) {
-  __threadfence();
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   if (threadIdx.x == 0) {
     const uint32_t prev = atomicAdd(done, 1u);
     const bool last = (prev + 1u == expect);
-    if (last) __hip_atomic_store(done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (last) st_agent(done, 0u);
     *lds_flag = last ? 1u : 0u;
   }
   __syncthreads();
-  const bool last = (*lds_flag != 0u);
-  if (last) __threadfence();
-  return last;
+  return *lds_flag != 0u;
 }
 
 }  // namespace rgc

@@ -13,7 +13,8 @@ constexpr int kBlockThreads = 256;                 // 4 waves per workgroup
 constexpr int kWavesPerBlock = kBlockThreads / kWaveSize;
 constexpr int kGroupElems = kWaveSize * 4;         // one float4 per lane per step
 constexpr int kHistBins = 4096;                    // radix digit of 12 bits (31-bit key = 12+12+7)
-constexpr int kCoarseBins = 2048;                  // candidate histogram bins (hinted path)
+constexpr int kCoarseBins = 1024;                  // candidate histogram bins (hinted path)
+constexpr int kCoarseRep = 8;                      // replicas of it, to spread same-address atomics
 constexpr int kMemberMax = 4096;                   // candidates of one coarse bin ranked in LDS
 constexpr uint32_t kKeyMask = 0x7FFFFFFFu;
 
@@ -66,9 +67,11 @@ struct LayerState {
   // speed hints (never influence results)
   uint32_t hint_valid;
   uint32_t tau;          // candidate threshold key for the next call
-  uint32_t shift;        // coarse bin = min((key - tau) >> shift, 2047)
+  uint32_t shift;        // coarse bin = min((key - tau) >> shift, kCoarseBins - 1)
   uint32_t tau_next;     // being derived during this call
   uint32_t hint_pending; // multi-pass: 0 none found yet / 1 refine in the next digit / 2 final
+  uint32_t T_prev;       // threshold key of the previous call (drift estimate), if has_prev
+  uint32_t has_prev;
   uint32_t pad;
 };
 
@@ -77,7 +80,7 @@ struct CompressArgs {
   LayerState* state;
   const uint32_t* wg2layer;
   uint32_t* hist;        // [layers][kHistBins]
-  uint32_t* coarse;      // [layers][kCoarseBins]
+  uint32_t* coarse;      // [layers][kCoarseRep][kCoarseBins]
   unsigned long long* members;  // [layers][kMemberMax]
   uint32_t* cand_cnt;    // [wave-chunks]
   uint2* slots;          // [wave-chunks][cap] (float bits, index), ascending index per chunk
