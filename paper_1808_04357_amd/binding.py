@@ -25,7 +25,7 @@ _LIB_PATH = os.path.join(_HERE, "librgc.so")
 
 EXPORTS = ["rgc_create", "rgc_destroy", "rgc_k_for_density", "rgc_compress_layers",
            "rgc_decompress_accumulate", "rgc_reset_hints", "rgc_poison_hints", "rgc_selftest",
-           "rgc_last_paths", "rgc_profile_enable", "rgc_profile_read", "rgc_strerror"]
+           "rgc_last_paths", "rgc_last_stats", "rgc_profile_enable", "rgc_profile_read", "rgc_strerror"]
 
 
 class RgcError(RuntimeError):
@@ -82,6 +82,8 @@ def load_library() -> ctypes.CDLL:
     L.rgc_selftest.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
     L.rgc_last_paths.restype = ctypes.c_int
     L.rgc_last_paths.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32), ctypes.c_int32, ctypes.c_void_p]
+    L.rgc_last_stats.restype = ctypes.c_int
+    L.rgc_last_stats.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64), ctypes.c_int32, ctypes.c_void_p]
     L.rgc_profile_enable.restype = ctypes.c_int
     L.rgc_profile_enable.argtypes = [ctypes.c_void_p, ctypes.c_int]
     L.rgc_profile_read.restype = ctypes.c_int
@@ -152,6 +154,12 @@ class Context:
         calls = (ctypes.c_int64 * 2)()
         _check(self._lib.rgc_profile_read(self._h, ms, calls))
         return list(ms), list(calls)
+
+    def last_stats(self, num_layers: int, stream=None) -> List[List[int]]:
+        """-> per layer [path, candidates, exactly ranked candidates, threshold key]."""
+        out = (ctypes.c_int64 * (4 * num_layers))()
+        _check(self._lib.rgc_last_stats(self._h, out, int(num_layers), _stream(stream)))
+        return [list(out[4 * l:4 * l + 4]) for l in range(num_layers)]
 
     def last_paths(self, num_layers: int, stream=None) -> List[int]:
         out = (ctypes.c_int32 * num_layers)()

@@ -38,13 +38,13 @@ constexpr uint32_t kChunkDefault = 8192;   // elements per wave-chunk
 constexpr uint32_t kChunkMin = 1024;
 constexpr uint32_t kCapDiv = 32;           // candidate slots per wave-chunk = chunk / 32
 
-// Elements per wave-chunk; RGC_CHUNK (a power of two >= 1024) overrides the default for tuning.
+// Elements per wave-chunk; RGC_CHUNK (a multiple of 256, >= 1024) overrides the default for tuning.
 uint32_t chunk_elems() {
   static const uint32_t v = [] {
     const char* e = std::getenv("RGC_CHUNK");
     if (e) {
       const long x = std::atol(e);
-      if (x >= static_cast<long>(kChunkMin) && x <= (1l << 20) && (x & (x - 1)) == 0) return static_cast<uint32_t>(x);
+      if (x >= static_cast<long>(kChunkMin) && x <= (1l << 20) && (x % 256) == 0) return static_cast<uint32_t>(x);
     }
     return kChunkDefault;
   }();
@@ -418,6 +418,10 @@ int rgc_compress_layers(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layer
   A.mask_momentum = (flags & RGC_NO_MOMENTUM_MASK) ? 0u : 1u;
   A.m = momentum;
   A.launch = 1;
+  {
+    const char* e = std::getenv("RGC_DEBUG");
+    A.debug = e ? static_cast<uint32_t>(std::atol(e)) : 0u;
+  }
   if (ctx->profiling) RGC_HIP(take_event(ctx, stream, ctx->ev_compress));
   RGC_HIP(launch_accumulate(A, plan->num_wgs, stream));
   if (ctx->profiling) RGC_HIP(take_event(ctx, stream, ctx->ev_compress));
@@ -446,6 +450,22 @@ int rgc_last_paths(rgc_ctx* ctx, int32_t* out, int32_t num_layers, void* hip_str
   RGC_HIP(hipStreamSynchronize(stream));
   for (int32_t l = 0; l < num_layers; ++l) out[l] = static_cast<int32_t>(st[l].path);
   return err ? RGC_EINTERNAL : RGC_OK;
+}
+
+int rgc_last_stats(rgc_ctx* ctx, int64_t* out, int32_t num_layers, void* hip_stream) {
+  if (!ctx || !out || num_layers < 1 || num_layers > ctx->max_layers) return RGC_EINVAL;
+  DeviceGuard guard(ctx->device);
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  std::vector<LayerState> st(num_layers);
+  RGC_HIP(hipMemcpyAsync(st.data(), ctx->d_state.p, sizeof(LayerState) * num_layers, hipMemcpyDeviceToHost, stream));
+  RGC_HIP(hipStreamSynchronize(stream));
+  for (int32_t l = 0; l < num_layers; ++l) {
+    out[4 * l + 0] = st[l].path;
+    out[4 * l + 1] = st[l].stat_candidates;
+    out[4 * l + 2] = st[l].stat_members;
+    out[4 * l + 3] = st[l].T;
+  }
+  return RGC_OK;
 }
 
 int rgc_selftest(rgc_ctx* ctx, void* hip_stream) {

@@ -29,10 +29,12 @@ namespace {
 __device__ __forceinline__ uint32_t fbits(float x) { return __float_as_uint(x); }
 
 typedef float vf4 __attribute__((ext_vector_type(4)));   // one 16-byte access per lane
+typedef uint32_t vu2 __attribute__((ext_vector_type(2))); // a candidate: (float bits, index)
 
 struct Collector {
-  uint2* slot;       // this wave-chunk's candidate list
-  uint32_t* coarse;  // the layer's coarse histogram
+  uint32_t debug;    // experiment switches, 0 in normal use
+  gptr<vu2> slot;    // this wave-chunk's candidate list
+  uint32_t* coarse;  // the workgroup's coarse histogram in LDS (flushed when the workgroup ends)
   uint32_t cap;
   uint32_t count;    // candidates seen so far (wave-uniform)
   uint32_t tau;
@@ -60,7 +62,7 @@ __device__ __forceinline__ void consume(const float (&a)[4], uint32_t nvalid, ui
 #pragma unroll
     for (int j = 0; j < 4; ++j) f[j] = (static_cast<uint32_t>(j) < nvalid) && (key[j] >= c.tau);
     const unsigned long long any = __ballot(f[0] | f[1] | f[2] | f[3]);
-    if (any != 0ull) {
+    if (any != 0ull && !(c.debug & 32u)) {
       const unsigned long long m0 = __ballot(f[0]), m1 = __ballot(f[1]), m2 = __ballot(f[2]),
                                m3 = __ballot(f[3]);
       uint32_t pos = c.count + rank_below(m0) + rank_below(m1) + rank_below(m2) + rank_below(m3);
@@ -68,8 +70,8 @@ __device__ __forceinline__ void consume(const float (&a)[4], uint32_t nvalid, ui
       for (int j = 0; j < 4; ++j) {
         if (f[j]) {
           if (pos < c.cap) {
-            c.slot[pos] = make_uint2(bits[j], idx0 + j);
-            atomicAdd(&c.coarse[coarse_bin(key[j], c.tau, c.shift)], 1u);
+            if (!(c.debug & 2u)) c.slot[pos] = vu2{bits[j], idx0 + j};
+            if (!(c.debug & 16u)) atomicAdd(&c.coarse[coarse_bin(key[j], c.tau, c.shift)], 1u);
           }
           ++pos;
         }
@@ -80,7 +82,7 @@ __device__ __forceinline__ void consume(const float (&a)[4], uint32_t nvalid, ui
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       if (static_cast<uint32_t>(j) < nvalid) {
-        if (key[j] != 0u) atomicAdd(&lds_hist[key[j] >> 19], 1u);
+        if (key[j] != 0u) { if (!(c.debug & 64u)) atomicAdd(&lds_hist[key[j] >> 19], 1u); }
         else ++zeros;
       }
     }
@@ -110,10 +112,10 @@ __device__ __forceinline__ void stream_chunk(const LayerDesc& L, uint32_t begin,
   uint32_t base = begin;
   if (L.vec_ok) {
     const uint32_t nfull = (end - begin) / kGroupElems;
-    const vf4* __restrict__ G4 = reinterpret_cast<const vf4*>(L.grad + begin);
-    vf4* __restrict__ V4 = reinterpret_cast<vf4*>(L.resid + begin);
-    vf4* __restrict__ U4 = kMom ? reinterpret_cast<vf4*>(L.mom + begin) : nullptr;
-    constexpr uint32_t kUnroll = 4;
+    const gptr<const vf4> G4 = as_global(reinterpret_cast<const vf4*>(L.grad + begin));
+    const gptr<vf4> V4 = as_global(reinterpret_cast<vf4*>(L.resid + begin));
+    const gptr<vf4> U4 = as_global(kMom ? reinterpret_cast<vf4*>(L.mom + begin) : nullptr);
+    constexpr uint32_t kUnroll = kMom ? 2 : 4;
     uint32_t g = 0;
     for (; g + kUnroll <= nfull; g += kUnroll) {
       vf4 gv[kUnroll], vv[kUnroll], uv[kUnroll];
@@ -155,6 +157,9 @@ __device__ __forceinline__ void stream_chunk(const LayerDesc& L, uint32_t begin,
     base = begin + nfull * kGroupElems;
   }
   // scalar groups: the ragged tail of an aligned layer, or every group of an unaligned one
+  const gptr<const float> Gs = as_global(L.grad);
+  const gptr<float> Vs = as_global(L.resid);
+  const gptr<float> Us = as_global(L.mom);
   for (; base < end; base += kGroupElems) {
     const uint32_t idx0 = base + lane * 4u;
     const uint32_t nvalid = idx0 < end ? ((end - idx0) < 4u ? (end - idx0) : 4u) : 0u;
@@ -162,9 +167,9 @@ __device__ __forceinline__ void stream_chunk(const LayerDesc& L, uint32_t begin,
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       if (static_cast<uint32_t>(j) < nvalid) {
-        gg[j] = L.grad[idx0 + j];
-        vvv[j] = L.resid[idx0 + j];
-        if constexpr (kMom) uu[j] = L.mom[idx0 + j];
+        gg[j] = Gs[idx0 + j];
+        vvv[j] = Vs[idx0 + j];
+        if constexpr (kMom) uu[j] = Us[idx0 + j];
       }
     }
     float a[4];
@@ -172,8 +177,8 @@ __device__ __forceinline__ void stream_chunk(const LayerDesc& L, uint32_t begin,
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       if (static_cast<uint32_t>(j) < nvalid) {
-        L.resid[idx0 + j] = a[j];
-        if constexpr (kMom) L.mom[idx0 + j] = uu[j];
+        Vs[idx0 + j] = a[j];
+        if constexpr (kMom) Us[idx0 + j] = uu[j];
       }
     }
     consume<kCollect>(a, nvalid, idx0, c, lds_hist, zeros);
@@ -186,15 +191,16 @@ __device__ __forceinline__ void stream_chunk(const LayerDesc& L, uint32_t begin,
 // Read-only walk over one wave-chunk of the updated residual, four elements per lane per step,
 // same element order as the streaming pass.  f(a[4], nvalid, idx0) must be wave-uniform code.
 template <typename F>
-__device__ __forceinline__ void for_each_group(const float* __restrict__ p, bool vec, uint32_t begin,
+__device__ __forceinline__ void for_each_group(const float* generic_p, bool vec, uint32_t begin,
                                                uint32_t end, F&& f) {
+  const gptr<const float> p = as_global(generic_p);
   const uint32_t lane = lane_id();
   for (uint32_t base = begin; base < end; base += kGroupElems) {
     const uint32_t idx0 = base + lane * 4u;
     float a[4] = {0.f, 0.f, 0.f, 0.f};
     uint32_t nvalid;
     if (vec && base + kGroupElems <= end) {
-      const vf4 q = *reinterpret_cast<const vf4*>(p + idx0);
+      const vf4 q = *reinterpret_cast<gptr<const vf4>>(p + idx0);
       a[0] = q.x; a[1] = q.y; a[2] = q.z; a[3] = q.w;
       nvalid = 4u;
     } else {
@@ -244,20 +250,84 @@ struct ResolveShared {
   uint32_t scan[4];
   uint32_t flag;
   uint32_t bin, above, cnt;     // bin holding the k-th key, keys above it, keys in it
-  uint32_t hbin, hcum, hcnt;    // bin where the cumulative count reaches k + margin
+  uint32_t hbin, hcum, hcnt;    // bin where the cumulative count reaches the hint's target rank
   uint32_t bad;
 };
+
+// Copy a (possibly replicated) global histogram into LDS, summing the replicas, and clear the
+// global copy for its next use.  The global bins were filled with device-scope atomics, so they
+// are read with device-scope loads; all loads of a thread are issued before the first use so
+// that their round trips overlap (this runs on the critical path of a layer's last workgroup).
+template <uint32_t kBins, uint32_t kReps>
+__device__ __forceinline__ void stage_hist(uint32_t* g, uint32_t* lds) {
+  constexpr uint32_t kPer = (kBins + kBlockThreads - 1) / kBlockThreads;
+  constexpr uint32_t kBatch = (kPer * kReps > 16u) ? (16u / kReps ? 16u / kReps : 1u) : kPer;   // <= 16 loads in flight
+  for (uint32_t i0 = 0; i0 < kPer; i0 += kBatch) {
+    uint32_t v[kBatch][kReps];
+#pragma unroll
+    for (uint32_t i = 0; i < kBatch; ++i) {
+      const uint32_t b = (i0 + i) * kBlockThreads + threadIdx.x;
+#pragma unroll
+      for (uint32_t rep = 0; rep < kReps; ++rep)
+        v[i][rep] = (i0 + i < kPer && b < kBins) ? ld_agent(&g[rep * kBins + b]) : 0u;
+    }
+#pragma unroll
+    for (uint32_t i = 0; i < kBatch; ++i) {
+      const uint32_t b = (i0 + i) * kBlockThreads + threadIdx.x;
+      if (i0 + i < kPer && b < kBins) {
+        uint32_t sum = 0;
+#pragma unroll
+        for (uint32_t rep = 0; rep < kReps; ++rep) {
+          sum += v[i][rep];
+          g[rep * kBins + b] = 0u;
+        }
+        lds[b] = sum;
+      }
+    }
+  }
+  __syncthreads();
+}
+
+// Walk the LDS histogram from its top bin downwards and find the bins where the cumulative
+// count first reaches want_k and want_h.  Results go to sh.{bin,above,cnt} and
+// sh.{hbin,hcum,hcnt} (bin = ~0 when the total stays below the wanted count); returns the total.
+// Kept light on registers: this code shares a kernel with the streaming loop.
+__device__ uint32_t locate_from_top(const uint32_t* lds, uint32_t bins, uint32_t want_k, uint32_t want_h,
+                                    ResolveShared& sh) {
+  const uint32_t t = threadIdx.x;
+  const uint32_t per = bins >= static_cast<uint32_t>(kBlockThreads) ? bins / kBlockThreads : 1u;
+  const bool active = t * per < bins;
+  uint32_t s = 0;
+  if (active) {
+#pragma unroll 1
+    for (uint32_t i = 0; i < per; ++i) s += lds[bins - 1u - (t * per + i)];
+  }
+  if (t == 0) { sh.bin = 0xFFFFFFFFu; sh.hbin = 0xFFFFFFFFu; sh.above = 0; sh.cnt = 0; sh.hcum = 0; sh.hcnt = 0; }
+  uint32_t total;
+  const uint32_t ex = block_excl_scan(s, sh.scan, total);   // barriers inside: the init is visible
+  if (active && ((ex < want_k && want_k <= ex + s) || (ex < want_h && want_h <= ex + s))) {
+    uint32_t cum = ex;
+#pragma unroll 1
+    for (uint32_t i = 0; i < per; ++i) {
+      const uint32_t b = bins - 1u - (t * per + i);
+      const uint32_t h = lds[b];
+      if (cum < want_k && cum + h >= want_k) { sh.bin = b; sh.above = cum; sh.cnt = h; }
+      if (cum < want_h && cum + h >= want_h) { sh.hbin = b; sh.hcum = cum + h; sh.hcnt = h; }
+      cum += h;
+    }
+  }
+  __syncthreads();
+  return total;
+}
 
 // Multi-pass path, one radix digit: the layer's histogram of this digit is complete.  Find the
 // bin holding the k_rem-th largest key, update prefix / k_rem, derive the threshold hint for
 // the next call on the way, clear the histogram, schedule the next phase.
+// `lds` holds >= kHistBins words and is free for use.
 template <int kLevel>
 __device__ void resolve_digit(const CompressArgs& A, uint32_t l, const LayerDesc& L, LayerState* st,
-                              ResolveShared& sh, uint32_t cur_launch) {
+                              ResolveShared& sh, uint32_t* lds, uint32_t cur_launch) {
   constexpr uint32_t kBins = (kLevel == 3) ? 128u : static_cast<uint32_t>(kHistBins);
-  constexpr uint32_t kPer = (kLevel == 3) ? 1u : kBins / kBlockThreads;
-  uint32_t* ghist = A.hist + static_cast<size_t>(l) * kHistBins;
-  const uint32_t t = threadIdx.x;
   const uint32_t k_rem = (kLevel == 1) ? L.k : st->k_rem;
   const uint32_t above_scope = L.k - k_rem;          // keys above the current scope
   // The k entries selected now leave the residual, so the next call's top-k come from ranks
@@ -265,49 +335,12 @@ __device__ void resolve_digit(const CompressArgs& A, uint32_t l, const LayerDesc
   const uint32_t target = 2u * L.k + L.margin;
   const uint32_t pending = (kLevel == 1) ? 1u : st->hint_pending;
   const uint32_t prefix = (kLevel == 1) ? 0u : st->prefix;
-
-  uint32_t h[kPer];
-  uint32_t s = 0;
-  const bool active = t * kPer < kBins;
-#pragma unroll
-  for (uint32_t i = 0; i < kPer; ++i) {
-    h[i] = active ? ld_agent(&ghist[kBins - 1u - (t * kPer + i)]) : 0u;
-    s += h[i];
-  }
-  if (t == 0) { sh.bin = 0xFFFFFFFFu; sh.hbin = 0xFFFFFFFFu; sh.above = 0; sh.cnt = 0; sh.hcum = 0; sh.hcnt = 0; }
-  uint32_t total;
-  const uint32_t ex = block_excl_scan(s, sh.scan, total);   // barriers inside: sh init is visible
-  if (active && ex < k_rem && k_rem <= ex + s) {
-    uint32_t cum = ex;
-#pragma unroll
-    for (uint32_t i = 0; i < kPer; ++i) {
-      if (cum < k_rem && cum + h[i] >= k_rem) {
-        sh.bin = kBins - 1u - (t * kPer + i); sh.above = cum; sh.cnt = h[i];
-      }
-      cum += h[i];
-    }
-  }
-  const uint32_t tgt_local = target - above_scope;   // > 0
-  if (active && ex < tgt_local && tgt_local <= ex + s) {
-    uint32_t cum = ex;
-#pragma unroll
-    for (uint32_t i = 0; i < kPer; ++i) {
-      if (cum < tgt_local && cum + h[i] >= tgt_local) {
-        sh.hbin = kBins - 1u - (t * kPer + i); sh.hcum = above_scope + cum + h[i]; sh.hcnt = h[i];
-      }
-      cum += h[i];
-    }
-  }
-  // clear the bins for the next digit / the next call
-#pragma unroll
-  for (uint32_t i = 0; i < kPer; ++i)
-    if (active) ghist[kBins - 1u - (t * kPer + i)] = 0u;
-  if (kLevel == 3) {   // digits 1 and 2 used all 4096 bins, digit 3 only 128: nothing else is dirty
-  }
-  __syncthreads();
-  if (t == 0) {
+  stage_hist<kBins, 1u>(A.hist + static_cast<size_t>(l) * kHistBins, lds);
+  (void)locate_from_top(lds, kBins, k_rem, target - above_scope, sh);
+  if (threadIdx.x == 0) {
     if (sh.bin == 0xFFFFFFFFu) { atomicOr(A.errflag, 1u); sh.bin = 0; }
     const uint32_t D = sh.bin;
+    const uint32_t hcum = above_scope + sh.hcum;
     auto edge = [&](uint32_t b) -> uint32_t {
       if (kLevel == 1) return b << 19;
       if (kLevel == 2) return (prefix << 19) | (b << 7);
@@ -316,14 +349,14 @@ __device__ void resolve_digit(const CompressArgs& A, uint32_t l, const LayerDesc
     // ---- hint derivation (speed only)
     uint32_t pend = pending;
     if (pend == 1u) {
-      if (sh.hbin == 0xFFFFFFFFu) {          // the whole layer holds fewer than k + margin keys
+      if (sh.hbin == 0xFFFFFFFFu) {          // the whole layer holds fewer keys than the target rank
         st->tau_next = 0u; pend = 2u;
-      } else if (sh.hcum <= L.cmax) {
+      } else if (hcum <= L.cmax) {
         st->tau_next = edge(sh.hbin); pend = 2u;
       } else if (sh.hbin == D) {
         pend = (kLevel < 3) ? 1u : 3u;      // refine inside the same bin, or give up (heavy ties)
       } else {
-        st->tau_next = edge(sh.hbin + 1u); pend = 2u;   // one bin up: count in [k, k + margin)
+        st->tau_next = edge(sh.hbin + 1u); pend = 2u;   // one bin up: fewer keys than aimed at, still >= k
       }
     }
     const uint32_t new_rem = k_rem - sh.above;
@@ -359,20 +392,20 @@ __device__ void resolve_digit(const CompressArgs& A, uint32_t l, const LayerDesc
 
 // Hinted path, end of the streaming pass: validate the candidate lists, locate the coarse bin
 // holding the k-th key, clear the coarse histogram, schedule PH_SEL or fall back.
+// `lds` holds >= kCoarseBins words and is free for use.
 __device__ void resolve_collect(const CompressArgs& A, uint32_t l, const LayerDesc& L, LayerState* st,
-                                ResolveShared& sh) {
+                                ResolveShared& sh, uint32_t* lds) {
   const uint32_t t = threadIdx.x;
-  uint32_t* coarse = A.coarse + static_cast<size_t>(l) * kCoarseRep * kCoarseBins;
   uint32_t total = 0, bad = 0;
-  for (uint32_t c0 = 0; c0 < L.wc_count; c0 += 4u * kBlockThreads) {
-    uint32_t v[4];
+  for (uint32_t c0 = 0; c0 < L.wc_count; c0 += 8u * kBlockThreads) {
+    uint32_t v[8];
 #pragma unroll
-    for (uint32_t j = 0; j < 4u; ++j) {
+    for (uint32_t j = 0; j < 8u; ++j) {
       const uint32_t c = c0 + j * kBlockThreads + t;
       v[j] = c < L.wc_count ? ld_agent(&A.cand_cnt[L.wc_first + c]) : 0u;
     }
 #pragma unroll
-    for (uint32_t j = 0; j < 4u; ++j) {
+    for (uint32_t j = 0; j < 8u; ++j) {
       bad |= (v[j] > A.cap) ? 1u : 0u;
       total += v[j];
     }
@@ -380,48 +413,12 @@ __device__ void resolve_collect(const CompressArgs& A, uint32_t l, const LayerDe
   uint32_t cand_total;
   (void)block_excl_scan(total, sh.scan, cand_total);
   bad = __syncthreads_or(static_cast<int>(bad)) ? 1u : 0u;
-
-  constexpr uint32_t kPer = kCoarseBins / kBlockThreads;   // 8
-  uint32_t h[kPer];
-  uint32_t s = 0;
-#pragma unroll
-  for (uint32_t i = 0; i < kPer; ++i) {
-    uint32_t part[kCoarseRep];
-#pragma unroll
-    for (uint32_t rep = 0; rep < kCoarseRep; ++rep)
-      part[rep] = ld_agent(&coarse[rep * kCoarseBins + kCoarseBins - 1u - (t * kPer + i)]);
-    h[i] = 0;
-#pragma unroll
-    for (uint32_t rep = 0; rep < kCoarseRep; ++rep) h[i] += part[rep];
-    s += h[i];
-  }
-  if (t == 0) { sh.bin = 0xFFFFFFFFu; sh.hbin = 0xFFFFFFFFu; sh.above = 0; sh.cnt = 0; sh.hcum = 0; }
-  uint32_t hist_total;
-  const uint32_t ex = block_excl_scan(s, sh.scan, hist_total);
+  stage_hist<kCoarseBins, kCoarseRep>(A.coarse + static_cast<size_t>(l) * kCoarseRep * kCoarseBins, lds);
   const uint32_t k = L.k, target = 2u * L.k + L.margin;   // see resolve_digit
-  if (ex < k && k <= ex + s) {
-    uint32_t cum = ex;
-#pragma unroll
-    for (uint32_t i = 0; i < kPer; ++i) {
-      if (cum < k && cum + h[i] >= k) { sh.bin = kCoarseBins - 1u - (t * kPer + i); sh.above = cum; sh.cnt = h[i]; }
-      cum += h[i];
-    }
-  }
-  if (ex < target && target <= ex + s) {
-    uint32_t cum = ex;
-#pragma unroll
-    for (uint32_t i = 0; i < kPer; ++i) {
-      if (cum < target && cum + h[i] >= target) { sh.hbin = kCoarseBins - 1u - (t * kPer + i); sh.hcum = cum + h[i]; }
-      cum += h[i];
-    }
-  }
-#pragma unroll
-  for (uint32_t i = 0; i < kPer; ++i)
-#pragma unroll
-    for (uint32_t rep = 0; rep < kCoarseRep; ++rep)
-      coarse[rep * kCoarseBins + kCoarseBins - 1u - (t * kPer + i)] = 0u;
-  __syncthreads();
+  const uint32_t hist_total = locate_from_top(lds, kCoarseBins, k, target, sh);
   if (t == 0) {
+    st->stat_candidates = cand_total;
+    st->stat_members = sh.cnt;
     const bool ok = !bad && cand_total >= k && hist_total == cand_total && sh.bin != 0xFFFFFFFFu &&
                     sh.cnt <= static_cast<uint32_t>(kMemberMax);
     if (ok) {
@@ -527,19 +524,20 @@ __global__ void __launch_bounds__(kBlockThreads) accumulate_kernel(CompressArgs 
   const LayerDesc L = A.layers[l];
   LayerState* st = A.state + l;
   const bool collect = A.use_hints && L.hintable && (st->hint_valid != 0u);
-  if (!collect) {
-    for (uint32_t b = threadIdx.x; b < kHistBins; b += kBlockThreads) lds_hist[b] = 0u;
-    __syncthreads();
-  }
+  // the same LDS array serves as 4096-bin digit histogram (hint-free) or 1024-bin coarse one
+  const uint32_t lds_bins = collect ? static_cast<uint32_t>(kCoarseBins) : static_cast<uint32_t>(kHistBins);
+  for (uint32_t b = threadIdx.x; b < lds_bins; b += kBlockThreads) lds_hist[b] = 0u;
+  __syncthreads();
   const uint32_t wave = threadIdx.x >> 6;
   const uint32_t wc_local = (wg - L.wg_first) * kWavesPerBlock + wave;
   if (wc_local < L.wc_count) {
     const uint32_t begin = wc_local * A.chunk;
     const uint32_t end = (L.n - begin) < A.chunk ? L.n : begin + A.chunk;
     Collector c;
-    c.slot = A.slots + static_cast<size_t>(L.wc_first + wc_local) * A.cap;
-    c.coarse = A.coarse + (static_cast<size_t>(l) * kCoarseRep + (wg & (kCoarseRep - 1))) * kCoarseBins;
+    c.slot = as_global(reinterpret_cast<vu2*>(A.slots + static_cast<size_t>(L.wc_first + wc_local) * A.cap));
+    c.coarse = lds_hist;
     c.cap = A.cap;
+    c.debug = A.debug;
     c.count = 0;
     c.tau = st->tau;
     c.shift = st->shift;
@@ -553,16 +551,23 @@ __global__ void __launch_bounds__(kBlockThreads) accumulate_kernel(CompressArgs 
       else stream_chunk<false, false>(L, begin, end, A.m, c, lds_hist);
     }
   }
-  if (!collect) {
-    __syncthreads();
+  if (A.debug & 8u) return;
+  __syncthreads();
+  if (collect) {
+    // Global atomics only here, in one burst per workgroup: inside the streaming loop each one
+    // would stall the wave's later loads behind the atomic's round trip.
+    flush_hist(lds_hist, A.coarse + (static_cast<size_t>(l) * kCoarseRep + (wg & (kCoarseRep - 1))) * kCoarseBins,
+               kCoarseBins);
+  } else {
     flush_hist(lds_hist, A.hist + static_cast<size_t>(l) * kHistBins, kHistBins);
   }
   if (last_block_of_layer(&st->done, L.wg_count, &sh.flag)) {
+    if (A.debug & 4u) return;
     if (collect) {
-      resolve_collect(A, l, L, st, sh);
+      resolve_collect(A, l, L, st, sh, lds_hist);
     } else {
-      if (threadIdx.x == 0) st->path = 1u;
-      resolve_digit<1>(A, l, L, st, sh, 1u);
+      if (threadIdx.x == 0) { st->path = 1u; st->stat_candidates = 0u; st->stat_members = 0u; }
+      resolve_digit<1>(A, l, L, st, sh, lds_hist, 1u);
     }
   }
 }
@@ -602,7 +607,7 @@ __device__ void phase_hist(const CompressArgs& A, uint32_t l, const LayerDesc& L
   }
   __syncthreads();
   flush_hist(lds_hist, A.hist + static_cast<size_t>(l) * kHistBins, kBins);
-  if (last_block_of_layer(&st->done, L.wg_count, &sh.flag)) resolve_digit<kLevel>(A, l, L, st, sh, A.launch);
+  if (last_block_of_layer(&st->done, L.wg_count, &sh.flag)) resolve_digit<kLevel>(A, l, L, st, sh, lds_hist, A.launch);
 }
 
 __device__ void phase_count(const CompressArgs& A, uint32_t l, const LayerDesc& L, LayerState* st,
@@ -649,6 +654,10 @@ __device__ void phase_out_v(const CompressArgs& A, const LayerDesc& L, LayerStat
   uint32_t out_pos = A.wc_a[L.wc_first + wc_local];
   uint32_t eq_seen = A.wc_b[L.wc_first + wc_local];
   const bool clear_mom = (L.mom != nullptr) && A.mask_momentum;
+  const gptr<int32_t> out_idx = as_global(L.out_idx);
+  const gptr<float> out_val = as_global(L.out_val);
+  const gptr<float> resid = as_global(L.resid);
+  const gptr<float> mom = as_global(L.mom);
   for_each_group(L.resid, L.vec_ok != 0u, begin, end,
                  [&](const float (&a)[4], uint32_t nvalid, uint32_t idx0) {
                    bool gt[4], eq[4];
@@ -679,17 +688,17 @@ __device__ void phase_out_v(const CompressArgs& A, const LayerDesc& L, LayerStat
                    for (int j = 0; j < 4; ++j) {
                      if (sel[j]) {
                        if (pos < L.k) {   // always true when the counts are consistent
-                         L.out_idx[pos] = static_cast<int32_t>(idx0 + j);
-                         L.out_val[pos] = a[j];
-                         L.resid[idx0 + j] = 0.0f;
-                         if (clear_mom) L.mom[idx0 + j] = 0.0f;
+                         out_idx[pos] = static_cast<int32_t>(idx0 + j);
+                         out_val[pos] = a[j];
+                         resid[idx0 + j] = 0.0f;
+                         if (clear_mom) mom[idx0 + j] = 0.0f;
                        }
                        ++pos;
                      }
                    }
                    out_pos += popc64(s0) + popc64(s1) + popc64(s2) + popc64(s3);
                  });
-  if (wc_local == 0 && lane_id() == 0) *L.out_count = static_cast<int32_t>(L.k);
+  if (wc_local == 0 && lane_id() == 0) *as_global(L.out_count) = static_cast<int32_t>(L.k);
 }
 
 // Hinted path: every wave looks at its own candidate list; candidates of the coarse bin that
@@ -772,6 +781,10 @@ __device__ void phase_out_c(const CompressArgs& A, const LayerDesc& L, LayerStat
   const uint32_t lane = lane_id();
   uint32_t out_pos = A.wc_a[wc];
   const bool clear_mom = (L.mom != nullptr) && A.mask_momentum;
+  const gptr<int32_t> out_idx = as_global(L.out_idx);
+  const gptr<float> out_val = as_global(L.out_val);
+  const gptr<float> resid = as_global(L.resid);
+  const gptr<float> mom = as_global(L.mom);
   for (uint32_t p0 = 0; p0 < cnt; p0 += kWaveSize) {
     const uint32_t p = p0 + lane;
     uint2 e = make_uint2(0u, 0u);
@@ -783,14 +796,14 @@ __device__ void phase_out_c(const CompressArgs& A, const LayerDesc& L, LayerStat
     const unsigned long long sm = __ballot(sel);
     const uint32_t pos = out_pos + rank_below(sm);
     if (sel && pos < L.k && e.y < L.n) {   // the bounds always hold when the counts are consistent
-      L.out_idx[pos] = static_cast<int32_t>(e.y);
-      L.out_val[pos] = __uint_as_float(e.x);
-      L.resid[e.y] = 0.0f;
-      if (clear_mom) L.mom[e.y] = 0.0f;
+      out_idx[pos] = static_cast<int32_t>(e.y);
+      out_val[pos] = __uint_as_float(e.x);
+      resid[e.y] = 0.0f;
+      if (clear_mom) mom[e.y] = 0.0f;
     }
     out_pos += popc64(sm);
   }
-  if (wc_local == 0 && lane == 0) *L.out_count = static_cast<int32_t>(L.k);
+  if (wc_local == 0 && lane == 0) *as_global(L.out_count) = static_cast<int32_t>(L.k);
 }
 
 }  // namespace

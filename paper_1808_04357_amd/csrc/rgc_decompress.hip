@@ -28,17 +28,18 @@ __global__ void __launch_bounds__(kBlockThreads) decompress_table_kernel(Decompr
   const uint32_t layer = bd.msg % A.num_layers;
   const uint32_t ntiles = A.layer_tiles[layer];
   uint32_t* row = A.tab + md.tab_base;   // ntiles + 1 words: first entry of tile t; row[ntiles] = count
+  const gptr<const int32_t> midx = as_global(md.idx);
   if (md.count == 0u) {
     for (uint32_t t = threadIdx.x; t <= ntiles; t += kBlockThreads) row[t] = 0u;
     return;
   }
   const uint32_t stop = (md.count - bd.first) < kTableBlockEntries ? md.count : bd.first + kTableBlockEntries;
   for (uint32_t j = bd.first + threadIdx.x; j < stop; j += kBlockThreads) {
-    uint32_t cur = static_cast<uint32_t>(md.idx[j]) >> kTileShift;
+    uint32_t cur = static_cast<uint32_t>(midx[j]) >> kTileShift;
     if (cur >= ntiles) cur = ntiles - 1u;                 // out-of-range index: stay inside the row
     uint32_t first = 0u;
     if (j != 0u) {
-      uint32_t prev = static_cast<uint32_t>(md.idx[j - 1u]) >> kTileShift;
+      uint32_t prev = static_cast<uint32_t>(midx[j - 1u]) >> kTileShift;
       if (prev >= ntiles) prev = ntiles - 1u;
       first = prev + 1u;
     }
@@ -101,8 +102,8 @@ __global__ void __launch_bounds__(kBlockThreads) decompress_tiles_kernel(Decompr
       if (tid == 0) { w_start[0] = s; w_pref[0] = c; w_idx[0] = ip; w_val[0] = vp; }
       __syncthreads();
       const uint32_t s0 = w_start[0], c0 = w_pref[0];
-      const int32_t* ip0 = w_idx[0];
-      const float* vp0 = w_val[0];
+      const gptr<const int32_t> ip0 = as_global(w_idx[0]);
+      const gptr<const float> vp0 = as_global(w_val[0]);
       for (uint32_t j = tid; j < c0; j += kBlockThreads) {
         const uint32_t p = static_cast<uint32_t>(ip0[s0 + j]) - tile.first;
         if (p < tile.len) acc[p] = __fadd_rn(acc[p], vp0[s0 + j]);
@@ -128,10 +129,10 @@ __global__ void __launch_bounds__(kBlockThreads) decompress_tiles_kernel(Decompr
         if (w_pref[mid] <= e) lo = mid; else hi = mid;
       }
       const uint32_t j = w_start[lo] + (e - w_pref[lo]);
-      const uint32_t p = static_cast<uint32_t>(w_idx[lo][j]) - tile.first;
+      const uint32_t p = static_cast<uint32_t>(as_global(w_idx[lo])[j]) - tile.first;
       if (p < tile.len) {
         e_pw[e] = p | (lo << 16);
-        e_val[e] = w_val[lo][j];
+        e_val[e] = as_global(w_val[lo])[j];
         atomicAdd(&cnt32[p >> 2], 1u << ((p & 3u) * 8u));
       } else {
         e_pw[e] = 0xFFFFFFFFu;
@@ -258,12 +259,12 @@ __global__ void __launch_bounds__(kBlockThreads) decompress_tiles_kernel(Decompr
   __syncthreads();
 
   // ---- write the tile once
-  float* d = tile.dense;
+  const gptr<float> d = as_global(tile.dense);
   const float scale = A.scale;
-  const bool vec = ((reinterpret_cast<uintptr_t>(d) & 15u) == 0u) && ((tile.len & 3u) == 0u);
+  const bool vec = ((reinterpret_cast<uintptr_t>(tile.dense) & 15u) == 0u) && ((tile.len & 3u) == 0u);
   if (vec) {
     typedef float vf4 __attribute__((ext_vector_type(4)));
-    vf4* d4 = reinterpret_cast<vf4*>(d);
+    const gptr<vf4> d4 = as_global(reinterpret_cast<vf4*>(tile.dense));
     for (uint32_t i = tid; i < tile.len / 4u; i += kBlockThreads) {
       vf4 o;
       o.x = __fmul_rn(acc[4 * i + 0], scale);

@@ -6,6 +6,18 @@
 
 namespace rgc {
 
+// Tensor pointers reach the kernels through descriptor tables in memory, so the compiler sees
+// generic ("flat") pointers and would emit flat_load/flat_store, which also tick the LDS
+// counter and make every LDS wait a wait for all outstanding global traffic.  Everything the
+// library touches through such pointers is global memory: say so.
+template <typename T>
+using gptr = __attribute__((address_space(1))) T*;
+
+template <typename T>
+__device__ __forceinline__ gptr<T> as_global(T* p) {
+  return (gptr<T>)p;
+}
+
 __device__ __forceinline__ uint32_t lane_id() {
   return __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
 }

@@ -72,6 +72,8 @@ struct LayerState {
   uint32_t hint_pending; // multi-pass: 0 none found yet / 1 refine in the next digit / 2 final
   uint32_t T_prev;       // threshold key of the previous call (drift estimate), if has_prev
   uint32_t has_prev;
+  uint32_t stat_candidates;  // diagnostics of the last call
+  uint32_t stat_members;
   uint32_t pad;
 };
 
@@ -94,6 +96,7 @@ struct CompressArgs {
   uint32_t mask_momentum;
   float m;
   uint32_t launch;       // launch number of the phase kernel (2..6)
+  uint32_t debug;        // experiment switches (RGC_DEBUG), 0 in normal use
 };
 
 // ---------------------------------------------------------------- decompress
