@@ -21,7 +21,7 @@ RGC_OVERWRITE = 0x10
 RGC_ADD_TO_DST = 0x20
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "librgc.so")
+_LIB_PATH = os.environ.get("RGC_LIB") or os.path.join(_HERE, "librgc.so")   # RGC_LIB: tuning builds only
 
 EXPORTS = ["rgc_create", "rgc_destroy", "rgc_k_for_density", "rgc_compress_layers",
            "rgc_decompress_accumulate", "rgc_reset_hints", "rgc_poison_hints", "rgc_selftest",

@@ -118,7 +118,7 @@ struct DecompressPlan {
   std::vector<float*> key_dense;
   std::vector<int64_t> key_n;
   int32_t workers = 0, layers = 0;
-  DevBuf<unsigned char> d_tables;   // MsgDesc[], TileDesc[], BlockDesc[], layer_tiles[]
+  DevBuf<unsigned char> d_tables;   // MsgDesc[], DecompressLayer[], BlockDesc[]
   DevBuf<uint32_t> d_tab;
   PinnedBuf staging;
   hipEvent_t uploaded = nullptr;
@@ -542,10 +542,9 @@ int rgc_decompress_accumulate(rgc_ctx* ctx, const rgc_msg* msgs, int32_t num_wor
     const uint64_t tab_words = stride * static_cast<uint64_t>(std::max(num_workers, 1));
     if (tiles > 0x7FFFFFFFull || blocks > 0x7FFFFFFFull || tab_words > 0xFFFFFFFFull) return RGC_ENOMEM;
     const size_t off_msgs = 0;
-    const size_t off_tiles = off_msgs + sizeof(MsgDesc) * std::max<size_t>(NM, 1);
-    const size_t off_blocks = off_tiles + sizeof(TileDesc) * tiles;
-    const size_t off_lt = off_blocks + sizeof(BlockDesc) * std::max<uint64_t>(blocks, 1);
-    const size_t bytes = off_lt + sizeof(uint32_t) * num_layers;
+    const size_t off_layers = off_msgs + sizeof(MsgDesc) * std::max<size_t>(NM, 1);
+    const size_t off_blocks = off_layers + sizeof(DecompressLayer) * num_layers;
+    const size_t bytes = off_blocks + sizeof(BlockDesc) * std::max<uint64_t>(blocks, 1);
     RGC_HIP(P.staging.ensure(bytes));
     if (P.d_tables.n < bytes) {
       hipError_t e = P.d_tables.alloc(bytes);
@@ -559,46 +558,50 @@ int rgc_decompress_accumulate(rgc_ctx* ctx, const rgc_msg* msgs, int32_t num_wor
     }
     char* base = static_cast<char*>(P.staging.p);
     MsgDesc* hm = reinterpret_cast<MsgDesc*>(base + off_msgs);
-    TileDesc* ht = reinterpret_cast<TileDesc*>(base + off_tiles);
+    DecompressLayer* hl = reinterpret_cast<DecompressLayer*>(base + off_layers);
     BlockDesc* hb = reinterpret_cast<BlockDesc*>(base + off_blocks);
-    uint32_t* hl = reinterpret_cast<uint32_t*>(base + off_lt);
     uint64_t nb = 0;
-    for (size_t i = 0; i < NM; ++i) {
-      const uint32_t w = static_cast<uint32_t>(i / num_layers), l = static_cast<uint32_t>(i % num_layers);
-      hm[i].idx = msgs[i].idx;
-      hm[i].val = msgs[i].val;
-      hm[i].count = static_cast<uint32_t>(msgs[i].count);
-      hm[i].tab_base = static_cast<uint32_t>(static_cast<uint64_t>(w) * stride + layer_col[l]);
-      const uint32_t cnt = hm[i].count;
-      uint32_t first = 0;
-      do {
-        hb[nb].msg = static_cast<uint32_t>(i);
-        hb[nb].first = first;
-        ++nb;
-        first += 1024;
-      } while (first < cnt);
-    }
-    uint64_t nt = 0;
-    for (int32_t l = 0; l < num_layers; ++l) {
-      hl[l] = layer_tiles[l];
-      for (uint32_t t = 0; t < layer_tiles[l]; ++t) {
-        TileDesc& td = ht[nt++];
-        td.first = t << kTileShift;
-        td.dense = dense[l] + td.first;
-        td.len = static_cast<uint32_t>(std::min<int64_t>(kTile, n[l] - static_cast<int64_t>(td.first)));
-        td.layer = static_cast<uint32_t>(l);
-        td.tab_col = t;
+    for (uint32_t l = 0; l < static_cast<uint32_t>(num_layers); ++l) {
+      for (uint32_t w = 0; w < static_cast<uint32_t>(num_workers); ++w) {
+        const rgc_msg& in = msgs[static_cast<size_t>(w) * num_layers + l];
+        const size_t i = static_cast<size_t>(l) * num_workers + w;      // device order: [layer][worker]
+        hm[i].idx = in.idx;
+        hm[i].val = in.val;
+        hm[i].count = static_cast<uint32_t>(in.count);
+        hm[i].tab_base = layer_col[l];
+        const uint32_t cnt = hm[i].count;
+        uint32_t first = 0;
+        do {
+          hb[nb].msg = static_cast<uint32_t>(i);
+          hb[nb].first = first;
+          ++nb;
+          first += 1024;
+        } while (first < cnt);
       }
+    }
+    uint32_t tile_base = 0;
+    for (int32_t l = 0; l < num_layers; ++l) {
+      hl[l].dense = dense[l];
+      hl[l].n = static_cast<uint32_t>(n[l]);
+      hl[l].tiles = layer_tiles[l];
+      hl[l].tile_base = tile_base;
+      hl[l].row_base = layer_col[l];
+      hl[l].pad[0] = hl[l].pad[1] = 0;
+      tile_base += layer_tiles[l];
     }
     RGC_HIP(hipMemcpyAsync(P.d_tables.p, P.staging.p, bytes, hipMemcpyHostToDevice, stream));
     RGC_HIP(hipEventRecord(P.uploaded, stream));
     DecompressArgs& A = P.args;
     A.msgs = reinterpret_cast<const MsgDesc*>(P.d_tables.p + off_msgs);
-    A.tiles = reinterpret_cast<const TileDesc*>(P.d_tables.p + off_tiles);
+    A.layers = reinterpret_cast<const DecompressLayer*>(P.d_tables.p + off_layers);
     A.blocks = reinterpret_cast<const BlockDesc*>(P.d_tables.p + off_blocks);
-    A.layer_tiles = reinterpret_cast<const uint32_t*>(P.d_tables.p + off_lt);
     A.tab = P.d_tab.p;
     A.tab_stride = static_cast<uint32_t>(stride);
+    {
+      hipDeviceProp_t prop;
+      RGC_HIP(hipGetDeviceProperties(&prop, ctx->device));
+      A.max_grid = static_cast<uint32_t>(std::max(8, (prop.multiProcessorCount * 4 / 8) * 8));
+    }
     A.num_workers = static_cast<uint32_t>(num_workers);
     A.num_layers = static_cast<uint32_t>(num_layers);
     A.num_tiles = static_cast<uint32_t>(tiles);

@@ -58,6 +58,12 @@ __device__ __forceinline__ void consume(const float (&a)[4], uint32_t nvalid, ui
     key[j] = bits[j] & kKeyMask;
   }
   if constexpr (kCollect) {
+    if (c.debug & 512u) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) atomicAdd(&lds_hist[1024u + (key[j] >> 19) % 3072u], 1u);
+    }
+    if (c.debug & 128u) __builtin_amdgcn_s_sleep(1);
+    if (c.debug & 256u) __builtin_amdgcn_s_sleep(4);
     bool f[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) f[j] = (static_cast<uint32_t>(j) < nvalid) && (key[j] >= c.tau);
@@ -115,7 +121,13 @@ __device__ __forceinline__ void stream_chunk(const LayerDesc& L, uint32_t begin,
     const gptr<const vf4> G4 = as_global(reinterpret_cast<const vf4*>(L.grad + begin));
     const gptr<vf4> V4 = as_global(reinterpret_cast<vf4*>(L.resid + begin));
     const gptr<vf4> U4 = as_global(kMom ? reinterpret_cast<vf4*>(L.mom + begin) : nullptr);
-    constexpr uint32_t kUnroll = kMom ? 2 : 4;
+#ifndef RGC_UNROLL_MOM
+#define RGC_UNROLL_MOM 2
+#endif
+#ifndef RGC_UNROLL_PLAIN
+#define RGC_UNROLL_PLAIN 4
+#endif
+    constexpr uint32_t kUnroll = kMom ? RGC_UNROLL_MOM : RGC_UNROLL_PLAIN;
     uint32_t g = 0;
     for (; g + kUnroll <= nfull; g += kUnroll) {
       vf4 gv[kUnroll], vv[kUnroll], uv[kUnroll];

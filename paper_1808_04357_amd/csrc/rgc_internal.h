@@ -111,15 +111,16 @@ struct MsgDesc {                                   // one (worker, layer) messag
   const int32_t* idx;
   const float* val;
   uint32_t count;
-  uint32_t tab_base;    // offset of this message's row segment: w * tab_stride + layer tab base
+  uint32_t tab_base;    // first table row of the message's layer
 };
 
-struct TileDesc {
-  float* dense;         // start of the tile
-  uint32_t len;         // positions in this tile (<= kTile)
-  uint32_t layer;
-  uint32_t tab_col;     // column of this tile inside a message's table row segment
-  uint32_t first;       // layer-local index of the tile's first position
+struct DecompressLayer {   // one dense buffer
+  float* dense;
+  uint32_t n;
+  uint32_t tiles;         // ceil(n / kTile)
+  uint32_t tile_base;     // global id of its first tile
+  uint32_t row_base;      // first table row (the layer owns tiles + 1 rows)
+  uint32_t pad[2];
 };
 
 struct BlockDesc {      // one block of the table-building kernel
@@ -128,12 +129,12 @@ struct BlockDesc {      // one block of the table-building kernel
 };
 
 struct DecompressArgs {
-  const MsgDesc* msgs;        // [workers][layers]
-  const TileDesc* tiles;
+  const MsgDesc* msgs;        // [layers][workers]
+  const DecompressLayer* layers;
   const BlockDesc* blocks;
-  const uint32_t* layer_tiles;  // [layers] number of tiles of the layer
-  uint32_t* tab;              // [workers][tab_stride] first entry of each tile, + sentinel per layer
+  uint32_t* tab;              // [tab_stride rows][workers]: first entry of each tile; one closing row per layer
   uint32_t tab_stride;
+  uint32_t max_grid;          // persistent grid of the tile kernel (multiple of 8)
   uint32_t num_workers;
   uint32_t num_layers;
   uint32_t num_tiles;
