@@ -68,8 +68,21 @@ class DecompressWorkload:
         self.workers = workers
         idx, val = synth.decompress_messages(sizes, num_workers=workers)
         self.entries = sum(int(a.size) for row in idx for a in row)
-        self.d_idx = [upload(torch, row, dev) for row in idx]
-        self.d_val = [upload(torch, row, dev) for row in val]
+        # the messages sit back to back, worker after worker, as an Allgather leaves them
+        self.recv_idx = torch.empty(self.entries, dtype=torch.int32, device=dev)
+        self.recv_val = torch.empty(self.entries, dtype=torch.float32, device=dev)
+        self.d_idx, self.d_val, o = [], [], 0
+        for w in range(workers):
+            ri, rv = [], []
+            for l in range(len(sizes)):
+                c = int(idx[w][l].size)
+                ri.append(self.recv_idx[o:o + c])
+                rv.append(self.recv_val[o:o + c])
+                ri[-1].copy_(torch.from_numpy(idx[w][l]))
+                rv[-1].copy_(torch.from_numpy(val[w][l]))
+                o += c
+            self.d_idx.append(ri)
+            self.d_val.append(rv)
         self.dense = [torch.empty(n, dtype=torch.float32, device=dev) for n in sizes]
         self.msgs = rgc.MessageList(self.d_idx, self.d_val, self.dense)
         self.scale = 1.0 / workers

@@ -34,22 +34,34 @@ int fail_hip(hipError_t e, const char* what) {
     if (e_ != hipSuccess) return fail_hip(e_, #call);   \
   } while (0)
 
-constexpr uint32_t kChunkDefault = 8192;   // elements per wave-chunk
+constexpr uint32_t kChunkSmallest = 4096;  // elements per wave-chunk for small layer sets
 constexpr uint32_t kChunkMin = 1024;
 constexpr uint32_t kCapDiv = 32;           // candidate slots per wave-chunk = chunk / 32
 
-// Elements per wave-chunk; RGC_CHUNK (a multiple of 256, >= 1024) overrides the default for tuning.
-uint32_t chunk_elems() {
+// RGC_CHUNK (a multiple of 256, >= 1024) fixes the wave-chunk size for tuning; 0 = automatic.
+uint32_t chunk_override() {
   static const uint32_t v = [] {
     const char* e = std::getenv("RGC_CHUNK");
     if (e) {
       const long x = std::atol(e);
       if (x >= static_cast<long>(kChunkMin) && x <= (1l << 20) && (x % 256) == 0) return static_cast<uint32_t>(x);
     }
-    return kChunkDefault;
+    return 0u;
   }();
   return v;
 }
+
+// Elements per wave-chunk for a call over `total` elements.  Larger chunks mean fewer per-chunk
+// counters for the per-layer serial steps, smaller ones more workgroups to fill 256 CUs.
+uint32_t chunk_for(int64_t total) {
+  if (chunk_override()) return chunk_override();
+  if (total >= (int64_t(48) << 20)) return 16384;
+  if (total >= (int64_t(8) << 20)) return 8192;
+  return kChunkSmallest;
+}
+
+// Smallest chunk any call may use: the scratch is sized for it.
+uint32_t chunk_smallest() { return chunk_override() ? std::min(chunk_override(), kChunkSmallest) : kChunkSmallest; }
 constexpr int kPlanCache = 8;
 constexpr int kLaunches = 6;               // streaming pass + at most five phase launches
 
@@ -104,6 +116,7 @@ struct PinnedBuf {
 // One cached translation of a layer list into device tables.
 struct CompressPlan {
   std::vector<rgc_layer> key;       // the caller's list this plan was built from
+  uint32_t chunk = 0;               // elements per wave-chunk of this plan
   DevBuf<LayerDesc> d_layers;
   DevBuf<uint32_t> d_wg2layer;
   PinnedBuf staging;
@@ -163,7 +176,10 @@ int build_compress_plan(rgc_ctx* ctx, CompressPlan& P, const rgc_layer* layers, 
   std::stable_sort(order.begin(), order.end(),
                    [&](int32_t a, int32_t b) { return layers[a].n > layers[b].n; });
   std::vector<LayerDesc> desc(L);
-  const uint32_t kChunk = chunk_elems(), kCap = kChunk / kCapDiv;
+  int64_t total_elems = 0;
+  for (int32_t l = 0; l < L; ++l) total_elems += layers[l].n;
+  const uint32_t kChunk = chunk_for(total_elems), kCap = kChunk / kCapDiv;
+  P.chunk = kChunk;
   uint32_t wc = 0, wg = 0;
   for (int32_t o = 0; o < L; ++o) {
     const int32_t l = order[o];
@@ -280,7 +296,7 @@ int rgc_create(rgc_ctx** out, int device_id, int64_t max_total_elems, int32_t ma
   c->device = device_id;
   c->max_total = max_total_elems;
   c->max_layers = max_layers;
-  const uint32_t kChunk = chunk_elems(), kCap = kChunk / kCapDiv;
+  const uint32_t kChunk = chunk_smallest(), kCap = kChunk / kCapDiv;
   const uint64_t wc_max = static_cast<uint64_t>((max_total_elems + kChunk - 1) / kChunk) + static_cast<uint64_t>(max_layers);
   if (wc_max > 0x7FFFFFFFull) return RGC_ENOMEM;
   c->wc_max = static_cast<uint32_t>(wc_max);
@@ -294,7 +310,13 @@ int rgc_create(rgc_ctx** out, int device_id, int64_t max_total_elems, int32_t ma
   chk(c->d_cand_cnt.alloc(wc_max));
   chk(c->d_wc_a.alloc(wc_max));
   chk(c->d_wc_b.alloc(wc_max));
-  chk(c->d_slots.alloc(wc_max * kCap));
+  {
+    // every wave-chunk owns chunk / kCapDiv slots whatever the chunk size: total / kCapDiv slots
+    // plus one (partly used) chunk per layer at the largest chunk size a plan may pick
+    const uint64_t largest = std::max<uint64_t>(16384, chunk_override());
+    (void)kCap;
+    chk(c->d_slots.alloc(static_cast<uint64_t>(max_total_elems) / kCapDiv + (static_cast<uint64_t>(max_layers) + 1) * (largest / kCapDiv)));
+  }
   chk(c->d_err.alloc(1));
   if (e == hipSuccess) chk(hipMemset(c->d_state.p, 0, sizeof(LayerState) * L));
   if (e == hipSuccess) chk(hipMemset(c->d_hist.p, 0, sizeof(uint32_t) * L * kHistBins));
@@ -411,7 +433,7 @@ int rgc_compress_layers(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layer
   A.wc_a = ctx->d_wc_a.p;
   A.wc_b = ctx->d_wc_b.p;
   A.errflag = ctx->d_err.p;
-  A.chunk = chunk_elems();
+  A.chunk = plan->chunk;
   A.cap = A.chunk / kCapDiv;
   A.use_hints = (sig_same && !no_hints) ? 1u : 0u;
   A.update_hints = no_hints ? 0u : 1u;
@@ -616,6 +638,10 @@ int rgc_decompress_accumulate(rgc_ctx* ctx, const rgc_msg* msgs, int32_t num_wor
   DecompressArgs A = P.args;
   A.add_to_dst = (flags == RGC_ADD_TO_DST) ? 1u : 0u;
   A.scale = scale;
+  {
+    const char* e = std::getenv("RGC_DEBUG");
+    A.debug = e ? static_cast<uint32_t>(std::atol(e)) : 0u;
+  }
   if (ctx->profiling) RGC_HIP(take_event(ctx, stream, ctx->ev_decompress));
   RGC_HIP(launch_decompress_table(A, stream));
   if (ctx->profiling) RGC_HIP(take_event(ctx, stream, ctx->ev_decompress));

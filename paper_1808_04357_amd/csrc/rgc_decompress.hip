@@ -30,6 +30,9 @@ constexpr uint32_t kTableBlockEntries = 1024;
 constexpr uint32_t kPerThread = kEntryCap / kBlockThreads;   // staged entries per thread (4)
 constexpr uint32_t kNone = 0xFFFFFFFFu;
 
+constexpr uint32_t kFastR = 8;                         // entries a thread keeps in registers per tile
+constexpr uint32_t kStagedCap = 2 * kEntryCap;          // colliding values placed by rank
+
 struct TileLds {
   float acc[kTile];
   uint32_t cnt32[kTile / 4];          // one byte counter per position
@@ -37,9 +40,14 @@ struct TileLds {
   uint32_t cbpre[kTile / 32];         // exclusive popcount prefix of cb
   uint32_t masks[kQMax * kMaskWords]; // per colliding position: which workers hit it
   uint32_t qbase[kQMax];
-  float staged[kEntryCap];
-  uint32_t e_pw[kEntryCap];           // position | local worker << 16, or ~0 if unusable
-  float e_val[kEntryCap];
+  union {
+    float staged[kStagedCap];         // colliding values in worker order, one run per position
+    struct {                          // unpipelined path only: the batch's entries
+      uint32_t e_pw[kEntryCap];       // position | local worker << 16, or ~0 if unusable
+      float e_val[kEntryCap];
+    };
+  };
+  float staged_generic[kEntryCap];    // the unpipelined path needs its entries and the runs at once
   uint32_t w_start[2][kBatchWorkers];
   uint32_t w_pref[2][kBatchWorkers + 1];
   const int32_t* w_idx[kBatchWorkers];
@@ -179,7 +187,7 @@ __device__ void accumulate_staged(TileLds& S, uint32_t E, uint32_t nw, const uin
   for (uint32_t it = 0; it < kPerThread; ++it) {
     if (myq[it] != kNone) {
       const uint32_t at = S.qbase[myq[it]] + myrank[it];
-      if (at < static_cast<uint32_t>(kEntryCap)) S.staged[at] = S.e_val[tid + it * kBlockThreads];
+      if (at < static_cast<uint32_t>(kEntryCap)) S.staged_generic[at] = S.e_val[tid + it * kBlockThreads];
     }
   }
   __syncthreads();
@@ -191,8 +199,94 @@ __device__ void accumulate_staged(TileLds& S, uint32_t E, uint32_t nw, const uin
       const uint32_t b = S.qbase[myq[it]];
       float sum = S.acc[p];
       for (uint32_t i = 0; i < mytotal[it] && b + i < static_cast<uint32_t>(kEntryCap); ++i)
-        sum = __fadd_rn(sum, S.staged[b + i]);
+        sum = __fadd_rn(sum, S.staged_generic[b + i]);
       S.acc[p] = sum;
+    }
+  }
+  __syncthreads();
+}
+
+// Same accumulation for entries that live in registers: thread (worker wl, slot) holds up to kFastR
+// entries of its worker, p[r] = position in the tile or kNone.  S.cnt32 already counts every
+// entry (barrier passed).  Ends with a barrier.
+__device__ void accumulate_regs(TileLds& S, const uint32_t (&p)[kFastR], const float (&v)[kFastR], uint32_t wl,
+                                uint32_t nw) {
+  const uint32_t tid = threadIdx.x;
+  bool coll[kFastR];
+#pragma unroll
+  for (uint32_t r = 0; r < kFastR; ++r) {
+    coll[r] = false;
+    if (p[r] != kNone) {
+      if (hits_of(S, p[r]) == 1u) S.acc[p[r]] = __fadd_rn(S.acc[p[r]], v[r]);
+      else { coll[r] = true; atomicOr(&S.cb[p[r] >> 5], 1u << (p[r] & 31u)); }
+    }
+  }
+  __syncthreads();
+  uint32_t nq;
+  {
+    const uint32_t pc = tid < static_cast<uint32_t>(kTile / 32) ? static_cast<uint32_t>(__popc(S.cb[tid])) : 0u;
+    const uint32_t pex = block_excl_scan(pc, S.scan_lds, nq);
+    if (tid < static_cast<uint32_t>(kTile / 32)) S.cbpre[tid] = pex;
+  }
+  __syncthreads();
+  if (nq == 0u) return;
+  if (nq > static_cast<uint32_t>(kQMax)) {
+    // too many colliding positions for the mask table: add worker after worker
+    for (uint32_t w = 0; w < nw; ++w) {
+      if (wl == w) {
+#pragma unroll
+        for (uint32_t r = 0; r < kFastR; ++r)
+          if (coll[r]) S.acc[p[r]] = __fadd_rn(S.acc[p[r]], v[r]);
+      }
+      __syncthreads();
+    }
+    return;
+  }
+  for (uint32_t i = tid; i < nq * kMaskWords; i += kBlockThreads) S.masks[i] = 0u;
+  __syncthreads();
+  uint32_t q[kFastR];
+#pragma unroll
+  for (uint32_t r = 0; r < kFastR; ++r) {
+    q[r] = kNone;
+    if (coll[r]) {
+      const uint32_t word = S.cb[p[r] >> 5], bit = 1u << (p[r] & 31u);
+      q[r] = S.cbpre[p[r] >> 5] + static_cast<uint32_t>(__popc(word & (bit - 1u)));
+      atomicOr(&S.masks[q[r] * kMaskWords + (wl >> 5)], 1u << (wl & 31u));
+    }
+  }
+  __syncthreads();
+  uint32_t rank[kFastR], total[kFastR];
+#pragma unroll
+  for (uint32_t r = 0; r < kFastR; ++r) {
+    rank[r] = 0;
+    total[r] = 0;
+    if (coll[r]) {
+      worker_rank(S, q[r], wl, rank[r], total[r]);
+      if (rank[r] == 0u) S.qbase[q[r]] = atomicAdd(&S.sh_cursor, total[r]);
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (uint32_t r = 0; r < kFastR; ++r) {
+    if (coll[r]) {
+      const uint32_t at = S.qbase[q[r]] + rank[r];
+      if (at < kStagedCap) S.staged[at] = v[r];
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (uint32_t r = 0; r < kFastR; ++r) {
+    if (coll[r] && rank[r] == 0u) {
+      const uint32_t b = S.qbase[q[r]];
+      const uint32_t n = (b + total[r] <= kStagedCap) ? total[r] : (b < kStagedCap ? kStagedCap - b : 0u);
+      float sum = S.acc[p[r]];
+      uint32_t i = 0;
+      for (; i + 4u <= n; i += 4u) {          // loads first, then the dependent adds, in worker order
+        const float a0 = S.staged[b + i], a1 = S.staged[b + i + 1u], a2 = S.staged[b + i + 2u], a3 = S.staged[b + i + 3u];
+        sum = __fadd_rn(__fadd_rn(__fadd_rn(__fadd_rn(sum, a0), a1), a2), a3);
+      }
+      for (; i < n; ++i) sum = __fadd_rn(sum, S.staged[b + i]);
+      S.acc[p[r]] = sum;
     }
   }
   __syncthreads();
@@ -357,19 +451,34 @@ __global__ void __launch_bounds__(kBlockThreads) decompress_tiles_kernel(Decompr
   __shared__ TileLds S;
   const uint32_t tid = threadIdx.x;
   const uint32_t N = A.num_workers;
-  // Workgroups are dealt to the 8 XCDs round-robin by index.  Give every XCD one contiguous
-  // range of tiles and every workgroup a contiguous piece of it.
-  uint32_t t_first, t_last;
+  // Workgroups are dealt to the 8 XCDs round-robin by index.  Every XCD gets one contiguous
+  // range of tiles, and the workgroups of an XCD take its tiles round-robin, so at any moment
+  // they work on neighbouring tiles: one 128-byte line of a message holds the entries of about
+  // 8 tiles, is fetched from HBM once and is then found in that XCD's L2 by the 7 other
+  // workgroups that need it (a blocked assignment makes the concurrent working set of an XCD
+  // as large as its L2 and fetches every line 8 times).
+  uint32_t t_first, t_last, stride;
   {
     const uint32_t xcd = blockIdx.x & 7u, slot = blockIdx.x >> 3, slots = gridDim.x >> 3;
     const uint32_t per_xcd = (A.num_tiles + 7u) >> 3;
     const uint32_t x0 = xcd * per_xcd < A.num_tiles ? xcd * per_xcd : A.num_tiles;
     const uint32_t x1 = x0 + per_xcd < A.num_tiles ? x0 + per_xcd : A.num_tiles;
-    const uint32_t per_slot = (x1 - x0 + slots - 1u) / slots;
-    t_first = x0 + slot * per_slot < x1 ? x0 + slot * per_slot : x1;
-    t_last = t_first + per_slot < x1 ? t_first + per_slot : x1;
+    if (A.debug & 8u) {          // blocked: a contiguous piece per workgroup
+      const uint32_t per_slot = (x1 - x0 + slots - 1u) / slots;
+      t_first = x0 + slot * per_slot < x1 ? x0 + slot * per_slot : x1;
+      t_last = t_first + per_slot < x1 ? t_first + per_slot : x1;
+      stride = 1u;
+    } else {
+      t_first = x0 + slot < x1 ? x0 + slot : x1;
+      t_last = x1;
+      stride = slots;
+    }
   }
   const bool pipelined = N >= 1u && N <= static_cast<uint32_t>(kBatchWorkers);
+  // threads per worker on the pipelined path: 256 / (N rounded up to a power of two), >= 2
+  uint32_t tpw_shift = 1;
+  while (tpw_shift < 8u && (N << (tpw_shift + 1u)) <= static_cast<uint32_t>(kBlockThreads)) ++tpw_shift;
+  const uint32_t tpw = 1u << tpw_shift;
 
   uint32_t tile_id = t_first;
   while (tile_id < t_last) {
@@ -379,7 +488,7 @@ __global__ void __launch_bounds__(kBlockThreads) decompress_tiles_kernel(Decompr
     const uint32_t run_end = (L.tile_base + L.tiles) < t_last ? (L.tile_base + L.tiles) : t_last;
 
     if (!pipelined) {
-      for (; tile_id < run_end; ++tile_id) {
+      for (; tile_id < run_end; tile_id += stride) {
         const TileGeom g = tile_geom(L, layer, tile_id);
         clear_tile(S);
         __syncthreads();
@@ -390,114 +499,117 @@ __global__ void __launch_bounds__(kBlockThreads) decompress_tiles_kernel(Decompr
       continue;
     }
 
-    // ---- pipelined run: all N workers form one batch
-    uint32_t my_count = 0;                       // entries in this thread's worker's message
-    __syncthreads();                             // nobody still reads the previous run's pointers
-    if (tid < N) {
-      const MsgDesc md = A.msgs[static_cast<size_t>(layer) * N + tid];
-      S.w_idx[tid] = md.idx;
-      S.w_val[tid] = md.val;
+    // ---- pipelined run.  Thread (worker wl, part) owns, of its worker's entries inside a tile,
+    // the groups of four consecutive entries number part, part + T, ... (T threads per worker),
+    // kFastR entries at most, fetched with one 16-byte load per group and array: an L1 lookup
+    // costs the same for 4 bytes as for 16, and one-entry gathers made this kernel bound by
+    // them.  A tile where some worker has more entries takes the unpipelined path.  The
+    // entries stay in registers from the prefetch to the end of their tile.
+    const uint32_t wl = tid & ((static_cast<uint32_t>(kBlockThreads) >> tpw_shift) - 1u);
+    const uint32_t part = tid >> (8u - tpw_shift);
+    const bool has_worker = wl < N;
+    uint32_t my_count = 0;
+    gptr<const int32_t> my_idx = nullptr;
+    gptr<const float> my_val = nullptr;
+    if (has_worker) {
+      const MsgDesc md = A.msgs[static_cast<size_t>(layer) * N + wl];
+      my_idx = as_global(md.idx);
+      my_val = as_global(md.val);
       my_count = md.count;
     }
-    const uint32_t* tabw = A.tab + tid;          // column of this thread's worker (tid < N)
+    const uint32_t* tabw = A.tab + (has_worker ? wl : 0u);
     auto row_at = [&](uint32_t row) -> uint32_t {
-      if (tid >= N) return 0u;
+      if (!has_worker) return 0u;
       const uint32_t v = tabw[static_cast<size_t>(row) * N];
       return v < my_count ? v : my_count;        // the table never exceeds the message; stay in bounds anyway
     };
     const uint32_t row0 = L.row_base + (tile_id - L.tile_base);
-    uint32_t r_start = row_at(row0);             // first entry of the tile being prefetched
-    uint32_t r_end = row_at(row0 + 1u);          // its end = first entry of the tile after it
-    uint32_t r_end2 = (tile_id + 1u < run_end) ? row_at(row0 + 2u) : 0u;   // end of the tile after it
+    uint32_t r_start = row_at(row0);             // entry range of the tile being prefetched
+    uint32_t r_end = row_at(row0 + 1u);
+    uint32_t r_start2 = 0, r_end2 = 0;           // entry range of this workgroup's tile after it
+    if (tile_id + stride < run_end) {
+      r_start2 = row_at(row0 + stride);
+      r_end2 = row_at(row0 + stride + 1u);
+    }
 
-    // prefetched entries of the next tile to process
-    uint32_t nx_lo[kPerThread], nx_idx[kPerThread];
-    float nx_val[kPerThread];
-    uint32_t nx_E = 0;
+    uint32_t nx_idx[kFastR];
+    float nx_val[kFastR];
+    uint32_t nx_cnt = 0;                         // how many of them exist (this thread)
     bool nx_generic = false;
-    // Computes the entry -> (worker, offset) mapping of the tile whose offsets are
-    // [r_start, r_end) into S.w_start/w_pref[buf] and issues the loads of its entries.
-    auto prefetch = [&](uint32_t buf) {
+    typedef uint32_t vu4 __attribute__((ext_vector_type(4), aligned(4)));
+    typedef float vf4u __attribute__((ext_vector_type(4), aligned(4)));
+    auto prefetch = [&]() {
       const uint32_t c = r_end > r_start ? r_end - r_start : 0u;
-      uint32_t total;
-      const uint32_t ex = block_excl_scan(tid < N ? c : 0u, S.scan_lds, total);
-      if (tid < N) { S.w_start[buf][tid] = r_start; S.w_pref[buf][tid] = ex; }
-      if (tid == N - 1u) S.w_pref[buf][N] = ex + c;
-      __syncthreads();
-      nx_E = total;
-      nx_generic = total > static_cast<uint32_t>(kEntryCap);
+      nx_generic = __syncthreads_or(c > tpw * kFastR ? 1 : 0) != 0;
+      nx_cnt = 0;
 #pragma unroll
-      for (uint32_t it = 0; it < kPerThread; ++it) {
-        const uint32_t e = tid + it * kBlockThreads;
-        nx_lo[it] = kNone;
-        nx_idx[it] = 0;
-        nx_val[it] = 0.0f;
-        if (!nx_generic && e < total) {
-          uint32_t lo = 0, hi = N;
-          while (hi - lo > 1u) {
-            const uint32_t mid = (lo + hi) >> 1;
-            if (S.w_pref[buf][mid] <= e) lo = mid; else hi = mid;
+      for (uint32_t r = 0; r < kFastR / 4u; ++r) {
+        const uint32_t off = 4u * (part + r * tpw);          // first entry of this group inside the tile
+#pragma unroll
+        for (uint32_t j = 0; j < 4u; ++j) { nx_idx[4u * r + j] = 0; nx_val[4u * r + j] = 0.0f; }
+        if (!nx_generic && off < c) {
+          const uint32_t at = r_start + off;
+          const uint32_t have = (c - off) < 4u ? (c - off) : 4u;
+          if (at + 4u <= my_count) {                         // the 16-byte load stays inside the message
+            const vu4 qi = *reinterpret_cast<gptr<const vu4>>(my_idx + at);
+            const vf4u qv = *reinterpret_cast<gptr<const vf4u>>(my_val + at);
+            nx_idx[4u * r + 0] = qi.x; nx_idx[4u * r + 1] = qi.y; nx_idx[4u * r + 2] = qi.z; nx_idx[4u * r + 3] = qi.w;
+            nx_val[4u * r + 0] = qv.x; nx_val[4u * r + 1] = qv.y; nx_val[4u * r + 2] = qv.z; nx_val[4u * r + 3] = qv.w;
+          } else {
+#pragma unroll
+            for (uint32_t j = 0; j < 4u; ++j) {
+              if (j < have) {
+                nx_idx[4u * r + j] = static_cast<uint32_t>(my_idx[at + j]);
+                nx_val[4u * r + j] = my_val[at + j];
+              }
+            }
           }
-          const uint32_t j = S.w_start[buf][lo] + (e - S.w_pref[buf][lo]);
-          nx_lo[it] = lo;
-          nx_idx[it] = static_cast<uint32_t>(as_global(S.w_idx[lo])[j]);
-          nx_val[it] = as_global(S.w_val[lo])[j];
+          nx_cnt = 4u * r + have;
         }
       }
     };
-    __syncthreads();                             // S.w_idx / S.w_val are set
-    uint32_t buf = 0;
-    prefetch(buf);
+    prefetch();
 
-    for (; tile_id < run_end; ++tile_id) {
+    for (; tile_id < run_end; tile_id += stride) {
       const TileGeom g = tile_geom(L, layer, tile_id);
-      const uint32_t E = nx_E;
       const bool generic = nx_generic;
-      const uint32_t cur_buf = buf;
       clear_tile(S);
       clear_batch(S);
       __syncthreads();
-      // ---- stage this tile's entries (prefetched during the previous tile)
-      if (!generic) {
+      // ---- this tile's entries were prefetched during the previous tile: count the hits
+      uint32_t cur_p[kFastR];
+      float cur_v[kFastR];
 #pragma unroll
-        for (uint32_t it = 0; it < kPerThread; ++it) {
-          const uint32_t e = tid + it * kBlockThreads;
-          if (e < E) {
-            const uint32_t p = nx_idx[it] - g.first;
-            if (p < g.len) {
-              S.e_pw[e] = p | (nx_lo[it] << 16);
-              S.e_val[e] = nx_val[it];
-              atomicAdd(&S.cnt32[p >> 2], 1u << ((p & 3u) * 8u));
-            } else {
-              S.e_pw[e] = kNone;
-            }
+      for (uint32_t r = 0; r < kFastR; ++r) {
+        cur_p[r] = kNone;
+        cur_v[r] = nx_val[r];
+        if (!generic && r < nx_cnt) {
+          const uint32_t p = nx_idx[r] - g.first;
+          if (p < g.len) {
+            cur_p[r] = p;
+            atomicAdd(&S.cnt32[p >> 2], 1u << ((p & 3u) * 8u));
           }
         }
       }
       __syncthreads();
       // ---- start fetching the next tile of the run
-      if (tile_id + 1u < run_end) {
-        r_start = r_end;
+      if (tile_id + stride < run_end) {
+        r_start = r_start2;
         r_end = r_end2;
-        if (tile_id + 2u < run_end) r_end2 = row_at(L.row_base + (tile_id - L.tile_base) + 3u);
-        buf ^= 1u;
-        if (!generic) prefetch(buf);
+        if (tile_id + 2u * stride < run_end) {
+          const uint32_t row2 = L.row_base + (tile_id - L.tile_base) + 2u * stride;
+          r_start2 = row_at(row2);
+          r_end2 = row_at(row2 + 1u);
+        }
+        if (!(A.debug & 2u)) prefetch();
       }
       // ---- accumulate and write this tile
       if (generic) {
-        tile_generic(A, S, g);                   // too many entries for one batch: unpipelined
-        // tile_generic overwrote S.w_idx / S.w_val and buffer 0 of the mapping arrays
-        if (tid < N) {
-          const MsgDesc md = A.msgs[static_cast<size_t>(layer) * N + tid];
-          S.w_idx[tid] = md.idx;
-          S.w_val[tid] = md.val;
-        }
-        __syncthreads();
-        if (tile_id + 1u < run_end) prefetch(buf);
-      } else if (E != 0u) {
-        accumulate_staged(S, E, N, S.w_pref[cur_buf]);
+        tile_generic(A, S, g);                   // some worker has too many entries here: unpipelined
+      } else if (!(A.debug & 1u)) {
+        accumulate_regs(S, cur_p, cur_v, wl, N);
       }
-      write_tile(S, g, A.scale, A.add_to_dst);
+      if (!(A.debug & 4u)) write_tile(S, g, A.scale, A.add_to_dst);
       __syncthreads();
     }
   }

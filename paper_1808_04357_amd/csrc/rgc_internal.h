@@ -141,6 +141,7 @@ struct DecompressArgs {
   uint32_t num_blocks;
   uint32_t add_to_dst;
   float scale;
+  uint32_t debug;             // experiment switches (RGC_DEBUG), 0 in normal use
 };
 
 // kernel launchers (defined in the .hip files)
