@@ -163,6 +163,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--skip-others", action="store_true", help="only the headline VGG16 step")
     ap.add_argument("--skip-cpu", action="store_true", help="leave out the oracle timing")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three plain device copies of 4*138,344,128 bytes (a yardstick of known "
+                         "size for rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1")
@@ -211,6 +214,14 @@ def main():
     roofline = {"bound": "hbm", "kernel": "accumulate_kernel (fused residual/momentum accumulate + candidate collect)",
                 "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                 "traffic": None, "bytes_per_launch": vgg.alg_bytes_stream, "avg_launch_ms": k_ms}
+
+    if args.calibrate_copy:
+        src = torch.zeros(vgg.total, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     others = {}
     if not args.skip_others:
