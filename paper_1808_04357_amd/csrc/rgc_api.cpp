@@ -55,7 +55,6 @@ uint32_t chunk_override() {
 // counters for the per-layer serial steps, smaller ones more workgroups to fill 256 CUs.
 uint32_t chunk_for(int64_t total) {
   if (chunk_override()) return chunk_override();
-  if (total >= (int64_t(48) << 20)) return 16384;
   if (total >= (int64_t(8) << 20)) return 8192;
   return kChunkSmallest;
 }
@@ -63,6 +62,7 @@ uint32_t chunk_for(int64_t total) {
 // Smallest chunk any call may use: the scratch is sized for it.
 uint32_t chunk_smallest() { return chunk_override() ? std::min(chunk_override(), kChunkSmallest) : kChunkSmallest; }
 constexpr int kPlanCache = 8;
+constexpr uint32_t kElectGroupHost = 32;   // = kElectGroup of the kernels (workgroups per election group)
 constexpr int kLaunches = 6;               // streaming pass + at most five phase launches
 
 struct DeviceGuard {
@@ -147,7 +147,7 @@ struct rgc_ctx {
   int32_t max_layers = 0;
   uint32_t wc_max = 0;
   DevBuf<LayerState> d_state;
-  DevBuf<uint32_t> d_hist, d_coarse, d_cand_cnt, d_wc_a, d_wc_b, d_err;
+  DevBuf<uint32_t> d_hist, d_coarse, d_cand_cnt, d_wc_a, d_wc_b, d_err, d_group;
   DevBuf<unsigned long long> d_members;
   DevBuf<uint2> d_slots;
   CompressPlan plans[kPlanCache];
@@ -180,7 +180,7 @@ int build_compress_plan(rgc_ctx* ctx, CompressPlan& P, const rgc_layer* layers, 
   for (int32_t l = 0; l < L; ++l) total_elems += layers[l].n;
   const uint32_t kChunk = chunk_for(total_elems), kCap = kChunk / kCapDiv;
   P.chunk = kChunk;
-  uint32_t wc = 0, wg = 0;
+  uint32_t wc = 0, wg = 0, grp = 0;
   for (int32_t o = 0; o < L; ++o) {
     const int32_t l = order[o];
     const rgc_layer& in = layers[l];
@@ -197,6 +197,9 @@ int build_compress_plan(rgc_ctx* ctx, CompressPlan& P, const rgc_layer* layers, 
     d.wc_count = static_cast<uint32_t>((in.n + kChunk - 1) / kChunk);
     d.wg_first = wg;
     d.wg_count = (d.wc_count + kWavesPerBlock - 1) / kWavesPerBlock;
+    d.grp_first = grp;
+    grp += (d.wg_count + kElectGroupHost - 1) / kElectGroupHost;
+    d.pad_ = 0;
     const uintptr_t bits = reinterpret_cast<uintptr_t>(in.grad) | reinterpret_cast<uintptr_t>(in.residual) |
                            reinterpret_cast<uintptr_t>(in.momentum);
     d.vec_ok = (bits & 15u) == 0 ? 1u : 0u;
@@ -318,11 +321,14 @@ int rgc_create(rgc_ctx** out, int device_id, int64_t max_total_elems, int32_t ma
     chk(c->d_slots.alloc(static_cast<uint64_t>(max_total_elems) / kCapDiv + (static_cast<uint64_t>(max_layers) + 1) * (largest / kCapDiv)));
   }
   chk(c->d_err.alloc(1));
+  const uint64_t grp_max = wc_max / (kWavesPerBlock * kElectGroupHost) + 2 * L + 2;
+  chk(c->d_group.alloc(grp_max));
   if (e == hipSuccess) chk(hipMemset(c->d_state.p, 0, sizeof(LayerState) * L));
   if (e == hipSuccess) chk(hipMemset(c->d_hist.p, 0, sizeof(uint32_t) * L * kHistBins));
   if (e == hipSuccess) chk(hipMemset(c->d_coarse.p, 0, sizeof(uint32_t) * L * kCoarseRep * kCoarseBins));
   if (e == hipSuccess) chk(hipMemset(c->d_cand_cnt.p, 0, sizeof(uint32_t) * wc_max));
   if (e == hipSuccess) chk(hipMemset(c->d_err.p, 0, sizeof(uint32_t)));
+  if (e == hipSuccess) chk(hipMemset(c->d_group.p, 0, sizeof(uint32_t) * grp_max));
   if (e == hipSuccess) chk(hipDeviceSynchronize());
   if (e != hipSuccess) {
     rgc_ctx* raw = c.release();
@@ -351,6 +357,7 @@ int rgc_destroy(rgc_ctx* ctx) {
   ctx->d_wc_b.release();
   ctx->d_slots.release();
   ctx->d_err.release();
+  ctx->d_group.release();
   for (auto* v : {&ctx->ev_compress, &ctx->ev_decompress, &ctx->ev_pool})
     for (hipEvent_t e : *v) (void)hipEventDestroy(e);
   delete ctx;
@@ -433,6 +440,7 @@ int rgc_compress_layers(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layer
   A.wc_a = ctx->d_wc_a.p;
   A.wc_b = ctx->d_wc_b.p;
   A.errflag = ctx->d_err.p;
+  A.group_done = ctx->d_group.p;
   A.chunk = plan->chunk;
   A.cap = A.chunk / kCapDiv;
   A.use_hints = (sig_same && !no_hints) ? 1u : 0u;

@@ -58,6 +58,7 @@ __device__ __forceinline__ void consume(const float (&a)[4], uint32_t nvalid, ui
     key[j] = bits[j] & kKeyMask;
   }
   if constexpr (kCollect) {
+    if (c.debug & 1024u) return;
     if (c.debug & 512u) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) atomicAdd(&lds_hist[1024u + (key[j] >> 19) % 3072u], 1u);
@@ -468,7 +469,7 @@ __device__ void resolve_collect(const CompressArgs& A, uint32_t l, const LayerDe
 //            (= prefix(a) + min(prefix(b), r)), b[] = prefix(b).
 __device__ void scan_chunks(uint32_t* a, uint32_t* b, uint32_t count, uint32_t r, bool with_ties,
                             uint32_t* lds_scan, uint32_t* out_total) {
-  constexpr uint32_t kItems = 4;
+  constexpr uint32_t kItems = 16;   // many independent device-scope loads in flight per thread: this is a serial step
   uint32_t carry_a = 0, carry_b = 0;
   for (uint32_t base = 0; base < count; base += kBlockThreads * kItems) {
     uint32_t va[kItems], vb[kItems];
@@ -554,7 +555,7 @@ __global__ void __launch_bounds__(kBlockThreads) accumulate_kernel(CompressArgs 
     c.tau = st->tau;
     c.shift = st->shift;
     const bool mom = (L.mom != nullptr);
-    if (collect) {
+    if (collect && !(A.debug & 2048u)) {
       if (mom) stream_chunk<true, true>(L, begin, end, A.m, c, lds_hist);
       else stream_chunk<false, true>(L, begin, end, A.m, c, lds_hist);
       if (lane_id() == 0) st_agent(&A.cand_cnt[L.wc_first + wc_local], c.count);
@@ -573,7 +574,7 @@ __global__ void __launch_bounds__(kBlockThreads) accumulate_kernel(CompressArgs 
   } else {
     flush_hist(lds_hist, A.hist + static_cast<size_t>(l) * kHistBins, kHistBins);
   }
-  if (last_block_of_layer(&st->done, L.wg_count, &sh.flag)) {
+  if (last_block_of_layer(&st->done, A.group_done + L.grp_first, blockIdx.x - L.wg_first, L.wg_count, &sh.flag)) {
     if (A.debug & 4u) return;
     if (collect) {
       resolve_collect(A, l, L, st, sh, lds_hist);
@@ -619,7 +620,7 @@ __device__ void phase_hist(const CompressArgs& A, uint32_t l, const LayerDesc& L
   }
   __syncthreads();
   flush_hist(lds_hist, A.hist + static_cast<size_t>(l) * kHistBins, kBins);
-  if (last_block_of_layer(&st->done, L.wg_count, &sh.flag)) resolve_digit<kLevel>(A, l, L, st, sh, lds_hist, A.launch);
+  if (last_block_of_layer(&st->done, A.group_done + L.grp_first, blockIdx.x - L.wg_first, L.wg_count, &sh.flag)) resolve_digit<kLevel>(A, l, L, st, sh, lds_hist, A.launch);
 }
 
 __device__ void phase_count(const CompressArgs& A, uint32_t l, const LayerDesc& L, LayerState* st,
@@ -647,7 +648,7 @@ __device__ void phase_count(const CompressArgs& A, uint32_t l, const LayerDesc& 
       st_agent(&A.wc_b[L.wc_first + wc_local], eq_all);
     }
   }
-  if (last_block_of_layer(&st->done, L.wg_count, &sh.flag)) {
+  if (last_block_of_layer(&st->done, A.group_done + L.grp_first, blockIdx.x - L.wg_first, L.wg_count, &sh.flag)) {
     scan_chunks(A.wc_a + L.wc_first, A.wc_b + L.wc_first, L.wc_count, st->r, true, sh.scan, &sh.cnt);
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -744,7 +745,7 @@ __device__ void phase_sel(const CompressArgs& A, uint32_t l, const LayerDesc& L,
     const uint32_t hi_all = wave_total(wave_incl_scan(hi));
     if (lane == 0) st_agent(&A.wc_a[wc], hi_all);
   }
-  if (!last_block_of_layer(&st->done, L.wg_count, &sh.flag)) return;
+  if (!last_block_of_layer(&st->done, A.group_done + L.grp_first, blockIdx.x - L.wg_first, L.wg_count, &sh.flag)) return;
 
   const uint32_t m = ld_agent(&st->nmembers);
   const uint32_t k_rem = st->k_rem;

@@ -44,10 +44,12 @@ struct LayerDesc {
   uint32_t wc_count;   // number of wave-chunks = ceil(n / chunk)
   uint32_t wg_first;   // first workgroup of this layer
   uint32_t wg_count;   // = ceil(wc_count / 4)
+  uint32_t grp_first;  // first election-group counter of this layer
   uint32_t vec_ok;     // every tensor pointer is 16-byte aligned
   uint32_t hintable;   // candidate lists are large enough for k + margin at this density
   uint32_t margin;     // extra candidates aimed for beyond k
   uint32_t cmax;       // largest candidate total a hint may aim at
+  uint32_t pad_;
 };
 
 // Per layer state living in the context (device memory).  Everything but the hint fields is
@@ -88,6 +90,7 @@ struct CompressArgs {
   uint2* slots;          // [wave-chunks][cap] (float bits, index), ascending index per chunk
   uint32_t* wc_a;        // [wave-chunks] counts, then output offsets
   uint32_t* wc_b;        // [wave-chunks] tie counts, then tie prefixes
+  uint32_t* group_done;  // [election groups] workgroups of the group that finished the current phase
   uint32_t* errflag;     // set non-zero on an internal inconsistency
   uint32_t chunk;        // elements per wave-chunk (multiple of 256)
   uint32_t cap;          // candidate slots per wave-chunk
