@@ -1,25 +1,33 @@
 // gfx950 kernels of the decompression step (RedSync, Section 2.3: after the Allgather every
 // node adds the N gathered sparse messages into a dense array).
 //
-// Tile ownership: one workgroup owns kTile consecutive positions of one dense buffer, keeps
-// them in LDS, adds every worker's entries that fall into the tile and writes the tile once
-// (scaled).  Entries of one worker are unique inside a tile, so positions hit by a single
-// worker need no ordering; positions hit by several workers are summed strictly in worker
-// order by one lane each: a per-position bitmask of the hitting workers (built with
-// order-independent atomic ORs) gives every colliding entry its rank among them, the values
-// are placed by rank and then added left to right.  The result is therefore independent of
-// scheduling and equals the sequential sum bit for bit; no floating-point atomics are used.
+// Tile ownership: one workgroup owns kTile consecutive positions of one dense buffer, adds every
+// worker's entries that fall into the tile and writes the tile once (scaled).  Entries of one
+// worker are unique inside a tile, so positions hit by a single worker need no ordering;
+// positions hit by several workers are summed strictly in worker order by one lane each: a
+// per-position bitmask of the hitting workers (built with order-independent atomic ORs) gives
+// every colliding entry its rank among them, the values are placed by rank and then added left
+// to right.  The result is therefore independent of scheduling and equals the sequential sum
+// bit for bit; no floating-point atomics are used.
 //
 // A first kernel builds a table with the offset of the first entry of every tile in every
-// (worker, layer) message (the messages are sorted by index); rows are tiles, columns are
-// workers, so a tile reads all its offsets from two contiguous rows.
+// (worker, layer) message (the messages are sorted by index); one row per worker, so both the
+// builder's stores and a worker's reads for neighbouring tiles fall into the same cache lines.
 //
 // The tile kernel is persistent and XCD-aware: every XCD gets one contiguous range of tiles and
-// every workgroup a contiguous piece of it, so neighbouring tiles share table rows and message
-// cache lines inside one L2.  Inside a run of tiles of one layer the kernel is software
-// pipelined: while tile i is accumulated in LDS, the entries of tile i+1 are already being
-// loaded into registers and the table row of tile i+2 is in flight, so no tile waits for a
-// chain of dependent global loads.
+// its workgroups take them round-robin, so neighbouring tiles share table and message cache
+// lines inside one L2.  A tile is a few hundred entries in 4096 positions, so the kernel keeps
+// it sparse: a bitmap of the hit positions, their sums in a compact array, and the dense tile is
+// formed in registers on the way out (mostly zeros).  That keeps the LDS footprint at 20 KB (8
+// workgroups per CU, which is what hides the store and gather latencies) and removes the dense
+// clear.  Inside a run of tiles of one layer the kernel is software pipelined: while tile i is
+// processed, the entries of tile i+1 are already being loaded into registers and the table
+// entries of tile i+2 are in flight.
+//
+// Tiles the fast kernel cannot take (a worker with more entries than its threads hold, too many
+// distinct or colliding positions) are appended to a list and redone by a second kernel with
+// larger staging buffers and no pipelining; with more than kBatchWorkers workers that kernel
+// does every tile.
 #include "rgc_device.h"
 
 namespace rgc {
@@ -29,38 +37,17 @@ namespace {
 constexpr uint32_t kTableBlockEntries = 1024;
 constexpr uint32_t kPerThread = kEntryCap / kBlockThreads;   // staged entries per thread (4)
 constexpr uint32_t kNone = 0xFFFFFFFFu;
+constexpr uint32_t kWords = kTile / 32;                 // words of a one-bit-per-position map
 
-constexpr uint32_t kFastR = 8;                         // entries a thread keeps in registers per tile
-constexpr uint32_t kStagedCap = 2 * kEntryCap;          // colliding values placed by rank
-
-struct TileLds {
-  float acc[kTile];
-  uint32_t cnt32[kTile / 4];          // one byte counter per position
-  uint32_t cb[kTile / 32];            // positions hit more than once in this batch
-  uint32_t cbpre[kTile / 32];         // exclusive popcount prefix of cb
-  uint32_t masks[kQMax * kMaskWords]; // per colliding position: which workers hit it
-  uint32_t qbase[kQMax];
-  union {
-    float staged[kStagedCap];         // colliding values in worker order, one run per position
-    struct {                          // unpipelined path only: the batch's entries
-      uint32_t e_pw[kEntryCap];       // position | local worker << 16, or ~0 if unusable
-      float e_val[kEntryCap];
-    };
-  };
-  float staged_generic[kEntryCap];    // the unpipelined path needs its entries and the runs at once
-  uint32_t w_start[2][kBatchWorkers];
-  uint32_t w_pref[2][kBatchWorkers + 1];
-  const int32_t* w_idx[kBatchWorkers];
-  const float* w_val[kBatchWorkers];
-  uint32_t scan_lds[4];
-  uint32_t sh_end, sh_entries, sh_cursor;
-};
+typedef uint32_t vu2l __attribute__((ext_vector_type(2)));
+typedef uint32_t vu4l __attribute__((ext_vector_type(4)));
+typedef float vf4 __attribute__((ext_vector_type(4)));
 
 struct TileGeom {          // one tile, derived arithmetically from its layer
   float* dense;            // start of the tile
   uint32_t first;          // layer-local index of its first position
   uint32_t len;            // positions in it (<= kTile)
-  uint32_t row;            // its table row; row + 1 closes it
+  uint32_t row;            // its table entry inside a worker's row; row + 1 closes it
   uint32_t layer;
 };
 
@@ -84,26 +71,65 @@ __device__ __forceinline__ TileGeom tile_geom(const DecompressLayer& L, uint32_t
   return g;
 }
 
-__device__ __forceinline__ void clear_tile(TileLds& S) {
+// The tiles of workgroup `wg` of a persistent grid: t_first, t_first + stride, ... < t_last.
+// Workgroups are dealt to the 8 XCDs round-robin by index.  Every XCD gets one contiguous range
+// of tiles, and the workgroups of an XCD take its tiles round-robin, so at any moment they work on
+// neighbouring tiles: one 128-byte line of a message holds the entries of about 8 tiles, is
+// fetched from HBM once and is then found in that XCD's L2 by the 7 other workgroups that need it
+// (a blocked assignment makes the concurrent working set of an XCD as large as its L2 and fetches
+// every line 8 times).
+__device__ __forceinline__ void tiles_of_workgroup(uint32_t num_tiles, uint32_t& t_first, uint32_t& t_last,
+                                                   uint32_t& stride) {
+  const uint32_t xcd = blockIdx.x & 7u, slot = blockIdx.x >> 3, slots = gridDim.x >> 3;
+  const uint32_t per_xcd = (num_tiles + 7u) >> 3;
+  const uint32_t x0 = xcd * per_xcd < num_tiles ? xcd * per_xcd : num_tiles;
+  const uint32_t x1 = x0 + per_xcd < num_tiles ? x0 + per_xcd : num_tiles;
+  t_first = x0 + slot < x1 ? x0 + slot : x1;
+  t_last = x1;
+  stride = slots;
+}
+
+// =================================================================== generic tiles
+struct alignas(16) GenericLds {
+  float acc[kTile];
+  uint32_t cnt32[kTile / 4];          // one byte counter per position
+  uint32_t cb[kWords];                // positions hit more than once in this batch
+  uint32_t cbpre[kWords];             // exclusive popcount prefix of cb
+  uint32_t masks[kQMax * kMaskWords]; // per colliding position: which workers hit it
+  uint32_t qbase[kQMax];
+  uint32_t e_pw[kEntryCap];           // position | local worker << 16, or ~0 if unusable
+  float e_val[kEntryCap];
+  float staged[kEntryCap];            // colliding values in worker order, one run per position
+  uint32_t w_start[kBatchWorkers];
+  uint32_t w_pref[kBatchWorkers + 1];
+  const int32_t* w_idx[kBatchWorkers];
+  const float* w_val[kBatchWorkers];
+  uint32_t scan_lds[4];
+  uint32_t sh_end, sh_entries, sh_cursor;
+};
+
+__device__ __forceinline__ void clear_tile(GenericLds& S) {
   for (uint32_t i = threadIdx.x; i < static_cast<uint32_t>(kTile); i += kBlockThreads) S.acc[i] = 0.0f;
 }
 
-__device__ __forceinline__ void clear_batch(TileLds& S) {
+__device__ __forceinline__ void clear_batch(GenericLds& S) {
   for (uint32_t i = threadIdx.x; i < static_cast<uint32_t>(kTile / 4); i += kBlockThreads) S.cnt32[i] = 0u;
-  if (threadIdx.x < static_cast<uint32_t>(kTile / 32)) S.cb[threadIdx.x] = 0u;
+  if (threadIdx.x < kWords) S.cb[threadIdx.x] = 0u;
   if (threadIdx.x == 0) S.sh_cursor = 0u;
 }
 
-__device__ __forceinline__ uint32_t hits_of(const TileLds& S, uint32_t p) {
+__device__ __forceinline__ uint32_t hits_of(const GenericLds& S, uint32_t p) {
   return (S.cnt32[p >> 2] >> ((p & 3u) * 8u)) & 0xFFu;
 }
 
-__device__ __forceinline__ void worker_rank(const TileLds& S, uint32_t q, uint32_t wl, uint32_t& rank, uint32_t& total) {
+// Rank of worker `wl` among the workers in the mask of colliding position q, and their number.
+__device__ __forceinline__ void worker_rank(const uint32_t* masks, uint32_t q, uint32_t wl, uint32_t& rank,
+                                            uint32_t& total) {
   rank = 0;
   total = 0;
 #pragma unroll
   for (uint32_t mw = 0; mw < static_cast<uint32_t>(kMaskWords); ++mw) {
-    const uint32_t mk = S.masks[q * kMaskWords + mw];
+    const uint32_t mk = masks[q * kMaskWords + mw];
     total += static_cast<uint32_t>(__popc(mk));
     if (mw < (wl >> 5)) rank += static_cast<uint32_t>(__popc(mk));
     else if (mw == (wl >> 5)) rank += static_cast<uint32_t>(__popc(mk & ((1u << (wl & 31u)) - 1u)));
@@ -114,7 +140,7 @@ __device__ __forceinline__ void worker_rank(const TileLds& S, uint32_t q, uint32
 // followed by a barrier).  Adds them into S.acc in worker order.  `pref` = exclusive prefix of
 // the per-worker entry counts of the batch (nw + 1 values), used by the rare slow path only.
 // Ends with a barrier.
-__device__ void accumulate_staged(TileLds& S, uint32_t E, uint32_t nw, const uint32_t* pref) {
+__device__ void accumulate_staged(GenericLds& S, uint32_t E, uint32_t nw, const uint32_t* pref) {
   const uint32_t tid = threadIdx.x;
   // ---- positions hit once are final; mark the others
   for (uint32_t e = tid; e < E; e += kBlockThreads) {
@@ -128,9 +154,9 @@ __device__ void accumulate_staged(TileLds& S, uint32_t E, uint32_t nw, const uin
   // ---- dense numbering of the colliding positions
   uint32_t nq;
   {
-    const uint32_t pc = tid < static_cast<uint32_t>(kTile / 32) ? static_cast<uint32_t>(__popc(S.cb[tid])) : 0u;
+    const uint32_t pc = tid < kWords ? static_cast<uint32_t>(__popc(S.cb[tid])) : 0u;
     const uint32_t pex = block_excl_scan(pc, S.scan_lds, nq);
-    if (tid < static_cast<uint32_t>(kTile / 32)) S.cbpre[tid] = pex;
+    if (tid < kWords) S.cbpre[tid] = pex;
   }
   __syncthreads();
   if (nq == 0u) return;
@@ -177,7 +203,7 @@ __device__ void accumulate_staged(TileLds& S, uint32_t E, uint32_t nw, const uin
     mytotal[it] = 0;
     if (myq[it] != kNone) {
       const uint32_t wl = S.e_pw[tid + it * kBlockThreads] >> 16;
-      worker_rank(S, myq[it], wl, myrank[it], mytotal[it]);
+      worker_rank(S.masks, myq[it], wl, myrank[it], mytotal[it]);
       if (myrank[it] == 0u) S.qbase[myq[it]] = atomicAdd(&S.sh_cursor, mytotal[it]);
     }
   }
@@ -187,7 +213,7 @@ __device__ void accumulate_staged(TileLds& S, uint32_t E, uint32_t nw, const uin
   for (uint32_t it = 0; it < kPerThread; ++it) {
     if (myq[it] != kNone) {
       const uint32_t at = S.qbase[myq[it]] + myrank[it];
-      if (at < static_cast<uint32_t>(kEntryCap)) S.staged_generic[at] = S.e_val[tid + it * kBlockThreads];
+      if (at < static_cast<uint32_t>(kEntryCap)) S.staged[at] = S.e_val[tid + it * kBlockThreads];
     }
   }
   __syncthreads();
@@ -199,106 +225,19 @@ __device__ void accumulate_staged(TileLds& S, uint32_t E, uint32_t nw, const uin
       const uint32_t b = S.qbase[myq[it]];
       float sum = S.acc[p];
       for (uint32_t i = 0; i < mytotal[it] && b + i < static_cast<uint32_t>(kEntryCap); ++i)
-        sum = __fadd_rn(sum, S.staged_generic[b + i]);
+        sum = __fadd_rn(sum, S.staged[b + i]);
       S.acc[p] = sum;
     }
   }
   __syncthreads();
 }
 
-// Same accumulation for entries that live in registers: thread (worker wl, slot) holds up to kFastR
-// entries of its worker, p[r] = position in the tile or kNone.  S.cnt32 already counts every
-// entry (barrier passed).  Ends with a barrier.
-__device__ void accumulate_regs(TileLds& S, const uint32_t (&p)[kFastR], const float (&v)[kFastR], uint32_t wl,
-                                uint32_t nw) {
-  const uint32_t tid = threadIdx.x;
-  bool coll[kFastR];
-#pragma unroll
-  for (uint32_t r = 0; r < kFastR; ++r) {
-    coll[r] = false;
-    if (p[r] != kNone) {
-      if (hits_of(S, p[r]) == 1u) S.acc[p[r]] = __fadd_rn(S.acc[p[r]], v[r]);
-      else { coll[r] = true; atomicOr(&S.cb[p[r] >> 5], 1u << (p[r] & 31u)); }
-    }
-  }
-  __syncthreads();
-  uint32_t nq;
-  {
-    const uint32_t pc = tid < static_cast<uint32_t>(kTile / 32) ? static_cast<uint32_t>(__popc(S.cb[tid])) : 0u;
-    const uint32_t pex = block_excl_scan(pc, S.scan_lds, nq);
-    if (tid < static_cast<uint32_t>(kTile / 32)) S.cbpre[tid] = pex;
-  }
-  __syncthreads();
-  if (nq == 0u) return;
-  if (nq > static_cast<uint32_t>(kQMax)) {
-    // too many colliding positions for the mask table: add worker after worker
-    for (uint32_t w = 0; w < nw; ++w) {
-      if (wl == w) {
-#pragma unroll
-        for (uint32_t r = 0; r < kFastR; ++r)
-          if (coll[r]) S.acc[p[r]] = __fadd_rn(S.acc[p[r]], v[r]);
-      }
-      __syncthreads();
-    }
-    return;
-  }
-  for (uint32_t i = tid; i < nq * kMaskWords; i += kBlockThreads) S.masks[i] = 0u;
-  __syncthreads();
-  uint32_t q[kFastR];
-#pragma unroll
-  for (uint32_t r = 0; r < kFastR; ++r) {
-    q[r] = kNone;
-    if (coll[r]) {
-      const uint32_t word = S.cb[p[r] >> 5], bit = 1u << (p[r] & 31u);
-      q[r] = S.cbpre[p[r] >> 5] + static_cast<uint32_t>(__popc(word & (bit - 1u)));
-      atomicOr(&S.masks[q[r] * kMaskWords + (wl >> 5)], 1u << (wl & 31u));
-    }
-  }
-  __syncthreads();
-  uint32_t rank[kFastR], total[kFastR];
-#pragma unroll
-  for (uint32_t r = 0; r < kFastR; ++r) {
-    rank[r] = 0;
-    total[r] = 0;
-    if (coll[r]) {
-      worker_rank(S, q[r], wl, rank[r], total[r]);
-      if (rank[r] == 0u) S.qbase[q[r]] = atomicAdd(&S.sh_cursor, total[r]);
-    }
-  }
-  __syncthreads();
-#pragma unroll
-  for (uint32_t r = 0; r < kFastR; ++r) {
-    if (coll[r]) {
-      const uint32_t at = S.qbase[q[r]] + rank[r];
-      if (at < kStagedCap) S.staged[at] = v[r];
-    }
-  }
-  __syncthreads();
-#pragma unroll
-  for (uint32_t r = 0; r < kFastR; ++r) {
-    if (coll[r] && rank[r] == 0u) {
-      const uint32_t b = S.qbase[q[r]];
-      const uint32_t n = (b + total[r] <= kStagedCap) ? total[r] : (b < kStagedCap ? kStagedCap - b : 0u);
-      float sum = S.acc[p[r]];
-      uint32_t i = 0;
-      for (; i + 4u <= n; i += 4u) {          // loads first, then the dependent adds, in worker order
-        const float a0 = S.staged[b + i], a1 = S.staged[b + i + 1u], a2 = S.staged[b + i + 2u], a3 = S.staged[b + i + 3u];
-        sum = __fadd_rn(__fadd_rn(__fadd_rn(__fadd_rn(sum, a0), a1), a2), a3);
-      }
-      for (; i < n; ++i) sum = __fadd_rn(sum, S.staged[b + i]);
-      S.acc[p[r]] = sum;
-    }
-  }
-  __syncthreads();
-}
-
 // Write the finished tile once (scaled).  Followed by a barrier at the caller.
-__device__ __forceinline__ void write_tile(const TileLds& S, const TileGeom& g, float scale, uint32_t add_to_dst) {
+__device__ __forceinline__ void write_tile(const GenericLds& S, const TileGeom& g, float scale, uint32_t add_to_dst) {
   const uint32_t tid = threadIdx.x;
   const gptr<float> d = as_global(g.dense);
   const bool vec = ((reinterpret_cast<uintptr_t>(g.dense) & 15u) == 0u) && ((g.len & 3u) == 0u);
   if (vec) {
-    typedef float vf4 __attribute__((ext_vector_type(4)));
     const gptr<vf4> d4 = as_global(reinterpret_cast<vf4*>(g.dense));
     for (uint32_t i = tid; i < g.len / 4u; i += kBlockThreads) {
       vf4 o;
@@ -325,7 +264,7 @@ __device__ __forceinline__ void write_tile(const TileLds& S, const TileGeom& g, 
 // One tile, any number of workers, any number of entries: workers are taken in batches that fit
 // the staging buffers; every batch fetches its own offsets and entries (no prefetching).
 // S.acc must be cleared (barrier passed); ends with the tile accumulated in S.acc and a barrier.
-__device__ void tile_generic(const DecompressArgs& A, TileLds& S, const TileGeom& g) {
+__device__ void tile_generic(const DecompressArgs& A, GenericLds& S, const TileGeom& g) {
   const uint32_t tid = threadIdx.x;
   const uint32_t N = A.num_workers;
   uint32_t w0 = 0;
@@ -336,9 +275,9 @@ __device__ void tile_generic(const DecompressArgs& A, TileLds& S, const TileGeom
     const float* vp = nullptr;
     if (tid < nb) {
       const MsgDesc md = A.msgs[static_cast<size_t>(g.layer) * N + w0 + tid];
-      const uint32_t* row = A.tab + static_cast<size_t>(g.row) * N + w0 + tid;
+      const uint32_t* row = A.tab + static_cast<size_t>(w0 + tid) * A.tab_stride + g.row;
       s = row[0];
-      uint32_t e = row[N];
+      uint32_t e = row[1];
       if (e > md.count) e = md.count;     // the table never exceeds the message; stay in bounds anyway
       c = e > s ? e - s : 0u;
       ip = md.idx;
@@ -353,9 +292,9 @@ __device__ void tile_generic(const DecompressArgs& A, TileLds& S, const TileGeom
     const uint32_t nw = S.sh_end;
     if (nw == 0u) {
       // the first worker alone exceeds the staging capacity: its positions are unique, add directly
-      if (tid == 0) { S.w_start[0][0] = s; S.w_pref[0][0] = c; S.w_idx[0] = ip; S.w_val[0] = vp; }
+      if (tid == 0) { S.w_start[0] = s; S.w_pref[0] = c; S.w_idx[0] = ip; S.w_val[0] = vp; }
       __syncthreads();
-      const uint32_t s0 = S.w_start[0][0], c0 = S.w_pref[0][0];
+      const uint32_t s0 = S.w_start[0], c0 = S.w_pref[0];
       const gptr<const int32_t> ip0 = as_global(S.w_idx[0]);
       const gptr<const float> vp0 = as_global(S.w_val[0]);
       for (uint32_t j = tid; j < c0; j += kBlockThreads) {
@@ -366,8 +305,8 @@ __device__ void tile_generic(const DecompressArgs& A, TileLds& S, const TileGeom
       w0 += 1u;
       continue;
     }
-    if (tid < nw) { S.w_start[0][tid] = s; S.w_pref[0][tid] = ex; S.w_idx[tid] = ip; S.w_val[tid] = vp; }
-    if (tid == nw - 1u) { S.w_pref[0][nw] = ex + c; S.sh_entries = ex + c; }
+    if (tid < nw) { S.w_start[tid] = s; S.w_pref[tid] = ex; S.w_idx[tid] = ip; S.w_val[tid] = vp; }
+    if (tid == nw - 1u) { S.w_pref[nw] = ex + c; S.sh_entries = ex + c; }
     __syncthreads();
     const uint32_t E = S.sh_entries;
     if (E != 0u) {
@@ -384,9 +323,9 @@ __device__ void tile_generic(const DecompressArgs& A, TileLds& S, const TileGeom
           uint32_t lo = 0, hi = nw;
           while (hi - lo > 1u) {
             const uint32_t mid = (lo + hi) >> 1;
-            if (S.w_pref[0][mid] <= e) lo = mid; else hi = mid;
+            if (S.w_pref[mid] <= e) lo = mid; else hi = mid;
           }
-          const uint32_t j = S.w_start[0][lo] + (e - S.w_pref[0][lo]);
+          const uint32_t j = S.w_start[lo] + (e - S.w_pref[lo]);
           lo_[it] = lo;
           idx_[it] = static_cast<uint32_t>(as_global(S.w_idx[lo])[j]);
           val_[it] = as_global(S.w_val[lo])[j];
@@ -407,10 +346,41 @@ __device__ void tile_generic(const DecompressArgs& A, TileLds& S, const TileGeom
         }
       }
       __syncthreads();
-      accumulate_staged(S, E, nw, S.w_pref[0]);
+      accumulate_staged(S, E, nw, S.w_pref);
     }
     w0 += nw;
     __syncthreads();
+  }
+}
+
+// =================================================================== fast tiles
+constexpr uint32_t kFastShift = 9;
+constexpr uint32_t kFastThreads = 1u << kFastShift;   // 8 waves per tile
+constexpr uint32_t kFastR = 4;                  // entries a thread keeps in registers per tile
+constexpr uint32_t kStagedCap = 2048;           // entries on positions hit more than once, with padding
+constexpr uint32_t kRunPad = 8;                 // run lengths are rounded up to this
+
+// seen / cb / masks exist twice: tile i uses set i & 1 while the other set is being cleared.
+struct alignas(16) FastLds {
+  float acc[kTile];                          // the tile; all zero between tiles
+  uint32_t seen[2][kWords];                  // positions hit at all
+  uint32_t cb[2][kWords];                    // positions hit more than once
+  uint32_t masks[2][kQMax * kMaskWords];     // per colliding position: which workers hit it
+  uint32_t pre_cb[kWords];                   // exclusive popcount prefix of cb
+  uint32_t qbase[kQMax + 4];                 // first staged value of every colliding position, +1 closing
+  uint16_t run_p[kQMax];                     // the position a run belongs to
+  float staged[kStagedCap];                  // colliding values in worker order, one run per position
+};
+static_assert(sizeof(FastLds) <= 40960 - 256, "four 8-wave workgroups per CU need <= 40 KB of LDS each");
+static_assert(kWords == 2 * kWaveSize && kQMax == 2 * kWaveSize, "one wave scans the maps, two words per lane");
+
+// per entry, packed into one register: position | colliding position << 12 | colliding << 31
+constexpr uint32_t kPkColl = 0x80000000u;
+
+__device__ __forceinline__ void push_generic(const DecompressArgs& A, uint32_t tile_id) {
+  if (threadIdx.x == 0) {
+    const uint32_t at = atomicAdd(A.gen_count, 1u);
+    if (at < A.num_tiles) A.gen_list[at] = tile_id;
   }
 }
 
@@ -424,10 +394,10 @@ __global__ void __launch_bounds__(kBlockThreads) decompress_table_kernel(Decompr
   const uint32_t layer = bd.msg / N, w = bd.msg % N;
   const DecompressLayer L = A.layers[layer];
   const uint32_t ntiles = L.tiles;
-  uint32_t* col = A.tab + static_cast<size_t>(L.row_base) * N + w;   // col[t * N] = first entry of tile t
+  const gptr<uint32_t> col = as_global(A.tab + static_cast<size_t>(w) * A.tab_stride + L.row_base);   // col[t] = first entry of tile t
   const gptr<const int32_t> midx = as_global(md.idx);
   if (md.count == 0u) {
-    for (uint32_t t = threadIdx.x; t <= ntiles; t += kBlockThreads) col[static_cast<size_t>(t) * N] = 0u;
+    for (uint32_t t = threadIdx.x; t <= ntiles; t += kBlockThreads) col[t] = 0u;
     return;
   }
   const uint32_t stop = (md.count - bd.first) < kTableBlockEntries ? md.count : bd.first + kTableBlockEntries;
@@ -440,74 +410,47 @@ __global__ void __launch_bounds__(kBlockThreads) decompress_table_kernel(Decompr
       if (prev >= ntiles) prev = ntiles - 1u;
       first = prev + 1u;
     }
-    for (uint32_t t = first; t <= cur; ++t) col[static_cast<size_t>(t) * N] = j;
+    for (uint32_t t = first; t <= cur; ++t) col[t] = j;
     if (j == md.count - 1u)
-      for (uint32_t t = cur + 1u; t <= ntiles; ++t) col[static_cast<size_t>(t) * N] = md.count;
+      for (uint32_t t = cur + 1u; t <= ntiles; ++t) col[t] = md.count;
   }
 }
 
-// ------------------------------------------------------------------ tile accumulation
-__global__ void __launch_bounds__(kBlockThreads) decompress_tiles_kernel(DecompressArgs A) {
-  __shared__ TileLds S;
-  const uint32_t tid = threadIdx.x;
-  const uint32_t N = A.num_workers;
-  // Workgroups are dealt to the 8 XCDs round-robin by index.  Every XCD gets one contiguous
-  // range of tiles, and the workgroups of an XCD take its tiles round-robin, so at any moment
-  // they work on neighbouring tiles: one 128-byte line of a message holds the entries of about
-  // 8 tiles, is fetched from HBM once and is then found in that XCD's L2 by the 7 other
-  // workgroups that need it (a blocked assignment makes the concurrent working set of an XCD
-  // as large as its L2 and fetches every line 8 times).
+// ------------------------------------------------------------------ tile accumulation, fast path
+__global__ void __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(6, 6)))
+decompress_tiles_kernel(DecompressArgs A) {
+  __shared__ FastLds S;
+  const uint32_t tid = threadIdx.x, lane = tid & 63u;
+  const uint32_t N = A.num_workers;                    // 1 .. kBatchWorkers (the host checks)
   uint32_t t_first, t_last, stride;
-  {
-    const uint32_t xcd = blockIdx.x & 7u, slot = blockIdx.x >> 3, slots = gridDim.x >> 3;
-    const uint32_t per_xcd = (A.num_tiles + 7u) >> 3;
-    const uint32_t x0 = xcd * per_xcd < A.num_tiles ? xcd * per_xcd : A.num_tiles;
-    const uint32_t x1 = x0 + per_xcd < A.num_tiles ? x0 + per_xcd : A.num_tiles;
-    if (A.debug & 8u) {          // blocked: a contiguous piece per workgroup
-      const uint32_t per_slot = (x1 - x0 + slots - 1u) / slots;
-      t_first = x0 + slot * per_slot < x1 ? x0 + slot * per_slot : x1;
-      t_last = t_first + per_slot < x1 ? t_first + per_slot : x1;
-      stride = 1u;
-    } else {
-      t_first = x0 + slot < x1 ? x0 + slot : x1;
-      t_last = x1;
-      stride = slots;
-    }
-  }
-  const bool pipelined = N >= 1u && N <= static_cast<uint32_t>(kBatchWorkers);
-  // threads per worker on the pipelined path: 256 / (N rounded up to a power of two), >= 2
+  tiles_of_workgroup(A.num_tiles, t_first, t_last, stride);
+  // The threads of a worker are neighbouring lanes of one wave (at most all 64): the 16-byte
+  // pieces they load from the worker's message are adjacent, so the wave's load touches a line
+  // or two per worker instead of one per lane.
   uint32_t tpw_shift = 1;
-  while (tpw_shift < 8u && (N << (tpw_shift + 1u)) <= static_cast<uint32_t>(kBlockThreads)) ++tpw_shift;
+  while (tpw_shift < 6u && (N << (tpw_shift + 1u)) <= kFastThreads) ++tpw_shift;
   const uint32_t tpw = 1u << tpw_shift;
+  const uint32_t wl = tid >> tpw_shift;
+  const uint32_t part = tid & (tpw - 1u);
+  const bool has_worker = wl < N;
+  const int lead_lane4 = static_cast<int>((lane & ~(tpw - 1u)) * 4u);   // the worker's first lane, as a byte address for ds_bpermute
+  for (uint32_t i = tid; i < static_cast<uint32_t>(kTile); i += kFastThreads) S.acc[i] = 0.0f;
+  for (uint32_t i = tid; i < 2u * kWords; i += kFastThreads) { (&S.seen[0][0])[i] = 0u; (&S.cb[0][0])[i] = 0u; }
+  for (uint32_t i = tid; i < 2u * kQMax * kMaskWords; i += kFastThreads) (&S.masks[0][0])[i] = 0u;
+  __syncthreads();
+  uint32_t par = 0;                                    // which set of maps the current tile uses
 
   uint32_t tile_id = t_first;
   while (tile_id < t_last) {
-    // ---- a run of consecutive tiles of one layer
+    // ---- a run of this workgroup's tiles inside one layer
     const uint32_t layer = layer_of_tile(A, tile_id);
     const DecompressLayer L = A.layers[layer];
     const uint32_t run_end = (L.tile_base + L.tiles) < t_last ? (L.tile_base + L.tiles) : t_last;
 
-    if (!pipelined) {
-      for (; tile_id < run_end; tile_id += stride) {
-        const TileGeom g = tile_geom(L, layer, tile_id);
-        clear_tile(S);
-        __syncthreads();
-        tile_generic(A, S, g);
-        write_tile(S, g, A.scale, A.add_to_dst);
-        __syncthreads();
-      }
-      continue;
-    }
-
-    // ---- pipelined run.  Thread (worker wl, part) owns, of its worker's entries inside a tile,
-    // the groups of four consecutive entries number part, part + T, ... (T threads per worker),
-    // kFastR entries at most, fetched with one 16-byte load per group and array: an L1 lookup
-    // costs the same for 4 bytes as for 16, and one-entry gathers made this kernel bound by
-    // them.  A tile where some worker has more entries takes the unpipelined path.  The
-    // entries stay in registers from the prefetch to the end of their tile.
-    const uint32_t wl = tid & ((static_cast<uint32_t>(kBlockThreads) >> tpw_shift) - 1u);
-    const uint32_t part = tid >> (8u - tpw_shift);
-    const bool has_worker = wl < N;
+    // Thread (worker wl, part) owns, of its worker's entries inside a tile, the groups of four
+    // consecutive entries number part, part + T, ... (T threads per worker), kFastR entries at
+    // most, fetched with one 16-byte load per group and array.  They are loaded into registers
+    // while the previous tile is being finished and stay there.
     uint32_t my_count = 0;
     gptr<const int32_t> my_idx = nullptr;
     gptr<const float> my_val = nullptr;
@@ -517,101 +460,256 @@ __global__ void __launch_bounds__(kBlockThreads) decompress_tiles_kernel(Decompr
       my_val = as_global(md.val);
       my_count = md.count;
     }
-    const uint32_t* tabw = A.tab + (has_worker ? wl : 0u);
-    auto row_at = [&](uint32_t row) -> uint32_t {
-      if (!has_worker) return 0u;
-      const uint32_t v = tabw[static_cast<size_t>(row) * N];
-      return v < my_count ? v : my_count;        // the table never exceeds the message; stay in bounds anyway
-    };
+    const gptr<const uint32_t> tabw = as_global(A.tab + static_cast<size_t>(has_worker ? wl : 0u) * A.tab_stride);
     const uint32_t row0 = L.row_base + (tile_id - L.tile_base);
-    uint32_t r_start = row_at(row0);             // entry range of the tile being prefetched
-    uint32_t r_end = row_at(row0 + 1u);
+    uint32_t r_start = 0, r_end = 0;             // entry range of the tile being fetched
     uint32_t r_start2 = 0, r_end2 = 0;           // entry range of this workgroup's tile after it
-    if (tile_id + stride < run_end) {
-      r_start2 = row_at(row0 + stride);
-      r_end2 = row_at(row0 + stride + 1u);
-    }
+    // a worker's first lane reads the table for all of them
+    auto table_at = [&](uint32_t row, uint32_t& first, uint32_t& last) {
+      uint32_t a = 0, b = 0;
+      if (has_worker && part == 0u) { a = tabw[row]; b = tabw[row + 1u]; }
+      first = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(lead_lane4, static_cast<int>(a)));
+      last = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(lead_lane4, static_cast<int>(b)));
+    };
+    table_at(row0, r_start, r_end);
+    if (tile_id + stride < run_end) table_at(row0 + stride, r_start2, r_end2);
 
-    uint32_t nx_idx[kFastR];
-    float nx_val[kFastR];
-    uint32_t nx_cnt = 0;                         // how many of them exist (this thread)
-    bool nx_generic = false;
+    uint32_t e_idx[kFastR];                      // index as loaded, then the packed word
+    float e_val[kFastR];
+    uint32_t e_cnt = 0;                          // how many of them exist (this thread)
+    bool e_over = false;                         // the worker has more entries here than its threads hold
     typedef uint32_t vu4 __attribute__((ext_vector_type(4), aligned(4)));
     typedef float vf4u __attribute__((ext_vector_type(4), aligned(4)));
-    auto prefetch = [&]() {
-      const uint32_t c = r_end > r_start ? r_end - r_start : 0u;
-      nx_generic = __syncthreads_or(c > tpw * kFastR ? 1 : 0) != 0;
-      nx_cnt = 0;
+    auto fetch = [&]() {
+      const uint32_t e1 = r_end < my_count ? r_end : my_count;   // the table never exceeds the message; stay in bounds anyway
+      const uint32_t c = e1 > r_start ? e1 - r_start : 0u;
+      e_over = c > tpw * kFastR;
+      e_cnt = 0;
 #pragma unroll
       for (uint32_t r = 0; r < kFastR / 4u; ++r) {
         const uint32_t off = 4u * (part + r * tpw);          // first entry of this group inside the tile
 #pragma unroll
-        for (uint32_t j = 0; j < 4u; ++j) { nx_idx[4u * r + j] = 0; nx_val[4u * r + j] = 0.0f; }
-        if (!nx_generic && off < c) {
+        for (uint32_t j = 0; j < 4u; ++j) { e_idx[4u * r + j] = 0; e_val[4u * r + j] = 0.0f; }
+        if (!e_over && off < c) {
           const uint32_t at = r_start + off;
           const uint32_t have = (c - off) < 4u ? (c - off) : 4u;
           if (at + 4u <= my_count) {                         // the 16-byte load stays inside the message
             const vu4 qi = *reinterpret_cast<gptr<const vu4>>(my_idx + at);
             const vf4u qv = *reinterpret_cast<gptr<const vf4u>>(my_val + at);
-            nx_idx[4u * r + 0] = qi.x; nx_idx[4u * r + 1] = qi.y; nx_idx[4u * r + 2] = qi.z; nx_idx[4u * r + 3] = qi.w;
-            nx_val[4u * r + 0] = qv.x; nx_val[4u * r + 1] = qv.y; nx_val[4u * r + 2] = qv.z; nx_val[4u * r + 3] = qv.w;
+            e_idx[4u * r + 0] = qi.x; e_idx[4u * r + 1] = qi.y; e_idx[4u * r + 2] = qi.z; e_idx[4u * r + 3] = qi.w;
+            e_val[4u * r + 0] = qv.x; e_val[4u * r + 1] = qv.y; e_val[4u * r + 2] = qv.z; e_val[4u * r + 3] = qv.w;
           } else {
 #pragma unroll
             for (uint32_t j = 0; j < 4u; ++j) {
               if (j < have) {
-                nx_idx[4u * r + j] = static_cast<uint32_t>(my_idx[at + j]);
-                nx_val[4u * r + j] = my_val[at + j];
+                e_idx[4u * r + j] = static_cast<uint32_t>(my_idx[at + j]);
+                e_val[4u * r + j] = my_val[at + j];
               }
             }
           }
-          nx_cnt = 4u * r + have;
+          e_cnt = 4u * r + have;
         }
       }
     };
-    prefetch();
+    // Start fetching this workgroup's next tile of the run (and the table entries of the one after).
+    auto fetch_next = [&](uint32_t cur_tile) {
+      if (cur_tile + stride < run_end) {
+        r_start = r_start2;
+        r_end = r_end2;
+        if (cur_tile + 2u * stride < run_end)
+          table_at(L.row_base + (cur_tile - L.tile_base) + 2u * stride, r_start2, r_end2);
+        fetch();
+      }
+    };
+    fetch();
 
-    for (; tile_id < run_end; tile_id += stride) {
+    for (; tile_id < run_end; tile_id += stride, par ^= 1u) {
       const TileGeom g = tile_geom(L, layer, tile_id);
-      const bool generic = nx_generic;
-      clear_tile(S);
-      clear_batch(S);
-      __syncthreads();
-      // ---- this tile's entries were prefetched during the previous tile: count the hits
-      uint32_t cur_p[kFastR];
-      float cur_v[kFastR];
+      uint32_t* const seen = S.seen[par];
+      uint32_t* const cb = S.cb[par];
+      uint32_t* const masks = S.masks[par];
+      // ---- mark the positions hit, and those hit again
 #pragma unroll
       for (uint32_t r = 0; r < kFastR; ++r) {
-        cur_p[r] = kNone;
-        cur_v[r] = nx_val[r];
-        if (!generic && r < nx_cnt) {
-          const uint32_t p = nx_idx[r] - g.first;
+        uint32_t pk = kNone;
+        if (r < e_cnt) {
+          const uint32_t p = e_idx[r] - g.first;
           if (p < g.len) {
-            cur_p[r] = p;
-            atomicAdd(&S.cnt32[p >> 2], 1u << ((p & 3u) * 8u));
+            pk = p;
+            const uint32_t bit = 1u << (p & 31u);
+            if (atomicOr(&seen[p >> 5], bit) & bit) atomicOr(&cb[p >> 5], bit);
+          }
+        }
+        e_idx[r] = pk;
+      }
+      const bool over = __syncthreads_or(e_over ? 1 : 0) != 0;
+      // ---- clear the maps the previous tile used
+      if (tid < kWords) { S.seen[par ^ 1u][tid] = 0u; S.cb[par ^ 1u][tid] = 0u; }
+      for (uint32_t i = tid; i < kQMax * kMaskWords; i += kFastThreads) S.masks[par ^ 1u][i] = 0u;
+      // the runs of colliding values are padded with +0 to whole groups of kRunPad
+      for (uint32_t i = tid; i < kStagedCap / 4u; i += kFastThreads) reinterpret_cast<vf4*>(S.staged)[i] = vf4{0.0f, 0.0f, 0.0f, 0.0f};
+      // ---- dense numbering of the colliding positions; every wave computes the same prefix and
+      // writes it (identical values), so it may read it back at once
+      uint32_t nq;
+      {
+        const vu2l cw = *reinterpret_cast<const vu2l*>(&cb[2u * lane]);
+        const uint32_t c0 = static_cast<uint32_t>(__popc(cw.x)), c1 = static_cast<uint32_t>(__popc(cw.y));
+        const uint32_t incl = wave_incl_scan(c0 + c1);
+        nq = wave_total(incl);
+        *reinterpret_cast<vu2l*>(&S.pre_cb[2u * lane]) = vu2l{incl - c0 - c1, incl - c1};
+      }
+      if (over || nq > static_cast<uint32_t>(kQMax)) {
+        push_generic(A, tile_id);
+        fetch_next(tile_id);
+        __syncthreads();                         // the clears above end before the next tile marks
+        continue;
+      }
+      // ---- positions hit once are final; the others collect the set of their workers
+#pragma unroll
+      for (uint32_t r = 0; r < kFastR; ++r) {
+        if (e_idx[r] != kNone) {
+          const uint32_t p = e_idx[r], w = p >> 5, sh = p & 31u;
+          const uint32_t cword = nq != 0u ? cb[w] : 0u;
+          if (!((cword >> sh) & 1u)) {
+            S.acc[p] = __fadd_rn(0.0f, e_val[r]);
+          } else {
+            const uint32_t q = S.pre_cb[w] + static_cast<uint32_t>(__popc(cword & ((1u << sh) - 1u)));
+            e_idx[r] = p | (q << 12) | kPkColl;
+            atomicOr(&masks[q * kMaskWords + (wl >> 5)], 1u << (wl & 31u));
           }
         }
       }
       __syncthreads();
-      // ---- start fetching the next tile of the run
-      if (tile_id + stride < run_end) {
-        r_start = r_start2;
-        r_end = r_end2;
-        if (tile_id + 2u * stride < run_end) {
-          const uint32_t row2 = L.row_base + (tile_id - L.tile_base) + 2u * stride;
-          r_start2 = row_at(row2);
-          r_end2 = row_at(row2 + 1u);
+      if (nq != 0u) {
+        // ---- runs of staged values, one per colliding position, in position order
+        uint32_t staged_total;
+        {
+          const vu4l m0 = *reinterpret_cast<const vu4l*>(&masks[(2u * lane) * kMaskWords]);
+          const vu4l m1 = *reinterpret_cast<const vu4l*>(&masks[(2u * lane + 1u) * kMaskWords]);
+          const uint32_t t0 = (static_cast<uint32_t>(__popc(m0.x) + __popc(m0.y) + __popc(m0.z) + __popc(m0.w)) + kRunPad - 1u) & ~(kRunPad - 1u);
+          const uint32_t t1 = (static_cast<uint32_t>(__popc(m1.x) + __popc(m1.y) + __popc(m1.z) + __popc(m1.w)) + kRunPad - 1u) & ~(kRunPad - 1u);
+          const uint32_t incl = wave_incl_scan(t0 + t1);
+          staged_total = wave_total(incl);
+          *reinterpret_cast<vu2l*>(&S.qbase[2u * lane]) = vu2l{incl - t0 - t1, incl - t1};
+          if (lane == 63u) S.qbase[kQMax] = incl;
         }
-        if (!(A.debug & 2u)) prefetch();
+        // the workers below this thread's, as a mask over the words of a position's worker set
+        vu4l lt;
+        {
+          const uint32_t part_bits = (1u << (wl & 31u)) - 1u, ww = wl >> 5;
+          lt.x = ww > 0u ? ~0u : part_bits;
+          lt.y = ww > 1u ? ~0u : (ww == 1u ? part_bits : 0u);
+          lt.z = ww > 2u ? ~0u : (ww == 2u ? part_bits : 0u);
+          lt.w = ww == 3u ? part_bits : 0u;
+        }
+        if (staged_total > kStagedCap) {
+          // undo the single hits: the tile's accumulator has to be all zero again
+#pragma unroll
+          for (uint32_t r = 0; r < kFastR; ++r)
+            if (e_idx[r] != kNone && !(e_idx[r] & kPkColl)) S.acc[e_idx[r]] = 0.0f;
+          push_generic(A, tile_id);
+          fetch_next(tile_id);
+          __syncthreads();
+          continue;
+        }
+#pragma unroll
+        for (uint32_t r = 0; r < kFastR; ++r) {
+          if (e_idx[r] != kNone && (e_idx[r] & kPkColl)) {
+            const uint32_t q = (e_idx[r] >> 12) & 0x7Fu;
+            const vu4l m = *reinterpret_cast<const vu4l*>(&masks[q * kMaskWords]);
+            const uint32_t rank = static_cast<uint32_t>(__popc(m.x & lt.x) + __popc(m.y & lt.y) + __popc(m.z & lt.z) + __popc(m.w & lt.w));
+            S.staged[S.qbase[q] + rank] = e_val[r];
+            if (rank == 0u) S.run_p[q] = static_cast<uint16_t>(e_idx[r] & 0xFFFu);
+          }
+        }
+        __syncthreads();
       }
-      // ---- accumulate and write this tile
-      if (generic) {
-        tile_generic(A, S, g);                   // some worker has too many entries here: unpipelined
-      } else if (!(A.debug & 1u)) {
-        accumulate_regs(S, cur_p, cur_v, wl, N);
+      // the entries are used up: their registers take the next tile's
+      fetch_next(tile_id);
+      if (nq != 0u) {
+        // ---- one lane per colliding position adds its run in worker order; the padding adds +0,
+        // which leaves every partial sum as it is (a partial sum is never -0)
+        if (tid < nq) {
+          const uint32_t g0 = S.qbase[tid] / 4u, g1 = S.qbase[tid + 1u] / 4u;   // groups of four values
+          const vf4* const s4 = reinterpret_cast<const vf4*>(S.staged);
+          float sum = 0.0f;
+          for (uint32_t gi = g0; gi < g1; gi += 4u) {   // loads first, then the dependent adds
+            const vf4 x0 = s4[gi], x1 = s4[gi + 1u];
+            vf4 x2 = vf4{0.0f, 0.0f, 0.0f, 0.0f}, x3 = x2;
+            if (gi + 2u < g1) { x2 = s4[gi + 2u]; x3 = s4[gi + 3u]; }
+            sum = __fadd_rn(__fadd_rn(__fadd_rn(__fadd_rn(sum, x0.x), x0.y), x0.z), x0.w);
+            sum = __fadd_rn(__fadd_rn(__fadd_rn(__fadd_rn(sum, x1.x), x1.y), x1.z), x1.w);
+            sum = __fadd_rn(__fadd_rn(__fadd_rn(__fadd_rn(sum, x2.x), x2.y), x2.z), x2.w);
+            sum = __fadd_rn(__fadd_rn(__fadd_rn(__fadd_rn(sum, x3.x), x3.y), x3.z), x3.w);
+          }
+          S.acc[S.run_p[tid]] = sum;
+        }
+        __syncthreads();
       }
-      if (!(A.debug & 4u)) write_tile(S, g, A.scale, A.add_to_dst);
-      __syncthreads();
+      // ---- write the tile (scaled) and leave its accumulator cleared
+      const bool vec = ((reinterpret_cast<uintptr_t>(g.dense) & 15u) == 0u) && ((g.len & 3u) == 0u);
+      if (vec) {
+        const gptr<vf4> d4 = as_global(reinterpret_cast<vf4*>(g.dense));
+        vf4* const acc4 = reinterpret_cast<vf4*>(S.acc);
+#pragma unroll
+        for (uint32_t j = 0; j < static_cast<uint32_t>(kTile) / (4u * kFastThreads); ++j) {
+          const uint32_t i4 = tid + j * kFastThreads;
+          if (4u * i4 < g.len) {
+            const vf4 a = acc4[i4];
+            acc4[i4] = vf4{0.0f, 0.0f, 0.0f, 0.0f};
+            vf4 o;
+            o.x = __fmul_rn(a.x, A.scale); o.y = __fmul_rn(a.y, A.scale);
+            o.z = __fmul_rn(a.z, A.scale); o.w = __fmul_rn(a.w, A.scale);
+            if (A.add_to_dst) {
+              const vf4 old = d4[i4];
+              o.x = __fadd_rn(old.x, o.x); o.y = __fadd_rn(old.y, o.y);
+              o.z = __fadd_rn(old.z, o.z); o.w = __fadd_rn(old.w, o.w);
+            }
+            d4[i4] = o;
+          }
+        }
+      } else {
+        const gptr<float> d = as_global(g.dense);
+        for (uint32_t i = tid; i < g.len; i += kFastThreads) {
+          float o = __fmul_rn(S.acc[i], A.scale);
+          S.acc[i] = 0.0f;
+          if (A.add_to_dst) o = __fadd_rn(d[i], o);
+          d[i] = o;
+        }
+      }
+      // no barrier here: the next tile marks in the other set of maps, and writes nothing that
+      // the threads still busy with this tile read before the barrier that follows the marking
     }
+  }
+}
+
+// ------------------------------------------------------------------ tile accumulation, generic path
+// all_tiles != 0: every tile (the fast kernel did not run); else the tiles the fast kernel listed.
+__global__ void __launch_bounds__(kBlockThreads) decompress_generic_kernel(DecompressArgs A, uint32_t all_tiles) {
+  __shared__ GenericLds S;
+  auto one_tile = [&](uint32_t tile_id) {
+    const uint32_t layer = layer_of_tile(A, tile_id);
+    const TileGeom g = tile_geom(A.layers[layer], layer, tile_id);
+    clear_tile(S);
+    __syncthreads();
+    tile_generic(A, S, g);
+    write_tile(S, g, A.scale, A.add_to_dst);
+    __syncthreads();
+  };
+  if (all_tiles) {
+    uint32_t t_first, t_last, stride;
+    tiles_of_workgroup(A.num_tiles, t_first, t_last, stride);
+    for (uint32_t t = t_first; t < t_last; t += stride) one_tile(t);
+    return;
+  }
+  uint32_t count = ld_agent(A.gen_count);
+  if (count > A.num_tiles) count = A.num_tiles;
+  for (uint32_t i = blockIdx.x; i < count; i += gridDim.x) one_tile(A.gen_list[i]);
+  // the last workgroup to get here empties the list for the next call
+  __syncthreads();
+  if (threadIdx.x == 0 && atomicAdd(A.gen_done, 1u) + 1u == gridDim.x) {
+    st_agent(A.gen_count, 0u);
+    st_agent(A.gen_done, 0u);
   }
 }
 
@@ -621,12 +719,41 @@ hipError_t launch_decompress_table(const DecompressArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+// Persistent grids: as many workgroups as fit on the device at once, a multiple of 8 so that
+// every XCD gets its share.  cus = compute units of the current device.
+static uint32_t resident_grid(const void* kernel, uint32_t threads, uint32_t cus) {
+  int per_cu = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, static_cast<int>(threads), 0) != hipSuccess || per_cu < 1) {
+    (void)hipGetLastError();
+    per_cu = 1;
+  }
+  const uint32_t g = (static_cast<uint32_t>(per_cu) * cus / 8u) * 8u;
+  return g < 8u ? 8u : g;
+}
+
 hipError_t launch_decompress_tiles(const DecompressArgs& a, hipStream_t s) {
   if (a.num_tiles == 0) return hipSuccess;
-  // persistent: at most 4 workgroups per CU (LDS), a multiple of 8 so that every XCD gets its share
-  uint32_t grid = ((a.num_tiles + 7u) / 8u) * 8u;
-  if (grid > a.max_grid) grid = a.max_grid;
-  hipLaunchKernelGGL(decompress_tiles_kernel, dim3(grid), dim3(kBlockThreads), 0, s, a);
+  static uint32_t per_cu_fast = 0, per_cu_generic = 0;   // workgroups per CU; a property of the code object
+  if (per_cu_fast == 0) {
+    per_cu_fast = resident_grid(reinterpret_cast<const void*>(decompress_tiles_kernel), kFastThreads, 8u) / 8u;
+    per_cu_generic = resident_grid(reinterpret_cast<const void*>(decompress_generic_kernel), kBlockThreads, 8u) / 8u;
+  }
+  const uint32_t want = ((a.num_tiles + 7u) / 8u) * 8u;
+  const uint32_t cus8 = a.cus < 8u ? 8u : (a.cus / 8u) * 8u;
+  if (a.num_workers >= 1u && a.num_workers <= static_cast<uint32_t>(kBatchWorkers)) {
+    const uint32_t cap = per_cu_fast * cus8;
+    const uint32_t grid = want < cap ? want : cap;
+    hipLaunchKernelGGL(decompress_tiles_kernel, dim3(grid), dim3(kFastThreads), 0, s, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    // the listed tiles are few: a small grid keeps the launch cheap when the list is empty
+    const uint32_t ggrid = want < cus8 ? want : cus8;
+    hipLaunchKernelGGL(decompress_generic_kernel, dim3(ggrid), dim3(kBlockThreads), 0, s, a, 0u);
+    return hipGetLastError();
+  }
+  const uint32_t cap = per_cu_generic * cus8;
+  const uint32_t grid = want < cap ? want : cap;
+  hipLaunchKernelGGL(decompress_generic_kernel, dim3(grid), dim3(kBlockThreads), 0, s, a, 1u);
   return hipGetLastError();
 }
 

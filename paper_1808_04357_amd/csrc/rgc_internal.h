@@ -105,7 +105,7 @@ struct CompressArgs {
 // ---------------------------------------------------------------- decompress
 constexpr int kTileShift = 12;
 constexpr int kTile = 1 << kTileShift;            // dense positions owned by one workgroup
-constexpr int kEntryCap = 1024;                   // entries staged per worker batch
+constexpr int kEntryCap = 1024;                   // entries staged per worker batch (generic tiles)
 constexpr int kBatchWorkers = 128;                // workers per batch (mask of 4 words)
 constexpr int kMaskWords = kBatchWorkers / 32;
 constexpr int kQMax = 128;                        // positions hit more than once per batch
@@ -135,16 +135,18 @@ struct DecompressArgs {
   const MsgDesc* msgs;        // [layers][workers]
   const DecompressLayer* layers;
   const BlockDesc* blocks;
-  uint32_t* tab;              // [tab_stride rows][workers]: first entry of each tile; one closing row per layer
+  uint32_t* tab;              // [workers][tab_stride]: first entry of each tile; one closing entry per layer
+  uint32_t* gen_list;         // [num_tiles] tiles left to the generic kernel by the fast one
+  uint32_t* gen_count;        // how many; zero between calls
+  uint32_t* gen_done;         // workgroups of the generic kernel that are through; zero between calls
   uint32_t tab_stride;
-  uint32_t max_grid;          // persistent grid of the tile kernel (multiple of 8)
+  uint32_t cus;               // compute units of the device (sizes the persistent grids)
   uint32_t num_workers;
   uint32_t num_layers;
   uint32_t num_tiles;
   uint32_t num_blocks;
   uint32_t add_to_dst;
   float scale;
-  uint32_t debug;             // experiment switches (RGC_DEBUG), 0 in normal use
 };
 
 // kernel launchers (defined in the .hip files)
