@@ -370,6 +370,7 @@ struct alignas(16) FastLds {
   uint32_t qbase[kQMax + 4];                 // first staged value of every colliding position, +1 closing
   uint16_t run_p[kQMax];                     // the position a run belongs to
   float staged[kStagedCap];                  // colliding values in worker order, one run per position
+  uint32_t over[2];                          // some worker has more entries in the tile than its threads hold
 };
 static_assert(sizeof(FastLds) <= 40960 - 256, "four 8-wave workgroups per CU need <= 40 KB of LDS each");
 static_assert(kWords == 2 * kWaveSize && kQMax == 2 * kWaveSize, "one wave scans the maps, two words per lane");
@@ -437,6 +438,7 @@ decompress_tiles_kernel(DecompressArgs A) {
   for (uint32_t i = tid; i < static_cast<uint32_t>(kTile); i += kFastThreads) S.acc[i] = 0.0f;
   for (uint32_t i = tid; i < 2u * kWords; i += kFastThreads) { (&S.seen[0][0])[i] = 0u; (&S.cb[0][0])[i] = 0u; }
   for (uint32_t i = tid; i < 2u * kQMax * kMaskWords; i += kFastThreads) (&S.masks[0][0])[i] = 0u;
+  if (tid < 2u) S.over[tid] = 0u;
   __syncthreads();
   uint32_t par = 0;                                    // which set of maps the current tile uses
 
@@ -460,14 +462,15 @@ decompress_tiles_kernel(DecompressArgs A) {
       my_val = as_global(md.val);
       my_count = md.count;
     }
-    const gptr<const uint32_t> tabw = as_global(A.tab + static_cast<size_t>(has_worker ? wl : 0u) * A.tab_stride);
+    const gptr<const uint32_t> tab = as_global(A.tab);
+    const uint32_t tab_w = (has_worker ? wl : 0u) * A.tab_stride;   // the host keeps the table below 2^32 words
     const uint32_t row0 = L.row_base + (tile_id - L.tile_base);
     uint32_t r_start = 0, r_end = 0;             // entry range of the tile being fetched
     uint32_t r_start2 = 0, r_end2 = 0;           // entry range of this workgroup's tile after it
     // a worker's first lane reads the table for all of them
     auto table_at = [&](uint32_t row, uint32_t& first, uint32_t& last) {
       uint32_t a = 0, b = 0;
-      if (has_worker && part == 0u) { a = tabw[row]; b = tabw[row + 1u]; }
+      if (has_worker && part == 0u) { a = tab[tab_w + row]; b = tab[tab_w + row + 1u]; }
       first = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(lead_lane4, static_cast<int>(a)));
       last = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(lead_lane4, static_cast<int>(b)));
     };
@@ -542,8 +545,11 @@ decompress_tiles_kernel(DecompressArgs A) {
         }
         e_idx[r] = pk;
       }
-      const bool over = __syncthreads_or(e_over ? 1 : 0) != 0;
+      if (e_over) S.over[par] = 1u;
+      __syncthreads();
+      const bool over = S.over[par] != 0u;
       // ---- clear the maps the previous tile used
+      if (tid == 0u) S.over[par ^ 1u] = 0u;
       if (tid < kWords) { S.seen[par ^ 1u][tid] = 0u; S.cb[par ^ 1u][tid] = 0u; }
       for (uint32_t i = tid; i < kQMax * kMaskWords; i += kFastThreads) S.masks[par ^ 1u][i] = 0u;
       // the runs of colliding values are padded with +0 to whole groups of kRunPad
@@ -630,17 +636,21 @@ decompress_tiles_kernel(DecompressArgs A) {
         // ---- one lane per colliding position adds its run in worker order; the padding adds +0,
         // which leaves every partial sum as it is (a partial sum is never -0)
         if (tid < nq) {
-          const uint32_t g0 = S.qbase[tid] / 4u, g1 = S.qbase[tid + 1u] / 4u;   // groups of four values
+          const uint32_t g1 = S.qbase[tid + 1u] / 4u;     // in groups of four values
+          uint32_t gi = S.qbase[tid] / 4u;
           const vf4* const s4 = reinterpret_cast<const vf4*>(S.staged);
           float sum = 0.0f;
-          for (uint32_t gi = g0; gi < g1; gi += 4u) {   // loads first, then the dependent adds
-            const vf4 x0 = s4[gi], x1 = s4[gi + 1u];
-            vf4 x2 = vf4{0.0f, 0.0f, 0.0f, 0.0f}, x3 = x2;
-            if (gi + 2u < g1) { x2 = s4[gi + 2u]; x3 = s4[gi + 3u]; }
-            sum = __fadd_rn(__fadd_rn(__fadd_rn(__fadd_rn(sum, x0.x), x0.y), x0.z), x0.w);
-            sum = __fadd_rn(__fadd_rn(__fadd_rn(__fadd_rn(sum, x1.x), x1.y), x1.z), x1.w);
-            sum = __fadd_rn(__fadd_rn(__fadd_rn(__fadd_rn(sum, x2.x), x2.y), x2.z), x2.w);
-            sum = __fadd_rn(__fadd_rn(__fadd_rn(__fadd_rn(sum, x3.x), x3.y), x3.z), x3.w);
+          // the next kRunPad values are on their way while the current ones are added
+          vf4 c0 = s4[gi], c1 = s4[gi + 1u];
+          for (;;) {
+            gi += kRunPad / 4u;
+            const bool more = gi < g1;
+            vf4 n0 = c0, n1 = c1;
+            if (more) { n0 = s4[gi]; n1 = s4[gi + 1u]; }
+            sum = __fadd_rn(__fadd_rn(__fadd_rn(__fadd_rn(sum, c0.x), c0.y), c0.z), c0.w);
+            sum = __fadd_rn(__fadd_rn(__fadd_rn(__fadd_rn(sum, c1.x), c1.y), c1.z), c1.w);
+            if (!more) break;
+            c0 = n0; c1 = n1;
           }
           S.acc[S.run_p[tid]] = sum;
         }
