@@ -357,26 +357,22 @@ __device__ void tile_generic(const DecompressArgs& A, GenericLds& S, const TileG
 constexpr uint32_t kFastShift = 9;
 constexpr uint32_t kFastThreads = 1u << kFastShift;   // 8 waves per tile
 constexpr uint32_t kFastR = 4;                  // entries a thread keeps in registers per tile
-constexpr uint32_t kStagedCap = 2048;           // entries on positions hit more than once, with padding
-constexpr uint32_t kRunPad = 8;                 // run lengths are rounded up to this
+constexpr uint32_t kRows = 48;                  // positions hit more than once in one tile
+constexpr uint32_t kRowStride = kBatchWorkers + 4;   // floats; the +4 spreads the rows over the LDS banks
 
-// seen / cb / masks exist twice: tile i uses set i & 1 while the other set is being cleared.
+// seen / cb / nq / over exist twice: tile i uses set i & 1 while the other set is being cleared.
 struct alignas(16) FastLds {
   float acc[kTile];                          // the tile; all zero between tiles
+  float rows[kRows * kRowStride];            // per colliding position one slot per worker; all +0 between tiles
   uint32_t seen[2][kWords];                  // positions hit at all
   uint32_t cb[2][kWords];                    // positions hit more than once
-  uint32_t masks[2][kQMax * kMaskWords];     // per colliding position: which workers hit it
-  uint32_t pre_cb[kWords];                   // exclusive popcount prefix of cb
-  uint32_t qbase[kQMax + 4];                 // first staged value of every colliding position, +1 closing
-  uint16_t run_p[kQMax];                     // the position a run belongs to
-  float staged[kStagedCap];                  // colliding values in worker order, one run per position
+  uint32_t nq[2];                            // how many of those
   uint32_t over[2];                          // some worker has more entries in the tile than its threads hold
+  uint16_t run_p[kRows];                     // the position a row belongs to
+  uint8_t qmap[kTile];                       // the row of a colliding position (valid where cb is set)
 };
-static_assert(sizeof(FastLds) <= 40960 - 256, "four 8-wave workgroups per CU need <= 40 KB of LDS each");
-static_assert(kWords == 2 * kWaveSize && kQMax == 2 * kWaveSize, "one wave scans the maps, two words per lane");
-
-// per entry, packed into one register: position | colliding position << 12 | colliding << 31
-constexpr uint32_t kPkColl = 0x80000000u;
+static_assert(sizeof(FastLds) <= 53 * 1024, "three 8-wave workgroups per CU");
+static_assert(kRows <= 64 && kRows < 256, "one wave adds the rows; row numbers are bytes");
 
 __device__ __forceinline__ void push_generic(const DecompressArgs& A, uint32_t tile_id) {
   if (threadIdx.x == 0) {
@@ -425,20 +421,26 @@ decompress_tiles_kernel(DecompressArgs A) {
   const uint32_t N = A.num_workers;                    // 1 .. kBatchWorkers (the host checks)
   uint32_t t_first, t_last, stride;
   tiles_of_workgroup(A.num_tiles, t_first, t_last, stride);
-  // The threads of a worker are neighbouring lanes of one wave (at most all 64): the 16-byte
-  // pieces they load from the worker's message are adjacent, so the wave's load touches a line
-  // or two per worker instead of one per lane.
-  uint32_t tpw_shift = 1;
-  while (tpw_shift < 6u && (N << (tpw_shift + 1u)) <= kFastThreads) ++tpw_shift;
-  const uint32_t tpw = 1u << tpw_shift;
-  const uint32_t wl = tid >> tpw_shift;
-  const uint32_t part = tid & (tpw - 1u);
+  // A worker has T = 2^tpw_shift threads, T * kFastR >= 16 entries per tile.  Its first T/2 are
+  // neighbouring lanes in the lower four waves, the others sit in the same lanes of the upper
+  // four: a worker seldom has more than T/2 * kFastR entries in a tile, so the upper waves
+  // mostly have nothing to do and skip the per-entry work, while the 16-byte pieces that
+  // neighbouring lanes load from a message are adjacent (a line or two per worker and wave).
+  uint32_t tpw_shift = 2;
+  while (tpw_shift < 7u && (N << (tpw_shift + 1u)) <= kFastThreads) ++tpw_shift;
+  const uint32_t half_shift = tpw_shift - 1u, tph = 1u << half_shift;   // threads per worker in one half
+  const uint32_t upper = tid >> (kFastShift - 1u);
+  const uint32_t wl = (tid & (kFastThreads / 2u - 1u)) >> half_shift;
+  const uint32_t part = (tid & (tph - 1u)) + upper * tph;
+  const uint32_t tpw = 2u * tph;
   const bool has_worker = wl < N;
-  const int lead_lane4 = static_cast<int>((lane & ~(tpw - 1u)) * 4u);   // the worker's first lane, as a byte address for ds_bpermute
+  const int lead_lane4 = static_cast<int>((lane & ~(tph - 1u)) * 4u);   // the worker's first lane in this wave, as a byte address for ds_bpermute
+  const uint32_t row_groups = (N + 3u) / 4u;           // a row's slots, in groups of four
+
   for (uint32_t i = tid; i < static_cast<uint32_t>(kTile); i += kFastThreads) S.acc[i] = 0.0f;
+  for (uint32_t i = tid; i < kRows * kRowStride; i += kFastThreads) S.rows[i] = 0.0f;
   for (uint32_t i = tid; i < 2u * kWords; i += kFastThreads) { (&S.seen[0][0])[i] = 0u; (&S.cb[0][0])[i] = 0u; }
-  for (uint32_t i = tid; i < 2u * kQMax * kMaskWords; i += kFastThreads) (&S.masks[0][0])[i] = 0u;
-  if (tid < 2u) S.over[tid] = 0u;
+  if (tid < 2u) { S.over[tid] = 0u; S.nq[tid] = 0u; }
   __syncthreads();
   uint32_t par = 0;                                    // which set of maps the current tile uses
 
@@ -450,9 +452,9 @@ decompress_tiles_kernel(DecompressArgs A) {
     const uint32_t run_end = (L.tile_base + L.tiles) < t_last ? (L.tile_base + L.tiles) : t_last;
 
     // Thread (worker wl, part) owns, of its worker's entries inside a tile, the groups of four
-    // consecutive entries number part, part + T, ... (T threads per worker), kFastR entries at
-    // most, fetched with one 16-byte load per group and array.  They are loaded into registers
-    // while the previous tile is being finished and stay there.
+    // consecutive entries number part, part + T, ..., kFastR entries at most, fetched with one
+    // 16-byte load per group and array.  They are loaded into registers while the previous
+    // tile is being finished and stay there.
     uint32_t my_count = 0;
     gptr<const int32_t> my_idx = nullptr;
     gptr<const float> my_val = nullptr;
@@ -467,17 +469,17 @@ decompress_tiles_kernel(DecompressArgs A) {
     const uint32_t row0 = L.row_base + (tile_id - L.tile_base);
     uint32_t r_start = 0, r_end = 0;             // entry range of the tile being fetched
     uint32_t r_start2 = 0, r_end2 = 0;           // entry range of this workgroup's tile after it
-    // a worker's first lane reads the table for all of them
+    // a worker's first lane of each wave reads the table for the others
     auto table_at = [&](uint32_t row, uint32_t& first, uint32_t& last) {
       uint32_t a = 0, b = 0;
-      if (has_worker && part == 0u) { a = tab[tab_w + row]; b = tab[tab_w + row + 1u]; }
+      if (has_worker && (part & (tph - 1u)) == 0u) { a = tab[tab_w + row]; b = tab[tab_w + row + 1u]; }
       first = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(lead_lane4, static_cast<int>(a)));
       last = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(lead_lane4, static_cast<int>(b)));
     };
     table_at(row0, r_start, r_end);
     if (tile_id + stride < run_end) table_at(row0 + stride, r_start2, r_end2);
 
-    uint32_t e_idx[kFastR];                      // index as loaded, then the packed word
+    uint32_t e_idx[kFastR];                      // index as loaded, then the position in the tile
     float e_val[kFastR];
     uint32_t e_cnt = 0;                          // how many of them exist (this thread)
     bool e_over = false;                         // the worker has more entries here than its threads hold
@@ -530,123 +532,71 @@ decompress_tiles_kernel(DecompressArgs A) {
       const TileGeom g = tile_geom(L, layer, tile_id);
       uint32_t* const seen = S.seen[par];
       uint32_t* const cb = S.cb[par];
-      uint32_t* const masks = S.masks[par];
-      // ---- mark the positions hit, and those hit again
+      // ---- mark the positions hit, and those hit again; whoever finds a position hit for the
+      // second time gives it a row (the numbering depends on timing, the sums do not)
+      if (e_cnt != 0u) {
 #pragma unroll
-      for (uint32_t r = 0; r < kFastR; ++r) {
-        uint32_t pk = kNone;
-        if (r < e_cnt) {
-          const uint32_t p = e_idx[r] - g.first;
-          if (p < g.len) {
-            pk = p;
-            const uint32_t bit = 1u << (p & 31u);
-            if (atomicOr(&seen[p >> 5], bit) & bit) atomicOr(&cb[p >> 5], bit);
+        for (uint32_t r = 0; r < kFastR; ++r) {
+          uint32_t p = kNone;
+          if (r < e_cnt) {
+            p = e_idx[r] - g.first;
+            if (p < g.len) {
+              const uint32_t bit = 1u << (p & 31u);
+              if (atomicOr(&seen[p >> 5], bit) & bit) {
+                if (!(atomicOr(&cb[p >> 5], bit) & bit)) {
+                  const uint32_t q = atomicAdd(&S.nq[par], 1u);
+                  if (q < kRows) { S.qmap[p] = static_cast<uint8_t>(q); S.run_p[q] = static_cast<uint16_t>(p); }
+                }
+              }
+            } else {
+              p = kNone;
+            }
           }
+          e_idx[r] = p;
         }
-        e_idx[r] = pk;
       }
       if (e_over) S.over[par] = 1u;
       __syncthreads();
       const bool over = S.over[par] != 0u;
+      const uint32_t nq = S.nq[par];
       // ---- clear the maps the previous tile used
-      if (tid == 0u) S.over[par ^ 1u] = 0u;
+      if (tid < 2u) { if (tid == 0u) S.over[par ^ 1u] = 0u; else S.nq[par ^ 1u] = 0u; }
       if (tid < kWords) { S.seen[par ^ 1u][tid] = 0u; S.cb[par ^ 1u][tid] = 0u; }
-      for (uint32_t i = tid; i < kQMax * kMaskWords; i += kFastThreads) S.masks[par ^ 1u][i] = 0u;
-      // the runs of colliding values are padded with +0 to whole groups of kRunPad
-      for (uint32_t i = tid; i < kStagedCap / 4u; i += kFastThreads) reinterpret_cast<vf4*>(S.staged)[i] = vf4{0.0f, 0.0f, 0.0f, 0.0f};
-      // ---- dense numbering of the colliding positions; every wave computes the same prefix and
-      // writes it (identical values), so it may read it back at once
-      uint32_t nq;
-      {
-        const vu2l cw = *reinterpret_cast<const vu2l*>(&cb[2u * lane]);
-        const uint32_t c0 = static_cast<uint32_t>(__popc(cw.x)), c1 = static_cast<uint32_t>(__popc(cw.y));
-        const uint32_t incl = wave_incl_scan(c0 + c1);
-        nq = wave_total(incl);
-        *reinterpret_cast<vu2l*>(&S.pre_cb[2u * lane]) = vu2l{incl - c0 - c1, incl - c1};
-      }
-      if (over || nq > static_cast<uint32_t>(kQMax)) {
+      if (over || nq > kRows) {
         push_generic(A, tile_id);
         fetch_next(tile_id);
         __syncthreads();                         // the clears above end before the next tile marks
         continue;
       }
-      // ---- positions hit once are final; the others collect the set of their workers
+      // ---- positions hit once are final; the others put their value into their worker's slot of the row
+      if (e_cnt != 0u) {
 #pragma unroll
-      for (uint32_t r = 0; r < kFastR; ++r) {
-        if (e_idx[r] != kNone) {
-          const uint32_t p = e_idx[r], w = p >> 5, sh = p & 31u;
-          const uint32_t cword = nq != 0u ? cb[w] : 0u;
-          if (!((cword >> sh) & 1u)) {
-            S.acc[p] = __fadd_rn(0.0f, e_val[r]);
-          } else {
-            const uint32_t q = S.pre_cb[w] + static_cast<uint32_t>(__popc(cword & ((1u << sh) - 1u)));
-            e_idx[r] = p | (q << 12) | kPkColl;
-            atomicOr(&masks[q * kMaskWords + (wl >> 5)], 1u << (wl & 31u));
+        for (uint32_t r = 0; r < kFastR; ++r) {
+          if (e_idx[r] != kNone) {
+            const uint32_t p = e_idx[r];
+            const uint32_t colliding = nq != 0u ? (cb[p >> 5] >> (p & 31u)) & 1u : 0u;
+            if (!colliding) S.acc[p] = __fadd_rn(0.0f, e_val[r]);
+            else S.rows[static_cast<uint32_t>(S.qmap[p]) * kRowStride + wl] = e_val[r];
           }
         }
       }
       __syncthreads();
-      if (nq != 0u) {
-        // ---- runs of staged values, one per colliding position, in position order
-        uint32_t staged_total;
-        {
-          const vu4l m0 = *reinterpret_cast<const vu4l*>(&masks[(2u * lane) * kMaskWords]);
-          const vu4l m1 = *reinterpret_cast<const vu4l*>(&masks[(2u * lane + 1u) * kMaskWords]);
-          const uint32_t t0 = (static_cast<uint32_t>(__popc(m0.x) + __popc(m0.y) + __popc(m0.z) + __popc(m0.w)) + kRunPad - 1u) & ~(kRunPad - 1u);
-          const uint32_t t1 = (static_cast<uint32_t>(__popc(m1.x) + __popc(m1.y) + __popc(m1.z) + __popc(m1.w)) + kRunPad - 1u) & ~(kRunPad - 1u);
-          const uint32_t incl = wave_incl_scan(t0 + t1);
-          staged_total = wave_total(incl);
-          *reinterpret_cast<vu2l*>(&S.qbase[2u * lane]) = vu2l{incl - t0 - t1, incl - t1};
-          if (lane == 63u) S.qbase[kQMax] = incl;
-        }
-        // the workers below this thread's, as a mask over the words of a position's worker set
-        vu4l lt;
-        {
-          const uint32_t part_bits = (1u << (wl & 31u)) - 1u, ww = wl >> 5;
-          lt.x = ww > 0u ? ~0u : part_bits;
-          lt.y = ww > 1u ? ~0u : (ww == 1u ? part_bits : 0u);
-          lt.z = ww > 2u ? ~0u : (ww == 2u ? part_bits : 0u);
-          lt.w = ww == 3u ? part_bits : 0u;
-        }
-        if (staged_total > kStagedCap) {
-          // undo the single hits: the tile's accumulator has to be all zero again
-#pragma unroll
-          for (uint32_t r = 0; r < kFastR; ++r)
-            if (e_idx[r] != kNone && !(e_idx[r] & kPkColl)) S.acc[e_idx[r]] = 0.0f;
-          push_generic(A, tile_id);
-          fetch_next(tile_id);
-          __syncthreads();
-          continue;
-        }
-#pragma unroll
-        for (uint32_t r = 0; r < kFastR; ++r) {
-          if (e_idx[r] != kNone && (e_idx[r] & kPkColl)) {
-            const uint32_t q = (e_idx[r] >> 12) & 0x7Fu;
-            const vu4l m = *reinterpret_cast<const vu4l*>(&masks[q * kMaskWords]);
-            const uint32_t rank = static_cast<uint32_t>(__popc(m.x & lt.x) + __popc(m.y & lt.y) + __popc(m.z & lt.z) + __popc(m.w & lt.w));
-            S.staged[S.qbase[q] + rank] = e_val[r];
-            if (rank == 0u) S.run_p[q] = static_cast<uint16_t>(e_idx[r] & 0xFFFu);
-          }
-        }
-        __syncthreads();
-      }
       // the entries are used up: their registers take the next tile's
       fetch_next(tile_id);
       if (nq != 0u) {
-        // ---- one lane per colliding position adds its run in worker order; the padding adds +0,
-        // which leaves every partial sum as it is (a partial sum is never -0)
+        // ---- one lane per colliding position adds its row in worker order; the slots of the
+        // workers that did not hit it hold +0, which leaves every partial sum as it is (a
+        // partial sum is never -0)
         if (tid < nq) {
-          const uint32_t g1 = S.qbase[tid + 1u] / 4u;     // in groups of four values
-          uint32_t gi = S.qbase[tid] / 4u;
-          const vf4* const s4 = reinterpret_cast<const vf4*>(S.staged);
+          const vf4* const r4 = reinterpret_cast<const vf4*>(S.rows + tid * kRowStride);
           float sum = 0.0f;
-          // the next kRunPad values are on their way while the current ones are added
-          vf4 c0 = s4[gi], c1 = s4[gi + 1u];
+          uint32_t gi = 0;
+          vf4 c0 = r4[0], c1 = r4[1];            // the next eight slots are on their way while these are added
           for (;;) {
-            gi += kRunPad / 4u;
-            const bool more = gi < g1;
+            gi += 2u;
+            const bool more = gi < row_groups;
             vf4 n0 = c0, n1 = c1;
-            if (more) { n0 = s4[gi]; n1 = s4[gi + 1u]; }
+            if (more) { n0 = r4[gi]; n1 = r4[gi + 1u]; }
             sum = __fadd_rn(__fadd_rn(__fadd_rn(__fadd_rn(sum, c0.x), c0.y), c0.z), c0.w);
             sum = __fadd_rn(__fadd_rn(__fadd_rn(__fadd_rn(sum, c1.x), c1.y), c1.z), c1.w);
             if (!more) break;
@@ -655,6 +605,9 @@ decompress_tiles_kernel(DecompressArgs A) {
           S.acc[S.run_p[tid]] = sum;
         }
         __syncthreads();
+        // the rows go back to +0
+        for (uint32_t i = tid; i < nq * (kRowStride / 4u); i += kFastThreads)
+          reinterpret_cast<vf4*>(S.rows)[i] = vf4{0.0f, 0.0f, 0.0f, 0.0f};
       }
       // ---- write the tile (scaled) and leave its accumulator cleared
       const bool vec = ((reinterpret_cast<uintptr_t>(g.dense) & 15u) == 0u) && ((g.len & 3u) == 0u);
