@@ -472,7 +472,12 @@ decompress_tiles_kernel(DecompressArgs A) {
     // a worker's first lane of each wave reads the table for the others
     auto table_at = [&](uint32_t row, uint32_t& first, uint32_t& last) {
       uint32_t a = 0, b = 0;
-      if (has_worker && (part & (tph - 1u)) == 0u) { a = tab[tab_w + row]; b = tab[tab_w + row + 1u]; }
+      if (has_worker && (part & (tph - 1u)) == 0u) {
+        typedef uint32_t vu2u __attribute__((ext_vector_type(2), aligned(4)));
+        const vu2u ab = *reinterpret_cast<gptr<const vu2u>>(tab + (tab_w + row));   // one access for both
+        a = ab.x;
+        b = ab.y;
+      }
       first = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(lead_lane4, static_cast<int>(a)));
       last = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(lead_lane4, static_cast<int>(b)));
     };
