@@ -357,7 +357,7 @@ __device__ void tile_generic(const DecompressArgs& A, GenericLds& S, const TileG
 constexpr uint32_t kFastShift = 9;
 constexpr uint32_t kFastThreads = 1u << kFastShift;   // 8 waves per tile
 constexpr uint32_t kFastR = 4;                  // entries a thread keeps in registers per tile
-constexpr uint32_t kRows = 48;                  // positions hit more than once in one tile
+constexpr uint32_t kRows = 32;                  // positions hit more than once in one tile
 constexpr uint32_t kRowStride = kBatchWorkers + 4;   // floats; the +4 spreads the rows over the LDS banks
 
 // seen / cb / nq / over exist twice: tile i uses set i & 1 while the other set is being cleared.
@@ -371,8 +371,17 @@ struct alignas(16) FastLds {
   uint16_t run_p[kRows];                     // the position a row belongs to
   uint8_t qmap[kTile];                       // the row of a colliding position (valid where cb is set)
 };
-static_assert(sizeof(FastLds) <= 53 * 1024, "three 8-wave workgroups per CU");
+static_assert(sizeof(FastLds) <= 40 * 1024, "four 8-wave workgroups per CU");
 static_assert(kRows <= 64 && kRows < 256, "one wave adds the rows; row numbers are bytes");
+
+// threadIdx.x behind a veil: what is derived from it is recomputed where it is used instead of
+// being kept in a register across the whole tile loop (the loop is short of registers for eight
+// waves per SIMD, and a spilled value comes back through a vector-memory wait).
+__device__ __forceinline__ uint32_t fresh_tid() {
+  uint32_t t = threadIdx.x;
+  asm volatile("" : "+v"(t));
+  return t;
+}
 
 __device__ __forceinline__ void push_generic(const DecompressArgs& A, uint32_t tile_id) {
   if (threadIdx.x == 0) {
@@ -414,7 +423,7 @@ __global__ void __launch_bounds__(kBlockThreads) decompress_table_kernel(Decompr
 }
 
 // ------------------------------------------------------------------ tile accumulation, fast path
-__global__ void __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(6, 6)))
+__global__ void __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
 decompress_tiles_kernel(DecompressArgs A) {
   __shared__ FastLds S;
   const uint32_t tid = threadIdx.x, lane = tid & 63u;
@@ -575,13 +584,14 @@ decompress_tiles_kernel(DecompressArgs A) {
       }
       // ---- positions hit once are final; the others put their value into their worker's slot of the row
       if (e_cnt != 0u) {
+        const uint32_t my_slot = (fresh_tid() & (kFastThreads / 2u - 1u)) >> half_shift;   // = wl
 #pragma unroll
         for (uint32_t r = 0; r < kFastR; ++r) {
           if (e_idx[r] != kNone) {
             const uint32_t p = e_idx[r];
             const uint32_t colliding = nq != 0u ? (cb[p >> 5] >> (p & 31u)) & 1u : 0u;
             if (!colliding) S.acc[p] = __fadd_rn(0.0f, e_val[r]);
-            else S.rows[static_cast<uint32_t>(S.qmap[p]) * kRowStride + wl] = e_val[r];
+            else S.rows[static_cast<uint32_t>(S.qmap[p]) * kRowStride + my_slot] = e_val[r];
           }
         }
       }
@@ -592,8 +602,9 @@ decompress_tiles_kernel(DecompressArgs A) {
         // ---- one lane per colliding position adds its row in worker order; the slots of the
         // workers that did not hit it hold +0, which leaves every partial sum as it is (a
         // partial sum is never -0)
-        if (tid < nq) {
-          const vf4* const r4 = reinterpret_cast<const vf4*>(S.rows + tid * kRowStride);
+        const uint32_t row = fresh_tid();
+        if (row < nq) {
+          const vf4* const r4 = reinterpret_cast<const vf4*>(S.rows + row * kRowStride);
           float sum = 0.0f;
           uint32_t gi = 0;
           vf4 c0 = r4[0], c1 = r4[1];            // the next eight slots are on their way while these are added
@@ -607,21 +618,22 @@ decompress_tiles_kernel(DecompressArgs A) {
             if (!more) break;
             c0 = n0; c1 = n1;
           }
-          S.acc[S.run_p[tid]] = sum;
+          S.acc[S.run_p[row]] = sum;
         }
         __syncthreads();
         // the rows go back to +0
-        for (uint32_t i = tid; i < nq * (kRowStride / 4u); i += kFastThreads)
+        for (uint32_t i = row; i < nq * (kRowStride / 4u); i += kFastThreads)
           reinterpret_cast<vf4*>(S.rows)[i] = vf4{0.0f, 0.0f, 0.0f, 0.0f};
       }
       // ---- write the tile (scaled) and leave its accumulator cleared
       const bool vec = ((reinterpret_cast<uintptr_t>(g.dense) & 15u) == 0u) && ((g.len & 3u) == 0u);
+      const uint32_t out_tid = fresh_tid();
       if (vec) {
         const gptr<vf4> d4 = as_global(reinterpret_cast<vf4*>(g.dense));
         vf4* const acc4 = reinterpret_cast<vf4*>(S.acc);
 #pragma unroll
         for (uint32_t j = 0; j < static_cast<uint32_t>(kTile) / (4u * kFastThreads); ++j) {
-          const uint32_t i4 = tid + j * kFastThreads;
+          const uint32_t i4 = out_tid + j * kFastThreads;
           if (4u * i4 < g.len) {
             const vf4 a = acc4[i4];
             acc4[i4] = vf4{0.0f, 0.0f, 0.0f, 0.0f};
@@ -638,7 +650,7 @@ decompress_tiles_kernel(DecompressArgs A) {
         }
       } else {
         const gptr<float> d = as_global(g.dense);
-        for (uint32_t i = tid; i < g.len; i += kFastThreads) {
+        for (uint32_t i = out_tid; i < g.len; i += kFastThreads) {
           float o = __fmul_rn(S.acc[i], A.scale);
           S.acc[i] = 0.0f;
           if (A.add_to_dst) o = __fadd_rn(d[i], o);
