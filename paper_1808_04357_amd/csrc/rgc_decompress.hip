@@ -3,31 +3,27 @@
 //
 // Tile ownership: one workgroup owns kTile consecutive positions of one dense buffer, adds every
 // worker's entries that fall into the tile and writes the tile once (scaled).  Entries of one
-// worker are unique inside a tile, so positions hit by a single worker need no ordering;
-// positions hit by several workers are summed strictly in worker order by one lane each: a
-// per-position bitmask of the hitting workers (built with order-independent atomic ORs) gives
-// every colliding entry its rank among them, the values are placed by rank and then added left
-// to right.  The result is therefore independent of scheduling and equals the sequential sum
-// bit for bit; no floating-point atomics are used.
+// worker are unique inside a tile, so positions hit by a single worker need no ordering.  A
+// position hit by several workers gets a row with one slot per worker: every hitter stores its
+// value into its own slot, the other slots hold +0, and one lane adds the row from slot 0
+// upwards.  Adding +0 leaves a partial sum as it is, so this is the sequential sum over the
+// workers bit for bit, independent of scheduling; no floating-point atomics are used.
 //
 // A first kernel builds a table with the offset of the first entry of every tile in every
-// (worker, layer) message (the messages are sorted by index); one row per worker, so both the
-// builder's stores and a worker's reads for neighbouring tiles fall into the same cache lines.
+// (worker, layer) message (the messages are sorted by index); one row per worker, so the
+// builder's stores fall into the same cache lines.
 //
 // The tile kernel is persistent and XCD-aware: every XCD gets one contiguous range of tiles and
 // its workgroups take them round-robin, so neighbouring tiles share table and message cache
-// lines inside one L2.  A tile is a few hundred entries in 4096 positions, so the kernel keeps
-// it sparse: a bitmap of the hit positions, their sums in a compact array, and the dense tile is
-// formed in registers on the way out (mostly zeros).  That keeps the LDS footprint at 20 KB (8
-// workgroups per CU, which is what hides the store and gather latencies) and removes the dense
-// clear.  Inside a run of tiles of one layer the kernel is software pipelined: while tile i is
-// processed, the entries of tile i+1 are already being loaded into registers and the table
-// entries of tile i+2 are in flight.
+// lines inside one L2.  Inside a run of tiles of one layer the kernel is software pipelined:
+// while tile i is processed, the entries of tile i+1 are already being loaded into registers
+// and the table entries of tile i+2 are in flight.  What bounds it is the number of small
+// gathers (one 16- or 32-byte piece per worker, tile and array, each an L1 miss), not the LDS
+// work: the thread-to-worker mapping is chosen to make those gathers few and adjacent.
 //
-// Tiles the fast kernel cannot take (a worker with more entries than its threads hold, too many
-// distinct or colliding positions) are appended to a list and redone by a second kernel with
-// larger staging buffers and no pipelining; with more than kBatchWorkers workers that kernel
-// does every tile.
+// Tiles the fast kernel cannot take (more colliding positions than it has rows) are appended to
+// a list and redone by a second kernel, which sorts the colliding entries by rank in a worker
+// bitmask instead; with more than kBatchWorkers workers that kernel does every tile.
 #include "rgc_device.h"
 
 namespace rgc {
@@ -78,9 +74,15 @@ __device__ __forceinline__ TileGeom tile_geom(const DecompressLayer& L, uint32_t
 // fetched from HBM once and is then found in that XCD's L2 by the 7 other workgroups that need it
 // (a blocked assignment makes the concurrent working set of an XCD as large as its L2 and fetches
 // every line 8 times).
-__device__ __forceinline__ void tiles_of_workgroup(uint32_t num_tiles, uint32_t& t_first, uint32_t& t_last,
+__device__ __forceinline__ void tiles_of_workgroup(uint32_t num_tiles, uint32_t cus, uint32_t& t_first, uint32_t& t_last,
                                                    uint32_t& stride) {
-  const uint32_t xcd = blockIdx.x & 7u, slot = blockIdx.x >> 3, slots = gridDim.x >> 3;
+  const uint32_t xcd = blockIdx.x & 7u, slots = gridDim.x >> 3;
+  uint32_t slot = blockIdx.x >> 3;
+  // The workgroups that share a CU (an XCD's CUs are filled round-robin, so these are the slots
+  // c, c + C, c + 2C, ... for C CUs) take directly neighbouring tiles: the message lines one of
+  // them pulls into the CU's L1 are the ones the others need.
+  const uint32_t cu_per_xcd = cus >> 3;
+  if (cu_per_xcd != 0u && slots % cu_per_xcd == 0u) slot = (slot % cu_per_xcd) * (slots / cu_per_xcd) + slot / cu_per_xcd;
   const uint32_t per_xcd = (num_tiles + 7u) >> 3;
   const uint32_t x0 = xcd * per_xcd < num_tiles ? xcd * per_xcd : num_tiles;
   const uint32_t x1 = x0 + per_xcd < num_tiles ? x0 + per_xcd : num_tiles;
@@ -90,6 +92,10 @@ __device__ __forceinline__ void tiles_of_workgroup(uint32_t num_tiles, uint32_t&
 }
 
 // =================================================================== generic tiles
+// Any number of workers and entries.  Workers are taken in batches of kBatchWorkers; inside a
+// batch a per-position bitmask of the hitting workers (built with order-independent atomic ORs)
+// gives every colliding entry its rank among them, the values are placed by rank and then added
+// left to right by one lane per position.
 struct alignas(16) GenericLds {
   float acc[kTile];
   uint32_t cnt32[kTile / 4];          // one byte counter per position
@@ -357,21 +363,20 @@ __device__ void tile_generic(const DecompressArgs& A, GenericLds& S, const TileG
 constexpr uint32_t kFastShift = 9;
 constexpr uint32_t kFastThreads = 1u << kFastShift;   // 8 waves per tile
 constexpr uint32_t kFastR = 4;                  // entries a thread keeps in registers per tile
-constexpr uint32_t kRows = 32;                  // positions hit more than once in one tile
+constexpr uint32_t kRows = 48;                  // positions hit more than once in one tile
 constexpr uint32_t kRowStride = kBatchWorkers + 4;   // floats; the +4 spreads the rows over the LDS banks
 
-// seen / cb / nq / over exist twice: tile i uses set i & 1 while the other set is being cleared.
+// seen / cb / nq exist twice: tile i uses set i & 1 while the other set is being cleared.
 struct alignas(16) FastLds {
   float acc[kTile];                          // the tile; all zero between tiles
   float rows[kRows * kRowStride];            // per colliding position one slot per worker; all +0 between tiles
   uint32_t seen[2][kWords];                  // positions hit at all
   uint32_t cb[2][kWords];                    // positions hit more than once
   uint32_t nq[2];                            // how many of those
-  uint32_t over[2];                          // some worker has more entries in the tile than its threads hold
   uint16_t run_p[kRows];                     // the position a row belongs to
   uint8_t qmap[kTile];                       // the row of a colliding position (valid where cb is set)
 };
-static_assert(sizeof(FastLds) <= 40 * 1024, "four 8-wave workgroups per CU");
+static_assert(sizeof(FastLds) <= 53 * 1024, "three 8-wave workgroups per CU");
 static_assert(kRows <= 64 && kRows < 256, "one wave adds the rows; row numbers are bytes");
 
 // threadIdx.x behind a veil: what is derived from it is recomputed where it is used instead of
@@ -423,13 +428,13 @@ __global__ void __launch_bounds__(kBlockThreads) decompress_table_kernel(Decompr
 }
 
 // ------------------------------------------------------------------ tile accumulation, fast path
-__global__ void __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
+__global__ void __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(6, 6)))
 decompress_tiles_kernel(DecompressArgs A) {
   __shared__ FastLds S;
   const uint32_t tid = threadIdx.x, lane = tid & 63u;
   const uint32_t N = A.num_workers;                    // 1 .. kBatchWorkers (the host checks)
   uint32_t t_first, t_last, stride;
-  tiles_of_workgroup(A.num_tiles, t_first, t_last, stride);
+  tiles_of_workgroup(A.num_tiles, A.cus, t_first, t_last, stride);
   // A worker has T = 2^tpw_shift threads, T * kFastR >= 16 entries per tile.  Its first T/2 are
   // neighbouring lanes in the lower four waves, the others sit in the same lanes of the upper
   // four: a worker seldom has more than T/2 * kFastR entries in a tile, so the upper waves
@@ -449,7 +454,7 @@ decompress_tiles_kernel(DecompressArgs A) {
   for (uint32_t i = tid; i < static_cast<uint32_t>(kTile); i += kFastThreads) S.acc[i] = 0.0f;
   for (uint32_t i = tid; i < kRows * kRowStride; i += kFastThreads) S.rows[i] = 0.0f;
   for (uint32_t i = tid; i < 2u * kWords; i += kFastThreads) { (&S.seen[0][0])[i] = 0u; (&S.cb[0][0])[i] = 0u; }
-  if (tid < 2u) { S.over[tid] = 0u; S.nq[tid] = 0u; }
+  if (tid < 2u) S.nq[tid] = 0u;
   __syncthreads();
   uint32_t par = 0;                                    // which set of maps the current tile uses
 
@@ -496,20 +501,21 @@ decompress_tiles_kernel(DecompressArgs A) {
     uint32_t e_idx[kFastR];                      // index as loaded, then the position in the tile
     float e_val[kFastR];
     uint32_t e_cnt = 0;                          // how many of them exist (this thread)
-    bool e_over = false;                         // the worker has more entries here than its threads hold
+    uint32_t e_start = 0, e_c = 0;               // the worker's entries in that tile: first, how many
     typedef uint32_t vu4 __attribute__((ext_vector_type(4), aligned(4)));
     typedef float vf4u __attribute__((ext_vector_type(4), aligned(4)));
     auto fetch = [&]() {
       const uint32_t e1 = r_end < my_count ? r_end : my_count;   // the table never exceeds the message; stay in bounds anyway
       const uint32_t c = e1 > r_start ? e1 - r_start : 0u;
-      e_over = c > tpw * kFastR;
+      e_start = r_start;
+      e_c = c;
       e_cnt = 0;
 #pragma unroll
       for (uint32_t r = 0; r < kFastR / 4u; ++r) {
         const uint32_t off = 4u * (part + r * tpw);          // first entry of this group inside the tile
 #pragma unroll
         for (uint32_t j = 0; j < 4u; ++j) { e_idx[4u * r + j] = 0; e_val[4u * r + j] = 0.0f; }
-        if (!e_over && off < c) {
+        if (off < c) {
           const uint32_t at = r_start + off;
           const uint32_t have = (c - off) < 4u ? (c - off) : 4u;
           if (at + 4u <= my_count) {                         // the 16-byte load stays inside the message
@@ -548,35 +554,40 @@ decompress_tiles_kernel(DecompressArgs A) {
       uint32_t* const cb = S.cb[par];
       // ---- mark the positions hit, and those hit again; whoever finds a position hit for the
       // second time gives it a row (the numbering depends on timing, the sums do not)
+      auto mark = [&](uint32_t p) {
+        const uint32_t bit = 1u << (p & 31u);
+        if (atomicOr(&seen[p >> 5], bit) & bit) {
+          if (!(atomicOr(&cb[p >> 5], bit) & bit)) {
+            const uint32_t q = atomicAdd(&S.nq[par], 1u);
+            if (q < kRows) { S.qmap[p] = static_cast<uint8_t>(q); S.run_p[q] = static_cast<uint16_t>(p); }
+          }
+        }
+      };
       if (e_cnt != 0u) {
 #pragma unroll
         for (uint32_t r = 0; r < kFastR; ++r) {
           uint32_t p = kNone;
           if (r < e_cnt) {
             p = e_idx[r] - g.first;
-            if (p < g.len) {
-              const uint32_t bit = 1u << (p & 31u);
-              if (atomicOr(&seen[p >> 5], bit) & bit) {
-                if (!(atomicOr(&cb[p >> 5], bit) & bit)) {
-                  const uint32_t q = atomicAdd(&S.nq[par], 1u);
-                  if (q < kRows) { S.qmap[p] = static_cast<uint8_t>(q); S.run_p[q] = static_cast<uint16_t>(p); }
-                }
-              }
-            } else {
-              p = kNone;
-            }
+            if (p < g.len) mark(p); else p = kNone;
           }
           e_idx[r] = p;
         }
+        // a worker with more entries in this tile than its threads hold (rare): the further
+        // groups come straight from memory, here and again below
+        for (uint32_t off = 4u * (part + tpw); off < e_c; off += 4u * tpw) {
+          for (uint32_t j = 0; j < 4u && off + j < e_c; ++j) {
+            const uint32_t p = static_cast<uint32_t>(my_idx[e_start + off + j]) - g.first;
+            if (p < g.len) mark(p);
+          }
+        }
       }
-      if (e_over) S.over[par] = 1u;
       __syncthreads();
-      const bool over = S.over[par] != 0u;
       const uint32_t nq = S.nq[par];
       // ---- clear the maps the previous tile used
-      if (tid < 2u) { if (tid == 0u) S.over[par ^ 1u] = 0u; else S.nq[par ^ 1u] = 0u; }
+      if (tid == 0u) S.nq[par ^ 1u] = 0u;
       if (tid < kWords) { S.seen[par ^ 1u][tid] = 0u; S.cb[par ^ 1u][tid] = 0u; }
-      if (over || nq > kRows) {
+      if (nq > kRows) {
         push_generic(A, tile_id);
         fetch_next(tile_id);
         __syncthreads();                         // the clears above end before the next tile marks
@@ -585,13 +596,18 @@ decompress_tiles_kernel(DecompressArgs A) {
       // ---- positions hit once are final; the others put their value into their worker's slot of the row
       if (e_cnt != 0u) {
         const uint32_t my_slot = (fresh_tid() & (kFastThreads / 2u - 1u)) >> half_shift;   // = wl
+        auto place = [&](uint32_t p, float v) {
+          const uint32_t colliding = nq != 0u ? (cb[p >> 5] >> (p & 31u)) & 1u : 0u;
+          if (!colliding) S.acc[p] = __fadd_rn(0.0f, v);
+          else S.rows[static_cast<uint32_t>(S.qmap[p]) * kRowStride + my_slot] = v;
+        };
 #pragma unroll
-        for (uint32_t r = 0; r < kFastR; ++r) {
-          if (e_idx[r] != kNone) {
-            const uint32_t p = e_idx[r];
-            const uint32_t colliding = nq != 0u ? (cb[p >> 5] >> (p & 31u)) & 1u : 0u;
-            if (!colliding) S.acc[p] = __fadd_rn(0.0f, e_val[r]);
-            else S.rows[static_cast<uint32_t>(S.qmap[p]) * kRowStride + my_slot] = e_val[r];
+        for (uint32_t r = 0; r < kFastR; ++r)
+          if (e_idx[r] != kNone) place(e_idx[r], e_val[r]);
+        for (uint32_t off = 4u * (part + tpw); off < e_c; off += 4u * tpw) {
+          for (uint32_t j = 0; j < 4u && off + j < e_c; ++j) {
+            const uint32_t p = static_cast<uint32_t>(my_idx[e_start + off + j]) - g.first;
+            if (p < g.len) place(p, my_val[e_start + off + j]);
           }
         }
       }
@@ -678,7 +694,7 @@ __global__ void __launch_bounds__(kBlockThreads) decompress_generic_kernel(Decom
   };
   if (all_tiles) {
     uint32_t t_first, t_last, stride;
-    tiles_of_workgroup(A.num_tiles, t_first, t_last, stride);
+    tiles_of_workgroup(A.num_tiles, A.cus, t_first, t_last, stride);
     for (uint32_t t = t_first; t < t_last; t += stride) one_tile(t);
     return;
   }
@@ -727,7 +743,8 @@ hipError_t launch_decompress_tiles(const DecompressArgs& a, hipStream_t s) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     // the listed tiles are few: a small grid keeps the launch cheap when the list is empty
-    const uint32_t ggrid = want < cus8 ? want : cus8;
+    const uint32_t gcap = cus8 / 2u < 8u ? 8u : ((cus8 / 2u) / 8u) * 8u;
+    const uint32_t ggrid = want < gcap ? want : gcap;
     hipLaunchKernelGGL(decompress_generic_kernel, dim3(ggrid), dim3(kBlockThreads), 0, s, a, 0u);
     return hipGetLastError();
   }
