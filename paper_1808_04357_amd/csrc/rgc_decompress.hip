@@ -74,15 +74,9 @@ __device__ __forceinline__ TileGeom tile_geom(const DecompressLayer& L, uint32_t
 // fetched from HBM once and is then found in that XCD's L2 by the 7 other workgroups that need it
 // (a blocked assignment makes the concurrent working set of an XCD as large as its L2 and fetches
 // every line 8 times).
-__device__ __forceinline__ void tiles_of_workgroup(uint32_t num_tiles, uint32_t cus, uint32_t& t_first, uint32_t& t_last,
+__device__ __forceinline__ void tiles_of_workgroup(uint32_t num_tiles, uint32_t& t_first, uint32_t& t_last,
                                                    uint32_t& stride) {
-  const uint32_t xcd = blockIdx.x & 7u, slots = gridDim.x >> 3;
-  uint32_t slot = blockIdx.x >> 3;
-  // The workgroups that share a CU (an XCD's CUs are filled round-robin, so these are the slots
-  // c, c + C, c + 2C, ... for C CUs) take directly neighbouring tiles: the message lines one of
-  // them pulls into the CU's L1 are the ones the others need.
-  const uint32_t cu_per_xcd = cus >> 3;
-  if (cu_per_xcd != 0u && slots % cu_per_xcd == 0u) slot = (slot % cu_per_xcd) * (slots / cu_per_xcd) + slot / cu_per_xcd;
+  const uint32_t xcd = blockIdx.x & 7u, slot = blockIdx.x >> 3, slots = gridDim.x >> 3;
   const uint32_t per_xcd = (num_tiles + 7u) >> 3;
   const uint32_t x0 = xcd * per_xcd < num_tiles ? xcd * per_xcd : num_tiles;
   const uint32_t x1 = x0 + per_xcd < num_tiles ? x0 + per_xcd : num_tiles;
@@ -434,7 +428,7 @@ decompress_tiles_kernel(DecompressArgs A) {
   const uint32_t tid = threadIdx.x, lane = tid & 63u;
   const uint32_t N = A.num_workers;                    // 1 .. kBatchWorkers (the host checks)
   uint32_t t_first, t_last, stride;
-  tiles_of_workgroup(A.num_tiles, A.cus, t_first, t_last, stride);
+  tiles_of_workgroup(A.num_tiles, t_first, t_last, stride);
   // A worker has T = 2^tpw_shift threads, T * kFastR >= 16 entries per tile.  Its first T/2 are
   // neighbouring lanes in the lower four waves, the others sit in the same lanes of the upper
   // four: a worker seldom has more than T/2 * kFastR entries in a tile, so the upper waves
@@ -694,7 +688,7 @@ __global__ void __launch_bounds__(kBlockThreads) decompress_generic_kernel(Decom
   };
   if (all_tiles) {
     uint32_t t_first, t_last, stride;
-    tiles_of_workgroup(A.num_tiles, A.cus, t_first, t_last, stride);
+    tiles_of_workgroup(A.num_tiles, t_first, t_last, stride);
     for (uint32_t t = t_first; t < t_last; t += stride) one_tile(t);
     return;
   }
