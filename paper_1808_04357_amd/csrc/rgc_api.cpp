@@ -450,10 +450,6 @@ int rgc_compress_layers(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layer
   A.mask_momentum = (flags & RGC_NO_MOMENTUM_MASK) ? 0u : 1u;
   A.m = momentum;
   A.launch = 1;
-  {
-    const char* e = std::getenv("RGC_DEBUG");
-    A.debug = e ? static_cast<uint32_t>(std::atol(e)) : 0u;
-  }
   if (ctx->profiling) RGC_HIP(take_event(ctx, stream, ctx->ev_compress));
   RGC_HIP(launch_accumulate(A, plan->num_wgs, stream));
   if (ctx->profiling) RGC_HIP(take_event(ctx, stream, ctx->ev_compress));

@@ -32,7 +32,6 @@ typedef float vf4 __attribute__((ext_vector_type(4)));   // one 16-byte access p
 typedef uint32_t vu2 __attribute__((ext_vector_type(2))); // a candidate: (float bits, index)
 
 struct Collector {
-  uint32_t debug;    // experiment switches, 0 in normal use
   gptr<vu2> slot;    // this wave-chunk's candidate list
   uint32_t* coarse;  // the workgroup's coarse histogram in LDS (flushed when the workgroup ends)
   uint32_t cap;
@@ -58,18 +57,11 @@ __device__ __forceinline__ void consume(const float (&a)[4], uint32_t nvalid, ui
     key[j] = bits[j] & kKeyMask;
   }
   if constexpr (kCollect) {
-    if (c.debug & 1024u) return;
-    if (c.debug & 512u) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) atomicAdd(&lds_hist[1024u + (key[j] >> 19) % 3072u], 1u);
-    }
-    if (c.debug & 128u) __builtin_amdgcn_s_sleep(1);
-    if (c.debug & 256u) __builtin_amdgcn_s_sleep(4);
     bool f[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) f[j] = (static_cast<uint32_t>(j) < nvalid) && (key[j] >= c.tau);
     const unsigned long long any = __ballot(f[0] | f[1] | f[2] | f[3]);
-    if (any != 0ull && !(c.debug & 32u)) {
+    if (any != 0ull) {
       const unsigned long long m0 = __ballot(f[0]), m1 = __ballot(f[1]), m2 = __ballot(f[2]),
                                m3 = __ballot(f[3]);
       uint32_t pos = c.count + rank_below(m0) + rank_below(m1) + rank_below(m2) + rank_below(m3);
@@ -77,8 +69,8 @@ __device__ __forceinline__ void consume(const float (&a)[4], uint32_t nvalid, ui
       for (int j = 0; j < 4; ++j) {
         if (f[j]) {
           if (pos < c.cap) {
-            if (!(c.debug & 2u)) c.slot[pos] = vu2{bits[j], idx0 + j};
-            if (!(c.debug & 16u)) atomicAdd(&c.coarse[coarse_bin(key[j], c.tau, c.shift)], 1u);
+            c.slot[pos] = vu2{bits[j], idx0 + j};
+            atomicAdd(&c.coarse[coarse_bin(key[j], c.tau, c.shift)], 1u);
           }
           ++pos;
         }
@@ -89,7 +81,7 @@ __device__ __forceinline__ void consume(const float (&a)[4], uint32_t nvalid, ui
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       if (static_cast<uint32_t>(j) < nvalid) {
-        if (key[j] != 0u) { if (!(c.debug & 64u)) atomicAdd(&lds_hist[key[j] >> 19], 1u); }
+        if (key[j] != 0u) atomicAdd(&lds_hist[key[j] >> 19], 1u);
         else ++zeros;
       }
     }
@@ -122,13 +114,7 @@ __device__ __forceinline__ void stream_chunk(const LayerDesc& L, uint32_t begin,
     const gptr<const vf4> G4 = as_global(reinterpret_cast<const vf4*>(L.grad + begin));
     const gptr<vf4> V4 = as_global(reinterpret_cast<vf4*>(L.resid + begin));
     const gptr<vf4> U4 = as_global(kMom ? reinterpret_cast<vf4*>(L.mom + begin) : nullptr);
-#ifndef RGC_UNROLL_MOM
-#define RGC_UNROLL_MOM 2
-#endif
-#ifndef RGC_UNROLL_PLAIN
-#define RGC_UNROLL_PLAIN 4
-#endif
-    constexpr uint32_t kUnroll = kMom ? RGC_UNROLL_MOM : RGC_UNROLL_PLAIN;
+    constexpr uint32_t kUnroll = kMom ? 2u : 4u;   // 16-byte loads in flight per lane: 6 or 8
     uint32_t g = 0;
     for (; g + kUnroll <= nfull; g += kUnroll) {
       vf4 gv[kUnroll], vv[kUnroll], uv[kUnroll];
@@ -550,12 +536,11 @@ __global__ void __launch_bounds__(kBlockThreads) accumulate_kernel(CompressArgs 
     c.slot = as_global(reinterpret_cast<vu2*>(A.slots + static_cast<size_t>(L.wc_first + wc_local) * A.cap));
     c.coarse = lds_hist;
     c.cap = A.cap;
-    c.debug = A.debug;
     c.count = 0;
     c.tau = st->tau;
     c.shift = st->shift;
     const bool mom = (L.mom != nullptr);
-    if (collect && !(A.debug & 2048u)) {
+    if (collect) {
       if (mom) stream_chunk<true, true>(L, begin, end, A.m, c, lds_hist);
       else stream_chunk<false, true>(L, begin, end, A.m, c, lds_hist);
       if (lane_id() == 0) st_agent(&A.cand_cnt[L.wc_first + wc_local], c.count);
@@ -564,7 +549,6 @@ __global__ void __launch_bounds__(kBlockThreads) accumulate_kernel(CompressArgs 
       else stream_chunk<false, false>(L, begin, end, A.m, c, lds_hist);
     }
   }
-  if (A.debug & 8u) return;
   __syncthreads();
   if (collect) {
     // Global atomics only here, in one burst per workgroup: inside the streaming loop each one
@@ -575,7 +559,6 @@ __global__ void __launch_bounds__(kBlockThreads) accumulate_kernel(CompressArgs 
     flush_hist(lds_hist, A.hist + static_cast<size_t>(l) * kHistBins, kHistBins);
   }
   if (last_block_of_layer(&st->done, A.group_done + L.grp_first, blockIdx.x - L.wg_first, L.wg_count, &sh.flag)) {
-    if (A.debug & 4u) return;
     if (collect) {
       resolve_collect(A, l, L, st, sh, lds_hist);
     } else {

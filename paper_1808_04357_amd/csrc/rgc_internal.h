@@ -99,7 +99,6 @@ struct CompressArgs {
   uint32_t mask_momentum;
   float m;
   uint32_t launch;       // launch number of the phase kernel (2..6)
-  uint32_t debug;        // experiment switches (RGC_DEBUG), 0 in normal use
 };
 
 // ---------------------------------------------------------------- decompress
