@@ -508,6 +508,12 @@ __device__ void bitonic_sort_desc(unsigned long long* s, uint32_t n2) {
   __syncthreads();
 }
 
+// The zeros that mask a sent entry out of the residual (and the velocity) are isolated 4-byte
+// writes, one cache line in a thousand.  Left dirty in the caches they are written to DRAM one
+// by one while the next streaming pass runs and cost it about a tenth of its bandwidth; stored
+// with the streaming hint they leave the caches early and cost half of that.
+__device__ __forceinline__ void mask_store(gptr<float> p) { __builtin_nontemporal_store(0.0f, p); }
+
 __device__ __forceinline__ unsigned long long composite(uint32_t key, uint32_t idx) {
   return (static_cast<unsigned long long>(key) << 32) | static_cast<unsigned long long>(0xFFFFFFFFu - idx);
 }
@@ -794,8 +800,8 @@ __device__ void phase_out_c(const CompressArgs& A, const LayerDesc& L, LayerStat
     if (sel && pos < L.k && e.y < L.n) {   // the bounds always hold when the counts are consistent
       out_idx[pos] = static_cast<int32_t>(e.y);
       out_val[pos] = __uint_as_float(e.x);
-      resid[e.y] = 0.0f;
-      if (clear_mom) mom[e.y] = 0.0f;
+      mask_store(&resid[e.y]);
+      if (clear_mom) mask_store(&mom[e.y]);
     }
     out_pos += popc64(sm);
   }
