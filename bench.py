@@ -214,6 +214,16 @@ def main():
     roofline = {"bound": "hbm", "kernel": "accumulate_kernel (fused residual/momentum accumulate + candidate collect)",
                 "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                 "traffic": None, "bytes_per_launch": vgg.alg_bytes_stream, "avg_launch_ms": k_ms}
+    # HBM bytes per launch of that kernel as counted by rocprofv3 (FETCH_SIZE + WRITE_SIZE, scaled by a
+    # copy of known size): a counter run cannot share a process with the timed run, so the figure
+    # comes from the committed summary of the same command; null if that file is not there
+    try:
+        with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic.json")) as f:
+            t = json.load(f)
+        roofline["traffic"] = t["fetch_bytes_per_launch"] + t["write_bytes_per_launch"]
+        roofline["traffic_source"] = t["source"]
+    except (OSError, ValueError, KeyError):
+        pass
 
     if args.calibrate_copy:
         src = torch.zeros(vgg.total, dtype=torch.float32, device=dev)
