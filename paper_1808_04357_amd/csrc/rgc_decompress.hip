@@ -264,7 +264,18 @@ __device__ __forceinline__ void write_tile(const GenericLds& S, const TileGeom& 
 // One tile, any number of workers, any number of entries: workers are taken in batches that fit
 // the staging buffers; every batch fetches its own offsets and entries (no prefetching).
 // S.acc must be cleared (barrier passed); ends with the tile accumulated in S.acc and a barrier.
-__device__ void tile_generic(const DecompressArgs& A, GenericLds& S, const TileGeom& g) {
+__device__ __forceinline__ uint32_t lower_bound_idx(gptr<const int32_t> idx, uint32_t count, uint32_t target) {
+  uint32_t lo = 0, hi = count;                        // idx[lo - 1] < target <= idx[hi]
+  while (lo < hi) {
+    const uint32_t mid = (lo + hi) >> 1;
+    if (static_cast<uint32_t>(idx[mid]) < target) lo = mid + 1u; else hi = mid;
+  }
+  return lo;
+}
+
+// use_table: the tile's entry ranges come from the offset table (built when this kernel does
+// every tile); otherwise from two binary searches per worker (a few listed tiles only).
+__device__ void tile_generic(const DecompressArgs& A, GenericLds& S, const TileGeom& g, bool use_table) {
   const uint32_t tid = threadIdx.x;
   const uint32_t N = A.num_workers;
   uint32_t w0 = 0;
@@ -275,9 +286,15 @@ __device__ void tile_generic(const DecompressArgs& A, GenericLds& S, const TileG
     const float* vp = nullptr;
     if (tid < nb) {
       const MsgDesc md = A.msgs[static_cast<size_t>(g.layer) * N + w0 + tid];
-      const uint32_t* row = A.tab + static_cast<size_t>(w0 + tid) * A.tab_stride + g.row;
-      s = row[0];
-      uint32_t e = row[1];
+      uint32_t e;
+      if (use_table) {
+        const uint32_t* row = A.tab + static_cast<size_t>(w0 + tid) * A.tab_stride + g.row;
+        s = row[0];
+        e = row[1];
+      } else {
+        s = lower_bound_idx(as_global(md.idx), md.count, g.first);
+        e = lower_bound_idx(as_global(md.idx), md.count, g.first + g.len);
+      }
       if (e > md.count) e = md.count;     // the table never exceeds the message; stay in bounds anyway
       c = e > s ? e - s : 0u;
       ip = md.idx;
@@ -422,27 +439,47 @@ __global__ void __launch_bounds__(kBlockThreads) decompress_table_kernel(Decompr
 }
 
 // ------------------------------------------------------------------ tile accumulation, fast path
+namespace {
+
+// Sum over the four lanes of a quad (lanes 4k .. 4k+3), in every lane of it.
+__device__ __forceinline__ uint32_t quad_sum(uint32_t v) {
+  v += static_cast<uint32_t>(__builtin_amdgcn_mov_dpp(static_cast<int>(v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+  v += static_cast<uint32_t>(__builtin_amdgcn_mov_dpp(static_cast<int>(v), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+  return v;
+}
+
+__device__ __forceinline__ uint32_t quad_lane0(uint32_t v) {
+  return static_cast<uint32_t>(__builtin_amdgcn_mov_dpp(static_cast<int>(v), 0x00, 0xF, 0xF, true));  // quad_perm [0,0,0,0]
+}
+
+}  // namespace
+
+// A workgroup owns a contiguous range of tiles and walks through it once.  Four neighbouring lanes
+// serve one worker and keep a window of its message in registers: two blocks of 16 consecutive
+// entries (block b in slot b & 1, four entries per lane), so that a block comes from memory once,
+// as one 64-byte piece per array, and serves the four or so tiles its entries fall into.  E is
+// the number of the worker's entries that lie before the current tile; the window is the two
+// blocks starting at the one that holds entry E, and the blocks that enter it are loaded while
+// the tile is being finished.  There is no per-tile offset table: E starts from a binary search
+// at the first tile of a layer and then advances by what each tile consumes.
 __global__ void __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(6, 6)))
 decompress_tiles_kernel(DecompressArgs A) {
   __shared__ FastLds S;
-  const uint32_t tid = threadIdx.x, lane = tid & 63u;
+  const uint32_t tid = threadIdx.x;
   const uint32_t N = A.num_workers;                    // 1 .. kBatchWorkers (the host checks)
-  uint32_t t_first, t_last, stride;
-  tiles_of_workgroup(A.num_tiles, t_first, t_last, stride);
-  // A worker has T = 2^tpw_shift threads, T * kFastR >= 16 entries per tile.  Its first T/2 are
-  // neighbouring lanes in the lower four waves, the others sit in the same lanes of the upper
-  // four: a worker seldom has more than T/2 * kFastR entries in a tile, so the upper waves
-  // mostly have nothing to do and skip the per-entry work, while the 16-byte pieces that
-  // neighbouring lanes load from a message are adjacent (a line or two per worker and wave).
-  uint32_t tpw_shift = 2;
-  while (tpw_shift < 7u && (N << (tpw_shift + 1u)) <= kFastThreads) ++tpw_shift;
-  const uint32_t half_shift = tpw_shift - 1u, tph = 1u << half_shift;   // threads per worker in one half
-  const uint32_t upper = tid >> (kFastShift - 1u);
-  const uint32_t wl = (tid & (kFastThreads / 2u - 1u)) >> half_shift;
-  const uint32_t part = (tid & (tph - 1u)) + upper * tph;
-  const uint32_t tpw = 2u * tph;
+  // this workgroup's tiles: a contiguous piece of its XCD's contiguous range
+  uint32_t t_first, t_last;
+  {
+    const uint32_t xcd = blockIdx.x & 7u, slot = blockIdx.x >> 3, slots = gridDim.x >> 3;
+    const uint32_t per_xcd = (A.num_tiles + 7u) >> 3;
+    const uint32_t x0 = xcd * per_xcd < A.num_tiles ? xcd * per_xcd : A.num_tiles;
+    const uint32_t x1 = x0 + per_xcd < A.num_tiles ? x0 + per_xcd : A.num_tiles;
+    const uint32_t per_slot = (x1 - x0 + slots - 1u) / slots;
+    t_first = x0 + slot * per_slot < x1 ? x0 + slot * per_slot : x1;
+    t_last = t_first + per_slot < x1 ? t_first + per_slot : x1;
+  }
+  const uint32_t wl = tid >> 2, q = tid & 3u;          // worker, lane of the worker
   const bool has_worker = wl < N;
-  const int lead_lane4 = static_cast<int>((lane & ~(tph - 1u)) * 4u);   // the worker's first lane in this wave, as a byte address for ds_bpermute
   const uint32_t row_groups = (N + 3u) / 4u;           // a row's slots, in groups of four
 
   for (uint32_t i = tid; i < static_cast<uint32_t>(kTile); i += kFastThreads) S.acc[i] = 0.0f;
@@ -452,6 +489,9 @@ decompress_tiles_kernel(DecompressArgs A) {
   __syncthreads();
   uint32_t par = 0;                                    // which set of maps the current tile uses
 
+  typedef uint32_t vu4 __attribute__((ext_vector_type(4), aligned(4)));
+  typedef float vf4u __attribute__((ext_vector_type(4), aligned(4)));
+
   uint32_t tile_id = t_first;
   while (tile_id < t_last) {
     // ---- a run of this workgroup's tiles inside one layer
@@ -459,10 +499,6 @@ decompress_tiles_kernel(DecompressArgs A) {
     const DecompressLayer L = A.layers[layer];
     const uint32_t run_end = (L.tile_base + L.tiles) < t_last ? (L.tile_base + L.tiles) : t_last;
 
-    // Thread (worker wl, part) owns, of its worker's entries inside a tile, the groups of four
-    // consecutive entries number part, part + T, ..., kFastR entries at most, fetched with one
-    // 16-byte load per group and array.  They are loaded into registers while the previous
-    // tile is being finished and stay there.
     uint32_t my_count = 0;
     gptr<const int32_t> my_idx = nullptr;
     gptr<const float> my_val = nullptr;
@@ -472,77 +508,51 @@ decompress_tiles_kernel(DecompressArgs A) {
       my_val = as_global(md.val);
       my_count = md.count;
     }
-    const gptr<const uint32_t> tab = as_global(A.tab);
-    const uint32_t tab_w = (has_worker ? wl : 0u) * A.tab_stride;   // the host keeps the table below 2^32 words
-    const uint32_t row0 = L.row_base + (tile_id - L.tile_base);
-    uint32_t r_start = 0, r_end = 0;             // entry range of the tile being fetched
-    uint32_t r_start2 = 0, r_end2 = 0;           // entry range of this workgroup's tile after it
-    // a worker's first lane of each wave reads the table for the others
-    auto table_at = [&](uint32_t row, uint32_t& first, uint32_t& last) {
-      uint32_t a = 0, b = 0;
-      if (has_worker && (part & (tph - 1u)) == 0u) {
-        typedef uint32_t vu2u __attribute__((ext_vector_type(2), aligned(4)));
-        const vu2u ab = *reinterpret_cast<gptr<const vu2u>>(tab + (tab_w + row));   // one access for both
-        a = ab.x;
-        b = ab.y;
-      }
-      first = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(lead_lane4, static_cast<int>(a)));
-      last = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(lead_lane4, static_cast<int>(b)));
-    };
-    table_at(row0, r_start, r_end);
-    if (tile_id + stride < run_end) table_at(row0 + stride, r_start2, r_end2);
+    // E: entries of the worker before the run's first tile (the messages are sorted by index)
+    uint32_t E = 0;
+    if (q == 0u) E = lower_bound_idx(my_idx, my_count, (tile_id - L.tile_base) << kTileShift);
+    E = quad_lane0(E);
 
-    uint32_t e_idx[kFastR];                      // index as loaded, then the position in the tile
-    float e_val[kFastR];
-    uint32_t e_cnt = 0;                          // how many of them exist (this thread)
-    uint32_t e_start = 0, e_c = 0;               // the worker's entries in that tile: first, how many
-    typedef uint32_t vu4 __attribute__((ext_vector_type(4), aligned(4)));
-    typedef float vf4u __attribute__((ext_vector_type(4), aligned(4)));
-    auto fetch = [&]() {
-      const uint32_t e1 = r_end < my_count ? r_end : my_count;   // the table never exceeds the message; stay in bounds anyway
-      const uint32_t c = e1 > r_start ? e1 - r_start : 0u;
-      e_start = r_start;
-      e_c = c;
-      e_cnt = 0;
+    // the window: slot s holds block have[s] (kNone: nothing), this lane its entries 4q .. 4q+3
+    uint32_t b_idx[2][4];
+    float b_val[2][4];
+    uint32_t have[2] = {kNone, kNone};
 #pragma unroll
-      for (uint32_t r = 0; r < kFastR / 4u; ++r) {
-        const uint32_t off = 4u * (part + r * tpw);          // first entry of this group inside the tile
+    for (uint32_t sl = 0; sl < 2u; ++sl)
 #pragma unroll
-        for (uint32_t j = 0; j < 4u; ++j) { e_idx[4u * r + j] = 0; e_val[4u * r + j] = 0.0f; }
-        if (off < c) {
-          const uint32_t at = r_start + off;
-          const uint32_t have = (c - off) < 4u ? (c - off) : 4u;
-          if (at + 4u <= my_count) {                         // the 16-byte load stays inside the message
+      for (uint32_t r = 0; r < 4u; ++r) { b_idx[sl][r] = kNone; b_val[sl][r] = 0.0f; }
+    // Bring the blocks that hold entries E .. (two blocks) into their slots; entries past the
+    // end of the message read as index kNone, which no tile contains.
+    auto fill_window = [&]() {
+      const uint32_t bc = E >> 4;
+#pragma unroll
+      for (uint32_t sl = 0; sl < 2u; ++sl) {
+        const uint32_t want = bc + ((sl ^ bc) & 1u);
+        if (want != have[sl]) {
+          have[sl] = want;
+          const uint32_t at = want * 16u + 4u * q;
+          if (at + 4u <= my_count) {
             const vu4 qi = *reinterpret_cast<gptr<const vu4>>(my_idx + at);
             const vf4u qv = *reinterpret_cast<gptr<const vf4u>>(my_val + at);
-            e_idx[4u * r + 0] = qi.x; e_idx[4u * r + 1] = qi.y; e_idx[4u * r + 2] = qi.z; e_idx[4u * r + 3] = qi.w;
-            e_val[4u * r + 0] = qv.x; e_val[4u * r + 1] = qv.y; e_val[4u * r + 2] = qv.z; e_val[4u * r + 3] = qv.w;
+            b_idx[sl][0] = qi.x; b_idx[sl][1] = qi.y; b_idx[sl][2] = qi.z; b_idx[sl][3] = qi.w;
+            b_val[sl][0] = qv.x; b_val[sl][1] = qv.y; b_val[sl][2] = qv.z; b_val[sl][3] = qv.w;
           } else {
 #pragma unroll
-            for (uint32_t j = 0; j < 4u; ++j) {
-              if (j < have) {
-                e_idx[4u * r + j] = static_cast<uint32_t>(my_idx[at + j]);
-                e_val[4u * r + j] = my_val[at + j];
+            for (uint32_t r = 0; r < 4u; ++r) {
+              b_idx[sl][r] = kNone;
+              b_val[sl][r] = 0.0f;
+              if (at + r < my_count) {
+                b_idx[sl][r] = static_cast<uint32_t>(my_idx[at + r]);
+                b_val[sl][r] = my_val[at + r];
               }
             }
           }
-          e_cnt = 4u * r + have;
         }
       }
     };
-    // Start fetching this workgroup's next tile of the run (and the table entries of the one after).
-    auto fetch_next = [&](uint32_t cur_tile) {
-      if (cur_tile + stride < run_end) {
-        r_start = r_start2;
-        r_end = r_end2;
-        if (cur_tile + 2u * stride < run_end)
-          table_at(L.row_base + (cur_tile - L.tile_base) + 2u * stride, r_start2, r_end2);
-        fetch();
-      }
-    };
-    fetch();
+    fill_window();
 
-    for (; tile_id < run_end; tile_id += stride, par ^= 1u) {
+    for (; tile_id < run_end; ++tile_id, par ^= 1u) {
       const TileGeom g = tile_geom(L, layer, tile_id);
       uint32_t* const seen = S.seen[par];
       uint32_t* const cb = S.cb[par];
@@ -552,30 +562,38 @@ decompress_tiles_kernel(DecompressArgs A) {
         const uint32_t bit = 1u << (p & 31u);
         if (atomicOr(&seen[p >> 5], bit) & bit) {
           if (!(atomicOr(&cb[p >> 5], bit) & bit)) {
-            const uint32_t q = atomicAdd(&S.nq[par], 1u);
-            if (q < kRows) { S.qmap[p] = static_cast<uint8_t>(q); S.run_p[q] = static_cast<uint16_t>(p); }
+            const uint32_t qq = atomicAdd(&S.nq[par], 1u);
+            if (qq < kRows) { S.qmap[p] = static_cast<uint8_t>(qq); S.run_p[qq] = static_cast<uint16_t>(p); }
           }
         }
       };
-      if (e_cnt != 0u) {
+      uint32_t mine = 0;                           // entries of this lane inside the tile
+      uint32_t last_in = 0;                        // the window's last entry is inside the tile
 #pragma unroll
-        for (uint32_t r = 0; r < kFastR; ++r) {
-          uint32_t p = kNone;
-          if (r < e_cnt) {
-            p = e_idx[r] - g.first;
-            if (p < g.len) mark(p); else p = kNone;
-          }
-          e_idx[r] = p;
-        }
-        // a worker with more entries in this tile than its threads hold (rare): the further
-        // groups come straight from memory, here and again below
-        for (uint32_t off = 4u * (part + tpw); off < e_c; off += 4u * tpw) {
-          for (uint32_t j = 0; j < 4u && off + j < e_c; ++j) {
-            const uint32_t p = static_cast<uint32_t>(my_idx[e_start + off + j]) - g.first;
-            if (p < g.len) mark(p);
+      for (uint32_t sl = 0; sl < 2u; ++sl) {
+#pragma unroll
+        for (uint32_t r = 0; r < 4u; ++r) {
+          const uint32_t p = b_idx[sl][r] - g.first;
+          if (p < g.len) {
+            mark(p);
+            ++mine;
+            if (r == 3u && q == 3u && have[sl] == (E >> 4) + 1u) last_in = 1u;
           }
         }
       }
+      // the worker's entries inside the tile go on beyond the window (rare): straight from memory,
+      // here and again below
+      const uint32_t beyond = (E >> 4) * 16u + 32u;
+      const bool more = quad_sum(last_in) != 0u;
+      if (more) {
+        for (uint32_t e = beyond + q; e < my_count; e += 4u) {
+          const uint32_t p = static_cast<uint32_t>(my_idx[e]) - g.first;
+          if (p >= g.len) break;
+          mark(p);
+          ++mine;
+        }
+      }
+      const uint32_t consumed = quad_sum(mine);
       __syncthreads();
       const uint32_t nq = S.nq[par];
       // ---- clear the maps the previous tile used
@@ -583,31 +601,39 @@ decompress_tiles_kernel(DecompressArgs A) {
       if (tid < kWords) { S.seen[par ^ 1u][tid] = 0u; S.cb[par ^ 1u][tid] = 0u; }
       if (nq > kRows) {
         push_generic(A, tile_id);
-        fetch_next(tile_id);
+        E += consumed;
+        fill_window();
         __syncthreads();                         // the clears above end before the next tile marks
         continue;
       }
       // ---- positions hit once are final; the others put their value into their worker's slot of the row
-      if (e_cnt != 0u) {
-        const uint32_t my_slot = (fresh_tid() & (kFastThreads / 2u - 1u)) >> half_shift;   // = wl
+      if (mine != 0u) {
+        const uint32_t my_slot = fresh_tid() >> 2;   // = wl
         auto place = [&](uint32_t p, float v) {
           const uint32_t colliding = nq != 0u ? (cb[p >> 5] >> (p & 31u)) & 1u : 0u;
           if (!colliding) S.acc[p] = __fadd_rn(0.0f, v);
           else S.rows[static_cast<uint32_t>(S.qmap[p]) * kRowStride + my_slot] = v;
         };
 #pragma unroll
-        for (uint32_t r = 0; r < kFastR; ++r)
-          if (e_idx[r] != kNone) place(e_idx[r], e_val[r]);
-        for (uint32_t off = 4u * (part + tpw); off < e_c; off += 4u * tpw) {
-          for (uint32_t j = 0; j < 4u && off + j < e_c; ++j) {
-            const uint32_t p = static_cast<uint32_t>(my_idx[e_start + off + j]) - g.first;
-            if (p < g.len) place(p, my_val[e_start + off + j]);
+        for (uint32_t sl = 0; sl < 2u; ++sl) {
+#pragma unroll
+          for (uint32_t r = 0; r < 4u; ++r) {
+            const uint32_t p = b_idx[sl][r] - g.first;
+            if (p < g.len) place(p, b_val[sl][r]);
+          }
+        }
+        if (more) {
+          for (uint32_t e = beyond + q; e < my_count; e += 4u) {
+            const uint32_t p = static_cast<uint32_t>(my_idx[e]) - g.first;
+            if (p >= g.len) break;
+            place(p, my_val[e]);
           }
         }
       }
       __syncthreads();
-      // the entries are used up: their registers take the next tile's
-      fetch_next(tile_id);
+      // the tile's entries are used up: move the window on; its new blocks arrive while the tile is finished
+      E += consumed;
+      fill_window();
       if (nq != 0u) {
         // ---- one lane per colliding position adds its row in worker order; the slots of the
         // workers that did not hit it hold +0, which leaves every partial sum as it is (a
@@ -620,12 +646,12 @@ decompress_tiles_kernel(DecompressArgs A) {
           vf4 c0 = r4[0], c1 = r4[1];            // the next eight slots are on their way while these are added
           for (;;) {
             gi += 2u;
-            const bool more = gi < row_groups;
+            const bool again = gi < row_groups;
             vf4 n0 = c0, n1 = c1;
-            if (more) { n0 = r4[gi]; n1 = r4[gi + 1u]; }
+            if (again) { n0 = r4[gi]; n1 = r4[gi + 1u]; }
             sum = __fadd_rn(__fadd_rn(__fadd_rn(__fadd_rn(sum, c0.x), c0.y), c0.z), c0.w);
             sum = __fadd_rn(__fadd_rn(__fadd_rn(__fadd_rn(sum, c1.x), c1.y), c1.z), c1.w);
-            if (!more) break;
+            if (!again) break;
             c0 = n0; c1 = n1;
           }
           S.acc[S.run_p[row]] = sum;
@@ -682,7 +708,7 @@ __global__ void __launch_bounds__(kBlockThreads) decompress_generic_kernel(Decom
     const TileGeom g = tile_geom(A.layers[layer], layer, tile_id);
     clear_tile(S);
     __syncthreads();
-    tile_generic(A, S, g);
+    tile_generic(A, S, g, all_tiles != 0u);
     write_tile(S, g, A.scale, A.add_to_dst);
     __syncthreads();
   };
@@ -704,7 +730,8 @@ __global__ void __launch_bounds__(kBlockThreads) decompress_generic_kernel(Decom
 }
 
 hipError_t launch_decompress_table(const DecompressArgs& a, hipStream_t s) {
-  if (a.num_blocks == 0) return hipSuccess;
+  // only the kernel that takes any number of workers reads the table
+  if (a.num_blocks == 0 || a.num_workers <= static_cast<uint32_t>(kBatchWorkers)) return hipSuccess;
   hipLaunchKernelGGL(decompress_table_kernel, dim3(a.num_blocks), dim3(kBlockThreads), 0, s, a);
   return hipGetLastError();
 }
