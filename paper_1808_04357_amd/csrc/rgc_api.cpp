@@ -349,6 +349,7 @@ int rgc_destroy(rgc_ctx* ctx) {
   if (ctx->dplan.uploaded) { (void)hipEventSynchronize(ctx->dplan.uploaded); (void)hipEventDestroy(ctx->dplan.uploaded); }
   ctx->dplan.d_tables.release();
   ctx->dplan.d_tab.release();
+  ctx->dplan.d_gen.release();
   ctx->dplan.staging.release();
   ctx->d_state.release();
   ctx->d_hist.release();
@@ -579,7 +580,8 @@ int rgc_decompress_accumulate(rgc_ctx* ctx, const rgc_msg* msgs, int32_t num_wor
       if (e == hipErrorOutOfMemory) { (void)hipGetLastError(); return RGC_ENOMEM; }
       RGC_HIP(e);
     }
-    if (P.d_tab.n < tab_words) {
+    const bool need_table = num_workers > kBatchWorkers;   // only the any-number-of-workers kernel reads it
+    if (need_table && P.d_tab.n < tab_words) {
       hipError_t e = P.d_tab.alloc(tab_words);
       if (e == hipErrorOutOfMemory) { (void)hipGetLastError(); return RGC_ENOMEM; }
       RGC_HIP(e);

@@ -9,21 +9,18 @@
 // upwards.  Adding +0 leaves a partial sum as it is, so this is the sequential sum over the
 // workers bit for bit, independent of scheduling; no floating-point atomics are used.
 //
-// A first kernel builds a table with the offset of the first entry of every tile in every
-// (worker, layer) message (the messages are sorted by index); one row per worker, so the
-// builder's stores fall into the same cache lines.
-//
-// The tile kernel is persistent and XCD-aware: every XCD gets one contiguous range of tiles and
-// its workgroups take them round-robin, so neighbouring tiles share table and message cache
-// lines inside one L2.  Inside a run of tiles of one layer the kernel is software pipelined:
-// while tile i is processed, the entries of tile i+1 are already being loaded into registers
-// and the table entries of tile i+2 are in flight.  What bounds it is the number of small
-// gathers (one 16- or 32-byte piece per worker, tile and array, each an L1 miss), not the LDS
-// work: the thread-to-worker mapping is chosen to make those gathers few and adjacent.
+// The fast kernel (up to kBatchWorkers workers) is persistent and XCD-aware: every XCD gets one
+// contiguous range of tiles and every workgroup a contiguous piece of it, which it walks through
+// once.  Four lanes serve one worker and keep a window of its (sorted) message in registers, so
+// a message is read once, front to back, in 64-byte pieces, and no table of per-tile offsets is
+// needed: a binary search finds where the workgroup's first tile of a layer starts, afterwards
+// the count of consumed entries says where the next tile starts.  Blocks that enter the window
+// are loaded while the current tile is being finished.
 //
 // Tiles the fast kernel cannot take (more colliding positions than it has rows) are appended to
 // a list and redone by a second kernel, which sorts the colliding entries by rank in a worker
-// bitmask instead; with more than kBatchWorkers workers that kernel does every tile.
+// bitmask instead.  With more than kBatchWorkers workers that kernel does every tile, from a table
+// of per-tile offsets that a third kernel builds first.
 #include "rgc_device.h"
 
 namespace rgc {
