@@ -132,6 +132,40 @@ def test_dense_messages_exceed_staging(rgc, oracle):
     ctx.close()
 
 
+def test_window_overflow_mixed_with_sparse_and_empty_workers(rgc, oracle):
+    """128 workers over 49 tiles: most send a few scattered entries, some send nothing, some
+    have a burst of 100 consecutive indices (more entries in one tile than a worker's register
+    window holds, next to workers that have one or none there)."""
+    g = np.random.default_rng(10)
+    n, N = 200_000, 128
+    idx, val = [], []
+    for w in range(N):
+        if w % 11 == 3:
+            ii = np.empty(0, np.int64)
+        else:
+            ii = g.choice(n, size=int(g.integers(1, 400)), replace=False)
+            if w % 5 == 0:
+                start = int(g.integers(0, n - 100))
+                ii = np.concatenate([ii, np.arange(start, start + 100)])
+            ii = np.unique(ii)
+        idx.append([ii.astype(np.int32)])
+        val.append([g.standard_normal(ii.size).astype(np.float32)])
+    ctx = rgc.Context(1024, 1)
+    compare("mixed", gpu_decompress(rgc, ctx, idx, val, [n], 1.0 / N), oracle_all(oracle, idx, val, [n], 1.0 / N))
+    ctx.close()
+
+
+def test_uniform_messages_many_two_way_collisions(rgc, oracle):
+    """128 workers x 0.1 % of 2 Mi uniformly drawn positions: ~33 positions per tile are hit twice
+    (around the number of rows the fast kernel has), a few tiles exceed it."""
+    g = np.random.default_rng(11)
+    n, N = 1 << 21, 128
+    idx, val = random_messages(g, [n], N, [n // 1000])
+    ctx = rgc.Context(1024, 1)
+    compare("uniform", gpu_decompress(rgc, ctx, idx, val, [n], 1.0 / N), oracle_all(oracle, idx, val, [n], 1.0 / N))
+    ctx.close()
+
+
 def test_roundtrip_with_compress(rgc, oracle):
     import torch
     g = np.random.default_rng(9)
