@@ -133,8 +133,6 @@ struct DecompressPlan {
   int32_t workers = 0, layers = 0;
   DevBuf<unsigned char> d_tables;   // MsgDesc[], DecompressLayer[], BlockDesc[]
   DevBuf<uint32_t> d_tab;
-  DevBuf<uint32_t> d_gen;           // generic-tile list, then its two counters
-  bool gen_zeroed = false;
   PinnedBuf staging;
   hipEvent_t uploaded = nullptr;
   DecompressArgs args{};
@@ -349,7 +347,6 @@ int rgc_destroy(rgc_ctx* ctx) {
   if (ctx->dplan.uploaded) { (void)hipEventSynchronize(ctx->dplan.uploaded); (void)hipEventDestroy(ctx->dplan.uploaded); }
   ctx->dplan.d_tables.release();
   ctx->dplan.d_tab.release();
-  ctx->dplan.d_gen.release();
   ctx->dplan.staging.release();
   ctx->d_state.release();
   ctx->d_hist.release();
@@ -586,17 +583,6 @@ int rgc_decompress_accumulate(rgc_ctx* ctx, const rgc_msg* msgs, int32_t num_wor
       if (e == hipErrorOutOfMemory) { (void)hipGetLastError(); return RGC_ENOMEM; }
       RGC_HIP(e);
     }
-    if (P.d_gen.n < tiles + 2u) {
-      hipError_t e = P.d_gen.alloc(tiles + 2u);
-      if (e == hipErrorOutOfMemory) { (void)hipGetLastError(); return RGC_ENOMEM; }
-      RGC_HIP(e);
-      P.gen_zeroed = false;
-    }
-    if (!P.gen_zeroed) {
-      // the two counters sit in front of the list; the generic kernel leaves them at zero
-      RGC_HIP(hipMemsetAsync(P.d_gen.p, 0, 2 * sizeof(uint32_t), stream));
-      P.gen_zeroed = true;
-    }
     char* base = static_cast<char*>(P.staging.p);
     MsgDesc* hm = reinterpret_cast<MsgDesc*>(base + off_msgs);
     DecompressLayer* hl = reinterpret_cast<DecompressLayer*>(base + off_layers);
@@ -637,9 +623,6 @@ int rgc_decompress_accumulate(rgc_ctx* ctx, const rgc_msg* msgs, int32_t num_wor
     A.layers = reinterpret_cast<const DecompressLayer*>(P.d_tables.p + off_layers);
     A.blocks = reinterpret_cast<const BlockDesc*>(P.d_tables.p + off_blocks);
     A.tab = P.d_tab.p;
-    A.gen_count = P.d_gen.p;
-    A.gen_done = P.d_gen.p + 1;
-    A.gen_list = P.d_gen.p + 2;
     A.tab_stride = static_cast<uint32_t>(stride);
     {
       hipDeviceProp_t prop;

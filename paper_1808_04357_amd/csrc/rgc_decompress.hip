@@ -17,10 +17,10 @@
 // the count of consumed entries says where the next tile starts.  Blocks that enter the window
 // are loaded while the current tile is being finished.
 //
-// Tiles the fast kernel cannot take (more colliding positions than it has rows) are appended to
-// a list and redone by a second kernel, which sorts the colliding entries by rank in a worker
-// bitmask instead.  With more than kBatchWorkers workers that kernel does every tile, from a table
-// of per-tile offsets that a third kernel builds first.
+// A tile with more colliding positions than the kernel has rows (rare) takes them a row-set at a
+// time.  With more than kBatchWorkers workers a second kernel does the job instead: workers in
+// batches, colliding entries sorted by their rank in a per-position worker bitmask, entry ranges
+// from a table of per-tile offsets that a third kernel builds first.
 #include "rgc_device.h"
 
 namespace rgc {
@@ -270,9 +270,7 @@ __device__ __forceinline__ uint32_t lower_bound_idx(gptr<const int32_t> idx, uin
   return lo;
 }
 
-// use_table: the tile's entry ranges come from the offset table (built when this kernel does
-// every tile); otherwise from two binary searches per worker (a few listed tiles only).
-__device__ void tile_generic(const DecompressArgs& A, GenericLds& S, const TileGeom& g, bool use_table) {
+__device__ void tile_generic(const DecompressArgs& A, GenericLds& S, const TileGeom& g) {
   const uint32_t tid = threadIdx.x;
   const uint32_t N = A.num_workers;
   uint32_t w0 = 0;
@@ -283,15 +281,9 @@ __device__ void tile_generic(const DecompressArgs& A, GenericLds& S, const TileG
     const float* vp = nullptr;
     if (tid < nb) {
       const MsgDesc md = A.msgs[static_cast<size_t>(g.layer) * N + w0 + tid];
-      uint32_t e;
-      if (use_table) {
-        const uint32_t* row = A.tab + static_cast<size_t>(w0 + tid) * A.tab_stride + g.row;
-        s = row[0];
-        e = row[1];
-      } else {
-        s = lower_bound_idx(as_global(md.idx), md.count, g.first);
-        e = lower_bound_idx(as_global(md.idx), md.count, g.first + g.len);
-      }
+      const uint32_t* row = A.tab + static_cast<size_t>(w0 + tid) * A.tab_stride + g.row;
+      s = row[0];
+      uint32_t e = row[1];
       if (e > md.count) e = md.count;     // the table never exceeds the message; stay in bounds anyway
       c = e > s ? e - s : 0u;
       ip = md.idx;
@@ -382,6 +374,7 @@ struct alignas(16) FastLds {
   uint32_t cb[2][kWords];                    // positions hit more than once
   uint32_t nq[2];                            // how many of those
   uint16_t run_p[kRows];                     // the position a row belongs to
+  uint32_t pre_cb[kWords];                   // exclusive popcount prefix of cb (only when the rows do not suffice)
   uint8_t qmap[kTile];                       // the row of a colliding position (valid where cb is set)
 };
 static_assert(sizeof(FastLds) <= 53 * 1024, "three 8-wave workgroups per CU");
@@ -394,13 +387,6 @@ __device__ __forceinline__ uint32_t fresh_tid() {
   uint32_t t = threadIdx.x;
   asm volatile("" : "+v"(t));
   return t;
-}
-
-__device__ __forceinline__ void push_generic(const DecompressArgs& A, uint32_t tile_id) {
-  if (threadIdx.x == 0) {
-    const uint32_t at = atomicAdd(A.gen_count, 1u);
-    if (at < A.num_tiles) A.gen_list[at] = tile_id;
-  }
 }
 
 }  // namespace
@@ -596,47 +582,12 @@ decompress_tiles_kernel(DecompressArgs A) {
       // ---- clear the maps the previous tile used
       if (tid == 0u) S.nq[par ^ 1u] = 0u;
       if (tid < kWords) { S.seen[par ^ 1u][tid] = 0u; S.cb[par ^ 1u][tid] = 0u; }
-      if (nq > kRows) {
-        push_generic(A, tile_id);
-        E += consumed;
-        fill_window();
-        __syncthreads();                         // the clears above end before the next tile marks
-        continue;
-      }
-      // ---- positions hit once are final; the others put their value into their worker's slot of the row
-      if (mine != 0u) {
-        const uint32_t my_slot = fresh_tid() >> 2;   // = wl
-        auto place = [&](uint32_t p, float v) {
-          const uint32_t colliding = nq != 0u ? (cb[p >> 5] >> (p & 31u)) & 1u : 0u;
-          if (!colliding) S.acc[p] = __fadd_rn(0.0f, v);
-          else S.rows[static_cast<uint32_t>(S.qmap[p]) * kRowStride + my_slot] = v;
-        };
-#pragma unroll
-        for (uint32_t sl = 0; sl < 2u; ++sl) {
-#pragma unroll
-          for (uint32_t r = 0; r < 4u; ++r) {
-            const uint32_t p = b_idx[sl][r] - g.first;
-            if (p < g.len) place(p, b_val[sl][r]);
-          }
-        }
-        if (more) {
-          for (uint32_t e = beyond + q; e < my_count; e += 4u) {
-            const uint32_t p = static_cast<uint32_t>(my_idx[e]) - g.first;
-            if (p >= g.len) break;
-            place(p, my_val[e]);
-          }
-        }
-      }
-      __syncthreads();
-      // the tile's entries are used up: move the window on; its new blocks arrive while the tile is finished
-      E += consumed;
-      fill_window();
-      if (nq != 0u) {
-        // ---- one lane per colliding position adds its row in worker order; the slots of the
-        // workers that did not hit it hold +0, which leaves every partial sum as it is (a
-        // partial sum is never -0)
+      // one lane per row adds the row's slots in worker order; the slots of the workers that did
+      // not hit the position hold +0, which leaves every partial sum as it is (a partial sum is
+      // never -0)
+      auto sum_rows = [&](uint32_t count) {
         const uint32_t row = fresh_tid();
-        if (row < nq) {
+        if (row < count) {
           const vf4* const r4 = reinterpret_cast<const vf4*>(S.rows + row * kRowStride);
           float sum = 0.0f;
           uint32_t gi = 0;
@@ -655,8 +606,73 @@ decompress_tiles_kernel(DecompressArgs A) {
         }
         __syncthreads();
         // the rows go back to +0
-        for (uint32_t i = row; i < nq * (kRowStride / 4u); i += kFastThreads)
+        for (uint32_t i = row; i < count * (kRowStride / 4u); i += kFastThreads)
           reinterpret_cast<vf4*>(S.rows)[i] = vf4{0.0f, 0.0f, 0.0f, 0.0f};
+      };
+      // run f(position, value) over this lane's entries inside the tile
+      auto for_my_entries = [&](auto&& f) {
+        if (mine == 0u) return;
+        uint32_t first = g.first;
+        asm volatile("" : "+s"(first));          // recompute the positions here rather than keep (and spill) them
+#pragma unroll
+        for (uint32_t sl = 0; sl < 2u; ++sl) {
+#pragma unroll
+          for (uint32_t r = 0; r < 4u; ++r) {
+            const uint32_t p = b_idx[sl][r] - first;
+            if (p < g.len) f(p, b_val[sl][r]);
+          }
+        }
+        if (more) {
+          for (uint32_t e = beyond + q; e < my_count; e += 4u) {
+            const uint32_t p = static_cast<uint32_t>(my_idx[e]) - first;
+            if (p >= g.len) break;
+            f(p, my_val[e]);
+          }
+        }
+      };
+      if (nq > kRows) {
+        // ---- more colliding positions than rows (rare): they are taken kRows at a time, numbered by
+        // position (popcount prefix over the bitmap; every wave computes the same prefix and writes
+        // it, so it may read it back at once)
+        {
+          const uint32_t ln = fresh_tid() & 63u;
+          const vu2l cw = *reinterpret_cast<const vu2l*>(&cb[2u * ln]);
+          const uint32_t c0 = static_cast<uint32_t>(__popc(cw.x)), c1 = static_cast<uint32_t>(__popc(cw.y));
+          const uint32_t incl = wave_incl_scan(c0 + c1);
+          *reinterpret_cast<vu2l*>(&S.pre_cb[2u * ln]) = vu2l{incl - c0 - c1, incl - c1};
+        }
+        const uint32_t my_slot = fresh_tid() >> 2;   // = wl
+        for (uint32_t d0 = 0; d0 < nq; d0 += kRows) {
+          for_my_entries([&](uint32_t p, float v) {
+            const uint32_t word = cb[p >> 5], sh = p & 31u;
+            if (!((word >> sh) & 1u)) {
+              if (d0 == 0u) S.acc[p] = __fadd_rn(0.0f, v);
+            } else {
+              const uint32_t d = S.pre_cb[p >> 5] + static_cast<uint32_t>(__popc(word & ((1u << sh) - 1u))) - d0;
+              if (d < kRows) { S.rows[d * kRowStride + my_slot] = v; S.run_p[d] = static_cast<uint16_t>(p); }
+            }
+          });
+          __syncthreads();
+          sum_rows(nq - d0 < kRows ? nq - d0 : kRows);
+          __syncthreads();
+        }
+        E += consumed;
+        fill_window();
+      } else {
+        // ---- positions hit once are final; the others put their value into their worker's slot of the row
+        {
+          const uint32_t my_slot = fresh_tid() >> 2;   // = wl
+          for_my_entries([&](uint32_t p, float v) {
+            const uint32_t colliding = nq != 0u ? (cb[p >> 5] >> (p & 31u)) & 1u : 0u;
+            if (!colliding) S.acc[p] = __fadd_rn(0.0f, v);
+            else S.rows[static_cast<uint32_t>(S.qmap[p]) * kRowStride + my_slot] = v;
+          });
+        }
+        __syncthreads();
+        // the tile's entries are used up: move the window on; its new blocks arrive while the tile is finished
+        E += consumed;
+        fill_window();
+        if (nq != 0u) sum_rows(nq);
       }
       // ---- write the tile (scaled) and leave its accumulator cleared
       const bool vec = ((reinterpret_cast<uintptr_t>(g.dense) & 15u) == 0u) && ((g.len & 3u) == 0u);
@@ -696,33 +712,19 @@ decompress_tiles_kernel(DecompressArgs A) {
   }
 }
 
-// ------------------------------------------------------------------ tile accumulation, generic path
-// all_tiles != 0: every tile (the fast kernel did not run); else the tiles the fast kernel listed.
-__global__ void __launch_bounds__(kBlockThreads) decompress_generic_kernel(DecompressArgs A, uint32_t all_tiles) {
+// ------------------------------------------------------------------ tile accumulation, any number of workers
+__global__ void __launch_bounds__(kBlockThreads) decompress_generic_kernel(DecompressArgs A) {
   __shared__ GenericLds S;
-  auto one_tile = [&](uint32_t tile_id) {
+  uint32_t t_first, t_last, stride;
+  tiles_of_workgroup(A.num_tiles, t_first, t_last, stride);
+  for (uint32_t tile_id = t_first; tile_id < t_last; tile_id += stride) {
     const uint32_t layer = layer_of_tile(A, tile_id);
     const TileGeom g = tile_geom(A.layers[layer], layer, tile_id);
     clear_tile(S);
     __syncthreads();
-    tile_generic(A, S, g, all_tiles != 0u);
+    tile_generic(A, S, g);
     write_tile(S, g, A.scale, A.add_to_dst);
     __syncthreads();
-  };
-  if (all_tiles) {
-    uint32_t t_first, t_last, stride;
-    tiles_of_workgroup(A.num_tiles, t_first, t_last, stride);
-    for (uint32_t t = t_first; t < t_last; t += stride) one_tile(t);
-    return;
-  }
-  uint32_t count = ld_agent(A.gen_count);
-  if (count > A.num_tiles) count = A.num_tiles;
-  for (uint32_t i = blockIdx.x; i < count; i += gridDim.x) one_tile(A.gen_list[i]);
-  // the last workgroup to get here empties the list for the next call
-  __syncthreads();
-  if (threadIdx.x == 0 && atomicAdd(A.gen_done, 1u) + 1u == gridDim.x) {
-    st_agent(A.gen_count, 0u);
-    st_agent(A.gen_done, 0u);
   }
 }
 
@@ -754,21 +756,11 @@ hipError_t launch_decompress_tiles(const DecompressArgs& a, hipStream_t s) {
   }
   const uint32_t want = ((a.num_tiles + 7u) / 8u) * 8u;
   const uint32_t cus8 = a.cus < 8u ? 8u : (a.cus / 8u) * 8u;
-  if (a.num_workers >= 1u && a.num_workers <= static_cast<uint32_t>(kBatchWorkers)) {
-    const uint32_t cap = per_cu_fast * cus8;
-    const uint32_t grid = want < cap ? want : cap;
-    hipLaunchKernelGGL(decompress_tiles_kernel, dim3(grid), dim3(kFastThreads), 0, s, a);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    // the listed tiles are few: a small grid keeps the launch cheap when the list is empty
-    const uint32_t gcap = cus8 / 2u < 8u ? 8u : ((cus8 / 2u) / 8u) * 8u;
-    const uint32_t ggrid = want < gcap ? want : gcap;
-    hipLaunchKernelGGL(decompress_generic_kernel, dim3(ggrid), dim3(kBlockThreads), 0, s, a, 0u);
-    return hipGetLastError();
-  }
-  const uint32_t cap = per_cu_generic * cus8;
+  const bool fast = a.num_workers >= 1u && a.num_workers <= static_cast<uint32_t>(kBatchWorkers);
+  const uint32_t cap = (fast ? per_cu_fast : per_cu_generic) * cus8;
   const uint32_t grid = want < cap ? want : cap;
-  hipLaunchKernelGGL(decompress_generic_kernel, dim3(grid), dim3(kBlockThreads), 0, s, a, 1u);
+  if (fast) hipLaunchKernelGGL(decompress_tiles_kernel, dim3(grid), dim3(kFastThreads), 0, s, a);
+  else hipLaunchKernelGGL(decompress_generic_kernel, dim3(grid), dim3(kBlockThreads), 0, s, a);
   return hipGetLastError();
 }
 

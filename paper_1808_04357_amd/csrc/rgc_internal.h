@@ -135,9 +135,6 @@ struct DecompressArgs {
   const DecompressLayer* layers;
   const BlockDesc* blocks;
   uint32_t* tab;              // [workers][tab_stride]: first entry of each tile; one closing entry per layer
-  uint32_t* gen_list;         // [num_tiles] tiles left to the generic kernel by the fast one
-  uint32_t* gen_count;        // how many; zero between calls
-  uint32_t* gen_done;         // workgroups of the generic kernel that are through; zero between calls
   uint32_t tab_stride;
   uint32_t cus;               // compute units of the device (sizes the persistent grids)
   uint32_t num_workers;
