@@ -238,7 +238,9 @@ def main():
         del step
         for name, make in (("lstm", lambda: synth.config_lstm(num_grads=NUM_GRAD_SETS)),
                            ("resnet50", lambda: synth.config_resnet50(num_grads=NUM_GRAD_SETS)),
-                           ("single_1Mi", lambda: synth.config_single(1 << 20, num_grads=NUM_GRAD_SETS))):
+                           ("single_1Mi", lambda: synth.config_single(1 << 20, num_grads=NUM_GRAD_SETS)),
+                           # the value law of the paper's own selection benchmark (Figure 2), 64 Mi elements
+                           ("uniform_64Mi", lambda: synth.config_uniform(1 << 26, num_grads=NUM_GRAD_SETS))):
             log("workload %s..." % name)
             wl = CompressWorkload(torch, rgc, make(), dev)
             others[name] = measure_compress(torch, rgc, ctx, wl, stream, args.steps, args.warmup)
