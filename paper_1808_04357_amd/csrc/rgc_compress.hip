@@ -245,6 +245,9 @@ __device__ __forceinline__ uint32_t drifted_tau(uint32_t tau_rank, uint32_t T, u
   return static_cast<uint32_t>(t);
 }
 
+constexpr uint32_t kOffsetGroup = 64;   // wave-chunks whose output offsets one wave of PH_OUT_C derives by itself
+static_assert(kOffsetGroup == kWaveSize, "one lane per wave-chunk of the group");
+
 struct ResolveShared {
   uint32_t scan[4];
   uint32_t flag;
@@ -415,6 +418,9 @@ __device__ void resolve_collect(const CompressArgs& A, uint32_t l, const LayerDe
   stage_hist<kCoarseBins, kCoarseRep>(A.coarse + static_cast<size_t>(l) * kCoarseRep * kCoarseBins, lds);
   const uint32_t k = L.k, target = 2u * L.k + L.margin;   // see resolve_digit
   const uint32_t hist_total = locate_from_top(lds, kCoarseBins, k, target, sh);
+  // PH_SEL adds the selected counts of every kOffsetGroup wave-chunks up in wc_b: start from zero
+  for (uint32_t g = t; g < (L.wc_count + kOffsetGroup - 1u) / kOffsetGroup; g += kBlockThreads)
+    st_agent(&A.wc_b[L.wc_first + g], 0u);
   if (t == 0) {
     st->stat_candidates = cand_total;
     st->stat_members = sh.cnt;
@@ -491,21 +497,46 @@ __device__ void scan_chunks(uint32_t* a, uint32_t* b, uint32_t count, uint32_t r
   if (threadIdx.x == 0) *out_total = carry_a + (with_ties ? (carry_b < r ? carry_b : r) : 0u);
 }
 
-// Descending bitonic sort of n2 (power of two) 64-bit keys in LDS by 256 threads.
-__device__ void bitonic_sort_desc(unsigned long long* s, uint32_t n2) {
-  for (uint32_t size = 2; size <= n2; size <<= 1) {
-    for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
-      __syncthreads();
-      for (uint32_t i = threadIdx.x; i < (n2 >> 1); i += kBlockThreads) {
-        const uint32_t lo = 2u * i - (i & (stride - 1u));
-        const uint32_t hi = lo + stride;
-        const bool desc = ((lo & size) == 0u);
-        const unsigned long long x = s[lo], y = s[hi];
-        if ((x < y) == desc) { s[lo] = y; s[hi] = x; }
+// The kk-th largest (1-based) of the m distinct 64-bit values v[0..m) in LDS, by radix selection
+// from the top byte down: a 256-bin histogram of the values that match the bytes fixed so far,
+// a scan from the top bin, the next byte.  Stops as soon as one value is left.  (A bitonic sort
+// of the same values took 55 dependent LDS round trips; this takes a few.)  All threads of the
+// workgroup call it; hist holds 256 words.
+__device__ unsigned long long select_kth_largest(const unsigned long long* v, uint32_t m, uint32_t kk,
+                                                 uint32_t* hist, ResolveShared& sh) {
+  const uint32_t t = threadIdx.x;
+  unsigned long long prefix = 0ull;
+  for (int shift = 56; shift >= 0; shift -= 8) {
+    const unsigned long long himask = shift == 56 ? 0ull : (~0ull << (shift + 8));
+    hist[t] = 0u;
+    __syncthreads();
+    for (uint32_t i = t; i < m; i += kBlockThreads) {
+      const unsigned long long x = v[i];
+      if ((x & himask) == prefix) atomicAdd(&hist[static_cast<uint32_t>(x >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    const uint32_t h = hist[255u - t];
+    uint32_t total;
+    const uint32_t above = block_excl_scan(h, sh.scan, total);   // values in higher bins
+    if (above < kk && above + h >= kk) { sh.bin = 255u - t; sh.above = above; sh.cnt = h; }
+    __syncthreads();
+    prefix |= static_cast<unsigned long long>(sh.bin) << shift;
+    kk -= sh.above;
+    const uint32_t left = sh.cnt;
+    __syncthreads();
+    if (left == 1u && shift > 0) {
+      const unsigned long long lomask = ~0ull << shift;
+      for (uint32_t i = t; i < m; i += kBlockThreads) {
+        const unsigned long long x = v[i];
+        if ((x & lomask) == prefix) { sh.hbin = static_cast<uint32_t>(x); sh.hcum = static_cast<uint32_t>(x >> 32); }
       }
+      __syncthreads();
+      const unsigned long long r = (static_cast<unsigned long long>(sh.hcum) << 32) | sh.hbin;
+      __syncthreads();
+      return r;
     }
   }
-  __syncthreads();
+  return prefix;
 }
 
 // The zeros that mask a sent entry out of the residual (and the velocity) are isolated 4-byte
@@ -513,6 +544,8 @@ __device__ void bitonic_sort_desc(unsigned long long* s, uint32_t n2) {
 // by one while the next streaming pass runs and cost it about a tenth of its bandwidth; stored
 // with the streaming hint they leave the caches early and cost half of that.
 __device__ __forceinline__ void mask_store(gptr<float> p) { __builtin_nontemporal_store(0.0f, p); }
+
+constexpr uint32_t kListGroup = 4;   // workgroups' worth of candidate lists one workgroup of PH_SEL / PH_OUT_C takes
 
 __device__ __forceinline__ unsigned long long composite(uint32_t key, uint32_t idx) {
   return (static_cast<unsigned long long>(key) << 32) | static_cast<unsigned long long>(0xFFFFFFFFu - idx);
@@ -707,19 +740,39 @@ __device__ void phase_out_v(const CompressArgs& A, const LayerDesc& L, LayerStat
 // holds the k-th key become "members" (ranked exactly by the last workgroup), candidates of
 // higher bins are counted as certainly selected.
 __device__ void phase_sel(const CompressArgs& A, uint32_t l, const LayerDesc& L, LayerState* st,
-                          uint32_t wc_local, unsigned long long* sortbuf, ResolveShared& sh) {
+                          unsigned long long* sortbuf, uint32_t* sel_hist, ResolveShared& sh) {
+  // The lists are short (a few dozen entries), so this phase is a chain of dependent loads per
+  // workgroup and little else: one workgroup in kListGroup takes the lists of kListGroup
+  // workgroups, with the loads of all of them in flight together; the others leave at once.
+  const uint32_t wgl = blockIdx.x - L.wg_first;
+  if (wgl % kListGroup != 0u) return;
   const uint32_t tau = st->tau, shift = st->shift, bstar = st->bstar;
   unsigned long long* members = A.members + static_cast<size_t>(l) * kMemberMax;
-  const uint32_t lane = lane_id();
-  if (wc_local < L.wc_count) {
-    const uint32_t wc = L.wc_first + wc_local;
-    const uint32_t cnt = A.cand_cnt[wc];
-    const uint2* slot = A.slots + static_cast<size_t>(wc) * A.cap;
+  const uint32_t lane = lane_id(), wave = threadIdx.x >> 6;
+  if (threadIdx.x == 0) sh.hcnt = 0u;              // what this workgroup's lists add to their offset group
+  __syncthreads();
+  uint32_t wc[kListGroup], cnt[kListGroup];
+#pragma unroll
+  for (uint32_t i = 0; i < kListGroup; ++i) {
+    const uint32_t wc_local = (wgl + i) * kWavesPerBlock + wave;
+    wc[i] = L.wc_first + wc_local;
+    cnt[i] = wc_local < L.wc_count ? A.cand_cnt[wc[i]] : 0xFFFFFFFFu;   // ~0: no such list
+  }
+  uint2 first[kListGroup];
+#pragma unroll
+  for (uint32_t i = 0; i < kListGroup; ++i) {
+    first[i] = make_uint2(0u, 0u);
+    if (cnt[i] != 0xFFFFFFFFu && lane < cnt[i]) first[i] = (A.slots + static_cast<size_t>(wc[i]) * A.cap)[lane];
+  }
+#pragma unroll
+  for (uint32_t i = 0; i < kListGroup; ++i) {
+    if (cnt[i] == 0xFFFFFFFFu) continue;
+    const uint2* slot = A.slots + static_cast<size_t>(wc[i]) * A.cap;
     uint32_t hi = 0;
-    for (uint32_t p0 = 0; p0 < cnt; p0 += kWaveSize) {
+    for (uint32_t p0 = 0; p0 < cnt[i]; p0 += kWaveSize) {
       const uint32_t p = p0 + lane;
-      if (p < cnt) {
-        const uint2 e = slot[p];
+      if (p < cnt[i]) {
+        const uint2 e = p0 == 0u ? first[i] : slot[p];
         const uint32_t key = e.x & kKeyMask;
         const uint32_t bin = coarse_bin(key, tau, shift);
         if (bin > bstar) {
@@ -732,9 +785,17 @@ __device__ void phase_sel(const CompressArgs& A, uint32_t l, const LayerDesc& L,
       }
     }
     const uint32_t hi_all = wave_total(wave_incl_scan(hi));
-    if (lane == 0) st_agent(&A.wc_a[wc], hi_all);
+    if (lane == 0) {
+      st_agent(&A.wc_a[wc[i]], hi_all);
+      if (hi_all) atomicAdd(&sh.hcnt, hi_all);
+    }
   }
-  if (!last_block_of_layer(&st->done, A.group_done + L.grp_first, blockIdx.x - L.wg_first, L.wg_count, &sh.flag)) return;
+  // one device-scope atomic per workgroup (its 16 wave-chunks lie in one offset group): such atomics
+  // on one address take their turns at a fraction of a microsecond each
+  __syncthreads();
+  if (threadIdx.x == 0 && sh.hcnt != 0u) atomicAdd(&A.wc_b[L.wc_first + (wgl * kWavesPerBlock) / kOffsetGroup], sh.hcnt);
+  if (!last_block_of_layer(&st->done, A.group_done + L.grp_first, wgl / kListGroup,
+                           (L.wg_count + kListGroup - 1u) / kListGroup, &sh.flag)) return;
 
   const uint32_t m = ld_agent(&st->nmembers);
   const uint32_t k_rem = st->k_rem;
@@ -742,20 +803,23 @@ __device__ void phase_sel(const CompressArgs& A, uint32_t l, const LayerDesc& L,
     if (threadIdx.x == 0) atomicOr(A.errflag, 4u);
     return;   // cannot happen when the histogram and the lists agree; leave the layer unscheduled
   }
-  uint32_t n2 = 2;
-  while (n2 < m) n2 <<= 1;
-  for (uint32_t i = threadIdx.x; i < n2; i += kBlockThreads)
-    sortbuf[i] = (i < m) ? __hip_atomic_load(&members[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0ull;
-  bitonic_sort_desc(sortbuf, n2);
-  const unsigned long long thr = sortbuf[k_rem - 1u];
-  // members at sorted positions < k_rem are selected: credit them to their wave-chunks
-  for (uint32_t i = threadIdx.x; i < k_rem; i += kBlockThreads) {
+  for (uint32_t i = threadIdx.x; i < m; i += kBlockThreads)
+    sortbuf[i] = __hip_atomic_load(&members[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __syncthreads();
+  const unsigned long long thr = select_kth_largest(sortbuf, m, k_rem, sel_hist, sh);
+  // members not below thr are selected: credit them to their wave-chunks
+  for (uint32_t i = threadIdx.x; i < m; i += kBlockThreads) {
+    if (sortbuf[i] < thr) continue;
     const uint32_t idx = 0xFFFFFFFFu - static_cast<uint32_t>(sortbuf[i] & 0xFFFFFFFFull);
-    atomicAdd(&A.wc_a[L.wc_first + idx / A.chunk], 1u);
+    const uint32_t c = idx / A.chunk;
+    atomicAdd(&A.wc_a[L.wc_first + c], 1u);
+    atomicAdd(&A.wc_b[L.wc_first + c / kOffsetGroup], 1u);
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the credits are device-scope atomics
   __syncthreads();
-  scan_chunks(A.wc_a + L.wc_first, nullptr, L.wc_count, 0u, false, sh.scan, &sh.cnt);
+  // output offsets: only the sums of groups of kOffsetGroup wave-chunks are scanned here (this is
+  // a serial step of one workgroup); PH_OUT_C scans inside its group itself
+  scan_chunks(A.wc_b + L.wc_first, nullptr, (L.wc_count + kOffsetGroup - 1u) / kOffsetGroup, 0u, false, sh.scan, &sh.cnt);
   __syncthreads();
   if (threadIdx.x == 0) {
     if (sh.cnt != L.k) atomicOr(A.errflag, 8u);
@@ -774,38 +838,64 @@ __device__ void phase_sel(const CompressArgs& A, uint32_t l, const LayerDesc& L,
   }
 }
 
-__device__ void phase_out_c(const CompressArgs& A, const LayerDesc& L, LayerState* st, uint32_t wc_local) {
-  if (wc_local >= L.wc_count) return;
+__device__ void phase_out_c(const CompressArgs& A, const LayerDesc& L, LayerState* st) {
+  const uint32_t wgl = blockIdx.x - L.wg_first;
+  if (wgl % kListGroup != 0u) return;               // see phase_sel
   const unsigned long long thr = st->thr;
-  const uint32_t wc = L.wc_first + wc_local;
-  const uint32_t cnt = A.cand_cnt[wc];
-  const uint2* slot = A.slots + static_cast<size_t>(wc) * A.cap;
-  const uint32_t lane = lane_id();
-  uint32_t out_pos = A.wc_a[wc];
+  const uint32_t lane = lane_id(), wave = threadIdx.x >> 6;
   const bool clear_mom = (L.mom != nullptr) && A.mask_momentum;
   const gptr<int32_t> out_idx = as_global(L.out_idx);
   const gptr<float> out_val = as_global(L.out_val);
   const gptr<float> resid = as_global(L.resid);
   const gptr<float> mom = as_global(L.mom);
-  for (uint32_t p0 = 0; p0 < cnt; p0 += kWaveSize) {
-    const uint32_t p = p0 + lane;
-    uint2 e = make_uint2(0u, 0u);
-    bool sel = false;
-    if (p < cnt) {
-      e = slot[p];
-      sel = composite(e.x & kKeyMask, e.y) >= thr;
-    }
-    const unsigned long long sm = __ballot(sel);
-    const uint32_t pos = out_pos + rank_below(sm);
-    if (sel && pos < L.k && e.y < L.n) {   // the bounds always hold when the counts are consistent
-      out_idx[pos] = static_cast<int32_t>(e.y);
-      out_val[pos] = __uint_as_float(e.x);
-      mask_store(&resid[e.y]);
-      if (clear_mom) mask_store(&mom[e.y]);
-    }
-    out_pos += popc64(sm);
+  uint32_t wc[kListGroup], cnt[kListGroup], out_at[kListGroup];
+  // this wave's lists are wave-chunks (wgl + i) * 4 + wave: all inside one group of kOffsetGroup
+  const uint32_t grp = (wgl * kWavesPerBlock) / kOffsetGroup;
+  uint32_t excl;
+  {
+    const uint32_t c = grp * kOffsetGroup + lane;
+    const uint32_t mine = c < L.wc_count ? A.wc_a[L.wc_first + c] : 0u;   // selected entries of the group's chunks
+    excl = wave_incl_scan(mine) - mine + A.wc_b[L.wc_first + grp];
   }
-  if (wc_local == 0 && lane == 0) *as_global(L.out_count) = static_cast<int32_t>(L.k);
+#pragma unroll
+  for (uint32_t i = 0; i < kListGroup; ++i) {
+    const uint32_t wc_local = (wgl + i) * kWavesPerBlock + wave;
+    wc[i] = L.wc_first + wc_local;
+    cnt[i] = 0u;
+    out_at[i] = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(excl),
+                                                                 static_cast<int>(__builtin_amdgcn_readfirstlane(wc_local % kOffsetGroup))));
+    if (wc_local < L.wc_count) cnt[i] = A.cand_cnt[wc[i]];
+  }
+  uint2 first[kListGroup];
+#pragma unroll
+  for (uint32_t i = 0; i < kListGroup; ++i) {
+    first[i] = make_uint2(0u, 0u);
+    if (lane < cnt[i]) first[i] = (A.slots + static_cast<size_t>(wc[i]) * A.cap)[lane];
+  }
+#pragma unroll
+  for (uint32_t i = 0; i < kListGroup; ++i) {
+    const uint2* slot = A.slots + static_cast<size_t>(wc[i]) * A.cap;
+    uint32_t out_pos = out_at[i];
+    for (uint32_t p0 = 0; p0 < cnt[i]; p0 += kWaveSize) {
+      const uint32_t p = p0 + lane;
+      uint2 e = make_uint2(0u, 0u);
+      bool sel = false;
+      if (p < cnt[i]) {
+        e = p0 == 0u ? first[i] : slot[p];
+        sel = composite(e.x & kKeyMask, e.y) >= thr;
+      }
+      const unsigned long long sm = __ballot(sel);
+      const uint32_t pos = out_pos + rank_below(sm);
+      if (sel && pos < L.k && e.y < L.n) {   // the bounds always hold when the counts are consistent
+        out_idx[pos] = static_cast<int32_t>(e.y);
+        out_val[pos] = __uint_as_float(e.x);
+        mask_store(&resid[e.y]);
+        if (clear_mom) mask_store(&mom[e.y]);
+      }
+      out_pos += popc64(sm);
+    }
+  }
+  if (wgl == 0u && threadIdx.x == 0u) *as_global(L.out_count) = static_cast<int32_t>(L.k);
 }
 
 }  // namespace
@@ -816,6 +906,7 @@ __global__ void __launch_bounds__(kBlockThreads) phase_kernel(CompressArgs A) {
     unsigned long long sortbuf[kMemberMax];
   } sm;
   __shared__ ResolveShared sh;
+  __shared__ uint32_t sel_hist[256];
   const uint32_t wg = blockIdx.x;
   const uint32_t l = A.wg2layer[wg];
   LayerState* st = A.state + l;
@@ -824,8 +915,8 @@ __global__ void __launch_bounds__(kBlockThreads) phase_kernel(CompressArgs A) {
   const uint32_t phase = st->next_phase;
   const uint32_t wc_local = (wg - L.wg_first) * kWavesPerBlock + (threadIdx.x >> 6);
   switch (phase) {
-    case PH_SEL:   phase_sel(A, l, L, st, wc_local, sm.sortbuf, sh); break;
-    case PH_OUT_C: phase_out_c(A, L, st, wc_local); break;
+    case PH_SEL:   phase_sel(A, l, L, st, sm.sortbuf, sel_hist, sh); break;
+    case PH_OUT_C: phase_out_c(A, L, st); break;
     case PH_HIST1: phase_hist<1>(A, l, L, st, wc_local, sm.hist, sh); break;
     case PH_HIST2: phase_hist<2>(A, l, L, st, wc_local, sm.hist, sh); break;
     case PH_HIST3: phase_hist<3>(A, l, L, st, wc_local, sm.hist, sh); break;
