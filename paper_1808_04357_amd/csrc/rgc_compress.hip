@@ -325,7 +325,7 @@ __device__ uint32_t locate_from_top(const uint32_t* lds, uint32_t bins, uint32_t
 // Multi-pass path, one radix digit: the layer's histogram of this digit is complete.  Find the
 // bin holding the k_rem-th largest key, update prefix / k_rem, derive the threshold hint for
 // the next call on the way, clear the histogram, schedule the next phase.
-// `lds` holds >= kHistBins words and is free for use.
+// `lds` holds the bins of this level (kHistBins words, 128 at the last level) and is free for use.
 template <int kLevel>
 __device__ void resolve_digit(const CompressArgs& A, uint32_t l, const LayerDesc& L, LayerState* st,
                               ResolveShared& sh, uint32_t* lds, uint32_t cur_launch) {
@@ -498,45 +498,82 @@ __device__ void scan_chunks(uint32_t* a, uint32_t* b, uint32_t count, uint32_t r
 }
 
 // The kk-th largest (1-based) of the m distinct 64-bit values v[0..m) in LDS, by radix selection
-// from the top byte down: a 256-bin histogram of the values that match the bytes fixed so far,
-// a scan from the top bin, the next byte.  Stops as soon as one value is left.  (A bitonic sort
-// of the same values took 55 dependent LDS round trips; this takes a few.)  All threads of the
-// workgroup call it; hist holds 256 words.
+// from the top byte in which the values differ at all (the members of one coarse bin share
+// their leading bytes) downwards: a 256-bin histogram of the values that match the bytes fixed
+// so far, a scan from the top bin, the next byte; stops as soon as one value is left.  One
+// barrier per byte: every wave scans the finished histogram for itself (four bins a lane), and
+// three histograms take turns, the one two bytes ahead being cleared meanwhile.  (A bitonic
+// sort of the same values took 55 dependent LDS round trips.)  All threads of the workgroup call
+// it; hist holds 3 * 256 words.
+static_assert(kBlockThreads == 256, "one thread per histogram bin");
 __device__ unsigned long long select_kth_largest(const unsigned long long* v, uint32_t m, uint32_t kk,
                                                  uint32_t* hist, ResolveShared& sh) {
-  const uint32_t t = threadIdx.x;
-  unsigned long long prefix = 0ull;
-  for (int shift = 56; shift >= 0; shift -= 8) {
+  const uint32_t t = threadIdx.x, lane = lane_id();
+  const unsigned long long v0 = v[0];
+  unsigned long long diff = 0ull;
+  for (uint32_t i = t; i < m; i += kBlockThreads) diff |= v[i] ^ v0;
+  int top = diff ? 63 - __clzll(static_cast<long long>(diff)) : -1;   // highest differing bit this thread saw
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) {
+    const int other = __shfl_xor(top, o);
+    top = other > top ? other : top;
+  }
+  if (lane == 0) sh.scan[t >> 6] = static_cast<uint32_t>(top + 1);
+  hist[t] = 0u; hist[256u + t] = 0u; hist[512u + t] = 0u;
+  __syncthreads();
+  {
+    const uint32_t a = sh.scan[0], b = sh.scan[1], c = sh.scan[2], d = sh.scan[3];
+    const uint32_t ab = a > b ? a : b, cd = c > d ? c : d;
+    top = static_cast<int>(ab > cd ? ab : cd) - 1;
+  }
+  if (top < 0) return v0;                                   // a single value
+  int shift = (top >> 3) << 3;
+  unsigned long long prefix = shift == 56 ? 0ull : (v0 & (~0ull << (shift + 8)));
+  for (uint32_t pass = 0;; ++pass, shift -= 8) {
+    uint32_t* const H = hist + (pass % 3u) * 256u;
     const unsigned long long himask = shift == 56 ? 0ull : (~0ull << (shift + 8));
-    hist[t] = 0u;
-    __syncthreads();
     for (uint32_t i = t; i < m; i += kBlockThreads) {
       const unsigned long long x = v[i];
-      if ((x & himask) == prefix) atomicAdd(&hist[static_cast<uint32_t>(x >> shift) & 255u], 1u);
+      if ((x & himask) == prefix) atomicAdd(&H[static_cast<uint32_t>(x >> shift) & 255u], 1u);
     }
     __syncthreads();
-    const uint32_t h = hist[255u - t];
-    uint32_t total;
-    const uint32_t above = block_excl_scan(h, sh.scan, total);   // values in higher bins
-    if (above < kk && above + h >= kk) { sh.bin = 255u - t; sh.above = above; sh.cnt = h; }
-    __syncthreads();
-    prefix |= static_cast<unsigned long long>(sh.bin) << shift;
-    kk -= sh.above;
-    const uint32_t left = sh.cnt;
-    __syncthreads();
-    if (left == 1u && shift > 0) {
-      const unsigned long long lomask = ~0ull << shift;
-      for (uint32_t i = t; i < m; i += kBlockThreads) {
-        const unsigned long long x = v[i];
-        if ((x & lomask) == prefix) { sh.hbin = static_cast<uint32_t>(x); sh.hcum = static_cast<uint32_t>(x >> 32); }
-      }
-      __syncthreads();
-      const unsigned long long r = (static_cast<unsigned long long>(sh.hcum) << 32) | sh.hbin;
-      __syncthreads();
-      return r;
+    hist[((pass + 2u) % 3u) * 256u + t] = 0u;
+    // each wave for itself: lane L holds bins 4L .. 4L+3
+    const uint32_t h0 = H[4u * lane], h1 = H[4u * lane + 1u], h2 = H[4u * lane + 2u], h3 = H[4u * lane + 3u];
+    const uint32_t mine = h0 + h1 + h2 + h3;
+    const uint32_t incl = wave_incl_scan(mine);
+    const uint32_t higher = wave_total(incl) - incl;        // values in the bins of higher lanes
+    const bool here = higher < kk && kk <= higher + mine;
+    uint32_t bin = 0, above = 0, cnt = 0;
+    if (here) {
+      uint32_t a = higher;
+      if (kk <= a + h3) { bin = 3u; cnt = h3; }
+      else { a += h3; if (kk <= a + h2) { bin = 2u; cnt = h2; }
+      else { a += h2; if (kk <= a + h1) { bin = 1u; cnt = h1; }
+      else { a += h1; bin = 0u; cnt = h0; } } }
+      bin += 4u * lane;
+      above = a;
     }
+    const unsigned long long who = __ballot(here);          // exactly one lane when 1 <= kk <= values in scope
+    const int src = who ? static_cast<int>(__ffsll(static_cast<long long>(who))) - 1 : 0;
+    bin = static_cast<uint32_t>(__shfl(static_cast<int>(bin), src));
+    above = static_cast<uint32_t>(__shfl(static_cast<int>(above), src));
+    cnt = static_cast<uint32_t>(__shfl(static_cast<int>(cnt), src));
+    prefix |= static_cast<unsigned long long>(bin) << shift;
+    kk -= above;
+    if (shift == 0) return prefix;
+    if (cnt <= 1u) break;
   }
-  return prefix;
+  // one value is left under these leading bytes: whoever holds it tells the others
+  const unsigned long long lomask = ~0ull << shift;
+  for (uint32_t i = t; i < m; i += kBlockThreads) {
+    const unsigned long long x = v[i];
+    if ((x & lomask) == prefix) { sh.hbin = static_cast<uint32_t>(x); sh.hcum = static_cast<uint32_t>(x >> 32); }
+  }
+  __syncthreads();
+  const unsigned long long r = (static_cast<unsigned long long>(sh.hcum) << 32) | sh.hbin;
+  __syncthreads();
+  return r;
 }
 
 // The zeros that mask a sent entry out of the residual (and the velocity) are isolated 4-byte
@@ -906,7 +943,7 @@ __global__ void __launch_bounds__(kBlockThreads) phase_kernel(CompressArgs A) {
     unsigned long long sortbuf[kMemberMax];
   } sm;
   __shared__ ResolveShared sh;
-  __shared__ uint32_t sel_hist[256];
+  __shared__ __attribute__((aligned(16))) uint32_t sel_hist[3 * 256];
   const uint32_t wg = blockIdx.x;
   const uint32_t l = A.wg2layer[wg];
   LayerState* st = A.state + l;
@@ -923,6 +960,28 @@ __global__ void __launch_bounds__(kBlockThreads) phase_kernel(CompressArgs A) {
     case PH_COUNT: phase_count(A, l, L, st, wc_local, sh); break;
     case PH_OUT_V: phase_out_v(A, L, st, wc_local); break;
     default: break;
+  }
+}
+
+// Launches 4..6 can only meet the last three phases of the multi-pass path (a layer that missed
+// its hint is at PH_HIST3 in launch 4 at the earliest), and in steady state they meet nothing at
+// all.  They get a kernel of their own that needs next to no LDS: twice as many of its
+// workgroups fit on the device at once, so the launches that find nothing to do are over sooner.
+constexpr uint32_t kFirstLateLaunch = 4;
+__global__ void __launch_bounds__(kBlockThreads) phase_late_kernel(CompressArgs A) {
+  __shared__ uint32_t hist[128];
+  __shared__ ResolveShared sh;
+  const uint32_t wg = blockIdx.x;
+  const uint32_t l = A.wg2layer[wg];
+  LayerState* st = A.state + l;
+  if (st->next_launch != A.launch) return;
+  const LayerDesc L = A.layers[l];
+  const uint32_t wc_local = (wg - L.wg_first) * kWavesPerBlock + (threadIdx.x >> 6);
+  switch (st->next_phase) {
+    case PH_HIST3: phase_hist<3>(A, l, L, st, wc_local, hist, sh); break;
+    case PH_COUNT: phase_count(A, l, L, st, wc_local, sh); break;
+    case PH_OUT_V: phase_out_v(A, L, st, wc_local); break;
+    default: if (threadIdx.x == 0) atomicOr(A.errflag, 16u); break;   // no other phase can be due this late
   }
 }
 
@@ -956,7 +1015,8 @@ hipError_t launch_accumulate(const CompressArgs& a, uint32_t num_wgs, hipStream_
 }
 
 hipError_t launch_phase(const CompressArgs& a, uint32_t num_wgs, hipStream_t s) {
-  hipLaunchKernelGGL(phase_kernel, dim3(num_wgs), dim3(kBlockThreads), 0, s, a);
+  if (a.launch >= kFirstLateLaunch) hipLaunchKernelGGL(phase_late_kernel, dim3(num_wgs), dim3(kBlockThreads), 0, s, a);
+  else hipLaunchKernelGGL(phase_kernel, dim3(num_wgs), dim3(kBlockThreads), 0, s, a);
   return hipGetLastError();
 }
 

@@ -492,9 +492,30 @@ decompress_tiles_kernel(DecompressArgs A) {
       my_count = md.count;
     }
     // E: entries of the worker before the run's first tile (the messages are sorted by index)
+    // The four lanes of a worker search together: each step they probe the four inner fifth points
+    // of the range at once, so the search is log5 deep instead of log2.  A run that starts a
+    // layer needs no search.
     uint32_t E = 0;
-    if (q == 0u) E = lower_bound_idx(my_idx, my_count, (tile_id - L.tile_base) << kTileShift);
-    E = quad_lane0(E);
+    {
+      const uint32_t target = (tile_id - L.tile_base) << kTileShift;
+      uint32_t lo = 0, hi = target != 0u ? my_count : 0u;   // idx[lo - 1] < target <= idx[hi]
+      while (__builtin_amdgcn_ballot_w64(lo < hi) != 0ull) {
+        const uint32_t span = hi - lo;                       // the same in the four lanes of a quad
+        const uint32_t s5 = span / 5u, r5 = span % 5u;
+        auto fifths = [&](uint32_t j) { return s5 * j + (r5 * j + 4u) / 5u; };   // ceil(j * span / 5)
+        // probe points lo + ceil((q+1) * span / 5) - 1: ascending, all inside [lo, hi)
+        const uint32_t at = lo + fifths(q + 1u) - 1u;
+        uint32_t below = 0;
+        if (lo < hi) below = static_cast<uint32_t>(my_idx[at]) < target ? 1u : 0u;
+        const uint32_t nb = quad_sum(below);                 // the probes are ordered: the first nb lie below
+        if (lo < hi) {
+          const uint32_t new_lo = nb == 0u ? lo : lo + fifths(nb);              // one past probe nb-1
+          const uint32_t new_hi = nb == 4u ? hi : lo + fifths(nb + 1u) - 1u;    // probe nb
+          lo = new_lo; hi = new_hi;
+        }
+      }
+      E = lo;
+    }
 
     // the window: slot s holds block have[s] (kNone: nothing), this lane its entries 4q .. 4q+3
     uint32_t b_idx[2][4];
@@ -694,7 +715,7 @@ decompress_tiles_kernel(DecompressArgs A) {
               o.x = __fadd_rn(old.x, o.x); o.y = __fadd_rn(old.y, o.y);
               o.z = __fadd_rn(old.z, o.z); o.w = __fadd_rn(old.w, o.w);
             }
-            d4[i4] = o;
+            __builtin_nontemporal_store(o, &d4[i4]);       // written once, not read here again: keep it from pushing the message lines out of the L2
           }
         }
       } else {

@@ -224,3 +224,32 @@ def test_argument_errors(rgc):
     assert e.value.status == -1
     torch.cuda.synchronize()
     ctx.close()
+
+
+def test_zeros_cancellations_and_denormals(rgc, oracle):
+    """Values that make a position's running sum zero or denormal: +0, -0, x followed by -x,
+    denormals alone and together.  The worker-order sum must come out bit for bit whichever
+    worker's entry reaches the position first."""
+    g = np.random.default_rng(11)
+    n, N = 3 * 4096 + 5, 48
+    pos = np.sort(g.choice(n, size=300, replace=False)).astype(np.int32)
+    tiny = np.float32(1e-41)                                  # denormal
+    special = np.array([0.0, -0.0, 1.5, -1.5, tiny, -tiny, 3 * tiny, 1e-38, -1e-38, 2.0 ** -126], dtype=np.float32)
+    idx, val = [], []
+    for w in range(N):
+        keep = g.random(pos.size) < 0.5                       # every position: about half the workers
+        v = special[g.integers(0, special.size, pos.size)]
+        idx.append([pos[keep]])
+        val.append([v[keep].astype(np.float32)])
+    # some positions hit by exactly one worker, with each special value
+    lone = np.setdiff1d(np.arange(n, dtype=np.int32), pos)[: special.size]
+    idx[3][0] = np.concatenate([idx[3][0], lone]); val[3][0] = np.concatenate([val[3][0], special])
+    o = np.argsort(idx[3][0], kind="stable"); idx[3][0] = idx[3][0][o]; val[3][0] = val[3][0][o]
+    ctx = rgc.Context(1024, 1)
+    for scale in (1.0, 1.0 / N):
+        got = gpu_decompress(rgc, ctx, idx, val, [n], scale)
+        compare("special values scale %g" % scale, got, oracle_all(oracle, idx, val, [n], scale))
+    init = [g.standard_normal(n).astype(np.float32)]
+    got = gpu_decompress(rgc, ctx, idx, val, [n], 1.0, dense_init=init)
+    compare("special values add", got, oracle_all(oracle, idx, val, [n], 1.0, dense_init=init))
+    ctx.close()
