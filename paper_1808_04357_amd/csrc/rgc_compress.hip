@@ -505,7 +505,7 @@ __device__ void scan_chunks(uint32_t* a, uint32_t* b, uint32_t count, uint32_t r
 // three histograms take turns, the one two bytes ahead being cleared meanwhile.  (A bitonic
 // sort of the same values took 55 dependent LDS round trips.)  All threads of the workgroup call
 // it; hist holds 3 * 256 words.
-static_assert(kBlockThreads == 256, "one thread per histogram bin");
+static_assert(kBlockThreads == 256, "one thread per histogram bin");   // (PH_SEL also counts on hist holding 3 * kBlockThreads words)
 __device__ unsigned long long select_kth_largest(const unsigned long long* v, uint32_t m, uint32_t kk,
                                                  uint32_t* hist, ResolveShared& sh) {
   const uint32_t t = threadIdx.x, lane = lane_id();
@@ -795,11 +795,13 @@ __device__ void phase_sel(const CompressArgs& A, uint32_t l, const LayerDesc& L,
     wc[i] = L.wc_first + wc_local;
     cnt[i] = wc_local < L.wc_count ? A.cand_cnt[wc[i]] : 0xFFFFFFFFu;   // ~0: no such list
   }
+  // the first 64 slots of every list are asked for together with the lists' lengths, not after them
+  // (the slots exist whatever the length; what lies beyond it is not looked at)
   uint2 first[kListGroup];
 #pragma unroll
   for (uint32_t i = 0; i < kListGroup; ++i) {
     first[i] = make_uint2(0u, 0u);
-    if (cnt[i] != 0xFFFFFFFFu && lane < cnt[i]) first[i] = (A.slots + static_cast<size_t>(wc[i]) * A.cap)[lane];
+    if ((wgl + i) * kWavesPerBlock + wave < L.wc_count && lane < A.cap) first[i] = (A.slots + static_cast<size_t>(wc[i]) * A.cap)[lane];
   }
 #pragma unroll
   for (uint32_t i = 0; i < kListGroup; ++i) {
@@ -840,23 +842,63 @@ __device__ void phase_sel(const CompressArgs& A, uint32_t l, const LayerDesc& L,
     if (threadIdx.x == 0) atomicOr(A.errflag, 4u);
     return;   // cannot happen when the histogram and the lists agree; leave the layer unscheduled
   }
+  // Output offsets: only the sums of groups of kOffsetGroup wave-chunks are scanned here (this is a
+  // serial step of one workgroup); PH_OUT_C scans inside its group itself.  Up to kLdsGroups groups
+  // (every layer below 400 M elements) the sums are fetched now, three a thread, while the members
+  // are ranked; the members' own credits to them are then counted in LDS, which spares the round
+  // trip of device-scope atomics followed by loads of the same words.
+  constexpr uint32_t kLdsGroups = 3u * kBlockThreads;
+  const uint32_t groups = (L.wc_count + kOffsetGroup - 1u) / kOffsetGroup;
+  const bool in_lds = groups <= kLdsGroups;
+  uint32_t gsum[3] = {0u, 0u, 0u};
+  if (in_lds) {
+#pragma unroll
+    for (uint32_t j = 0; j < 3u; ++j) {
+      const uint32_t g = 3u * threadIdx.x + j;
+      if (g < groups) gsum[j] = ld_agent(&A.wc_b[L.wc_first + g]);
+    }
+  }
   for (uint32_t i = threadIdx.x; i < m; i += kBlockThreads)
     sortbuf[i] = __hip_atomic_load(&members[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   __syncthreads();
   const unsigned long long thr = select_kth_largest(sortbuf, m, k_rem, sel_hist, sh);
-  // members not below thr are selected: credit them to their wave-chunks
+  __syncthreads();                                  // every wave is done with the selection's histograms
+  if (in_lds) {
+    sel_hist[threadIdx.x] = 0u; sel_hist[kBlockThreads + threadIdx.x] = 0u; sel_hist[2u * kBlockThreads + threadIdx.x] = 0u;
+    __syncthreads();
+  }
+  // members not below thr are selected: credit them to their wave-chunks (and to the chunks' groups)
   for (uint32_t i = threadIdx.x; i < m; i += kBlockThreads) {
     if (sortbuf[i] < thr) continue;
     const uint32_t idx = 0xFFFFFFFFu - static_cast<uint32_t>(sortbuf[i] & 0xFFFFFFFFull);
     const uint32_t c = idx / A.chunk;
     atomicAdd(&A.wc_a[L.wc_first + c], 1u);
-    atomicAdd(&A.wc_b[L.wc_first + c / kOffsetGroup], 1u);
+    if (in_lds) atomicAdd(&sel_hist[c / kOffsetGroup], 1u);
+    else atomicAdd(&A.wc_b[L.wc_first + c / kOffsetGroup], 1u);
   }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the credits are device-scope atomics
-  __syncthreads();
-  // output offsets: only the sums of groups of kOffsetGroup wave-chunks are scanned here (this is
-  // a serial step of one workgroup); PH_OUT_C scans inside its group itself
-  scan_chunks(A.wc_b + L.wc_first, nullptr, (L.wc_count + kOffsetGroup - 1u) / kOffsetGroup, 0u, false, sh.scan, &sh.cnt);
+  if (in_lds) {
+    __syncthreads();
+    uint32_t v[3], mine = 0u;
+#pragma unroll
+    for (uint32_t j = 0; j < 3u; ++j) {
+      const uint32_t g = 3u * threadIdx.x + j;
+      v[j] = g < groups ? gsum[j] + sel_hist[g] : 0u;
+      mine += v[j];
+    }
+    uint32_t total;
+    uint32_t ex = block_excl_scan(mine, sh.scan, total);
+#pragma unroll
+    for (uint32_t j = 0; j < 3u; ++j) {
+      const uint32_t g = 3u * threadIdx.x + j;
+      if (g < groups) A.wc_b[L.wc_first + g] = ex;
+      ex += v[j];
+    }
+    if (threadIdx.x == 0) sh.cnt = total;
+  } else {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the credits are device-scope atomics
+    __syncthreads();
+    scan_chunks(A.wc_b + L.wc_first, nullptr, groups, 0u, false, sh.scan, &sh.cnt);
+  }
   __syncthreads();
   if (threadIdx.x == 0) {
     if (sh.cnt != L.k) atomicOr(A.errflag, 8u);
