@@ -42,6 +42,11 @@ extern "C" {
 /* rgc_decompress_accumulate: exactly one of the two */
 #define RGC_OVERWRITE        0x10u /* dense = acc * scale                                   */
 #define RGC_ADD_TO_DST       0x20u /* dense = dense + acc * scale (two roundings, no fma)   */
+#define RGC_VALIDATE         0x40u /* with either of the two: also check the messages on the
+                                      device (see rgc_decompress_status)                    */
+/* bits of the status word of rgc_decompress_status */
+#define RGC_STATUS_INDEX_RANGE 0x1u /* some message holds an index outside [0, n) of its layer */
+#define RGC_STATUS_INDEX_ORDER 0x2u /* some message's indices are not strictly ascending       */
 
 typedef struct rgc_ctx rgc_ctx; /* opaque */
 
@@ -109,11 +114,19 @@ int rgc_compress_layers(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layer
  *   RGC_ADD_TO_DST: dense[l][i] = dense[l][i] + acc * scale
  * The summation order is fixed, so the result does not depend on scheduling.
  * dense: host array of num_layers device pointers; n: host array of their lengths.
- * Precondition (not checked): each message's idx strictly ascending and < n[l].
+ * Precondition: each message's idx strictly ascending and < n[l] (what compression emits, and
+ * what an Allgather of such messages holds: Section 2.3).  It is not checked unless flags
+ * carries RGC_VALIDATE; a message that violates it never makes the kernels leave the buffers
+ * they were given, but the dense result is then unspecified.
  * Errors (nothing enqueued): RGC_EINVAL, RGC_ENOMEM, RGC_EHIP. */
 int rgc_decompress_accumulate(rgc_ctx* ctx, const rgc_msg* msgs, int32_t num_workers,
                               int32_t num_layers, float* const* dense, const int64_t* n,
                               float scale, uint32_t flags, void* hip_stream);
+
+/* What the RGC_VALIDATE checks of the decompression calls enqueued so far have found: waits for
+ * `hip_stream`, stores the OR of their RGC_STATUS_* bits into *out_status (host memory; 0 = all
+ * messages met the precondition) and clears the word.  Errors: RGC_EINVAL, RGC_EHIP. */
+int rgc_decompress_status(rgc_ctx* ctx, uint32_t* out_status, void* hip_stream);
 
 /* Speed-hint control (never changes results).  rgc_reset_hints forgets every cached
  * threshold, so the next call behaves like a first call.  rgc_poison_hints overwrites the

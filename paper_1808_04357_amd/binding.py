@@ -19,13 +19,16 @@ RGC_NO_MOMENTUM_MASK = 0x1
 RGC_NO_HINTS = 0x2
 RGC_OVERWRITE = 0x10
 RGC_ADD_TO_DST = 0x20
+RGC_VALIDATE = 0x40
+RGC_STATUS_INDEX_RANGE = 0x1
+RGC_STATUS_INDEX_ORDER = 0x2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("RGC_LIB") or os.path.join(_HERE, "librgc.so")   # RGC_LIB: tuning builds only
 
 EXPORTS = ["rgc_create", "rgc_destroy", "rgc_k_for_density", "rgc_compress_layers",
            "rgc_decompress_accumulate", "rgc_reset_hints", "rgc_poison_hints", "rgc_selftest",
-           "rgc_last_paths", "rgc_last_stats", "rgc_profile_enable", "rgc_profile_read", "rgc_strerror"]
+           "rgc_last_paths", "rgc_last_stats", "rgc_decompress_status", "rgc_profile_enable", "rgc_profile_read", "rgc_strerror"]
 
 
 class RgcError(RuntimeError):
@@ -84,6 +87,8 @@ def load_library() -> ctypes.CDLL:
     L.rgc_last_paths.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32), ctypes.c_int32, ctypes.c_void_p]
     L.rgc_last_stats.restype = ctypes.c_int
     L.rgc_last_stats.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64), ctypes.c_int32, ctypes.c_void_p]
+    L.rgc_decompress_status.restype = ctypes.c_int
+    L.rgc_decompress_status.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_uint32), ctypes.c_void_p]
     L.rgc_profile_enable.restype = ctypes.c_int
     L.rgc_profile_enable.argtypes = [ctypes.c_void_p, ctypes.c_int]
     L.rgc_profile_read.restype = ctypes.c_int
@@ -160,6 +165,12 @@ class Context:
         out = (ctypes.c_int64 * (4 * num_layers))()
         _check(self._lib.rgc_last_stats(self._h, out, int(num_layers), _stream(stream)))
         return [list(out[4 * l:4 * l + 4]) for l in range(num_layers)]
+
+    def decompress_status(self, stream=None) -> int:
+        """OR of the RGC_STATUS_* bits found by the RGC_VALIDATE checks so far (waits for the stream; clears the word)."""
+        out = ctypes.c_uint32(0)
+        _check(self._lib.rgc_decompress_status(self._h, ctypes.byref(out), _stream(stream)))
+        return int(out.value)
 
     def last_paths(self, num_layers: int, stream=None) -> List[int]:
         out = (ctypes.c_int32 * num_layers)()

@@ -320,14 +320,14 @@ int rgc_create(rgc_ctx** out, int device_id, int64_t max_total_elems, int32_t ma
     (void)kCap;
     chk(c->d_slots.alloc(static_cast<uint64_t>(max_total_elems) / kCapDiv + (static_cast<uint64_t>(max_layers) + 1) * (largest / kCapDiv)));
   }
-  chk(c->d_err.alloc(1));
+  chk(c->d_err.alloc(2));                  // [0] internal inconsistencies of compression, [1] status of the message checks
   const uint64_t grp_max = wc_max / (kWavesPerBlock * kElectGroupHost) + 2 * L + 2;
   chk(c->d_group.alloc(grp_max));
   if (e == hipSuccess) chk(hipMemset(c->d_state.p, 0, sizeof(LayerState) * L));
   if (e == hipSuccess) chk(hipMemset(c->d_hist.p, 0, sizeof(uint32_t) * L * kHistBins));
   if (e == hipSuccess) chk(hipMemset(c->d_coarse.p, 0, sizeof(uint32_t) * L * kCoarseRep * kCoarseBins));
   if (e == hipSuccess) chk(hipMemset(c->d_cand_cnt.p, 0, sizeof(uint32_t) * wc_max));
-  if (e == hipSuccess) chk(hipMemset(c->d_err.p, 0, sizeof(uint32_t)));
+  if (e == hipSuccess) chk(hipMemset(c->d_err.p, 0, 2 * sizeof(uint32_t)));
   if (e == hipSuccess) chk(hipMemset(c->d_group.p, 0, sizeof(uint32_t) * grp_max));
   if (e == hipSuccess) chk(hipDeviceSynchronize());
   if (e != hipSuccess) {
@@ -528,6 +528,8 @@ int rgc_decompress_accumulate(rgc_ctx* ctx, const rgc_msg* msgs, int32_t num_wor
                               void* hip_stream) {
   if (!ctx || !dense || !n || num_layers < 1 || num_workers < 0) return RGC_EINVAL;
   if (num_workers > 0 && !msgs) return RGC_EINVAL;
+  const bool validate = (flags & RGC_VALIDATE) != 0;
+  flags &= ~RGC_VALIDATE;
   if (flags != RGC_OVERWRITE && flags != RGC_ADD_TO_DST) return RGC_EINVAL;
   if (static_cast<int64_t>(num_workers) * num_layers > (int64_t(1) << 24)) return RGC_EINVAL;
   for (int32_t l = 0; l < num_layers; ++l) {
@@ -643,11 +645,24 @@ int rgc_decompress_accumulate(rgc_ctx* ctx, const rgc_msg* msgs, int32_t num_wor
   DecompressArgs A = P.args;
   A.add_to_dst = (flags == RGC_ADD_TO_DST) ? 1u : 0u;
   A.scale = scale;
+  if (validate) RGC_HIP(launch_decompress_validate(A, ctx->d_err.p + 1, stream));
   if (ctx->profiling) RGC_HIP(take_event(ctx, stream, ctx->ev_decompress));
   RGC_HIP(launch_decompress_table(A, stream));
   if (ctx->profiling) RGC_HIP(take_event(ctx, stream, ctx->ev_decompress));
   RGC_HIP(launch_decompress_tiles(A, stream));
   if (ctx->profiling) RGC_HIP(take_event(ctx, stream, ctx->ev_decompress));
+  return RGC_OK;
+}
+
+int rgc_decompress_status(rgc_ctx* ctx, uint32_t* out_status, void* hip_stream) {
+  if (!ctx || !out_status) return RGC_EINVAL;
+  DeviceGuard guard(ctx->device);
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  uint32_t word = 0;
+  RGC_HIP(hipMemcpyAsync(&word, ctx->d_err.p + 1, sizeof word, hipMemcpyDeviceToHost, stream));
+  RGC_HIP(hipMemsetAsync(ctx->d_err.p + 1, 0, sizeof word, stream));
+  RGC_HIP(hipStreamSynchronize(stream));
+  *out_status = word;
   return RGC_OK;
 }
 

@@ -749,6 +749,30 @@ __global__ void __launch_bounds__(kBlockThreads) decompress_generic_kernel(Decom
   }
 }
 
+// ------------------------------------------------------------------ precondition check (on request)
+// One workgroup per message: every index must lie inside the layer and exceed its predecessor
+// (Section 2.3: a message is what compression emitted).  Violations are ORed into *status
+// (bit 0: range, bit 1: order); nothing else is touched.
+__global__ void __launch_bounds__(kBlockThreads) decompress_validate_kernel(DecompressArgs A, uint32_t* status) {
+  const MsgDesc md = A.msgs[blockIdx.x];            // messages are stored [layer][worker]
+  const uint32_t n = A.layers[blockIdx.x / A.num_workers].n;
+  const gptr<const int32_t> idx = as_global(md.idx);
+  uint32_t bad = 0;
+  for (uint32_t j = threadIdx.x; j < md.count; j += kBlockThreads) {
+    const uint32_t v = static_cast<uint32_t>(idx[j]);                 // a negative index reads as a huge one
+    if (v >= n) bad |= 1u;
+    if (j != 0u && static_cast<uint32_t>(idx[j - 1u]) >= v) bad |= 2u;
+  }
+  if (bad != 0u) atomicOr(status, bad);
+}
+
+hipError_t launch_decompress_validate(const DecompressArgs& a, uint32_t* status, hipStream_t s) {
+  const uint32_t msgs = a.num_workers * a.num_layers;
+  if (msgs == 0) return hipSuccess;
+  hipLaunchKernelGGL(decompress_validate_kernel, dim3(msgs), dim3(kBlockThreads), 0, s, a, status);
+  return hipGetLastError();
+}
+
 hipError_t launch_decompress_table(const DecompressArgs& a, hipStream_t s) {
   // only the kernel that takes any number of workers reads the table
   if (a.num_blocks == 0 || a.num_workers <= static_cast<uint32_t>(kBatchWorkers)) return hipSuccess;

@@ -151,6 +151,7 @@ hipError_t launch_phase(const CompressArgs& a, uint32_t num_wgs, hipStream_t s);
 hipError_t launch_poison(LayerState* st, uint32_t num_layers, int mode, hipStream_t s);
 hipError_t launch_decompress_table(const DecompressArgs& a, hipStream_t s);
 hipError_t launch_decompress_tiles(const DecompressArgs& a, hipStream_t s);
+hipError_t launch_decompress_validate(const DecompressArgs& a, uint32_t* status, hipStream_t s);
 hipError_t launch_wave_scan_selftest(uint32_t* io, hipStream_t s);
 
 }  // namespace rgc

@@ -253,3 +253,45 @@ def test_zeros_cancellations_and_denormals(rgc, oracle):
     got = gpu_decompress(rgc, ctx, idx, val, [n], 1.0, dense_init=init)
     compare("special values add", got, oracle_all(oracle, idx, val, [n], 1.0, dense_init=init))
     ctx.close()
+
+
+def test_validate_flag_reports_bad_messages(rgc, oracle):
+    """RGC_VALIDATE: messages that meet the precondition (ascending indices inside the layer) leave
+    the status word at 0 and the result unchanged; an index beyond the layer or a pair out of order
+    is reported by its bit.  (The dense result of a bad message is unspecified; only that the call
+    completes and reports is checked.)"""
+    import torch
+    g = np.random.default_rng(21)
+    sizes = [5000, 3 * 4096 + 9]
+    N = 6
+    idx, val = random_messages(g, sizes, N, [40, 300])
+    ctx = rgc.Context(1024, 1)
+    dev = torch.device("cuda:0")
+
+    def run(idx_, flags):
+        d_idx = [[torch.from_numpy(np.ascontiguousarray(idx_[w][l])).to(dev) for l in range(len(sizes))] for w in range(N)]
+        d_val = [[torch.from_numpy(np.ascontiguousarray(val[w][l])).to(dev) for l in range(len(sizes))] for w in range(N)]
+        dense = [torch.zeros(n, dtype=torch.float32, device=dev) for n in sizes]
+        msgs = rgc.MessageList(d_idx, d_val, dense)
+        rgc.rgc_decompress_accumulate(ctx, msgs, 1.0, flags, torch.cuda.current_stream())
+        status = ctx.decompress_status(torch.cuda.current_stream())
+        return status, [d.cpu().numpy() for d in dense]
+
+    status, got = run(idx, rgc.RGC_OVERWRITE | rgc.RGC_VALIDATE)
+    assert status == 0
+    compare("validated", got, oracle_all(oracle, idx, val, sizes, 1.0))
+    # an index one past the end of layer 0 in worker 2's message (it stays the largest: order is intact)
+    bad = [[a.copy() for a in row] for row in idx]
+    bad[2][0][-1] = sizes[0]
+    status, _ = run(bad, rgc.RGC_OVERWRITE | rgc.RGC_VALIDATE)
+    assert status == rgc.RGC_STATUS_INDEX_RANGE
+    # two neighbours swapped in worker 4's message for layer 1
+    bad = [[a.copy() for a in row] for row in idx]
+    bad[4][1][[10, 11]] = bad[4][1][[11, 10]]
+    status, _ = run(bad, rgc.RGC_ADD_TO_DST | rgc.RGC_VALIDATE)
+    assert status == rgc.RGC_STATUS_INDEX_ORDER
+    # the word was cleared by the read; without the flag nothing is checked
+    assert ctx.decompress_status(torch.cuda.current_stream()) == 0
+    status, _ = run(bad, rgc.RGC_OVERWRITE)
+    assert status == 0
+    ctx.close()
