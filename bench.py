@@ -106,10 +106,28 @@ def measure_compress(torch, rgc, ctx, wl, stream, steps, warmup):
     out = {"elements": wl.total, "tensors": len(wl.sizes), "sum_k": sum(wl.ks)}
     ctx.reset_hints()
     out["first_call_ms"] = time_loop(torch, lambda: wl.step(ctx, stream), 1)
-    for _ in range(warmup):
+    # After a reset the threshold hints (and their drift estimate) take a few dozen calls to settle:
+    # the embedding-like tensor of the LSTM set misses on every other call until about the 30th.
+    # Training runs for thousands of iterations, so the steady state is what is timed: at least
+    # 40 warm-up calls here, and the hint misses inside the timed calls are counted and reported.
+    settle = max(warmup, 40)
+    for _ in range(settle):
         wl.step(ctx, stream)
+    misses0 = sum(r[4] for r in ctx.last_stats(len(wl.sizes), stream))
     ms = time_loop(torch, lambda: wl.step(ctx, stream), steps)
     out["ms_per_iter"] = ms
+    out["warmup_calls"] = settle
+    out["hint_misses_in_timed_calls"] = sum(r[4] for r in ctx.last_stats(len(wl.sizes), stream)) - misses0
+    # the same iterations once more, each bracketed by its own pair of events on the stream (median and minimum)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for a, b in evs:
+        a.record(stream)
+        wl.step(ctx, stream)
+        b.record(stream)
+    torch.cuda.synchronize()
+    per = sorted(a.elapsed_time(b) for a, b in evs)
+    out["ms_median"] = per[len(per) // 2]
+    out["ms_min"] = per[0]
     out["gradient_GBps"] = 4.0 * wl.total / ms / 1e6
     out["alg_bytes"] = wl.alg_bytes
     out["hbm_frac_algorithmic"] = wl.alg_bytes / (ms * 1e-3) / (HBM_PEAK_GBPS * 1e9)
@@ -130,29 +148,30 @@ def measure_compress(torch, rgc, ctx, wl, stream, steps, warmup):
 
 
 def cpu_baseline(torch, wl):
-    """The oracle as it stands, timed on the host on a bounded sample of the same workload: every
-    tensor of the set except the largest one(s), capped at ~40 M elements."""
-    import numpy as np
+    """The oracle as it stands, timed on the host: one compress step of the whole layer set on one
+    thread (about 10 s for the VGG16 set: the largest tensor alone is a 103 M-pair sort), and once
+    more with the layers spread over the host's threads (layers are independent; the largest one
+    bounds the gain)."""
     import oracle
     torch.cuda.synchronize()
-    order = sorted(range(len(wl.sizes)), key=lambda l: wl.sizes[l])
-    pick, tot = [], 0
-    for l in order:
-        if tot + wl.sizes[l] > 40_000_000:
-            break
-        pick.append(l)
-        tot += wl.sizes[l]
-    pick.sort()
-    G = [wl.G[0][l].cpu().numpy() for l in pick]
-    V = [wl.V[l].cpu().numpy().copy() for l in pick]
-    U = [wl.U[l].cpu().numpy().copy() for l in pick] if wl.U is not None else None
-    ks = [wl.ks[l] for l in pick]
-    t0 = time.perf_counter()
-    oracle.compress_layers(G, V, ks, momenta=U, m=wl.m, threads=1)
-    dt = time.perf_counter() - t0
-    return {"value": 4.0 * tot / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": "compress step of %d of the %d %s tensors (%d of %d elements: all but the largest), "
-                      "plain C++ full-sort oracle, 1 thread, %.1f s" % (len(pick), len(wl.sizes), wl.name, tot, wl.total, dt),
+    G = [g.cpu().numpy() for g in wl.G[0]]
+    V0 = [v.cpu().numpy() for v in wl.V]
+    U0 = [u.cpu().numpy() for u in wl.U] if wl.U is not None else None
+
+    def run(threads):
+        V = [v.copy() for v in V0]
+        U = [u.copy() for u in U0] if U0 is not None else None
+        t0 = time.perf_counter()
+        oracle.compress_layers(G, V, wl.ks, momenta=U, m=wl.m, threads=threads)
+        return time.perf_counter() - t0
+
+    dt1 = run(1)
+    T = min(oracle.hardware_threads(), len(wl.sizes), 16)
+    dtT = run(T)
+    return {"value": 4.0 * wl.total / dt1 / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": "one compress step of all %d %s tensors (%d elements), plain C++ full-sort oracle, 1 thread, %.1f s"
+                      % (len(wl.sizes), wl.name, wl.total, dt1),
+            "layer_parallel": {"value": 4.0 * wl.total / dtT / 1e9, "unit": "GB/s", "cores": T, "seconds": dtT},
             "host_threads_available": oracle.hardware_threads()}
 
 
@@ -200,7 +219,9 @@ def main():
     # the timed region: the library records HIP events around its kernels on the caller's stream,
     # so the dominant kernel's launch duration comes from these very K steps
     ctx.profile_enable(True)
+    misses0 = sum(r[4] for r in ctx.last_stats(len(vgg.sizes), stream))
     ms_step = time_loop(torch, step, args.steps)
+    step_misses = sum(r[4] for r in ctx.last_stats(len(vgg.sizes), stream)) - misses0
     step_ms4, step_calls = ctx.profile_read()
     ctx.profile_enable(False)
     step_bytes = vgg.alg_bytes + dec.alg_bytes
@@ -233,6 +254,7 @@ def main():
             t = json.load(f)
         roofline["traffic"] = t["fetch_bytes_per_launch"] + t["write_bytes_per_launch"]
         roofline["traffic_source"] = t["source"]
+        roofline["frac_measured_traffic"] = roofline["traffic"] / (k_ms * 1e-3) / (HBM_PEAK_GBPS * 1e9)
     except (OSError, ValueError, KeyError):
         pass
 
@@ -250,6 +272,7 @@ def main():
         for name, make in (("lstm", lambda: synth.config_lstm(num_grads=NUM_GRAD_SETS)),
                            ("resnet50", lambda: synth.config_resnet50(num_grads=NUM_GRAD_SETS)),
                            ("single_1Mi", lambda: synth.config_single(1 << 20, num_grads=NUM_GRAD_SETS)),
+                           ("uniform_1Mi", lambda: synth.config_uniform(1 << 20, num_grads=NUM_GRAD_SETS)),
                            # the value law of the paper's own selection benchmark (Figure 2), 64 Mi elements
                            ("uniform_64Mi", lambda: synth.config_uniform(1 << 26, num_grads=NUM_GRAD_SETS))):
             log("workload %s..." % name)
@@ -260,7 +283,7 @@ def main():
 
     cpu = None
     if not args.skip_cpu:
-        log("timing the CPU oracle on a bounded sample...")
+        log("timing the CPU oracle on the VGG16-shaped set (1 thread, then layer-parallel; about 20 s)...")
         cpu = cpu_baseline(torch, vgg)
 
     line = {
@@ -270,9 +293,11 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "VGG16-shaped layer set: compress (16 tensors, 138,344,128 elements, momentum 0.9, "
                                "density 0.1 %) + decompress of 128 virtual workers into the same shape",
-                   "step": "rgc_compress_layers + rgc_decompress_accumulate", "gradient_sets_rotated": NUM_GRAD_SETS},
+                   "step": "rgc_compress_layers + rgc_decompress_accumulate", "gradient_sets_rotated": NUM_GRAD_SETS,
+                   "kernel_launches_per_step": {"compress": 6, "decompress": 1}},
         "hbm_frac_step_algorithmic": step_bytes / (ms_step * 1e-3) / (HBM_PEAK_GBPS * 1e9),
         "ms_per_step_without_kernel_events": ms_step_plain,
+        "hint_misses_in_timed_steps": step_misses,
         "step_kernels_ms": {"accumulate_kernel": step_ms4[0] / max(step_calls[0], 1),
                             "phase_launches": step_ms4[1] / max(step_calls[0], 1),
                             "decompress_tiles_kernel": step_ms4[3] / max(step_calls[1], 1)},

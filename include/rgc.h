@@ -147,9 +147,10 @@ int rgc_selftest(rgc_ctx* ctx, void* hip_stream);
  * inconsistency.  A diagnostic for tests and benchmarks. */
 int rgc_last_paths(rgc_ctx* ctx, int32_t* out, int32_t num_layers, void* hip_stream);
 
-/* Like rgc_last_paths with more detail: out is int64[num_layers][4] = { path, number of
+/* Like rgc_last_paths with more detail: out is int64[num_layers][5] = { path, number of
  * candidates the streaming pass collected (0 on the hint-free path), number of candidates that
- * had to be ranked exactly, magnitude key (float bits, sign cleared) of the k-th entry }. */
+ * had to be ranked exactly, magnitude key (float bits, sign cleared) of the k-th entry, number
+ * of calls since rgc_create in which this layer slot's hint missed (path 2) }. */
 int rgc_last_stats(rgc_ctx* ctx, int64_t* out, int32_t num_layers, void* hip_stream);
 
 /* Kernel timing for benchmarks.  rgc_profile_enable(ctx, 1) makes every later compression and

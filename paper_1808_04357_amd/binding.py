@@ -161,10 +161,10 @@ class Context:
         return list(ms), list(calls)
 
     def last_stats(self, num_layers: int, stream=None) -> List[List[int]]:
-        """-> per layer [path, candidates, exactly ranked candidates, threshold key]."""
-        out = (ctypes.c_int64 * (4 * num_layers))()
+        """-> per layer [path, candidates, exactly ranked candidates, threshold key, hint misses so far]."""
+        out = (ctypes.c_int64 * (5 * num_layers))()
         _check(self._lib.rgc_last_stats(self._h, out, int(num_layers), _stream(stream)))
-        return [list(out[4 * l:4 * l + 4]) for l in range(num_layers)]
+        return [list(out[5 * l:5 * l + 5]) for l in range(num_layers)]
 
     def decompress_status(self, stream=None) -> int:
         """OR of the RGC_STATUS_* bits found by the RGC_VALIDATE checks so far (waits for the stream; clears the word)."""

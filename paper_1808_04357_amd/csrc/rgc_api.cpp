@@ -486,10 +486,11 @@ int rgc_last_stats(rgc_ctx* ctx, int64_t* out, int32_t num_layers, void* hip_str
   RGC_HIP(hipMemcpyAsync(st.data(), ctx->d_state.p, sizeof(LayerState) * num_layers, hipMemcpyDeviceToHost, stream));
   RGC_HIP(hipStreamSynchronize(stream));
   for (int32_t l = 0; l < num_layers; ++l) {
-    out[4 * l + 0] = st[l].path;
-    out[4 * l + 1] = st[l].stat_candidates;
-    out[4 * l + 2] = st[l].stat_members;
-    out[4 * l + 3] = st[l].T;
+    out[5 * l + 0] = st[l].path;
+    out[5 * l + 1] = st[l].stat_candidates;
+    out[5 * l + 2] = st[l].stat_members;
+    out[5 * l + 3] = st[l].T;
+    out[5 * l + 4] = st[l].stat_misses;
   }
   return RGC_OK;
 }

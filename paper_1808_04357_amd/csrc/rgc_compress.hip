@@ -450,6 +450,7 @@ __device__ void resolve_collect(const CompressArgs& A, uint32_t l, const LayerDe
       st->tau_next = static_cast<uint32_t>(tn);
     } else {
       st->path = 2u;
+      st->stat_misses += 1u;
       st->next_phase = PH_HIST1;
     }
     st->next_launch = 2u;

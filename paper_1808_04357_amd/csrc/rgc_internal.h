@@ -76,7 +76,7 @@ struct LayerState {
   uint32_t has_prev;
   uint32_t stat_candidates;  // diagnostics of the last call
   uint32_t stat_members;
-  uint32_t pad;
+  uint32_t stat_misses;      // calls so far in which this layer's hint missed (never reset)
 };
 
 struct CompressArgs {
