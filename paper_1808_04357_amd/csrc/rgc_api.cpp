@@ -211,6 +211,10 @@ int build_compress_plan(rgc_ctx* ctx, CompressPlan& P, const rgc_layer* layers, 
     const uint64_t target = 2 * k + margin;   // rank the next threshold is aimed at
     const uint64_t per_chunk = (target * kChunk + span - 1) / span;         // expected per wave-chunk
     d.hintable = (2 * per_chunk + 16 <= kCap) ? 1u : 0u;
+    // The candidates between the threshold aimed at and the k-th key fall into several hundred coarse
+    // bins, and the one bin that holds the k-th key must fit the member list: beyond about a million
+    // selected entries per layer it would not, and the hint would miss on every call.
+    if (k > static_cast<uint64_t>(kMemberMax) * 256u) d.hintable = 0u;
     d.margin = static_cast<uint32_t>(margin);
     const uint64_t cmax = std::min<uint64_t>(2 * target, (kCap / 2) * (span / kChunk));
     d.cmax = static_cast<uint32_t>(std::min<uint64_t>(cmax, 0x7FFFFFFFu));

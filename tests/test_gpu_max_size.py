@@ -1,0 +1,126 @@
+"""GPU checks at the largest tensor the interface admits (n = 2^31 - 1, an odd length): the index
+arithmetic of both entry points next to its limit.  A full sort of two billion pairs is out of the
+oracle's reach, so the outputs are checked through what defines them at any size (Section 2.1:
+the communication-set is the k entries of largest magnitude; Algorithm 1: the rest stays in the
+residual): count, order and range of the indices, values and residual bit for bit against the
+accumulated tensor, every key above the k-th selected, the k-th key's ties taken from the lowest
+indices.  The accumulated tensor itself is one IEEE fp32 addition per element, done here with a
+plain device-wide tensor addition."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+N_MAX = 2 ** 31 - 1
+
+
+@pytest.fixture(scope="module")
+def rgc():
+    torch = pytest.importorskip("torch")
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    free, _ = torch.cuda.mem_get_info()
+    if free < 80 * 2 ** 30:
+        pytest.skip("needs 80 GiB of free device memory")
+    import paper_1808_04357_amd as pkg
+    pkg.load_library()
+    return pkg
+
+
+def check_selection(torch, tag, a_ref, k, out_idx, out_val, out_count, V_new):
+    n = a_ref.numel()
+    assert int(out_count.item()) == k, tag + ": count"
+    idx = out_idx.to(torch.int64)
+    assert int(idx.min()) >= 0 and int(idx.max()) < n, tag + ": index range"
+    assert bool((idx[1:] > idx[:-1]).all()), tag + ": indices not strictly ascending"
+    bits = a_ref.view(torch.int32)
+    assert torch.equal(out_val.view(torch.int32), bits[idx]), tag + ": values are not the accumulated entries"
+    expect = a_ref.clone()
+    expect[idx] = 0.0
+    assert torch.equal(V_new.view(torch.int32), expect.view(torch.int32)), tag + ": residual"
+    del expect
+    keys = bits & 0x7FFFFFFF
+    sel_keys = keys[idx]
+    T = int(sel_keys.min())
+    above = int((keys > T).sum())
+    at_least = int((keys >= T).sum())
+    assert above < k <= at_least, tag + ": the smallest selected key is not the k-th largest"
+    assert int((sel_keys > T).sum()) == above, tag + ": an entry above the k-th key was left out"
+    ties = torch.nonzero(keys == T).flatten()           # ascending
+    admitted = ties[: k - above]
+    pos = torch.searchsorted(idx, admitted)
+    pos = pos.clamp(max=idx.numel() - 1)
+    assert torch.equal(idx[pos], admitted), tag + ": ties at the k-th key were not taken from the lowest indices"
+
+
+@pytest.mark.parametrize("ppm,k_expected", [(1000, 2_147_484), (100, 214_749)])
+def test_compress_largest_tensor(rgc, ppm, k_expected):
+    """Density 0.1 %: more than a million entries are selected, such a layer always takes the
+    multi-pass path.  Density 0.01 %: the hinted one-pass path runs from the second or third call on."""
+    import torch
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(0x5EED0001)
+    n = N_MAX
+    k = rgc.rgc_k_for_density(n, ppm)
+    assert k == k_expected
+    V = torch.randn(n, device=dev, generator=gen) * 5e-3
+    # a run of equal magnitudes across the k-th key region would need luck; plant a small one at the top instead:
+    # 64 entries of the same large magnitude with mixed signs, the tie rule decides nothing here but the keys tie
+    V[torch.arange(7, 7 + 64 * 1000, 1000, device=dev)] = 1.0
+    V[torch.arange(7 + 500, 7 + 500 + 64 * 1000, 1000, device=dev)] = -1.0
+    out_idx = torch.full((k,), -1, dtype=torch.int32, device=dev)
+    out_val = torch.full((k,), float("nan"), dtype=torch.float32, device=dev)
+    out_count = torch.full((1,), -1, dtype=torch.int32, device=dev)
+    G = torch.empty(n, dtype=torch.float32, device=dev)
+    layers = rgc.LayerList([G], [V], [k], [out_idx], [out_val], out_count)
+    ctx = rgc.Context(n, 1)
+    stream = torch.cuda.current_stream()
+    seen_paths = set()
+    for step in range(4):                               # hint-free first call, hinted calls after it
+        G.copy_(torch.randn(n, device=dev, generator=gen) * 1e-3)
+        a_ref = V + G
+        rgc.rgc_compress_layers(ctx, layers, 0.0, 0, stream)
+        torch.cuda.synchronize()
+        paths = ctx.last_paths(1, stream)
+        print("  largest tensor step %d: path %s" % (step, paths), flush=True)
+        seen_paths.add(paths[0])
+        check_selection(torch, "n=2^31-1 density %d ppm step %d" % (ppm, step), a_ref, k, out_idx, out_val, out_count, V)
+        del a_ref
+    assert 1 in seen_paths
+    if ppm == 100:
+        assert 0 in seen_paths, "the one-pass path is meant to run here"
+    ctx.close()
+
+
+def test_decompress_largest_tensor_disjoint_workers(rgc):
+    """Workers with disjoint index sets: every position receives at most one value, so the result is
+    the plain scatter of the values times the scale, whatever the order."""
+    import torch
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(0x5EED0005)
+    n, N, per = N_MAX, 4, 1_000_000
+    d_idx, d_val = [], []
+    for w in range(N):
+        base = torch.randint(0, (n - 8) // N, (per,), device=dev, generator=gen, dtype=torch.int64)
+        ii = torch.unique(base) * N + w                 # sorted, distinct, congruent to w modulo N
+        if w == (n - 1) % N:
+            ii = torch.cat([ii[ii < n - 1], torch.tensor([n - 1], device=dev)])   # the very last position
+        if w == 0:
+            ii = torch.unique(torch.cat([torch.tensor([0], device=dev), ii]))     # and the first
+        assert int(ii.max()) < n
+        d_idx.append([ii.to(torch.int32)])
+        d_val.append([torch.randn(ii.numel(), device=dev, generator=gen)])
+    dense = torch.full((n,), float("nan"), dtype=torch.float32, device=dev)
+    msgs = rgc.MessageList(d_idx, d_val, [dense])
+    ctx = rgc.Context(1024, 1)
+    scale = 0.25
+    flags = rgc.RGC_OVERWRITE | rgc.RGC_VALIDATE
+    rgc.rgc_decompress_accumulate(ctx, msgs, scale, flags, torch.cuda.current_stream())
+    assert ctx.decompress_status(torch.cuda.current_stream()) == 0
+    ref = torch.zeros(n, dtype=torch.float32, device=dev)
+    for w in range(N):
+        ref[d_idx[w][0].to(torch.int64)] = (0.0 + d_val[w][0]) * scale
+    assert torch.equal(dense.view(torch.int32), ref.view(torch.int32))
+    ctx.close()
