@@ -15,6 +15,10 @@
  * the call returns.  Work is enqueued on the caller's HIP stream; nothing synchronises the
  * stream or the device.  The context owns only scratch memory and speed hints: results never
  * depend on what an earlier call left in it.
+ * A context serves one call at a time: the calls made on it must be ordered on the device (one
+ * stream, or streams the caller has ordered with events) and come from one host thread at a
+ * time, because they share its scratch.  Different contexts are independent of each other and
+ * may be used from different streams and threads concurrently.
  */
 #ifndef RGC_H_
 #define RGC_H_

@@ -222,3 +222,32 @@ def test_argument_errors(rgc):
     assert status(lambda: rgc.rgc_compress_layers(ctx, bad)) == -1
     torch.cuda.synchronize()
     ctx.close()
+
+
+def test_two_contexts_on_two_streams(rgc, oracle):
+    """Two contexts used on two streams at once (calls of the two interleaved, nothing between them
+    synchronised): each must give its own layer set's oracle result on every step."""
+    import torch
+    g = np.random.default_rng(52)
+    sets = []
+    for s, sizes in enumerate([[300_000, 70_000, 5_000], [1 << 20]]):
+        V = [(g.standard_normal(n) * 5e-3).astype(np.float32) for n in sizes]
+        Gs = [[(g.standard_normal(n) * 1e-3).astype(np.float32) for n in sizes] for _ in range(4)]
+        ks = [rgc.rgc_k_for_density(n) for n in sizes]
+        stream = torch.cuda.Stream()
+        with torch.cuda.stream(stream):
+            dev = GpuLayers(rgc, V, ks)
+        sets.append(dict(V=[v.copy() for v in V], Gs=Gs, ks=ks, dev=dev, stream=stream,
+                         ctx=rgc.Context(sum(sizes), len(sizes))))
+    torch.cuda.synchronize()
+    for t in range(4):
+        for S in sets:                                   # enqueue on both streams before looking at either
+            with torch.cuda.stream(S["stream"]):
+                S["dev"].set_grads(S["Gs"][t])
+            rgc.rgc_compress_layers(S["ctx"], S["dev"].layers, 0.0, 0, S["stream"])
+        for s, S in enumerate(sets):
+            S["stream"].synchronize()
+            msgs = oracle_step(oracle, S["Gs"][t], S["V"], S["ks"])
+            assert_layers_equal("stream %d step %d" % (s, t), S["ks"], S["dev"].results(), msgs, S["V"])
+    for S in sets:
+        S["ctx"].close()
