@@ -3,11 +3,13 @@
 //
 // Tile ownership: one workgroup owns kTile consecutive positions of one dense buffer, adds every
 // worker's entries that fall into the tile and writes the tile once (scaled).  Entries of one
-// worker are unique inside a tile, so positions hit by a single worker need no ordering.  A
-// position hit by several workers gets a row with one slot per worker: every hitter stores its
-// value into its own slot, the other slots hold +0, and one lane adds the row from slot 0
-// upwards.  Adding +0 leaves a partial sum as it is, so this is the sequential sum over the
-// workers bit for bit, independent of scheduling; no floating-point atomics are used.
+// worker are unique inside a tile, so positions hit by a single worker need no ordering: the
+// first entry to reach a position stores its value there.  A position hit by several workers
+// gets a row with one slot per worker: every later hitter stores its value into its own slot,
+// the first one's value is moved from the tile into its slot, the other slots hold +0, and one
+// lane adds the row from slot 0 upwards.  Adding +0 leaves a partial sum as it is, so this is
+// the sequential sum over the workers bit for bit, independent of scheduling; no floating-point
+// atomics are used.
 //
 // The fast kernel (up to kBatchWorkers workers) is persistent and XCD-aware: every XCD gets one
 // contiguous range of tiles and every workgroup a contiguous piece of it, which it walks through
@@ -376,6 +378,7 @@ struct alignas(16) FastLds {
   uint16_t run_p[kRows];                     // the position a row belongs to
   uint32_t pre_cb[kWords];                   // exclusive popcount prefix of cb (only when the rows do not suffice)
   uint8_t qmap[kTile];                       // the row of a colliding position (valid where cb is set)
+  uint8_t who[kTile];                        // the worker whose entry reached a position first (valid where seen is set)
 };
 static_assert(sizeof(FastLds) <= 53 * 1024, "three 8-wave workgroups per CU");
 static_assert(kRows <= 64 && kRows < 256, "one wave adds the rows; row numbers are bytes");
@@ -562,24 +565,32 @@ decompress_tiles_kernel(DecompressArgs A) {
       uint32_t* const cb = S.cb[par];
       // ---- mark the positions hit, and those hit again; whoever finds a position hit for the
       // second time gives it a row (the numbering depends on timing, the sums do not)
-      auto mark = [&](uint32_t p) {
+      // The first entry to reach a position puts its value straight into the tile and leaves its
+      // worker's number there; should the position turn out to be hit again, the lane that adds the
+      // position's row up moves that value into the row first.  Returns whether the entry came later.
+      auto mark = [&](uint32_t p, float v) -> bool {
         const uint32_t bit = 1u << (p & 31u);
         if (atomicOr(&seen[p >> 5], bit) & bit) {
           if (!(atomicOr(&cb[p >> 5], bit) & bit)) {
             const uint32_t qq = atomicAdd(&S.nq[par], 1u);
             if (qq < kRows) { S.qmap[p] = static_cast<uint8_t>(qq); S.run_p[qq] = static_cast<uint16_t>(p); }
           }
+          return true;
         }
+        S.acc[p] = __fadd_rn(0.0f, v);
+        S.who[p] = static_cast<uint8_t>(fresh_tid() >> 2);
+        return false;
       };
       uint32_t mine = 0;                           // entries of this lane inside the tile
       uint32_t last_in = 0;                        // the window's last entry is inside the tile
+      uint32_t late = 0;                           // bit 4*sl+r: that window entry was not the first at its position
 #pragma unroll
       for (uint32_t sl = 0; sl < 2u; ++sl) {
 #pragma unroll
         for (uint32_t r = 0; r < 4u; ++r) {
           const uint32_t p = b_idx[sl][r] - g.first;
           if (p < g.len) {
-            mark(p);
+            if (mark(p, b_val[sl][r])) late |= 1u << (4u * sl + r);
             ++mine;
             if (r == 3u && q == 3u && have[sl] == (E >> 4) + 1u) last_in = 1u;
           }
@@ -593,7 +604,7 @@ decompress_tiles_kernel(DecompressArgs A) {
         for (uint32_t e = beyond + q; e < my_count; e += 4u) {
           const uint32_t p = static_cast<uint32_t>(my_idx[e]) - g.first;
           if (p >= g.len) break;
-          mark(p);
+          (void)mark(p, my_val[e]);
           ++mine;
         }
       }
@@ -609,6 +620,10 @@ decompress_tiles_kernel(DecompressArgs A) {
       auto sum_rows = [&](uint32_t count) {
         const uint32_t row = fresh_tid();
         if (row < count) {
+          {
+            const uint32_t p = S.run_p[row];
+            S.rows[row * kRowStride + S.who[p]] = S.acc[p];   // the position's first arrival (it may be there already)
+          }
           const vf4* const r4 = reinterpret_cast<const vf4*>(S.rows + row * kRowStride);
           float sum = 0.0f;
           uint32_t gi = 0;
@@ -666,9 +681,7 @@ decompress_tiles_kernel(DecompressArgs A) {
         for (uint32_t d0 = 0; d0 < nq; d0 += kRows) {
           for_my_entries([&](uint32_t p, float v) {
             const uint32_t word = cb[p >> 5], sh = p & 31u;
-            if (!((word >> sh) & 1u)) {
-              if (d0 == 0u) S.acc[p] = __fadd_rn(0.0f, v);
-            } else {
+            if ((word >> sh) & 1u) {
               const uint32_t d = S.pre_cb[p >> 5] + static_cast<uint32_t>(__popc(word & ((1u << sh) - 1u))) - d0;
               if (d < kRows) { S.rows[d * kRowStride + my_slot] = v; S.run_p[d] = static_cast<uint16_t>(p); }
             }
@@ -680,16 +693,33 @@ decompress_tiles_kernel(DecompressArgs A) {
         E += consumed;
         fill_window();
       } else {
-        // ---- positions hit once are final; the others put their value into their worker's slot of the row
-        {
+        // ---- positions hit once are final; the entries that came later put their value into their
+        // worker's slot of the position's row
+        if (nq != 0u) {
           const uint32_t my_slot = fresh_tid() >> 2;   // = wl
-          for_my_entries([&](uint32_t p, float v) {
-            const uint32_t colliding = nq != 0u ? (cb[p >> 5] >> (p & 31u)) & 1u : 0u;
-            if (!colliding) S.acc[p] = __fadd_rn(0.0f, v);
-            else S.rows[static_cast<uint32_t>(S.qmap[p]) * kRowStride + my_slot] = v;
-          });
+          if (late != 0u) {
+            uint32_t first = g.first;
+            asm volatile("" : "+s"(first));        // recompute the positions here rather than keep (and spill) them
+#pragma unroll
+            for (uint32_t sl = 0; sl < 2u; ++sl) {
+#pragma unroll
+              for (uint32_t r = 0; r < 4u; ++r) {
+                if ((late >> (4u * sl + r)) & 1u) {
+                  const uint32_t p = b_idx[sl][r] - first;
+                  S.rows[static_cast<uint32_t>(S.qmap[p]) * kRowStride + my_slot] = b_val[sl][r];
+                }
+              }
+            }
+          }
+          if (more) {                              // beyond the window: whoever is on a colliding position (a first arrival twice: harmless)
+            for (uint32_t e = beyond + q; e < my_count; e += 4u) {
+              const uint32_t p = static_cast<uint32_t>(my_idx[e]) - g.first;
+              if (p >= g.len) break;
+              if ((cb[p >> 5] >> (p & 31u)) & 1u) S.rows[static_cast<uint32_t>(S.qmap[p]) * kRowStride + my_slot] = my_val[e];
+            }
+          }
+          __syncthreads();
         }
-        __syncthreads();
         // the tile's entries are used up: move the window on; its new blocks arrive while the tile is finished
         E += consumed;
         fill_window();
@@ -727,8 +757,7 @@ decompress_tiles_kernel(DecompressArgs A) {
           d[i] = o;
         }
       }
-      // no barrier here: the next tile marks in the other set of maps, and writes nothing that
-      // the threads still busy with this tile read before the barrier that follows the marking
+      __syncthreads();                             // the next tile's first arrivals write into the accumulator that this one has just cleared
     }
   }
 }
