@@ -50,6 +50,19 @@ def lib() -> ctypes.CDLL:
             ctypes.POINTER(_f32p), ctypes.POINTER(_f32p), ctypes.POINTER(_f32p),
             ctypes.POINTER(ctypes.c_int64), _i32p, ctypes.c_int32, ctypes.c_float, ctypes.c_int,
             ctypes.POINTER(_i32p), ctypes.POINTER(_f32p), _i32p, ctypes.c_int32]
+        L.rgc_oracle_compress_layer_ex.restype = ctypes.c_int
+        L.rgc_oracle_compress_layer_ex.argtypes = [_f32p, _f32p, _f32p, ctypes.c_int64, ctypes.c_int32,
+                                                   ctypes.c_float, ctypes.c_int, ctypes.c_int, _f32p,
+                                                   _i32p, _f32p, _i32p]
+        L.rgc_oracle_compress_layers_ex.restype = ctypes.c_int
+        L.rgc_oracle_compress_layers_ex.argtypes = [
+            ctypes.POINTER(_f32p), ctypes.POINTER(_f32p), ctypes.POINTER(_f32p),
+            ctypes.POINTER(ctypes.c_int64), _i32p, ctypes.c_int32, ctypes.c_float, ctypes.c_int,
+            ctypes.c_int, _f32p, ctypes.POINTER(_i32p), ctypes.POINTER(_f32p), _i32p, ctypes.c_int32]
+        L.rgc_oracle_clip_coefficient.restype = ctypes.c_float
+        L.rgc_oracle_clip_coefficient.argtypes = [ctypes.POINTER(_f32p), ctypes.POINTER(ctypes.c_int64),
+                                                  ctypes.c_int32, ctypes.c_float, ctypes.c_int32,
+                                                  ctypes.POINTER(ctypes.c_double)]
         L.rgc_oracle_decompress.restype = ctypes.c_int
         L.rgc_oracle_decompress.argtypes = [
             ctypes.POINTER(_i32p), ctypes.POINTER(_f32p), _i32p, ctypes.c_int32, _f32p,
@@ -78,9 +91,18 @@ def hardware_threads() -> int:
     return int(lib().rgc_oracle_hardware_threads())
 
 
+def _scale_arg(grad_scale):
+    """None, or a one-element float32 array holding the clipping coefficient."""
+    if grad_scale is None:
+        return None, None
+    keep = np.array([grad_scale], dtype=np.float32)
+    return keep, _f32(keep)
+
+
 def compress_layer(grad: np.ndarray, residual: np.ndarray, k: int,
                    momentum: Optional[np.ndarray] = None, m: float = 0.0,
-                   mask_momentum: bool = True, bruteforce: bool = False
+                   mask_momentum: bool = True, bruteforce: bool = False,
+                   nesterov: bool = False, grad_scale: Optional[float] = None
                    ) -> Tuple[np.ndarray, np.ndarray, int]:
     """Compress one layer IN PLACE (residual, momentum are updated).
 
@@ -90,6 +112,16 @@ def compress_layer(grad: np.ndarray, residual: np.ndarray, k: int,
     out_idx = np.empty(k, dtype=np.int32)
     out_val = np.empty(k, dtype=np.float32)
     out_cnt = np.zeros(1, dtype=np.int32)
+    if nesterov or grad_scale is not None:
+        assert not bruteforce
+        keep, sp = _scale_arg(grad_scale)
+        rc = lib().rgc_oracle_compress_layer_ex(
+            _f32(grad), _f32(residual), _f32(momentum) if momentum is not None else None, n, int(k),
+            float(m), 1 if mask_momentum else 0, 1 if nesterov else 0, sp, _i32(out_idx),
+            _f32(out_val), _i32(out_cnt))
+        if rc != 0:
+            raise ValueError("oracle rejected the arguments")
+        return out_idx, out_val, int(out_cnt[0])
     fn = lib().rgc_oracle_compress_layer_bruteforce if bruteforce else lib().rgc_oracle_compress_layer
     rc = fn(_f32(grad), _f32(residual), _f32(momentum) if momentum is not None else None,
             n, int(k), float(m), 1 if mask_momentum else 0, _i32(out_idx), _f32(out_val),
@@ -101,7 +133,8 @@ def compress_layer(grad: np.ndarray, residual: np.ndarray, k: int,
 
 def compress_layers(grads: Sequence[np.ndarray], residuals: Sequence[np.ndarray],
                     ks: Sequence[int], momenta: Optional[Sequence[np.ndarray]] = None,
-                    m: float = 0.0, mask_momentum: bool = True, threads: int = 1
+                    m: float = 0.0, mask_momentum: bool = True, threads: int = 1,
+                    nesterov: bool = False, grad_scale: Optional[float] = None
                     ) -> List[Tuple[np.ndarray, np.ndarray, int]]:
     """Compress a whole layer set in place, optionally on several host threads."""
     L = len(grads)
@@ -115,12 +148,24 @@ def compress_layers(grads: Sequence[np.ndarray], residuals: Sequence[np.ndarray]
     ov = (_f32p * L)(*[_f32(a) for a in out_val])
     n = (ctypes.c_int64 * L)(*[int(a.size) for a in grads])
     kk = (ctypes.c_int32 * L)(*[int(k) for k in ks])
-    rc = lib().rgc_oracle_compress_layers(g, r, mo, n, kk, L, float(m),
-                                          1 if mask_momentum else 0, oi, ov, _i32(out_cnt),
-                                          int(threads))
+    keep, sp = _scale_arg(grad_scale)
+    rc = lib().rgc_oracle_compress_layers_ex(g, r, mo, n, kk, L, float(m),
+                                             1 if mask_momentum else 0, 1 if nesterov else 0, sp,
+                                             oi, ov, _i32(out_cnt), int(threads))
     if rc != 0:
         raise ValueError("oracle rejected the arguments")
     return [(out_idx[l], out_val[l], int(out_cnt[l])) for l in range(L)]
+
+
+def clip_coefficient(grads: Sequence[np.ndarray], max_norm: float, num_workers: int
+                     ) -> Tuple[float, float]:
+    """-> (coefficient as float32, squared L2 norm over all layers in fp64)."""
+    L = len(grads)
+    g = (_f32p * L)(*[_f32(a) for a in grads])
+    n = (ctypes.c_int64 * L)(*[int(a.size) for a in grads])
+    sq = ctypes.c_double(0.0)
+    c = lib().rgc_oracle_clip_coefficient(g, n, L, float(max_norm), int(num_workers), ctypes.byref(sq))
+    return float(np.float32(c)), float(sq.value)
 
 
 def decompress(idx: Sequence[np.ndarray], val: Sequence[np.ndarray], n: int, scale: float,

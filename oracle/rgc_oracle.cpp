@@ -32,6 +32,19 @@
 //       u = fma(m, u, g)   (one rounding)
 //       a = V + u
 //     and the sent entries are cleared from u as well (momentum masking).
+//   * Nesterov form of the momentum correction (Section 2.5 names it for
+//     Nesterov momentum SGD and defers to DGC, whose rule is
+//     U <- m*(U + G), V <- V + U + G), every operation rounded on its own, the
+//     additions taken from the left:
+//       u = m * (u + g)
+//       a = (V + u) + g
+//   * local gradient clipping (Section 2.4, "Overlapping Communication and
+//     Computation": clipping by a threshold N^(-1/2) of the original one,
+//     locally, before the gradients are added to the residuals): with the
+//     L2 norm taken over all layers of the call, summed in fp64,
+//       c = norm > t ? t / norm : 1,   t = max_norm / sqrt(N)   (fp64, then
+//     rounded to fp32 once), and every gradient element enters the
+//     accumulate as fl(c * g).
 //   * decompression: acc starts at +0, workers are added in order 0..N-1 and
 //     entries in message order, all in fp32; then either dense = acc*scale or
 //     dense = dense + acc*scale (two roundings, no fused multiply-add).
@@ -58,16 +71,26 @@ inline uint32_t magnitude_key(float x) { return float_bits(x) & 0x7FFFFFFFu; }
 
 // Step 1 of the layer loop: produce the accumulated tensor a (and the updated
 // velocity when momentum correction is on).  Writes a into `acc`.
+// `scale` (may be NULL) is the clipping coefficient applied to every gradient
+// element first; `nesterov` selects the Nesterov form of the correction.
 void accumulate(const float* grad, const float* residual, float* momentum,
-                int64_t n, float m, std::vector<float>& acc) {
+                int64_t n, float m, int nesterov, const float* scale, std::vector<float>& acc) {
   acc.resize(static_cast<size_t>(n));
-  if (momentum == nullptr) {
-    for (int64_t i = 0; i < n; ++i) acc[i] = residual[i] + grad[i];
-  } else {
-    for (int64_t i = 0; i < n; ++i) {
-      float u = std::fmaf(m, momentum[i], grad[i]);
+  for (int64_t i = 0; i < n; ++i) {
+    float g = grad[i];
+    if (scale != nullptr) g = *scale * g;
+    if (momentum == nullptr) {
+      acc[i] = residual[i] + g;
+    } else if (!nesterov) {
+      float u = std::fmaf(m, momentum[i], g);
       momentum[i] = u;
       acc[i] = residual[i] + u;
+    } else {
+      float t = momentum[i] + g;
+      float u = m * t;
+      momentum[i] = u;
+      float s = residual[i] + u;
+      acc[i] = s + g;
     }
   }
 }
@@ -108,13 +131,15 @@ int32_t rgc_oracle_k_for_density(int64_t n, uint32_t density_ppm) {
 // One layer of the compression step, exact top-k by a full sort of
 // (magnitude key descending, index ascending).  `momentum` may be NULL.
 // Returns 0, or -1 on bad arguments.
-int rgc_oracle_compress_layer(const float* grad, float* residual, float* momentum,
-                              int64_t n, int32_t k, float m, int mask_momentum,
-                              int32_t* out_idx, float* out_val, int32_t* out_count) {
+// `nesterov` and `scale` (NULL: none) as described at the top of this file.
+int rgc_oracle_compress_layer_ex(const float* grad, float* residual, float* momentum,
+                                 int64_t n, int32_t k, float m, int mask_momentum, int nesterov,
+                                 const float* scale,
+                                 int32_t* out_idx, float* out_val, int32_t* out_count) {
   if (!grad || !residual || !out_idx || !out_val || !out_count) return -1;
   if (n < 1 || n >= (int64_t(1) << 31) || k < 1 || k > n) return -1;
   std::vector<float> acc;
-  accumulate(grad, residual, momentum, n, m, acc);
+  accumulate(grad, residual, momentum, n, m, nesterov, scale, acc);
 
   std::vector<std::pair<uint32_t, int32_t>> order(static_cast<size_t>(n));
   for (int64_t i = 0; i < n; ++i)
@@ -130,6 +155,13 @@ int rgc_oracle_compress_layer(const float* grad, float* residual, float* momentu
   return 0;
 }
 
+int rgc_oracle_compress_layer(const float* grad, float* residual, float* momentum,
+                              int64_t n, int32_t k, float m, int mask_momentum,
+                              int32_t* out_idx, float* out_val, int32_t* out_count) {
+  return rgc_oracle_compress_layer_ex(grad, residual, momentum, n, k, m, mask_momentum, 0, nullptr,
+                                      out_idx, out_val, out_count);
+}
+
 // Same result by brute force, for tiny n only: k rounds of "largest remaining
 // magnitude, first occurrence".  Exists to pin the sort-based version.
 int rgc_oracle_compress_layer_bruteforce(const float* grad, float* residual, float* momentum,
@@ -138,7 +170,7 @@ int rgc_oracle_compress_layer_bruteforce(const float* grad, float* residual, flo
   if (!grad || !residual || !out_idx || !out_val || !out_count) return -1;
   if (n < 1 || n > 4096 || k < 1 || k > n) return -1;
   std::vector<float> acc;
-  accumulate(grad, residual, momentum, n, m, acc);
+  accumulate(grad, residual, momentum, n, m, 0, nullptr, acc);
   std::vector<char> taken(static_cast<size_t>(n), 0);
   std::vector<int32_t> sel;
   for (int32_t round = 0; round < k; ++round) {
@@ -157,18 +189,19 @@ int rgc_oracle_compress_layer_bruteforce(const float* grad, float* residual, flo
 // A whole layer set, layers handed to `threads` host threads round-robin
 // (layers are independent in Algorithm 1's inner loop).  threads <= 1 runs the
 // plain sequential loop.  Only used to time the oracle on several cores.
-int rgc_oracle_compress_layers(const float* const* grad, float* const* residual,
-                               float* const* momentum, const int64_t* n, const int32_t* k,
-                               int32_t num_layers, float m, int mask_momentum,
-                               int32_t* const* out_idx, float* const* out_val,
-                               int32_t* out_count, int32_t threads) {
+int rgc_oracle_compress_layers_ex(const float* const* grad, float* const* residual,
+                                  float* const* momentum, const int64_t* n, const int32_t* k,
+                                  int32_t num_layers, float m, int mask_momentum, int nesterov,
+                                  const float* scale,
+                                  int32_t* const* out_idx, float* const* out_val,
+                                  int32_t* out_count, int32_t threads) {
   if (num_layers < 0) return -1;
   std::vector<int> rc(static_cast<size_t>(num_layers), 0);
   auto work = [&](int32_t first, int32_t step) {
     for (int32_t l = first; l < num_layers; l += step)
-      rc[l] = rgc_oracle_compress_layer(grad[l], residual[l], momentum ? momentum[l] : nullptr,
-                                        n[l], k[l], m, mask_momentum, out_idx[l], out_val[l],
-                                        &out_count[l]);
+      rc[l] = rgc_oracle_compress_layer_ex(grad[l], residual[l], momentum ? momentum[l] : nullptr,
+                                           n[l], k[l], m, mask_momentum, nesterov, scale,
+                                           out_idx[l], out_val[l], &out_count[l]);
   };
   if (threads <= 1) {
     work(0, 1);
@@ -180,6 +213,32 @@ int rgc_oracle_compress_layers(const float* const* grad, float* const* residual,
   for (int32_t l = 0; l < num_layers; ++l)
     if (rc[l] != 0) return -1;
   return 0;
+}
+
+int rgc_oracle_compress_layers(const float* const* grad, float* const* residual,
+                               float* const* momentum, const int64_t* n, const int32_t* k,
+                               int32_t num_layers, float m, int mask_momentum,
+                               int32_t* const* out_idx, float* const* out_val,
+                               int32_t* out_count, int32_t threads) {
+  return rgc_oracle_compress_layers_ex(grad, residual, momentum, n, k, num_layers, m, mask_momentum,
+                                       0, nullptr, out_idx, out_val, out_count, threads);
+}
+
+// Local gradient clipping coefficient over all layers of one call (see the top
+// of this file).  Also stores the squared norm (fp64) if sqnorm is not NULL.
+float rgc_oracle_clip_coefficient(const float* const* grad, const int64_t* n, int32_t num_layers,
+                                  float max_norm, int32_t num_workers, double* sqnorm) {
+  double sum = 0.0;
+  for (int32_t l = 0; l < num_layers; ++l)
+    for (int64_t i = 0; i < n[l]; ++i) {
+      double g = static_cast<double>(grad[l][i]);
+      sum += g * g;
+    }
+  if (sqnorm) *sqnorm = sum;
+  double norm = std::sqrt(sum);
+  double t = static_cast<double>(max_norm) / std::sqrt(static_cast<double>(num_workers));
+  double c = norm > t ? t / norm : 1.0;
+  return static_cast<float>(c);
 }
 
 // Decompression of one layer: N messages (idx[w], val[w], count[w]) added in

@@ -320,6 +320,98 @@ def test_momentum_zero_reduces_to_plain(oracle):
     assert np.array_equal(i1, i2) and np.array_equal(x1, x2) and np.array_equal(v1, v2)
 
 
+# ------------------------------------------------------------------ Nesterov form, clipping
+
+def test_nesterov_form_against_exact_rational(oracle):
+    """u = m*(u+g), a = (V+u)+g with every operation rounded on its own (DGC's rule for Nesterov
+    momentum, which Section 2.5 adopts): each rounding is redone here in exact rational arithmetic."""
+    g = np.random.default_rng(31)
+    n, k = 300, 3
+    G = g.standard_normal(n).astype(np.float32)
+    U = g.standard_normal(n).astype(np.float32)
+    V = g.standard_normal(n).astype(np.float32)
+    m = np.float32(0.9)
+    F = lambda x: Fraction(float(x))
+    t = [_round_to_f32(F(U[i]) + F(G[i])) for i in range(n)]
+    u_exp = np.array([_round_to_f32(F(m) * F(t[i])) for i in range(n)], np.float32)
+    s_exp = [_round_to_f32(F(V[i]) + F(u_exp[i])) for i in range(n)]
+    a_exp = np.array([_round_to_f32(F(s_exp[i]) + F(G[i])) for i in range(n)], np.float32)
+    u, v = U.copy(), V.copy()
+    idx, val, cnt = oracle.compress_layer(G, v, k, momentum=u, m=float(m), nesterov=True)
+    check_invariants(a_exp, k, idx, val, cnt, v)
+    sel = np.zeros(n, bool)
+    sel[idx] = True
+    assert np.array_equal(u[~sel].view(np.uint32), u_exp[~sel].view(np.uint32))
+    assert np.all(u.view(np.uint32)[sel] == 0)
+
+
+def test_nesterov_hand_case_differs_from_plain_correction(oracle):
+    """V=0, u=1, g=1, m=1/2: plain correction gives u = 1.5, a = 1.5; the Nesterov form u = 1, a = 2."""
+    for nesterov, u_want, a_want in ((False, 1.5, 1.5), (True, 1.0, 2.0)):
+        G = np.array([1.0, 0.0], np.float32)
+        U = np.array([1.0, 0.0], np.float32)
+        V = np.array([0.0, 50.0], np.float32)          # element 1 is the one that gets sent
+        idx, val, cnt = oracle.compress_layer(G, V, 1, momentum=U, m=0.5, nesterov=nesterov)
+        assert idx.tolist() == [1]
+        assert U[0] == np.float32(u_want) and V[0] == np.float32(a_want)
+
+
+def test_nesterov_additions_are_taken_from_the_left(oracle):
+    """(V + u) + g, not V + (u + g): V = 2^24, u' = 1, g = 1 gives 2^24 one way and 2^24 + 2 the other."""
+    m = np.float32(1.0)
+    G = np.array([1.0, 0.0], np.float32)
+    U = np.array([0.0, 0.0], np.float32)                # u' = 1 * (0 + 1) = 1
+    V = np.array([2.0 ** 24, 2.0 ** 30], np.float32)
+    oracle.compress_layer(G, V, 1, momentum=U, m=float(m), nesterov=True)
+    assert V[0] == np.float32(2.0 ** 24)                # (2^24 + 1) rounds to 2^24, + 1 again
+
+
+def test_gradient_scale_is_one_rounded_product(oracle):
+    g = np.random.default_rng(32)
+    n, k = 400, 4
+    G = g.standard_normal(n).astype(np.float32)
+    V = g.standard_normal(n).astype(np.float32)
+    c = np.float32(0.3)
+    F = lambda x: Fraction(float(x))
+    gs = np.array([_round_to_f32(F(c) * F(G[i])) for i in range(n)], np.float32)
+    v1, v2 = V.copy(), V.copy()
+    i1, x1, _ = oracle.compress_layer(G, v1, k, grad_scale=float(c))
+    i2, x2, _ = oracle.compress_layer(gs, v2, k)
+    assert np.array_equal(i1, i2) and np.array_equal(x1.view(np.uint32), x2.view(np.uint32))
+    assert np.array_equal(v1.view(np.uint32), v2.view(np.uint32))
+    # a coefficient of one changes nothing
+    v3 = V.copy()
+    i3, x3, _ = oracle.compress_layer(G, v3, k, grad_scale=1.0)
+    v4 = V.copy()
+    i4, x4, _ = oracle.compress_layer(G, v4, k)
+    assert np.array_equal(i3, i4) and np.array_equal(v3.view(np.uint32), v4.view(np.uint32))
+
+
+def test_clip_coefficient_closed_forms(oracle):
+    """Section 2.4: local clipping by a threshold N^(-1/2) of the original one."""
+    ones = [np.ones(9, np.float32), np.ones(7, np.float32)]          # norm 4 over both layers
+    c, sq = oracle.clip_coefficient(ones, 1.0, 4)                      # threshold 1/2
+    assert sq == 16.0 and c == np.float32(0.125)
+    c, _ = oracle.clip_coefficient(ones, 8.0, 4)                       # threshold 4 = norm: not exceeded
+    assert c == 1.0
+    c, _ = oracle.clip_coefficient(ones, 100.0, 1)
+    assert c == 1.0
+    c, _ = oracle.clip_coefficient([np.zeros(5, np.float32)], 1.0, 16)
+    assert c == 1.0
+    # a 3-4-5 triangle split over two layers, 16 workers: threshold 10/4 = 2.5, norm 5
+    c, sq = oracle.clip_coefficient([np.array([3.0], np.float32), np.array([0.0, 4.0], np.float32)], 10.0, 16)
+    assert sq == 25.0 and c == np.float32(0.5)
+    # against an exact sum: integers small enough for every partial sum to be exact in fp64
+    g = np.random.default_rng(33)
+    G = [g.integers(-1000, 1000, 5000).astype(np.float32), g.integers(-1000, 1000, 777).astype(np.float32)]
+    exact = sum(int(x) * int(x) for a in G for x in a)
+    c, sq = oracle.clip_coefficient(G, 3.0, 9)
+    assert sq == float(exact)
+    from math import isqrt
+    want = Fraction(1) / Fraction(exact)                               # c^2 = (3/3)^2 / exact = 1 / exact
+    assert abs(Fraction(float(c)) ** 2 - want) <= want * Fraction(1, 2 ** 22)
+
+
 # ------------------------------------------------------------------ several iterations
 
 def test_conservation_over_iterations_and_drain(oracle):
