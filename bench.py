@@ -258,6 +258,18 @@ def main():
     except (OSError, ValueError, KeyError):
         pass
 
+    # the step before the accumulate when gradients are clipped locally (Section 2.4): one read of all gradients
+    clip_info = None
+    if not args.step_only:
+        coef = torch.zeros(1, dtype=torch.float32, device=dev)
+        ms_clip = time_loop(torch, lambda: rgc.rgc_clip_coefficient(ctx, vgg.lists[0], 1.0, 128, coef, stream), args.steps)
+        ms_scaled = time_loop(torch, lambda: rgc.rgc_compress_layers_scaled(ctx, vgg.lists[0], vgg.m, coef, rgc.RGC_NESTEROV, stream),
+                              min(args.steps, 20))
+        clip_info = {"clip_coefficient_ms": ms_clip, "gradient_read_GBps": 4.0 * vgg.total / ms_clip / 1e6,
+                     "hbm_frac": 4.0 * vgg.total / (ms_clip * 1e-3) / (HBM_PEAK_GBPS * 1e9),
+                     "coefficient": float(coef.cpu()[0]),
+                     "scaled_nesterov_compress_ms": ms_scaled}
+
     if args.calibrate_copy:
         src = torch.zeros(vgg.total, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
@@ -301,7 +313,7 @@ def main():
         "step_kernels_ms": {"accumulate_kernel": step_ms4[0] / max(step_calls[0], 1),
                             "phase_launches": step_ms4[1] / max(step_calls[0], 1),
                             "decompress_tiles_kernel": step_ms4[3] / max(step_calls[1], 1)},
-        "compress": comp, "decompress": dec_info, "other_workloads": others,
+        "compress": comp, "decompress": dec_info, "local_clipping": clip_info, "other_workloads": others,
         "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(line))

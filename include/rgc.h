@@ -44,6 +44,7 @@ extern "C" {
 #define RGC_NO_HINTS         0x2u /* ignore and do not update the per-layer speed hints:
                                      every layer takes the hint-free multi-pass path        */
 /* rgc_decompress_accumulate: exactly one of the two */
+#define RGC_NESTEROV         0x4u /* momentum correction in its Nesterov form (see below)      */
 #define RGC_OVERWRITE        0x10u /* dense = acc * scale                                   */
 #define RGC_ADD_TO_DST       0x20u /* dense = dense + acc * scale (two roundings, no fma)   */
 #define RGC_VALIDATE         0x40u /* with either of the two: also check the messages on the
@@ -109,6 +110,26 @@ int32_t rgc_k_for_density(int64_t n, uint32_t density_ppm);
  * Errors (nothing is enqueued, no buffer is modified): RGC_EINVAL, RGC_ENOMEM, RGC_EHIP. */
 int rgc_compress_layers(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers,
                         float momentum, uint32_t flags, void* hip_stream);
+
+/* rgc_compress_layers with every gradient element multiplied first by *grad_scale, a float in
+ * DEVICE memory read when the kernel runs (one rounding: g' = fl(scale * g)); NULL = no scaling.
+ * This is how the coefficient of local gradient clipping (Section 2.4) enters the accumulate.
+ * With RGC_NESTEROV (either entry point) the layers that have a velocity use the Nesterov form
+ * of the momentum correction that Section 2.5 names (rule of the DGC paper it defers to):
+ *   u = m * (u + g),  a = (V + u) + g,  every operation rounded on its own, left to right. */
+int rgc_compress_layers_scaled(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers,
+                               float momentum, const float* grad_scale, uint32_t flags,
+                               void* hip_stream);
+
+/* Local gradient clipping (Section 2.4: the gradients of all layers are clipped by their common
+ * norm before they are added to the residuals, with a threshold of N^(-1/2) of the original one).
+ * Enqueues two small kernels that read layers[l].grad of every layer (only grad and n are used) and
+ * store  c = norm > t ? t / norm : 1,  t = max_norm / sqrt(num_workers),  norm = the L2 norm over
+ * all elements of all layers (squares and sums in fp64, a fixed order of additions), into
+ * *coefficient, a float in DEVICE memory, for rgc_compress_layers_scaled to use on the same stream.
+ * Errors (nothing enqueued): RGC_EINVAL (also max_norm <= 0, num_workers < 1), RGC_ENOMEM, RGC_EHIP. */
+int rgc_clip_coefficient(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers, float max_norm,
+                         int32_t num_workers, float* coefficient, void* hip_stream);
 
 /* Decompression of Section 2.3 for `num_layers` dense buffers and `num_workers` workers.
  * msgs is worker-major: msgs[w * num_layers + l] is worker w's message for layer l.

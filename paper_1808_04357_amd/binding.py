@@ -17,6 +17,7 @@ RGC_EHIP = -3
 RGC_EINTERNAL = -4
 RGC_NO_MOMENTUM_MASK = 0x1
 RGC_NO_HINTS = 0x2
+RGC_NESTEROV = 0x4
 RGC_OVERWRITE = 0x10
 RGC_ADD_TO_DST = 0x20
 RGC_VALIDATE = 0x40
@@ -27,6 +28,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("RGC_LIB") or os.path.join(_HERE, "librgc.so")   # RGC_LIB: tuning builds only
 
 EXPORTS = ["rgc_create", "rgc_destroy", "rgc_k_for_density", "rgc_compress_layers",
+           "rgc_compress_layers_scaled", "rgc_clip_coefficient",
            "rgc_decompress_accumulate", "rgc_reset_hints", "rgc_poison_hints", "rgc_selftest",
            "rgc_last_paths", "rgc_last_stats", "rgc_decompress_status", "rgc_profile_enable", "rgc_profile_read", "rgc_strerror"]
 
@@ -72,6 +74,12 @@ def load_library() -> ctypes.CDLL:
     L.rgc_compress_layers.restype = ctypes.c_int
     L.rgc_compress_layers.argtypes = [ctypes.c_void_p, ctypes.POINTER(rgc_layer), ctypes.c_int32,
                                       ctypes.c_float, ctypes.c_uint32, ctypes.c_void_p]
+    L.rgc_compress_layers_scaled.restype = ctypes.c_int
+    L.rgc_compress_layers_scaled.argtypes = [ctypes.c_void_p, ctypes.POINTER(rgc_layer), ctypes.c_int32,
+                                             ctypes.c_float, ctypes.c_void_p, ctypes.c_uint32, ctypes.c_void_p]
+    L.rgc_clip_coefficient.restype = ctypes.c_int
+    L.rgc_clip_coefficient.argtypes = [ctypes.c_void_p, ctypes.POINTER(rgc_layer), ctypes.c_int32, ctypes.c_float,
+                                       ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
     L.rgc_decompress_accumulate.restype = ctypes.c_int
     L.rgc_decompress_accumulate.argtypes = [ctypes.c_void_p, ctypes.POINTER(rgc_msg), ctypes.c_int32,
                                             ctypes.c_int32, ctypes.POINTER(ctypes.c_void_p),
@@ -224,6 +232,20 @@ def rgc_compress_layers(ctx: Context, layers: LayerList, momentum: float = 0.0, 
                         stream=None) -> None:
     _check(load_library().rgc_compress_layers(ctx.handle, layers.array, layers.num_layers,
                                               float(momentum), int(flags), _stream(stream)))
+
+
+def rgc_compress_layers_scaled(ctx: Context, layers: LayerList, momentum: float = 0.0, grad_scale=None,
+                               flags: int = 0, stream=None) -> None:
+    """grad_scale: a one-element float32 device tensor (or None)."""
+    _check(load_library().rgc_compress_layers_scaled(ctx.handle, layers.array, layers.num_layers,
+                                                     float(momentum), _ptr(grad_scale), int(flags), _stream(stream)))
+
+
+def rgc_clip_coefficient(ctx: Context, layers: LayerList, max_norm: float, num_workers: int, coefficient,
+                         stream=None) -> None:
+    """coefficient: a one-element float32 device tensor that receives the clipping coefficient."""
+    _check(load_library().rgc_clip_coefficient(ctx.handle, layers.array, layers.num_layers, float(max_norm),
+                                               int(num_workers), _ptr(coefficient), _stream(stream)))
 
 
 def rgc_decompress_accumulate(ctx: Context, msgs: MessageList, scale: float,

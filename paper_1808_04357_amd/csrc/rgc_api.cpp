@@ -122,6 +122,7 @@ struct CompressPlan {
   PinnedBuf staging;
   hipEvent_t uploaded = nullptr;    // recorded after the uploads
   uint32_t num_wgs = 0;
+  uint32_t num_chunks = 0;                 // wave-chunks over all layers
   uint64_t last_use = 0;
   bool valid = false;
 };
@@ -149,6 +150,7 @@ struct rgc_ctx {
   DevBuf<LayerState> d_state;
   DevBuf<uint32_t> d_hist, d_coarse, d_cand_cnt, d_wc_a, d_wc_b, d_err, d_group;
   DevBuf<unsigned long long> d_members;
+  DevBuf<double> d_norm_part;              // [wave-chunks] partial sums of squares (clipping coefficient)
   DevBuf<uint2> d_slots;
   CompressPlan plans[kPlanCache];
   uint64_t tick = 0;
@@ -238,6 +240,7 @@ int build_compress_plan(rgc_ctx* ctx, CompressPlan& P, const rgc_layer* layers, 
   RGC_HIP(hipEventRecord(P.uploaded, stream));
   P.key.assign(layers, layers + L);
   P.num_wgs = wg;
+  P.num_chunks = wc;
   P.valid = true;
   return RGC_OK;
 }
@@ -362,6 +365,7 @@ int rgc_destroy(rgc_ctx* ctx) {
   ctx->d_slots.release();
   ctx->d_err.release();
   ctx->d_group.release();
+  ctx->d_norm_part.release();
   for (auto* v : {&ctx->ev_compress, &ctx->ev_decompress, &ctx->ev_pool})
     for (hipEvent_t e : *v) (void)hipEventDestroy(e);
   delete ctx;
@@ -383,10 +387,14 @@ int rgc_poison_hints(rgc_ctx* ctx, int mode, void* hip_stream) {
   return RGC_OK;
 }
 
-int rgc_compress_layers(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers, float momentum,
-                        uint32_t flags, void* hip_stream) {
-  if (!ctx || !layers || num_layers < 1 || num_layers > ctx->max_layers) return RGC_EINVAL;
-  if (flags & ~(RGC_NO_MOMENTUM_MASK | RGC_NO_HINTS)) return RGC_EINVAL;
+}  // extern "C"
+
+namespace {
+
+// Checks a layer list and finds (or builds) its plan.  On success *out is the plan and the device
+// of the context is current.
+int plan_for_layers(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers, hipStream_t stream,
+                    CompressPlan** out) {
   int64_t total = 0;
   for (int32_t l = 0; l < num_layers; ++l) {
     const rgc_layer& a = layers[l];
@@ -399,9 +407,6 @@ int rgc_compress_layers(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layer
     total += a.n;
   }
   if (total > ctx->max_total) return RGC_ENOMEM;
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  DeviceGuard guard(ctx->device);
-  if (!guard.ok) return fail_hip(hipErrorInvalidDevice, "hipSetDevice");
 
   // ---- find or build the plan for this exact layer list
   CompressPlan* plan = nullptr;
@@ -423,6 +428,57 @@ int rgc_compress_layers(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layer
     plan = victim;
   }
   plan->last_use = ++ctx->tick;
+  *out = plan;
+  return RGC_OK;
+}
+
+void fill_plan_args(rgc_ctx* ctx, const CompressPlan* plan, CompressArgs& A) {
+  A.layers = plan->d_layers.p;
+  A.wg2layer = plan->d_wg2layer.p;
+  A.chunk = plan->chunk;
+  A.norm_part = ctx->d_norm_part.p;
+}
+
+}  // namespace
+
+extern "C" {
+
+int rgc_clip_coefficient(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers, float max_norm,
+                         int32_t num_workers, float* coefficient, void* hip_stream) {
+  if (!ctx || !layers || !coefficient || num_layers < 1 || num_layers > ctx->max_layers) return RGC_EINVAL;
+  if (!(max_norm > 0.0f) || num_workers < 1 || (reinterpret_cast<uintptr_t>(coefficient) & 3u)) return RGC_EINVAL;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return fail_hip(hipErrorInvalidDevice, "hipSetDevice");
+  CompressPlan* plan = nullptr;
+  const int rc = plan_for_layers(ctx, layers, num_layers, stream, &plan);
+  if (rc != RGC_OK) return rc;
+  if (ctx->d_norm_part.n < ctx->wc_max) RGC_HIP(ctx->d_norm_part.alloc(ctx->wc_max));   // first use only
+  CompressArgs A{};
+  fill_plan_args(ctx, plan, A);
+  const float threshold = static_cast<float>(static_cast<double>(max_norm) / std::sqrt(static_cast<double>(num_workers)));
+  RGC_HIP(launch_clip_coefficient(A, plan->num_wgs, plan->num_chunks, threshold, coefficient, stream));
+  return RGC_OK;
+}
+
+int rgc_compress_layers(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers, float momentum,
+                        uint32_t flags, void* hip_stream) {
+  return rgc_compress_layers_scaled(ctx, layers, num_layers, momentum, nullptr, flags, hip_stream);
+}
+
+int rgc_compress_layers_scaled(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers, float momentum,
+                               const float* grad_scale, uint32_t flags, void* hip_stream) {
+  if (!ctx || !layers || num_layers < 1 || num_layers > ctx->max_layers) return RGC_EINVAL;
+  if (flags & ~(RGC_NO_MOMENTUM_MASK | RGC_NO_HINTS | RGC_NESTEROV)) return RGC_EINVAL;
+  if (reinterpret_cast<uintptr_t>(grad_scale) & 3u) return RGC_EINVAL;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return fail_hip(hipErrorInvalidDevice, "hipSetDevice");
+  CompressPlan* plan = nullptr;
+  {
+    const int rc = plan_for_layers(ctx, layers, num_layers, stream, &plan);
+    if (rc != RGC_OK) return rc;
+  }
 
   // ---- hints belong to a (n, k) sequence; anything else starts hint-free
   bool sig_same = !ctx->hints_reset && ctx->hint_sig.size() == static_cast<size_t>(num_layers);
@@ -450,6 +506,8 @@ int rgc_compress_layers(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layer
   A.use_hints = (sig_same && !no_hints) ? 1u : 0u;
   A.update_hints = no_hints ? 0u : 1u;
   A.mask_momentum = (flags & RGC_NO_MOMENTUM_MASK) ? 0u : 1u;
+  A.nesterov = (flags & RGC_NESTEROV) ? 1u : 0u;
+  A.grad_scale = grad_scale;
   A.m = momentum;
   A.launch = 1;
   if (ctx->profiling) RGC_HIP(take_event(ctx, stream, ctx->ev_compress));

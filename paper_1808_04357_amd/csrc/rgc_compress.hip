@@ -88,24 +88,38 @@ __device__ __forceinline__ void consume(const float (&a)[4], uint32_t nvalid, ui
   }
 }
 
-template <bool kMom>
+// The accumulate of Algorithm 1 and its variants (Sections 2.4, 2.5): every gradient element is
+// first multiplied with the clipping coefficient (1 when there is none: an exact product), then
+//   plain:                a = V + g
+//   momentum correction:  u = fma(m, u, g),   a = V + u
+//   its Nesterov form:    u = m * (u + g),    a = (V + u) + g      (every operation rounded)
+struct AccumRule {
+  float m;       // momentum factor
+  float scale;   // clipping coefficient
+};
+
+template <bool kMom, bool kNest>
 __device__ __forceinline__ void accum4(const float (&g)[4], const float (&v)[4], float (&u)[4],
-                                       float m, float (&a)[4]) {
+                                       const AccumRule& r, float (&a)[4]) {
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    if constexpr (kMom) {
-      u[j] = __fmaf_rn(m, u[j], g[j]);
+    const float gs = __fmul_rn(r.scale, g[j]);
+    if constexpr (kMom && kNest) {
+      u[j] = __fmul_rn(r.m, __fadd_rn(u[j], gs));
+      a[j] = __fadd_rn(__fadd_rn(v[j], u[j]), gs);
+    } else if constexpr (kMom) {
+      u[j] = __fmaf_rn(r.m, u[j], gs);
       a[j] = __fadd_rn(v[j], u[j]);
     } else {
-      a[j] = __fadd_rn(v[j], g[j]);
+      a[j] = __fadd_rn(v[j], gs);
     }
   }
 }
 
 // Streaming pass over one wave-chunk [begin, end) of a layer.
-template <bool kMom, bool kCollect>
+template <bool kMom, bool kCollect, bool kNest = false>
 __device__ __forceinline__ void stream_chunk(const LayerDesc& L, uint32_t begin, uint32_t end,
-                                             float m, Collector& c, uint32_t* lds_hist) {
+                                             const AccumRule m, Collector& c, uint32_t* lds_hist) {
   const uint32_t lane = lane_id();
   uint32_t zeros = 0;
   uint32_t base = begin;
@@ -133,7 +147,7 @@ __device__ __forceinline__ void stream_chunk(const LayerDesc& L, uint32_t begin,
         float uu[4] = {0.f, 0.f, 0.f, 0.f};
         if constexpr (kMom) { uu[0] = uv[t].x; uu[1] = uv[t].y; uu[2] = uv[t].z; uu[3] = uv[t].w; }
         float a[4];
-        accum4<kMom>(gg, vvv, uu, m, a);
+        accum4<kMom, kNest>(gg, vvv, uu, m, a);
         V4[o] = vf4{a[0], a[1], a[2], a[3]};
         if constexpr (kMom) U4[o] = vf4{uu[0], uu[1], uu[2], uu[3]};
         consume<kCollect>(a, 4u, begin + o * 4u, c, lds_hist, zeros);
@@ -148,7 +162,7 @@ __device__ __forceinline__ void stream_chunk(const LayerDesc& L, uint32_t begin,
       float uu[4] = {0.f, 0.f, 0.f, 0.f};
       if constexpr (kMom) { const vf4 uq = U4[o]; uu[0] = uq.x; uu[1] = uq.y; uu[2] = uq.z; uu[3] = uq.w; }
       float a[4];
-      accum4<kMom>(gg, vvv, uu, m, a);
+      accum4<kMom, kNest>(gg, vvv, uu, m, a);
       V4[o] = vf4{a[0], a[1], a[2], a[3]};
       if constexpr (kMom) U4[o] = vf4{uu[0], uu[1], uu[2], uu[3]};
       consume<kCollect>(a, 4u, begin + o * 4u, c, lds_hist, zeros);
@@ -172,7 +186,7 @@ __device__ __forceinline__ void stream_chunk(const LayerDesc& L, uint32_t begin,
       }
     }
     float a[4];
-    accum4<kMom>(gg, vvv, uu, m, a);
+    accum4<kMom, kNest>(gg, vvv, uu, m, a);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       if (static_cast<uint32_t>(j) < nvalid) {
@@ -617,13 +631,18 @@ __global__ void __launch_bounds__(kBlockThreads) accumulate_kernel(CompressArgs 
     c.tau = st->tau;
     c.shift = st->shift;
     const bool mom = (L.mom != nullptr);
+    AccumRule rule;
+    rule.m = A.m;
+    rule.scale = A.grad_scale ? *as_global(A.grad_scale) : 1.0f;
     if (collect) {
-      if (mom) stream_chunk<true, true>(L, begin, end, A.m, c, lds_hist);
-      else stream_chunk<false, true>(L, begin, end, A.m, c, lds_hist);
+      if (!mom) stream_chunk<false, true>(L, begin, end, rule, c, lds_hist);
+      else if (!A.nesterov) stream_chunk<true, true>(L, begin, end, rule, c, lds_hist);
+      else stream_chunk<true, true, true>(L, begin, end, rule, c, lds_hist);
       if (lane_id() == 0) st_agent(&A.cand_cnt[L.wc_first + wc_local], c.count);
     } else {
-      if (mom) stream_chunk<true, false>(L, begin, end, A.m, c, lds_hist);
-      else stream_chunk<false, false>(L, begin, end, A.m, c, lds_hist);
+      if (!mom) stream_chunk<false, false>(L, begin, end, rule, c, lds_hist);
+      else if (!A.nesterov) stream_chunk<true, false>(L, begin, end, rule, c, lds_hist);
+      else stream_chunk<true, false, true>(L, begin, end, rule, c, lds_hist);
     }
   }
   __syncthreads();
@@ -1050,6 +1069,64 @@ __global__ void wave_scan_selftest_kernel(uint32_t* io) {
   io[threadIdx.x] = ex;
   io[512 + threadIdx.x] = rank_below(odd);
   if (threadIdx.x == 0) io[256] = total;
+}
+
+// ------------------------------------------------------------------ local gradient clipping
+// Section 2.4: the gradients of all layers are clipped by their common L2 norm, locally and
+// before they are added to the residuals, with a threshold of N^(-1/2) of the original one.
+// Two launches, both with a fixed order of additions (the same coefficient on every run): every
+// wave sums the squares of its wave-chunk of the gradient in fp64 (the product of two floats is
+// exact there) and leaves one partial sum per wave-chunk; one workgroup then adds the partial
+// sums up and stores  c = norm > threshold ? threshold / norm : 1  as a float.
+__global__ void __launch_bounds__(kBlockThreads) grad_sqnorm_kernel(CompressArgs A) {
+  const uint32_t wg = blockIdx.x;
+  const uint32_t l = A.wg2layer[wg];
+  const LayerDesc L = A.layers[l];
+  const uint32_t wc_local = (wg - L.wg_first) * kWavesPerBlock + (threadIdx.x >> 6);
+  if (wc_local >= L.wc_count) return;
+  const uint32_t begin = wc_local * A.chunk;
+  const uint32_t end = (L.n - begin) < A.chunk ? L.n : begin + A.chunk;
+  double sum = 0.0;
+  for_each_group(L.grad, L.vec_ok != 0u, begin, end,
+                 [&](const float (&a)[4], uint32_t nvalid, uint32_t) {
+#pragma unroll
+                   for (int j = 0; j < 4; ++j) {
+                     if (static_cast<uint32_t>(j) < nvalid) {
+                       const double x = static_cast<double>(a[j]);
+                       sum += x * x;
+                     }
+                   }
+                 });
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) sum += __shfl_xor(sum, o);
+  if (lane_id() == 0) A.norm_part[L.wc_first + wc_local] = sum;
+}
+
+__global__ void __launch_bounds__(kBlockThreads) clip_coefficient_kernel(const double* part, uint32_t count,
+                                                                          float threshold, float* coef) {
+  __shared__ double red[kBlockThreads];
+  double sum = 0.0;
+  for (uint32_t i = threadIdx.x; i < count; i += kBlockThreads) sum += part[i];
+  red[threadIdx.x] = sum;
+  __syncthreads();
+  for (uint32_t step = kBlockThreads / 2u; step >= 1u; step >>= 1) {
+    if (threadIdx.x < step) red[threadIdx.x] += red[threadIdx.x + step];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const double norm = sqrt(red[0]);
+    const double t = static_cast<double>(threshold);
+    *coef = static_cast<float>(norm > t ? t / norm : 1.0);
+  }
+}
+
+hipError_t launch_clip_coefficient(const CompressArgs& a, uint32_t num_wgs, uint32_t num_chunks, float threshold,
+                                   float* d_coef, hipStream_t s) {
+  hipLaunchKernelGGL(grad_sqnorm_kernel, dim3(num_wgs), dim3(kBlockThreads), 0, s, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(clip_coefficient_kernel, dim3(1), dim3(kBlockThreads), 0, s, a.norm_part, num_chunks, threshold, d_coef);
+  return hipGetLastError();
 }
 
 hipError_t launch_accumulate(const CompressArgs& a, uint32_t num_wgs, hipStream_t s) {

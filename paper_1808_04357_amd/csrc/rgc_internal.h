@@ -99,6 +99,9 @@ struct CompressArgs {
   uint32_t mask_momentum;
   float m;
   uint32_t launch;       // launch number of the phase kernel (2..6)
+  uint32_t nesterov;     // momentum correction in its Nesterov form: u = m (u + g), a = (V + u) + g
+  const float* grad_scale;   // device word every gradient element is multiplied with first, or null
+  double* norm_part;     // [wave-chunks] partial sums of squares (clipping coefficient only)
 };
 
 // ---------------------------------------------------------------- decompress
@@ -148,6 +151,8 @@ struct DecompressArgs {
 // kernel launchers (defined in the .hip files)
 hipError_t launch_accumulate(const CompressArgs& a, uint32_t num_wgs, hipStream_t s);
 hipError_t launch_phase(const CompressArgs& a, uint32_t num_wgs, hipStream_t s);
+hipError_t launch_clip_coefficient(const CompressArgs& a, uint32_t num_wgs, uint32_t num_chunks, float threshold,
+                                   float* d_coef, hipStream_t s);
 hipError_t launch_poison(LayerState* st, uint32_t num_layers, int mode, hipStream_t s);
 hipError_t launch_decompress_table(const DecompressArgs& a, hipStream_t s);
 hipError_t launch_decompress_tiles(const DecompressArgs& a, hipStream_t s);

@@ -45,8 +45,12 @@ class GpuLayers:
         for l in range(self.L):
             self.G[l].copy_(self.torch.from_numpy(G[l]))
 
-    def step(self, ctx, m: float = 0.0, flags: int = 0) -> None:
-        self.rgc.rgc_compress_layers(ctx, self.layers, m, flags, self.torch.cuda.current_stream())
+    def step(self, ctx, m: float = 0.0, flags: int = 0, grad_scale=None) -> None:
+        if grad_scale is None:
+            self.rgc.rgc_compress_layers(ctx, self.layers, m, flags, self.torch.cuda.current_stream())
+        else:
+            self.rgc.rgc_compress_layers_scaled(ctx, self.layers, m, grad_scale, flags,
+                                                self.torch.cuda.current_stream())
 
     def results(self):
         self.torch.cuda.synchronize()
@@ -74,9 +78,10 @@ def assert_layers_equal(tag, ks, got, oracle_msgs, V_ref, U_ref=None):
             assert np.array_equal(u32(U[l]), u32(U_ref[l])), where + ": momentum"
 
 
-def oracle_step(oracle, G, V, ks, U=None, m=0.0, mask_momentum=True, threads=1):
+def oracle_step(oracle, G, V, ks, U=None, m=0.0, mask_momentum=True, threads=1, nesterov=False, grad_scale=None):
     """Runs the oracle in place on host copies V (and U); returns the messages."""
-    return oracle.compress_layers(G, V, ks, momenta=U, m=m, mask_momentum=mask_momentum, threads=threads)
+    return oracle.compress_layers(G, V, ks, momenta=U, m=m, mask_momentum=mask_momentum, threads=threads,
+                                  nesterov=nesterov, grad_scale=grad_scale)
 
 
 def check_properties(a: np.ndarray, k: int, idx: np.ndarray, val: np.ndarray, cnt: int, v_new: np.ndarray):

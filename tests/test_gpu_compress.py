@@ -37,7 +37,7 @@ def run_iterations(rgc, oracle, V0, G_list, ks, U0=None, m=0.0, flags=0, ctx=Non
         dev.set_grads(G)
         dev.step(ctx, m, flags)
         msgs = oracle_step(oracle, G, Vh, ks, Uh, m, mask_momentum=not (flags & rgc.RGC_NO_MOMENTUM_MASK),
-                           threads=threads)
+                           threads=threads, nesterov=bool(flags & rgc.RGC_NESTEROV))
         assert_layers_equal("%s step %d" % (tag, t), ks, dev.results(), msgs, Vh, Uh)
         paths.append(ctx.last_paths(len(V0)))
     if expect_paths is not None:
@@ -251,3 +251,78 @@ def test_two_contexts_on_two_streams(rgc, oracle):
             assert_layers_equal("stream %d step %d" % (s, t), S["ks"], S["dev"].results(), msgs, S["V"])
     for S in sets:
         S["ctx"].close()
+
+
+def test_nesterov_form_of_the_momentum_correction(rgc, oracle):
+    """RGC_NESTEROV: u = m (u + g), a = (V + u) + g, over several steps, with and without masking."""
+    g = np.random.default_rng(61)
+    sizes = [150_000, 33_333, 4097, 9]
+    for flags in (rgc.RGC_NESTEROV, rgc.RGC_NESTEROV | rgc.RGC_NO_MOMENTUM_MASK):
+        V = [(g.standard_normal(n) * 5e-3).astype(np.float32) for n in sizes]
+        U = [(g.standard_normal(n) * 1e-3).astype(np.float32) for n in sizes]
+        Gs = [[(g.standard_normal(n) * 1e-3).astype(np.float32) for n in sizes] for _ in range(5)]
+        ks = [rgc.rgc_k_for_density(n) for n in sizes]
+        run_iterations(rgc, oracle, V, Gs, ks, U0=U, m=0.9, flags=flags, tag="nesterov flags %d" % flags)
+    # layers without a velocity ignore the flag
+    V = [(g.standard_normal(n) * 5e-3).astype(np.float32) for n in sizes]
+    Gs = [[(g.standard_normal(n) * 1e-3).astype(np.float32) for n in sizes] for _ in range(2)]
+    run_iterations(rgc, oracle, V, Gs, [rgc.rgc_k_for_density(n) for n in sizes], flags=rgc.RGC_NESTEROV, tag="no velocity")
+
+
+def ulp_distance(a, b):
+    ia = int(np.array(a, np.float32).view(np.int32))
+    ib = int(np.array(b, np.float32).view(np.int32))
+    return abs(ia - ib)
+
+
+def test_clipping_coefficient_and_scaled_gradients(rgc, oracle):
+    """rgc_clip_coefficient against the oracle's fp64 sum (the order of additions differs: one fp32 ulp
+    is allowed), then rgc_compress_layers_scaled with that very coefficient against the oracle fed the
+    same number: bit for bit, several steps, plain, momentum-corrected and Nesterov."""
+    import torch
+    g = np.random.default_rng(62)
+    sizes = [300_000, 70_001, 4096, 5]
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.current_stream()
+    coef = torch.full((1,), float("nan"), dtype=torch.float32, device=dev)
+    for m, flags, with_u in ((0.0, 0, False), (0.9, 0, True), (0.9, rgc.RGC_NESTEROV, True)):
+        V = [(g.standard_normal(n) * 5e-3).astype(np.float32) for n in sizes]
+        U = [(g.standard_normal(n) * 1e-3).astype(np.float32) for n in sizes] if with_u else None
+        ks = [rgc.rgc_k_for_density(n) for n in sizes]
+        ctx = rgc.Context(sum(sizes), len(sizes))
+        layers = GpuLayers(rgc, V, ks, U)
+        Vh = [v.copy() for v in V]
+        Uh = [u.copy() for u in U] if with_u else None
+        for t in range(4):
+            G = [(g.standard_normal(n) * (1e-3 * (1 + 3 * (t % 2)))).astype(np.float32) for n in sizes]
+            layers.set_grads(G)
+            max_norm = 4.0                             # threshold 4 / sqrt(16) = 1: exceeded on the odd steps only (norms 0.6 and 2.4)
+            rgc.rgc_clip_coefficient(ctx, layers.layers, max_norm, 16, coef, stream)
+            c_gpu = float(coef.cpu().numpy()[0])
+            c_ref, sq = oracle.clip_coefficient(G, max_norm, 16)
+            assert ulp_distance(c_gpu, c_ref) <= 1, (t, c_gpu, c_ref)
+            if t % 2 == 0:
+                assert c_ref == 1.0 and c_gpu == 1.0, "below the threshold nothing is scaled"
+            else:
+                assert c_ref < 1.0
+            layers.step(ctx, m, flags, grad_scale=coef)
+            msgs = oracle_step(oracle, G, Vh, ks, Uh, m, nesterov=bool(flags & rgc.RGC_NESTEROV), grad_scale=c_gpu)
+            assert_layers_equal("scaled m=%g flags=%d step %d" % (m, flags, t), ks, layers.results(), msgs, Vh, Uh)
+        ctx.close()
+
+
+def test_clipping_coefficient_full_size_vgg16(rgc, oracle):
+    import torch
+    cfg = synth.config_vgg16(num_grads=1)
+    G = cfg["G"][0]
+    V = cfg["V"]
+    ks = [rgc.rgc_k_for_density(v.size) for v in V]
+    layers = GpuLayers(rgc, V, ks)
+    layers.set_grads(G)
+    ctx = rgc.Context(sum(v.size for v in V), len(V))
+    coef = torch.zeros(1, dtype=torch.float32, device=torch.device("cuda:0"))
+    rgc.rgc_clip_coefficient(ctx, layers.layers, 1.0, 128, coef, torch.cuda.current_stream())
+    c_ref, sq = oracle.clip_coefficient(G, 1.0, 128)
+    c_gpu = float(coef.cpu().numpy()[0])
+    assert c_ref < 1.0 and ulp_distance(c_gpu, c_ref) <= 1, (c_gpu, c_ref, sq)
+    ctx.close()
