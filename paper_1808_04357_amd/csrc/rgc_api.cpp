@@ -506,6 +506,7 @@ int rgc_compress_layers_scaled(rgc_ctx* ctx, const rgc_layer* layers, int32_t nu
   A.use_hints = (sig_same && !no_hints) ? 1u : 0u;
   A.update_hints = no_hints ? 0u : 1u;
   A.mask_momentum = (flags & RGC_NO_MOMENTUM_MASK) ? 0u : 1u;
+  A.reverse = static_cast<uint32_t>(ctx->tick & 1u);
   A.nesterov = (flags & RGC_NESTEROV) ? 1u : 0u;
   A.grad_scale = grad_scale;
   A.m = momentum;

@@ -609,7 +609,10 @@ __device__ __forceinline__ unsigned long long composite(uint32_t key, uint32_t i
 __global__ void __launch_bounds__(kBlockThreads) accumulate_kernel(CompressArgs A) {
   __shared__ uint32_t lds_hist[kHistBins];
   __shared__ ResolveShared sh;
-  const uint32_t wg = blockIdx.x;
+  // Every other call walks through the tensors from the end: when calls follow each other closely,
+  // what the previous one wrote last (the tails of V and u, still in the memory-side cache) is what
+  // this one reads first.
+  const uint32_t wg = A.reverse ? gridDim.x - 1u - blockIdx.x : blockIdx.x;
   const uint32_t l = A.wg2layer[wg];
   const LayerDesc L = A.layers[l];
   LayerState* st = A.state + l;
@@ -654,7 +657,7 @@ __global__ void __launch_bounds__(kBlockThreads) accumulate_kernel(CompressArgs 
   } else {
     flush_hist(lds_hist, A.hist + static_cast<size_t>(l) * kHistBins, kHistBins);
   }
-  if (last_block_of_layer(&st->done, A.group_done + L.grp_first, blockIdx.x - L.wg_first, L.wg_count, &sh.flag)) {
+  if (last_block_of_layer(&st->done, A.group_done + L.grp_first, wg - L.wg_first, L.wg_count, &sh.flag)) {
     if (collect) {
       resolve_collect(A, l, L, st, sh, lds_hist);
     } else {

@@ -99,6 +99,7 @@ struct CompressArgs {
   uint32_t mask_momentum;
   float m;
   uint32_t launch;       // launch number of the phase kernel (2..6)
+  uint32_t reverse;      // the streaming pass takes its workgroups in descending order
   uint32_t nesterov;     // momentum correction in its Nesterov form: u = m (u + g), a = (V + u) + g
   const float* grad_scale;   // device word every gradient element is multiplied with first, or null
   double* norm_part;     // [wave-chunks] partial sums of squares (clipping coefficient only)
