@@ -123,6 +123,7 @@ struct CompressPlan {
   hipEvent_t uploaded = nullptr;    // recorded after the uploads
   uint32_t num_wgs = 0;
   uint32_t num_chunks = 0;                 // wave-chunks over all layers
+  uint64_t write_bytes = 0;                // what the streaming pass writes (V, and u where there is one)
   uint64_t last_use = 0;
   bool valid = false;
 };
@@ -154,6 +155,7 @@ struct rgc_ctx {
   DevBuf<uint2> d_slots;
   CompressPlan plans[kPlanCache];
   uint64_t tick = 0;
+  uint64_t compress_calls = 0;             // its parity is the direction of the next streaming pass
   std::vector<std::pair<int64_t, int32_t>> hint_sig;   // (n, k) per layer slot the hints belong to
   bool hints_reset = true;
   int32_t last_layers = 0;
@@ -241,6 +243,8 @@ int build_compress_plan(rgc_ctx* ctx, CompressPlan& P, const rgc_layer* layers, 
   P.key.assign(layers, layers + L);
   P.num_wgs = wg;
   P.num_chunks = wc;
+  P.write_bytes = 0;
+  for (int32_t l = 0; l < L; ++l) P.write_bytes += static_cast<uint64_t>(layers[l].n) * (layers[l].momentum ? 8u : 4u);
   P.valid = true;
   return RGC_OK;
 }
@@ -432,6 +436,16 @@ int plan_for_layers(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers, h
   return RGC_OK;
 }
 
+// Direction of the streaming pass of compression call number `call` (0: workgroups ascending).
+// Every other call goes backwards when the call writes more than the memory-side cache holds
+// (256 MB on MI355X): the tail of what the previous call wrote is then still cached and is read
+// first.  Smaller layer sets stay cached whatever the order, and ascending order (largest layers
+// first) is the better one for them.
+uint32_t streaming_direction(const CompressPlan* plan, uint64_t call) {
+  constexpr uint64_t kMemorySideCacheBytes = 256ull << 20;
+  return (plan->write_bytes > kMemorySideCacheBytes) ? static_cast<uint32_t>(call & 1u) : 0u;
+}
+
 void fill_plan_args(rgc_ctx* ctx, const CompressPlan* plan, CompressArgs& A) {
   A.layers = plan->d_layers.p;
   A.wg2layer = plan->d_wg2layer.p;
@@ -456,6 +470,7 @@ int rgc_clip_coefficient(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_laye
   if (ctx->d_norm_part.n < ctx->wc_max) RGC_HIP(ctx->d_norm_part.alloc(ctx->wc_max));   // first use only
   CompressArgs A{};
   fill_plan_args(ctx, plan, A);
+  A.reverse = streaming_direction(plan, ctx->compress_calls) ^ 1u;   // against the direction of the compression call to come
   const float threshold = static_cast<float>(static_cast<double>(max_norm) / std::sqrt(static_cast<double>(num_workers)));
   RGC_HIP(launch_clip_coefficient(A, plan->num_wgs, plan->num_chunks, threshold, coefficient, stream));
   return RGC_OK;
@@ -506,7 +521,7 @@ int rgc_compress_layers_scaled(rgc_ctx* ctx, const rgc_layer* layers, int32_t nu
   A.use_hints = (sig_same && !no_hints) ? 1u : 0u;
   A.update_hints = no_hints ? 0u : 1u;
   A.mask_momentum = (flags & RGC_NO_MOMENTUM_MASK) ? 0u : 1u;
-  A.reverse = static_cast<uint32_t>(ctx->tick & 1u);
+  A.reverse = streaming_direction(plan, ctx->compress_calls++);
   A.nesterov = (flags & RGC_NESTEROV) ? 1u : 0u;
   A.grad_scale = grad_scale;
   A.m = momentum;
