@@ -155,6 +155,7 @@ struct rgc_ctx {
   DevBuf<uint2> d_slots;
   CompressPlan plans[kPlanCache];
   uint64_t tick = 0;
+  bool compressed_since_decompress = false;
   uint64_t compress_calls = 0;             // its parity is the direction of the next streaming pass
   std::vector<std::pair<int64_t, int32_t>> hint_sig;   // (n, k) per layer slot the hints belong to
   bool hints_reset = true;
@@ -522,6 +523,7 @@ int rgc_compress_layers_scaled(rgc_ctx* ctx, const rgc_layer* layers, int32_t nu
   A.update_hints = no_hints ? 0u : 1u;
   A.mask_momentum = (flags & RGC_NO_MOMENTUM_MASK) ? 0u : 1u;
   A.reverse = streaming_direction(plan, ctx->compress_calls++);
+  ctx->compressed_since_decompress = true;
   A.nesterov = (flags & RGC_NESTEROV) ? 1u : 0u;
   A.grad_scale = grad_scale;
   A.m = momentum;
@@ -724,6 +726,10 @@ int rgc_decompress_accumulate(rgc_ctx* ctx, const rgc_msg* msgs, int32_t num_wor
   DecompressArgs A = P.args;
   A.add_to_dst = (flags == RGC_ADD_TO_DST) ? 1u : 0u;
   A.scale = scale;
+  // A compression call since the last decompression: the tails of its tensors are in the memory-side
+  // cache and its next call will start with them, so this call leaves them there.
+  A.stream_msgs = ctx->compressed_since_decompress ? 1u : 0u;
+  ctx->compressed_since_decompress = false;
   if (validate) RGC_HIP(launch_decompress_validate(A, ctx->d_err.p + 1, stream));
   if (ctx->profiling) RGC_HIP(take_event(ctx, stream, ctx->ev_decompress));
   RGC_HIP(launch_decompress_table(A, stream));

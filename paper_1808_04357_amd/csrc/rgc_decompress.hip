@@ -448,6 +448,7 @@ __device__ __forceinline__ uint32_t quad_lane0(uint32_t v) {
 // blocks starting at the one that holds entry E, and the blocks that enter it are loaded while
 // the tile is being finished.  There is no per-tile offset table: E starts from a binary search
 // at the first tile of a layer and then advances by what each tile consumes.
+template <bool kStreamMsgs>
 __global__ void __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(6, 6)))
 decompress_tiles_kernel(DecompressArgs A) {
   __shared__ FastLds S;
@@ -539,8 +540,20 @@ decompress_tiles_kernel(DecompressArgs A) {
           have[sl] = want;
           const uint32_t at = want * 16u + 4u * q;
           if (at + 4u <= my_count) {
-            const vu4 qi = *reinterpret_cast<gptr<const vu4>>(my_idx + at);
-            const vf4u qv = *reinterpret_cast<gptr<const vf4u>>(my_val + at);
+            // Streaming loads when the caller alternates compression and decompression: what the
+            // memory-side cache holds of the compression's tensors is worth more to the next call than
+            // the other half of this 128-byte line, which then comes from DRAM again four tiles later.
+            // (a template parameter, not a run-time flag: merged into one branch-free load the two
+            // flavours would lose the hint)
+            vu4 qi;
+            vf4u qv;
+            if constexpr (kStreamMsgs) {
+              qi = __builtin_nontemporal_load(reinterpret_cast<gptr<const vu4>>(my_idx + at));
+              qv = __builtin_nontemporal_load(reinterpret_cast<gptr<const vf4u>>(my_val + at));
+            } else {
+              qi = *reinterpret_cast<gptr<const vu4>>(my_idx + at);
+              qv = *reinterpret_cast<gptr<const vf4u>>(my_val + at);
+            }
             b_idx[sl][0] = qi.x; b_idx[sl][1] = qi.y; b_idx[sl][2] = qi.z; b_idx[sl][3] = qi.w;
             b_val[sl][0] = qv.x; b_val[sl][1] = qv.y; b_val[sl][2] = qv.z; b_val[sl][3] = qv.w;
           } else {
@@ -825,7 +838,7 @@ hipError_t launch_decompress_tiles(const DecompressArgs& a, hipStream_t s) {
   if (a.num_tiles == 0) return hipSuccess;
   static uint32_t per_cu_fast = 0, per_cu_generic = 0;   // workgroups per CU; a property of the code object
   if (per_cu_fast == 0) {
-    per_cu_fast = resident_grid(reinterpret_cast<const void*>(decompress_tiles_kernel), kFastThreads, 8u) / 8u;
+    per_cu_fast = resident_grid(reinterpret_cast<const void*>(decompress_tiles_kernel<false>), kFastThreads, 8u) / 8u;
     per_cu_generic = resident_grid(reinterpret_cast<const void*>(decompress_generic_kernel), kBlockThreads, 8u) / 8u;
   }
   const uint32_t want = ((a.num_tiles + 7u) / 8u) * 8u;
@@ -833,7 +846,8 @@ hipError_t launch_decompress_tiles(const DecompressArgs& a, hipStream_t s) {
   const bool fast = a.num_workers >= 1u && a.num_workers <= static_cast<uint32_t>(kBatchWorkers);
   const uint32_t cap = (fast ? per_cu_fast : per_cu_generic) * cus8;
   const uint32_t grid = want < cap ? want : cap;
-  if (fast) hipLaunchKernelGGL(decompress_tiles_kernel, dim3(grid), dim3(kFastThreads), 0, s, a);
+  if (fast && a.stream_msgs) hipLaunchKernelGGL(decompress_tiles_kernel<true>, dim3(grid), dim3(kFastThreads), 0, s, a);
+  else if (fast) hipLaunchKernelGGL(decompress_tiles_kernel<false>, dim3(grid), dim3(kFastThreads), 0, s, a);
   else hipLaunchKernelGGL(decompress_generic_kernel, dim3(grid), dim3(kBlockThreads), 0, s, a);
   return hipGetLastError();
 }

@@ -146,6 +146,7 @@ struct DecompressArgs {
   uint32_t num_tiles;
   uint32_t num_blocks;
   uint32_t add_to_dst;
+  uint32_t stream_msgs;       // read the messages with streaming loads (see decompress_tiles_kernel)
   float scale;
 };
 
