@@ -63,6 +63,13 @@ def lib() -> ctypes.CDLL:
         L.rgc_oracle_clip_coefficient.argtypes = [ctypes.POINTER(_f32p), ctypes.POINTER(ctypes.c_int64),
                                                   ctypes.c_int32, ctypes.c_float, ctypes.c_int32,
                                                   ctypes.POINTER(ctypes.c_double)]
+        L.rgc_oracle_compress_layer_asq.restype = ctypes.c_int
+        L.rgc_oracle_compress_layer_asq.argtypes = [_f32p, _f32p, _f32p, ctypes.c_int64, ctypes.c_int32,
+                                                    ctypes.c_float, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                                    _i32p, _f32p, _i32p]
+        L.rgc_oracle_decompress_scalar.restype = ctypes.c_int
+        L.rgc_oracle_decompress_scalar.argtypes = [ctypes.POINTER(_i32p), _f32p, _i32p, ctypes.c_int32, _f32p,
+                                                   ctypes.c_int64, ctypes.c_float, ctypes.c_int]
         L.rgc_oracle_decompress.restype = ctypes.c_int
         L.rgc_oracle_decompress.argtypes = [
             ctypes.POINTER(_i32p), ctypes.POINTER(_f32p), _i32p, ctypes.c_int32, _f32p,
@@ -155,6 +162,42 @@ def compress_layers(grads: Sequence[np.ndarray], residuals: Sequence[np.ndarray]
     if rc != 0:
         raise ValueError("oracle rejected the arguments")
     return [(out_idx[l], out_val[l], int(out_cnt[l])) for l in range(L)]
+
+
+def compress_layer_asq(grad: np.ndarray, residual: np.ndarray, k: int, sign: int,
+                       momentum: Optional[np.ndarray] = None, m: float = 0.0,
+                       mask_momentum: bool = True, bruteforce: bool = False
+                       ) -> Tuple[np.ndarray, float, int]:
+    """Alternating Signs Quantization of one layer IN PLACE: sign = +1 the k largest, -1 the k smallest.
+
+    Returns (out_idx int32[k], mean as float32, count)."""
+    out_idx = np.empty(k, dtype=np.int32)
+    out_mean = np.zeros(1, dtype=np.float32)
+    out_cnt = np.zeros(1, dtype=np.int32)
+    rc = lib().rgc_oracle_compress_layer_asq(
+        _f32(grad), _f32(residual), _f32(momentum) if momentum is not None else None, grad.size, int(k),
+        float(m), 1 if mask_momentum else 0, int(sign), 1 if bruteforce else 0, _i32(out_idx),
+        _f32(out_mean), _i32(out_cnt))
+    if rc != 0:
+        raise ValueError("oracle rejected the arguments")
+    return out_idx, np.float32(out_mean[0]), int(out_cnt[0])
+
+
+def decompress_scalar(idx: Sequence[np.ndarray], values: Sequence[float], n: int, scale: float,
+                      dense: Optional[np.ndarray] = None) -> np.ndarray:
+    """Decompress one layer whose messages carry one value each."""
+    N = len(idx)
+    add = dense is not None
+    if dense is None:
+        dense = np.empty(n, dtype=np.float32)
+    ip = (_i32p * max(N, 1))(*[_i32(a) for a in idx])
+    val = np.array(list(values) if N else [0.0], dtype=np.float32)
+    cnt = np.array([a.size for a in idx], dtype=np.int32) if N else np.zeros(1, np.int32)
+    rc = lib().rgc_oracle_decompress_scalar(ip, _f32(val), _i32(cnt), N, _f32(dense), int(n), float(scale),
+                                            1 if add else 0)
+    if rc != 0:
+        raise ValueError("oracle rejected the arguments")
+    return dense
 
 
 def clip_coefficient(grads: Sequence[np.ndarray], max_norm: float, num_workers: int

@@ -45,6 +45,21 @@
 //       c = norm > t ? t / norm : 1,   t = max_norm / sqrt(N)   (fp64, then
 //     rounded to fp32 once), and every gradient element enters the
 //     accumulate as fl(c * g).
+//   * Alternating Signs Quantization (Section 2.2, "Quantization of Sparsified
+//     Residuals"): in one iteration the communication-set is the k largest
+//     elements of the layer, in the next the k smallest, and one average is
+//     sent in place of the k values.  The paper takes the k largest to be all
+//     positive (the k smallest all negative) and says nothing else; read here
+//     as: elements that do not carry the iteration's sign bit (and zeros) all
+//     rank last and equal, i.e. the selection key is the magnitude key of the
+//     elements with the iteration's sign and 0 for all others, ties to the
+//     lowest index as everywhere; the message lists the k indices ascending
+//     and the mean of the k accumulated values, summed in index order in fp64,
+//     divided by k in fp64 and rounded to fp32 once; the sent entries leave
+//     the residual (and the velocity) exactly as in Algorithm 1.  A layer with
+//     fewer than k elements of the sign thus completes its set with the
+//     lowest-index other elements, whose values enter the mean as they are.
+//     Decompression adds the message's one value at each of its indices.
 //   * decompression: acc starts at +0, workers are added in order 0..N-1 and
 //     entries in message order, all in fp32; then either dense = acc*scale or
 //     dense = dense + acc*scale (two roundings, no fused multiply-add).
@@ -160,6 +175,83 @@ int rgc_oracle_compress_layer(const float* grad, float* residual, float* momentu
                               int32_t* out_idx, float* out_val, int32_t* out_count) {
   return rgc_oracle_compress_layer_ex(grad, residual, momentum, n, k, m, mask_momentum, 0, nullptr,
                                       out_idx, out_val, out_count);
+}
+
+// Selection key of Alternating Signs Quantization: sign = +1 keeps the elements
+// whose sign bit is clear, sign = -1 those whose sign bit is set.
+inline uint32_t asq_key(float x, int sign) {
+  const uint32_t b = float_bits(x);
+  const bool negative = (b >> 31) != 0u;
+  return (negative == (sign < 0)) ? (b & 0x7FFFFFFFu) : 0u;
+}
+
+// One layer of the compression step with Alternating Signs Quantization (see
+// the top of this file).  out_idx[k]; *out_mean is the one value of the message.
+// bruteforce != 0 (tiny n only): k rounds of "largest remaining key, first
+// occurrence" instead of the sort.
+int rgc_oracle_compress_layer_asq(const float* grad, float* residual, float* momentum,
+                                  int64_t n, int32_t k, float m, int mask_momentum, int sign,
+                                  int bruteforce, int32_t* out_idx, float* out_mean,
+                                  int32_t* out_count) {
+  if (!grad || !residual || !out_idx || !out_mean || !out_count) return -1;
+  if (n < 1 || n >= (int64_t(1) << 31) || k < 1 || k > n || (sign != 1 && sign != -1)) return -1;
+  if (bruteforce && n > 4096) return -1;
+  std::vector<float> acc;
+  accumulate(grad, residual, momentum, n, m, 0, nullptr, acc);
+  std::vector<int32_t> sel;
+  if (bruteforce) {
+    std::vector<char> taken(static_cast<size_t>(n), 0);
+    for (int32_t round = 0; round < k; ++round) {
+      int64_t best = -1;
+      for (int64_t i = 0; i < n; ++i) {
+        if (taken[i]) continue;
+        if (best < 0 || asq_key(acc[i], sign) > asq_key(acc[best], sign)) best = i;
+      }
+      taken[best] = 1;
+      sel.push_back(static_cast<int32_t>(best));
+    }
+  } else {
+    std::vector<std::pair<uint32_t, int32_t>> order(static_cast<size_t>(n));
+    for (int64_t i = 0; i < n; ++i) order[i] = {asq_key(acc[i], sign), static_cast<int32_t>(i)};
+    std::sort(order.begin(), order.end(),
+              [](const std::pair<uint32_t, int32_t>& a, const std::pair<uint32_t, int32_t>& b) {
+                if (a.first != b.first) return a.first > b.first;
+                return a.second < b.second;
+              });
+    for (int32_t j = 0; j < k; ++j) sel.push_back(order[j].second);
+  }
+  std::vector<float> values(static_cast<size_t>(k));
+  emit(acc, sel, residual, momentum, mask_momentum, n, out_idx, values.data(), out_count);
+  double sum = 0.0;
+  for (int32_t j = 0; j < k; ++j) sum += static_cast<double>(values[j]);   // index order
+  *out_mean = static_cast<float>(sum / static_cast<double>(k));
+  return 0;
+}
+
+// Decompression of messages that carry one value each (Alternating Signs
+// Quantization): worker w adds value[w] at each of its indices.
+int rgc_oracle_decompress_scalar(const int32_t* const* idx, const float* value,
+                                 const int32_t* count, int32_t num_workers, float* dense,
+                                 int64_t n, float scale, int add_to_dst) {
+  if (!dense || n < 1 || num_workers < 0) return -1;
+  std::vector<float> acc(static_cast<size_t>(n), 0.0f);
+  for (int32_t w = 0; w < num_workers; ++w) {
+    if (count[w] < 0) return -1;
+    for (int32_t j = 0; j < count[w]; ++j) {
+      int32_t i = idx[w][j];
+      if (i < 0 || i >= n) return -1;
+      acc[i] = acc[i] + value[w];
+    }
+  }
+  if (add_to_dst) {
+    for (int64_t i = 0; i < n; ++i) {
+      float scaled = acc[i] * scale;
+      dense[i] = dense[i] + scaled;
+    }
+  } else {
+    for (int64_t i = 0; i < n; ++i) dense[i] = acc[i] * scale;
+  }
+  return 0;
 }
 
 // Same result by brute force, for tiny n only: k rounds of "largest remaining

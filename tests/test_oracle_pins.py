@@ -412,6 +412,111 @@ def test_clip_coefficient_closed_forms(oracle):
     assert abs(Fraction(float(c)) ** 2 - want) <= want * Fraction(1, 2 ** 22)
 
 
+# ------------------------------------------------------------------ Alternating Signs Quantization
+
+def _exact_mean_f32(values):
+    """Correctly rounded float32 of the exact mean of float32 values."""
+    total = sum(Fraction(float(v)) for v in values)
+    return _round_to_f32(total / len(values))
+
+
+def test_asq_equals_signed_top_k_when_enough_elements_have_the_sign(oracle):
+    """Section 2.2: the k largest elements in one iteration, the k smallest in the next; with at
+    least k positive (negative) elements that is the plain signed order, here from a library sort."""
+    g = np.random.default_rng(71)
+    n, k = 5000, 37
+    G = g.standard_normal(n).astype(np.float32)
+    V = g.standard_normal(n).astype(np.float32)
+    a = V + G
+    for sign in (+1, -1):
+        v = V.copy()
+        idx, mean, cnt = oracle.compress_layer_asq(G, v, k, sign)
+        order = np.argsort(-a if sign > 0 else a, kind="stable")[:k]       # largest / smallest k, ties to the lowest index
+        assert cnt == k and np.array_equal(idx, np.sort(order).astype(np.int32))
+        assert np.all(a[idx] > 0) if sign > 0 else np.all(a[idx] < 0), "all of one sign"
+        assert mean == _exact_mean_f32(a[idx]), "the one value of the message is the mean of the set"
+        sel = np.zeros(n, bool)
+        sel[idx] = True
+        assert np.all(v.view(np.uint32)[sel] == 0)
+        assert np.array_equal(v.view(np.uint32)[~sel], a.view(np.uint32)[~sel])
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_asq_sort_equals_bruteforce_on_tiny_inputs(oracle, seed):
+    g = np.random.default_rng(700 + seed)
+    n = int(g.integers(1, 60))
+    k = int(g.integers(1, n + 1))
+    vals = np.array([0.0, -0.0, 0.5, -0.5, 1.0, -1.0, 2.0, -3.0], np.float32)     # many ties, zeros of both signs
+    G = vals[g.integers(0, vals.size, n)]
+    V = vals[g.integers(0, vals.size, n)]
+    for sign in (+1, -1):
+        v1, v2 = V.copy(), V.copy()
+        i1, m1, c1 = oracle.compress_layer_asq(G, v1, k, sign)
+        i2, m2, c2 = oracle.compress_layer_asq(G, v2, k, sign, bruteforce=True)
+        assert np.array_equal(i1, i2) and c1 == c2 == k
+        assert np.float32(m1).view(np.uint32) == np.float32(m2).view(np.uint32)
+        assert np.array_equal(v1.view(np.uint32), v2.view(np.uint32))
+
+
+def test_asq_python_loop_independent_of_cpp(oracle):
+    """The reading for layers short of elements of the sign: the others rank last and equal (lowest index first)."""
+    a = np.array([-1.0, 0.0, 3.0, -0.0, -2.0, 1.0, -5.0], np.float32)
+    G = np.zeros_like(a)
+    # largest 4: the two positives (3, 1), then the lowest-index others: indices 0 and 1
+    idx, mean, cnt = oracle.compress_layer_asq(G, a.copy(), 4, +1)
+    assert idx.tolist() == [0, 1, 2, 5]
+    assert mean == np.float32((-1.0 + 0.0 + 3.0 + 1.0) / 4)
+    # smallest 2: -5 and -2; smallest 4: all three negatives and -0 (its sign bit is set, its magnitude key is 0:
+    # it ties with the non-negatives at rank zero, and index 1 comes before index 3)
+    idx, mean, cnt = oracle.compress_layer_asq(G, a.copy(), 2, -1)
+    assert idx.tolist() == [4, 6] and mean == np.float32(-3.5)
+    idx, mean, cnt = oracle.compress_layer_asq(G, a.copy(), 4, -1)
+    assert idx.tolist() == [0, 1, 4, 6]
+
+
+def test_asq_all_positive_layer_equals_magnitude_selection(oracle):
+    g = np.random.default_rng(72)
+    n, k = 3000, 30
+    V = np.abs(g.standard_normal(n)).astype(np.float32) + np.float32(0.01)
+    G = np.zeros(n, np.float32)
+    v1, v2 = V.copy(), V.copy()
+    i1, mean, _ = oracle.compress_layer_asq(G, v1, k, +1)
+    i2, x2, _ = oracle.compress_layer(G, v2, k)
+    assert np.array_equal(i1, i2) and np.array_equal(v1.view(np.uint32), v2.view(np.uint32))
+    assert mean == _exact_mean_f32(x2)
+
+
+def test_asq_momentum_masking_and_alternation(oracle):
+    g = np.random.default_rng(73)
+    n, k = 2000, 20
+    V = g.standard_normal(n).astype(np.float32)
+    U = g.standard_normal(n).astype(np.float32)
+    sent = np.zeros(n)
+    total_in = V.astype(np.float64).copy()
+    for t in range(6):
+        G = g.standard_normal(n).astype(np.float32) * np.float32(0.1)
+        sign = +1 if t % 2 == 0 else -1
+        u_before = U.copy()
+        idx, mean, cnt = oracle.compress_layer_asq(G, V, k, sign, momentum=U, m=0.5)
+        assert cnt == k and np.all(U[idx] == 0) and np.all(V[idx] == 0)
+        assert (mean > 0) == (sign > 0)
+
+
+def test_decompress_scalar_matches_plain_decompress_of_constant_values(oracle):
+    g = np.random.default_rng(74)
+    n, N = 4000, 9
+    idx = [np.sort(g.choice(n, size=60, replace=False)).astype(np.int32) for _ in range(N)]
+    means = [np.float32(x) for x in g.standard_normal(N)]
+    val = [np.full(60, means[w], np.float32) for w in range(N)]
+    a = oracle.decompress_scalar(idx, means, n, 0.25)
+    b = oracle.decompress(idx, val, n, 0.25)
+    assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    d0 = g.standard_normal(n).astype(np.float32)
+    a = oracle.decompress_scalar(idx, means, n, 0.5, dense=d0.copy())
+    b = oracle.decompress(idx, val, n, 0.5, dense=d0.copy())
+    assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+
+
 # ------------------------------------------------------------------ several iterations
 
 def test_conservation_over_iterations_and_drain(oracle):
