@@ -270,6 +270,35 @@ def main():
                      "coefficient": float(coef.cpu()[0]),
                      "scaled_nesterov_compress_ms": ms_scaled}
 
+    # Alternating Signs Quantization (Section 2.2): the k largest and the k smallest elements in turn, one
+    # average per message, decompression of one-value messages; the same tensors and index sets as the headline step
+    asq_info = None
+    if not args.step_only:
+        means = torch.zeros(len(vgg.sizes), dtype=torch.float32, device=dev)
+        one_value = rgc.RGC_OVERWRITE | rgc.RGC_ONE_VALUE
+
+        def asq_compress():
+            vgg.step(ctx, stream, rgc.RGC_SELECT_LARGEST if vgg.t % 2 == 0 else rgc.RGC_SELECT_SMALLEST)
+
+        def asq_step():
+            asq_compress()
+            rgc.rgc_message_means(ctx, vgg.lists[0], means, stream)
+            rgc.rgc_decompress_accumulate(ctx, dec.msgs, dec.scale, one_value, stream)
+
+        for _ in range(60):                               # each sign keeps hints of its own: both settle
+            asq_step()
+        misses0 = sum(r[4] for r in ctx.last_stats(len(vgg.sizes), stream))
+        ms_asq = time_loop(torch, asq_step, args.steps)
+        asq_misses = sum(r[4] for r in ctx.last_stats(len(vgg.sizes), stream)) - misses0
+        ms_asq_comp = time_loop(torch, asq_compress, args.steps)
+        ms_means = time_loop(torch, lambda: rgc.rgc_message_means(ctx, vgg.lists[0], means, stream), args.steps)
+        ms_dec1 = time_loop(torch, lambda: rgc.rgc_decompress_accumulate(ctx, dec.msgs, dec.scale, one_value, stream),
+                            args.steps)
+        asq_info = {"ms_per_step": ms_asq, "gradient_GBps": 4.0 * vgg.total / ms_asq / 1e6,
+                    "hint_misses_in_timed_steps": asq_misses, "compress_ms": ms_asq_comp,
+                    "message_means_ms": ms_means, "decompress_one_value_ms": ms_dec1,
+                    "decompress_alg_bytes": 4 * dec.entries + 4 * sum(dec.sizes)}
+
     if args.calibrate_copy:
         src = torch.zeros(vgg.total, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
@@ -313,7 +342,7 @@ def main():
         "step_kernels_ms": {"accumulate_kernel": step_ms4[0] / max(step_calls[0], 1),
                             "phase_launches": step_ms4[1] / max(step_calls[0], 1),
                             "decompress_tiles_kernel": step_ms4[3] / max(step_calls[1], 1)},
-        "compress": comp, "decompress": dec_info, "local_clipping": clip_info, "other_workloads": others,
+        "compress": comp, "decompress": dec_info, "local_clipping": clip_info, "alternating_signs": asq_info, "other_workloads": others,
         "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(line))

@@ -45,8 +45,12 @@ extern "C" {
                                      every layer takes the hint-free multi-pass path        */
 /* rgc_decompress_accumulate: exactly one of the two */
 #define RGC_NESTEROV         0x4u /* momentum correction in its Nesterov form (see below)      */
+#define RGC_SELECT_LARGEST   0x100u /* the communication-set is the k LARGEST elements (see below)   */
+#define RGC_SELECT_SMALLEST  0x200u /* ... the k SMALLEST elements                                  */
 #define RGC_OVERWRITE        0x10u /* dense = acc * scale                                   */
 #define RGC_ADD_TO_DST       0x20u /* dense = dense + acc * scale (two roundings, no fma)   */
+#define RGC_ONE_VALUE        0x80u /* with either of the two: every message's val points to ONE float
+                                      that all its entries carry (quantized messages, Section 2.2) */
 #define RGC_VALIDATE         0x40u /* with either of the two: also check the messages on the
                                       device (see rgc_decompress_status)                    */
 /* bits of the status word of rgc_decompress_status */
@@ -120,6 +124,26 @@ int rgc_compress_layers(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layer
 int rgc_compress_layers_scaled(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers,
                                float momentum, const float* grad_scale, uint32_t flags,
                                void* hip_stream);
+
+/* Alternating Signs Quantization (Section 2.2): in one iteration the communication-set of a layer
+ * is its k largest elements, in the next its k smallest, and the message carries the k indices and
+ * ONE value, the average of the k elements.  Here it is three pieces:
+ *  - selection: rgc_compress_layers(_scaled) with RGC_SELECT_LARGEST or RGC_SELECT_SMALLEST (the
+ *    caller alternates them).  The elements that carry the iteration's sign bit (clear / set) rank
+ *    by magnitude, all other elements rank last and equal, ties to the lowest index as always; so
+ *    with at least k elements of that sign the set is the k largest (smallest) of the layer, and a
+ *    layer short of them completes its set with the lowest-index other elements.  Everything else
+ *    (indices ascending, out_val = the k accumulated values, masking of residual and velocity) is
+ *    as in the plain call.  The speed hints of the three selection modes are kept apart.
+ *  - rgc_message_means: means[l] = average of layer l's out_val[0 .. *out_count), summed in fp64 in
+ *    a fixed order and rounded to fp32 once; `means` is DEVICE memory, num_layers floats.  The
+ *    message of layer l is then (count, out_idx, means[l]); layers the caller does not want
+ *    quantized (the paper leaves the output layer alone) simply keep their out_val.
+ *  - decompression: rgc_decompress_accumulate with RGC_ONE_VALUE takes such messages (val -> the
+ *    message's one float).
+ * Errors (nothing enqueued): RGC_EINVAL (also both selection flags at once), RGC_ENOMEM, RGC_EHIP. */
+int rgc_message_means(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers, float* means,
+                      void* hip_stream);
 
 /* Local gradient clipping (Section 2.4: the gradients of all layers are clipped by their common
  * norm before they are added to the residuals, with a threshold of N^(-1/2) of the original one).

@@ -21,6 +21,9 @@ RGC_NESTEROV = 0x4
 RGC_OVERWRITE = 0x10
 RGC_ADD_TO_DST = 0x20
 RGC_VALIDATE = 0x40
+RGC_ONE_VALUE = 0x80
+RGC_SELECT_LARGEST = 0x100
+RGC_SELECT_SMALLEST = 0x200
 RGC_STATUS_INDEX_RANGE = 0x1
 RGC_STATUS_INDEX_ORDER = 0x2
 
@@ -28,7 +31,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("RGC_LIB") or os.path.join(_HERE, "librgc.so")   # RGC_LIB: tuning builds only
 
 EXPORTS = ["rgc_create", "rgc_destroy", "rgc_k_for_density", "rgc_compress_layers",
-           "rgc_compress_layers_scaled", "rgc_clip_coefficient",
+           "rgc_compress_layers_scaled", "rgc_clip_coefficient", "rgc_message_means",
            "rgc_decompress_accumulate", "rgc_reset_hints", "rgc_poison_hints", "rgc_selftest",
            "rgc_last_paths", "rgc_last_stats", "rgc_decompress_status", "rgc_profile_enable", "rgc_profile_read", "rgc_strerror"]
 
@@ -77,6 +80,9 @@ def load_library() -> ctypes.CDLL:
     L.rgc_compress_layers_scaled.restype = ctypes.c_int
     L.rgc_compress_layers_scaled.argtypes = [ctypes.c_void_p, ctypes.POINTER(rgc_layer), ctypes.c_int32,
                                              ctypes.c_float, ctypes.c_void_p, ctypes.c_uint32, ctypes.c_void_p]
+    L.rgc_message_means.restype = ctypes.c_int
+    L.rgc_message_means.argtypes = [ctypes.c_void_p, ctypes.POINTER(rgc_layer), ctypes.c_int32, ctypes.c_void_p,
+                                    ctypes.c_void_p]
     L.rgc_clip_coefficient.restype = ctypes.c_int
     L.rgc_clip_coefficient.argtypes = [ctypes.c_void_p, ctypes.POINTER(rgc_layer), ctypes.c_int32, ctypes.c_float,
                                        ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
@@ -239,6 +245,11 @@ def rgc_compress_layers_scaled(ctx: Context, layers: LayerList, momentum: float 
     """grad_scale: a one-element float32 device tensor (or None)."""
     _check(load_library().rgc_compress_layers_scaled(ctx.handle, layers.array, layers.num_layers,
                                                      float(momentum), _ptr(grad_scale), int(flags), _stream(stream)))
+
+
+def rgc_message_means(ctx: Context, layers: LayerList, means, stream=None) -> None:
+    """means: a float32 device tensor of num_layers elements that receives each layer's average value."""
+    _check(load_library().rgc_message_means(ctx.handle, layers.array, layers.num_layers, _ptr(means), _stream(stream)))
 
 
 def rgc_clip_coefficient(ctx: Context, layers: LayerList, max_norm: float, num_workers: int, coefficient,

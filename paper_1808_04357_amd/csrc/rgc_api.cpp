@@ -124,6 +124,7 @@ struct CompressPlan {
   uint32_t num_wgs = 0;
   uint32_t num_chunks = 0;                 // wave-chunks over all layers
   uint64_t write_bytes = 0;                // what the streaming pass writes (V, and u where there is one)
+  uint32_t max_k = 0;                      // the largest k of the list
   uint64_t last_use = 0;
   bool valid = false;
 };
@@ -152,13 +153,18 @@ struct rgc_ctx {
   DevBuf<uint32_t> d_hist, d_coarse, d_cand_cnt, d_wc_a, d_wc_b, d_err, d_group;
   DevBuf<unsigned long long> d_members;
   DevBuf<double> d_norm_part;              // [wave-chunks] partial sums of squares (clipping coefficient)
+  DevBuf<double> d_mean_part;              // [layers][kMeanPartsMax] partial sums of message values
   DevBuf<uint2> d_slots;
   CompressPlan plans[kPlanCache];
   uint64_t tick = 0;
   bool compressed_since_decompress = false;
   uint64_t compress_calls = 0;             // its parity is the direction of the next streaming pass
-  std::vector<std::pair<int64_t, int32_t>> hint_sig;   // (n, k) per layer slot the hints belong to
-  bool hints_reset = true;
+  // Speed hints are kept per selection mode (0 magnitude, 1 largest, 2 smallest: the thresholds of
+  // the positive and the negative tail differ, and Alternating Signs Quantization switches between
+  // them from call to call): bank b uses the layer states [b * max_layers, (b + 1) * max_layers).
+  std::vector<std::pair<int64_t, int32_t>> hint_sig[3];   // (n, k) per layer slot the hints belong to
+  bool hints_reset[3] = {true, true, true};
+  int last_bank = 0;
   int32_t last_layers = 0;
   DecompressPlan dplan;
   // benchmark timing: events recorded around the kernels of each call while enabled
@@ -245,7 +251,11 @@ int build_compress_plan(rgc_ctx* ctx, CompressPlan& P, const rgc_layer* layers, 
   P.num_wgs = wg;
   P.num_chunks = wc;
   P.write_bytes = 0;
-  for (int32_t l = 0; l < L; ++l) P.write_bytes += static_cast<uint64_t>(layers[l].n) * (layers[l].momentum ? 8u : 4u);
+  P.max_k = 0;
+  for (int32_t l = 0; l < L; ++l) {
+    P.write_bytes += static_cast<uint64_t>(layers[l].n) * (layers[l].momentum ? 8u : 4u);
+    P.max_k = std::max(P.max_k, static_cast<uint32_t>(layers[l].k));
+  }
   P.valid = true;
   return RGC_OK;
 }
@@ -318,7 +328,7 @@ int rgc_create(rgc_ctx** out, int device_id, int64_t max_total_elems, int32_t ma
   const size_t L = static_cast<size_t>(max_layers);
   hipError_t e = hipSuccess;
   auto chk = [&](hipError_t r) { if (e == hipSuccess && r != hipSuccess) e = r; };
-  chk(c->d_state.alloc(L));
+  chk(c->d_state.alloc(3 * L));
   chk(c->d_hist.alloc(L * kHistBins));
   chk(c->d_coarse.alloc(L * kCoarseRep * kCoarseBins));
   chk(c->d_members.alloc(L * kMemberMax));
@@ -335,7 +345,7 @@ int rgc_create(rgc_ctx** out, int device_id, int64_t max_total_elems, int32_t ma
   chk(c->d_err.alloc(2));                  // [0] internal inconsistencies of compression, [1] status of the message checks
   const uint64_t grp_max = wc_max / (kWavesPerBlock * kElectGroupHost) + 2 * L + 2;
   chk(c->d_group.alloc(grp_max));
-  if (e == hipSuccess) chk(hipMemset(c->d_state.p, 0, sizeof(LayerState) * L));
+  if (e == hipSuccess) chk(hipMemset(c->d_state.p, 0, sizeof(LayerState) * 3 * L));
   if (e == hipSuccess) chk(hipMemset(c->d_hist.p, 0, sizeof(uint32_t) * L * kHistBins));
   if (e == hipSuccess) chk(hipMemset(c->d_coarse.p, 0, sizeof(uint32_t) * L * kCoarseRep * kCoarseBins));
   if (e == hipSuccess) chk(hipMemset(c->d_cand_cnt.p, 0, sizeof(uint32_t) * wc_max));
@@ -371,6 +381,7 @@ int rgc_destroy(rgc_ctx* ctx) {
   ctx->d_err.release();
   ctx->d_group.release();
   ctx->d_norm_part.release();
+  ctx->d_mean_part.release();
   for (auto* v : {&ctx->ev_compress, &ctx->ev_decompress, &ctx->ev_pool})
     for (hipEvent_t e : *v) (void)hipEventDestroy(e);
   delete ctx;
@@ -379,16 +390,16 @@ int rgc_destroy(rgc_ctx* ctx) {
 
 int rgc_reset_hints(rgc_ctx* ctx) {
   if (!ctx) return RGC_EINVAL;
-  ctx->hints_reset = true;
+  for (bool& r : ctx->hints_reset) r = true;
   return RGC_OK;
 }
 
 int rgc_poison_hints(rgc_ctx* ctx, int mode, void* hip_stream) {
   if (!ctx || mode < 0 || mode > 2) return RGC_EINVAL;
   DeviceGuard guard(ctx->device);
-  RGC_HIP(launch_poison(ctx->d_state.p, static_cast<uint32_t>(ctx->max_layers), mode,
+  RGC_HIP(launch_poison(ctx->d_state.p, 3u * static_cast<uint32_t>(ctx->max_layers), mode,
                         static_cast<hipStream_t>(hip_stream)));
-  ctx->hints_reset = false;   // the poisoned values are to be used
+  for (bool& r : ctx->hints_reset) r = false;   // the poisoned values are to be used
   return RGC_OK;
 }
 
@@ -477,6 +488,27 @@ int rgc_clip_coefficient(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_laye
   return RGC_OK;
 }
 
+int rgc_message_means(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers, float* means,
+                      void* hip_stream) {
+  if (!ctx || !layers || !means || num_layers < 1 || num_layers > ctx->max_layers) return RGC_EINVAL;
+  if (reinterpret_cast<uintptr_t>(means) & 3u) return RGC_EINVAL;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return fail_hip(hipErrorInvalidDevice, "hipSetDevice");
+  CompressPlan* plan = nullptr;
+  const int rc = plan_for_layers(ctx, layers, num_layers, stream, &plan);
+  if (rc != RGC_OK) return rc;
+  const size_t part_slots = static_cast<size_t>(num_layers) * kMeanPartsMax;
+  if (ctx->d_mean_part.n < part_slots) {                    // first use, or a longer list than before
+    RGC_HIP(hipStreamSynchronize(stream));                  // the buffer may still be in use
+    RGC_HIP(ctx->d_mean_part.alloc(part_slots));
+  }
+  CompressArgs A{};
+  fill_plan_args(ctx, plan, A);
+  RGC_HIP(launch_message_means(A, static_cast<uint32_t>(num_layers), plan->max_k, ctx->d_mean_part.p, means, stream));
+  return RGC_OK;
+}
+
 int rgc_compress_layers(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers, float momentum,
                         uint32_t flags, void* hip_stream) {
   return rgc_compress_layers_scaled(ctx, layers, num_layers, momentum, nullptr, flags, hip_stream);
@@ -485,8 +517,10 @@ int rgc_compress_layers(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layer
 int rgc_compress_layers_scaled(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers, float momentum,
                                const float* grad_scale, uint32_t flags, void* hip_stream) {
   if (!ctx || !layers || num_layers < 1 || num_layers > ctx->max_layers) return RGC_EINVAL;
-  if (flags & ~(RGC_NO_MOMENTUM_MASK | RGC_NO_HINTS | RGC_NESTEROV)) return RGC_EINVAL;
+  if (flags & ~(RGC_NO_MOMENTUM_MASK | RGC_NO_HINTS | RGC_NESTEROV | RGC_SELECT_LARGEST | RGC_SELECT_SMALLEST)) return RGC_EINVAL;
+  if ((flags & RGC_SELECT_LARGEST) && (flags & RGC_SELECT_SMALLEST)) return RGC_EINVAL;
   if (reinterpret_cast<uintptr_t>(grad_scale) & 3u) return RGC_EINVAL;
+  const int bank = (flags & RGC_SELECT_LARGEST) ? 1 : (flags & RGC_SELECT_SMALLEST) ? 2 : 0;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return fail_hip(hipErrorInvalidDevice, "hipSetDevice");
@@ -497,16 +531,19 @@ int rgc_compress_layers_scaled(rgc_ctx* ctx, const rgc_layer* layers, int32_t nu
   }
 
   // ---- hints belong to a (n, k) sequence; anything else starts hint-free
-  bool sig_same = !ctx->hints_reset && ctx->hint_sig.size() == static_cast<size_t>(num_layers);
+  auto& hint_sig = ctx->hint_sig[bank];
+  bool sig_same = !ctx->hints_reset[bank] && hint_sig.size() == static_cast<size_t>(num_layers);
   if (sig_same) {
     for (int32_t l = 0; l < num_layers; ++l)
-      if (ctx->hint_sig[l].first != layers[l].n || ctx->hint_sig[l].second != layers[l].k) { sig_same = false; break; }
+      if (hint_sig[l].first != layers[l].n || hint_sig[l].second != layers[l].k) { sig_same = false; break; }
   }
   const bool no_hints = (flags & RGC_NO_HINTS) != 0;
 
   CompressArgs A{};
   A.layers = plan->d_layers.p;
-  A.state = ctx->d_state.p;
+  A.state = ctx->d_state.p + static_cast<size_t>(bank) * ctx->max_layers;
+  A.sign_filter = bank ? 0xFFFFFFFFu : 0u;
+  A.sign_xor = bank == 2 ? 0x80000000u : 0u;
   A.wg2layer = plan->d_wg2layer.p;
   A.hist = ctx->d_hist.p;
   A.coarse = ctx->d_coarse.p;
@@ -537,10 +574,11 @@ int rgc_compress_layers_scaled(rgc_ctx* ctx, const rgc_layer* layers, int32_t nu
   }
   if (ctx->profiling) RGC_HIP(take_event(ctx, stream, ctx->ev_compress));
   if (!no_hints) {
-    ctx->hint_sig.resize(num_layers);
-    for (int32_t l = 0; l < num_layers; ++l) ctx->hint_sig[l] = {layers[l].n, layers[l].k};
-    ctx->hints_reset = false;
+    hint_sig.resize(num_layers);
+    for (int32_t l = 0; l < num_layers; ++l) hint_sig[l] = {layers[l].n, layers[l].k};
+    ctx->hints_reset[bank] = false;
   }
+  ctx->last_bank = bank;
   ctx->last_layers = num_layers;
   return RGC_OK;
 }
@@ -551,7 +589,8 @@ int rgc_last_paths(rgc_ctx* ctx, int32_t* out, int32_t num_layers, void* hip_str
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   std::vector<LayerState> st(num_layers);
   uint32_t err = 0;
-  RGC_HIP(hipMemcpyAsync(st.data(), ctx->d_state.p, sizeof(LayerState) * num_layers, hipMemcpyDeviceToHost, stream));
+  RGC_HIP(hipMemcpyAsync(st.data(), ctx->d_state.p + static_cast<size_t>(ctx->last_bank) * ctx->max_layers,
+                         sizeof(LayerState) * num_layers, hipMemcpyDeviceToHost, stream));
   RGC_HIP(hipMemcpyAsync(&err, ctx->d_err.p, sizeof err, hipMemcpyDeviceToHost, stream));
   RGC_HIP(hipStreamSynchronize(stream));
   for (int32_t l = 0; l < num_layers; ++l) out[l] = static_cast<int32_t>(st[l].path);
@@ -563,7 +602,8 @@ int rgc_last_stats(rgc_ctx* ctx, int64_t* out, int32_t num_layers, void* hip_str
   DeviceGuard guard(ctx->device);
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   std::vector<LayerState> st(num_layers);
-  RGC_HIP(hipMemcpyAsync(st.data(), ctx->d_state.p, sizeof(LayerState) * num_layers, hipMemcpyDeviceToHost, stream));
+  RGC_HIP(hipMemcpyAsync(st.data(), ctx->d_state.p + static_cast<size_t>(ctx->last_bank) * ctx->max_layers,
+                         sizeof(LayerState) * num_layers, hipMemcpyDeviceToHost, stream));
   RGC_HIP(hipStreamSynchronize(stream));
   for (int32_t l = 0; l < num_layers; ++l) {
     out[5 * l + 0] = st[l].path;
@@ -610,7 +650,8 @@ int rgc_decompress_accumulate(rgc_ctx* ctx, const rgc_msg* msgs, int32_t num_wor
   if (!ctx || !dense || !n || num_layers < 1 || num_workers < 0) return RGC_EINVAL;
   if (num_workers > 0 && !msgs) return RGC_EINVAL;
   const bool validate = (flags & RGC_VALIDATE) != 0;
-  flags &= ~RGC_VALIDATE;
+  const bool one_value = (flags & RGC_ONE_VALUE) != 0;
+  flags &= ~(RGC_VALIDATE | RGC_ONE_VALUE);
   if (flags != RGC_OVERWRITE && flags != RGC_ADD_TO_DST) return RGC_EINVAL;
   if (static_cast<int64_t>(num_workers) * num_layers > (int64_t(1) << 24)) return RGC_EINVAL;
   for (int32_t l = 0; l < num_layers; ++l) {
@@ -728,6 +769,7 @@ int rgc_decompress_accumulate(rgc_ctx* ctx, const rgc_msg* msgs, int32_t num_wor
   A.scale = scale;
   // A compression call since the last decompression: the tails of its tensors are in the memory-side
   // cache and its next call will start with them, so this call leaves them there.
+  A.one_value = one_value ? 1u : 0u;
   A.stream_msgs = ctx->compressed_since_decompress ? 1u : 0u;
   ctx->compressed_since_decompress = false;
   if (validate) RGC_HIP(launch_decompress_validate(A, ctx->d_err.p + 1, stream));

@@ -38,7 +38,22 @@ struct Collector {
   uint32_t count;    // candidates seen so far (wave-uniform)
   uint32_t tau;
   uint32_t shift;
+  uint32_t sign_xor, sign_filter;   // see key_of()
 };
+
+// The selection key of an element with bit pattern `bits`.  Plain top-k (Section 2.1): its
+// magnitude, sign bit cleared.  Alternating Signs Quantization (Section 2.2: the k largest
+// elements in one iteration, the k smallest in the next): the magnitude of the elements that
+// carry the iteration's sign bit, 0 for all others, which thereby rank last and equal.
+//   sign_filter = 0:                      key = bits & 0x7FFFFFFF
+//   sign_filter = ~0, sign_xor = 0:       key = sign bit clear ? bits              : 0   (largest)
+//   sign_filter = ~0, sign_xor = 1 << 31: key = sign bit set   ? bits & 0x7FFFFFFF : 0   (smallest)
+// One AND with a wave-uniform mask, one XOR, one signed maximum: after the XOR the elements of the
+// other sign are the negative integers.
+__device__ __forceinline__ uint32_t key_of(uint32_t bits, uint32_t sign_xor, uint32_t sign_filter) {
+  const int32_t t = static_cast<int32_t>((bits & (kKeyMask | sign_filter)) ^ sign_xor);
+  return static_cast<uint32_t>(t > 0 ? t : 0);
+}
 
 __device__ __forceinline__ uint32_t coarse_bin(uint32_t key, uint32_t tau, uint32_t shift) {
   const uint32_t b = (key - tau) >> shift;
@@ -54,7 +69,7 @@ __device__ __forceinline__ void consume(const float (&a)[4], uint32_t nvalid, ui
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     bits[j] = fbits(a[j]);
-    key[j] = bits[j] & kKeyMask;
+    key[j] = key_of(bits[j], c.sign_xor, c.sign_filter);
   }
   if constexpr (kCollect) {
     bool f[4];
@@ -633,6 +648,8 @@ __global__ void __launch_bounds__(kBlockThreads) accumulate_kernel(CompressArgs 
     c.count = 0;
     c.tau = st->tau;
     c.shift = st->shift;
+    c.sign_xor = A.sign_xor;
+    c.sign_filter = A.sign_filter;
     const bool mom = (L.mom != nullptr);
     AccumRule rule;
     rule.m = A.m;
@@ -686,7 +703,7 @@ __device__ void phase_hist(const CompressArgs& A, uint32_t l, const LayerDesc& L
 #pragma unroll
                      for (int j = 0; j < 4; ++j) {
                        if (static_cast<uint32_t>(j) < nvalid) {
-                         const uint32_t key = fbits(a[j]) & kKeyMask;
+                         const uint32_t key = key_of(fbits(a[j]), A.sign_xor, A.sign_filter);
                          if (kLevel == 1) {
                            if (key != 0u) atomicAdd(&lds_hist[key >> 19], 1u);
                            else ++zeros;
@@ -717,7 +734,7 @@ __device__ void phase_count(const CompressArgs& A, uint32_t l, const LayerDesc& 
 #pragma unroll
                      for (int j = 0; j < 4; ++j) {
                        if (static_cast<uint32_t>(j) < nvalid) {
-                         const uint32_t key = fbits(a[j]) & kKeyMask;
+                         const uint32_t key = key_of(fbits(a[j]), A.sign_xor, A.sign_filter);
                          gt += (key > T) ? 1u : 0u;
                          eq += (key == T) ? 1u : 0u;
                        }
@@ -758,7 +775,7 @@ __device__ void phase_out_v(const CompressArgs& A, const LayerDesc& L, LayerStat
                    bool gt[4], eq[4];
 #pragma unroll
                    for (int j = 0; j < 4; ++j) {
-                     const uint32_t key = fbits(a[j]) & kKeyMask;
+                     const uint32_t key = key_of(fbits(a[j]), A.sign_xor, A.sign_filter);
                      const bool valid = static_cast<uint32_t>(j) < nvalid;
                      gt[j] = valid && key > T;
                      eq[j] = valid && key == T;
@@ -835,7 +852,7 @@ __device__ void phase_sel(const CompressArgs& A, uint32_t l, const LayerDesc& L,
       const uint32_t p = p0 + lane;
       if (p < cnt[i]) {
         const uint2 e = p0 == 0u ? first[i] : slot[p];
-        const uint32_t key = e.x & kKeyMask;
+        const uint32_t key = key_of(e.x, A.sign_xor, A.sign_filter);
         const uint32_t bin = coarse_bin(key, tau, shift);
         if (bin > bstar) {
           ++hi;
@@ -984,7 +1001,7 @@ __device__ void phase_out_c(const CompressArgs& A, const LayerDesc& L, LayerStat
       bool sel = false;
       if (p < cnt[i]) {
         e = p0 == 0u ? first[i] : slot[p];
-        sel = composite(e.x & kKeyMask, e.y) >= thr;
+        sel = composite(key_of(e.x, A.sign_xor, A.sign_filter), e.y) >= thr;
       }
       const unsigned long long sm = __ballot(sel);
       const uint32_t pos = out_pos + rank_below(sm);
@@ -1158,6 +1175,72 @@ hipError_t launch_clip_coefficient(const CompressArgs& a, uint32_t num_wgs, uint
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(clip_coefficient_kernel, dim3(1), dim3(kBlockThreads), 0, s, a.norm_part, num_chunks, threshold, d_coef);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ one value per message
+// Section 2.2 (quantization of the sparsified residuals): the k values of a message are replaced by
+// their average, so that the message carries its indices and one value.  The sum is taken in fp64 in
+// an order fixed by the layer list alone: the values are cut into parts of `part` elements (a
+// multiple of 256, at least 2048, and large enough that the longest message has at most
+// kMeanPartsMax parts); workgroup (l, p) adds part p of layer l up (thread t takes the elements
+// t, t + 256, ... of the part in that order, the 256 sums are added pairwise), a second launch adds
+// each layer's partial sums (lane i takes i, i + 64, ..., the 64 sums pairwise) and stores
+// (float)(sum / count).
+__device__ __forceinline__ double block_tree_sum(double x, double* red, uint32_t threads) {
+  red[threadIdx.x] = x;
+  __syncthreads();
+  for (uint32_t step = threads / 2u; step >= 1u; step >>= 1) {
+    if (threadIdx.x < step) red[threadIdx.x] += red[threadIdx.x + step];
+    __syncthreads();
+  }
+  return red[0];
+}
+
+__global__ void __launch_bounds__(kBlockThreads) message_part_sums_kernel(CompressArgs A, uint32_t part, double* part_sums) {
+  __shared__ double red[kBlockThreads];
+  const LayerDesc L = A.layers[blockIdx.x];
+  const uint32_t count = static_cast<uint32_t>(*as_global(L.out_count));
+  const uint64_t first = static_cast<uint64_t>(blockIdx.y) * part;
+  if (first >= count) return;                               // uniform over the workgroup
+  const uint32_t len = static_cast<uint32_t>(count - first < part ? count - first : part);
+  const gptr<const float> val = as_global(L.out_val) + first;
+  double sum = 0.0;
+  uint32_t i = threadIdx.x;
+  for (; i + 7u * kBlockThreads < len; i += 8u * kBlockThreads) {   // eight loads in flight, added in order
+    float v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = val[i + static_cast<uint32_t>(j) * kBlockThreads];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) sum += static_cast<double>(v[j]);
+  }
+  for (; i < len; i += kBlockThreads) sum += static_cast<double>(val[i]);
+  const double total = block_tree_sum(sum, red, kBlockThreads);
+  if (threadIdx.x == 0) part_sums[static_cast<size_t>(blockIdx.x) * kMeanPartsMax + blockIdx.y] = total;
+}
+
+__global__ void __launch_bounds__(64) message_means_kernel(CompressArgs A, uint32_t part, const double* part_sums, float* means) {
+  __shared__ double red[64];
+  const LayerDesc L = A.layers[blockIdx.x];
+  const uint32_t count = static_cast<uint32_t>(*as_global(L.out_count));
+  const uint32_t parts = static_cast<uint32_t>((static_cast<uint64_t>(count) + part - 1u) / part);
+  const double* mine = part_sums + static_cast<size_t>(blockIdx.x) * kMeanPartsMax;
+  double sum = 0.0;
+  for (uint32_t i = threadIdx.x; i < parts; i += 64u) sum += mine[i];
+  const double total = block_tree_sum(sum, red, 64u);
+  if (threadIdx.x == 0) means[blockIdx.x] = count ? static_cast<float>(total / static_cast<double>(count)) : 0.0f;
+}
+
+hipError_t launch_message_means(const CompressArgs& a, uint32_t num_layers, uint32_t max_k, double* d_part,
+                                float* d_means, hipStream_t s) {
+  uint32_t part = (max_k + kMeanPartsMax - 1u) / kMeanPartsMax;
+  part = (part + 255u) / 256u * 256u;
+  if (part < 2048u) part = 2048u;
+  const uint32_t parts_max = (max_k + part - 1u) / part;    // <= kMeanPartsMax
+  hipLaunchKernelGGL(message_part_sums_kernel, dim3(num_layers, parts_max ? parts_max : 1u), dim3(kBlockThreads), 0, s, a, part, d_part);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(message_means_kernel, dim3(num_layers), dim3(64), 0, s, a, part, static_cast<const double*>(d_part), d_means);
   return hipGetLastError();
 }
 

@@ -307,7 +307,7 @@ __device__ void tile_generic(const DecompressArgs& A, GenericLds& S, const TileG
       const gptr<const float> vp0 = as_global(S.w_val[0]);
       for (uint32_t j = tid; j < c0; j += kBlockThreads) {
         const uint32_t p = static_cast<uint32_t>(ip0[s0 + j]) - g.first;
-        if (p < g.len) S.acc[p] = __fadd_rn(S.acc[p], vp0[s0 + j]);
+        if (p < g.len) S.acc[p] = __fadd_rn(S.acc[p], vp0[A.one_value ? 0u : s0 + j]);
       }
       __syncthreads();
       w0 += 1u;
@@ -336,7 +336,7 @@ __device__ void tile_generic(const DecompressArgs& A, GenericLds& S, const TileG
           const uint32_t j = S.w_start[lo] + (e - S.w_pref[lo]);
           lo_[it] = lo;
           idx_[it] = static_cast<uint32_t>(as_global(S.w_idx[lo])[j]);
-          val_[it] = as_global(S.w_val[lo])[j];
+          val_[it] = as_global(S.w_val[lo])[A.one_value ? 0u : j];   // one value for the whole message (Section 2.2), or one per entry
         }
       }
 #pragma unroll
@@ -448,7 +448,7 @@ __device__ __forceinline__ uint32_t quad_lane0(uint32_t v) {
 // blocks starting at the one that holds entry E, and the blocks that enter it are loaded while
 // the tile is being finished.  There is no per-tile offset table: E starts from a binary search
 // at the first tile of a layer and then advances by what each tile consumes.
-template <bool kStreamMsgs>
+template <bool kStreamMsgs, bool kOneValue>
 __global__ void __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(6, 6)))
 decompress_tiles_kernel(DecompressArgs A) {
   __shared__ FastLds S;
@@ -495,6 +495,15 @@ decompress_tiles_kernel(DecompressArgs A) {
       my_val = as_global(md.val);
       my_count = md.count;
     }
+    // messages that carry one value for all their entries (the average of Section 2.2's
+    // quantization): it is read once per run and stands in for every entry's value
+    float my_one = 0.0f;
+    if constexpr (kOneValue) {
+      if (my_count != 0u) my_one = my_val[0];
+    }
+    auto value_at = [&](uint32_t e) -> float {
+      if constexpr (kOneValue) return my_one; else return my_val[e];
+    };
     // E: entries of the worker before the run's first tile (the messages are sorted by index)
     // The four lanes of a worker search together: each step they probe the four inner fifth points
     // of the range at once, so the search is log5 deep instead of log2.  A run that starts a
@@ -549,11 +558,12 @@ decompress_tiles_kernel(DecompressArgs A) {
             vf4u qv;
             if constexpr (kStreamMsgs) {
               qi = __builtin_nontemporal_load(reinterpret_cast<gptr<const vu4>>(my_idx + at));
-              qv = __builtin_nontemporal_load(reinterpret_cast<gptr<const vf4u>>(my_val + at));
+              if constexpr (!kOneValue) qv = __builtin_nontemporal_load(reinterpret_cast<gptr<const vf4u>>(my_val + at));
             } else {
               qi = *reinterpret_cast<gptr<const vu4>>(my_idx + at);
-              qv = *reinterpret_cast<gptr<const vf4u>>(my_val + at);
+              if constexpr (!kOneValue) qv = *reinterpret_cast<gptr<const vf4u>>(my_val + at);
             }
+            if constexpr (kOneValue) qv = vf4u{my_one, my_one, my_one, my_one};
             b_idx[sl][0] = qi.x; b_idx[sl][1] = qi.y; b_idx[sl][2] = qi.z; b_idx[sl][3] = qi.w;
             b_val[sl][0] = qv.x; b_val[sl][1] = qv.y; b_val[sl][2] = qv.z; b_val[sl][3] = qv.w;
           } else {
@@ -563,7 +573,7 @@ decompress_tiles_kernel(DecompressArgs A) {
               b_val[sl][r] = 0.0f;
               if (at + r < my_count) {
                 b_idx[sl][r] = static_cast<uint32_t>(my_idx[at + r]);
-                b_val[sl][r] = my_val[at + r];
+                b_val[sl][r] = value_at(at + r);
               }
             }
           }
@@ -617,7 +627,7 @@ decompress_tiles_kernel(DecompressArgs A) {
         for (uint32_t e = beyond + q; e < my_count; e += 4u) {
           const uint32_t p = static_cast<uint32_t>(my_idx[e]) - g.first;
           if (p >= g.len) break;
-          (void)mark(p, my_val[e]);
+          (void)mark(p, value_at(e));
           ++mine;
         }
       }
@@ -675,7 +685,7 @@ decompress_tiles_kernel(DecompressArgs A) {
           for (uint32_t e = beyond + q; e < my_count; e += 4u) {
             const uint32_t p = static_cast<uint32_t>(my_idx[e]) - first;
             if (p >= g.len) break;
-            f(p, my_val[e]);
+            f(p, value_at(e));
           }
         }
       };
@@ -728,7 +738,7 @@ decompress_tiles_kernel(DecompressArgs A) {
             for (uint32_t e = beyond + q; e < my_count; e += 4u) {
               const uint32_t p = static_cast<uint32_t>(my_idx[e]) - g.first;
               if (p >= g.len) break;
-              if ((cb[p >> 5] >> (p & 31u)) & 1u) S.rows[static_cast<uint32_t>(S.qmap[p]) * kRowStride + my_slot] = my_val[e];
+              if ((cb[p >> 5] >> (p & 31u)) & 1u) S.rows[static_cast<uint32_t>(S.qmap[p]) * kRowStride + my_slot] = value_at(e);
             }
           }
           __syncthreads();
@@ -838,7 +848,7 @@ hipError_t launch_decompress_tiles(const DecompressArgs& a, hipStream_t s) {
   if (a.num_tiles == 0) return hipSuccess;
   static uint32_t per_cu_fast = 0, per_cu_generic = 0;   // workgroups per CU; a property of the code object
   if (per_cu_fast == 0) {
-    per_cu_fast = resident_grid(reinterpret_cast<const void*>(decompress_tiles_kernel<false>), kFastThreads, 8u) / 8u;
+    per_cu_fast = resident_grid(reinterpret_cast<const void*>(decompress_tiles_kernel<false, false>), kFastThreads, 8u) / 8u;
     per_cu_generic = resident_grid(reinterpret_cast<const void*>(decompress_generic_kernel), kBlockThreads, 8u) / 8u;
   }
   const uint32_t want = ((a.num_tiles + 7u) / 8u) * 8u;
@@ -846,8 +856,13 @@ hipError_t launch_decompress_tiles(const DecompressArgs& a, hipStream_t s) {
   const bool fast = a.num_workers >= 1u && a.num_workers <= static_cast<uint32_t>(kBatchWorkers);
   const uint32_t cap = (fast ? per_cu_fast : per_cu_generic) * cus8;
   const uint32_t grid = want < cap ? want : cap;
-  if (fast && a.stream_msgs) hipLaunchKernelGGL(decompress_tiles_kernel<true>, dim3(grid), dim3(kFastThreads), 0, s, a);
-  else if (fast) hipLaunchKernelGGL(decompress_tiles_kernel<false>, dim3(grid), dim3(kFastThreads), 0, s, a);
+  if (fast && a.one_value) {
+    if (a.stream_msgs) hipLaunchKernelGGL((decompress_tiles_kernel<true, true>), dim3(grid), dim3(kFastThreads), 0, s, a);
+    else hipLaunchKernelGGL((decompress_tiles_kernel<false, true>), dim3(grid), dim3(kFastThreads), 0, s, a);
+  } else if (fast) {
+    if (a.stream_msgs) hipLaunchKernelGGL((decompress_tiles_kernel<true, false>), dim3(grid), dim3(kFastThreads), 0, s, a);
+    else hipLaunchKernelGGL((decompress_tiles_kernel<false, false>), dim3(grid), dim3(kFastThreads), 0, s, a);
+  }
   else hipLaunchKernelGGL(decompress_generic_kernel, dim3(grid), dim3(kBlockThreads), 0, s, a);
   return hipGetLastError();
 }

@@ -99,6 +99,8 @@ struct CompressArgs {
   uint32_t mask_momentum;
   float m;
   uint32_t launch;       // launch number of the phase kernel (2..6)
+  uint32_t sign_xor;     // selection key: see key_of() (0 / 0x80000000: which sign bit keeps an element in the ranking)
+  uint32_t sign_filter;  // 0: every element ranks by magnitude; ~0: elements of the other sign rank last (key 0)
   uint32_t reverse;      // the streaming pass takes its workgroups in descending order
   uint32_t nesterov;     // momentum correction in its Nesterov form: u = m (u + g), a = (V + u) + g
   const float* grad_scale;   // device word every gradient element is multiplied with first, or null
@@ -147,12 +149,16 @@ struct DecompressArgs {
   uint32_t num_blocks;
   uint32_t add_to_dst;
   uint32_t stream_msgs;       // read the messages with streaming loads (see decompress_tiles_kernel)
+  uint32_t one_value;         // every message's val points to ONE float that all its entries carry
   float scale;
 };
 
 // kernel launchers (defined in the .hip files)
 hipError_t launch_accumulate(const CompressArgs& a, uint32_t num_wgs, hipStream_t s);
 hipError_t launch_phase(const CompressArgs& a, uint32_t num_wgs, hipStream_t s);
+constexpr uint32_t kMeanPartsMax = 1024;   // partial sums per layer at most (rgc_message_means)
+hipError_t launch_message_means(const CompressArgs& a, uint32_t num_layers, uint32_t max_k, double* d_part,
+                                float* d_means, hipStream_t s);
 hipError_t launch_clip_coefficient(const CompressArgs& a, uint32_t num_wgs, uint32_t num_chunks, float threshold,
                                    float* d_coef, hipStream_t s);
 hipError_t launch_poison(LayerState* st, uint32_t num_layers, int mode, hipStream_t s);
