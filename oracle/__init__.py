@@ -67,6 +67,10 @@ def lib() -> ctypes.CDLL:
         L.rgc_oracle_compress_layer_asq.argtypes = [_f32p, _f32p, _f32p, ctypes.c_int64, ctypes.c_int32,
                                                     ctypes.c_float, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                                     _i32p, _f32p, _i32p]
+        L.rgc_oracle_compress_layer_threshold.restype = ctypes.c_int
+        L.rgc_oracle_compress_layer_threshold.argtypes = [
+            _f32p, _f32p, _f32p, ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_int, ctypes.c_int,
+            ctypes.c_int, _f32p, ctypes.c_int32, _i32p, _f32p, _i32p, ctypes.POINTER(ctypes.c_int64), _f32p]
         L.rgc_oracle_decompress_scalar.restype = ctypes.c_int
         L.rgc_oracle_decompress_scalar.argtypes = [ctypes.POINTER(_i32p), _f32p, _i32p, ctypes.c_int32, _f32p,
                                                    ctypes.c_int64, ctypes.c_float, ctypes.c_int]
@@ -181,6 +185,34 @@ def compress_layer_asq(grad: np.ndarray, residual: np.ndarray, k: int, sign: int
     if rc != 0:
         raise ValueError("oracle rejected the arguments")
     return out_idx, np.float32(out_mean[0]), int(out_cnt[0])
+
+
+def compress_layer_threshold(grad: np.ndarray, residual: np.ndarray, k: int, search: bool = True,
+                             threshold: float = 0.0, cap: Optional[int] = None,
+                             momentum: Optional[np.ndarray] = None, m: float = 0.0,
+                             mask_momentum: bool = True, nesterov: bool = False):
+    """Threshold binary search selection of one layer IN PLACE (Algorithm 3; search=False applies
+    `threshold` as given).  cap defaults to 2k.
+
+    Returns (out_idx int32[count], out_val float32[count], nnz, threshold float32,
+    trace = (mean, max, counts taken, last ratio) or None)."""
+    if cap is None:
+        cap = 2 * int(k)
+    out_idx = np.empty(cap, dtype=np.int32)
+    out_val = np.empty(cap, dtype=np.float32)
+    out_cnt = np.zeros(1, dtype=np.int32)
+    nnz = ctypes.c_int64(0)
+    thr = np.array([threshold], dtype=np.float32)
+    trace = np.zeros(4, dtype=np.float32)
+    rc = lib().rgc_oracle_compress_layer_threshold(
+        _f32(grad), _f32(residual), _f32(momentum) if momentum is not None else None, grad.size, int(k),
+        float(m), 1 if mask_momentum else 0, 1 if nesterov else 0, 1 if search else 0, _f32(thr), int(cap),
+        _i32(out_idx), _f32(out_val), _i32(out_cnt), ctypes.byref(nnz), _f32(trace))
+    if rc != 0:
+        raise ValueError("oracle rejected the arguments")
+    c = int(out_cnt[0])
+    tr = (np.float32(trace[0]), np.float32(trace[1]), int(trace[2]), float(trace[3])) if search else None
+    return out_idx[:c].copy(), out_val[:c].copy(), int(nnz.value), np.float32(thr[0]), tr
 
 
 def decompress_scalar(idx: Sequence[np.ndarray], values: Sequence[float], n: int, scale: float,

@@ -60,6 +60,27 @@
 //     fewer than k elements of the sign thus completes its set with the
 //     lowest-index other elements, whose values enter the mean as they are.
 //     Decompression adds the message's one value at each of its indices.
+//   * threshold binary search selection (Section 2.1, Algorithm 3): the
+//     communication-set is every element whose magnitude exceeds a threshold,
+//     and the threshold is searched so that between k and 2k elements pass:
+//       mean = mean(|a|), max = max(|a|); l = 0, r = 1;
+//       while r - l > eps: ratio = l + (r - l)/2;
+//         threshold = mean + ratio * (max - mean); nnz = #{|a| > threshold};
+//         k < nnz < 2k: stop;  nnz <= k: r = ratio;  otherwise l = ratio.
+//     The listing's second branch is printed as "nnz < k/2 -> r = ratio, else
+//     l = ratio", which raises the threshold when k/2 <= nnz <= k although too
+//     few elements pass already and contradicts the text (the threshold is to
+//     end between the k-th and the 2k-th largest element); read as above.
+//     eps is not given: 2^-10, i.e. at most ten counts.  Precision is not
+//     given: mean = the fp64 sum of |a| in index order divided by n in fp64
+//     and rounded to fp32; ratio, max - mean, the product and the sum in fp32,
+//     each operation rounded on its own.  If the loop ends without a stop the
+//     last threshold tried is used, as the listing does.  The message is as
+//     long as it comes out (the listing sends every element above the
+//     threshold); a message buffer of `cap` entries takes the first cap of
+//     them in index order and the others stay in the residual.  The sampled
+//     variant of the same section reuses a threshold found earlier: the search
+//     is skipped and the given threshold is applied.  Inputs must be finite.
 //   * decompression: acc starts at +0, workers are added in order 0..N-1 and
 //     entries in message order, all in fp32; then either dense = acc*scale or
 //     dense = dense + acc*scale (two roundings, no fused multiply-add).
@@ -225,6 +246,71 @@ int rgc_oracle_compress_layer_asq(const float* grad, float* residual, float* mom
   double sum = 0.0;
   for (int32_t j = 0; j < k; ++j) sum += static_cast<double>(values[j]);   // index order
   *out_mean = static_cast<float>(sum / static_cast<double>(k));
+  return 0;
+}
+
+// One layer of the compression step with threshold binary search selection
+// (see the top of this file).  search != 0: Algorithm 3 finds *threshold;
+// search == 0: *threshold is applied as given.  out_idx / out_val hold cap
+// entries; *out_count = min(nnz, cap); *out_nnz = the number of elements above
+// the threshold.  out_trace (may be NULL, 4 floats): mean, max, number of
+// counts taken, last ratio.
+int rgc_oracle_compress_layer_threshold(const float* grad, float* residual, float* momentum,
+                                        int64_t n, int32_t k, float m, int mask_momentum,
+                                        int nesterov, int search, float* threshold, int32_t cap,
+                                        int32_t* out_idx, float* out_val, int32_t* out_count,
+                                        int64_t* out_nnz, float* out_trace) {
+  if (!grad || !residual || !threshold || !out_idx || !out_val || !out_count || !out_nnz) return -1;
+  if (n < 1 || n >= (int64_t(1) << 31) || k < 1 || k > n || cap < 1) return -1;
+  std::vector<float> acc;
+  accumulate(grad, residual, momentum, n, m, nesterov, nullptr, acc);
+  auto count_above = [&](float t) {
+    int64_t c = 0;
+    for (int64_t i = 0; i < n; ++i) c += (std::fabs(acc[i]) > t) ? 1 : 0;
+    return c;
+  };
+  if (search) {
+    double sum = 0.0;
+    float max = 0.0f;
+    for (int64_t i = 0; i < n; ++i) {
+      const float mag = std::fabs(acc[i]);
+      sum += static_cast<double>(mag);
+      if (mag > max) max = mag;
+    }
+    const float mean = static_cast<float>(sum / static_cast<double>(n));
+    const float eps = 1.0f / 1024.0f;
+    float l = 0.0f, r = 1.0f, thr = 0.0f, ratio = 0.0f;
+    int counts = 0;
+    while (r - l > eps) {
+      const float half = (r - l) / 2.0f;
+      ratio = l + half;
+      const float span = max - mean;
+      const float offset = ratio * span;
+      thr = mean + offset;
+      const int64_t nnz = count_above(thr);
+      ++counts;
+      if (nnz > k && nnz < 2 * static_cast<int64_t>(k)) break;
+      if (nnz <= k) r = ratio; else l = ratio;
+    }
+    *threshold = thr;
+    if (out_trace) {
+      out_trace[0] = mean;
+      out_trace[1] = max;
+      out_trace[2] = static_cast<float>(counts);
+      out_trace[3] = ratio;
+    }
+  }
+  const float thr = *threshold;
+  std::vector<int32_t> sel;
+  int64_t nnz = 0;
+  for (int64_t i = 0; i < n; ++i) {
+    if (std::fabs(acc[i]) > thr) {
+      if (nnz < cap) sel.push_back(static_cast<int32_t>(i));
+      ++nnz;
+    }
+  }
+  *out_nnz = nnz;
+  emit(acc, sel, residual, momentum, mask_momentum, n, out_idx, out_val, out_count);
   return 0;
 }
 

@@ -650,3 +650,116 @@ def test_decompress_empty_and_zero_workers(oracle):
     assert np.all(out.view(np.uint32) == 0)
     out = oracle.decompress([np.empty(0, np.int32)], [np.empty(0, np.float32)], 10, 2.0)
     assert np.all(out.view(np.uint32) == 0)
+
+
+# ---------------------------------------------------------------------------------------------
+# Threshold binary search selection (Section 2.1, Algorithm 3)
+
+def _uniform_grid(n, seed):
+    """|a_i| runs over i/n, i = 1..n, in a shuffled order with random signs (n a power of two: every value,
+    the mean (n+1)/(2n) and every threshold of the search are exact in fp32)."""
+    g = np.random.default_rng(seed)
+    mag = ((g.permutation(n) + 1) / n).astype(np.float32)
+    return mag * np.where(g.random(n) < 0.5, -1.0, 1.0).astype(np.float32)
+
+
+@pytest.mark.parametrize("k,counts,ratio,threshold,nnz", [
+    # traced by hand on |a| = i/4096: mean = 4097/8192, max = 1, threshold(ratio) = (8194 + 8190 ratio)/16384,
+    # nnz(threshold) = 4096 - floor(4096 threshold)
+    (600, 1, Fraction(1, 2), Fraction(12289, 16384), 1024),                 # 600 < 1024 < 1200 at once
+    (100, 4, Fraction(15, 16), Fraction(15872125, 16384000), 128),          # 1024, 512, 256 too many; 128 fits
+    (5, 8, Fraction(255, 256), Fraction(8194 * 256 + 8190 * 255, 16384 * 256), 8),
+    (2000, 6, Fraction(1, 64), Fraction(8194 * 64 + 8190, 16384 * 64), 2016),   # 1024 ... 1984 too few: down
+    (3000, 10, Fraction(1, 1024), Fraction(8194 * 1024 + 8190, 16384 * 1024), 2046),   # never enough: ten counts
+])
+def test_threshold_search_hand_traces(oracle, k, counts, ratio, threshold, nnz):
+    n = 4096
+    a = _uniform_grid(n, 5)
+    V = np.zeros(n, np.float32)
+    idx, val, got_nnz, thr, trace = oracle.compress_layer_threshold(a, V, k, cap=n)
+    assert Fraction(float(trace[0])) == Fraction(4097, 8192) and float(trace[1]) == 1.0
+    assert trace[2] == counts
+    assert Fraction(trace[3]) == ratio
+    assert Fraction(float(thr)) == threshold
+    assert got_nnz == nnz == idx.size
+    assert np.array_equal(idx, np.nonzero(np.abs(a) > thr)[0])
+    assert np.array_equal(val.view(np.uint32), a[idx].view(np.uint32))
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_threshold_search_contains_the_exact_top_k(oracle, seed):
+    """When the search stops on k < nnz < 2k the set holds every one of the k largest magnitudes (the reason
+    the paper gives for its convergence), the threshold lies between the 2k-th and the k-th largest
+    magnitude, and message + residual rebuild the accumulated tensor."""
+    g = np.random.default_rng(300 + seed)
+    n = int(g.integers(20_000, 60_000))
+    k = max(1, n // 1000)
+    V = (g.standard_normal(n) * 5e-3).astype(np.float32)
+    G = (g.laplace(0, 1e-3, n)).astype(np.float32)
+    a = V + G
+    v = V.copy()
+    idx, val, nnz, thr, trace = oracle.compress_layer_threshold(G, v, k)
+    assert k < nnz < 2 * k and idx.size == nnz and trace[2] <= 10
+    mags = np.sort(np.abs(a))[::-1]
+    assert mags[nnz - 1] > thr >= mags[nnz]
+    assert mags[k - 1] > thr >= mags[2 * k - 1]
+    exact_idx, _, _ = oracle.compress_layer(G, V.copy(), k)
+    assert np.all(np.isin(exact_idx, idx))
+    assert np.array_equal(idx, np.nonzero(np.abs(a) > thr)[0])
+    assert np.array_equal(val.view(np.uint32), a[idx].view(np.uint32))
+    rebuilt = v.copy()
+    assert np.all(rebuilt[idx].view(np.uint32) == 0)
+    rebuilt[idx] = val
+    assert np.array_equal(rebuilt.view(np.uint32), a.view(np.uint32))
+    # mean and max as the definition has them: the exactly rounded sum (math.fsum) agrees here
+    import math
+    assert trace[0] == np.float32(math.fsum(np.abs(a).astype(np.float64)) / n)
+    assert trace[1] == np.abs(a).max()
+    # every threshold the search can visit is mean + (j/1024)(max - mean): the last ratio is such a j
+    assert (trace[3] * 1024) == int(trace[3] * 1024) and 0 < trace[3] < 1
+    assert thr == np.float32(trace[0] + np.float32(np.float32(trace[3]) * np.float32(trace[1] - trace[0])))
+
+
+def test_threshold_search_without_a_stop(oracle):
+    """Ten equal large magnitudes over a constant floor: the count jumps from 10 (too few for k = 20) to n
+    (too many), so the search never stops early, takes its ten counts and uses the last threshold."""
+    n, k = 1000, 20
+    a = np.full(n, 0.25, np.float32)
+    a[::100] = -4.0
+    V = np.zeros(n, np.float32)
+    idx, val, nnz, thr, trace = oracle.compress_layer_threshold(a, V, k, cap=n)
+    assert trace[2] == 10
+    assert nnz in (10, n) and idx.size == nnz
+    assert np.array_equal(idx, np.nonzero(np.abs(a) > thr)[0])
+    # all-equal magnitudes: max = mean, nothing exceeds the threshold, the message is empty
+    a = np.full(64, -3.0, np.float32)
+    V = np.zeros(64, np.float32)
+    idx, val, nnz, thr, trace = oracle.compress_layer_threshold(a, V, 4)
+    assert nnz == 0 and idx.size == 0 and trace[2] == 10 and thr == 3.0
+    assert np.array_equal(V, a)
+
+
+def test_threshold_reuse_and_capacity(oracle):
+    """The sampled variant applies a threshold found earlier: the set is a plain comparison; a buffer of
+    cap entries takes the first cap of them in index order and leaves the rest in the residual."""
+    g = np.random.default_rng(31)
+    n, k = 50_000, 50
+    V = (g.standard_normal(n) * 5e-3).astype(np.float32)
+    G = (g.standard_normal(n) * 1e-3).astype(np.float32)
+    U = (g.standard_normal(n) * 1e-3).astype(np.float32)
+    u_ref = np.float32(0.9) * U.astype(np.float64) + G.astype(np.float64)   # fma: one rounding
+    u_ref = u_ref.astype(np.float32)
+    a = V + u_ref
+    t = np.float32(0.0150)
+    want = np.nonzero(np.abs(a) > t)[0]
+    assert want.size > 2 * k                                    # more than the default buffer holds
+    v, u = V.copy(), U.copy()
+    idx, val, nnz, thr, trace = oracle.compress_layer_threshold(G, v, k, search=False, threshold=float(t),
+                                                                momentum=u, m=0.9)
+    assert trace is None and thr == t and nnz == want.size
+    assert np.array_equal(idx, want[: 2 * k])
+    assert np.array_equal(val.view(np.uint32), a[idx].view(np.uint32))
+    kept = np.ones(n, bool)
+    kept[idx] = False
+    assert np.array_equal(v[kept].view(np.uint32), a[kept].view(np.uint32)) and np.all(v[idx].view(np.uint32) == 0)
+    assert np.array_equal(u[kept].view(np.uint32), u_ref[kept].view(np.uint32)) and np.all(u[idx].view(np.uint32) == 0)
