@@ -299,6 +299,34 @@ def main():
                     "message_means_ms": ms_means, "decompress_one_value_ms": ms_dec1,
                     "decompress_alg_bytes": 4 * dec.entries + 4 * sum(dec.sizes)}
 
+    # Threshold binary search selection (Section 2.1, Algorithm 3) and its sampled variant on the same tensors:
+    # a call that searches the thresholds, a call that reuses them, and the paper's schedule (search every fifth call)
+    tbs_info = None
+    if not args.step_only:
+        out_idx2 = [torch.empty(2 * k, dtype=torch.int32, device=dev) for k in vgg.ks]
+        out_val2 = [torch.empty(2 * k, dtype=torch.float32, device=dev) for k in vgg.ks]
+        lists2 = [rgc.LayerList(g, vgg.V, vgg.ks, out_idx2, out_val2, vgg.out_count, vgg.U) for g in vgg.G]
+        thr = torch.zeros(len(vgg.sizes), dtype=torch.float32, device=dev)
+        nnz = torch.zeros(len(vgg.sizes), dtype=torch.int32, device=dev)
+        calls = [0]
+
+        def tbs(search):
+            rgc.rgc_compress_layers_threshold(ctx, lists2[calls[0] % len(lists2)], vgg.m, thr, nnz,
+                                              rgc.RGC_THRESHOLD_SEARCH if search else 0, stream)
+            calls[0] += 1
+
+        for _ in range(5):
+            tbs(True)
+        ms_search = time_loop(torch, lambda: tbs(True), min(args.steps, 50))
+        ms_reuse = time_loop(torch, lambda: tbs(False), min(args.steps, 50))
+        ms_sampled = time_loop(torch, lambda: tbs(calls[0] % 5 == 0), 5 * max(1, min(args.steps, 50) // 5))
+        sent = nnz.cpu().numpy()
+        tbs_info = {"search_call_ms": ms_search, "reuse_call_ms": ms_reuse, "sampled_every_5_ms": ms_sampled,
+                    "sent_over_k_last_call": float(sent.sum()) / float(sum(vgg.ks)),
+                    "search_call_alg_bytes": vgg.alg_bytes_stream + 3 * 4 * vgg.total,
+                    "reuse_call_alg_bytes": vgg.alg_bytes_stream + 4 * vgg.total}
+        del out_idx2, out_val2, lists2
+
     if args.calibrate_copy:
         src = torch.zeros(vgg.total, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
@@ -342,7 +370,7 @@ def main():
         "step_kernels_ms": {"accumulate_kernel": step_ms4[0] / max(step_calls[0], 1),
                             "phase_launches": step_ms4[1] / max(step_calls[0], 1),
                             "decompress_tiles_kernel": step_ms4[3] / max(step_calls[1], 1)},
-        "compress": comp, "decompress": dec_info, "local_clipping": clip_info, "alternating_signs": asq_info, "other_workloads": others,
+        "compress": comp, "decompress": dec_info, "local_clipping": clip_info, "alternating_signs": asq_info, "threshold_search": tbs_info, "other_workloads": others,
         "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(line))

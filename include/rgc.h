@@ -47,6 +47,7 @@ extern "C" {
 #define RGC_NESTEROV         0x4u /* momentum correction in its Nesterov form (see below)      */
 #define RGC_SELECT_LARGEST   0x100u /* the communication-set is the k LARGEST elements (see below)   */
 #define RGC_SELECT_SMALLEST  0x200u /* ... the k SMALLEST elements                                  */
+#define RGC_THRESHOLD_SEARCH 0x400u /* rgc_compress_layers_threshold: search the thresholds (Algorithm 3) */
 #define RGC_OVERWRITE        0x10u /* dense = acc * scale                                   */
 #define RGC_ADD_TO_DST       0x20u /* dense = dense + acc * scale (two roundings, no fma)   */
 #define RGC_ONE_VALUE        0x80u /* with either of the two: every message's val points to ONE float
@@ -144,6 +145,33 @@ int rgc_compress_layers_scaled(rgc_ctx* ctx, const rgc_layer* layers, int32_t nu
  * Errors (nothing enqueued): RGC_EINVAL (also both selection flags at once), RGC_ENOMEM, RGC_EHIP. */
 int rgc_message_means(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers, float* means,
                       void* hip_stream);
+
+/* The compression step with threshold binary search selection (Section 2.1, Algorithm 3) in place
+ * of the exact top-k: the communication-set of a layer is EVERY element of the accumulated tensor
+ * whose magnitude exceeds the layer's threshold, so the message length varies.
+ *  - With RGC_THRESHOLD_SEARCH the thresholds are searched first, per layer, as Algorithm 3 does:
+ *      mean = mean |a|, max = max |a|; l = 0, r = 1;
+ *      while r - l > 2^-10: ratio = l + (r - l)/2; t = mean + ratio * (max - mean);
+ *                           nnz = #{|a| > t};  k < nnz < 2k: stop;  nnz <= k: r = ratio;  else l = ratio
+ *    (the listing's second branch as its text means it; its epsilon, not given, is 2^-10; mean from an
+ *    fp64 sum rounded to fp32, everything else in fp32, each operation rounded; if no count falls
+ *    between k and 2k the last threshold tried is used), and thresholds[l] receives the result.
+ *  - Without the flag thresholds[l] is applied as given: the sampled variant of the same section,
+ *    which searches once and reuses the threshold for the next few iterations; the caller keeps the
+ *    schedule (the paper's interval is 5).
+ * thresholds: DEVICE memory, num_layers floats, read and (with the flag) written when the kernels
+ * run.  nnz: DEVICE memory, num_layers int32, or NULL: receives the number of elements above the
+ * threshold.  layers[l].k is the k of the search; out_idx and out_val must hold 2 * k entries
+ * (k <= 2^30).  *out_count = min(nnz, 2k): if more than 2k elements exceed the threshold (possible
+ * with a reused threshold or a search that found no count between k and 2k) the first 2k of them in
+ * index order are sent and the others stay in the residual.  Indices ascending, values, masking of
+ * residual and velocity, momentum correction (momentum, RGC_NESTEROV, RGC_NO_MOMENTUM_MASK) as in
+ * rgc_compress_layers.  Inputs must be finite.  Shares the context's scratch with the other calls
+ * (one at a time per context) and leaves the speed hints of rgc_compress_layers alone.
+ * Errors (nothing enqueued): RGC_EINVAL, RGC_ENOMEM, RGC_EHIP. */
+int rgc_compress_layers_threshold(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers,
+                                  float momentum, float* thresholds, int32_t* nnz, uint32_t flags,
+                                  void* hip_stream);
 
 /* Local gradient clipping (Section 2.4: the gradients of all layers are clipped by their common
  * norm before they are added to the residuals, with a threshold of N^(-1/2) of the original one).

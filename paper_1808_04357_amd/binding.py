@@ -24,6 +24,7 @@ RGC_VALIDATE = 0x40
 RGC_ONE_VALUE = 0x80
 RGC_SELECT_LARGEST = 0x100
 RGC_SELECT_SMALLEST = 0x200
+RGC_THRESHOLD_SEARCH = 0x400
 RGC_STATUS_INDEX_RANGE = 0x1
 RGC_STATUS_INDEX_ORDER = 0x2
 
@@ -31,7 +32,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("RGC_LIB") or os.path.join(_HERE, "librgc.so")   # RGC_LIB: tuning builds only
 
 EXPORTS = ["rgc_create", "rgc_destroy", "rgc_k_for_density", "rgc_compress_layers",
-           "rgc_compress_layers_scaled", "rgc_clip_coefficient", "rgc_message_means",
+           "rgc_compress_layers_scaled", "rgc_clip_coefficient", "rgc_message_means", "rgc_compress_layers_threshold",
            "rgc_decompress_accumulate", "rgc_reset_hints", "rgc_poison_hints", "rgc_selftest",
            "rgc_last_paths", "rgc_last_stats", "rgc_decompress_status", "rgc_profile_enable", "rgc_profile_read", "rgc_strerror"]
 
@@ -80,6 +81,10 @@ def load_library() -> ctypes.CDLL:
     L.rgc_compress_layers_scaled.restype = ctypes.c_int
     L.rgc_compress_layers_scaled.argtypes = [ctypes.c_void_p, ctypes.POINTER(rgc_layer), ctypes.c_int32,
                                              ctypes.c_float, ctypes.c_void_p, ctypes.c_uint32, ctypes.c_void_p]
+    L.rgc_compress_layers_threshold.restype = ctypes.c_int
+    L.rgc_compress_layers_threshold.argtypes = [ctypes.c_void_p, ctypes.POINTER(rgc_layer), ctypes.c_int32,
+                                                ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint32,
+                                                ctypes.c_void_p]
     L.rgc_message_means.restype = ctypes.c_int
     L.rgc_message_means.argtypes = [ctypes.c_void_p, ctypes.POINTER(rgc_layer), ctypes.c_int32, ctypes.c_void_p,
                                     ctypes.c_void_p]
@@ -245,6 +250,16 @@ def rgc_compress_layers_scaled(ctx: Context, layers: LayerList, momentum: float 
     """grad_scale: a one-element float32 device tensor (or None)."""
     _check(load_library().rgc_compress_layers_scaled(ctx.handle, layers.array, layers.num_layers,
                                                      float(momentum), _ptr(grad_scale), int(flags), _stream(stream)))
+
+
+def rgc_compress_layers_threshold(ctx: Context, layers: LayerList, momentum: float, thresholds, nnz=None,
+                                  flags: int = 0, stream=None) -> None:
+    """thresholds: float32 device tensor of num_layers elements (written with RGC_THRESHOLD_SEARCH, read
+    otherwise); nnz: int32 device tensor of num_layers elements or None.  The layers' out_idx / out_val
+    hold 2 * k entries."""
+    _check(load_library().rgc_compress_layers_threshold(ctx.handle, layers.array, layers.num_layers, float(momentum),
+                                                        _ptr(thresholds), _ptr(nnz) if nnz is not None else None,
+                                                        int(flags), _stream(stream)))
 
 
 def rgc_message_means(ctx: Context, layers: LayerList, means, stream=None) -> None:

@@ -154,6 +154,7 @@ struct rgc_ctx {
   DevBuf<unsigned long long> d_members;
   DevBuf<double> d_norm_part;              // [wave-chunks] partial sums of squares (clipping coefficient)
   DevBuf<double> d_mean_part;              // [layers][kMeanPartsMax] partial sums of message values
+  DevBuf<ThresholdMoments> d_moments;      // [max_layers] threshold binary search: mean, max of each layer
   DevBuf<uint2> d_slots;
   CompressPlan plans[kPlanCache];
   uint64_t tick = 0;
@@ -382,6 +383,7 @@ int rgc_destroy(rgc_ctx* ctx) {
   ctx->d_group.release();
   ctx->d_norm_part.release();
   ctx->d_mean_part.release();
+  ctx->d_moments.release();
   for (auto* v : {&ctx->ev_compress, &ctx->ev_decompress, &ctx->ev_pool})
     for (hipEvent_t e : *v) (void)hipEventDestroy(e);
   delete ctx;
@@ -506,6 +508,42 @@ int rgc_message_means(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers,
   CompressArgs A{};
   fill_plan_args(ctx, plan, A);
   RGC_HIP(launch_message_means(A, static_cast<uint32_t>(num_layers), plan->max_k, ctx->d_mean_part.p, means, stream));
+  return RGC_OK;
+}
+
+int rgc_compress_layers_threshold(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers, float momentum,
+                                  float* thresholds, int32_t* nnz, uint32_t flags, void* hip_stream) {
+  if (!ctx || !layers || !thresholds || num_layers < 1 || num_layers > ctx->max_layers) return RGC_EINVAL;
+  if (flags & ~(RGC_NO_MOMENTUM_MASK | RGC_NESTEROV | RGC_THRESHOLD_SEARCH)) return RGC_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(thresholds) | reinterpret_cast<uintptr_t>(nnz)) & 3u) return RGC_EINVAL;
+  for (int32_t l = 0; l < num_layers; ++l)
+    if (layers[l].k > (int32_t(1) << 30)) return RGC_EINVAL;              // 2k entries must be countable
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return fail_hip(hipErrorInvalidDevice, "hipSetDevice");
+  CompressPlan* plan = nullptr;
+  const int rc = plan_for_layers(ctx, layers, num_layers, stream, &plan);
+  if (rc != RGC_OK) return rc;
+  if (ctx->d_norm_part.n < ctx->wc_max) RGC_HIP(ctx->d_norm_part.alloc(ctx->wc_max));          // first use only
+  if (ctx->d_moments.n < static_cast<size_t>(ctx->max_layers))
+    RGC_HIP(ctx->d_moments.alloc(static_cast<size_t>(ctx->max_layers)));
+  ThresholdArgs A{};
+  A.layers = plan->d_layers.p;
+  A.wg2layer = plan->d_wg2layer.p;
+  A.thresholds = thresholds;
+  A.nnz = nnz;
+  A.part_sum = ctx->d_norm_part.p;
+  A.part_max = reinterpret_cast<float*>(ctx->d_wc_b.p);
+  A.counts = ctx->d_wc_a.p;
+  A.hist = ctx->d_hist.p;
+  A.moments = ctx->d_moments.p;
+  A.chunk = plan->chunk;
+  A.search = (flags & RGC_THRESHOLD_SEARCH) ? 1u : 0u;
+  A.mask_momentum = (flags & RGC_NO_MOMENTUM_MASK) ? 0u : 1u;
+  A.nesterov = (flags & RGC_NESTEROV) ? 1u : 0u;
+  A.m = momentum;
+  RGC_HIP(launch_threshold_compress(A, plan->num_wgs, static_cast<uint32_t>(num_layers), stream));
+  ctx->compressed_since_decompress = true;
   return RGC_OK;
 }
 

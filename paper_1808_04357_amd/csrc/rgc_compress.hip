@@ -26,9 +26,6 @@ namespace rgc {
 
 namespace {
 
-__device__ __forceinline__ uint32_t fbits(float x) { return __float_as_uint(x); }
-
-typedef float vf4 __attribute__((ext_vector_type(4)));   // one 16-byte access per lane
 typedef uint32_t vu2 __attribute__((ext_vector_type(2))); // a candidate: (float bits, index)
 
 struct Collector {
@@ -99,34 +96,6 @@ __device__ __forceinline__ void consume(const float (&a)[4], uint32_t nvalid, ui
         if (key[j] != 0u) atomicAdd(&lds_hist[key[j] >> 19], 1u);
         else ++zeros;
       }
-    }
-  }
-}
-
-// The accumulate of Algorithm 1 and its variants (Sections 2.4, 2.5): every gradient element is
-// first multiplied with the clipping coefficient (1 when there is none: an exact product), then
-//   plain:                a = V + g
-//   momentum correction:  u = fma(m, u, g),   a = V + u
-//   its Nesterov form:    u = m * (u + g),    a = (V + u) + g      (every operation rounded)
-struct AccumRule {
-  float m;       // momentum factor
-  float scale;   // clipping coefficient
-};
-
-template <bool kMom, bool kNest>
-__device__ __forceinline__ void accum4(const float (&g)[4], const float (&v)[4], float (&u)[4],
-                                       const AccumRule& r, float (&a)[4]) {
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const float gs = __fmul_rn(r.scale, g[j]);
-    if constexpr (kMom && kNest) {
-      u[j] = __fmul_rn(r.m, __fadd_rn(u[j], gs));
-      a[j] = __fadd_rn(__fadd_rn(v[j], u[j]), gs);
-    } else if constexpr (kMom) {
-      u[j] = __fmaf_rn(r.m, u[j], gs);
-      a[j] = __fadd_rn(v[j], u[j]);
-    } else {
-      a[j] = __fadd_rn(v[j], gs);
     }
   }
 }

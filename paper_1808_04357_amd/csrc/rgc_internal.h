@@ -107,6 +107,33 @@ struct CompressArgs {
   double* norm_part;     // [wave-chunks] partial sums of squares (clipping coefficient only)
 };
 
+// ---------------------------------------------------------------- threshold binary search selection
+struct ThresholdMoments {   // per layer, written by the moments kernel
+  float mean;               // mean of |a|
+  float max;                // max of |a|
+  float span;               // max - mean, rounded
+  uint32_t counts_taken;    // counts the bisection took (diagnostics)
+};
+
+struct ThresholdArgs {
+  const LayerDesc* layers;
+  const uint32_t* wg2layer;
+  float* thresholds;        // [layers] the caller's: written by a search, read otherwise
+  int32_t* nnz;             // [layers] the caller's, or null: elements above the threshold
+  double* part_sum;         // [wave-chunks] partial sums of |a|
+  float* part_max;          // [wave-chunks] partial maxima of |a|
+  uint32_t* counts;         // [wave-chunks] elements above the threshold, then first output positions
+  uint32_t* hist;           // [layers][kHistBins], the first 1024 bins of each are used
+  ThresholdMoments* moments;  // [layers]
+  uint32_t chunk;           // elements per wave-chunk
+  uint32_t search;          // 1: Algorithm 3 finds the thresholds; 0: they are given
+  uint32_t mask_momentum;
+  uint32_t nesterov;
+  float m;
+};
+
+hipError_t launch_threshold_compress(const ThresholdArgs& a, uint32_t num_wgs, uint32_t num_layers, hipStream_t s);
+
 // ---------------------------------------------------------------- decompress
 constexpr int kTileShift = 12;
 constexpr int kTile = 1 << kTileShift;            // dense positions owned by one workgroup

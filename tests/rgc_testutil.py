@@ -15,7 +15,7 @@ class GpuLayers:
     """Device copies of a layer set plus output buffers, and the rgc_layer list over them."""
 
     def __init__(self, rgc, V: Sequence[np.ndarray], ks: Sequence[int], U: Optional[Sequence[np.ndarray]] = None,
-                 misalign: int = 0):
+                 misalign: int = 0, out_factor: int = 1):
         import torch
         self.torch = torch
         self.rgc = rgc
@@ -36,8 +36,8 @@ class GpuLayers:
         self.V = [up(v) for v in V]
         self.U = [up(u) for u in U] if U is not None else None
         self.G = [torch.empty_like(v) for v in self.V]
-        self.out_idx = [torch.full((k,), -1, dtype=torch.int32, device=dev) for k in self.ks]
-        self.out_val = [torch.full((k,), float("nan"), dtype=torch.float32, device=dev) for k in self.ks]
+        self.out_idx = [torch.full((out_factor * k,), -1, dtype=torch.int32, device=dev) for k in self.ks]
+        self.out_val = [torch.full((out_factor * k,), float("nan"), dtype=torch.float32, device=dev) for k in self.ks]
         self.out_count = torch.full((self.L,), -1, dtype=torch.int32, device=dev)
         self.layers = rgc.LayerList(self.G, self.V, self.ks, self.out_idx, self.out_val, self.out_count, self.U)
 
