@@ -52,10 +52,10 @@ struct Place {           // where a wave works
   uint32_t begin, end;   // element range inside the layer; begin == end: nothing to do
 };
 
-__device__ __forceinline__ Place place_of(const ThresholdArgs& A, const LayerDesc& L, uint32_t l) {
+__device__ __forceinline__ Place place_of(const ThresholdArgs& A, const LayerDesc& L, uint32_t l, uint32_t wg) {
   Place p;
   p.l = l;
-  const uint32_t wc_local = (blockIdx.x - L.wg_first) * kWavesPerBlock + (threadIdx.x >> 6);
+  const uint32_t wc_local = (wg - L.wg_first) * kWavesPerBlock + (threadIdx.x >> 6);
   p.wc = L.wc_first + wc_local;
   if (wc_local < L.wc_count) {
     p.begin = wc_local * A.chunk;
@@ -67,12 +67,26 @@ __device__ __forceinline__ Place place_of(const ThresholdArgs& A, const LayerDes
 }
 
 // Calls f(a, nvalid, idx0) for the groups of 256 elements of [begin, end) of tensor p: lane-major,
-// four consecutive elements per lane.
+// four consecutive elements per lane; whole groups of an aligned tensor four at a time.
 template <typename F>
 __device__ __forceinline__ void read_groups(const float* generic_p, bool vec, uint32_t begin, uint32_t end, F&& f) {
   const gptr<const float> p = as_global(generic_p);
   const uint32_t lane = lane_id();
-  for (uint32_t base = begin; base < end; base += kGroupElems) {
+  uint32_t base = begin;
+  if (vec) {
+    constexpr uint32_t kUnroll = 4u;
+    for (; base + kUnroll * kGroupElems <= end; base += kUnroll * kGroupElems) {
+      vf4 q[kUnroll];
+#pragma unroll
+      for (uint32_t t = 0; t < kUnroll; ++t) q[t] = *reinterpret_cast<gptr<const vf4>>(p + base + t * kGroupElems + lane * 4u);
+#pragma unroll
+      for (uint32_t t = 0; t < kUnroll; ++t) {
+        const float a[4] = {q[t].x, q[t].y, q[t].z, q[t].w};
+        f(a, 4u, base + t * kGroupElems + lane * 4u);
+      }
+    }
+  }
+  for (; base < end; base += kGroupElems) {
     const uint32_t idx0 = base + lane * 4u;
     float a[4] = {0.f, 0.f, 0.f, 0.f};
     uint32_t nvalid;
@@ -91,14 +105,41 @@ __device__ __forceinline__ void read_groups(const float* generic_p, bool vec, ui
 }
 
 // The accumulate of Algorithm 1 over [begin, end) of a layer (same arithmetic as the exact path:
-// accum4), handing every group of accumulated values to f.
+// accum4), handing every group of accumulated values to f.  Whole groups of an aligned layer are
+// taken four (two with a velocity) at a time, all their loads issued before the first use.
 template <bool kMom, bool kNest, typename F>
 __device__ __forceinline__ void accumulate_groups(const LayerDesc& L, uint32_t begin, uint32_t end, const AccumRule& rule, F&& f) {
   const gptr<const float> G = as_global(L.grad);
   const gptr<float> V = as_global(L.resid);
   const gptr<float> U = as_global(L.mom);
   const uint32_t lane = lane_id();
-  for (uint32_t base = begin; base < end; base += kGroupElems) {
+  uint32_t base = begin;
+  if (L.vec_ok) {
+    constexpr uint32_t kUnroll = kMom ? 2u : 4u;
+    for (; base + kUnroll * kGroupElems <= end; base += kUnroll * kGroupElems) {
+      vf4 gq[kUnroll], vq[kUnroll], uq[kUnroll];
+#pragma unroll
+      for (uint32_t t = 0; t < kUnroll; ++t) {
+        const uint32_t idx0 = base + t * kGroupElems + lane * 4u;
+        gq[t] = __builtin_nontemporal_load(reinterpret_cast<gptr<const vf4>>(G + idx0));
+        vq[t] = *reinterpret_cast<gptr<const vf4>>(V + idx0);
+        if constexpr (kMom) uq[t] = *reinterpret_cast<gptr<const vf4>>(U + idx0);
+      }
+#pragma unroll
+      for (uint32_t t = 0; t < kUnroll; ++t) {
+        const uint32_t idx0 = base + t * kGroupElems + lane * 4u;
+        const float g[4] = {gq[t].x, gq[t].y, gq[t].z, gq[t].w};
+        const float v[4] = {vq[t].x, vq[t].y, vq[t].z, vq[t].w};
+        float u[4] = {0.f, 0.f, 0.f, 0.f}, a[4];
+        if constexpr (kMom) { u[0] = uq[t].x; u[1] = uq[t].y; u[2] = uq[t].z; u[3] = uq[t].w; }
+        accum4<kMom, kNest>(g, v, u, rule, a);
+        *reinterpret_cast<gptr<vf4>>(V + idx0) = vf4{a[0], a[1], a[2], a[3]};
+        if constexpr (kMom) *reinterpret_cast<gptr<vf4>>(U + idx0) = vf4{u[0], u[1], u[2], u[3]};
+        f(a, 4u, idx0);
+      }
+    }
+  }
+  for (; base < end; base += kGroupElems) {
     const uint32_t idx0 = base + lane * 4u;
     float g[4] = {0.f, 0.f, 0.f, 0.f}, v[4] = {0.f, 0.f, 0.f, 0.f}, u[4] = {0.f, 0.f, 0.f, 0.f}, a[4];
     if (L.vec_ok && base + kGroupElems <= end) {
@@ -154,11 +195,12 @@ __device__ __forceinline__ float wave_max(float x) {
 // ------------------------------------------------------------------ accumulate (+ moments or counts)
 // kCount = false (a search follows): leaves per wave-chunk the fp64 sum and the maximum of |a|.
 // kCount = true (the threshold is given): leaves per wave-chunk the number of |a| > threshold.
-template <bool kCount>
+template <bool kCount, bool kReverse>
 __global__ void __launch_bounds__(kBlockThreads) threshold_accumulate_kernel(ThresholdArgs A) {
-  const uint32_t l = A.wg2layer[blockIdx.x];
+  const uint32_t wg = kReverse ? gridDim.x - 1u - blockIdx.x : blockIdx.x;
+  const uint32_t l = A.wg2layer[wg];
   const LayerDesc L = A.layers[l];
-  const Place p = place_of(A, L, l);
+  const Place p = place_of(A, L, l, wg);
   if (p.begin == p.end) return;
   const float thr = kCount ? *as_global(A.thresholds + l) : 0.0f;
   double sum = 0.0;
@@ -235,11 +277,13 @@ __global__ void __launch_bounds__(kBlockThreads) threshold_moments_kernel(Thresh
 }
 
 // ------------------------------------------------------------------ histogram over the candidate thresholds
+template <bool kReverse>
 __global__ void __launch_bounds__(kBlockThreads) threshold_histogram_kernel(ThresholdArgs A) {
   __shared__ uint32_t lds_hist[kSteps];
-  const uint32_t l = A.wg2layer[blockIdx.x];
+  const uint32_t wg = kReverse ? gridDim.x - 1u - blockIdx.x : blockIdx.x;
+  const uint32_t l = A.wg2layer[wg];
   const LayerDesc L = A.layers[l];
-  const Place p = place_of(A, L, l);
+  const Place p = place_of(A, L, l, wg);
   for (uint32_t b = threadIdx.x; b < kSteps; b += kBlockThreads) lds_hist[b] = 0u;
   __syncthreads();
   const ThresholdMoments M = A.moments[l];
@@ -314,10 +358,12 @@ __global__ void __launch_bounds__(kBlockThreads) threshold_search_kernel(Thresho
 }
 
 // ------------------------------------------------------------------ count, offsets, emit
+template <bool kReverse>
 __global__ void __launch_bounds__(kBlockThreads) threshold_count_kernel(ThresholdArgs A) {
-  const uint32_t l = A.wg2layer[blockIdx.x];
+  const uint32_t wg = kReverse ? gridDim.x - 1u - blockIdx.x : blockIdx.x;
+  const uint32_t l = A.wg2layer[wg];
   const LayerDesc L = A.layers[l];
-  const Place p = place_of(A, L, l);
+  const Place p = place_of(A, L, l, wg);
   if (p.begin == p.end) return;
   const float thr = *as_global(A.thresholds + l);
   uint32_t cnt = 0u;
@@ -361,10 +407,12 @@ __global__ void __launch_bounds__(kBlockThreads) threshold_offsets_kernel(Thresh
   }
 }
 
+template <bool kReverse>
 __global__ void __launch_bounds__(kBlockThreads) threshold_emit_kernel(ThresholdArgs A) {
-  const uint32_t l = A.wg2layer[blockIdx.x];
+  const uint32_t wg = kReverse ? gridDim.x - 1u - blockIdx.x : blockIdx.x;
+  const uint32_t l = A.wg2layer[wg];
   const LayerDesc L = A.layers[l];
-  const Place p = place_of(A, L, l);
+  const Place p = place_of(A, L, l, wg);
   if (p.begin == p.end) return;
   const float thr = *as_global(A.thresholds + l);
   const uint32_t cap = 2u * L.k;
@@ -401,24 +449,29 @@ __global__ void __launch_bounds__(kBlockThreads) threshold_emit_kernel(Threshold
 hipError_t launch_threshold_compress(const ThresholdArgs& a, uint32_t num_wgs, uint32_t num_layers, hipStream_t s) {
   const dim3 block(kBlockThreads);
 #define RGC_LAUNCHED() do { hipError_t e_ = hipGetLastError(); if (e_ != hipSuccess) return e_; } while (0)
+  // Each pass over the tensors runs against the direction of the one before it: what that one touched last
+  // (still in the memory-side cache) is read first.
   if (a.search) {
-    hipLaunchKernelGGL(threshold_accumulate_kernel<false>, dim3(num_wgs), block, 0, s, a);
+    hipLaunchKernelGGL((threshold_accumulate_kernel<false, false>), dim3(num_wgs), block, 0, s, a);
     RGC_LAUNCHED();
     hipLaunchKernelGGL(threshold_moments_kernel, dim3(num_layers), block, 0, s, a);
     RGC_LAUNCHED();
-    hipLaunchKernelGGL(threshold_histogram_kernel, dim3(num_wgs), block, 0, s, a);
+    hipLaunchKernelGGL(threshold_histogram_kernel<true>, dim3(num_wgs), block, 0, s, a);
     RGC_LAUNCHED();
     hipLaunchKernelGGL(threshold_search_kernel, dim3(num_layers), block, 0, s, a);
     RGC_LAUNCHED();
-    hipLaunchKernelGGL(threshold_count_kernel, dim3(num_wgs), block, 0, s, a);
+    hipLaunchKernelGGL(threshold_count_kernel<false>, dim3(num_wgs), block, 0, s, a);
     RGC_LAUNCHED();
+    hipLaunchKernelGGL(threshold_offsets_kernel, dim3(num_layers), block, 0, s, a);
+    RGC_LAUNCHED();
+    hipLaunchKernelGGL(threshold_emit_kernel<true>, dim3(num_wgs), block, 0, s, a);
   } else {
-    hipLaunchKernelGGL(threshold_accumulate_kernel<true>, dim3(num_wgs), block, 0, s, a);
+    hipLaunchKernelGGL((threshold_accumulate_kernel<true, false>), dim3(num_wgs), block, 0, s, a);
     RGC_LAUNCHED();
+    hipLaunchKernelGGL(threshold_offsets_kernel, dim3(num_layers), block, 0, s, a);
+    RGC_LAUNCHED();
+    hipLaunchKernelGGL(threshold_emit_kernel<true>, dim3(num_wgs), block, 0, s, a);
   }
-  hipLaunchKernelGGL(threshold_offsets_kernel, dim3(num_layers), block, 0, s, a);
-  RGC_LAUNCHED();
-  hipLaunchKernelGGL(threshold_emit_kernel, dim3(num_wgs), block, 0, s, a);
 #undef RGC_LAUNCHED
   return hipGetLastError();
 }

@@ -124,3 +124,53 @@ def test_decompress_largest_tensor_disjoint_workers(rgc):
         ref[d_idx[w][0].to(torch.int64)] = (0.0 + d_val[w][0]) * scale
     assert torch.equal(dense.view(torch.int32), ref.view(torch.int32))
     ctx.close()
+
+
+def test_threshold_search_largest_tensor(rgc):
+    """Threshold binary search selection (Section 2.1, Algorithm 3) on 2^31 - 1 elements: the search
+    stops with between k and 2k elements above its threshold, the message is exactly those elements
+    in index order, the rest stays in the residual; then the same threshold reused on the next
+    gradient."""
+    import torch
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(0x5EED0007)
+    n = N_MAX
+    k = rgc.rgc_k_for_density(n, 100)
+    V = torch.randn(n, device=dev, generator=gen) * 5e-3
+    G = torch.empty(n, dtype=torch.float32, device=dev)
+    out_idx = torch.full((2 * k,), -1, dtype=torch.int32, device=dev)
+    out_val = torch.full((2 * k,), float("nan"), dtype=torch.float32, device=dev)
+    out_count = torch.full((1,), -1, dtype=torch.int32, device=dev)
+    thr = torch.zeros(1, dtype=torch.float32, device=dev)
+    nnz = torch.zeros(1, dtype=torch.int32, device=dev)
+    layers = rgc.LayerList([G], [V], [k], [out_idx], [out_val], out_count)
+    ctx = rgc.Context(n, 1)
+    stream = torch.cuda.current_stream()
+    for step, search in enumerate((True, False)):
+        print("  largest tensor, threshold %s" % ("search" if search else "reuse"), flush=True)
+        G.copy_(torch.randn(n, device=dev, generator=gen) * 1e-3)
+        a_ref = V + G
+        rgc.rgc_compress_layers_threshold(ctx, layers, 0.0, thr, nnz, rgc.RGC_THRESHOLD_SEARCH if search else 0, stream)
+        torch.cuda.synchronize()
+        t = thr[0]
+        above = a_ref.abs() > t
+        want = int(above.sum())
+        assert int(nnz.item()) == want
+        if search:
+            assert k < want < 2 * k, "the search is meant to stop between k and 2k here"
+            mean = float(a_ref.abs().sum(dtype=torch.float64) / n)
+            top = float(a_ref.abs().max())
+            ratio = (float(t) - mean) / (top - mean)
+            assert 0.0 < ratio < 1.0 and abs(ratio * 1024 - round(ratio * 1024)) < 1e-2, ratio
+        c = min(want, 2 * k)
+        assert int(out_count.item()) == c
+        idx = torch.nonzero(above).flatten()[:c]
+        del above
+        assert torch.equal(out_idx[:c].to(torch.int64), idx)
+        assert torch.equal(out_val[:c].view(torch.int32), a_ref[idx].view(torch.int32))
+        expect = a_ref
+        expect[idx] = 0.0
+        assert torch.equal(V.view(torch.int32), expect.view(torch.int32))
+        del a_ref, expect, idx
+    ctx.close()
