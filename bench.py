@@ -101,6 +101,34 @@ def time_loop(torch, fn, steps):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
+def measure_threshold(torch, rgc, ctx, wl, stream, steps, dev):
+    """A call that searches the thresholds, a call that reuses them, and the paper's schedule (search every
+    fifth call) on the workload's tensors; message buffers of 2k entries."""
+    out_idx2 = [torch.empty(2 * k, dtype=torch.int32, device=dev) for k in wl.ks]
+    out_val2 = [torch.empty(2 * k, dtype=torch.float32, device=dev) for k in wl.ks]
+    lists2 = [rgc.LayerList(g, wl.V, wl.ks, out_idx2, out_val2, wl.out_count, wl.U) for g in wl.G]
+    thr = torch.zeros(len(wl.sizes), dtype=torch.float32, device=dev)
+    nnz = torch.zeros(len(wl.sizes), dtype=torch.int32, device=dev)
+    calls = [0]
+
+    def tbs(search):
+        rgc.rgc_compress_layers_threshold(ctx, lists2[calls[0] % len(lists2)], wl.m, thr, nnz,
+                                          rgc.RGC_THRESHOLD_SEARCH if search else 0, stream)
+        calls[0] += 1
+
+    for _ in range(5):
+        tbs(True)
+    reps = min(steps, 50)
+    ms_search = time_loop(torch, lambda: tbs(True), reps)
+    ms_reuse = time_loop(torch, lambda: tbs(False), reps)
+    ms_sampled = time_loop(torch, lambda: tbs(calls[0] % 5 == 0), 5 * max(1, reps // 5))
+    sent = nnz.cpu().numpy()
+    return {"search_call_ms": ms_search, "reuse_call_ms": ms_reuse, "sampled_every_5_ms": ms_sampled,
+            "sent_over_k_last_call": float(sent.sum()) / float(sum(wl.ks)),
+            "search_call_alg_bytes": wl.alg_bytes_stream + 3 * 4 * wl.total,
+            "reuse_call_alg_bytes": wl.alg_bytes_stream + 4 * wl.total}
+
+
 def measure_compress(torch, rgc, ctx, wl, stream, steps, warmup):
     """Steady-state ms/iter plus first-call and hint-free timings of one compress workload."""
     out = {"elements": wl.total, "tensors": len(wl.sizes), "sum_k": sum(wl.ks)}
@@ -299,33 +327,10 @@ def main():
                     "message_means_ms": ms_means, "decompress_one_value_ms": ms_dec1,
                     "decompress_alg_bytes": 4 * dec.entries + 4 * sum(dec.sizes)}
 
-    # Threshold binary search selection (Section 2.1, Algorithm 3) and its sampled variant on the same tensors:
-    # a call that searches the thresholds, a call that reuses them, and the paper's schedule (search every fifth call)
+    # Threshold binary search selection (Section 2.1, Algorithm 3) and its sampled variant on the same tensors
     tbs_info = None
     if not args.step_only:
-        out_idx2 = [torch.empty(2 * k, dtype=torch.int32, device=dev) for k in vgg.ks]
-        out_val2 = [torch.empty(2 * k, dtype=torch.float32, device=dev) for k in vgg.ks]
-        lists2 = [rgc.LayerList(g, vgg.V, vgg.ks, out_idx2, out_val2, vgg.out_count, vgg.U) for g in vgg.G]
-        thr = torch.zeros(len(vgg.sizes), dtype=torch.float32, device=dev)
-        nnz = torch.zeros(len(vgg.sizes), dtype=torch.int32, device=dev)
-        calls = [0]
-
-        def tbs(search):
-            rgc.rgc_compress_layers_threshold(ctx, lists2[calls[0] % len(lists2)], vgg.m, thr, nnz,
-                                              rgc.RGC_THRESHOLD_SEARCH if search else 0, stream)
-            calls[0] += 1
-
-        for _ in range(5):
-            tbs(True)
-        ms_search = time_loop(torch, lambda: tbs(True), min(args.steps, 50))
-        ms_reuse = time_loop(torch, lambda: tbs(False), min(args.steps, 50))
-        ms_sampled = time_loop(torch, lambda: tbs(calls[0] % 5 == 0), 5 * max(1, min(args.steps, 50) // 5))
-        sent = nnz.cpu().numpy()
-        tbs_info = {"search_call_ms": ms_search, "reuse_call_ms": ms_reuse, "sampled_every_5_ms": ms_sampled,
-                    "sent_over_k_last_call": float(sent.sum()) / float(sum(vgg.ks)),
-                    "search_call_alg_bytes": vgg.alg_bytes_stream + 3 * 4 * vgg.total,
-                    "reuse_call_alg_bytes": vgg.alg_bytes_stream + 4 * vgg.total}
-        del out_idx2, out_val2, lists2
+        tbs_info = measure_threshold(torch, rgc, ctx, vgg, stream, args.steps, dev)
 
     if args.calibrate_copy:
         src = torch.zeros(vgg.total, dtype=torch.float32, device=dev)
@@ -347,6 +352,8 @@ def main():
             log("workload %s..." % name)
             wl = CompressWorkload(torch, rgc, make(), dev)
             others[name] = measure_compress(torch, rgc, ctx, wl, stream, args.steps, args.warmup)
+            if name == "lstm":      # the paper selects the large layers of its recurrent models this way
+                others[name]["threshold_search"] = measure_threshold(torch, rgc, ctx, wl, stream, args.steps, dev)
             del wl
             torch.cuda.empty_cache()
 

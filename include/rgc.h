@@ -166,12 +166,14 @@ int rgc_message_means(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers,
  * with a reused threshold or a search that found no count between k and 2k) the first 2k of them in
  * index order are sent and the others stay in the residual.  Indices ascending, values, masking of
  * residual and velocity, momentum correction (momentum, RGC_NESTEROV, RGC_NO_MOMENTUM_MASK) as in
- * rgc_compress_layers.  Inputs must be finite.  Shares the context's scratch with the other calls
+ * rgc_compress_layers, grad_scale (DEVICE, or NULL) as in rgc_compress_layers_scaled: the paper
+ * clips the gradients of its recurrent models, whose large layers are the ones it selects this
+ * way.  Inputs must be finite.  Shares the context's scratch with the other calls
  * (one at a time per context) and leaves the speed hints of rgc_compress_layers alone.
  * Errors (nothing enqueued): RGC_EINVAL, RGC_ENOMEM, RGC_EHIP. */
 int rgc_compress_layers_threshold(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers,
-                                  float momentum, float* thresholds, int32_t* nnz, uint32_t flags,
-                                  void* hip_stream);
+                                  float momentum, const float* grad_scale, float* thresholds,
+                                  int32_t* nnz, uint32_t flags, void* hip_stream);
 
 /* Local gradient clipping (Section 2.4: the gradients of all layers are clipped by their common
  * norm before they are added to the residuals, with a threshold of N^(-1/2) of the original one).

@@ -70,7 +70,7 @@ def lib() -> ctypes.CDLL:
         L.rgc_oracle_compress_layer_threshold.restype = ctypes.c_int
         L.rgc_oracle_compress_layer_threshold.argtypes = [
             _f32p, _f32p, _f32p, ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_int, ctypes.c_int,
-            ctypes.c_int, _f32p, ctypes.c_int32, _i32p, _f32p, _i32p, ctypes.POINTER(ctypes.c_int64), _f32p]
+            _f32p, ctypes.c_int, _f32p, ctypes.c_int32, _i32p, _f32p, _i32p, ctypes.POINTER(ctypes.c_int64), _f32p]
         L.rgc_oracle_decompress_scalar.restype = ctypes.c_int
         L.rgc_oracle_decompress_scalar.argtypes = [ctypes.POINTER(_i32p), _f32p, _i32p, ctypes.c_int32, _f32p,
                                                    ctypes.c_int64, ctypes.c_float, ctypes.c_int]
@@ -190,7 +190,8 @@ def compress_layer_asq(grad: np.ndarray, residual: np.ndarray, k: int, sign: int
 def compress_layer_threshold(grad: np.ndarray, residual: np.ndarray, k: int, search: bool = True,
                              threshold: float = 0.0, cap: Optional[int] = None,
                              momentum: Optional[np.ndarray] = None, m: float = 0.0,
-                             mask_momentum: bool = True, nesterov: bool = False):
+                             mask_momentum: bool = True, nesterov: bool = False,
+                             grad_scale: Optional[float] = None):
     """Threshold binary search selection of one layer IN PLACE (Algorithm 3; search=False applies
     `threshold` as given).  cap defaults to 2k.
 
@@ -204,9 +205,11 @@ def compress_layer_threshold(grad: np.ndarray, residual: np.ndarray, k: int, sea
     nnz = ctypes.c_int64(0)
     thr = np.array([threshold], dtype=np.float32)
     trace = np.zeros(4, dtype=np.float32)
+    sc = np.array([grad_scale], dtype=np.float32) if grad_scale is not None else None
     rc = lib().rgc_oracle_compress_layer_threshold(
         _f32(grad), _f32(residual), _f32(momentum) if momentum is not None else None, grad.size, int(k),
-        float(m), 1 if mask_momentum else 0, 1 if nesterov else 0, 1 if search else 0, _f32(thr), int(cap),
+        float(m), 1 if mask_momentum else 0, 1 if nesterov else 0, _f32(sc) if sc is not None else None,
+        1 if search else 0, _f32(thr), int(cap),
         _i32(out_idx), _f32(out_val), _i32(out_cnt), ctypes.byref(nnz), _f32(trace))
     if rc != 0:
         raise ValueError("oracle rejected the arguments")

@@ -250,20 +250,22 @@ int rgc_oracle_compress_layer_asq(const float* grad, float* residual, float* mom
 }
 
 // One layer of the compression step with threshold binary search selection
-// (see the top of this file).  search != 0: Algorithm 3 finds *threshold;
+// (see the top of this file).  `scale` (NULL: none) is the clipping coefficient
+// of the accumulate.  search != 0: Algorithm 3 finds *threshold;
 // search == 0: *threshold is applied as given.  out_idx / out_val hold cap
 // entries; *out_count = min(nnz, cap); *out_nnz = the number of elements above
 // the threshold.  out_trace (may be NULL, 4 floats): mean, max, number of
 // counts taken, last ratio.
 int rgc_oracle_compress_layer_threshold(const float* grad, float* residual, float* momentum,
                                         int64_t n, int32_t k, float m, int mask_momentum,
-                                        int nesterov, int search, float* threshold, int32_t cap,
+                                        int nesterov, const float* scale, int search, float* threshold,
+                                        int32_t cap,
                                         int32_t* out_idx, float* out_val, int32_t* out_count,
                                         int64_t* out_nnz, float* out_trace) {
   if (!grad || !residual || !threshold || !out_idx || !out_val || !out_count || !out_nnz) return -1;
   if (n < 1 || n >= (int64_t(1) << 31) || k < 1 || k > n || cap < 1) return -1;
   std::vector<float> acc;
-  accumulate(grad, residual, momentum, n, m, nesterov, nullptr, acc);
+  accumulate(grad, residual, momentum, n, m, nesterov, scale, acc);
   auto count_above = [&](float t) {
     int64_t c = 0;
     for (int64_t i = 0; i < n; ++i) c += (std::fabs(acc[i]) > t) ? 1 : 0;

@@ -83,8 +83,8 @@ def load_library() -> ctypes.CDLL:
                                              ctypes.c_float, ctypes.c_void_p, ctypes.c_uint32, ctypes.c_void_p]
     L.rgc_compress_layers_threshold.restype = ctypes.c_int
     L.rgc_compress_layers_threshold.argtypes = [ctypes.c_void_p, ctypes.POINTER(rgc_layer), ctypes.c_int32,
-                                                ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint32,
-                                                ctypes.c_void_p]
+                                                ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                                ctypes.c_uint32, ctypes.c_void_p]
     L.rgc_message_means.restype = ctypes.c_int
     L.rgc_message_means.argtypes = [ctypes.c_void_p, ctypes.POINTER(rgc_layer), ctypes.c_int32, ctypes.c_void_p,
                                     ctypes.c_void_p]
@@ -253,11 +253,12 @@ def rgc_compress_layers_scaled(ctx: Context, layers: LayerList, momentum: float 
 
 
 def rgc_compress_layers_threshold(ctx: Context, layers: LayerList, momentum: float, thresholds, nnz=None,
-                                  flags: int = 0, stream=None) -> None:
+                                  flags: int = 0, stream=None, grad_scale=None) -> None:
     """thresholds: float32 device tensor of num_layers elements (written with RGC_THRESHOLD_SEARCH, read
-    otherwise); nnz: int32 device tensor of num_layers elements or None.  The layers' out_idx / out_val
-    hold 2 * k entries."""
+    otherwise); nnz: int32 device tensor of num_layers elements or None; grad_scale: a one-element float32
+    device tensor or None.  The layers' out_idx / out_val hold 2 * k entries."""
     _check(load_library().rgc_compress_layers_threshold(ctx.handle, layers.array, layers.num_layers, float(momentum),
+                                                        _ptr(grad_scale) if grad_scale is not None else None,
                                                         _ptr(thresholds), _ptr(nnz) if nnz is not None else None,
                                                         int(flags), _stream(stream)))
 

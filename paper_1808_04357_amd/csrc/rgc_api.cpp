@@ -512,10 +512,12 @@ int rgc_message_means(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers,
 }
 
 int rgc_compress_layers_threshold(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers, float momentum,
-                                  float* thresholds, int32_t* nnz, uint32_t flags, void* hip_stream) {
+                                  const float* grad_scale, float* thresholds, int32_t* nnz, uint32_t flags,
+                                  void* hip_stream) {
   if (!ctx || !layers || !thresholds || num_layers < 1 || num_layers > ctx->max_layers) return RGC_EINVAL;
   if (flags & ~(RGC_NO_MOMENTUM_MASK | RGC_NESTEROV | RGC_THRESHOLD_SEARCH)) return RGC_EINVAL;
-  if ((reinterpret_cast<uintptr_t>(thresholds) | reinterpret_cast<uintptr_t>(nnz)) & 3u) return RGC_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(thresholds) | reinterpret_cast<uintptr_t>(nnz) |
+       reinterpret_cast<uintptr_t>(grad_scale)) & 3u) return RGC_EINVAL;
   for (int32_t l = 0; l < num_layers; ++l)
     if (layers[l].k > (int32_t(1) << 30)) return RGC_EINVAL;              // 2k entries must be countable
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -532,6 +534,7 @@ int rgc_compress_layers_threshold(rgc_ctx* ctx, const rgc_layer* layers, int32_t
   A.wg2layer = plan->d_wg2layer.p;
   A.thresholds = thresholds;
   A.nnz = nnz;
+  A.grad_scale = grad_scale;
   A.part_sum = ctx->d_norm_part.p;
   A.part_max = reinterpret_cast<float*>(ctx->d_wc_b.p);
   A.counts = ctx->d_wc_a.p;

@@ -120,6 +120,7 @@ struct ThresholdArgs {
   const uint32_t* wg2layer;
   float* thresholds;        // [layers] the caller's: written by a search, read otherwise
   int32_t* nnz;             // [layers] the caller's, or null: elements above the threshold
+  const float* grad_scale;  // device word every gradient element is multiplied with first, or null
   double* part_sum;         // [wave-chunks] partial sums of |a|
   float* part_max;          // [wave-chunks] partial maxima of |a|
   uint32_t* counts;         // [wave-chunks] elements above the threshold, then first output positions

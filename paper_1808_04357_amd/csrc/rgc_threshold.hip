@@ -222,7 +222,7 @@ __global__ void __launch_bounds__(kBlockThreads) threshold_accumulate_kernel(Thr
   };
   AccumRule rule;
   rule.m = A.m;
-  rule.scale = 1.0f;
+  rule.scale = A.grad_scale ? *as_global(A.grad_scale) : 1.0f;
   if (L.mom == nullptr) accumulate_groups<false, false>(L, p.begin, p.end, rule, take);
   else if (!A.nesterov) accumulate_groups<true, false>(L, p.begin, p.end, rule, take);
   else accumulate_groups<true, true>(L, p.begin, p.end, rule, take);

@@ -36,13 +36,16 @@ class Runner:
         self.thr_h = [0.0] * len(V0)
         self.t = 0
 
-    def step(self, G, search, nesterov=False):
+    def step(self, G, search, nesterov=False, grad_scale=None):
         rgc, torch = self.rgc, self.torch
         print("  %s step %d %s" % (self.tag, self.t, "search" if search else "reuse"), flush=True)
         self.dev.set_grads(G)
         flags = (rgc.RGC_THRESHOLD_SEARCH if search else 0) | (rgc.RGC_NESTEROV if nesterov else 0)
+        d_scale = None
+        if grad_scale is not None:
+            d_scale = torch.full((1,), float(grad_scale), dtype=torch.float32, device=self.thr.device)
         rgc.rgc_compress_layers_threshold(self.ctx, self.dev.layers, self.m, self.thr, self.nnz, flags,
-                                          torch.cuda.current_stream())
+                                          torch.cuda.current_stream(), grad_scale=d_scale)
         idx, val, cnt, V, U = self.dev.results()
         thr = self.thr.cpu().numpy()
         nnz = self.nnz.cpu().numpy()
@@ -50,7 +53,8 @@ class Runner:
         for l, k in enumerate(self.ks):
             oi, ov, onnz, othr, trace = self.oracle.compress_layer_threshold(
                 G[l], self.Vh[l], k, search=search, threshold=float(self.thr_h[l]),
-                momentum=self.Uh[l] if self.Uh is not None else None, m=self.m, nesterov=nesterov)
+                momentum=self.Uh[l] if self.Uh is not None else None, m=self.m, nesterov=nesterov,
+                grad_scale=grad_scale)
             self.thr_h[l] = othr
             where = "%s step %d layer %d (n=%d, k=%d)" % (self.tag, self.t, l, self.Vh[l].size, k)
             assert u32(np.array([thr[l]], np.float32))[0] == u32(np.array([othr], np.float32))[0], \
@@ -102,7 +106,7 @@ def test_search_with_momentum_and_nesterov_unaligned(rgc, oracle):
                    tag="threshold momentum nesterov=%s misalign=%d" % (nesterov, misalign))
         for t in range(3):
             G = [(g.laplace(0, 1e-3, n)).astype(np.float32) for n in sizes]
-            r.step(G, search=(t != 1), nesterov=nesterov)
+            r.step(G, search=(t != 1), nesterov=nesterov, grad_scale=None if t == 0 else 0.37)
         r.close()
 
 
