@@ -126,7 +126,7 @@ def measure_threshold(torch, rgc, ctx, wl, stream, steps, dev):
     return {"search_call_ms": ms_search, "reuse_call_ms": ms_reuse, "sampled_every_5_ms": ms_sampled,
             "sent_over_k_last_call": float(sent.sum()) / float(sum(wl.ks)),
             "search_call_alg_bytes": wl.alg_bytes_stream + 3 * 4 * wl.total,
-            "reuse_call_alg_bytes": wl.alg_bytes_stream + 4 * wl.total}
+            "reuse_call_alg_bytes": wl.alg_bytes_stream}
 
 
 def measure_compress(torch, rgc, ctx, wl, stream, steps, warmup):

@@ -160,6 +160,7 @@ struct rgc_ctx {
   uint64_t tick = 0;
   bool compressed_since_decompress = false;
   uint64_t compress_calls = 0;             // its parity is the direction of the next streaming pass
+  uint32_t threshold_reverse = 0;          // direction of the next threshold-selection call's first pass
   // Speed hints are kept per selection mode (0 magnitude, 1 largest, 2 smallest: the thresholds of
   // the positive and the negative tail differ, and Alternating Signs Quantization switches between
   // them from call to call): bank b uses the layer states [b * max_layers, (b + 1) * max_layers).
@@ -455,8 +456,8 @@ int plan_for_layers(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers, h
 // (256 MB on MI355X): the tail of what the previous call wrote is then still cached and is read
 // first.  Smaller layer sets stay cached whatever the order, and ascending order (largest layers
 // first) is the better one for them.
+constexpr uint64_t kMemorySideCacheBytes = 256ull << 20;
 uint32_t streaming_direction(const CompressPlan* plan, uint64_t call) {
-  constexpr uint64_t kMemorySideCacheBytes = 256ull << 20;
   return (plan->write_bytes > kMemorySideCacheBytes) ? static_cast<uint32_t>(call & 1u) : 0u;
 }
 
@@ -538,6 +539,9 @@ int rgc_compress_layers_threshold(rgc_ctx* ctx, const rgc_layer* layers, int32_t
   A.part_sum = ctx->d_norm_part.p;
   A.part_max = reinterpret_cast<float*>(ctx->d_wc_b.p);
   A.counts = ctx->d_wc_a.p;
+  A.listed = ctx->d_cand_cnt.p;
+  A.slots = ctx->d_slots.p;
+  A.cap = plan->chunk / kCapDiv;
   A.hist = ctx->d_hist.p;
   A.moments = ctx->d_moments.p;
   A.chunk = plan->chunk;
@@ -545,7 +549,12 @@ int rgc_compress_layers_threshold(rgc_ctx* ctx, const rgc_layer* layers, int32_t
   A.mask_momentum = (flags & RGC_NO_MOMENTUM_MASK) ? 0u : 1u;
   A.nesterov = (flags & RGC_NESTEROV) ? 1u : 0u;
   A.m = momentum;
+  // A searching call passes over the tensors four times and ends where it began; a reusing call passes once:
+  // the call after it starts from the end it stopped at, whose data the memory-side cache still holds.
+  const bool alternate = plan->write_bytes > kMemorySideCacheBytes;
+  A.reverse = alternate ? ctx->threshold_reverse : 0u;
   RGC_HIP(launch_threshold_compress(A, plan->num_wgs, static_cast<uint32_t>(num_layers), stream));
+  if (!A.search) ctx->threshold_reverse ^= 1u;
   ctx->compressed_since_decompress = true;
   return RGC_OK;
 }

@@ -124,10 +124,14 @@ struct ThresholdArgs {
   double* part_sum;         // [wave-chunks] partial sums of |a|
   float* part_max;          // [wave-chunks] partial maxima of |a|
   uint32_t* counts;         // [wave-chunks] elements above the threshold, then first output positions
+  uint32_t* listed;         // [wave-chunks] elements above the threshold (kept; more than cap: list incomplete)
+  uint2* slots;             // [wave-chunks][cap] (float bits, index) of the elements above a reused threshold
+  uint32_t cap;             // list slots per wave-chunk
   uint32_t* hist;           // [layers][kHistBins], the first 1024 bins of each are used
   ThresholdMoments* moments;  // [layers]
   uint32_t chunk;           // elements per wave-chunk
   uint32_t search;          // 1: Algorithm 3 finds the thresholds; 0: they are given
+  uint32_t reverse;         // the first pass takes its workgroups in descending order (and every pass after it the other way)
   uint32_t mask_momentum;
   uint32_t nesterov;
   float m;

@@ -14,7 +14,8 @@
 // Launches of one call (same workgroup -> layer -> wave-chunk decomposition as the exact path):
 //   search:  accumulate (+ partial sums and maxima of |a|)  ->  moments  ->  histogram  ->  search
 //            ->  count  ->  offsets  ->  emit
-//   reuse:   accumulate (+ counts above the given threshold)  ->  offsets  ->  emit
+//   reuse:   accumulate (+ the elements above the given threshold, listed per wave-chunk)  ->  offsets
+//            ->  emit from the lists
 #include "rgc_device.h"
 
 namespace rgc {
@@ -22,6 +23,13 @@ namespace rgc {
 namespace {
 
 constexpr uint32_t kSteps = 1024;   // 1 / epsilon of the search: ratios are multiples of 2^-10
+
+typedef uint32_t vu2 __attribute__((ext_vector_type(2)));   // a listed element: (float bits, index)
+
+// The zeros that mask a sent entry out of the residual (and the velocity) are isolated 4-byte writes;
+// stored with the streaming hint they leave the caches early instead of being written back one by
+// one while the next pass over the tensors runs.
+__device__ __forceinline__ void mask_store(gptr<float> p) { __builtin_nontemporal_store(0.0f, p); }
 
 // T(j), j = 1 .. 1023; the operations and their order are those of Algorithm 3.
 __device__ __forceinline__ float threshold_at(float mean, float span, uint32_t j) {
@@ -194,10 +202,11 @@ __device__ __forceinline__ float wave_max(float x) {
 
 // ------------------------------------------------------------------ accumulate (+ moments or counts)
 // kCount = false (a search follows): leaves per wave-chunk the fp64 sum and the maximum of |a|.
-// kCount = true (the threshold is given): leaves per wave-chunk the number of |a| > threshold.
+// kCount = true (the threshold is given): leaves per wave-chunk the number of |a| > threshold and, in
+// the wave-chunk's list, those elements themselves (as many as the list holds).
 template <bool kCount, bool kReverse>
 __global__ void __launch_bounds__(kBlockThreads) threshold_accumulate_kernel(ThresholdArgs A) {
-  const uint32_t wg = kReverse ? gridDim.x - 1u - blockIdx.x : blockIdx.x;
+  const uint32_t wg = (kReverse != (A.reverse != 0u)) ? gridDim.x - 1u - blockIdx.x : blockIdx.x;
   const uint32_t l = A.wg2layer[wg];
   const LayerDesc L = A.layers[l];
   const Place p = place_of(A, L, l, wg);
@@ -205,15 +214,31 @@ __global__ void __launch_bounds__(kBlockThreads) threshold_accumulate_kernel(Thr
   const float thr = kCount ? *as_global(A.thresholds + l) : 0.0f;
   double sum = 0.0;
   float mx = 0.0f;
-  uint32_t cnt = 0u;
-  auto take = [&](const float (&a)[4], uint32_t nvalid, uint32_t) {
+  uint32_t cnt = 0u;                      // kCount: elements above the threshold so far, the same in every lane
+  const gptr<vu2> slot = as_global(reinterpret_cast<vu2*>(A.slots + static_cast<size_t>(p.wc) * A.cap));
+  auto take = [&](const float (&a)[4], uint32_t nvalid, uint32_t idx0) {
+    if constexpr (kCount) {
+      // the elements above the threshold go to the wave-chunk's list in index order (ballot ranks);
+      // a list that is full only counts on, and the emit pass reads that wave-chunk from V instead
+      bool f[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      if (static_cast<uint32_t>(j) < nvalid) {
-        const float mag = fabsf(a[j]);
-        if constexpr (kCount) {
-          cnt += (mag > thr) ? 1u : 0u;
-        } else {
+      for (int j = 0; j < 4; ++j) f[j] = static_cast<uint32_t>(j) < nvalid && fabsf(a[j]) > thr;
+      const unsigned long long m0 = __ballot(f[0]), m1 = __ballot(f[1]), m2 = __ballot(f[2]), m3 = __ballot(f[3]);
+      if ((m0 | m1 | m2 | m3) == 0ull) return;
+      uint32_t pos = cnt + rank_below(m0) + rank_below(m1) + rank_below(m2) + rank_below(m3);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (f[j]) {
+          if (pos < A.cap) slot[pos] = vu2{fbits(a[j]), idx0 + static_cast<uint32_t>(j)};
+          ++pos;
+        }
+      }
+      cnt += popc64(m0) + popc64(m1) + popc64(m2) + popc64(m3);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (static_cast<uint32_t>(j) < nvalid) {
+          const float mag = fabsf(a[j]);
           sum += static_cast<double>(mag);
           mx = fmaxf(mx, mag);
         }
@@ -227,8 +252,10 @@ __global__ void __launch_bounds__(kBlockThreads) threshold_accumulate_kernel(Thr
   else if (!A.nesterov) accumulate_groups<true, false>(L, p.begin, p.end, rule, take);
   else accumulate_groups<true, true>(L, p.begin, p.end, rule, take);
   if constexpr (kCount) {
-    const uint32_t total = wave_total(wave_incl_scan(cnt));
-    if (lane_id() == 0u) A.counts[p.wc] = total;
+    if (lane_id() == 0u) {
+      A.counts[p.wc] = cnt;
+      A.listed[p.wc] = cnt;
+    }
   } else {
     const double s = wave_sum(sum);
     const float m = wave_max(mx);
@@ -280,7 +307,7 @@ __global__ void __launch_bounds__(kBlockThreads) threshold_moments_kernel(Thresh
 template <bool kReverse>
 __global__ void __launch_bounds__(kBlockThreads) threshold_histogram_kernel(ThresholdArgs A) {
   __shared__ uint32_t lds_hist[kSteps];
-  const uint32_t wg = kReverse ? gridDim.x - 1u - blockIdx.x : blockIdx.x;
+  const uint32_t wg = (kReverse != (A.reverse != 0u)) ? gridDim.x - 1u - blockIdx.x : blockIdx.x;
   const uint32_t l = A.wg2layer[wg];
   const LayerDesc L = A.layers[l];
   const Place p = place_of(A, L, l, wg);
@@ -360,7 +387,7 @@ __global__ void __launch_bounds__(kBlockThreads) threshold_search_kernel(Thresho
 // ------------------------------------------------------------------ count, offsets, emit
 template <bool kReverse>
 __global__ void __launch_bounds__(kBlockThreads) threshold_count_kernel(ThresholdArgs A) {
-  const uint32_t wg = kReverse ? gridDim.x - 1u - blockIdx.x : blockIdx.x;
+  const uint32_t wg = (kReverse != (A.reverse != 0u)) ? gridDim.x - 1u - blockIdx.x : blockIdx.x;
   const uint32_t l = A.wg2layer[wg];
   const LayerDesc L = A.layers[l];
   const Place p = place_of(A, L, l, wg);
@@ -407,14 +434,15 @@ __global__ void __launch_bounds__(kBlockThreads) threshold_offsets_kernel(Thresh
   }
 }
 
-template <bool kReverse>
+// kLists: the accumulate pass of this call left the elements above the threshold in the wave-chunk
+// lists; a wave-chunk whose list holds them all is written from it, without another look at V.
+template <bool kReverse, bool kLists>
 __global__ void __launch_bounds__(kBlockThreads) threshold_emit_kernel(ThresholdArgs A) {
-  const uint32_t wg = kReverse ? gridDim.x - 1u - blockIdx.x : blockIdx.x;
+  const uint32_t wg = (kReverse != (A.reverse != 0u)) ? gridDim.x - 1u - blockIdx.x : blockIdx.x;
   const uint32_t l = A.wg2layer[wg];
   const LayerDesc L = A.layers[l];
   const Place p = place_of(A, L, l, wg);
   if (p.begin == p.end) return;
-  const float thr = *as_global(A.thresholds + l);
   const uint32_t cap = 2u * L.k;
   uint32_t out_pos = A.counts[p.wc];
   if (out_pos >= cap) return;                      // the buffer is full: the rest stays in the residual
@@ -423,6 +451,24 @@ __global__ void __launch_bounds__(kBlockThreads) threshold_emit_kernel(Threshold
   const gptr<float> out_val = as_global(L.out_val);
   const gptr<float> resid = as_global(L.resid);
   const gptr<float> mom = as_global(L.mom);
+  if constexpr (kLists) {
+    const uint32_t listed = A.listed[p.wc];
+    if (listed <= A.cap) {
+      const gptr<const vu2> slot = as_global(reinterpret_cast<const vu2*>(A.slots + static_cast<size_t>(p.wc) * A.cap));
+      for (uint32_t i = lane_id(); i < listed; i += kWaveSize) {
+        const uint32_t pos = out_pos + i;
+        if (pos < cap) {
+          const vu2 e = slot[i];
+          out_idx[pos] = static_cast<int32_t>(e.y);
+          out_val[pos] = __uint_as_float(e.x);
+          mask_store(resid + e.y);
+          if (clear_mom) mask_store(mom + e.y);
+        }
+      }
+      return;
+    }
+  }
+  const float thr = *as_global(A.thresholds + l);
   read_groups(L.resid, L.vec_ok != 0u, p.begin, p.end, [&](const float (&a)[4], uint32_t nvalid, uint32_t idx0) {
     bool sel[4];
 #pragma unroll
@@ -436,8 +482,8 @@ __global__ void __launch_bounds__(kBlockThreads) threshold_emit_kernel(Threshold
         if (pos < cap) {
           out_idx[pos] = static_cast<int32_t>(idx0 + j);
           out_val[pos] = a[j];
-          resid[idx0 + j] = 0.0f;
-          if (clear_mom) mom[idx0 + j] = 0.0f;
+          mask_store(resid + idx0 + j);
+          if (clear_mom) mask_store(mom + idx0 + j);
         }
         ++pos;
       }
@@ -450,7 +496,7 @@ hipError_t launch_threshold_compress(const ThresholdArgs& a, uint32_t num_wgs, u
   const dim3 block(kBlockThreads);
 #define RGC_LAUNCHED() do { hipError_t e_ = hipGetLastError(); if (e_ != hipSuccess) return e_; } while (0)
   // Each pass over the tensors runs against the direction of the one before it: what that one touched last
-  // (still in the memory-side cache) is read first.
+  // (still in the memory-side cache) is read first.  a.reverse turns the whole sequence round.
   if (a.search) {
     hipLaunchKernelGGL((threshold_accumulate_kernel<false, false>), dim3(num_wgs), block, 0, s, a);
     RGC_LAUNCHED();
@@ -464,13 +510,13 @@ hipError_t launch_threshold_compress(const ThresholdArgs& a, uint32_t num_wgs, u
     RGC_LAUNCHED();
     hipLaunchKernelGGL(threshold_offsets_kernel, dim3(num_layers), block, 0, s, a);
     RGC_LAUNCHED();
-    hipLaunchKernelGGL(threshold_emit_kernel<true>, dim3(num_wgs), block, 0, s, a);
+    hipLaunchKernelGGL((threshold_emit_kernel<true, false>), dim3(num_wgs), block, 0, s, a);
   } else {
     hipLaunchKernelGGL((threshold_accumulate_kernel<true, false>), dim3(num_wgs), block, 0, s, a);
     RGC_LAUNCHED();
     hipLaunchKernelGGL(threshold_offsets_kernel, dim3(num_layers), block, 0, s, a);
     RGC_LAUNCHED();
-    hipLaunchKernelGGL(threshold_emit_kernel<true>, dim3(num_wgs), block, 0, s, a);
+    hipLaunchKernelGGL((threshold_emit_kernel<true, true>), dim3(num_wgs), block, 0, s, a);
   }
 #undef RGC_LAUNCHED
   return hipGetLastError();
