@@ -39,15 +39,16 @@ extern "C" {
 #define RGC_EINTERNAL (-4) /* a kernel reported an inconsistency (a bug; results invalid)  */
 
 /* ---- flags -------------------------------------------------------------------------- */
-/* rgc_compress_layers */
+/* rgc_compress_layers, rgc_compress_layers_scaled */
 #define RGC_NO_MOMENTUM_MASK 0x1u /* keep the velocity u of sent entries (default clears it) */
 #define RGC_NO_HINTS         0x2u /* ignore and do not update the per-layer speed hints:
                                      every layer takes the hint-free multi-pass path        */
-/* rgc_decompress_accumulate: exactly one of the two */
-#define RGC_NESTEROV         0x4u /* momentum correction in its Nesterov form (see below)      */
-#define RGC_SELECT_LARGEST   0x100u /* the communication-set is the k LARGEST elements (see below)   */
-#define RGC_SELECT_SMALLEST  0x200u /* ... the k SMALLEST elements                                  */
-#define RGC_THRESHOLD_SEARCH 0x400u /* rgc_compress_layers_threshold: search the thresholds (Algorithm 3) */
+#define RGC_NESTEROV         0x4u /* momentum correction in its Nesterov form (see below)    */
+#define RGC_SELECT_LARGEST   0x100u /* the communication-set is the k LARGEST elements (see below) */
+#define RGC_SELECT_SMALLEST  0x200u /* ... the k SMALLEST elements; at most one of the two     */
+/* rgc_compress_layers_threshold: RGC_NO_MOMENTUM_MASK, RGC_NESTEROV and */
+#define RGC_THRESHOLD_SEARCH 0x400u /* search the thresholds (Algorithm 3) instead of reusing them */
+/* rgc_decompress_accumulate: exactly one of the first two */
 #define RGC_OVERWRITE        0x10u /* dense = acc * scale                                   */
 #define RGC_ADD_TO_DST       0x20u /* dense = dense + acc * scale (two roundings, no fma)   */
 #define RGC_ONE_VALUE        0x80u /* with either of the two: every message's val points to ONE float
