@@ -380,7 +380,8 @@ struct alignas(16) FastLds {
   uint8_t qmap[kTile];                       // the row of a colliding position (valid where cb is set)
   uint8_t who[kTile];                        // the worker whose entry reached a position first (valid where seen is set)
 };
-static_assert(sizeof(FastLds) <= 53 * 1024, "three 8-wave workgroups per CU");
+static_assert(sizeof(FastLds) <= 80 * 1024, "two 8-wave workgroups per CU");
+static_assert(kWords % 64u == 0u, "a wave scans the colliding-position bitmap, a whole number of words per lane");
 static_assert(kRows <= 64 && kRows < 256, "one wave adds the rows; row numbers are bytes");
 
 // threadIdx.x behind a veil: what is derived from it is recomputed where it is used instead of
@@ -449,7 +450,7 @@ __device__ __forceinline__ uint32_t quad_lane0(uint32_t v) {
 // the tile is being finished.  There is no per-tile offset table: E starts from a binary search
 // at the first tile of a layer and then advances by what each tile consumes.
 template <bool kStreamMsgs, bool kOneValue>
-__global__ void __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(6, 6)))
+__global__ void __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(4, 4)))
 decompress_tiles_kernel(DecompressArgs A) {
   __shared__ FastLds S;
   const uint32_t tid = threadIdx.x;
@@ -694,11 +695,20 @@ decompress_tiles_kernel(DecompressArgs A) {
         // position (popcount prefix over the bitmap; every wave computes the same prefix and writes
         // it, so it may read it back at once)
         {
+          constexpr uint32_t kPerLane = kWords / 64u;     // words of the bitmap a lane takes
           const uint32_t ln = fresh_tid() & 63u;
-          const vu2l cw = *reinterpret_cast<const vu2l*>(&cb[2u * ln]);
-          const uint32_t c0 = static_cast<uint32_t>(__popc(cw.x)), c1 = static_cast<uint32_t>(__popc(cw.y));
-          const uint32_t incl = wave_incl_scan(c0 + c1);
-          *reinterpret_cast<vu2l*>(&S.pre_cb[2u * ln]) = vu2l{incl - c0 - c1, incl - c1};
+          uint32_t c[kPerLane], total = 0u;
+#pragma unroll
+          for (uint32_t i = 0; i < kPerLane; ++i) {
+            c[i] = static_cast<uint32_t>(__popc(cb[kPerLane * ln + i]));
+            total += c[i];
+          }
+          uint32_t run = wave_incl_scan(total) - total;
+#pragma unroll
+          for (uint32_t i = 0; i < kPerLane; ++i) {
+            S.pre_cb[kPerLane * ln + i] = run;
+            run += c[i];
+          }
         }
         const uint32_t my_slot = fresh_tid() >> 2;   // = wl
         for (uint32_t d0 = 0; d0 < nq; d0 += kRows) {

@@ -140,7 +140,7 @@ struct ThresholdArgs {
 hipError_t launch_threshold_compress(const ThresholdArgs& a, uint32_t num_wgs, uint32_t num_layers, hipStream_t s);
 
 // ---------------------------------------------------------------- decompress
-constexpr int kTileShift = 12;
+constexpr int kTileShift = 13;
 constexpr int kTile = 1 << kTileShift;            // dense positions owned by one workgroup
 constexpr int kEntryCap = 1024;                   // entries staged per worker batch (generic tiles)
 constexpr int kBatchWorkers = 128;                // workers per batch (mask of 4 words)
