@@ -69,8 +69,8 @@ __device__ __forceinline__ TileGeom tile_geom(const DecompressLayer& L, uint32_t
 // The tiles of workgroup `wg` of a persistent grid: t_first, t_first + stride, ... < t_last.
 // Workgroups are dealt to the 8 XCDs round-robin by index.  Every XCD gets one contiguous range
 // of tiles, and the workgroups of an XCD take its tiles round-robin, so at any moment they work on
-// neighbouring tiles: one 128-byte line of a message holds the entries of about 8 tiles, is
-// fetched from HBM once and is then found in that XCD's L2 by the 7 other workgroups that need it
+// neighbouring tiles: one 128-byte line of a message holds the entries of about 4 tiles, is
+// fetched from HBM once and is then found in that XCD's L2 by the other workgroups that need it
 // (a blocked assignment makes the concurrent working set of an XCD as large as its L2 and fetches
 // every line 8 times).
 __device__ __forceinline__ void tiles_of_workgroup(uint32_t num_tiles, uint32_t& t_first, uint32_t& t_last,

@@ -140,6 +140,8 @@ struct ThresholdArgs {
 hipError_t launch_threshold_compress(const ThresholdArgs& a, uint32_t num_wgs, uint32_t num_layers, hipStream_t s);
 
 // ---------------------------------------------------------------- decompress
+// 8192 positions: most of a tile's instructions (window checks, map clearing, barriers) are paid per tile,
+// not per position; 4096 was 28 % slower, 16384 leaves room for one workgroup per CU only and is slower too.
 constexpr int kTileShift = 13;
 constexpr int kTile = 1 << kTileShift;            // dense positions owned by one workgroup
 constexpr int kEntryCap = 1024;                   // entries staged per worker batch (generic tiles)
