@@ -87,7 +87,7 @@ typedef struct {
 
 /* Create a context on HIP device `device_id` able to handle calls whose layers hold at most
  * `max_total_elems` elements in total, in at most `max_layers` layers.  Allocates all scratch
- * once (about 0.26 byte per element plus 80 KiB per layer); later compression calls allocate
+ * once (about 0.51 byte per element plus 80 KiB per layer); later compression calls allocate
  * device memory only when they see a layer list (pointers, sizes) not seen recently.
  * Decompression grows its own tables on first use and when a call needs more.
  * Errors: RGC_EINVAL (null out, sizes < 1), RGC_ENOMEM, RGC_EHIP. */
