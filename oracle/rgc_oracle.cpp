@@ -48,17 +48,16 @@
 //   * Alternating Signs Quantization (Section 2.2, "Quantization of Sparsified
 //     Residuals"): in one iteration the communication-set is the k largest
 //     elements of the layer, in the next the k smallest, and one average is
-//     sent in place of the k values.  The paper takes the k largest to be all
-//     positive (the k smallest all negative) and says nothing else; read here
-//     as: elements that do not carry the iteration's sign bit (and zeros) all
-//     rank last and equal, i.e. the selection key is the magnitude key of the
-//     elements with the iteration's sign and 0 for all others, ties to the
-//     lowest index as everywhere; the message lists the k indices ascending
+//     sent in place of the k values.  "Largest" and "smallest" are taken as
+//     they read: by value, sign included (the paper expects the k largest to
+//     be positive; a layer with fewer than k positive elements goes on with
+//     its zeros and then its negative elements closest to zero), equal values
+//     to the lowest index as everywhere, +0 and -0 being equal values; NaNs
+//     rank by their bit pattern like the other keys here (sign bit clear: above
+//     +Inf, set: below -Inf).  The message lists the k indices ascending
 //     and the mean of the k accumulated values, summed in index order in fp64,
 //     divided by k in fp64 and rounded to fp32 once; the sent entries leave
-//     the residual (and the velocity) exactly as in Algorithm 1.  A layer with
-//     fewer than k elements of the sign thus completes its set with the
-//     lowest-index other elements, whose values enter the mean as they are.
+//     the residual (and the velocity) exactly as in Algorithm 1.
 //     Decompression adds the message's one value at each of its indices.
 //   * threshold binary search selection (Section 2.1, Algorithm 3): the
 //     communication-set is every element whose magnitude exceeds a threshold,
@@ -198,12 +197,14 @@ int rgc_oracle_compress_layer(const float* grad, float* residual, float* momentu
                                       out_idx, out_val, out_count);
 }
 
-// Selection key of Alternating Signs Quantization: sign = +1 keeps the elements
-// whose sign bit is clear, sign = -1 those whose sign bit is set.
+// Selection key of Alternating Signs Quantization: an unsigned integer that
+// grows with the value of x (sign = +1) or of -x (sign = -1); both zeros map
+// to the same key.
 inline uint32_t asq_key(float x, int sign) {
-  const uint32_t b = float_bits(x);
-  const bool negative = (b >> 31) != 0u;
-  return (negative == (sign < 0)) ? (b & 0x7FFFFFFFu) : 0u;
+  uint32_t b = float_bits(x);
+  if (sign < 0) b ^= 0x80000000u;               // -x
+  if ((b & 0x7FFFFFFFu) == 0u) b = 0u;          // -0 and +0 are the same value
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
 // One layer of the compression step with Alternating Signs Quantization (see

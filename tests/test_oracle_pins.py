@@ -420,20 +420,34 @@ def _exact_mean_f32(values):
     return _round_to_f32(total / len(values))
 
 
-def test_asq_equals_signed_top_k_when_enough_elements_have_the_sign(oracle):
-    """Section 2.2: the k largest elements in one iteration, the k smallest in the next; with at
-    least k positive (negative) elements that is the plain signed order, here from a library sort."""
+@pytest.mark.parametrize("law", ["normal", "mostly_zero", "few_positive", "ties"])
+def test_asq_equals_a_library_sort_by_value(oracle, law):
+    """Section 2.2: the k largest elements in one iteration, the k smallest in the next: the plain order by
+    value (equal values to the lowest index), here from a stable library sort, also where fewer than k
+    elements have the expected sign."""
     g = np.random.default_rng(71)
     n, k = 5000, 37
     G = g.standard_normal(n).astype(np.float32)
     V = g.standard_normal(n).astype(np.float32)
+    if law == "mostly_zero":
+        keep = g.random(n) < 0.004                       # about 20 nonzero elements, ten of either sign
+        G = np.where(keep, G, 0).astype(np.float32)
+        V = np.where(keep, V, -0.0).astype(np.float32)
+    elif law == "few_positive":
+        V = -np.abs(V)
+        G = -np.abs(G)
+        V[::500] = 7.0                                   # ten positive elements
+    elif law == "ties":
+        G = np.round(G).astype(np.float32)
+        V = np.round(V).astype(np.float32)
     a = V + G
     for sign in (+1, -1):
         v = V.copy()
         idx, mean, cnt = oracle.compress_layer_asq(G, v, k, sign)
         order = np.argsort(-a if sign > 0 else a, kind="stable")[:k]       # largest / smallest k, ties to the lowest index
         assert cnt == k and np.array_equal(idx, np.sort(order).astype(np.int32))
-        assert np.all(a[idx] > 0) if sign > 0 else np.all(a[idx] < 0), "all of one sign"
+        if law == "normal":
+            assert np.all(a[idx] > 0) if sign > 0 else np.all(a[idx] < 0), "all of one sign"
         assert mean == _exact_mean_f32(a[idx]), "the one value of the message is the mean of the set"
         sel = np.zeros(n, bool)
         sel[idx] = True
@@ -458,20 +472,26 @@ def test_asq_sort_equals_bruteforce_on_tiny_inputs(oracle, seed):
         assert np.array_equal(v1.view(np.uint32), v2.view(np.uint32))
 
 
-def test_asq_python_loop_independent_of_cpp(oracle):
-    """The reading for layers short of elements of the sign: the others rank last and equal (lowest index first)."""
+def test_asq_hand_case_short_of_a_sign(oracle):
+    """A layer with fewer than k elements of the expected sign goes on by value: zeros (both kinds equal, lowest
+    index first), then the elements of the other sign that are closest to zero."""
     a = np.array([-1.0, 0.0, 3.0, -0.0, -2.0, 1.0, -5.0], np.float32)
     G = np.zeros_like(a)
-    # largest 4: the two positives (3, 1), then the lowest-index others: indices 0 and 1
+    # largest 4: 3, 1, then the two zeros; largest 5: and -1
     idx, mean, cnt = oracle.compress_layer_asq(G, a.copy(), 4, +1)
-    assert idx.tolist() == [0, 1, 2, 5]
-    assert mean == np.float32((-1.0 + 0.0 + 3.0 + 1.0) / 4)
-    # smallest 2: -5 and -2; smallest 4: all three negatives and -0 (its sign bit is set, its magnitude key is 0:
-    # it ties with the non-negatives at rank zero, and index 1 comes before index 3)
+    assert idx.tolist() == [1, 2, 3, 5] and mean == np.float32(1.0)
+    idx, mean, cnt = oracle.compress_layer_asq(G, a.copy(), 5, +1)
+    assert idx.tolist() == [0, 1, 2, 3, 5] and mean == np.float32(3.0 / 5)
+    # largest 3: one of the two equal zeros, the one with the lower index
+    idx, mean, cnt = oracle.compress_layer_asq(G, a.copy(), 3, +1)
+    assert idx.tolist() == [1, 2, 5]
+    # smallest 2: -5 and -2; smallest 4: the three negatives and the first zero; smallest 6: all but 3
     idx, mean, cnt = oracle.compress_layer_asq(G, a.copy(), 2, -1)
     assert idx.tolist() == [4, 6] and mean == np.float32(-3.5)
     idx, mean, cnt = oracle.compress_layer_asq(G, a.copy(), 4, -1)
     assert idx.tolist() == [0, 1, 4, 6]
+    idx, mean, cnt = oracle.compress_layer_asq(G, a.copy(), 6, -1)
+    assert idx.tolist() == [0, 1, 3, 4, 5, 6]
 
 
 def test_asq_all_positive_layer_equals_magnitude_selection(oracle):
