@@ -131,12 +131,14 @@ int rgc_compress_layers_scaled(rgc_ctx* ctx, const rgc_layer* layers, int32_t nu
  * is its k largest elements, in the next its k smallest, and the message carries the k indices and
  * ONE value, the average of the k elements.  Here it is three pieces:
  *  - selection: rgc_compress_layers(_scaled) with RGC_SELECT_LARGEST or RGC_SELECT_SMALLEST (the
- *    caller alternates them).  The elements that carry the iteration's sign bit (clear / set) rank
- *    by magnitude, all other elements rank last and equal, ties to the lowest index as always; so
- *    with at least k elements of that sign the set is the k largest (smallest) of the layer, and a
- *    layer short of them completes its set with the lowest-index other elements.  Everything else
- *    (indices ascending, out_val = the k accumulated values, masking of residual and velocity) is
- *    as in the plain call.  The speed hints of the three selection modes are kept apart.
+ *    caller alternates them): the k largest (smallest) elements of the accumulated tensor BY VALUE,
+ *    sign included, equal values to the lowest index, +0 and -0 being equal; the paper expects
+ *    them to be all positive (negative), and a layer with fewer than k such elements goes on with
+ *    its zeros and then the elements of the other sign closest to zero.  NaNs rank by bit pattern
+ *    (sign bit clear: above +Inf; set: below -Inf).  Everything else (indices ascending, out_val =
+ *    the k accumulated values, masking of residual and velocity) is as in the plain call.  The
+ *    speed hints of the three selection modes are kept apart; a layer short of elements of the
+ *    expected sign has none and takes the multi-pass path on every call.
  *  - rgc_message_means: means[l] = average of layer l's out_val[0 .. *out_count), summed in fp64 in
  *    a fixed order and rounded to fp32 once; `means` is DEVICE memory, num_layers floats.  The
  *    message of layer l is then (count, out_idx, means[l]); layers the caller does not want

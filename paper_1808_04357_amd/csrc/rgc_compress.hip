@@ -52,6 +52,23 @@ __device__ __forceinline__ uint32_t key_of(uint32_t bits, uint32_t sign_xor, uin
   return static_cast<uint32_t>(t > 0 ? t : 0);
 }
 
+// The key of the multi-pass selection.  Plain top-k: the magnitude key (31 bits).  Alternating Signs
+// Quantization: a 32-bit key that grows with the value of the element (largest) or of its negative
+// (smallest), both zeros being one value: the order "by value" that Section 2.2 words, also for a layer
+// with fewer than k elements of the expected sign (its zeros come next, then the elements of the other
+// sign closest to zero).  For the elements that key_of() ranks (expected sign, not zero) the two keys
+// agree up to the top bit: ordered = key_of | 0x80000000; every other element lies below 0x80000000.
+__device__ __forceinline__ uint32_t ordered_key(uint32_t bits, uint32_t sign_xor, uint32_t sign_filter) {
+  if (sign_filter == 0u) return bits & kKeyMask;
+  uint32_t b = bits ^ sign_xor;
+  b = (b & kKeyMask) == 0u ? 0u : b;
+  const uint32_t neg = static_cast<uint32_t>(static_cast<int32_t>(b) >> 31);
+  return b ^ (neg | 0x80000000u);
+}
+
+// Digits of the multi-pass key: 12 + 12 + low bits, low = 7 (31-bit magnitude key) or 8 (32-bit ordered key).
+__device__ __forceinline__ uint32_t low_bits_of(uint32_t sign_filter) { return sign_filter ? 8u : 7u; }
+
 __device__ __forceinline__ uint32_t coarse_bin(uint32_t key, uint32_t tau, uint32_t shift) {
   const uint32_t b = (key - tau) >> shift;
   return b < static_cast<uint32_t>(kCoarseBins - 1) ? b : static_cast<uint32_t>(kCoarseBins - 1);
@@ -90,14 +107,20 @@ __device__ __forceinline__ void consume(const float (&a)[4], uint32_t nvalid, ui
       c.count += popc64(m0) + popc64(m1) + popc64(m2) + popc64(m3);
     }
   } else {
+    const uint32_t sh1 = low_bits_of(c.sign_filter) + 12u;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       if (static_cast<uint32_t>(j) < nvalid) {
-        if (key[j] != 0u) atomicAdd(&lds_hist[key[j] >> 19], 1u);
-        else ++zeros;
+        if ((bits[j] & kKeyMask) != 0u) atomicAdd(&lds_hist[ordered_key(bits[j], c.sign_xor, c.sign_filter) >> sh1], 1u);
+        else ++zeros;            // the zeros of a sparse tensor would all hit one bin: counted in a register
       }
     }
   }
+}
+
+// The first-digit bin of the value zero (where the zeros counted in registers are added).
+__device__ __forceinline__ uint32_t zero_bin(uint32_t sign_xor, uint32_t sign_filter) {
+  return ordered_key(0u, sign_xor, sign_filter) >> (low_bits_of(sign_filter) + 12u);
 }
 
 // Streaming pass over one wave-chunk [begin, end) of a layer.
@@ -181,7 +204,7 @@ __device__ __forceinline__ void stream_chunk(const LayerDesc& L, uint32_t begin,
     consume<kCollect>(a, nvalid, idx0, c, lds_hist, zeros);
   }
   if constexpr (!kCollect) {
-    if (zeros) atomicAdd(&lds_hist[0], zeros);
+    if (zeros) atomicAdd(&lds_hist[zero_bin(c.sign_xor, c.sign_filter)], zeros);
   }
 }
 
@@ -327,7 +350,8 @@ __device__ uint32_t locate_from_top(const uint32_t* lds, uint32_t bins, uint32_t
 template <int kLevel>
 __device__ void resolve_digit(const CompressArgs& A, uint32_t l, const LayerDesc& L, LayerState* st,
                               ResolveShared& sh, uint32_t* lds, uint32_t cur_launch) {
-  constexpr uint32_t kBins = (kLevel == 3) ? 128u : static_cast<uint32_t>(kHistBins);
+  constexpr uint32_t kBins = (kLevel == 3) ? 256u : static_cast<uint32_t>(kHistBins);   // the last digit has 7 or 8 bits
+  const uint32_t low = low_bits_of(A.sign_filter);
   const uint32_t k_rem = (kLevel == 1) ? L.k : st->k_rem;
   const uint32_t above_scope = L.k - k_rem;          // keys above the current scope
   // The k entries selected now leave the residual, so the next call's top-k come from ranks
@@ -342,9 +366,9 @@ __device__ void resolve_digit(const CompressArgs& A, uint32_t l, const LayerDesc
     const uint32_t D = sh.bin;
     const uint32_t hcum = above_scope + sh.hcum;
     auto edge = [&](uint32_t b) -> uint32_t {
-      if (kLevel == 1) return b << 19;
-      if (kLevel == 2) return (prefix << 19) | (b << 7);
-      return (prefix << 7) | b;
+      if (kLevel == 1) return b << (low + 12u);
+      if (kLevel == 2) return (prefix << (low + 12u)) | (b << low);
+      return (prefix << low) | b;
     };
     // ---- hint derivation (speed only)
     uint32_t pend = pending;
@@ -368,21 +392,32 @@ __device__ void resolve_digit(const CompressArgs& A, uint32_t l, const LayerDesc
       st->prefix = (prefix << 12) | D;
       st->next_phase = PH_HIST3;
     } else {
-      const uint32_t T = (prefix << 7) | D;
+      const uint32_t T = (prefix << low) | D;
       st->T = T;
       st->r = new_rem;
       st->next_phase = PH_COUNT;
       if (A.update_hints) {
-        if (pend == 2u) {
-          const uint32_t tn = st->tau_next;
-          st->tau = drifted_tau(tn, T, st->T_prev, A.use_hints && st->has_prev);
-          st->shift = shift_for(T, tn);
+        // The hints live in the key space of the one-pass path (key_of).  With the ordered key a hint
+        // exists only if the k-th key and the threshold aimed at both lie among the elements key_of()
+        // ranks (top bit set); a layer short of such elements has none and stays on this path.
+        uint32_t Th = T, tn = st->tau_next;
+        bool usable = (pend == 2u);
+        if (A.sign_filter) {
+          usable = usable && T > 0x80000000u && tn >= 0x80000000u;
+          Th = T & kKeyMask;
+          tn = (tn & kKeyMask) ? (tn & kKeyMask) : 1u;
+        }
+        if (usable) {
+          st->tau = drifted_tau(tn, Th, st->T_prev, A.use_hints && st->has_prev);
+          st->shift = shift_for(Th, tn);
           st->hint_valid = 1u;
+          st->T_prev = Th;
+          st->has_prev = 1u;
         } else {
           st->hint_valid = 0u;
+          st->has_prev = A.sign_filter ? 0u : 1u;
+          st->T_prev = Th;
         }
-        st->T_prev = T;
-        st->has_prev = 1u;
       }
     }
     st->hint_pending = pend;
@@ -600,7 +635,8 @@ __global__ void __launch_bounds__(kBlockThreads) accumulate_kernel(CompressArgs 
   const uint32_t l = A.wg2layer[wg];
   const LayerDesc L = A.layers[l];
   LayerState* st = A.state + l;
-  const bool collect = A.use_hints && L.hintable && (st->hint_valid != 0u);
+  // (with a sign filter a threshold of 0 would let the elements that key_of() ranks last and equal into the lists)
+  const bool collect = A.use_hints && L.hintable && (st->hint_valid != 0u) && !(A.sign_filter != 0u && st->tau == 0u);
   // the same LDS array serves as 4096-bin digit histogram (hint-free) or 1024-bin coarse one
   const uint32_t lds_bins = collect ? static_cast<uint32_t>(kCoarseBins) : static_cast<uint32_t>(kHistBins);
   for (uint32_t b = threadIdx.x; b < lds_bins; b += kBlockThreads) lds_hist[b] = 0u;
@@ -659,10 +695,11 @@ namespace {
 template <int kLevel>
 __device__ void phase_hist(const CompressArgs& A, uint32_t l, const LayerDesc& L, LayerState* st, uint32_t wg,
                            uint32_t wc_local, uint32_t* lds_hist, ResolveShared& sh) {
-  constexpr uint32_t kBins = (kLevel == 3) ? 128u : static_cast<uint32_t>(kHistBins);
+  constexpr uint32_t kBins = (kLevel == 3) ? 256u : static_cast<uint32_t>(kHistBins);
   for (uint32_t b = threadIdx.x; b < kBins; b += kBlockThreads) lds_hist[b] = 0u;
   __syncthreads();
   const uint32_t prefix = st->prefix;
+  const uint32_t low = low_bits_of(A.sign_filter), low_mask = (1u << low) - 1u;
   if (wc_local < L.wc_count) {
     const uint32_t begin = wc_local * A.chunk;
     const uint32_t end = (L.n - begin) < A.chunk ? L.n : begin + A.chunk;
@@ -672,19 +709,20 @@ __device__ void phase_hist(const CompressArgs& A, uint32_t l, const LayerDesc& L
 #pragma unroll
                      for (int j = 0; j < 4; ++j) {
                        if (static_cast<uint32_t>(j) < nvalid) {
-                         const uint32_t key = key_of(fbits(a[j]), A.sign_xor, A.sign_filter);
+                         const uint32_t bits = fbits(a[j]);
+                         const uint32_t key = ordered_key(bits, A.sign_xor, A.sign_filter);
                          if (kLevel == 1) {
-                           if (key != 0u) atomicAdd(&lds_hist[key >> 19], 1u);
+                           if ((bits & kKeyMask) != 0u) atomicAdd(&lds_hist[key >> (low + 12u)], 1u);
                            else ++zeros;
                          } else if (kLevel == 2) {
-                           if ((key >> 19) == prefix) atomicAdd(&lds_hist[(key >> 7) & 0xFFFu], 1u);
+                           if ((key >> (low + 12u)) == prefix) atomicAdd(&lds_hist[(key >> low) & 0xFFFu], 1u);
                          } else {
-                           if ((key >> 7) == prefix) atomicAdd(&lds_hist[key & 0x7Fu], 1u);
+                           if ((key >> low) == prefix) atomicAdd(&lds_hist[key & low_mask], 1u);
                          }
                        }
                      }
                    });
-    if (kLevel == 1 && zeros) atomicAdd(&lds_hist[0], zeros);
+    if (kLevel == 1 && zeros) atomicAdd(&lds_hist[zero_bin(A.sign_xor, A.sign_filter)], zeros);
   }
   __syncthreads();
   flush_hist(lds_hist, A.hist + static_cast<size_t>(l) * kHistBins, kBins);
@@ -703,7 +741,7 @@ __device__ void phase_count(const CompressArgs& A, uint32_t l, const LayerDesc& 
 #pragma unroll
                      for (int j = 0; j < 4; ++j) {
                        if (static_cast<uint32_t>(j) < nvalid) {
-                         const uint32_t key = key_of(fbits(a[j]), A.sign_xor, A.sign_filter);
+                         const uint32_t key = ordered_key(fbits(a[j]), A.sign_xor, A.sign_filter);
                          gt += (key > T) ? 1u : 0u;
                          eq += (key == T) ? 1u : 0u;
                        }
@@ -744,7 +782,7 @@ __device__ void phase_out_v(const CompressArgs& A, const LayerDesc& L, LayerStat
                    bool gt[4], eq[4];
 #pragma unroll
                    for (int j = 0; j < 4; ++j) {
-                     const uint32_t key = key_of(fbits(a[j]), A.sign_xor, A.sign_filter);
+                     const uint32_t key = ordered_key(fbits(a[j]), A.sign_xor, A.sign_filter);
                      const bool valid = static_cast<uint32_t>(j) < nvalid;
                      gt[j] = valid && key > T;
                      eq[j] = valid && key == T;
@@ -1026,7 +1064,7 @@ __global__ void __launch_bounds__(kBlockThreads) phase_kernel(CompressArgs A) {
 // workgroups fit on the device at once, so the launches that find nothing to do are over sooner.
 constexpr uint32_t kFirstLateLaunch = 4;
 __global__ void __launch_bounds__(kBlockThreads) phase_late_kernel(CompressArgs A) {
-  __shared__ uint32_t hist[128];
+  __shared__ uint32_t hist[256];   // the last digit: 7 or 8 bits
   __shared__ ResolveShared sh;
   const uint32_t wg = phase_workgroup(A);
   const uint32_t l = A.wg2layer[wg];

@@ -80,8 +80,8 @@ def test_selection_with_momentum_correction(rgc, oracle):
 
 
 def test_layers_short_of_one_sign(rgc, oracle):
-    """All-positive, all-negative, all-zero and nearly-all-zero layers: the set is completed with the
-    lowest-index other elements (the reading the oracle states), the same on both sides."""
+    """All-positive, all-negative, all-zero and nearly-all-zero layers: the set goes on by value (zeros, then
+    the elements of the other sign closest to zero), the same on both sides."""
     g = np.random.default_rng(83)
     n = 30_000
     V = [np.abs(g.standard_normal(n)).astype(np.float32),
