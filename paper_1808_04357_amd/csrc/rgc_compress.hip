@@ -388,6 +388,20 @@ __device__ void resolve_digit(const CompressArgs& A, uint32_t l, const LayerDesc
     if (kLevel == 1) {
       st->prefix = D;
       st->next_phase = PH_HIST2;
+      // A hint-free call needs no further digits if the keys from the first digit's bin upwards fit the
+      // candidate lists: one more pass over the residual collects them (threshold = the bin's lower edge,
+      // so at least k of them exist) and the call ends like a hinted one (PH_SEL, PH_OUT_C): two passes
+      // less.  Only straight after the streaming pass (a call that already lost a launch to a missed hint
+      // has too few launches left for the fall-back should a list overflow), and not for callers who asked
+      // for the hints to be left alone (the collection uses the hint's fields).
+      const uint32_t lower = edge(D);
+      const bool in_key_space = A.sign_filter == 0u || lower > 0x80000000u;   // see ordered_key / key_of
+      if (cur_launch == 1u && A.update_hints && L.hintable && in_key_space && sh.above + sh.cnt <= L.cmax) {
+        const uint32_t tau = (lower & kKeyMask) ? (lower & kKeyMask) : 1u;
+        st->tau = tau;
+        st->shift = shift_for(tau + ((1u << (low + 12u)) - 1u), tau);
+        st->next_phase = PH_COLLECT;
+      }
     } else if (kLevel == 2) {
       st->prefix = (prefix << 12) | D;
       st->next_phase = PH_HIST3;
@@ -428,8 +442,10 @@ __device__ void resolve_digit(const CompressArgs& A, uint32_t l, const LayerDesc
 // Hinted path, end of the streaming pass: validate the candidate lists, locate the coarse bin
 // holding the k-th key, clear the coarse histogram, schedule PH_SEL or fall back.
 // `lds` holds >= kCoarseBins words and is free for use.
+// `after_first_digit`: the lists come from PH_COLLECT of a hint-free call rather than from the streaming pass
+// of a hinted one; should they not do, the call goes on with the second digit.
 __device__ void resolve_collect(const CompressArgs& A, uint32_t l, const LayerDesc& L, LayerState* st,
-                                ResolveShared& sh, uint32_t* lds) {
+                                ResolveShared& sh, uint32_t* lds, bool after_first_digit, uint32_t cur_launch) {
   const uint32_t t = threadIdx.x;
   uint32_t total = 0, bad = 0;
   for (uint32_t c0 = 0; c0 < L.wc_count; c0 += 8u * kBlockThreads) {
@@ -464,7 +480,7 @@ __device__ void resolve_collect(const CompressArgs& A, uint32_t l, const LayerDe
       st->bstar = sh.bin;
       st->k_rem = k - sh.above;
       st->nmembers = 0u;
-      st->path = 0u;
+      if (!after_first_digit) st->path = 0u;
       st->next_phase = PH_SEL;
       unsigned long long tn;
       if (sh.hbin != 0xFFFFFFFFu) {
@@ -481,12 +497,14 @@ __device__ void resolve_collect(const CompressArgs& A, uint32_t l, const LayerDe
         tn = delta < tau ? tau - delta : 0ull;
       }
       st->tau_next = static_cast<uint32_t>(tn);
+    } else if (after_first_digit) {
+      st->next_phase = PH_HIST2;          // prefix and k_rem are still those of the first digit
     } else {
       st->path = 2u;
       st->stat_misses += 1u;
       st->next_phase = PH_HIST1;
     }
-    st->next_launch = 2u;
+    st->next_launch = cur_launch + 1u;
   }
 }
 
@@ -681,7 +699,7 @@ __global__ void __launch_bounds__(kBlockThreads) accumulate_kernel(CompressArgs 
   }
   if (last_block_of_layer(&st->done, A.group_done + L.grp_first, wg - L.wg_first, L.wg_count, &sh.flag)) {
     if (collect) {
-      resolve_collect(A, l, L, st, sh, lds_hist);
+      resolve_collect(A, l, L, st, sh, lds_hist, false, 1u);
     } else {
       if (threadIdx.x == 0) { st->path = 1u; st->stat_candidates = 0u; st->stat_members = 0u; }
       resolve_digit<1>(A, l, L, st, sh, lds_hist, 1u);
@@ -727,6 +745,37 @@ __device__ void phase_hist(const CompressArgs& A, uint32_t l, const LayerDesc& L
   __syncthreads();
   flush_hist(lds_hist, A.hist + static_cast<size_t>(l) * kHistBins, kBins);
   if (last_block_of_layer(&st->done, A.group_done + L.grp_first, wg - L.wg_first, L.wg_count, &sh.flag)) resolve_digit<kLevel>(A, l, L, st, sh, lds_hist, A.launch);
+}
+
+// PH_COLLECT: the streaming pass's candidate collection, from the updated residual (see resolve_digit<1>).
+__device__ void phase_collect(const CompressArgs& A, uint32_t l, const LayerDesc& L, LayerState* st, uint32_t wg,
+                              uint32_t wc_local, uint32_t* lds_hist, ResolveShared& sh) {
+  for (uint32_t b = threadIdx.x; b < static_cast<uint32_t>(kCoarseBins); b += kBlockThreads) lds_hist[b] = 0u;
+  __syncthreads();
+  if (wc_local < L.wc_count) {
+    const uint32_t begin = wc_local * A.chunk;
+    const uint32_t end = (L.n - begin) < A.chunk ? L.n : begin + A.chunk;
+    Collector c;
+    c.slot = as_global(reinterpret_cast<vu2*>(A.slots + static_cast<size_t>(L.wc_first + wc_local) * A.cap));
+    c.coarse = lds_hist;
+    c.cap = A.cap;
+    c.count = 0;
+    c.tau = st->tau;
+    c.shift = st->shift;
+    c.sign_xor = A.sign_xor;
+    c.sign_filter = A.sign_filter;
+    uint32_t zeros = 0;
+    for_each_group(L.resid, L.vec_ok != 0u, begin, end,
+                   [&](const float (&a)[4], uint32_t nvalid, uint32_t idx0) {
+                     consume<true>(a, nvalid, idx0, c, lds_hist, zeros);
+                   });
+    if (lane_id() == 0) st_agent(&A.cand_cnt[L.wc_first + wc_local], c.count);
+  }
+  __syncthreads();
+  flush_hist(lds_hist, A.coarse + (static_cast<size_t>(l) * kCoarseRep + (wg & (kCoarseRep - 1))) * kCoarseBins,
+             kCoarseBins);
+  if (last_block_of_layer(&st->done, A.group_done + L.grp_first, wg - L.wg_first, L.wg_count, &sh.flag))
+    resolve_collect(A, l, L, st, sh, lds_hist, true, A.launch);
 }
 
 __device__ void phase_count(const CompressArgs& A, uint32_t l, const LayerDesc& L, LayerState* st, uint32_t wg,
@@ -956,6 +1005,7 @@ __device__ void phase_sel(const CompressArgs& A, uint32_t l, const LayerDesc& L,
       const uint32_t tn = st->tau_next <= T ? st->tau_next : T;
       st->tau = drifted_tau(tn, T, st->T_prev, st->has_prev != 0u);
       st->shift = shift_for(T, tn);
+      st->hint_valid = 1u;               // (a hint-free call that collected after its first digit gets its hint here)
       st->T_prev = T;
       st->has_prev = 1u;
     }
@@ -1054,12 +1104,14 @@ __global__ void __launch_bounds__(kBlockThreads) phase_kernel(CompressArgs A) {
     case PH_HIST3: phase_hist<3>(A, l, L, st, wg, wc_local, sm.hist, sh); break;
     case PH_COUNT: phase_count(A, l, L, st, wg, wc_local, sh); break;
     case PH_OUT_V: phase_out_v(A, L, st, wc_local); break;
+    case PH_COLLECT: phase_collect(A, l, L, st, wg, wc_local, sm.hist, sh); break;
     default: break;
   }
 }
 
 // Launches 4..6 can only meet the last three phases of the multi-pass path (a layer that missed
-// its hint is at PH_HIST3 in launch 4 at the earliest), and in steady state they meet nothing at
+// its hint is at PH_HIST3 in launch 4 at the earliest) or the output phase of a hint-free call that
+// collected its candidates in launch 2, and in steady state they meet nothing at
 // all.  They get a kernel of their own that needs next to no LDS: twice as many of its
 // workgroups fit on the device at once, so the launches that find nothing to do are over sooner.
 constexpr uint32_t kFirstLateLaunch = 4;
@@ -1076,6 +1128,7 @@ __global__ void __launch_bounds__(kBlockThreads) phase_late_kernel(CompressArgs 
     case PH_HIST3: phase_hist<3>(A, l, L, st, wg, wc_local, hist, sh); break;
     case PH_COUNT: phase_count(A, l, L, st, wg, wc_local, sh); break;
     case PH_OUT_V: phase_out_v(A, L, st, wc_local); break;
+    case PH_OUT_C: phase_out_c(A, L, st, wg); break;                  // a hint-free call that collected after its first digit
     default: if (threadIdx.x == 0) atomicOr(A.errflag, 16u); break;   // no other phase can be due this late
   }
 }

@@ -28,6 +28,7 @@ enum Phase : uint32_t {
   PH_HIST3 = 5,    // multi-pass: digit-3 histogram
   PH_COUNT = 6,    // multi-pass: per wave-chunk counts of keys > T and == T
   PH_OUT_V = 7,    // multi-pass: ordered compaction from the updated residual
+  PH_COLLECT = 8,  // after the first digit: candidate lists from the updated residual, then PH_SEL / PH_OUT_C
 };
 
 // Per call, per layer descriptor (device copy of the caller's rgc_layer plus the tiling).
