@@ -68,6 +68,10 @@ def load_library() -> ctypes.CDLL:
     if not os.path.exists(_LIB_PATH):
         raise RuntimeError("librgc.so is not built: run `python -m paper_1808_04357_amd.build` "
                            "(or __graft_entry__.build()) first; there is no CPU fallback")
+    # The tensors handed to the library are PyTorch's, so both must talk to ONE HIP runtime: PyTorch's
+    # wheel brings its own libamdhip64.so.7, and whichever copy of that soname is mapped first serves the
+    # whole process.  Loaded before torch, librgc.so would bind to the system copy and see no device.
+    import torch  # noqa: F401
     L = ctypes.CDLL(_LIB_PATH)
     L.rgc_create.restype = ctypes.c_int
     L.rgc_create.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_int64, ctypes.c_int32]
