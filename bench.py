@@ -36,13 +36,13 @@ def upload(torch, arrays, dev):
 
 
 class CompressWorkload:
-    def __init__(self, torch, rgc, cfg, dev):
+    def __init__(self, torch, rgc, cfg, dev, ppm=1000):
         self.torch, self.rgc = torch, rgc
         self.name = cfg["name"]
         self.m = float(cfg["momentum"])
         self.sizes = [int(v.size) for v in cfg["V"]]
         self.total = sum(self.sizes)
-        self.ks = [rgc.rgc_k_for_density(n) for n in self.sizes]
+        self.ks = [rgc.rgc_k_for_density(n, ppm) for n in self.sizes]
         self.V = upload(torch, cfg["V"], dev)
         self.U = upload(torch, cfg["U"], dev) if cfg["U"] is not None else None
         self.G = [upload(torch, g, dev) for g in cfg["G"]]
@@ -332,6 +332,33 @@ def main():
     if not args.step_only:
         tbs_info = measure_threshold(torch, rgc, ctx, vgg, stream, args.steps, dev)
 
+    # The densities of a warm-up period (Section 2.5: 25 %, 6.25 %, 1.5625 %, 0.4 % before 0.1 %) on the same
+    # tensors: message buffers of their own, residual and velocity shared with the headline workload
+    warm_info = None
+    if not args.step_only:
+        warm_info = {}
+        for ppm in (250_000, 62_500, 15_625, 4_000):
+            ks = [rgc.rgc_k_for_density(n, ppm) for n in vgg.sizes]
+            oi = [torch.empty(k, dtype=torch.int32, device=dev) for k in ks]
+            ov = [torch.empty(k, dtype=torch.float32, device=dev) for k in ks]
+            lists = [rgc.LayerList(g, vgg.V, ks, oi, ov, vgg.out_count, vgg.U) for g in vgg.G]
+            calls = [0]
+
+            def warm_step():
+                rgc.rgc_compress_layers(ctx, lists[calls[0] % len(lists)], vgg.m, 0, stream)
+                calls[0] += 1
+
+            for _ in range(10):
+                warm_step()
+            ms = time_loop(torch, warm_step, min(args.steps, 20))
+            alg = vgg.alg_bytes_stream + 16 * sum(ks)
+            warm_info["%g%%" % (ppm / 1e4)] = {
+                "sum_k": sum(ks), "ms_per_iter": ms, "alg_bytes": alg,
+                "hbm_frac_algorithmic": alg / (ms * 1e-3) / (HBM_PEAK_GBPS * 1e9),
+                "layers_off_one_pass_path": sum(1 for p in ctx.last_paths(len(vgg.sizes), stream) if p != 0)}
+            del lists, oi, ov
+        torch.cuda.empty_cache()
+
     if args.calibrate_copy:
         src = torch.zeros(vgg.total, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
@@ -377,7 +404,8 @@ def main():
         "step_kernels_ms": {"accumulate_kernel": step_ms4[0] / max(step_calls[0], 1),
                             "phase_launches": step_ms4[1] / max(step_calls[0], 1),
                             "decompress_tiles_kernel": step_ms4[3] / max(step_calls[1], 1)},
-        "compress": comp, "decompress": dec_info, "local_clipping": clip_info, "alternating_signs": asq_info, "threshold_search": tbs_info, "other_workloads": others,
+        "compress": comp, "decompress": dec_info, "local_clipping": clip_info, "alternating_signs": asq_info, "threshold_search": tbs_info,
+        "warmup_densities": warm_info, "other_workloads": others,
         "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(line))
