@@ -114,6 +114,16 @@ def test_no_hints_gives_the_same(rgc, oracle):
     run_asq(rgc, oracle, V, Gs, ks, tag="asq no hints", extra_flags=rgc.RGC_NO_HINTS)
 
 
+def test_full_size_lstm_set_alternating(rgc, oracle):
+    """The LSTM-shaped layer set at full size (66.0 M elements, row-sparse embedding gradient): two hint-free
+    and two hinted calls, largest and smallest in turn."""
+    from paper_1808_04357_amd import synth
+    cfg = synth.config_lstm(num_grads=4)
+    ks = [rgc.rgc_k_for_density(v.size) for v in cfg["V"]]
+    assert sum(ks) == 66_024
+    run_asq(rgc, oracle, cfg["V"], cfg["G"], ks, tag="asq C4")
+
+
 def test_both_selection_flags_are_rejected(rgc):
     import torch
     dev = torch.device("cuda:0")

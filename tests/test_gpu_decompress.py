@@ -198,6 +198,20 @@ def test_config5_full_size(rgc, oracle):
     print("  oracle", flush=True)
     ref = oracle_all(oracle, idx, val, sizes, 1.0 / 128)
     compare("C5", got, ref)
+    # The benchmark's step decompresses right after a compression call on the same context, and the
+    # library then reads the messages with streaming loads (another instantiation of the tile kernel):
+    # the same messages once more in that configuration.
+    import torch
+    dev = torch.device("cuda:0")
+    n, k = 1000, 1
+    G, V = torch.ones(n, device=dev), torch.zeros(n, device=dev)
+    oi = torch.empty(k, dtype=torch.int32, device=dev)
+    ov = torch.empty(k, dtype=torch.float32, device=dev)
+    oc = torch.zeros(1, dtype=torch.int32, device=dev)
+    rgc.rgc_compress_layers(ctx, rgc.LayerList([G], [V], [k], [oi], [ov], oc))
+    print("  gpu, after a compression call", flush=True)
+    got = gpu_decompress(rgc, ctx, idx, val, sizes, 1.0 / 128)
+    compare("C5 after compress", got, ref)
     ctx.close()
 
 
