@@ -175,11 +175,12 @@ def measure_compress(torch, rgc, ctx, wl, stream, steps, warmup):
     return out
 
 
-def cpu_baseline(torch, wl):
-    """The oracle as it stands, timed on the host: one compress step of the whole layer set on one
-    thread (about 10 s for the VGG16 set: the largest tensor alone is a 103 M-pair sort), and once
-    more with the layers spread over the host's threads (layers are independent; the largest one
-    bounds the gain)."""
+def cpu_baseline(torch, wl, dec):
+    """The oracle as it stands, timed on the host over one whole step of the headline workload: one
+    compress step of the layer set on one thread (about 10 s for the VGG16 set: the largest tensor
+    alone is a 103 M-pair sort) plus the decompression of the same messages the GPU step consumes
+    (sequential scatter-add, one thread).  The compress step once more with the layers spread over
+    the host's threads (layers are independent; the largest one bounds the gain)."""
     import oracle
     torch.cuda.synchronize()
     G = [g.cpu().numpy() for g in wl.G[0]]
@@ -196,10 +197,20 @@ def cpu_baseline(torch, wl):
     dt1 = run(1)
     T = min(oracle.hardware_threads(), len(wl.sizes), 16)
     dtT = run(T)
-    return {"value": 4.0 * wl.total / dt1 / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": "one compress step of all %d %s tensors (%d elements), plain C++ full-sort oracle, 1 thread, %.1f s"
-                      % (len(wl.sizes), wl.name, wl.total, dt1),
-            "layer_parallel": {"value": 4.0 * wl.total / dtT / 1e9, "unit": "GB/s", "cores": T, "seconds": dtT},
+    h_idx = [[a.cpu().numpy() for a in row] for row in dec.d_idx]
+    h_val = [[a.cpu().numpy() for a in row] for row in dec.d_val]
+    t0 = time.perf_counter()
+    for l, n in enumerate(dec.sizes):
+        oracle.decompress([h_idx[w][l] for w in range(dec.workers)], [h_val[w][l] for w in range(dec.workers)],
+                          n, dec.scale)
+    dt_dec = time.perf_counter() - t0
+    return {"value": 4.0 * wl.total / (dt1 + dt_dec) / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": "one whole step: compress of all %d %s tensors (%d elements, plain C++ full-sort oracle, %.1f s) "
+                      "+ decompress of %d workers' messages (%d entries, %.2f s), 1 thread"
+                      % (len(wl.sizes), wl.name, wl.total, dt1, dec.workers, dec.entries, dt_dec),
+            "compress_seconds": dt1, "decompress_seconds": dt_dec,
+            "compress_only_GBps": 4.0 * wl.total / dt1 / 1e9,
+            "layer_parallel_compress": {"value": 4.0 * wl.total / dtT / 1e9, "unit": "GB/s", "cores": T, "seconds": dtT},
             "host_threads_available": oracle.hardware_threads()}
 
 
@@ -386,8 +397,8 @@ def main():
 
     cpu = None
     if not args.skip_cpu:
-        log("timing the CPU oracle on the VGG16-shaped set (1 thread, then layer-parallel; about 20 s)...")
-        cpu = cpu_baseline(torch, vgg)
+        log("timing the CPU oracle on one whole step (compress on 1 thread, then layer-parallel, decompress; about 20 s)...")
+        cpu = cpu_baseline(torch, vgg, dec)
 
     line = {
         "metric": "gradient GB/s through accumulate+top-k+pack (% HBM peak); ms/iter per layer set",
