@@ -21,9 +21,11 @@
  * may be used from different streams and threads concurrently.
  * Stream capture: the first call that shows a context a new list of layers (or of messages)
  * allocates device tables and uploads them; a repeated call with the same descriptors only
- * launches kernels.  After one such eager call, rgc_compress_layers (and its _scaled and
- * _threshold forms), rgc_message_means, rgc_clip_coefficient and rgc_decompress_accumulate may
- * therefore be recorded into a HIP graph on a capturing stream and replayed: all that changes
+ * launches kernels (rgc_message_means, rgc_clip_coefficient and rgc_compress_layers_threshold
+ * also allocate a scratch array on their first use).  After one eager call of the same function
+ * with the same descriptors, rgc_compress_layers (and its _scaled and _threshold forms),
+ * rgc_message_means, rgc_clip_coefficient and rgc_decompress_accumulate may therefore be
+ * recorded into a HIP graph on a capturing stream and replayed: all that changes
  * from step to step (residual, velocity, hints, per-layer state) is device memory.  The calls
  * that copy results to the host (rgc_last_paths, rgc_last_stats, rgc_decompress_status,
  * rgc_selftest, rgc_profile_read) and the event timing of rgc_profile_enable are not for capture.
