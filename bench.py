@@ -265,6 +265,16 @@ def main():
     ctx.profile_enable(False)
     step_bytes = vgg.alg_bytes + dec.alg_bytes
     value = 4.0 * vgg.total / ms_step / 1e6          # gradient GB/s through the whole step
+    # the same step K more times, each bracketed by its own pair of events on the stream (median and minimum)
+    per_step = [float("nan")]
+    if not args.step_only:
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        for a, b in evs:
+            a.record(stream)
+            step()
+            b.record(stream)
+        torch.cuda.synchronize()
+        per_step = sorted(a.elapsed_time(b) for a, b in evs)
 
     # ---- the two halves and the dominant kernel, measured live with HIP events
     comp = dec_info = None
@@ -411,6 +421,7 @@ def main():
                    "kernel_launches_per_step": {"compress": 6, "decompress": 1}},
         "hbm_frac_step_algorithmic": step_bytes / (ms_step * 1e-3) / (HBM_PEAK_GBPS * 1e9),
         "ms_per_step_without_kernel_events": ms_step_plain,
+        "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
         "hint_misses_in_timed_steps": step_misses,
         "step_kernels_ms": {"accumulate_kernel": step_ms4[0] / max(step_calls[0], 1),
                             "phase_launches": step_ms4[1] / max(step_calls[0], 1),
