@@ -3,6 +3,8 @@ from 0.01 % to 10 %, value laws (normal, Laplace, heavy ties, 90 % zeros), unali
 without momentum correction / its Nesterov form, through the exact selection (with and without hints),
 Alternating Signs Quantization and the threshold binary search selection, four calls each, everything
 compared with the oracle bit for bit (the average of a quantized message within one ulp)."""
+import os
+
 import numpy as np
 import pytest
 
@@ -23,8 +25,10 @@ def rgc():
 
 def test_random_configurations(rgc, oracle):
     import torch
-    iters = 80
+    iters = int(os.environ.get("RGC_RANDOM_ITERS", "80"))      # a longer sweep: RGC_RANDOM_ITERS=2500 pytest -s ...
     for it in range(iters):
+        if it % 100 == 99:
+            print("  configuration %d of %d" % (it + 1, iters), flush=True)
         g = np.random.default_rng(770_000 + it)
         L = int(g.integers(1, 7))
         sizes = [int(g.choice([1, 3, 63, 64, 255, 256, 257, 1000, 4095, 4096, 8191, 8193, 33000, 100_003, 400_000, 1_500_000])) for _ in range(L)]
@@ -97,7 +101,10 @@ def test_random_decompressions(rgc, oracle):
     import torch
     dev = torch.device("cuda:0")
     ctx = rgc.Context(1024, 1)
-    for it in range(60):
+    iters = int(os.environ.get("RGC_RANDOM_ITERS", "80")) * 3 // 4
+    for it in range(iters):
+        if it % 100 == 99:
+            print("  decompression %d of %d" % (it + 1, iters), flush=True)
         g = np.random.default_rng(880_000 + it)
         N = int(g.choice([0, 1, 2, 7, 64, 128, 129, 260]))
         L = int(g.integers(1, 5))
