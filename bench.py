@@ -224,6 +224,9 @@ def main():
     ap.add_argument("--step-only", action="store_true",
                     help="only the step loops (warm-up, K steps, K timed steps): what a profiler should see when its "
                          "per-kernel averages are to be those of the timed region")
+    ap.add_argument("--workload", choices=["lstm", "resnet50", "single_1Mi", "uniform_1Mi", "uniform_64Mi"],
+                    help="time only the compression call on this layer set and print its block (for a profiler: "
+                         "the per-kernel averages are then those of this workload)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain device copies of 4*138,344,128 bytes (a yardstick of known "
                          "size for rocprofv3 byte counters)")
@@ -238,6 +241,20 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     stream = torch.cuda.current_stream()
+
+    makers = {"lstm": lambda: synth.config_lstm(num_grads=NUM_GRAD_SETS),
+              "resnet50": lambda: synth.config_resnet50(num_grads=NUM_GRAD_SETS),
+              "single_1Mi": lambda: synth.config_single(1 << 20, num_grads=NUM_GRAD_SETS),
+              "uniform_1Mi": lambda: synth.config_uniform(1 << 20, num_grads=NUM_GRAD_SETS),
+              # the value law of the paper's own selection benchmark (Figure 2), 64 Mi elements
+              "uniform_64Mi": lambda: synth.config_uniform(1 << 26, num_grads=NUM_GRAD_SETS)}
+    if args.workload:
+        wl = CompressWorkload(torch, rgc, makers[args.workload](), dev)
+        ctx = rgc.Context(wl.total, 256)
+        out = measure_compress(torch, rgc, ctx, wl, stream, args.steps, args.warmup)
+        out["workload"] = args.workload
+        print(json.dumps(out))
+        return
 
     log("generating VGG16-shaped inputs (138.3 M elements, %d gradient sets)..." % NUM_GRAD_SETS)
     t0 = time.perf_counter()
@@ -391,12 +408,7 @@ def main():
     others = {}
     if not (args.skip_others or args.step_only):
         del step
-        for name, make in (("lstm", lambda: synth.config_lstm(num_grads=NUM_GRAD_SETS)),
-                           ("resnet50", lambda: synth.config_resnet50(num_grads=NUM_GRAD_SETS)),
-                           ("single_1Mi", lambda: synth.config_single(1 << 20, num_grads=NUM_GRAD_SETS)),
-                           ("uniform_1Mi", lambda: synth.config_uniform(1 << 20, num_grads=NUM_GRAD_SETS)),
-                           # the value law of the paper's own selection benchmark (Figure 2), 64 Mi elements
-                           ("uniform_64Mi", lambda: synth.config_uniform(1 << 26, num_grads=NUM_GRAD_SETS))):
+        for name, make in makers.items():
             log("workload %s..." % name)
             wl = CompressWorkload(torch, rgc, make(), dev)
             others[name] = measure_compress(torch, rgc, ctx, wl, stream, args.steps, args.warmup)
