@@ -84,7 +84,7 @@ typedef struct {
   int32_t*     out_idx;   /* [k] layer-local 0-based indices, strictly ascending            */
   float*       out_val;   /* [k] out_val[j] = accumulated value at out_idx[j], sign kept    */
   int32_t*     out_count; /* [1] device word, receives k: the message's length element
-                             (Section 2.3: "an initial element, which indicates the length") */
+                             (Section 2.3: a message starts with an element that gives its length) */
 } rgc_layer;
 
 /* One (worker, layer) message handed to decompression: `count` entries, `idx` strictly

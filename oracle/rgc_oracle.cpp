@@ -8,8 +8,8 @@
 // What it computes (RedSync paper, Algorithm 1, inner loop over layers):
 //   V_j += G_j                      (residual accumulate)
 //   Masks = select(V_j, D)          (communication-set = top-k by magnitude,
-//                                    Section 2.1, first paragraph: "top 0.1%
-//                                    elements ... of each layer")
+//                                    Section 2.1, first paragraph: the largest
+//                                    0.1 % of every layer's elements)
 //   message = compress(V_j . Masks) (k indices + k values + a length element,
 //                                    Section 2.2 first sentence, Section 2.3)
 //   V_j = V_j . (1 - Masks)         (sent entries leave the residual)
@@ -18,7 +18,7 @@
 //
 // The paper's own fast selection schemes (Algorithms 2 and 3) are NOT what is
 // implemented here: Algorithm 2 plus its radixSelect step yields exactly the
-// top-k set (Section 2.1: it keeps "the compression ratio to be exactly 0.1%"),
+// top-k set (Section 2.1: the compression ratio stays at exactly 0.1 % with it),
 // so the oracle is that definition written out with a full sort.
 //
 // Readings taken where the paper is silent:
