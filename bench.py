@@ -9,7 +9,11 @@ A step = one pass of the whole hot path over one batch of synthetic input:
 All inputs are resident in HBM before the timed region.  The residual and velocity evolve
 from step to step (steady-state RGC) while the gradient rotates through 4 pre-generated sets.
 
-Prints ONE JSON line; see the design doc for the meaning of every field.
+Prints ONE JSON line: `value` = gradient bytes through the whole step per second (wall-clock mean of the K
+timed steps); `compress`, `decompress`, `local_clipping`, `alternating_signs`, `threshold_search`,
+`warmup_densities` and `other_workloads` time the parts and the variants; `roofline` is the streaming
+accumulate kernel against the HBM peak, timed with HIP events inside the timed steps; `cpu_baseline` is the CPU
+oracle timed on the same step.
 """
 from __future__ import annotations
 
