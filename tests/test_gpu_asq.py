@@ -124,6 +124,16 @@ def test_full_size_lstm_set_alternating(rgc, oracle):
     run_asq(rgc, oracle, cfg["V"], cfg["G"], ks, tag="asq C4")
 
 
+def test_full_size_vgg16_set_alternating_with_momentum(rgc, oracle):
+    """The VGG16-shaped set at full size with the momentum correction, as the benchmark's alternating-signs
+    block runs it: the k largest, then the k smallest (both calls on the multi-pass path)."""
+    from paper_1808_04357_amd import synth
+    cfg = synth.config_vgg16(num_grads=2)
+    ks = [rgc.rgc_k_for_density(v.size) for v in cfg["V"]]
+    assert sum(ks) == 138_351
+    run_asq(rgc, oracle, cfg["V"], cfg["G"], ks, U0=cfg["U"], m=cfg["momentum"], tag="asq C3")
+
+
 def test_both_selection_flags_are_rejected(rgc):
     import torch
     dev = torch.device("cuda:0")
