@@ -367,9 +367,11 @@ int rgc_oracle_compress_layer_bruteforce(const float* grad, float* residual, flo
   return 0;
 }
 
-// A whole layer set, layers handed to `threads` host threads round-robin
-// (layers are independent in Algorithm 1's inner loop).  threads <= 1 runs the
-// plain sequential loop.  Only used to time the oracle on several cores.
+// A whole layer set: Algorithm 1's inner loop over the layers, which are
+// independent of each other, so layer l goes to host thread l mod `threads`
+// (threads <= 1 runs the plain sequential loop).  Every multi-layer reference of
+// the parity tests, the smoke check and the benchmark's CPU timing comes from
+// here; the pins compare it with one call per layer for several thread counts.
 int rgc_oracle_compress_layers_ex(const float* const* grad, float* const* residual,
                                   float* const* momentum, const int64_t* n, const int32_t* k,
                                   int32_t num_layers, float m, int mask_momentum, int nesterov,

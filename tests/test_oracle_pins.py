@@ -237,6 +237,58 @@ def test_against_torch_topk_value_multiset(oracle):
     assert np.array_equal(np.sort(top), np.sort(np.abs(val)))
 
 
+# ------------------------------------------------------------------ the loop over layers
+
+@pytest.mark.parametrize("variant", ["plain", "momentum", "momentum_unmasked", "nesterov", "scaled"])
+@pytest.mark.parametrize("threads", [1, 3, 16])
+def test_layer_set_equals_layer_by_layer(oracle, variant, threads):
+    """Algorithm 1's inner loop treats the layers independently: the whole-set call (which hands layers
+    to host threads) must give, layer for layer, what one call per layer gives -- messages, counts,
+    residuals and velocities bit for bit -- with more layers than threads and with fewer, and it must
+    pair every layer with its own k, its own buffers and its own count word."""
+    g = np.random.default_rng(700 + threads)
+    sizes = [1, 7, 5000, 64, 12_345, 300, 2, 900, 4096, 33, 70_001]          # 11 layers: > 3 threads, < 16
+    ks = [1, 3, 5, 64, 13, 2, 1, 9, 40, 33, 71]
+    G = [(g.standard_normal(n) * 1e-3).astype(np.float32) for n in sizes]
+    V0 = [(g.standard_normal(n) * 1e-2).astype(np.float32) for n in sizes]
+    G[2] = np.round(G[2] * 512).astype(np.float32) / 512                        # ties at the threshold
+    V0[2] = np.round(V0[2] * 512).astype(np.float32) / 512
+    mom = variant in ("momentum", "momentum_unmasked", "nesterov")
+    U0 = [(g.standard_normal(n) * 1e-3).astype(np.float32) for n in sizes] if mom else None
+    kw = dict(m=0.9 if mom else 0.0, mask_momentum=variant != "momentum_unmasked",
+              nesterov=variant == "nesterov", grad_scale=0.37 if variant == "scaled" else None)
+    Vs = [v.copy() for v in V0]
+    Us = [u.copy() for u in U0] if mom else None
+    got = oracle.compress_layers(G, Vs, ks, momenta=Us, threads=threads, **kw)
+    assert len(got) == len(sizes)
+    for l, (n, k) in enumerate(zip(sizes, ks)):
+        v = V0[l].copy()
+        u = U0[l].copy() if mom else None
+        idx, val, cnt = oracle.compress_layer(G[l], v, k, momentum=u, **kw)
+        assert got[l][2] == cnt == k, "count of layer %d" % l
+        assert got[l][0].size == k and np.array_equal(got[l][0], idx), "indices of layer %d" % l
+        assert np.array_equal(got[l][1].view(np.uint32), val.view(np.uint32)), "values of layer %d" % l
+        assert np.array_equal(Vs[l].view(np.uint32), v.view(np.uint32)), "residual of layer %d" % l
+        if mom:
+            assert np.array_equal(Us[l].view(np.uint32), u.view(np.uint32)), "velocity of layer %d" % l
+    # and against the definition itself on one layer of the set, so that this pin does not rest on the
+    # per-layer entry point alone: stable argsort by descending magnitude of V + G
+    if variant == "plain":
+        l = 10
+        a = V0[l] + G[l]
+        order = np.argsort(-key(a).astype(np.int64), kind="stable")
+        assert np.array_equal(got[l][0], np.sort(order[:ks[l]]).astype(np.int32))
+        check_invariants(a, ks[l], got[l][0], got[l][1], got[l][2], Vs[l])
+
+
+def test_layer_set_with_no_layers_and_bad_layer(oracle):
+    assert oracle.compress_layers([], [], [], threads=4) == []
+    G = [np.ones(4, np.float32), np.ones(4, np.float32)]
+    V = [np.zeros(4, np.float32), np.zeros(4, np.float32)]
+    with pytest.raises(ValueError):
+        oracle.compress_layers(G, V, [1, 5], threads=2)                         # k > n in the second layer
+
+
 # ------------------------------------------------------------------ accumulate / momentum
 
 def test_first_iteration_residual_zero_gives_gradient(oracle):
