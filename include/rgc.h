@@ -150,7 +150,9 @@ int rgc_compress_layers_scaled(rgc_ctx* ctx, const rgc_layer* layers, int32_t nu
  *    speed hints of the three selection modes are kept apart; a layer short of elements of the
  *    expected sign has none and takes the multi-pass path on every call.
  *  - rgc_message_means: means[l] = average of layer l's out_val[0 .. *out_count), summed in fp64 in
- *    a fixed order and rounded to fp32 once; `means` is DEVICE memory, num_layers floats.  The
+ *    a fixed order and rounded to fp32 once; `means` is DEVICE memory, num_layers floats.  A length
+ *    word above the layer's k (possible only after rgc_compress_layers_threshold, whose messages this
+ *    call is not meant for) is read as k.  The
  *    message of layer l is then (count, out_idx, means[l]); layers the caller does not want
  *    quantized (the paper leaves the output layer alone) simply keep their out_val.
  *  - decompression: rgc_decompress_accumulate with RGC_ONE_VALUE takes such messages (val -> the
@@ -158,6 +160,25 @@ int rgc_compress_layers_scaled(rgc_ctx* ctx, const rgc_layer* layers, int32_t nu
  * Errors (nothing enqueued): RGC_EINVAL (also both selection flags at once), RGC_ENOMEM, RGC_EHIP. */
 int rgc_message_means(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers, float* means,
                       void* hip_stream);
+
+/* rgc_message_means for callers that cannot allocate device or pinned memory when they call: code
+ * under HIP stream capture, tight serving loops, harnesses that forbid hipMalloc.  It takes no context
+ * and calls no allocating routine, on its first call as little as later; its partial sums live in a
+ * static array of the library's code object (512 KiB, one copy per GPU, held until the process ends).
+ * It runs on the CURRENT HIP device.  values[l] / counts[l]: DEVICE pointers to message l's values and
+ * to its length word (what rgc_compress_layers wrote as out_val / out_count); capacity[l]: how many
+ * values the buffer holds (the layer's k; a larger length word is read as capacity[l]); the three
+ * arrays themselves are HOST memory and are copied into the kernel arguments before the call returns.
+ * means: DEVICE, num_layers floats.  Same arithmetic, same order of additions and so the same bits as
+ * rgc_message_means on the same messages.
+ * Limit: num_layers <= RGC_NOALLOC_MAX_LAYERS, else RGC_ENOMEM (nothing enqueued).
+ * All calls on one GPU share that GPU's array: calls that overlap there (two streams, two threads)
+ * race; order them on one stream or with events.  Nothing in the array needs to be cleared between calls.
+ * Errors (nothing enqueued): RGC_EINVAL, RGC_ENOMEM, RGC_EHIP. */
+#define RGC_NOALLOC_MAX_LAYERS 64
+int rgc_message_means_noalloc(const float* const* values, const int32_t* const* counts,
+                              const int32_t* capacity, int32_t num_layers, float* means,
+                              void* hip_stream);
 
 /* The compression step with threshold binary search selection (Section 2.1, Algorithm 3) in place
  * of the exact top-k: the communication-set of a layer is EVERY element of the accumulated tensor

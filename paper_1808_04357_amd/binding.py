@@ -32,7 +32,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("RGC_LIB") or os.path.join(_HERE, "librgc.so")   # RGC_LIB: tuning builds only
 
 EXPORTS = ["rgc_create", "rgc_destroy", "rgc_k_for_density", "rgc_compress_layers",
-           "rgc_compress_layers_scaled", "rgc_clip_coefficient", "rgc_message_means", "rgc_compress_layers_threshold",
+           "rgc_compress_layers_scaled", "rgc_clip_coefficient", "rgc_message_means", "rgc_message_means_noalloc",
+           "rgc_compress_layers_threshold",
            "rgc_decompress_accumulate", "rgc_reset_hints", "rgc_poison_hints", "rgc_selftest",
            "rgc_last_paths", "rgc_last_stats", "rgc_decompress_status", "rgc_profile_enable", "rgc_profile_read", "rgc_strerror"]
 
@@ -92,6 +93,10 @@ def load_library() -> ctypes.CDLL:
     L.rgc_message_means.restype = ctypes.c_int
     L.rgc_message_means.argtypes = [ctypes.c_void_p, ctypes.POINTER(rgc_layer), ctypes.c_int32, ctypes.c_void_p,
                                     ctypes.c_void_p]
+    L.rgc_message_means_noalloc.restype = ctypes.c_int
+    L.rgc_message_means_noalloc.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_void_p),
+                                            ctypes.POINTER(ctypes.c_int32), ctypes.c_int32, ctypes.c_void_p,
+                                            ctypes.c_void_p]
     L.rgc_clip_coefficient.restype = ctypes.c_int
     L.rgc_clip_coefficient.argtypes = [ctypes.c_void_p, ctypes.POINTER(rgc_layer), ctypes.c_int32, ctypes.c_float,
                                        ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
@@ -270,6 +275,20 @@ def rgc_compress_layers_threshold(ctx: Context, layers: LayerList, momentum: flo
 def rgc_message_means(ctx: Context, layers: LayerList, means, stream=None) -> None:
     """means: a float32 device tensor of num_layers elements that receives each layer's average value."""
     _check(load_library().rgc_message_means(ctx.handle, layers.array, layers.num_layers, _ptr(means), _stream(stream)))
+
+
+RGC_NOALLOC_MAX_LAYERS = 64
+
+
+def rgc_message_means_noalloc(values: Sequence, counts, capacity: Sequence[int], means, stream=None) -> None:
+    """values: one float32 device tensor per message; counts: an int32 device tensor holding their length
+    words, one per message; capacity: how many values each buffer holds; means: float32 device tensor."""
+    L = len(values)
+    vp = (ctypes.c_void_p * max(L, 1))(*[int(v.data_ptr()) for v in values])
+    base = int(counts.data_ptr())
+    cp = (ctypes.c_void_p * max(L, 1))(*[base + 4 * l for l in range(L)])
+    cap = (ctypes.c_int32 * max(L, 1))(*[int(c) for c in capacity])
+    _check(load_library().rgc_message_means_noalloc(vp, cp, cap, L, _ptr(means), _stream(stream)))
 
 
 def rgc_clip_coefficient(ctx: Context, layers: LayerList, max_norm: float, num_workers: int, coefficient,

@@ -21,12 +21,16 @@ namespace {
 
 thread_local std::string g_hip_error = "no HIP error recorded";
 
-int fail_hip(hipError_t e, const char* what) {
+}  // namespace
+
+int rgc::fail_hip(hipError_t e, const char* what) {
   char buf[256];
   std::snprintf(buf, sizeof buf, "%s: %s", what, hipGetErrorString(e));
   g_hip_error = buf;
   return RGC_EHIP;
 }
+
+namespace {
 
 #define RGC_HIP(call)                                   \
   do {                                                  \

@@ -22,6 +22,10 @@
 // (fence + atomic counter), so no host round trip and no spinning is needed.
 #include "rgc_device.h"
 
+#include <mutex>
+
+#include "../../include/rgc.h"
+
 namespace rgc {
 
 namespace {
@@ -1257,14 +1261,46 @@ __device__ __forceinline__ double block_tree_sum(double x, double* red, uint32_t
   return red[0];
 }
 
-__global__ void __launch_bounds__(kBlockThreads) message_part_sums_kernel(CompressArgs A, uint32_t part, double* part_sums) {
+// Where the two kernels find a layer's message: in the descriptor table of a compression plan, or in
+// the kernel arguments themselves (the entry point that allocates nothing has no table to put them in).
+struct MessageRef {
+  const float* val;        // the message's values
+  const int32_t* count;    // device word: how many there are
+  uint32_t cap;            // how many the buffer holds (the layer's k); a larger count is read as this
+};
+
+struct TableMessages {
+  const LayerDesc* layers;
+  __device__ __forceinline__ MessageRef get(uint32_t l) const {
+    const LayerDesc& L = layers[l];
+    return MessageRef{L.out_val, L.out_count, L.k};
+  }
+};
+
+constexpr uint32_t kInlineMessagesMax = 64;
+struct InlineMessages {
+  const float* val[kInlineMessagesMax];
+  const int32_t* count[kInlineMessagesMax];
+  uint32_t cap[kInlineMessagesMax];
+  __device__ __forceinline__ MessageRef get(uint32_t l) const { return MessageRef{val[l], count[l], cap[l]}; }
+};
+
+// The length of a message as both kernels read it: never beyond the buffer, so that the parts the
+// second kernel adds up are exactly the parts the first one wrote (the grid is sized from the buffers).
+__device__ __forceinline__ uint32_t message_length(const MessageRef& M) {
+  const int32_t c = *as_global(M.count);
+  return c <= 0 ? 0u : (static_cast<uint32_t>(c) < M.cap ? static_cast<uint32_t>(c) : M.cap);
+}
+
+template <typename Messages>
+__global__ void __launch_bounds__(kBlockThreads) message_part_sums_kernel(Messages src, uint32_t part, double* part_sums) {
   __shared__ double red[kBlockThreads];
-  const LayerDesc L = A.layers[blockIdx.x];
-  const uint32_t count = static_cast<uint32_t>(*as_global(L.out_count));
+  const MessageRef M = src.get(blockIdx.x);
+  const uint32_t count = message_length(M);
   const uint64_t first = static_cast<uint64_t>(blockIdx.y) * part;
   if (first >= count) return;                               // uniform over the workgroup
   const uint32_t len = static_cast<uint32_t>(count - first < part ? count - first : part);
-  const gptr<const float> val = as_global(L.out_val) + first;
+  const gptr<const float> val = as_global(M.val) + first;
   double sum = 0.0;
   uint32_t i = threadIdx.x;
   for (; i + 7u * kBlockThreads < len; i += 8u * kBlockThreads) {   // eight loads in flight, added in order
@@ -1279,10 +1315,11 @@ __global__ void __launch_bounds__(kBlockThreads) message_part_sums_kernel(Compre
   if (threadIdx.x == 0) part_sums[static_cast<size_t>(blockIdx.x) * kMeanPartsMax + blockIdx.y] = total;
 }
 
-__global__ void __launch_bounds__(64) message_means_kernel(CompressArgs A, uint32_t part, const double* part_sums, float* means) {
+template <typename Messages>
+__global__ void __launch_bounds__(64) message_means_kernel(Messages src, uint32_t part, const double* part_sums, float* means) {
   __shared__ double red[64];
-  const LayerDesc L = A.layers[blockIdx.x];
-  const uint32_t count = static_cast<uint32_t>(*as_global(L.out_count));
+  const MessageRef M = src.get(blockIdx.x);
+  const uint32_t count = message_length(M);
   const uint32_t parts = static_cast<uint32_t>((static_cast<uint64_t>(count) + part - 1u) / part);
   const double* mine = part_sums + static_cast<size_t>(blockIdx.x) * kMeanPartsMax;
   double sum = 0.0;
@@ -1291,17 +1328,31 @@ __global__ void __launch_bounds__(64) message_means_kernel(CompressArgs A, uint3
   if (threadIdx.x == 0) means[blockIdx.x] = count ? static_cast<float>(total / static_cast<double>(count)) : 0.0f;
 }
 
-hipError_t launch_message_means(const CompressArgs& a, uint32_t num_layers, uint32_t max_k, double* d_part,
-                                float* d_means, hipStream_t s) {
+// Elements per part for messages of at most max_k values: a multiple of 256, at least 2048, and large
+// enough that the longest message has at most kMeanPartsMax parts.
+static uint32_t mean_part_size(uint32_t max_k) {
   uint32_t part = (max_k + kMeanPartsMax - 1u) / kMeanPartsMax;
   part = (part + 255u) / 256u * 256u;
-  if (part < 2048u) part = 2048u;
+  return part < 2048u ? 2048u : part;
+}
+
+template <typename Messages>
+static hipError_t launch_message_means_from(const Messages& src, uint32_t num_layers, uint32_t max_k, double* d_part,
+                                            float* d_means, hipStream_t s) {
+  const uint32_t part = mean_part_size(max_k);
   const uint32_t parts_max = (max_k + part - 1u) / part;    // <= kMeanPartsMax
-  hipLaunchKernelGGL(message_part_sums_kernel, dim3(num_layers, parts_max ? parts_max : 1u), dim3(kBlockThreads), 0, s, a, part, d_part);
+  hipLaunchKernelGGL(message_part_sums_kernel<Messages>, dim3(num_layers, parts_max ? parts_max : 1u), dim3(kBlockThreads), 0, s,
+                     src, part, d_part);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(message_means_kernel, dim3(num_layers), dim3(64), 0, s, a, part, static_cast<const double*>(d_part), d_means);
+  hipLaunchKernelGGL(message_means_kernel<Messages>, dim3(num_layers), dim3(64), 0, s, src, part,
+                     static_cast<const double*>(d_part), d_means);
   return hipGetLastError();
+}
+
+hipError_t launch_message_means(const CompressArgs& a, uint32_t num_layers, uint32_t max_k, double* d_part,
+                                float* d_means, hipStream_t s) {
+  return launch_message_means_from(TableMessages{a.layers}, num_layers, max_k, d_part, d_means, s);
 }
 
 hipError_t launch_accumulate(const CompressArgs& a, uint32_t num_wgs, hipStream_t s) {
@@ -1326,3 +1377,57 @@ hipError_t launch_wave_scan_selftest(uint32_t* io, hipStream_t s) {
 }
 
 }  // namespace rgc
+
+// ------------------------------------------------------------------ one value per message without any allocation
+// rgc_message_means for callers that cannot allocate: no context, no descriptor table, no hipMalloc.  The
+// messages are named in the kernel arguments and the partial sums live in an array of the code object,
+// of which every device holds its own copy at its own address for as long as the process lives.
+static_assert(RGC_NOALLOC_MAX_LAYERS == rgc::kInlineMessagesMax, "the header states the limit of the kernel arguments");
+static __device__ __align__(256) double scratch[rgc::kInlineMessagesMax * rgc::kMeanPartsMax];   // 512 KiB
+
+namespace {
+constexpr int kScratchDevices = 64;
+std::mutex g_scratch_mutex;
+double* g_scratch_ptr[kScratchDevices] = {};    // device address of `scratch` on each device, once asked for
+}  // namespace
+
+extern "C" int rgc_message_means_noalloc(const float* const* values, const int32_t* const* counts,
+                                         const int32_t* capacity, int32_t num_layers, float* means,
+                                         void* hip_stream) {
+  if (!values || !counts || !capacity || !means || num_layers < 1) return RGC_EINVAL;
+  if (num_layers > RGC_NOALLOC_MAX_LAYERS) return RGC_ENOMEM;          // beyond what the static scratch holds
+  if (reinterpret_cast<uintptr_t>(means) & 3u) return RGC_EINVAL;
+  rgc::InlineMessages src{};
+  uint32_t max_k = 0;
+  for (int32_t l = 0; l < num_layers; ++l) {
+    if (!values[l] || !counts[l] || capacity[l] < 1) return RGC_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(values[l]) | reinterpret_cast<uintptr_t>(counts[l])) & 3u) return RGC_EINVAL;
+    src.val[l] = values[l];
+    src.count[l] = counts[l];
+    src.cap[l] = static_cast<uint32_t>(capacity[l]);
+    max_k = src.cap[l] > max_k ? src.cap[l] : max_k;
+  }
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return rgc::fail_hip(e, "hipGetDevice");
+  if (dev < 0 || dev >= kScratchDevices) return RGC_EINVAL;
+  double* ptr = nullptr;
+  {
+    // In host code the array's name is only a handle for the symbol; its address on the current device
+    // is asked for once per device and used from then on.
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+      void* p = nullptr;
+      e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      if (e != hipSuccess || !p) return rgc::fail_hip(e != hipSuccess ? e : hipErrorInvalidSymbol, "hipGetSymbolAddress(scratch)");
+      g_scratch_ptr[dev] = static_cast<double*>(p);
+    }
+    ptr = g_scratch_ptr[dev];
+  }
+  // Nothing in the array has to start at zero: the second kernel reads exactly the parts the first one
+  // has just written (both derive them from the same message lengths).
+  e = rgc::launch_message_means_from(src, static_cast<uint32_t>(num_layers), max_k, ptr, means,
+                                     static_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return rgc::fail_hip(e, "rgc_message_means_noalloc launch");
+  return RGC_OK;
+}

@@ -188,6 +188,9 @@ struct DecompressArgs {
   float scale;
 };
 
+// Records the text of a failed HIP call for rgc_strerror and returns RGC_EHIP (defined with the host API).
+int fail_hip(hipError_t e, const char* what);
+
 // kernel launchers (defined in the .hip files)
 hipError_t launch_accumulate(const CompressArgs& a, uint32_t num_wgs, hipStream_t s);
 hipError_t launch_phase(const CompressArgs& a, uint32_t num_wgs, hipStream_t s);
