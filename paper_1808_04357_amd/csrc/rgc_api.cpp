@@ -45,6 +45,11 @@ constexpr uint32_t kChunkMin = 1024;
 // beyond the average; with chunk / 32 such a layer overflowed a list, and so missed its hint, in 20 of its first
 // 50 calls, with chunk / 16 in 2.
 constexpr uint32_t kCapDiv = 16;
+// Two-pass layers (high densities) list the keys around the hinted threshold in lists of their own, a quarter of a
+// wave-chunk long (2 bytes per element of scratch, allocated when such a layer is first seen), and rank up to this
+// many members of the k-th key's coarse bin:
+constexpr uint32_t kCapDiv2 = 4;
+// the members of the k-th key's coarse bin go to a pool in which every such layer owns max(4096, n / 64) entries.
 
 // RGC_CHUNK (a multiple of 256, >= 1024) fixes the wave-chunk size for tuning; 0 = automatic.
 uint32_t chunk_override() {
@@ -133,6 +138,7 @@ struct CompressPlan {
   uint32_t num_chunks = 0;                 // wave-chunks over all layers
   uint64_t write_bytes = 0;                // what the streaming pass writes (V, and u where there is one)
   uint32_t max_k = 0;                      // the largest k of the list
+  bool any_two_pass = false;               // some layer takes the probe pass + second pass when it has a hint
   uint64_t last_use = 0;
   bool valid = false;
 };
@@ -158,12 +164,15 @@ struct rgc_ctx {
   int32_t max_layers = 0;
   uint32_t wc_max = 0;
   DevBuf<LayerState> d_state;
-  DevBuf<uint32_t> d_hist, d_coarse, d_cand_cnt, d_wc_a, d_wc_b, d_err, d_group;
+  DevBuf<uint32_t> d_hist, d_coarse, d_cand_cnt, d_wc_a, d_wc_b, d_wc_c, d_err, d_group;
   DevBuf<unsigned long long> d_members;
   DevBuf<double> d_norm_part;              // [wave-chunks] partial sums of squares (clipping coefficient)
   DevBuf<double> d_mean_part;              // [layers][kMeanPartsMax] partial sums of message values
   DevBuf<ThresholdMoments> d_moments;      // [max_layers] threshold binary search: mean, max of each layer
   DevBuf<uint2> d_slots;
+  DevBuf<uint2> d_slots2;                  // the probe pass's lists of two-pass layers (first use)
+  DevBuf<unsigned long long> d_members2;   // member pool of the two-pass layers (first use)
+  DevBuf<uint32_t> d_shards;               // their sub-list counters (first use)
   CompressPlan plans[kPlanCache];
   uint64_t tick = 0;
   bool compressed_since_decompress = false;
@@ -202,6 +211,7 @@ int build_compress_plan(rgc_ctx* ctx, CompressPlan& P, const rgc_layer* layers, 
   const uint32_t kChunk = chunk_for(total_elems), kCap = kChunk / kCapDiv;
   P.chunk = kChunk;
   uint32_t wc = 0, wg = 0, grp = 0;
+  uint64_t mem = 0;                        // entries of the member pool handed out to two-pass layers
   for (int32_t o = 0; o < L; ++o) {
     const int32_t l = order[o];
     const rgc_layer& in = layers[l];
@@ -220,7 +230,8 @@ int build_compress_plan(rgc_ctx* ctx, CompressPlan& P, const rgc_layer* layers, 
     d.wg_count = (d.wc_count + kWavesPerBlock - 1) / kWavesPerBlock;
     d.grp_first = grp;
     grp += (d.wg_count + kElectGroupHost - 1) / kElectGroupHost;
-    d.pad_ = 0;
+    d.mem_cap = 0;
+    d.mem_first = 0;
     const uintptr_t bits = reinterpret_cast<uintptr_t>(in.grad) | reinterpret_cast<uintptr_t>(in.residual) |
                            reinterpret_cast<uintptr_t>(in.momentum);
     d.vec_ok = (bits & 15u) == 0 ? 1u : 0u;
@@ -237,7 +248,28 @@ int build_compress_plan(rgc_ctx* ctx, CompressPlan& P, const rgc_layer* layers, 
     // selected entries per layer it would not, and the hint would miss on every call.
     if (k > static_cast<uint64_t>(kMemberMax) * 256u) d.hintable = 0u;
     d.margin = static_cast<uint32_t>(margin);
-    const uint64_t cmax = std::min<uint64_t>(2 * target, (kCap / 2) * (span / kChunk));
+    uint64_t cmax = std::min<uint64_t>(2 * target, (kCap / 2) * (span / kChunk));
+    d.target = static_cast<uint32_t>(std::min<uint64_t>(target, 0xFFFFFFFFu));
+    d.two_pass = 0;
+    if (!d.hintable && d.wc_count >= 2) {
+      // High densities (the warm-up period of Section 2.5): no list can hold every element from the
+      // threshold upwards, but the lists of the probe pass (kCapDiv2) can hold the keys around it.  The
+      // hint is aimed at rank k + margin and accepted up to rank k + 1.5 margin; the probe pass lists the
+      // keys from the hinted threshold up to as far above the last k-th key as the threshold lies below
+      // it: about two margins' worth of keys, which must fit half the list capacity.
+      const uint32_t kCap2 = kChunk / kCapDiv2;
+      const uint64_t margin2 = std::max<uint64_t>(std::min<uint64_t>(2 * k, d.n / 24), 64);
+      const uint64_t band_per_chunk = (5 * margin2 / 2 * kChunk + span - 1) / span;
+      if (2 * band_per_chunk + 16 <= kCap2 && k + 2 * margin2 < d.n) {
+        d.two_pass = 1;
+        d.mem_cap = static_cast<uint32_t>(std::max<uint64_t>(4096, d.n / 64) / kMemberShards * kMemberShards);
+        d.mem_first = mem;
+        mem += d.mem_cap;
+        d.margin = static_cast<uint32_t>(margin2);
+        d.target = static_cast<uint32_t>(k + margin2);
+        cmax = k + margin2 + margin2 / 2;
+      }
+    }
     d.cmax = static_cast<uint32_t>(std::min<uint64_t>(cmax, 0x7FFFFFFFu));
     wc += d.wc_count;
     wg += d.wg_count;
@@ -262,7 +294,9 @@ int build_compress_plan(rgc_ctx* ctx, CompressPlan& P, const rgc_layer* layers, 
   P.num_chunks = wc;
   P.write_bytes = 0;
   P.max_k = 0;
+  P.any_two_pass = false;
   for (int32_t l = 0; l < L; ++l) {
+    P.any_two_pass = P.any_two_pass || desc[l].two_pass != 0;
     P.write_bytes += static_cast<uint64_t>(layers[l].n) * (layers[l].momentum ? 8u : 4u);
     P.max_k = std::max(P.max_k, static_cast<uint32_t>(layers[l].k));
   }
@@ -345,6 +379,7 @@ int rgc_create(rgc_ctx** out, int device_id, int64_t max_total_elems, int32_t ma
   chk(c->d_cand_cnt.alloc(wc_max));
   chk(c->d_wc_a.alloc(wc_max));
   chk(c->d_wc_b.alloc(wc_max));
+  chk(c->d_wc_c.alloc(wc_max));
   {
     // every wave-chunk owns chunk / kCapDiv slots whatever the chunk size: total / kCapDiv slots
     // plus one (partly used) chunk per layer at the largest chunk size a plan may pick
@@ -387,7 +422,11 @@ int rgc_destroy(rgc_ctx* ctx) {
   ctx->d_cand_cnt.release();
   ctx->d_wc_a.release();
   ctx->d_wc_b.release();
+  ctx->d_wc_c.release();
   ctx->d_slots.release();
+  ctx->d_slots2.release();
+  ctx->d_members2.release();
+  ctx->d_shards.release();
   ctx->d_err.release();
   ctx->d_group.release();
   ctx->d_norm_part.release();
@@ -610,6 +649,7 @@ int rgc_compress_layers_scaled(rgc_ctx* ctx, const rgc_layer* layers, int32_t nu
   A.slots = ctx->d_slots.p;
   A.wc_a = ctx->d_wc_a.p;
   A.wc_b = ctx->d_wc_b.p;
+  A.wc_c = ctx->d_wc_c.p;
   A.errflag = ctx->d_err.p;
   A.group_done = ctx->d_group.p;
   A.chunk = plan->chunk;
@@ -617,18 +657,50 @@ int rgc_compress_layers_scaled(rgc_ctx* ctx, const rgc_layer* layers, int32_t nu
   A.use_hints = (sig_same && !no_hints) ? 1u : 0u;
   A.update_hints = no_hints ? 0u : 1u;
   A.mask_momentum = (flags & RGC_NO_MOMENTUM_MASK) ? 0u : 1u;
-  A.reverse = streaming_direction(plan, ctx->compress_calls++);
+  const bool two_pass = plan->any_two_pass && A.use_hints;
+  if (plan->any_two_pass && !ctx->d_slots2.p) {   // the first call that shows the context such a layer
+    const uint64_t largest = std::max<uint64_t>(16384, chunk_override());
+    hipError_t e = ctx->d_slots2.alloc(static_cast<uint64_t>(ctx->max_total) / kCapDiv2 +
+                                       (static_cast<uint64_t>(ctx->max_layers) + 1) * (largest / kCapDiv2));
+    if (e == hipSuccess) e = ctx->d_members2.alloc(static_cast<uint64_t>(ctx->max_total) / 64 + static_cast<uint64_t>(ctx->max_layers) * 4096);
+    if (e == hipSuccess) e = ctx->d_shards.alloc(static_cast<size_t>(ctx->max_layers) * kMemberShards * kShardStride);
+    if (e != hipSuccess) {
+      ctx->d_slots2.release();
+      ctx->d_members2.release();
+      ctx->d_shards.release();
+      if (e == hipErrorOutOfMemory) { (void)hipGetLastError(); return RGC_ENOMEM; }
+      return fail_hip(e, "two-pass scratch allocation");
+    }
+  }
+  A.slots2 = ctx->d_slots2.p;
+  A.cap2 = A.chunk / kCapDiv2;
+  A.members2 = ctx->d_members2.p;
+  A.shard_cnt = ctx->d_shards.p;
+  // (a call with two-pass layers ends where it began: its second pass runs against its first)
+  A.reverse = two_pass ? 0u : streaming_direction(plan, ctx->compress_calls);
+  ++ctx->compress_calls;
   ctx->compressed_since_decompress = true;
   A.nesterov = (flags & RGC_NESTEROV) ? 1u : 0u;
   A.grad_scale = grad_scale;
   A.m = momentum;
   A.launch = 1;
+  // Layers of the two-pass kind that have a hint are probed by a kernel of their own (read-only) and
+  // skipped by the streaming kernel; if their probe misses they are streamed in a second launch of the
+  // streaming kernel, and if it does not they are ranked by a kernel of their own at launch 2 and end in the emit
+  // kernel at launch 3.
   if (ctx->profiling) RGC_HIP(take_event(ctx, stream, ctx->ev_compress));
   RGC_HIP(launch_accumulate(A, plan->num_wgs, stream));
+  // (after the streaming kernel: both decide from the same state which of them has a layer, and only the
+  // probe kernel changes that state, when it misses)
+  if (two_pass) RGC_HIP(launch_probe(A, plan->num_wgs, stream));
   if (ctx->profiling) RGC_HIP(take_event(ctx, stream, ctx->ev_compress));
-  for (int launch = 2; launch <= kLaunches; ++launch) {
+  // (a two-pass layer can fall back as late as launch 3 and then needs four more launches)
+  for (int launch = 2; launch <= kLaunches + (two_pass ? 1 : 0); ++launch) {
     A.launch = static_cast<uint32_t>(launch);
+    if (two_pass && launch <= 3) RGC_HIP(launch_accumulate(A, plan->num_wgs, stream));
     RGC_HIP(launch_phase(A, plan->num_wgs, stream));
+    if (two_pass && launch == 2) RGC_HIP(launch_rank(A, plan->num_wgs, stream));
+    if (two_pass && launch == 3) RGC_HIP(launch_emit(A, plan->num_wgs, stream));
   }
   if (ctx->profiling) RGC_HIP(take_event(ctx, stream, ctx->ev_compress));
   if (!no_hints) {

@@ -26,6 +26,13 @@
 
 #include "../../include/rgc.h"
 
+#ifndef RGC_PROBE_GROUP
+#define RGC_PROBE_GROUP 1
+#endif
+#ifndef RGC_RECOMPUTE_UNROLL
+#define RGC_RECOMPUTE_UNROLL 4
+#endif
+
 namespace rgc {
 
 namespace {
@@ -40,6 +47,7 @@ struct Collector {
   uint32_t tau;
   uint32_t shift;
   uint32_t sign_xor, sign_filter;   // see key_of()
+  uint32_t clip;     // probe pass of a two-pass layer: candidates of the coarse bins from this one upwards are counted, not listed
 };
 
 // The selection key of an element with bit pattern `bits`.  Plain top-k (Section 2.1): its
@@ -256,6 +264,14 @@ __device__ __forceinline__ uint32_t shift_for(uint32_t T, uint32_t tau) {
   return bl > kKeep ? bl - kKeep : 0u;
 }
 
+// Two-pass layers: the probe pass of the next call lists the keys from the hinted threshold tau up to as far above
+// the k-th key T of this call as tau lies below it (in coarse bins of the next call's shift).
+__device__ __forceinline__ uint32_t clip_for(uint32_t T, uint32_t tau, uint32_t shift) {
+  const uint32_t d = T >= tau ? T - tau : 0u;
+  const uint32_t b = 2u * (d >> shift) + 2u;
+  return b < static_cast<uint32_t>(kCoarseBins - 1) ? b : static_cast<uint32_t>(kCoarseBins - 1);
+}
+
 // Threshold for the next call = rank-based estimate from this call + the observed drift of the
 // k-th key between the last two calls (a steadily growing or shrinking residual moves the
 // threshold by about the same amount every call).  Speed only.
@@ -360,7 +376,7 @@ __device__ void resolve_digit(const CompressArgs& A, uint32_t l, const LayerDesc
   const uint32_t above_scope = L.k - k_rem;          // keys above the current scope
   // The k entries selected now leave the residual, so the next call's top-k come from ranks
   // k+1.. of this call: aim the next threshold at rank 2k + margin.
-  const uint32_t target = 2u * L.k + L.margin;
+  const uint32_t target = L.target;
   const uint32_t pending = (kLevel == 1) ? 1u : st->hint_pending;
   const uint32_t prefix = (kLevel == 1) ? 0u : st->prefix;
   stage_hist<kBins, 1u>(A.hist + static_cast<size_t>(l) * kHistBins, lds);
@@ -414,6 +430,7 @@ __device__ void resolve_digit(const CompressArgs& A, uint32_t l, const LayerDesc
       st->T = T;
       st->r = new_rem;
       st->next_phase = PH_COUNT;
+      if (A.update_hints && L.two_pass && st->probe_skip != 0u) st->probe_skip -= 1u;   // one more call without a probe pass
       if (A.update_hints) {
         // The hints live in the key space of the one-pass path (key_of).  With the ordered key a hint
         // exists only if the k-th key and the threshold aimed at both lie among the elements key_of()
@@ -428,6 +445,7 @@ __device__ void resolve_digit(const CompressArgs& A, uint32_t l, const LayerDesc
         if (usable) {
           st->tau = drifted_tau(tn, Th, st->T_prev, A.use_hints && st->has_prev);
           st->shift = shift_for(Th, tn);
+          st->clip = clip_for(Th, tn, st->shift);
           st->hint_valid = 1u;
           st->T_prev = Th;
           st->has_prev = 1u;
@@ -448,44 +466,51 @@ __device__ void resolve_digit(const CompressArgs& A, uint32_t l, const LayerDesc
 // `lds` holds >= kCoarseBins words and is free for use.
 // `after_first_digit`: the lists come from PH_COLLECT of a hint-free call rather than from the streaming pass
 // of a hinted one; should they not do, the call goes on with the second digit.
+// `probe`: the lists come from the read-only probe pass of a two-pass layer; they hold only the candidates
+// of the coarse bins below the layer's clip bin (the others were counted per wave-chunk in wc_c), the k-th key must lie
+// among those, and should they not do the layer is streamed after all (PH_STREAM).
 __device__ void resolve_collect(const CompressArgs& A, uint32_t l, const LayerDesc& L, LayerState* st,
-                                ResolveShared& sh, uint32_t* lds, bool after_first_digit, uint32_t cur_launch) {
+                                ResolveShared& sh, uint32_t* lds, bool after_first_digit, uint32_t cur_launch,
+                                bool probe = false) {
   const uint32_t t = threadIdx.x;
   uint32_t total = 0, bad = 0;
   for (uint32_t c0 = 0; c0 < L.wc_count; c0 += 8u * kBlockThreads) {
-    uint32_t v[8];
+    uint32_t v[8], w[8];
 #pragma unroll
     for (uint32_t j = 0; j < 8u; ++j) {
       const uint32_t c = c0 + j * kBlockThreads + t;
       v[j] = c < L.wc_count ? ld_agent(&A.cand_cnt[L.wc_first + c]) : 0u;
+      w[j] = (probe && c < L.wc_count) ? ld_agent(&A.wc_c[L.wc_first + c]) : 0u;
     }
 #pragma unroll
     for (uint32_t j = 0; j < 8u; ++j) {
-      bad |= (v[j] > A.cap) ? 1u : 0u;
-      total += v[j];
+      bad |= (v[j] > (probe ? A.cap2 : A.cap)) ? 1u : 0u;
+      total += v[j] + w[j];
     }
   }
   uint32_t cand_total;
   (void)block_excl_scan(total, sh.scan, cand_total);
   bad = __syncthreads_or(static_cast<int>(bad)) ? 1u : 0u;
   stage_hist<kCoarseBins, kCoarseRep>(A.coarse + static_cast<size_t>(l) * kCoarseRep * kCoarseBins, lds);
-  const uint32_t k = L.k, target = 2u * L.k + L.margin;   // see resolve_digit
+  const uint32_t k = L.k, target = L.target;   // see resolve_digit
   const uint32_t hist_total = locate_from_top(lds, kCoarseBins, k, target, sh);
   // PH_SEL adds the selected counts of every kOffsetGroup wave-chunks up in wc_b: start from zero
   for (uint32_t g = t; g < (L.wc_count + kOffsetGroup - 1u) / kOffsetGroup; g += kBlockThreads)
     st_agent(&A.wc_b[L.wc_first + g], 0u);
+  if (probe && t < kMemberShards) st_agent(&A.shard_cnt[(static_cast<size_t>(l) * kMemberShards + t) * kShardStride], 0u);
   if (t == 0) {
+    if (probe) st->shard_overflow = 0u;
     st->stat_candidates = cand_total;
     st->stat_members = sh.cnt;
     const bool ok = !bad && cand_total >= k && hist_total == cand_total && sh.bin != 0xFFFFFFFFu &&
-                    sh.cnt <= static_cast<uint32_t>(kMemberMax);
+                    sh.cnt <= (probe ? L.mem_cap / 4u : static_cast<uint32_t>(kMemberMax)) && (!probe || sh.bin < st->clip);
     if (ok) {
       const uint32_t tau = st->tau, shift = st->shift;
       st->bstar = sh.bin;
       st->k_rem = k - sh.above;
       st->nmembers = 0u;
       if (!after_first_digit) st->path = 0u;
-      st->next_phase = PH_SEL;
+      st->next_phase = probe ? PH_SEL2 : PH_SEL;
       unsigned long long tn;
       if (sh.hbin != 0xFFFFFFFFu) {
         tn = static_cast<unsigned long long>(tau) + (static_cast<unsigned long long>(sh.hbin) << shift);
@@ -503,6 +528,14 @@ __device__ void resolve_collect(const CompressArgs& A, uint32_t l, const LayerDe
       st->tau_next = static_cast<uint32_t>(tn);
     } else if (after_first_digit) {
       st->next_phase = PH_HIST2;          // prefix and k_rem are still those of the first digit
+    } else if (probe) {
+      st->path = 2u;
+      st->stat_misses += 1u;
+      st->next_phase = PH_STREAM;         // nothing has been written yet: the ordinary streaming pass, hint-free
+      // a wasted read-only pass: go without one for a while, twice as long after every further miss
+      const uint32_t wait = st->probe_backoff ? 2u * st->probe_backoff : 1u;
+      st->probe_backoff = wait < kProbeBackoffMax ? wait : kProbeBackoffMax;
+      st->probe_skip = st->probe_backoff + 1u;   // (the count-down of this call's own hint-free pass included)
     } else {
       st->path = 2u;
       st->stat_misses += 1u;
@@ -658,7 +691,13 @@ __global__ void __launch_bounds__(kBlockThreads) accumulate_kernel(CompressArgs 
   const LayerDesc L = A.layers[l];
   LayerState* st = A.state + l;
   // (with a sign filter a threshold of 0 would let the elements that key_of() ranks last and equal into the lists)
-  const bool collect = A.use_hints && L.hintable && (st->hint_valid != 0u) && !(A.sign_filter != 0u && st->tau == 0u);
+  const bool hinted = A.use_hints && (st->hint_valid != 0u) && !(A.sign_filter != 0u && st->tau == 0u);
+  if (A.launch == 1u) {
+    if (L.two_pass && hinted && st->probe_skip == 0u) return;   // the probe kernel has this layer
+  } else if (st->next_launch != A.launch || st->next_phase != PH_STREAM) {
+    return;                                 // second launch: only the layers whose probe missed
+  }
+  const bool collect = hinted && L.hintable && A.launch == 1u;
   // the same LDS array serves as 4096-bin digit histogram (hint-free) or 1024-bin coarse one
   const uint32_t lds_bins = collect ? static_cast<uint32_t>(kCoarseBins) : static_cast<uint32_t>(kHistBins);
   for (uint32_t b = threadIdx.x; b < lds_bins; b += kBlockThreads) lds_hist[b] = 0u;
@@ -705,8 +744,8 @@ __global__ void __launch_bounds__(kBlockThreads) accumulate_kernel(CompressArgs 
     if (collect) {
       resolve_collect(A, l, L, st, sh, lds_hist, false, 1u);
     } else {
-      if (threadIdx.x == 0) { st->path = 1u; st->stat_candidates = 0u; st->stat_members = 0u; }
-      resolve_digit<1>(A, l, L, st, sh, lds_hist, 1u);
+      if (threadIdx.x == 0 && A.launch == 1u) { st->path = 1u; st->stat_candidates = 0u; st->stat_members = 0u; }
+      resolve_digit<1>(A, l, L, st, sh, lds_hist, A.launch);
     }
   }
 }
@@ -1137,6 +1176,531 @@ __global__ void __launch_bounds__(kBlockThreads) phase_late_kernel(CompressArgs 
   }
 }
 
+// =================================================================== two-pass layers (high densities)
+// At the densities of a warm-up period (Section 2.5: 25 %, 6.25 %, 1.5625 % before 0.1 %) the candidate
+// lists cannot hold every element from the hinted threshold upwards, and masking the sent entries out of the
+// residual one by one would dirty most cache lines of V and u.  Such a layer, once it has a hint, takes two
+// streaming passes and no pass in between:
+//  1. probe_kernel reads G, V (, u), computes the accumulated values and writes NOTHING back: candidates
+//     (key >= tau) are counted in the coarse histogram as on the one-pass path, but only those of the coarse
+//     bins below the layer's clip bin (see clip_for) go to the lists; the others are counted per wave-chunk (wc_c).  If the k-th key
+//     turns out to lie among the listed ones, PH_SEL ranks them exactly as for a one-pass layer;
+//  2. emit_kernel reads G, V (, u) again, computes the same values, and with the k-th entry known writes the
+//     masked residual, the masked velocity and the message in one go (32 instead of 52 bytes per element
+//     moved at 25 %, and every write is a streaming one).
+// A probe that misses (too few candidates, the k-th key above the listed band, a list overflow) costs the
+// read-only pass: the layer is then streamed by a second launch of accumulate_kernel and goes on hint-free.
+namespace {
+
+// The probe pass's share of consume(): the four accumulated values of a lane.
+__device__ __forceinline__ void consume_probe(const float (&a)[4], uint32_t nvalid, uint32_t idx0, Collector& c,
+                                              uint32_t& certain) {
+  uint32_t bits[4], bin[4];
+  bool cand[4], listed[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    bits[j] = fbits(a[j]);
+    const uint32_t key = key_of(bits[j], c.sign_xor, c.sign_filter);
+    cand[j] = (static_cast<uint32_t>(j) < nvalid) && (key >= c.tau);
+    bin[j] = coarse_bin(key, c.tau, c.shift);
+    listed[j] = cand[j] && bin[j] < c.clip;
+  }
+  const unsigned long long any = __ballot(cand[0] | cand[1] | cand[2] | cand[3]);
+  if (any == 0ull) return;
+  // (the candidates above the band are added to the histogram's top bin once per wave, not one by one:
+  // they would all queue up on that one word)
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    if (listed[j]) atomicAdd(&c.coarse[bin[j]], 1u);
+  const unsigned long long c0 = __ballot(cand[0] && !listed[0]), c1 = __ballot(cand[1] && !listed[1]),
+                           c2 = __ballot(cand[2] && !listed[2]), c3 = __ballot(cand[3] && !listed[3]);
+  certain += popc64(c0) + popc64(c1) + popc64(c2) + popc64(c3);
+  const unsigned long long m0 = __ballot(listed[0]), m1 = __ballot(listed[1]), m2 = __ballot(listed[2]),
+                           m3 = __ballot(listed[3]);
+  if ((m0 | m1 | m2 | m3) == 0ull) return;
+  uint32_t pos = c.count + rank_below(m0) + rank_below(m1) + rank_below(m2) + rank_below(m3);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    if (listed[j]) {
+      if (pos < c.cap) c.slot[pos] = vu2{bits[j], idx0 + j};
+      ++pos;
+    }
+  }
+  c.count += popc64(m0) + popc64(m1) + popc64(m2) + popc64(m3);
+}
+
+// One wave-chunk of a two-pass layer, both passes: f(a[4], u[4], nvalid, idx0, vector group?) sees the accumulated
+// values (and the updated velocity) of four consecutive elements per lane, computed exactly as the
+// streaming pass computes them, in the same element order.
+template <bool kMom, bool kNest, typename F>
+__device__ __forceinline__ void recompute_chunk(const LayerDesc& L, uint32_t begin, uint32_t end, const AccumRule m, F&& f) {
+  const uint32_t lane = lane_id();
+  uint32_t base = begin;
+  if (L.vec_ok) {
+    const uint32_t nfull = (end - begin) / kGroupElems;
+    const gptr<const vf4> G4 = as_global(reinterpret_cast<const vf4*>(L.grad + begin));
+    const gptr<const vf4> V4 = as_global(reinterpret_cast<const vf4*>(L.resid + begin));
+    const gptr<const vf4> U4 = as_global(kMom ? reinterpret_cast<const vf4*>(L.mom + begin) : nullptr);
+    constexpr uint32_t kUnroll = kMom ? RGC_RECOMPUTE_UNROLL : 4u;
+    uint32_t g = 0;
+    for (; g < nfull; g += kUnroll) {
+      vf4 gv[kUnroll], vv[kUnroll], uv[kUnroll];
+#pragma unroll
+      for (uint32_t t = 0; t < kUnroll; ++t) {
+        if (g + t < nfull) {
+          const uint32_t o = (g + t) * kWaveSize + lane;
+          gv[t] = __builtin_nontemporal_load(&G4[o]);
+          vv[t] = V4[o];
+          if constexpr (kMom) uv[t] = U4[o];
+        }
+      }
+#pragma unroll
+      for (uint32_t t = 0; t < kUnroll; ++t) {
+        if (g + t < nfull) {
+          const uint32_t o = (g + t) * kWaveSize + lane;
+          const float gg[4] = {gv[t].x, gv[t].y, gv[t].z, gv[t].w};
+          const float vvv[4] = {vv[t].x, vv[t].y, vv[t].z, vv[t].w};
+          float uu[4] = {0.f, 0.f, 0.f, 0.f};
+          if constexpr (kMom) { uu[0] = uv[t].x; uu[1] = uv[t].y; uu[2] = uv[t].z; uu[3] = uv[t].w; }
+          float a[4];
+          accum4<kMom, kNest>(gg, vvv, uu, m, a);
+          f(a, uu, 4u, begin + o * 4u, true);
+        }
+      }
+    }
+    base = begin + nfull * kGroupElems;
+  }
+  const gptr<const float> Gs = as_global(L.grad);
+  const gptr<const float> Vs = as_global(L.resid);
+  const gptr<const float> Us = as_global(L.mom);
+  for (; base < end; base += kGroupElems) {
+    const uint32_t idx0 = base + lane * 4u;
+    const uint32_t nvalid = idx0 < end ? ((end - idx0) < 4u ? (end - idx0) : 4u) : 0u;
+    float gg[4] = {0.f, 0.f, 0.f, 0.f}, vvv[4] = {0.f, 0.f, 0.f, 0.f}, uu[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (static_cast<uint32_t>(j) < nvalid) {
+        gg[j] = Gs[idx0 + j];
+        vvv[j] = Vs[idx0 + j];
+        if constexpr (kMom) uu[j] = Us[idx0 + j];
+      }
+    }
+    float a[4];
+    accum4<kMom, kNest>(gg, vvv, uu, m, a);
+    f(a, uu, nvalid, idx0, false);
+  }
+}
+
+template <typename F>
+__device__ __forceinline__ void recompute_chunk_any(const CompressArgs& A, const LayerDesc& L, uint32_t begin, uint32_t end, F&& f) {
+  AccumRule rule;
+  rule.m = A.m;
+  rule.scale = A.grad_scale ? *as_global(A.grad_scale) : 1.0f;
+  if (L.mom == nullptr) recompute_chunk<false, false>(L, begin, end, rule, f);
+  else if (!A.nesterov) recompute_chunk<true, false>(L, begin, end, rule, f);
+  else recompute_chunk<true, true>(L, begin, end, rule, f);
+}
+
+}  // namespace
+
+constexpr uint32_t kProbeGroup = RGC_PROBE_GROUP;
+
+__global__ void __launch_bounds__(kBlockThreads) probe_kernel(CompressArgs A) {
+  __shared__ uint32_t lds_hist[kCoarseBins];
+  __shared__ ResolveShared sh;
+  const uint32_t wg = A.reverse ? gridDim.x - 1u - blockIdx.x : blockIdx.x;
+  const uint32_t l = A.wg2layer[wg];
+  const LayerDesc L = A.layers[l];
+  if (!L.two_pass) return;
+  LayerState* st = A.state + l;
+  // the same condition as in accumulate_kernel, which skips exactly the layers taken here
+  const bool hinted = A.use_hints && (st->hint_valid != 0u) && !(A.sign_filter != 0u && st->tau == 0u);
+  if (!hinted || st->probe_skip != 0u) return;
+  // One workgroup in kProbeGroup does the work of kProbeGroup workgroups (their wave-chunks one after the other, one
+  // histogram for all): a workgroup's epilogue -- up to a thousand device atomics that flush the histogram, then the
+  // election, which waits for them -- is paid a quarter as often, and the bins of 16 wave-chunks overlap.
+  const uint32_t wgl = wg - L.wg_first;
+  if (wgl % kProbeGroup != 0u) return;
+  for (uint32_t b = threadIdx.x; b < static_cast<uint32_t>(kCoarseBins); b += kBlockThreads) lds_hist[b] = 0u;
+  __syncthreads();
+  const uint32_t tau = st->tau, shift = st->shift, clip = st->clip;
+  for (uint32_t i = 0; i < kProbeGroup; ++i) {
+    const uint32_t wc_local = (wgl + i) * kWavesPerBlock + (threadIdx.x >> 6);
+    if (wc_local >= L.wc_count) break;
+    const uint32_t begin = wc_local * A.chunk;
+    const uint32_t end = (L.n - begin) < A.chunk ? L.n : begin + A.chunk;
+    Collector c;
+    c.slot = as_global(reinterpret_cast<vu2*>(A.slots2 + static_cast<size_t>(L.wc_first + wc_local) * A.cap2));
+    c.coarse = lds_hist;
+    c.cap = A.cap2;
+    c.count = 0;
+    c.tau = tau;
+    c.shift = shift;
+    c.sign_xor = A.sign_xor;
+    c.sign_filter = A.sign_filter;
+    c.clip = clip;
+    uint32_t certain = 0;
+    recompute_chunk_any(A, L, begin, end, [&](const float (&a)[4], const float (&)[4], uint32_t nvalid, uint32_t idx0, bool) {
+      consume_probe(a, nvalid, idx0, c, certain);
+    });
+    if (lane_id() == 0) {
+      st_agent(&A.cand_cnt[L.wc_first + wc_local], c.count);
+      st_agent(&A.wc_c[L.wc_first + wc_local], certain);
+      if (certain) atomicAdd(&lds_hist[kCoarseBins - 1], certain);
+    }
+  }
+  __syncthreads();
+  flush_hist(lds_hist, A.coarse + (static_cast<size_t>(l) * kCoarseRep + ((wgl / kProbeGroup) & (kCoarseRep - 1))) * kCoarseBins, kCoarseBins);
+  if (last_block_of_layer(&st->done, A.group_done + L.grp_first, wgl / kProbeGroup,
+                          (L.wg_count + kProbeGroup - 1u) / kProbeGroup, &sh.flag))
+    resolve_collect(A, l, L, st, sh, lds_hist, false, 1u, true);
+}
+
+namespace {
+
+// The members of a two-pass layer: kMemberShards sub-lists in global memory (region + s * shard_cap, n[s] entries),
+// which other workgroups filled with device-scope stores.  A thread asks for eight values at a time, so that
+// their round trips overlap.
+struct MemberLists {
+  const unsigned long long* region;
+  uint32_t shard_cap;
+  const uint32_t* first;  // [kMemberShards + 1], in LDS: running number of each sub-list's first member; [kMemberShards] = all
+};
+
+template <typename F>
+__device__ __forceinline__ void for_each_member(const MemberLists& M, F&& f) {
+  // one step takes the i-th member of every sub-list: kMemberShards independent loads of a thread in flight
+  uint32_t n[kMemberShards], nmax = 0u;
+#pragma unroll
+  for (uint32_t s = 0; s < kMemberShards; ++s) {
+    n[s] = M.first[s + 1] - M.first[s];
+    nmax = n[s] > nmax ? n[s] : nmax;
+  }
+  for (uint32_t i = threadIdx.x; i < nmax; i += kBlockThreads) {
+    unsigned long long x[kMemberShards];
+#pragma unroll
+    for (uint32_t s = 0; s < kMemberShards; ++s)
+      x[s] = i < n[s] ? __hip_atomic_load(&M.region[static_cast<size_t>(s) * M.shard_cap + i], __ATOMIC_RELAXED,
+                                          __HIP_MEMORY_SCOPE_AGENT)
+                      : 0ull;
+#pragma unroll
+    for (uint32_t s = 0; s < kMemberShards; ++s)
+      if (i < n[s]) f(x[s]);
+  }
+}
+
+// select_kth_largest() for such members (there may be more of them than the LDS holds): the same radix
+// selection, every digit one more pass over the values.  `any` is one of the values.  hist holds 3 * 256 words.
+__device__ unsigned long long select_kth_largest_global(const MemberLists& M, unsigned long long any, uint32_t kk,
+                                                        uint32_t* hist, ResolveShared& sh) {
+  const uint32_t t = threadIdx.x, lane = lane_id();
+  const unsigned long long v0 = any;
+  unsigned long long diff = 0ull;
+  for_each_member(M, [&](unsigned long long x) { diff |= x ^ v0; });
+  int top = diff ? 63 - __clzll(static_cast<long long>(diff)) : -1;
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) {
+    const int other = __shfl_xor(top, o);
+    top = other > top ? other : top;
+  }
+  if (lane == 0) sh.scan[t >> 6] = static_cast<uint32_t>(top + 1);
+  hist[t] = 0u; hist[256u + t] = 0u; hist[512u + t] = 0u;
+  __syncthreads();
+  {
+    const uint32_t a = sh.scan[0], b = sh.scan[1], c = sh.scan[2], d = sh.scan[3];
+    const uint32_t ab = a > b ? a : b, cd = c > d ? c : d;
+    top = static_cast<int>(ab > cd ? ab : cd) - 1;
+  }
+  if (top < 0) return v0;                                   // a single value
+  int shift = (top >> 3) << 3;
+  unsigned long long prefix = shift == 56 ? 0ull : (v0 & (~0ull << (shift + 8)));
+  for (uint32_t pass = 0;; ++pass, shift -= 8) {
+    uint32_t* const H = hist + (pass % 3u) * 256u;
+    const unsigned long long himask = shift == 56 ? 0ull : (~0ull << (shift + 8));
+    for_each_member(M, [&](unsigned long long x) {
+      if ((x & himask) == prefix) atomicAdd(&H[static_cast<uint32_t>(x >> shift) & 255u], 1u);
+    });
+    __syncthreads();
+    hist[((pass + 2u) % 3u) * 256u + t] = 0u;
+    const uint32_t h0 = H[4u * lane], h1 = H[4u * lane + 1u], h2 = H[4u * lane + 2u], h3 = H[4u * lane + 3u];
+    const uint32_t mine = h0 + h1 + h2 + h3;
+    const uint32_t incl = wave_incl_scan(mine);
+    const uint32_t higher = wave_total(incl) - incl;
+    const bool here = higher < kk && kk <= higher + mine;
+    uint32_t bin = 0, above = 0, cnt = 0;
+    if (here) {
+      uint32_t a = higher;
+      if (kk <= a + h3) { bin = 3u; cnt = h3; }
+      else { a += h3; if (kk <= a + h2) { bin = 2u; cnt = h2; }
+      else { a += h2; if (kk <= a + h1) { bin = 1u; cnt = h1; }
+      else { a += h1; bin = 0u; cnt = h0; } } }
+      bin += 4u * lane;
+      above = a;
+    }
+    const unsigned long long who = __ballot(here);          // exactly one lane when 1 <= kk <= values in scope
+    const int src = who ? static_cast<int>(__ffsll(static_cast<long long>(who))) - 1 : 0;
+    bin = static_cast<uint32_t>(__shfl(static_cast<int>(bin), src));
+    above = static_cast<uint32_t>(__shfl(static_cast<int>(above), src));
+    cnt = static_cast<uint32_t>(__shfl(static_cast<int>(cnt), src));
+    prefix |= static_cast<unsigned long long>(bin) << shift;
+    kk -= above;
+    if (shift == 0) return prefix;                          // the composites are distinct: this is the value itself
+    if (cnt <= 1u) break;
+  }
+  // one value is left under these leading bytes: whoever holds it tells the others
+  const unsigned long long lomask = ~0ull << shift;
+  for_each_member(M, [&](unsigned long long x) {
+    if ((x & lomask) == prefix) { sh.hbin = static_cast<uint32_t>(x); sh.hcum = static_cast<uint32_t>(x >> 32); }
+  });
+  __syncthreads();
+  const unsigned long long r = (static_cast<unsigned long long>(sh.hcum) << 32) | sh.hbin;
+  __syncthreads();
+  return r;
+}
+
+}  // namespace
+
+// Launch 2 of a call with two-pass layers: PH_SEL for the layers whose probe pass found the k-th key in its
+// lists.  Every wave takes its own wave-chunk's list; the layer's last workgroup ranks the members of the k-th
+// key's coarse bin (in global memory: there may be more of them than one workgroup's LDS holds), credits the
+// selected ones to their wave-chunks, scans the group sums into offsets and schedules the emit pass.
+__global__ void __launch_bounds__(kBlockThreads) rank_kernel(CompressArgs A) {
+  __shared__ ResolveShared sh;
+  __shared__ __attribute__((aligned(16))) uint32_t sel_hist[3 * 256];
+  __shared__ uint32_t shard_first[kMemberShards + 1];
+  const uint32_t wg = blockIdx.x;
+  const uint32_t l = A.wg2layer[wg];
+  LayerState* st = A.state + l;
+  if (st->next_launch != A.launch || st->next_phase != PH_SEL2) return;
+  const LayerDesc L = A.layers[l];
+  const uint32_t tau = st->tau, shift = st->shift, bstar = st->bstar;
+  unsigned long long* const region = A.members2 + L.mem_first;
+  const uint32_t shard_cap = L.mem_cap / kMemberShards;
+  const uint32_t lane = lane_id();
+  const uint32_t wc_local = (wg - L.wg_first) * kWavesPerBlock + (threadIdx.x >> 6);
+  if (threadIdx.x == 0) sh.hcnt = 0u;              // what this workgroup's lists add to their offset group
+  __syncthreads();
+  if (wc_local < L.wc_count) {
+    const uint32_t wc = L.wc_first + wc_local;
+    const uint32_t cnt = A.cand_cnt[wc];               // (<= cap2: the probe's resolve step has checked)
+    const uint2* slot = A.slots2 + static_cast<size_t>(wc) * A.cap2;
+    // One walk through the list, eight entries of a lane on their way at a time (the list is a few hundred
+    // entries long and every round trip counts).  A lane keeps the first two members it meets; the wave then
+    // appends all its members with ONE atomic, and only a wave in which some lane met more walks again.
+    uint32_t hi = 0, nm = 0;
+    unsigned long long keep0 = 0ull, keep1 = 0ull;
+    constexpr uint32_t kBatch = 8;
+    for (uint32_t p0 = 0; p0 < cnt; p0 += kBatch * kWaveSize) {
+      uint2 e[kBatch];
+#pragma unroll
+      for (uint32_t j = 0; j < kBatch; ++j) {
+        const uint32_t p = p0 + j * kWaveSize + lane;
+        e[j] = p < cnt ? slot[p] : make_uint2(0u, 0u);
+      }
+#pragma unroll
+      for (uint32_t j = 0; j < kBatch; ++j) {
+        if (p0 + j * kWaveSize + lane < cnt) {
+          const uint32_t key = key_of(e[j].x, A.sign_xor, A.sign_filter);
+          const uint32_t bin = coarse_bin(key, tau, shift);
+          hi += bin > bstar ? 1u : 0u;
+          if (bin == bstar) {
+            const unsigned long long c = composite(key, e[j].y);
+            if (nm == 0u) keep0 = c; else if (nm == 1u) keep1 = c;
+            ++nm;
+          }
+        }
+      }
+    }
+    const uint32_t nm_incl = wave_incl_scan(nm);
+    const uint32_t nm_all = wave_total(nm_incl);
+    if (nm_all != 0u) {
+      const uint32_t shard = wc_local % kMemberShards;
+      uint32_t base = 0;
+      if (lane == 0) base = atomicAdd(&A.shard_cnt[(static_cast<size_t>(l) * kMemberShards + shard) * kShardStride], nm_all);
+      base = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(base)));
+      if (base + nm_all > shard_cap) {
+        if (lane == 0) atomicOr(&st->shard_overflow, 1u);   // the layer is streamed after all (see below)
+      } else {
+        unsigned long long* out = region + static_cast<size_t>(shard) * shard_cap + base + (nm_incl - nm);
+        if (__ballot(nm > 2u) == 0ull) {
+          if (nm >= 1u) __hip_atomic_store(out, keep0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          if (nm >= 2u) __hip_atomic_store(out + 1, keep1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+          for (uint32_t p = lane; p < cnt; p += kWaveSize) {
+            const uint2 e = slot[p];
+            const uint32_t key = key_of(e.x, A.sign_xor, A.sign_filter);
+            if (coarse_bin(key, tau, shift) == bstar)
+              __hip_atomic_store(out++, composite(key, e.y), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
+        }
+      }
+    }
+    // the candidates above the listed band are all selected
+    const uint32_t hi_all = wave_total(wave_incl_scan(hi)) + A.wc_c[wc];
+    if (lane == 0) {
+      st_agent(&A.wc_a[wc], hi_all);
+      if (hi_all) atomicAdd(&sh.hcnt, hi_all);
+    }
+  }
+  // one device-scope atomic per workgroup (its four wave-chunks lie in one offset group)
+  __syncthreads();
+  if (threadIdx.x == 0 && sh.hcnt != 0u)
+    atomicAdd(&A.wc_b[L.wc_first + ((wg - L.wg_first) * kWavesPerBlock) / kOffsetGroup], sh.hcnt);
+  if (!last_block_of_layer(&st->done, A.group_done + L.grp_first, wg - L.wg_first, L.wg_count, &sh.flag)) return;
+
+  if (threadIdx.x == 0) {
+    uint32_t run = 0;
+    for (uint32_t s = 0; s < kMemberShards; ++s) {
+      const uint32_t c = ld_agent(&A.shard_cnt[(static_cast<size_t>(l) * kMemberShards + s) * kShardStride]);
+      shard_first[s] = run;
+      run += c < shard_cap ? c : shard_cap;
+    }
+    shard_first[kMemberShards] = run;
+  }
+  __syncthreads();
+  const uint32_t m = shard_first[kMemberShards];
+  const uint32_t k_rem = st->k_rem;
+  if (ld_agent(&st->shard_overflow) != 0u || k_rem == 0u || k_rem > m) {
+    // A sub-list ran over (the members crowd in a few wave-chunks), or the lists and the histogram disagree (a bug,
+    // flagged).  Nothing of the layer has been written yet: it is streamed by the next launch and goes on hint-free.
+    if (threadIdx.x == 0) {
+      if (ld_agent(&st->shard_overflow) == 0u) atomicOr(A.errflag, 32u);
+      st->path = 2u;
+      st->stat_misses += 1u;
+      const uint32_t wait = st->probe_backoff ? 2u * st->probe_backoff : 1u;
+      st->probe_backoff = wait < kProbeBackoffMax ? wait : kProbeBackoffMax;
+      st->probe_skip = st->probe_backoff + 1u;
+      st->next_phase = PH_STREAM;
+      st->next_launch = A.launch + 1u;
+    }
+    return;
+  }
+  MemberLists M{region, shard_cap, shard_first};
+  unsigned long long any = 0ull;
+  for (uint32_t s = 0; s < kMemberShards; ++s)
+    if (shard_first[s + 1] != shard_first[s]) { any = __hip_atomic_load(&region[static_cast<size_t>(s) * shard_cap], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); break; }
+  const unsigned long long thr = select_kth_largest_global(M, any, k_rem, sel_hist, sh);
+  // members not below thr are selected: credit them to their wave-chunks and to the chunks' groups
+  // (the groups' credits are counted in LDS where the groups fit, as in PH_SEL: their counters share a few cache lines)
+  const uint32_t groups = (L.wc_count + kOffsetGroup - 1u) / kOffsetGroup;
+  const bool in_lds = groups <= 3u * kBlockThreads;
+  __syncthreads();                                  // every wave is done with the selection's histograms
+  if (in_lds) {
+    sel_hist[threadIdx.x] = 0u; sel_hist[kBlockThreads + threadIdx.x] = 0u; sel_hist[2u * kBlockThreads + threadIdx.x] = 0u;
+    __syncthreads();
+  }
+  for_each_member(M, [&](unsigned long long x) {
+    if (x < thr) return;
+    const uint32_t idx = 0xFFFFFFFFu - static_cast<uint32_t>(x & 0xFFFFFFFFull);
+    const uint32_t c = idx / A.chunk;
+    atomicAdd(&A.wc_a[L.wc_first + c], 1u);
+    if (in_lds) atomicAdd(&sel_hist[c / kOffsetGroup], 1u);
+    else atomicAdd(&A.wc_b[L.wc_first + c / kOffsetGroup], 1u);
+  });
+  __syncthreads();
+  if (in_lds) {
+    for (uint32_t g = threadIdx.x; g < groups; g += kBlockThreads)
+      if (sel_hist[g] != 0u) atomicAdd(&A.wc_b[L.wc_first + g], sel_hist[g]);
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the credits are device-scope atomics
+  __syncthreads();
+  scan_chunks(A.wc_b + L.wc_first, nullptr, groups, 0u, false, sh.scan, &sh.cnt);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    if (sh.cnt != L.k) atomicOr(A.errflag, 64u);
+    const uint32_t T = static_cast<uint32_t>(thr >> 32);
+    st->thr = thr;
+    st->T = T;
+    if (A.update_hints) {
+      const uint32_t tn = st->tau_next <= T ? st->tau_next : T;
+      st->tau = drifted_tau(tn, T, st->T_prev, st->has_prev != 0u);
+      st->shift = shift_for(T, tn);
+      st->clip = clip_for(T, tn, st->shift);
+      st->probe_backoff = 0u;            // the probe pass did its job
+      st->hint_valid = 1u;
+      st->T_prev = T;
+      st->has_prev = 1u;
+    }
+    st->next_phase = PH_EMIT;
+    st->next_launch = A.launch + 1u;
+  }
+}
+
+// Second pass of a two-pass layer (launch 3, after PH_SEL): the composite of the k-th entry is known, so an
+// element is sent if and only if its composite (key, then lower index first) is not below it.
+__global__ void __launch_bounds__(kBlockThreads) emit_kernel(CompressArgs A) {
+  // against the direction of the probe pass: what that pass read last is still in the memory-side cache
+  const uint32_t wg = A.reverse ? blockIdx.x : gridDim.x - 1u - blockIdx.x;
+  const uint32_t l = A.wg2layer[wg];
+  LayerState* st = A.state + l;
+  if (st->next_launch != A.launch || st->next_phase != PH_EMIT) return;
+  const LayerDesc L = A.layers[l];
+  const uint32_t wc_local = (wg - L.wg_first) * kWavesPerBlock + (threadIdx.x >> 6);
+  if (wc_local >= L.wc_count) return;
+  const unsigned long long thr = st->thr;
+  const uint32_t lane = lane_id();
+  // the first output position of this wave-chunk: the offset of its group of kOffsetGroup wave-chunks (wc_b)
+  // plus the selected entries of the group's chunks before it (wc_a), as in PH_OUT_C
+  uint32_t out_pos;
+  {
+    const uint32_t grp = wc_local / kOffsetGroup;
+    const uint32_t c = grp * kOffsetGroup + lane;
+    const uint32_t mine = c < L.wc_count ? A.wc_a[L.wc_first + c] : 0u;
+    const uint32_t excl = wave_incl_scan(mine) - mine + A.wc_b[L.wc_first + grp];
+    out_pos = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(excl),
+                                                              static_cast<int>(__builtin_amdgcn_readfirstlane(wc_local % kOffsetGroup))));
+  }
+  const uint32_t begin = wc_local * A.chunk;
+  const uint32_t end = (L.n - begin) < A.chunk ? L.n : begin + A.chunk;
+  const bool clear_mom = (L.mom != nullptr) && A.mask_momentum;
+  const bool has_mom = L.mom != nullptr;
+  const gptr<int32_t> out_idx = as_global(L.out_idx);
+  const gptr<float> out_val = as_global(L.out_val);
+  const gptr<float> resid = as_global(L.resid);
+  const gptr<float> mom = as_global(L.mom);
+  recompute_chunk_any(A, L, begin, end, [&](const float (&a)[4], const float (&u)[4], uint32_t nvalid, uint32_t idx0, bool vec) {
+    bool sel[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      sel[j] = (static_cast<uint32_t>(j) < nvalid) &&
+               composite(key_of(fbits(a[j]), A.sign_xor, A.sign_filter), idx0 + j) >= thr;
+    const unsigned long long s0 = __ballot(sel[0]), s1 = __ballot(sel[1]), s2 = __ballot(sel[2]), s3 = __ballot(sel[3]);
+    if ((s0 | s1 | s2 | s3) != 0ull) {
+      uint32_t pos = out_pos + rank_below(s0) + rank_below(s1) + rank_below(s2) + rank_below(s3);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (sel[j]) {
+          if (pos < L.k) {   // always true when the counts are consistent
+            out_idx[pos] = static_cast<int32_t>(idx0 + j);
+            out_val[pos] = a[j];
+          }
+          ++pos;
+        }
+      }
+      out_pos += popc64(s0) + popc64(s1) + popc64(s2) + popc64(s3);
+    }
+    float v[4], w[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      v[j] = sel[j] ? 0.0f : a[j];
+      w[j] = (sel[j] && clear_mom) ? 0.0f : u[j];
+    }
+    if (vec) {
+      *reinterpret_cast<gptr<vf4>>(resid + idx0) = vf4{v[0], v[1], v[2], v[3]};
+      if (has_mom) *reinterpret_cast<gptr<vf4>>(mom + idx0) = vf4{w[0], w[1], w[2], w[3]};
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (static_cast<uint32_t>(j) < nvalid) {
+          resid[idx0 + j] = v[j];
+          if (has_mom) mom[idx0 + j] = w[j];
+        }
+      }
+    }
+  });
+  if (wc_local == 0 && lane == 0) *as_global(L.out_count) = static_cast<int32_t>(L.k);
+}
+
 // Overwrite the cached thresholds with wrong values (test hook: results must not change).
 __global__ void poison_kernel(LayerState* st, uint32_t num_layers, int mode) {
   const uint32_t l = blockIdx.x * blockDim.x + threadIdx.x;
@@ -1357,6 +1921,21 @@ hipError_t launch_message_means(const CompressArgs& a, uint32_t num_layers, uint
 
 hipError_t launch_accumulate(const CompressArgs& a, uint32_t num_wgs, hipStream_t s) {
   hipLaunchKernelGGL(accumulate_kernel, dim3(num_wgs), dim3(kBlockThreads), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_probe(const CompressArgs& a, uint32_t num_wgs, hipStream_t s) {
+  hipLaunchKernelGGL(probe_kernel, dim3(num_wgs), dim3(kBlockThreads), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_rank(const CompressArgs& a, uint32_t num_wgs, hipStream_t s) {
+  hipLaunchKernelGGL(rank_kernel, dim3(num_wgs), dim3(kBlockThreads), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_emit(const CompressArgs& a, uint32_t num_wgs, hipStream_t s) {
+  hipLaunchKernelGGL(emit_kernel, dim3(num_wgs), dim3(kBlockThreads), 0, s, a);
   return hipGetLastError();
 }
 

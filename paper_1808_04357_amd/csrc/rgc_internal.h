@@ -29,7 +29,18 @@ enum Phase : uint32_t {
   PH_COUNT = 6,    // multi-pass: per wave-chunk counts of keys > T and == T
   PH_OUT_V = 7,    // multi-pass: ordered compaction from the updated residual
   PH_COLLECT = 8,  // after the first digit: candidate lists from the updated residual, then PH_SEL / PH_OUT_C
+  PH_STREAM = 9,   // two-pass layers whose probe pass missed: the ordinary streaming pass after all (launch 2)
+  PH_EMIT = 10,    // two-pass layers: the second pass writes residual, velocity and message with the threshold known
+  PH_SEL2 = 11,    // two-pass layers: PH_SEL on the probe pass's lists (rank_kernel)
 };
+
+// Two-pass layers: after a probe pass that missed, the layer goes without one for a number of calls that
+// doubles with every further miss, up to this many.
+constexpr uint32_t kProbeBackoffMax = 64;
+// Two-pass layers: the members of the k-th key's coarse bin are appended to this many sub-lists, each with a counter
+// of its own (thousands of waves appending through one counter take their turns at ~20 ns each).
+constexpr uint32_t kMemberShards = 16;
+constexpr uint32_t kShardStride = 64;    // words between two counters: atomics on one cache line take their turns like atomics on one word
 
 // Per call, per layer descriptor (device copy of the caller's rgc_layer plus the tiling).
 struct LayerDesc {
@@ -47,10 +58,14 @@ struct LayerDesc {
   uint32_t wg_count;   // = ceil(wc_count / 4)
   uint32_t grp_first;  // first election-group counter of this layer
   uint32_t vec_ok;     // every tensor pointer is 16-byte aligned
-  uint32_t hintable;   // candidate lists are large enough for k + margin at this density
+  uint32_t hintable;   // one-pass layer: the candidate lists can hold every element from the hinted threshold upwards
   uint32_t margin;     // extra candidates aimed for beyond k
   uint32_t cmax;       // largest candidate total a hint may aim at
-  uint32_t pad_;
+  uint32_t target;     // rank the next call's threshold hint is aimed at (2k + margin, two-pass layers: k + margin)
+  uint32_t two_pass;   // high-density layer: a read-only probe pass lists only the keys around the hinted threshold,
+                       // the second pass applies the exact threshold (never set together with hintable)
+  uint32_t mem_cap;    // two-pass layers: entries of the layer's region of the member pool (a multiple of kMemberShards)
+  uint64_t mem_first;  // ... and where the region starts
 };
 
 // Per layer state living in the context (device memory).  Everything but the hint fields is
@@ -78,6 +93,12 @@ struct LayerState {
   uint32_t stat_candidates;  // diagnostics of the last call
   uint32_t stat_members;
   uint32_t stat_misses;      // calls so far in which this layer's hint missed (never reset)
+  // two-pass layers (speed only, like the hints)
+  uint32_t clip;             // the probe pass lists the candidates of the coarse bins below this one
+  uint32_t probe_backoff;    // calls the layer went without a probe pass after the last miss
+  uint32_t probe_skip;       // calls it still goes without one
+  uint32_t shard_overflow;   // a member sub-list ran over in this call's ranking launch
+  uint32_t pad_[3];
 };
 
 struct CompressArgs {
@@ -91,6 +112,11 @@ struct CompressArgs {
   uint2* slots;          // [wave-chunks][cap] (float bits, index), ascending index per chunk
   uint32_t* wc_a;        // [wave-chunks] counts, then output offsets
   uint32_t* wc_b;        // [wave-chunks] tie counts, then tie prefixes
+  uint32_t* wc_c;        // [wave-chunks] two-pass layers: candidates of the probe pass above the listed band
+  uint2* slots2;         // [wave-chunks][cap2] the probe pass's lists (allocated when a two-pass layer is first seen)
+  uint32_t cap2;         // slots per wave-chunk in slots2
+  unsigned long long* members2;  // member pool of the two-pass layers (LayerDesc::mem_first, mem_cap)
+  uint32_t* shard_cnt;   // [layers][kMemberShards][kShardStride] members appended to each sub-list, one counter per 256 bytes
   uint32_t* group_done;  // [election groups] workgroups of the group that finished the current phase
   uint32_t* errflag;     // set non-zero on an internal inconsistency
   uint32_t chunk;        // elements per wave-chunk (multiple of 256)
@@ -193,6 +219,9 @@ int fail_hip(hipError_t e, const char* what);
 
 // kernel launchers (defined in the .hip files)
 hipError_t launch_accumulate(const CompressArgs& a, uint32_t num_wgs, hipStream_t s);
+hipError_t launch_probe(const CompressArgs& a, uint32_t num_wgs, hipStream_t s);
+hipError_t launch_rank(const CompressArgs& a, uint32_t num_wgs, hipStream_t s);
+hipError_t launch_emit(const CompressArgs& a, uint32_t num_wgs, hipStream_t s);
 hipError_t launch_phase(const CompressArgs& a, uint32_t num_wgs, hipStream_t s);
 constexpr uint32_t kMeanPartsMax = 1024;   // partial sums per layer at most (rgc_message_means)
 hipError_t launch_message_means(const CompressArgs& a, uint32_t num_layers, uint32_t max_k, double* d_part,
