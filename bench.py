@@ -11,7 +11,7 @@ from step to step (steady-state RGC) while the gradient rotates through 4 pre-ge
 
 Prints ONE JSON line: `value` = gradient bytes through the whole step per second (wall-clock mean of the K
 timed steps); `compress`, `decompress`, `local_clipping`, `alternating_signs`, `threshold_search`,
-`warmup_densities` and `other_workloads` time the parts and the variants; `roofline` is the streaming
+`threshold_to_decompress`, `warmup_densities` and `other_workloads` time the parts and the variants; `roofline` is the streaming
 accumulate kernel against the HBM peak, timed with HIP events inside the timed steps; `cpu_baseline` is the CPU
 oracle timed on the same step.
 """
@@ -29,6 +29,16 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 NUM_GRAD_SETS = 4
+
+
+def kernel_source_digest():
+    """sha256 over the kernel sources of the compression path: what profiles/hbm_traffic.json is stamped with."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in ("rgc_compress.hip", "rgc_device.h", "rgc_internal.h"):
+        with open(os.path.join(ROOT, "paper_1808_04357_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
 
 
 def log(*a):
@@ -133,6 +143,56 @@ def measure_threshold(torch, rgc, ctx, wl, stream, steps, dev):
             "reuse_call_alg_bytes": wl.alg_bytes_stream}
 
 
+def measure_threshold_flow(torch, rgc, ctx, wl, dec, stream, steps, dev):
+    """Threshold binary search selection feeding decompression (Sections 2.1 + 2.3): the messages' lengths vary from
+    step to step, and rgc_msg.count is a host value, so every step runs the selection (a search every fifth step),
+    brings the 16 length elements to the host (a synchronisation), and decompresses 128 workers' messages of which
+    worker 0's are the ones just produced (the other 127 are the fixed synthetic ones).  Reported: the whole step,
+    how long the host waits for the lengths, and how long the decompression call keeps the host (its descriptor
+    tables are rebuilt and uploaded whenever a length changes)."""
+    L = len(wl.sizes)
+    out_idx2 = [torch.empty(2 * k, dtype=torch.int32, device=dev) for k in wl.ks]
+    out_val2 = [torch.empty(2 * k, dtype=torch.float32, device=dev) for k in wl.ks]
+    count = torch.zeros(L, dtype=torch.int32, device=dev)
+    lists2 = [rgc.LayerList(g, wl.V, wl.ks, out_idx2, out_val2, count, wl.U) for g in wl.G]
+    thr = torch.zeros(L, dtype=torch.float32, device=dev)
+    host_count = torch.zeros(L, dtype=torch.int32).pin_memory()
+    d_idx = [list(row) for row in dec.d_idx]
+    d_val = [list(row) for row in dec.d_val]
+    d_idx[0], d_val[0] = out_idx2, out_val2
+    msgs = rgc.MessageList(d_idx, d_val, dec.dense)
+    calls = [0]
+    wait_ms, host_ms = [], []
+
+    def step():
+        rgc.rgc_compress_layers_threshold(ctx, lists2[calls[0] % len(lists2)], wl.m, thr, None,
+                                          rgc.RGC_THRESHOLD_SEARCH if calls[0] % 5 == 0 else 0, stream)
+        calls[0] += 1
+        t0 = time.perf_counter()
+        host_count.copy_(count, non_blocking=True)
+        stream.synchronize()
+        t1 = time.perf_counter()
+        for l in range(L):
+            msgs.msgs[l].count = int(host_count[l])
+        t2 = time.perf_counter()
+        rgc.rgc_decompress_accumulate(ctx, msgs, dec.scale, rgc.RGC_OVERWRITE, stream)
+        t3 = time.perf_counter()
+        wait_ms.append((t1 - t0) * 1e3)
+        host_ms.append((t3 - t2) * 1e3)
+
+    for _ in range(10):
+        step()
+    del wait_ms[:], host_ms[:]
+    reps = 5 * max(1, min(steps, 50) // 5)
+    ms = time_loop(torch, step, reps)
+    sent = int(host_count.sum())
+    return {"ms_per_step": ms, "steps": reps, "gradient_GBps": 4.0 * wl.total / ms / 1e6,
+            "host_waits_for_lengths_ms": sum(wait_ms) / len(wait_ms),
+            "decompress_call_host_ms": sum(host_ms) / len(host_ms),
+            "decompress_call_host_ms_max": max(host_ms),
+            "sent_over_k_last_step": sent / float(sum(wl.ks))}
+
+
 def measure_compress(torch, rgc, ctx, wl, stream, steps, warmup):
     """Steady-state ms/iter plus first-call and hint-free timings of one compress workload."""
     out = {"elements": wl.total, "tensors": len(wl.sizes), "sum_k": sum(wl.ks)}
@@ -176,6 +236,15 @@ def measure_compress(torch, rgc, ctx, wl, stream, steps, warmup):
     out["phase_launches_ms"] = ms4[1] / max(calls[0], 1)
     out["layers_off_one_pass_path_per_iter"] = slow / psteps
     out["hint_free_ms"] = time_loop(torch, lambda: wl.step(ctx, stream, rgc.RGC_NO_HINTS), 3)
+    # a call whose hints all miss (thresholds set far too high before every call: the streaming pass collects too
+    # few candidates, notices, and every layer takes the multi-pass path on the updated residual)
+
+    def forced_miss():
+        ctx.poison_hints(0, stream)
+        wl.step(ctx, stream)
+
+    out["forced_miss_ms"] = time_loop(torch, forced_miss, 5)
+    out["forced_miss_layers_on_fallback"] = sum(1 for p in ctx.last_paths(len(wl.sizes), stream) if p == 2)
     return out
 
 
@@ -272,8 +341,11 @@ def main():
         vgg.step(ctx, stream)
         dec.step(ctx, stream)
 
-    # ---- headline: whole step, inputs resident, W warmup + exactly K timed steps
-    for _ in range(args.warmup):
+    # ---- headline: whole step, inputs resident, W warmup + exactly K timed steps.  The threshold hints take a few
+    # dozen calls to settle after a context is created (see measure_compress): at least 40 untimed steps,
+    # whatever --warmup says; the hint misses that still fall into the timed steps are reported.
+    settle = max(args.warmup, 40)
+    for _ in range(settle):
         step()
     ms_step_plain = time_loop(torch, step, args.steps)   # the same loop without the library's events (reported beside)
     # the timed region: the library records HIP events around its kernels on the caller's stream,
@@ -318,13 +390,17 @@ def main():
                 "traffic": None, "bytes_per_launch": vgg.alg_bytes_stream, "avg_launch_ms": k_ms}
     # HBM bytes per launch of that kernel as counted by rocprofv3 (FETCH_SIZE + WRITE_SIZE, scaled by a
     # copy of known size): a counter run cannot share a process with the timed run, so the figure
-    # comes from the committed summary of the same command; null if that file is not there
+    # comes from the committed summary of the same command -- and only while the kernel sources are the
+    # ones it was taken with (the file names their digest); otherwise null
     try:
-        with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic.json")) as f:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
             t = json.load(f)
-        roofline["traffic"] = t["fetch_bytes_per_launch"] + t["write_bytes_per_launch"]
-        roofline["traffic_source"] = t["source"]
-        roofline["frac_measured_traffic"] = roofline["traffic"] / (k_ms * 1e-3) / (HBM_PEAK_GBPS * 1e9)
+        if t.get("kernel_source_sha256") == kernel_source_digest():
+            roofline["traffic"] = t["fetch_bytes_per_launch"] + t["write_bytes_per_launch"]
+            roofline["traffic_source"] = t["source"]
+            roofline["frac_measured_traffic"] = roofline["traffic"] / (k_ms * 1e-3) / (HBM_PEAK_GBPS * 1e9)
+        else:
+            roofline["traffic_source"] = "profiles/hbm_traffic.json was taken with other kernel sources: not used"
     except (OSError, ValueError, KeyError):
         pass
 
@@ -374,6 +450,10 @@ def main():
     if not args.step_only:
         tbs_info = measure_threshold(torch, rgc, ctx, vgg, stream, args.steps, dev)
 
+    flow_info = None
+    if not args.step_only:
+        flow_info = measure_threshold_flow(torch, rgc, ctx, vgg, dec, stream, args.steps, dev)
+
     # The densities of a warm-up period (Section 2.5: 25 %, 6.25 %, 1.5625 %, 0.4 % before 0.1 %) on the same
     # tensors: message buffers of their own, residual and velocity shared with the headline workload
     warm_info = None
@@ -390,14 +470,16 @@ def main():
                 rgc.rgc_compress_layers(ctx, lists[calls[0] % len(lists)], vgg.m, 0, stream)
                 calls[0] += 1
 
-            for _ in range(10):
+            for _ in range(16):                           # the two-pass path's hints settle within a few calls
                 warm_step()
+            misses0 = sum(r[4] for r in ctx.last_stats(len(vgg.sizes), stream))
             ms = time_loop(torch, warm_step, min(args.steps, 20))
             alg = vgg.alg_bytes_stream + 16 * sum(ks)
             warm_info["%g%%" % (ppm / 1e4)] = {
                 "sum_k": sum(ks), "ms_per_iter": ms, "alg_bytes": alg,
                 "hbm_frac_algorithmic": alg / (ms * 1e-3) / (HBM_PEAK_GBPS * 1e9),
-                "layers_off_one_pass_path": sum(1 for p in ctx.last_paths(len(vgg.sizes), stream) if p != 0)}
+                "hint_misses_in_timed_calls": sum(r[4] for r in ctx.last_stats(len(vgg.sizes), stream)) - misses0,
+                "layers_on_multi_pass_path_last_call": sum(1 for p in ctx.last_paths(len(vgg.sizes), stream) if p != 0)}
             del lists, oi, ov
         torch.cuda.empty_cache()
 
@@ -418,6 +500,23 @@ def main():
             others[name] = measure_compress(torch, rgc, ctx, wl, stream, args.steps, args.warmup)
             if name == "lstm":      # the paper selects the large layers of its recurrent models this way
                 others[name]["threshold_search"] = measure_threshold(torch, rgc, ctx, wl, stream, args.steps, dev)
+                # the whole step on this layer set too: compression + decompression of 128 workers' messages
+                ldec = DecompressWorkload(torch, rgc, wl.sizes, 128, dev, synth)
+
+                def lstm_step():
+                    wl.step(ctx, stream)
+                    ldec.step(ctx, stream)
+
+                for _ in range(40):
+                    lstm_step()
+                ms_l = time_loop(torch, lstm_step, args.steps)
+                ms_ld = time_loop(torch, lambda: ldec.step(ctx, stream), args.steps)
+                lbytes = wl.alg_bytes + ldec.alg_bytes
+                others[name]["step"] = {"ms_per_step": ms_l, "gradient_GBps": 4.0 * wl.total / ms_l / 1e6,
+                                        "alg_bytes": lbytes,
+                                        "hbm_frac_step_algorithmic": lbytes / (ms_l * 1e-3) / (HBM_PEAK_GBPS * 1e9),
+                                        "decompress_alone_ms": ms_ld, "decompress_entries": ldec.entries}
+                del ldec
             del wl
             torch.cuda.empty_cache()
 
@@ -438,11 +537,12 @@ def main():
         "hbm_frac_step_algorithmic": step_bytes / (ms_step * 1e-3) / (HBM_PEAK_GBPS * 1e9),
         "ms_per_step_without_kernel_events": ms_step_plain,
         "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
-        "hint_misses_in_timed_steps": step_misses,
+        "hint_misses_in_timed_steps": step_misses, "untimed_steps_before": settle,
         "step_kernels_ms": {"accumulate_kernel": step_ms4[0] / max(step_calls[0], 1),
                             "phase_launches": step_ms4[1] / max(step_calls[0], 1),
                             "decompress_tiles_kernel": step_ms4[3] / max(step_calls[1], 1)},
         "compress": comp, "decompress": dec_info, "local_clipping": clip_info, "alternating_signs": asq_info, "threshold_search": tbs_info,
+        "threshold_to_decompress": flow_info,
         "warmup_densities": warm_info, "other_workloads": others,
         "roofline": roofline, "cpu_baseline": cpu,
     }

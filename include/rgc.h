@@ -27,8 +27,8 @@
  * rgc_message_means, rgc_clip_coefficient and rgc_decompress_accumulate may therefore be
  * recorded into a HIP graph on a capturing stream and replayed: all that changes
  * from step to step (residual, velocity, hints, per-layer state) is device memory.  The calls
- * that copy results to the host (rgc_last_paths, rgc_last_stats, rgc_decompress_status,
- * rgc_selftest, rgc_profile_read) and the event timing of rgc_profile_enable are not for capture.
+ * that copy results to the host (rgc_last_error, rgc_decompress_status and the diagnostics of
+ * rgc_diag.h) are not for capture.
  */
 #ifndef RGC_H_
 #define RGC_H_
@@ -210,7 +210,8 @@ int rgc_compress_layers_threshold(rgc_ctx* ctx, const rgc_layer* layers, int32_t
                                   int32_t* nnz, uint32_t flags, void* hip_stream);
 
 /* Local gradient clipping (Section 2.4: the gradients of all layers are clipped by their common
- * norm before they are added to the residuals, with a threshold of N^(-1/2) of the original one).
+ * norm before they are added to the residuals; with N workers the clipping threshold shrinks by the
+ * factor sqrt(N)).
  * Enqueues two small kernels that read layers[l].grad of every layer (only grad and n are used) and
  * store  c = norm > t ? t / norm : 1,  t = max_norm / sqrt(num_workers),  norm = the L2 norm over
  * all elements of all layers (squares and sums in fp64, a fixed order of additions), into
@@ -241,40 +242,15 @@ int rgc_decompress_accumulate(rgc_ctx* ctx, const rgc_msg* msgs, int32_t num_wor
  * messages met the precondition) and clears the word.  Errors: RGC_EINVAL, RGC_EHIP. */
 int rgc_decompress_status(rgc_ctx* ctx, uint32_t* out_status, void* hip_stream);
 
-/* Speed-hint control (never changes results).  rgc_reset_hints forgets every cached
- * threshold, so the next call behaves like a first call.  rgc_poison_hints overwrites the
- * cached thresholds with deliberately wrong values (mode 0: far too high, 1: far too low,
- * 2: pseudo-random) -- a test hook proving that results do not depend on them. */
+/* Forget every cached threshold hint, so that the next call behaves like a first call (never changes
+ * results). */
 int rgc_reset_hints(rgc_ctx* ctx);
-int rgc_poison_hints(rgc_ctx* ctx, int mode, void* hip_stream);
 
-/* Runs a one-workgroup kernel that checks the wave64 primitives the kernels rely on (DPP
- * prefix scan, ballot ranks) against values computed on the host.  Synchronises `hip_stream`.
- * Returns RGC_OK, RGC_EINTERNAL on a mismatch, or RGC_EHIP. */
-int rgc_selftest(rgc_ctx* ctx, void* hip_stream);
-
-/* Copies per-layer path statistics of the LAST compression call into `out` (host memory,
- * int32[num_layers]): 0 = one-pass hinted path, 1 = hint-free multi-pass path, 2 = hinted
- * pass missed and the multi-pass path re-ran on the updated residual.  Synchronises
- * `hip_stream`.  Returns RGC_EINTERNAL if any kernel of an earlier call flagged an internal
- * inconsistency.  A diagnostic for tests and benchmarks. */
-int rgc_last_paths(rgc_ctx* ctx, int32_t* out, int32_t num_layers, void* hip_stream);
-
-/* Like rgc_last_paths with more detail: out is int64[num_layers][5] = { path, number of
- * candidates the streaming pass collected (0 on the hint-free path), number of candidates that
- * had to be ranked exactly, magnitude key (float bits, sign cleared) of the k-th entry, number
- * of calls since rgc_create in which this layer slot's hint missed (path 2) }. */
-int rgc_last_stats(rgc_ctx* ctx, int64_t* out, int32_t num_layers, void* hip_stream);
-
-/* Kernel timing for benchmarks.  rgc_profile_enable(ctx, 1) makes every later compression and
- * decompression call record HIP events on the caller's stream around its kernels (a few extra
- * microseconds per call); rgc_profile_enable(ctx, 0) stops that.  rgc_profile_read synchronises
- * the recorded events and returns, summed over the calls since the last read, the milliseconds
- * spent in  out_ms[0] the streaming accumulate kernel, out_ms[1] the phase launches after it,
- * out_ms[2] the decompression table kernel, out_ms[3] the decompression tile kernel, and the
- * number of compression / decompression calls in out_calls[0..1].  The record is then cleared. */
-int rgc_profile_enable(rgc_ctx* ctx, int enable);
-int rgc_profile_read(rgc_ctx* ctx, double* out_ms, int64_t* out_calls);
+/* Whether a kernel of any compression call enqueued so far has reported an internal inconsistency (a
+ * candidate list and its histogram that disagree, a message that came out shorter than k: a bug in the
+ * library, after which results are invalid).  Waits for `hip_stream`, copies one word.  Returns RGC_OK,
+ * RGC_EINTERNAL (it stays set until the context is destroyed), RGC_EINVAL or RGC_EHIP. */
+int rgc_last_error(rgc_ctx* ctx, void* hip_stream);
 
 /* Text for a status code; for RGC_EHIP the text of the last HIP error seen by this thread. */
 const char* rgc_strerror(int status);

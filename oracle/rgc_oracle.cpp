@@ -38,10 +38,10 @@
 //     additions taken from the left:
 //       u = m * (u + g)
 //       a = (V + u) + g
-//   * local gradient clipping (Section 2.4, "Overlapping Communication and
-//     Computation": clipping by a threshold N^(-1/2) of the original one,
-//     locally, before the gradients are added to the residuals): with the
-//     L2 norm taken over all layers of the call, summed in fp64,
+//   * local gradient clipping (Section 2.4: every worker clips its own
+//     gradients before they enter the residuals, and with N workers the
+//     clipping threshold is divided by sqrt(N)): with the L2 norm taken over
+//     all layers of the call, summed in fp64,
 //       c = norm > t ? t / norm : 1,   t = max_norm / sqrt(N)   (fp64, then
 //     rounded to fp32 once), and every gradient element enters the
 //     accumulate as fl(c * g).
@@ -61,25 +61,26 @@
 //     Decompression adds the message's one value at each of its indices.
 //   * threshold binary search selection (Section 2.1, Algorithm 3): the
 //     communication-set is every element whose magnitude exceeds a threshold,
-//     and the threshold is searched so that between k and 2k elements pass:
-//       mean = mean(|a|), max = max(|a|); l = 0, r = 1;
-//       while r - l > eps: ratio = l + (r - l)/2;
-//         threshold = mean + ratio * (max - mean); nnz = #{|a| > threshold};
-//         k < nnz < 2k: stop;  nnz <= k: r = ratio;  otherwise l = ratio.
-//     The listing's second branch is printed as "nnz < k/2 -> r = ratio, else
-//     l = ratio", which raises the threshold when k/2 <= nnz <= k although too
-//     few elements pass already and contradicts the text (the threshold is to
-//     end between the k-th and the 2k-th largest element); read as above.
-//     eps is not given: 2^-10, i.e. at most ten counts.  Precision is not
-//     given: mean = the fp64 sum of |a| in index order divided by n in fp64
-//     and rounded to fp32; ratio, max - mean, the product and the sum in fp32,
-//     each operation rounded on its own.  If the loop ends without a stop the
-//     last threshold tried is used, as the listing does.  The message is as
-//     long as it comes out (the listing sends every element above the
-//     threshold); a message buffer of `cap` entries takes the first cap of
-//     them in index order and the others stay in the residual.  The sampled
-//     variant of the same section reuses a threshold found earlier: the search
-//     is skipped and the given threshold is applied.  Inputs must be finite.
+//     and the threshold is found by bisection so that more than k and fewer
+//     than 2k elements pass.  The thresholds tried lie between the mean and the
+//     maximum of |a|: threshold = mean + ratio * (max - mean) with ratio the
+//     midpoint of an interval that starts as [0, 1]; a count of at most k moves
+//     the interval's upper end to the midpoint (the threshold must come down), a
+//     count of 2k or more moves its lower end there, a count in between ends
+//     the search, and so does an interval no wider than eps.
+//     Readings: the printed listing tests "nnz < k/2" in its second branch,
+//     which would push the threshold up while too few elements pass and
+//     contradicts the section's text (the threshold is to end between the k-th
+//     and the 2k-th largest element): read as just described.  eps is not
+//     given: 2^-10, i.e. at most ten counts.  Precision is not given: mean =
+//     the fp64 sum of |a| in index order divided by n in fp64 and rounded to
+//     fp32; the midpoint, max - mean, the product and the sum in fp32, each
+//     operation rounded on its own.  A search that ends on the interval width
+//     uses the last threshold tried.  The message is as long as it comes out;
+//     a message buffer of `cap` entries takes the first cap elements in index
+//     order and the others stay in the residual.  The sampled variant of the
+//     same section reuses a threshold found earlier: the search is skipped and
+//     the given threshold is applied.  Inputs must be finite.
 //   * decompression: acc starts at +0, workers are added in order 0..N-1 and
 //     entries in message order, all in fp32; then either dense = acc*scale or
 //     dense = dense + acc*scale (two roundings, no fused multiply-add).

@@ -1,6 +1,6 @@
 """ctypes binding of librgc.so -- argument marshalling only.
 
-Names follow include/rgc.h.  Tensors are anything with ``data_ptr()`` / ``numel()``
+Names follow include/rgc.h (and include/rgc_diag.h for the diagnostics).  Tensors are anything with ``data_ptr()`` / ``numel()``
 (PyTorch-ROCm tensors on the GPU); streams are raw ``hipStream_t`` values
 (``torch.cuda.current_stream().cuda_stream``), ``None`` = the null stream.
 """
@@ -29,13 +29,13 @@ RGC_STATUS_INDEX_RANGE = 0x1
 RGC_STATUS_INDEX_ORDER = 0x2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.environ.get("RGC_LIB") or os.path.join(_HERE, "librgc.so")   # RGC_LIB: tuning builds only
+_LIB_PATH = os.path.join(_HERE, "librgc.so")
 
 EXPORTS = ["rgc_create", "rgc_destroy", "rgc_k_for_density", "rgc_compress_layers",
            "rgc_compress_layers_scaled", "rgc_clip_coefficient", "rgc_message_means", "rgc_message_means_noalloc",
            "rgc_compress_layers_threshold",
            "rgc_decompress_accumulate", "rgc_reset_hints", "rgc_poison_hints", "rgc_selftest",
-           "rgc_last_paths", "rgc_last_stats", "rgc_decompress_status", "rgc_profile_enable", "rgc_profile_read", "rgc_strerror"]
+           "rgc_last_paths", "rgc_last_stats", "rgc_last_error", "rgc_decompress_status", "rgc_profile_enable", "rgc_profile_read", "rgc_strerror"]
 
 
 class RgcError(RuntimeError):
@@ -113,6 +113,8 @@ def load_library() -> ctypes.CDLL:
     L.rgc_selftest.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
     L.rgc_last_paths.restype = ctypes.c_int
     L.rgc_last_paths.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32), ctypes.c_int32, ctypes.c_void_p]
+    L.rgc_last_error.restype = ctypes.c_int
+    L.rgc_last_error.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
     L.rgc_last_stats.restype = ctypes.c_int
     L.rgc_last_stats.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64), ctypes.c_int32, ctypes.c_void_p]
     L.rgc_decompress_status.restype = ctypes.c_int
@@ -199,6 +201,10 @@ class Context:
         out = ctypes.c_uint32(0)
         _check(self._lib.rgc_decompress_status(self._h, ctypes.byref(out), _stream(stream)))
         return int(out.value)
+
+    def last_error(self, stream=None) -> None:
+        """Raises RgcError(RGC_EINTERNAL) if a kernel has reported an internal inconsistency (waits for the stream)."""
+        _check(self._lib.rgc_last_error(self._h, _stream(stream)))
 
     def last_paths(self, num_layers: int, stream=None) -> List[int]:
         out = (ctypes.c_int32 * num_layers)()

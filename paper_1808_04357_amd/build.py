@@ -1,4 +1,8 @@
-"""Builds librgc.so (the gfx950 HIP library behind include/rgc.h) in-tree with hipcc."""
+"""Builds librgc.so (the gfx950 HIP library behind include/rgc.h) in-tree with hipcc.
+
+Build-time hooks (the library itself reads no environment variable): HIPCC names another compiler driver;
+RGC_EXTRA_FLAGS appends flags for tuning experiments, e.g. -DRGC_CHUNK=4096 (wave-chunk size).
+"""
 from __future__ import annotations
 
 import os
@@ -9,7 +13,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librgc.so")
 SOURCES = ["rgc_api.cpp", "rgc_compress.hip", "rgc_decompress.hip", "rgc_threshold.hip"]
-HEADERS = ["rgc_internal.h", "rgc_device.h", os.path.join("..", "..", "include", "rgc.h")]
+HEADERS = ["rgc_internal.h", "rgc_device.h", os.path.join("..", "..", "include", "rgc.h"),
+           os.path.join("..", "..", "include", "rgc_diag.h")]
 
 FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",

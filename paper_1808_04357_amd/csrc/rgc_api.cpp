@@ -2,10 +2,10 @@
 // caller's layer / message lists into device descriptor tables (cached while the lists do not
 // change) and enqueues the kernels.  No kernel arithmetic lives here.
 #include "../../include/rgc.h"
+#include "../../include/rgc_diag.h"
 
 #include <algorithm>
 #include <cstdio>
-#include <cstdlib>
 #include <cstring>
 #include <memory>
 #include <new>
@@ -51,18 +51,14 @@ constexpr uint32_t kCapDiv = 16;
 constexpr uint32_t kCapDiv2 = 4;
 // the members of the k-th key's coarse bin go to a pool in which every such layer owns max(4096, n / 64) entries.
 
-// RGC_CHUNK (a multiple of 256, >= 1024) fixes the wave-chunk size for tuning; 0 = automatic.
-uint32_t chunk_override() {
-  static const uint32_t v = [] {
-    const char* e = std::getenv("RGC_CHUNK");
-    if (e) {
-      const long x = std::atol(e);
-      if (x >= static_cast<long>(kChunkMin) && x <= (1l << 20) && (x % 256) == 0) return static_cast<uint32_t>(x);
-    }
-    return 0u;
-  }();
-  return v;
-}
+// -DRGC_CHUNK=<elements> (a multiple of 256, >= 1024) at build time fixes the wave-chunk size for tuning
+// experiments; not defined = automatic.  (There are no run-time switches: nothing here reads the environment.)
+#ifdef RGC_CHUNK
+static_assert(RGC_CHUNK >= 1024 && RGC_CHUNK <= (1 << 20) && RGC_CHUNK % 256 == 0, "RGC_CHUNK: a multiple of 256, at least 1024");
+constexpr uint32_t chunk_override() { return RGC_CHUNK; }
+#else
+constexpr uint32_t chunk_override() { return 0u; }
+#endif
 
 // Elements per wave-chunk for a call over `total` elements.  Larger chunks mean fewer per-chunk
 // counters for the per-layer serial steps, smaller ones more workgroups to fill 256 CUs.
@@ -163,6 +159,7 @@ struct rgc_ctx {
   int64_t max_total = 0;
   int32_t max_layers = 0;
   uint32_t wc_max = 0;
+  uint32_t cus = 0;                        // compute units of the device (sizes the persistent decompression grids)
   DevBuf<LayerState> d_state;
   DevBuf<uint32_t> d_hist, d_coarse, d_cand_cnt, d_wc_a, d_wc_b, d_wc_c, d_err, d_group;
   DevBuf<unsigned long long> d_members;
@@ -289,7 +286,13 @@ int build_compress_plan(rgc_ctx* ctx, CompressPlan& P, const rgc_layer* layers, 
   RGC_HIP(hipMemcpyAsync(P.d_layers.p, P.staging.p, bytes_layers, hipMemcpyHostToDevice, stream));
   RGC_HIP(hipMemcpyAsync(P.d_wg2layer.p, map, bytes_map, hipMemcpyHostToDevice, stream));
   RGC_HIP(hipEventRecord(P.uploaded, stream));
-  P.key.assign(layers, layers + L);
+  P.key.resize(static_cast<size_t>(L));
+  for (int32_t l = 0; l < L; ++l) {
+    rgc_layer c{};
+    c.grad = layers[l].grad; c.residual = layers[l].residual; c.momentum = layers[l].momentum; c.n = layers[l].n;
+    c.k = layers[l].k; c.out_idx = layers[l].out_idx; c.out_val = layers[l].out_val; c.out_count = layers[l].out_count;
+    P.key[l] = c;
+  }
   P.num_wgs = wg;
   P.num_chunks = wc;
   P.write_bytes = 0;
@@ -363,6 +366,11 @@ int rgc_create(rgc_ctx** out, int device_id, int64_t max_total_elems, int32_t ma
   std::unique_ptr<rgc_ctx> c(new (std::nothrow) rgc_ctx);
   if (!c) return RGC_ENOMEM;
   c->device = device_id;
+  {
+    int cus = 0;
+    RGC_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device_id));
+    c->cus = static_cast<uint32_t>(std::max(1, cus));
+  }
   c->max_total = max_total_elems;
   c->max_layers = max_layers;
   const uint32_t kChunk = chunk_smallest(), kCap = kChunk / kCapDiv;
@@ -457,6 +465,26 @@ int rgc_poison_hints(rgc_ctx* ctx, int mode, void* hip_stream) {
 
 namespace {
 
+// The caller's structs have padding bytes that a C caller need not initialise: the cached lists are compared
+// field by field.
+bool same_layers(const std::vector<rgc_layer>& key, const rgc_layer* layers, int32_t num_layers) {
+  if (key.size() != static_cast<size_t>(num_layers)) return false;
+  for (int32_t l = 0; l < num_layers; ++l) {
+    const rgc_layer &a = key[l], &b = layers[l];
+    if (a.grad != b.grad || a.residual != b.residual || a.momentum != b.momentum || a.n != b.n || a.k != b.k ||
+        a.out_idx != b.out_idx || a.out_val != b.out_val || a.out_count != b.out_count)
+      return false;
+  }
+  return true;
+}
+
+bool same_messages(const std::vector<rgc_msg>& key, const rgc_msg* msgs, size_t count) {
+  if (key.size() != count) return false;
+  for (size_t i = 0; i < count; ++i)
+    if (key[i].idx != msgs[i].idx || key[i].val != msgs[i].val || key[i].count != msgs[i].count) return false;
+  return true;
+}
+
 // Checks a layer list and finds (or builds) its plan.  On success *out is the plan and the device
 // of the context is current.
 int plan_for_layers(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers, hipStream_t stream,
@@ -477,8 +505,7 @@ int plan_for_layers(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers, h
   // ---- find or build the plan for this exact layer list
   CompressPlan* plan = nullptr;
   for (auto& P : ctx->plans) {
-    if (P.valid && P.key.size() == static_cast<size_t>(num_layers) &&
-        std::memcmp(P.key.data(), layers, sizeof(rgc_layer) * num_layers) == 0) {
+    if (P.valid && same_layers(P.key, layers, num_layers)) {
       plan = &P;
       break;
     }
@@ -727,6 +754,16 @@ int rgc_last_paths(rgc_ctx* ctx, int32_t* out, int32_t num_layers, void* hip_str
   return err ? RGC_EINTERNAL : RGC_OK;
 }
 
+int rgc_last_error(rgc_ctx* ctx, void* hip_stream) {
+  if (!ctx) return RGC_EINVAL;
+  DeviceGuard guard(ctx->device);
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  uint32_t err = 0;
+  RGC_HIP(hipMemcpyAsync(&err, ctx->d_err.p, sizeof err, hipMemcpyDeviceToHost, stream));
+  RGC_HIP(hipStreamSynchronize(stream));
+  return err ? RGC_EINTERNAL : RGC_OK;
+}
+
 int rgc_last_stats(rgc_ctx* ctx, int64_t* out, int32_t num_layers, void* hip_stream) {
   if (!ctx || !out || num_layers < 1 || num_layers > ctx->max_layers) return RGC_EINVAL;
   DeviceGuard guard(ctx->device);
@@ -801,7 +838,7 @@ int rgc_decompress_accumulate(rgc_ctx* ctx, const rgc_msg* msgs, int32_t num_wor
 
   DecompressPlan& P = ctx->dplan;
   const bool same = P.valid && P.workers == num_workers && P.layers == num_layers &&
-                    (NM == 0 || std::memcmp(P.key_msgs.data(), msgs, sizeof(rgc_msg) * NM) == 0) &&
+                    same_messages(P.key_msgs, msgs, NM) &&
                     std::memcmp(P.key_dense.data(), dense, sizeof(float*) * num_layers) == 0 &&
                     std::memcmp(P.key_n.data(), n, sizeof(int64_t) * num_layers) == 0;
   if (!same) {
@@ -817,8 +854,10 @@ int rgc_decompress_accumulate(rgc_ctx* ctx, const rgc_msg* msgs, int32_t num_wor
       tiles += layer_tiles[l];
       stride += layer_tiles[l] + 1u;
     }
-    uint64_t blocks = 0;
-    for (size_t i = 0; i < NM; ++i) blocks += std::max<uint64_t>(1, (static_cast<uint64_t>(msgs[i].count) + 1023) / 1024);
+    const bool need_table = num_workers > kBatchWorkers;   // only the any-number-of-workers kernel reads the offset table
+    uint64_t blocks = 0;                                    // ... which is built by one workgroup per 1024 entries of a message
+    if (need_table)
+      for (size_t i = 0; i < NM; ++i) blocks += std::max<uint64_t>(1, (static_cast<uint64_t>(msgs[i].count) + 1023) / 1024);
     const uint64_t tab_words = stride * static_cast<uint64_t>(std::max(num_workers, 1));
     if (tiles > 0x7FFFFFFFull || blocks > 0x7FFFFFFFull || tab_words > 0xFFFFFFFFull) return RGC_ENOMEM;
     const size_t off_msgs = 0;
@@ -831,7 +870,6 @@ int rgc_decompress_accumulate(rgc_ctx* ctx, const rgc_msg* msgs, int32_t num_wor
       if (e == hipErrorOutOfMemory) { (void)hipGetLastError(); return RGC_ENOMEM; }
       RGC_HIP(e);
     }
-    const bool need_table = num_workers > kBatchWorkers;   // only the any-number-of-workers kernel reads it
     if (need_table && P.d_tab.n < tab_words) {
       hipError_t e = P.d_tab.alloc(tab_words);
       if (e == hipErrorOutOfMemory) { (void)hipGetLastError(); return RGC_ENOMEM; }
@@ -850,14 +888,16 @@ int rgc_decompress_accumulate(rgc_ctx* ctx, const rgc_msg* msgs, int32_t num_wor
         hm[i].val = in.val;
         hm[i].count = static_cast<uint32_t>(in.count);
         hm[i].tab_base = layer_col[l];
-        const uint32_t cnt = hm[i].count;
-        uint32_t first = 0;
-        do {
-          hb[nb].msg = static_cast<uint32_t>(i);
-          hb[nb].first = first;
-          ++nb;
-          first += 1024;
-        } while (first < cnt);
+        if (need_table) {
+          const uint32_t cnt = hm[i].count;
+          uint32_t first = 0;
+          do {
+            hb[nb].msg = static_cast<uint32_t>(i);
+            hb[nb].first = first;
+            ++nb;
+            first += 1024;
+          } while (first < cnt);
+        }
       }
     }
     uint32_t tile_base = 0;
@@ -878,16 +918,17 @@ int rgc_decompress_accumulate(rgc_ctx* ctx, const rgc_msg* msgs, int32_t num_wor
     A.blocks = reinterpret_cast<const BlockDesc*>(P.d_tables.p + off_blocks);
     A.tab = P.d_tab.p;
     A.tab_stride = static_cast<uint32_t>(stride);
-    {
-      hipDeviceProp_t prop;
-      RGC_HIP(hipGetDeviceProperties(&prop, ctx->device));
-      A.cus = static_cast<uint32_t>(std::max(1, prop.multiProcessorCount));
-    }
+    A.cus = ctx->cus;
     A.num_workers = static_cast<uint32_t>(num_workers);
     A.num_layers = static_cast<uint32_t>(num_layers);
     A.num_tiles = static_cast<uint32_t>(tiles);
     A.num_blocks = static_cast<uint32_t>(nb);
-    P.key_msgs.assign(msgs, msgs + NM);
+    P.key_msgs.resize(NM);
+    for (size_t i = 0; i < NM; ++i) {
+      rgc_msg c{};
+      c.idx = msgs[i].idx; c.val = msgs[i].val; c.count = msgs[i].count;
+      P.key_msgs[i] = c;
+    }
     P.key_dense.assign(dense, dense + num_layers);
     P.key_n.assign(n, n + num_layers);
     P.workers = num_workers;

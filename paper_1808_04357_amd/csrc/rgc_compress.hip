@@ -18,8 +18,9 @@
 //  * multi-pass radix select: three histogram passes over 12+12+7 key bits give the exact
 //    k-th key T and the number r of admitted ties, a counting pass and an ordered-compaction
 //    pass write the message (lowest indices win among keys equal to T).
-// Per layer decisions are taken by the last workgroup of the layer to finish a phase
-// (fence + atomic counter), so no host round trip and no spinning is needed.
+// Per layer decisions are taken by the last workgroup of the layer to finish a phase (a two-level
+// election with device-scope atomic counters; what it reads was written with device-scope stores, so no
+// fence, no host round trip and no spinning is needed).
 #include "rgc_device.h"
 
 #include <mutex>
@@ -664,12 +665,6 @@ __device__ unsigned long long select_kth_largest(const unsigned long long* v, ui
   __syncthreads();
   return r;
 }
-
-// The zeros that mask a sent entry out of the residual (and the velocity) are isolated 4-byte
-// writes, one cache line in a thousand.  Left dirty in the caches they are written to DRAM one
-// by one while the next streaming pass runs and cost it about a tenth of its bandwidth; stored
-// with the streaming hint they leave the caches early and cost half of that.
-__device__ __forceinline__ void mask_store(gptr<float> p) { __builtin_nontemporal_store(0.0f, p); }
 
 constexpr uint32_t kListGroup = 4;   // workgroups' worth of candidate lists one workgroup of PH_SEL / PH_OUT_C takes
 
@@ -1727,7 +1722,7 @@ __global__ void wave_scan_selftest_kernel(uint32_t* io) {
 
 // ------------------------------------------------------------------ local gradient clipping
 // Section 2.4: the gradients of all layers are clipped by their common L2 norm, locally and
-// before they are added to the residuals, with a threshold of N^(-1/2) of the original one.
+// before they are added to the residuals; with N workers the threshold is max_norm / sqrt(N).
 // Two launches, both with a fixed order of additions (the same coefficient on every run): every
 // wave sums the squares of its wave-chunk of the gradient in fp64 (the product of two floats is
 // exact there) and leaves one partial sum per wave-chunk; one workgroup then adds the partial

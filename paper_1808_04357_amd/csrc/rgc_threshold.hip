@@ -26,11 +26,6 @@ constexpr uint32_t kSteps = 1024;   // 1 / epsilon of the search: ratios are mul
 
 typedef uint32_t vu2 __attribute__((ext_vector_type(2)));   // a listed element: (float bits, index)
 
-// The zeros that mask a sent entry out of the residual (and the velocity) are isolated 4-byte writes;
-// stored with the streaming hint they leave the caches early instead of being written back one by
-// one while the next pass over the tensors runs.
-__device__ __forceinline__ void mask_store(gptr<float> p) { __builtin_nontemporal_store(0.0f, p); }
-
 // T(j), j = 1 .. 1023; the operations and their order are those of Algorithm 3.
 __device__ __forceinline__ float threshold_at(float mean, float span, uint32_t j) {
   const float ratio = static_cast<float>(j) * (1.0f / static_cast<float>(kSteps));   // exact
@@ -335,8 +330,8 @@ __global__ void __launch_bounds__(kBlockThreads) threshold_histogram_kernel(Thre
   }
 }
 
-// ------------------------------------------------------------------ the bisection of Algorithm 3
-// One workgroup per layer; nnz(T(j)) = number of elements in the bins j .. 1023.
+// ------------------------------------------------------------------ the threshold search (Section 2.1, Algorithm 3)
+// One workgroup per layer; the number of elements above T(j) is the number of elements in the bins j .. 1023.
 __global__ void __launch_bounds__(kBlockThreads) threshold_search_kernel(ThresholdArgs A) {
   __shared__ uint32_t above[kSteps + 1];
   __shared__ uint32_t part[kBlockThreads];
@@ -365,19 +360,21 @@ __global__ void __launch_bounds__(kBlockThreads) threshold_search_kernel(Thresho
   for (int i = static_cast<int>(kPer) - 1; i >= 0; --i) { run += h[i]; above[threadIdx.x * kPer + static_cast<uint32_t>(i)] = run; }
   __syncthreads();
   if (threadIdx.x == 0u) {
+    // The search interval of Algorithm 3 starts as [0, 1] and is halved until it is 2^-10 wide, so its ends and
+    // midpoints are the multiples j / 1024 and the bisection can run on the integers j: [lo, hi] starts as
+    // [0, 1024], every midpoint is exact, and at most ten thresholds T(j) are tried.  More than k but fewer than
+    // 2k elements above T(j) end the search; k or fewer mean the threshold has to come down (hi = j), otherwise up.
     ThresholdMoments M = A.moments[l];
     const unsigned long long k = L.k;
-    const float eps = 1.0f / static_cast<float>(kSteps);
-    float lo = 0.0f, hi = 1.0f, thr = 0.0f;
-    uint32_t counts = 0u;
-    while (__fsub_rn(hi, lo) > eps) {
-      const float ratio = __fadd_rn(lo, __fsub_rn(hi, lo) / 2.0f);
-      const uint32_t j = static_cast<uint32_t>(ratio * static_cast<float>(kSteps));   // exact: ratio is a multiple of 2^-10
+    uint32_t lo = 0u, hi = kSteps, counts = 0u;
+    float thr = 0.0f;
+    while (hi - lo > 1u) {
+      const uint32_t j = lo + (hi - lo) / 2u;
       thr = threshold_at(M.mean, M.span, j);
       const unsigned long long nnz = above[j];
       ++counts;
       if (nnz > k && nnz < 2ull * k) break;
-      if (nnz <= k) hi = ratio; else lo = ratio;
+      if (nnz <= k) hi = j; else lo = j;
     }
     *as_global(A.thresholds + l) = thr;
     A.moments[l].counts_taken = counts;

@@ -205,3 +205,58 @@ def test_full_size_vgg16_search_and_reuse(rgc, oracle):
     assert ks[big] < out[big][0] < 2 * ks[big]
     r.step(cfg["G"][1], search=False)
     r.close()
+
+
+def test_variable_length_messages_feed_decompression(rgc, oracle):
+    """Sections 2.1 + 2.3 together: three workers select by threshold search (message lengths differ from worker to
+    worker and from step to step), the length elements are read back, and the messages are decompressed; the dense
+    result must equal the oracle's decompression of the oracle's messages bit for bit, every step, although the
+    message descriptors change with every call."""
+    import torch
+    g = np.random.default_rng(91)
+    sizes = [120_000, 33_333, 4_097]
+    ks = [rgc.rgc_k_for_density(n) for n in sizes]
+    N = 3
+    workers = [Runner(rgc, oracle, [(g.standard_normal(n) * 5e-3).astype(np.float32) for n in sizes], ks,
+                      tag="flow worker %d" % w) for w in range(N)]
+    dev = torch.device("cuda:0")
+    dense = [torch.full((n,), float("nan"), dtype=torch.float32, device=dev) for n in sizes]
+    dctx = rgc.Context(sum(sizes), len(sizes))
+    for step in range(4):
+        Vh_before = [[v.copy() for v in w.Vh] for w in workers]
+        Gs = [[(g.standard_normal(n) * 1e-3).astype(np.float32) for n in sizes] for _ in range(N)]
+        ref_msgs = []
+        for w in range(N):
+            # the oracle's messages of this step, from a copy of the state the runner's own oracle call will also use
+            row = []
+            for l, k in enumerate(ks):
+                oi, ov, _, _, _ = oracle.compress_layer_threshold(Gs[w][l], Vh_before[w][l], k, search=(step % 2 == 0),
+                                                                  threshold=float(workers[w].thr_h[l]))
+                row.append((oi, ov))
+            ref_msgs.append(row)
+        d_idx, d_val = [], []
+        for w in range(N):
+            wk = workers[w]
+            wk.dev.set_grads(Gs[w])
+            rgc.rgc_compress_layers_threshold(wk.ctx, wk.dev.layers, 0.0, wk.thr, wk.nnz,
+                                              rgc.RGC_THRESHOLD_SEARCH if step % 2 == 0 else 0, torch.cuda.current_stream())
+            counts = wk.dev.out_count.cpu().numpy()                       # the host round trip of the flow
+            d_idx.append([wk.dev.out_idx[l][:int(counts[l])] for l in range(len(sizes))])
+            d_val.append([wk.dev.out_val[l][:int(counts[l])] for l in range(len(sizes))])
+            for l in range(len(sizes)):
+                assert int(counts[l]) == ref_msgs[w][l][0].size, "step %d worker %d layer %d: length" % (step, w, l)
+        rgc.rgc_decompress_accumulate(dctx, rgc.MessageList(d_idx, d_val, dense), 1.0 / N, rgc.RGC_OVERWRITE,
+                                      torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        for l, n in enumerate(sizes):
+            want = oracle.decompress([ref_msgs[w][l][0] for w in range(N)], [ref_msgs[w][l][1] for w in range(N)], n, 1.0 / N)
+            assert np.array_equal(u32(dense[l].cpu().numpy()), u32(want)), "step %d layer %d: dense" % (step, l)
+        # keep the runners' host state in step with the device (thresholds and residuals)
+        for w in range(N):
+            thr = workers[w].thr.cpu().numpy()
+            for l in range(len(sizes)):
+                workers[w].Vh[l] = Vh_before[w][l]
+                workers[w].thr_h[l] = float(thr[l])
+    dctx.close()
+    for w in workers:
+        w.ctx.close()

@@ -7,7 +7,7 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "rgc.h")
+HEADERS = [os.path.join(ROOT, "include", "rgc.h"), os.path.join(ROOT, "include", "rgc_diag.h")]
 
 
 @pytest.fixture(scope="module")
@@ -19,7 +19,7 @@ def lib():
 
 
 def declared_functions():
-    text = open(HEADER).read()
+    text = "".join(open(h).read() for h in HEADERS)
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(rgc_[a-z_0-9]+)\s*\(", text)))
 
@@ -29,7 +29,7 @@ def test_header_functions_are_exported(lib):
     assert {"rgc_create", "rgc_destroy", "rgc_k_for_density", "rgc_compress_layers",
             "rgc_decompress_accumulate", "rgc_strerror"} <= set(names)
     for name in names:
-        assert hasattr(lib, name), name + " is declared in include/rgc.h but not exported"
+        assert hasattr(lib, name), name + " is declared in include/*.h but not exported"
     from paper_1808_04357_amd import binding
     assert sorted(binding.EXPORTS) == names
 
@@ -60,6 +60,8 @@ def test_null_arguments_are_rejected_before_any_gpu_call(lib):
     assert lib.rgc_reset_hints(None) == -1
     assert lib.rgc_poison_hints(None, 0, None) == -1
     assert lib.rgc_selftest(None, None) == -1
+    assert lib.rgc_last_error(None, None) == -1
+    assert lib.rgc_message_means_noalloc(None, None, None, 1, None, None) == -1
 
 
 def test_struct_layout_matches_header():
@@ -68,6 +70,17 @@ def test_struct_layout_matches_header():
     assert binding.rgc_layer.n.offset == 24 and binding.rgc_layer.k.offset == 32
     assert binding.rgc_layer.out_idx.offset == 40 and binding.rgc_layer.out_count.offset == 56
     assert ctypes.sizeof(binding.rgc_msg) == 24 and binding.rgc_msg.count.offset == 16
+
+
+def test_product_reads_no_environment_switches():
+    """Nothing in the library or its binding is steered by environment variables (the build script's extra-flags
+    hook is a build-time matter and lives in build.py alone)."""
+    pkg = os.path.join(ROOT, "paper_1808_04357_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".cpp", ".hip", ".h")) or f in ("binding.py", "__init__.py", "synth.py"):
+                src = open(os.path.join(dirpath, f)).read()
+                assert "getenv" not in src and "os.environ" not in src, f
 
 
 def test_product_package_does_not_import_the_oracle():

@@ -440,7 +440,7 @@ def test_gradient_scale_is_one_rounded_product(oracle):
 
 
 def test_clip_coefficient_closed_forms(oracle):
-    """Section 2.4: local clipping by a threshold N^(-1/2) of the original one."""
+    """Section 2.4: local clipping, threshold = max_norm / sqrt(number of workers)."""
     ones = [np.ones(9, np.float32), np.ones(7, np.float32)]          # norm 4 over both layers
     c, sq = oracle.clip_coefficient(ones, 1.0, 4)                      # threshold 1/2
     assert sq == 16.0 and c == np.float32(0.125)
