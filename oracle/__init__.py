@@ -79,6 +79,8 @@ def lib() -> ctypes.CDLL:
             ctypes.POINTER(_i32p), ctypes.POINTER(_f32p), _i32p, ctypes.c_int32, _f32p,
             ctypes.c_int64, ctypes.c_float, ctypes.c_int]
         L.rgc_oracle_hardware_threads.restype = ctypes.c_int32
+        L.rgc_oracle_exact_sum.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.c_int64]
+        L.rgc_oracle_exact_sum.restype = ctypes.c_double
         L.rgc_oracle_hardware_threads.argtypes = []
         _lib = L
     return _lib
@@ -96,6 +98,12 @@ def _i32(a: np.ndarray) -> "_i32p":
 
 def k_for_density(n: int, ppm: int = 1000) -> int:
     return int(lib().rgc_oracle_k_for_density(int(n), int(ppm)))
+
+
+def exact_sum(x: np.ndarray) -> float:
+    """Sum of fp64 terms rounded once (nearest, ties to even): what the oracle's three long sums are built on."""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    return float(lib().rgc_oracle_exact_sum(x.ctypes.data_as(ctypes.POINTER(ctypes.c_double)), x.size))
 
 
 def hardware_threads() -> int:

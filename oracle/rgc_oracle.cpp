@@ -41,7 +41,8 @@
 //   * local gradient clipping (Section 2.4: every worker clips its own
 //     gradients before they enter the residuals, and with N workers the
 //     clipping threshold is divided by sqrt(N)): with the L2 norm taken over
-//     all layers of the call, summed in fp64,
+//     all layers of the call (the squares, exact in fp64, summed without
+//     rounding and the sum rounded to fp64 once),
 //       c = norm > t ? t / norm : 1,   t = max_norm / sqrt(N)   (fp64, then
 //     rounded to fp32 once), and every gradient element enters the
 //     accumulate as fl(c * g).
@@ -55,9 +56,9 @@
 //     to the lowest index as everywhere, +0 and -0 being equal values; NaNs
 //     rank by their bit pattern like the other keys here (sign bit clear: above
 //     +Inf, set: below -Inf).  The message lists the k indices ascending
-//     and the mean of the k accumulated values, summed in index order in fp64,
-//     divided by k in fp64 and rounded to fp32 once; the sent entries leave
-//     the residual (and the velocity) exactly as in Algorithm 1.
+//     and the mean of the k accumulated values: their sum without rounding,
+//     rounded to fp64 once, divided by k in fp64 and rounded to fp32; the sent
+//     entries leave the residual (and the velocity) exactly as in Algorithm 1.
 //     Decompression adds the message's one value at each of its indices.
 //   * threshold binary search selection (Section 2.1, Algorithm 3): the
 //     communication-set is every element whose magnitude exceeds a threshold,
@@ -73,14 +74,22 @@
 //     contradicts the section's text (the threshold is to end between the k-th
 //     and the 2k-th largest element): read as just described.  eps is not
 //     given: 2^-10, i.e. at most ten counts.  Precision is not given: mean =
-//     the fp64 sum of |a| in index order divided by n in fp64 and rounded to
-//     fp32; the midpoint, max - mean, the product and the sum in fp32, each
-//     operation rounded on its own.  A search that ends on the interval width
+//     the sum of |a| without rounding, rounded to fp64 once, divided by n in
+//     fp64 and rounded to fp32; the midpoint, max - mean, the product and the
+//     sum in fp32, each operation rounded on its own.  A search that ends on the interval width
 //     uses the last threshold tried.  The message is as long as it comes out;
 //     a message buffer of `cap` entries takes the first cap elements in index
 //     order and the others stay in the residual.  The sampled variant of the
 //     same section reuses a threshold found earlier: the search is skipped and
 //     the given threshold is applied.  Inputs must be finite.
+//   * the three long sums (squares of the gradients, the k values of a one-value
+//     message, |a| over a layer): the paper fixes neither their precision nor
+//     the order of their additions, and a sum that depends on the order is one
+//     that only a single schedule can reproduce.  They are therefore read as
+//     the sum of the terms itself, rounded once to fp64 (nearest, ties to
+//     even): whatever the order and the grouping, every correct implementation
+//     arrives at the same bits.  A NaN term, or infinite terms of both signs,
+//     give NaN; infinite terms of one sign give that infinity.
 //   * decompression: acc starts at +0, workers are added in order 0..N-1 and
 //     entries in message order, all in fp32; then either dense = acc*scale or
 //     dense = dense + acc*scale (two roundings, no fused multiply-add).
@@ -104,6 +113,74 @@ inline uint32_t float_bits(float x) {
 
 // Monotone unsigned image of |x|.
 inline uint32_t magnitude_key(float x) { return float_bits(x) & 0x7FFFFFFFu; }
+
+// The sum of any number of doubles with one rounding at its end: the terms are
+// added as integers (in units of 2^-1074, the smallest step of the format), the
+// positive ones into one long integer and the magnitudes of the negative ones
+// into another; the difference of the two is rounded to the nearest double,
+// a tie to the one with an even last bit.  A NaN among the terms, or infinities
+// of both signs, give NaN; infinities of one sign give that infinity.
+class ExactSum {
+ public:
+  void add(double x) {
+    if (std::isnan(x)) { nan_ = true; return; }
+    if (std::isinf(x)) { (x > 0 ? pinf_ : ninf_) = true; return; }
+    if (x == 0.0) return;
+    int e;
+    const double f = std::frexp(std::fabs(x), &e);              // |x| = f * 2^e, f in [1/2, 1)
+    uint64_t mant = static_cast<uint64_t>(std::ldexp(f, 53));   // |x| = mant * 2^(e - 53)
+    int pos = e - 53 + 1074;                                    // position of mant's last bit
+    if (pos < 0) { mant >>= -pos; pos = 0; }                    // subnormal: the bits shifted out are zeros
+    uint32_t* w = x > 0 ? pos_ : neg_;
+    unsigned __int128 t = static_cast<unsigned __int128>(mant) << (pos % 32);
+    uint64_t carry = 0;
+    for (int i = pos / 32; i < kWords && (t != 0 || carry != 0); ++i) {
+      const uint64_t v = static_cast<uint64_t>(w[i]) + static_cast<uint32_t>(t) + carry;
+      w[i] = static_cast<uint32_t>(v);
+      carry = v >> 32;
+      t >>= 32;
+    }
+  }
+
+  double rounded() const {
+    if (nan_ || (pinf_ && ninf_)) return std::nan("");
+    if (pinf_) return HUGE_VAL;
+    if (ninf_) return -HUGE_VAL;
+    int cmp = 0;
+    for (int i = kWords - 1; i >= 0 && cmp == 0; --i)
+      if (pos_[i] != neg_[i]) cmp = pos_[i] > neg_[i] ? 1 : -1;
+    if (cmp == 0) return 0.0;
+    const uint32_t* big = cmp > 0 ? pos_ : neg_;
+    const uint32_t* small = cmp > 0 ? neg_ : pos_;
+    uint32_t d[kWords];
+    int64_t borrow = 0;
+    for (int i = 0; i < kWords; ++i) {
+      int64_t v = static_cast<int64_t>(big[i]) - static_cast<int64_t>(small[i]) - borrow;
+      borrow = v < 0 ? 1 : 0;
+      if (v < 0) v += int64_t(1) << 32;
+      d[i] = static_cast<uint32_t>(v);
+    }
+    auto bit = [&](int p) { return p < 0 ? 0u : (d[p / 32] >> (p % 32)) & 1u; };
+    int top = kWords * 32 - 1;
+    while (bit(top) == 0u) --top;                               // the difference is not zero
+    const int last = top >= 53 ? top - 52 : 0;                  // last bit that is kept
+    uint64_t mant = 0;
+    for (int p = top; p >= last; --p) mant = (mant << 1) | bit(p);
+    if (last > 0) {
+      bool rest = false;                                        // anything below the first dropped bit
+      for (int p = last - 2; p >= 0 && !rest; --p) rest = bit(p) != 0u;
+      if (bit(last - 1) != 0u && (rest || (mant & 1u) != 0u)) ++mant;
+    }
+    const double r = std::ldexp(static_cast<double>(mant), last - 1074);
+    return cmp > 0 ? r : -r;
+  }
+
+ private:
+  static constexpr int kWords = 68;      // 2176 bits: the format's 2098 and room for 2^64 terms
+  uint32_t pos_[kWords] = {};
+  uint32_t neg_[kWords] = {};
+  bool nan_ = false, pinf_ = false, ninf_ = false;
+};
 
 // Step 1 of the layer loop: produce the accumulated tensor a (and the updated
 // velocity when momentum correction is on).  Writes a into `acc`.
@@ -245,9 +322,9 @@ int rgc_oracle_compress_layer_asq(const float* grad, float* residual, float* mom
   }
   std::vector<float> values(static_cast<size_t>(k));
   emit(acc, sel, residual, momentum, mask_momentum, n, out_idx, values.data(), out_count);
-  double sum = 0.0;
-  for (int32_t j = 0; j < k; ++j) sum += static_cast<double>(values[j]);   // index order
-  *out_mean = static_cast<float>(sum / static_cast<double>(k));
+  ExactSum sum;
+  for (int32_t j = 0; j < k; ++j) sum.add(static_cast<double>(values[j]));
+  *out_mean = static_cast<float>(sum.rounded() / static_cast<double>(k));
   return 0;
 }
 
@@ -274,14 +351,14 @@ int rgc_oracle_compress_layer_threshold(const float* grad, float* residual, floa
     return c;
   };
   if (search) {
-    double sum = 0.0;
+    ExactSum sum;
     float max = 0.0f;
     for (int64_t i = 0; i < n; ++i) {
       const float mag = std::fabs(acc[i]);
-      sum += static_cast<double>(mag);
+      sum.add(static_cast<double>(mag));
       if (mag > max) max = mag;
     }
-    const float mean = static_cast<float>(sum / static_cast<double>(n));
+    const float mean = static_cast<float>(sum.rounded() / static_cast<double>(n));
     const float eps = 1.0f / 1024.0f;
     float l = 0.0f, r = 1.0f, thr = 0.0f, ratio = 0.0f;
     int counts = 0;
@@ -412,12 +489,13 @@ int rgc_oracle_compress_layers(const float* const* grad, float* const* residual,
 // of this file).  Also stores the squared norm (fp64) if sqnorm is not NULL.
 float rgc_oracle_clip_coefficient(const float* const* grad, const int64_t* n, int32_t num_layers,
                                   float max_norm, int32_t num_workers, double* sqnorm) {
-  double sum = 0.0;
+  ExactSum squares;
   for (int32_t l = 0; l < num_layers; ++l)
     for (int64_t i = 0; i < n[l]; ++i) {
       double g = static_cast<double>(grad[l][i]);
-      sum += g * g;
+      squares.add(g * g);                  // 24 bits times 24 bits: the product is exact in fp64
     }
+  const double sum = squares.rounded();
   if (sqnorm) *sqnorm = sum;
   double norm = std::sqrt(sum);
   double t = static_cast<double>(max_norm) / std::sqrt(static_cast<double>(num_workers));
@@ -450,6 +528,14 @@ int rgc_oracle_decompress(const int32_t* const* idx, const float* const* val,
     for (int64_t i = 0; i < n; ++i) dense[i] = acc[i] * scale;
   }
   return 0;
+}
+
+// The exactly rounded sum the three reductions above are built on, by itself
+// (for the tests that pin it).
+double rgc_oracle_exact_sum(const double* x, int64_t n) {
+  ExactSum sum;
+  for (int64_t i = 0; i < n; ++i) sum.add(x[i]);
+  return sum.rounded();
 }
 
 // Number of host threads the machine reports (for the benchmark's "cores").

@@ -22,6 +22,7 @@ int rgc_oracle_compress_layers_ex(const float* const*, float* const*, float* con
                                   int32_t, float, int, int, const float*, int32_t* const*, float* const*, int32_t*,
                                   int32_t);
 float rgc_oracle_clip_coefficient(const float* const*, const int64_t*, int32_t, float, int32_t, double*);
+double rgc_oracle_exact_sum(const double*, int64_t);
 int rgc_oracle_decompress(const int32_t* const*, const float* const*, const int32_t*, int32_t, float*, int64_t, float,
                           int);
 int rgc_oracle_decompress_scalar(const int32_t* const*, const float*, const int32_t*, int32_t, float*, int64_t, float,
@@ -90,6 +91,12 @@ int main() {
     double sq = 0.0;
     const float c = rgc_oracle_clip_coefficient(gp.data(), n.data(), L, 1.0f, 4, &sq);
     CHECK(c > 0.0f && c <= 1.0f && sq > 0.0);
+    // the exactly rounded sum at both ends of the format's range, with cancellation
+    const double ends[] = {1.7976931348623157e308, 4.9406564584124654e-324, -1.7976931348623157e308,
+                           1.0, -4.9406564584124654e-324, 1e-320, 1.7976931348623157e308};
+    CHECK(rgc_oracle_exact_sum(ends, 7) == 1.7976931348623157e308);
+    CHECK(rgc_oracle_exact_sum(ends, 6) == 1.0);
+    CHECK(rgc_oracle_exact_sum(ends, 0) == 0.0);
   }
   {
     // decompression: overlapping workers, an empty one, both destination modes, one-value messages

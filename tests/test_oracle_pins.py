@@ -835,3 +835,101 @@ def test_threshold_reuse_and_capacity(oracle):
     kept[idx] = False
     assert np.array_equal(v[kept].view(np.uint32), a[kept].view(np.uint32)) and np.all(v[idx].view(np.uint32) == 0)
     assert np.array_equal(u[kept].view(np.uint32), u_ref[kept].view(np.uint32)) and np.all(u[idx].view(np.uint32) == 0)
+
+
+# ------------------------------------------------------------------ the three long sums: rounded once
+
+def _fraction_sum_rounded(x):
+    """The sum of doubles in exact rational arithmetic, converted to the nearest double (ties to even)."""
+    return float(sum((Fraction(float(v)) for v in x), Fraction(0)))
+
+
+def test_exact_sum_worked_cases(oracle):
+    """Sums whose correctly rounded value is known by hand: cancellation, a tie that goes to the even
+    neighbour, a tie broken by the smallest representable term, subnormal terms, signed results."""
+    two53 = float(2 ** 53)
+    tiny = 5e-324                                        # 2^-1074
+    assert oracle.exact_sum(np.array([])) == 0.0
+    assert oracle.exact_sum(np.array([1e300, 1.0, -1e300])) == 1.0          # a left-to-right sum gives 0
+    assert oracle.exact_sum(np.array([1.0, 1e300, -1e300])) == 1.0
+    assert oracle.exact_sum(np.array([two53, 1.0])) == two53                # half way: the even neighbour
+    assert oracle.exact_sum(np.array([two53 + 2.0, 1.0])) == two53 + 4.0    # half way: the even neighbour is above
+    assert oracle.exact_sum(np.array([two53, 1.0, tiny])) == two53 + 2.0    # just above half way
+    assert oracle.exact_sum(np.array([two53, 1.0, -tiny])) == two53         # just below half way
+    assert oracle.exact_sum(np.array([-two53, -1.0, -tiny])) == -(two53 + 2.0)
+    assert oracle.exact_sum(np.array([tiny, tiny, tiny])) == 3 * tiny       # subnormal and exact
+    assert oracle.exact_sum(np.array([tiny, -tiny])) == 0.0
+    assert oracle.exact_sum(np.array([0.1] * 10)) == 1.0                    # ten times the double next to 1/10 rounds to 1
+    assert oracle.exact_sum(np.array([1.7976931348623157e308, 1.7976931348623157e308, -1.7976931348623157e308])) == 1.7976931348623157e308
+    assert oracle.exact_sum(np.array([2.0 ** -1022, -(2.0 ** -1022) + tiny])) == tiny
+    assert np.isnan(oracle.exact_sum(np.array([1.0, np.nan])))
+    assert np.isnan(oracle.exact_sum(np.array([np.inf, -np.inf, 1.0])))
+    assert oracle.exact_sum(np.array([np.inf, 1.0, -3.0])) == np.inf
+    assert oracle.exact_sum(np.array([-np.inf, 1e308, 1e308])) == -np.inf
+
+
+@pytest.mark.parametrize("law", ["wide", "cancelling", "f32_products", "subnormal", "same_sign"])
+def test_exact_sum_equals_the_library_and_rational_arithmetic(oracle, law):
+    """math.fsum returns the correctly rounded sum of doubles, and so does exact rational arithmetic converted
+    once; a naive left-to-right sum differs from both on most of these inputs."""
+    import math
+    g = np.random.default_rng({"wide": 1, "cancelling": 2, "f32_products": 3, "subnormal": 4, "same_sign": 5}[law])
+    differs = 0
+    for rep in range(40):
+        n = int(g.integers(1, 400))
+        if law == "wide":
+            x = g.standard_normal(n) * np.exp2(g.integers(-300, 300, n).astype(np.float64))
+        elif law == "cancelling":
+            h = g.standard_normal(n) * np.exp2(g.integers(-60, 60, n).astype(np.float64))
+            x = np.concatenate([h, -h, g.standard_normal(3) * 1e-30])
+            g.shuffle(x)
+        elif law == "f32_products":
+            f = (g.standard_normal(n) * np.exp2(g.integers(-70, 60, n))).astype(np.float32).astype(np.float64)
+            x = f * f
+        elif law == "subnormal":
+            x = g.integers(-2 ** 40, 2 ** 40, n).astype(np.float64) * 5e-324
+            x = np.concatenate([x, g.standard_normal(2) * 2.0 ** -1040])
+        else:
+            x = np.abs(g.standard_normal(n).astype(np.float32)).astype(np.float64)
+        got = oracle.exact_sum(x)
+        assert got == math.fsum(x), (law, rep)
+        assert got == _fraction_sum_rounded(x), (law, rep)
+        naive = 0.0
+        for v in x:
+            naive += float(v)
+        differs += naive != got
+    if law in ("wide", "cancelling", "f32_products"):
+        assert differs > 0, "the inputs do not tell an ordered sum from the exact one"
+
+
+def test_the_three_sums_do_not_depend_on_order(oracle):
+    """The mean of a one-value message, the mean of |a| under the threshold search and the squared norm
+    behind the clipping coefficient are each the exactly rounded sum: the values are chosen so that an
+    fp64 sum taken in index order gives other bits."""
+    import math
+    g = np.random.default_rng(77)
+    # one-value message (Section 2.2): k = n, every element is sent
+    n = 257
+    a = (g.standard_normal(n) * np.exp2(g.integers(-40, 40, n))).astype(np.float32)
+    a[0], a[-1] = np.float32(3e37), np.float32(-3e37)        # an ordered fp64 sum loses all that lies between
+    idx, mean, cnt = oracle.compress_layer_asq(np.zeros(n, np.float32), a.copy(), n, +1)
+    want = np.float32(math.fsum(a.astype(np.float64)) / n)
+    ordered = 0.0
+    for v in a:
+        ordered += float(v)
+    assert cnt == n and mean == want and np.float32(ordered / n) != want
+    # threshold search (Algorithm 3): trace[0] is the mean of |a|
+    b = np.abs(a)
+    b[0] = b[-1] = np.float32(1.0)
+    k = 8
+    _, _, _, _, trace = oracle.compress_layer_threshold(np.zeros(n, np.float32), b.copy(), k, search=True)
+    assert trace[0] == np.float32(math.fsum(b.astype(np.float64)) / n)
+    # clipping (Section 2.4): the squared norm over two layers
+    G = [g.standard_normal(5000).astype(np.float32), g.standard_normal(777).astype(np.float32)]
+    _, sq = oracle.clip_coefficient(G, 1.0, 4)
+    sq_want = math.fsum(float(v) * float(v) for layer in G for v in layer)
+    ordered = 0.0
+    for layer in G:
+        for v in layer:
+            ordered += float(v) * float(v)
+    assert sq == sq_want and ordered != sq_want
