@@ -149,8 +149,10 @@ int rgc_compress_layers_scaled(rgc_ctx* ctx, const rgc_layer* layers, int32_t nu
  *    the k accumulated values, masking of residual and velocity) is as in the plain call.  The
  *    speed hints of the three selection modes are kept apart; a layer short of elements of the
  *    expected sign has none and takes the multi-pass path on every call.
- *  - rgc_message_means: means[l] = average of layer l's out_val[0 .. *out_count), summed in fp64 in
- *    a fixed order and rounded to fp32 once; `means` is DEVICE memory, num_layers floats.  A length
+ *  - rgc_message_means: means[l] = average of layer l's out_val[0 .. *out_count): the sum of the
+ *    values rounded ONCE to fp64 (nearest even; no order of additions enters), divided by the count
+ *    in fp64 and rounded to fp32.  A NaN, or infinities of both signs, among the values give NaN,
+ *    infinities of one sign that infinity.  `means` is DEVICE memory, num_layers floats.  A length
  *    word above the layer's k (possible only after rgc_compress_layers_threshold, whose messages this
  *    call is not meant for) is read as k.  The
  *    message of layer l is then (count, out_idx, means[l]); layers the caller does not want
@@ -164,13 +166,13 @@ int rgc_message_means(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers,
 /* rgc_message_means for callers that cannot allocate device or pinned memory when they call: code
  * under HIP stream capture, tight serving loops, harnesses that forbid hipMalloc.  It takes no context
  * and calls no allocating routine, on its first call as little as later; its partial sums live in a
- * static array of the library's code object (512 KiB, one copy per GPU, held until the process ends).
+ * static array of the library's code object (1.44 MiB, one copy per GPU, held until the process ends).
  * It runs on the CURRENT HIP device.  values[l] / counts[l]: DEVICE pointers to message l's values and
  * to its length word (what rgc_compress_layers wrote as out_val / out_count); capacity[l]: how many
  * values the buffer holds (the layer's k; a larger length word is read as capacity[l]); the three
  * arrays themselves are HOST memory and are copied into the kernel arguments before the call returns.
- * means: DEVICE, num_layers floats.  Same arithmetic, same order of additions and so the same bits as
- * rgc_message_means on the same messages.
+ * means: DEVICE, num_layers floats.  Same arithmetic and so the same bits as rgc_message_means on
+ * the same messages.
  * Limit: num_layers <= RGC_NOALLOC_MAX_LAYERS, else RGC_ENOMEM (nothing enqueued).
  * All calls on one GPU share that GPU's array: calls that overlap there (two streams, two threads)
  * race; order them on one stream or with events.  Nothing in the array needs to be cleared between calls.
@@ -214,7 +216,8 @@ int rgc_compress_layers_threshold(rgc_ctx* ctx, const rgc_layer* layers, int32_t
  * factor sqrt(N)).
  * Enqueues two small kernels that read layers[l].grad of every layer (only grad and n are used) and
  * store  c = norm > t ? t / norm : 1,  t = max_norm / sqrt(num_workers),  norm = the L2 norm over
- * all elements of all layers (squares and sums in fp64, a fixed order of additions), into
+ * all elements of all layers (the squares are exact in fp64, their sum is rounded to fp64 ONCE, so
+ * no order of additions enters; an infinite element gives c = 0, a NaN gives c = 1), into
  * *coefficient, a float in DEVICE memory, for rgc_compress_layers_scaled to use on the same stream.
  * Errors (nothing enqueued): RGC_EINVAL (also max_norm <= 0, num_workers < 1), RGC_ENOMEM, RGC_EHIP. */
 int rgc_clip_coefficient(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers, float max_norm,

@@ -163,8 +163,8 @@ struct rgc_ctx {
   DevBuf<LayerState> d_state;
   DevBuf<uint32_t> d_hist, d_coarse, d_cand_cnt, d_wc_a, d_wc_b, d_wc_c, d_err, d_group;
   DevBuf<unsigned long long> d_members;
-  DevBuf<double> d_norm_part;              // [wave-chunks] partial sums of squares (clipping coefficient)
-  DevBuf<double> d_mean_part;              // [layers][kMeanPartsMax] partial sums of message values
+  DevBuf<long long> d_norm_part;           // [workgroups] parts of the sum of squares / of |a| (ExactParts)
+  DevBuf<long long> d_mean_part;           // [layers][kMeanPartsMax] parts of the sums of message values (ExactParts)
   DevBuf<ThresholdMoments> d_moments;      // [max_layers] threshold binary search: mean, max of each layer
   DevBuf<uint2> d_slots;
   DevBuf<uint2> d_slots2;                  // the probe pass's lists of two-pass layers (first use)
@@ -539,7 +539,7 @@ void fill_plan_args(rgc_ctx* ctx, const CompressPlan* plan, CompressArgs& A) {
   A.layers = plan->d_layers.p;
   A.wg2layer = plan->d_wg2layer.p;
   A.chunk = plan->chunk;
-  A.norm_part = ctx->d_norm_part.p;
+  A.norm_parts = exact_parts_at(ctx->d_norm_part.p, ctx->wc_max);
 }
 
 }  // namespace
@@ -556,12 +556,13 @@ int rgc_clip_coefficient(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_laye
   CompressPlan* plan = nullptr;
   const int rc = plan_for_layers(ctx, layers, num_layers, stream, &plan);
   if (rc != RGC_OK) return rc;
-  if (ctx->d_norm_part.n < ctx->wc_max) RGC_HIP(ctx->d_norm_part.alloc(ctx->wc_max));   // first use only
+  if (ctx->d_norm_part.n < ctx->wc_max * kExactWordsPerPart)                              // first use only
+    RGC_HIP(ctx->d_norm_part.alloc(ctx->wc_max * kExactWordsPerPart));                    // (no more workgroups than wave-chunks)
   CompressArgs A{};
   fill_plan_args(ctx, plan, A);
   A.reverse = streaming_direction(plan, ctx->compress_calls) ^ 1u;   // against the direction of the compression call to come
   const float threshold = static_cast<float>(static_cast<double>(max_norm) / std::sqrt(static_cast<double>(num_workers)));
-  RGC_HIP(launch_clip_coefficient(A, plan->num_wgs, plan->num_chunks, threshold, coefficient, stream));
+  RGC_HIP(launch_clip_coefficient(A, plan->num_wgs, threshold, coefficient, stream));
   return RGC_OK;
 }
 
@@ -575,14 +576,13 @@ int rgc_message_means(rgc_ctx* ctx, const rgc_layer* layers, int32_t num_layers,
   CompressPlan* plan = nullptr;
   const int rc = plan_for_layers(ctx, layers, num_layers, stream, &plan);
   if (rc != RGC_OK) return rc;
-  const size_t part_slots = static_cast<size_t>(num_layers) * kMeanPartsMax;
-  if (ctx->d_mean_part.n < part_slots) {                    // first use, or a longer list than before
-    RGC_HIP(hipStreamSynchronize(stream));                  // the buffer may still be in use
-    RGC_HIP(ctx->d_mean_part.alloc(part_slots));
-  }
+  const size_t parts = static_cast<size_t>(ctx->max_layers) * kMeanPartsMax;
+  if (ctx->d_mean_part.n < parts * kExactWordsPerPart)      // first use only
+    RGC_HIP(ctx->d_mean_part.alloc(parts * kExactWordsPerPart));
   CompressArgs A{};
   fill_plan_args(ctx, plan, A);
-  RGC_HIP(launch_message_means(A, static_cast<uint32_t>(num_layers), plan->max_k, ctx->d_mean_part.p, means, stream));
+  RGC_HIP(launch_message_means(A, static_cast<uint32_t>(num_layers), plan->max_k,
+                               exact_parts_at(ctx->d_mean_part.p, parts), means, stream));
   return RGC_OK;
 }
 
@@ -601,7 +601,8 @@ int rgc_compress_layers_threshold(rgc_ctx* ctx, const rgc_layer* layers, int32_t
   CompressPlan* plan = nullptr;
   const int rc = plan_for_layers(ctx, layers, num_layers, stream, &plan);
   if (rc != RGC_OK) return rc;
-  if (ctx->d_norm_part.n < ctx->wc_max) RGC_HIP(ctx->d_norm_part.alloc(ctx->wc_max));          // first use only
+  if (ctx->d_norm_part.n < ctx->wc_max * kExactWordsPerPart)                              // first use only
+    RGC_HIP(ctx->d_norm_part.alloc(ctx->wc_max * kExactWordsPerPart));
   if (ctx->d_moments.n < static_cast<size_t>(ctx->max_layers))
     RGC_HIP(ctx->d_moments.alloc(static_cast<size_t>(ctx->max_layers)));
   ThresholdArgs A{};
@@ -610,7 +611,7 @@ int rgc_compress_layers_threshold(rgc_ctx* ctx, const rgc_layer* layers, int32_t
   A.thresholds = thresholds;
   A.nnz = nnz;
   A.grad_scale = grad_scale;
-  A.part_sum = ctx->d_norm_part.p;
+  A.sum_parts = exact_parts_at(ctx->d_norm_part.p, ctx->wc_max);
   A.part_max = reinterpret_cast<float*>(ctx->d_wc_b.p);
   A.counts = ctx->d_wc_a.p;
   A.listed = ctx->d_cand_cnt.p;

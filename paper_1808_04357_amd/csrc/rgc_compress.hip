@@ -21,7 +21,7 @@
 // Per layer decisions are taken by the last workgroup of the layer to finish a phase (a two-level
 // election with device-scope atomic counters; what it reads was written with device-scope stores, so no
 // fence, no host round trip and no spinning is needed).
-#include "rgc_device.h"
+#include "rgc_exact.h"
 
 #include <mutex>
 
@@ -1723,11 +1723,14 @@ __global__ void wave_scan_selftest_kernel(uint32_t* io) {
 // ------------------------------------------------------------------ local gradient clipping
 // Section 2.4: the gradients of all layers are clipped by their common L2 norm, locally and
 // before they are added to the residuals; with N workers the threshold is max_norm / sqrt(N).
-// Two launches, both with a fixed order of additions (the same coefficient on every run): every
-// wave sums the squares of its wave-chunk of the gradient in fp64 (the product of two floats is
-// exact there) and leaves one partial sum per wave-chunk; one workgroup then adds the partial
-// sums up and stores  c = norm > threshold ? threshold / norm : 1  as a float.
+// The norm is the square root of the exactly rounded sum of the squares (rgc_exact.h), so the same
+// coefficient comes out whatever the tiling.  Two launches: every workgroup leaves one part of the
+// sum for its four wave-chunks of the gradient; one workgroup then adds the parts up, rounds, and
+// stores  c = norm > threshold ? threshold / norm : 1  as a float.
 __global__ void __launch_bounds__(kBlockThreads) grad_sqnorm_kernel(CompressArgs A) {
+  __shared__ ExactShared sh;
+  exact_shared_init(sh);
+  __syncthreads();
   // The workgroups walk through the gradients against the direction of the streaming pass that
   // follows: what this pass reads last is what that one reads first, and finds in the memory-side
   // cache (the pair of calls is 18 us shorter on the VGG16-shaped set than with both walking the
@@ -1736,90 +1739,73 @@ __global__ void __launch_bounds__(kBlockThreads) grad_sqnorm_kernel(CompressArgs
   const uint32_t l = A.wg2layer[wg];
   const LayerDesc L = A.layers[l];
   const uint32_t wc_local = (wg - L.wg_first) * kWavesPerBlock + (threadIdx.x >> 6);
-  if (wc_local >= L.wc_count) return;
-  const uint32_t begin = wc_local * A.chunk;
-  const uint32_t end = (L.n - begin) < A.chunk ? L.n : begin + A.chunk;
-  const uint32_t lane = lane_id();
-  double sum = 0.0;
-  uint32_t base = begin;
-  if ((reinterpret_cast<uintptr_t>(L.grad) & 15u) == 0u) {
-    // whole groups of 64 x 4 elements, eight 16-byte loads of a lane in flight
-    const gptr<const vf4> G4 = as_global(reinterpret_cast<const vf4*>(L.grad + begin));
-    const uint32_t nfull = (end - begin) / kGroupElems;
-    uint32_t g = 0;
-    for (; g + 8u <= nfull; g += 8u) {
-      vf4 q[8];
+  ExactAcc acc{0.0, 0.0, 0u};
+  if (wc_local < L.wc_count) {
+    const uint32_t begin = wc_local * A.chunk;
+    const uint32_t end = (L.n - begin) < A.chunk ? L.n : begin + A.chunk;
+    const uint32_t lane = lane_id();
+    uint32_t base = begin;
+    if ((reinterpret_cast<uintptr_t>(L.grad) & 15u) == 0u) {
+      // whole groups of 64 x 4 elements, eight 16-byte loads of a lane in flight
+      const gptr<const vf4> G4 = as_global(reinterpret_cast<const vf4*>(L.grad + begin));
+      const uint32_t nfull = (end - begin) / kGroupElems;
+      uint32_t g = 0;
+      for (; g + 8u <= nfull; g += 8u) {
+        vf4 q[8];
 #pragma unroll
-      for (uint32_t t = 0; t < 8u; ++t) q[t] = G4[(g + t) * kWaveSize + lane];
+        for (uint32_t t = 0; t < 8u; ++t) q[t] = G4[(g + t) * kWaveSize + lane];
 #pragma unroll
-      for (uint32_t t = 0; t < 8u; ++t) {
-        const double x = q[t].x, y = q[t].y, z = q[t].z, w = q[t].w;
-        sum += x * x; sum += y * y; sum += z * z; sum += w * w;
+        for (uint32_t t = 0; t < 8u; ++t) {
+          exact_add_square(acc, q[t].x, sh.digits);
+          exact_add_square(acc, q[t].y, sh.digits);
+          exact_add_square(acc, q[t].z, sh.digits);
+          exact_add_square(acc, q[t].w, sh.digits);
+        }
       }
+      base = begin + g * kGroupElems;
     }
-    base = begin + g * kGroupElems;
-  }
-  for_each_group(L.grad, false, base, end,
-                 [&](const float (&a)[4], uint32_t nvalid, uint32_t) {
+    for_each_group(L.grad, false, base, end,
+                   [&](const float (&a)[4], uint32_t nvalid, uint32_t) {
 #pragma unroll
-                   for (int j = 0; j < 4; ++j) {
-                     if (static_cast<uint32_t>(j) < nvalid) {
-                       const double x = static_cast<double>(a[j]);
-                       sum += x * x;
+                     for (int j = 0; j < 4; ++j) {
+                       if (static_cast<uint32_t>(j) < nvalid) exact_add_square(acc, a[j], sh.digits);
                      }
-                   }
-                 });
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) sum += __shfl_xor(sum, o);
-  if (lane_id() == 0) A.norm_part[L.wc_first + wc_local] = sum;
+                   });
+  }
+  const ExactAcc total = exact_block_total(acc, sh);
+  if (threadIdx.x == 0u) exact_store_part(A.norm_parts, wg, total, sh);
 }
 
-__global__ void __launch_bounds__(kBlockThreads) clip_coefficient_kernel(const double* part, uint32_t count,
+__global__ void __launch_bounds__(kBlockThreads) clip_coefficient_kernel(ExactParts parts, uint32_t count,
                                                                           float threshold, float* coef) {
-  __shared__ double red[kBlockThreads];
-  double sum = 0.0;
-  for (uint32_t i = threadIdx.x; i < count; i += kBlockThreads) sum += part[i];
-  red[threadIdx.x] = sum;
+  __shared__ ExactShared sh;
+  exact_shared_init(sh);
   __syncthreads();
-  for (uint32_t step = kBlockThreads / 2u; step >= 1u; step >>= 1) {
-    if (threadIdx.x < step) red[threadIdx.x] += red[threadIdx.x + step];
-    __syncthreads();
-  }
-  if (threadIdx.x == 0) {
-    const double norm = sqrt(red[0]);
+  ExactAcc acc{0.0, 0.0, 0u};
+  for (uint32_t i = threadIdx.x; i < count; i += kBlockThreads) exact_take_part(acc, parts, i, sh);
+  const ExactAcc total = exact_block_total(acc, sh);
+  if (threadIdx.x == 0u) {
+    const double norm = sqrt(exact_round(total, sh));
     const double t = static_cast<double>(threshold);
     *coef = static_cast<float>(norm > t ? t / norm : 1.0);
   }
 }
 
-hipError_t launch_clip_coefficient(const CompressArgs& a, uint32_t num_wgs, uint32_t num_chunks, float threshold,
-                                   float* d_coef, hipStream_t s) {
+hipError_t launch_clip_coefficient(const CompressArgs& a, uint32_t num_wgs, float threshold, float* d_coef, hipStream_t s) {
   hipLaunchKernelGGL(grad_sqnorm_kernel, dim3(num_wgs), dim3(kBlockThreads), 0, s, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(clip_coefficient_kernel, dim3(1), dim3(kBlockThreads), 0, s, a.norm_part, num_chunks, threshold, d_coef);
+  hipLaunchKernelGGL(clip_coefficient_kernel, dim3(1), dim3(kBlockThreads), 0, s, a.norm_parts, num_wgs, threshold, d_coef);
   return hipGetLastError();
 }
 
 // ------------------------------------------------------------------ one value per message
 // Section 2.2 (quantization of the sparsified residuals): the k values of a message are replaced by
-// their average, so that the message carries its indices and one value.  The sum is taken in fp64 in
-// an order fixed by the layer list alone: the values are cut into parts of `part` elements (a
-// multiple of 256, at least 2048, and large enough that the longest message has at most
-// kMeanPartsMax parts); workgroup (l, p) adds part p of layer l up (thread t takes the elements
-// t, t + 256, ... of the part in that order, the 256 sums are added pairwise), a second launch adds
-// each layer's partial sums (lane i takes i, i + 64, ..., the 64 sums pairwise) and stores
-// (float)(sum / count).
-__device__ __forceinline__ double block_tree_sum(double x, double* red, uint32_t threads) {
-  red[threadIdx.x] = x;
-  __syncthreads();
-  for (uint32_t step = threads / 2u; step >= 1u; step >>= 1) {
-    if (threadIdx.x < step) red[threadIdx.x] += red[threadIdx.x + step];
-    __syncthreads();
-  }
-  return red[0];
-}
-
+// their average, so that the message carries its indices and one value.  The sum of the values is the
+// exactly rounded one (rgc_exact.h), divided by the count in fp64 and rounded to fp32.  The values are
+// cut into parts of `part` elements (a multiple of 256, at least 2048, and large enough that the
+// longest message has at most kMeanPartsMax parts); workgroup (l, p) takes part p of layer l, a second
+// launch adds each layer's parts up and stores the mean.  How the values are cut changes nothing.
 // Where the two kernels find a layer's message: in the descriptor table of a compression plan, or in
 // the kernel arguments themselves (the entry point that allocates nothing has no table to put them in).
 struct MessageRef {
@@ -1852,39 +1838,46 @@ __device__ __forceinline__ uint32_t message_length(const MessageRef& M) {
 }
 
 template <typename Messages>
-__global__ void __launch_bounds__(kBlockThreads) message_part_sums_kernel(Messages src, uint32_t part, double* part_sums) {
-  __shared__ double red[kBlockThreads];
+__global__ void __launch_bounds__(kBlockThreads) message_part_sums_kernel(Messages src, uint32_t part, ExactParts parts) {
+  __shared__ ExactShared sh;
+  exact_shared_init(sh);
+  __syncthreads();
   const MessageRef M = src.get(blockIdx.x);
   const uint32_t count = message_length(M);
   const uint64_t first = static_cast<uint64_t>(blockIdx.y) * part;
   if (first >= count) return;                               // uniform over the workgroup
   const uint32_t len = static_cast<uint32_t>(count - first < part ? count - first : part);
   const gptr<const float> val = as_global(M.val) + first;
-  double sum = 0.0;
+  ExactAcc acc{0.0, 0.0, 0u};
   uint32_t i = threadIdx.x;
-  for (; i + 7u * kBlockThreads < len; i += 8u * kBlockThreads) {   // eight loads in flight, added in order
+  for (; i + 7u * kBlockThreads < len; i += 8u * kBlockThreads) {   // eight loads in flight
     float v[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) v[j] = val[i + static_cast<uint32_t>(j) * kBlockThreads];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) sum += static_cast<double>(v[j]);
+    for (int j = 0; j < 8; ++j) exact_add_f32(acc, v[j], sh.digits);
   }
-  for (; i < len; i += kBlockThreads) sum += static_cast<double>(val[i]);
-  const double total = block_tree_sum(sum, red, kBlockThreads);
-  if (threadIdx.x == 0) part_sums[static_cast<size_t>(blockIdx.x) * kMeanPartsMax + blockIdx.y] = total;
+  for (; i < len; i += kBlockThreads) exact_add_f32(acc, val[i], sh.digits);
+  const ExactAcc total = exact_block_total(acc, sh);
+  if (threadIdx.x == 0u) exact_store_part(parts, static_cast<size_t>(blockIdx.x) * kMeanPartsMax + blockIdx.y, total, sh);
 }
 
 template <typename Messages>
-__global__ void __launch_bounds__(64) message_means_kernel(Messages src, uint32_t part, const double* part_sums, float* means) {
-  __shared__ double red[64];
+__global__ void __launch_bounds__(kBlockThreads) message_means_kernel(Messages src, uint32_t part, ExactParts parts, float* means) {
+  __shared__ ExactShared sh;
+  exact_shared_init(sh);
+  __syncthreads();
   const MessageRef M = src.get(blockIdx.x);
   const uint32_t count = message_length(M);
-  const uint32_t parts = static_cast<uint32_t>((static_cast<uint64_t>(count) + part - 1u) / part);
-  const double* mine = part_sums + static_cast<size_t>(blockIdx.x) * kMeanPartsMax;
-  double sum = 0.0;
-  for (uint32_t i = threadIdx.x; i < parts; i += 64u) sum += mine[i];
-  const double total = block_tree_sum(sum, red, 64u);
-  if (threadIdx.x == 0) means[blockIdx.x] = count ? static_cast<float>(total / static_cast<double>(count)) : 0.0f;
+  const uint32_t nparts = static_cast<uint32_t>((static_cast<uint64_t>(count) + part - 1u) / part);
+  ExactAcc acc{0.0, 0.0, 0u};
+  for (uint32_t i = threadIdx.x; i < nparts; i += kBlockThreads)
+    exact_take_part(acc, parts, static_cast<size_t>(blockIdx.x) * kMeanPartsMax + i, sh);
+  const ExactAcc total = exact_block_total(acc, sh);
+  if (threadIdx.x == 0u) {
+    const double sum = exact_round(total, sh);
+    means[blockIdx.x] = count ? static_cast<float>(sum / static_cast<double>(count)) : 0.0f;
+  }
 }
 
 // Elements per part for messages of at most max_k values: a multiple of 256, at least 2048, and large
@@ -1896,22 +1889,21 @@ static uint32_t mean_part_size(uint32_t max_k) {
 }
 
 template <typename Messages>
-static hipError_t launch_message_means_from(const Messages& src, uint32_t num_layers, uint32_t max_k, double* d_part,
+static hipError_t launch_message_means_from(const Messages& src, uint32_t num_layers, uint32_t max_k, const ExactParts& parts,
                                             float* d_means, hipStream_t s) {
   const uint32_t part = mean_part_size(max_k);
   const uint32_t parts_max = (max_k + part - 1u) / part;    // <= kMeanPartsMax
   hipLaunchKernelGGL(message_part_sums_kernel<Messages>, dim3(num_layers, parts_max ? parts_max : 1u), dim3(kBlockThreads), 0, s,
-                     src, part, d_part);
+                     src, part, parts);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(message_means_kernel<Messages>, dim3(num_layers), dim3(64), 0, s, src, part,
-                     static_cast<const double*>(d_part), d_means);
+  hipLaunchKernelGGL(message_means_kernel<Messages>, dim3(num_layers), dim3(kBlockThreads), 0, s, src, part, parts, d_means);
   return hipGetLastError();
 }
 
-hipError_t launch_message_means(const CompressArgs& a, uint32_t num_layers, uint32_t max_k, double* d_part,
+hipError_t launch_message_means(const CompressArgs& a, uint32_t num_layers, uint32_t max_k, const ExactParts& parts,
                                 float* d_means, hipStream_t s) {
-  return launch_message_means_from(TableMessages{a.layers}, num_layers, max_k, d_part, d_means, s);
+  return launch_message_means_from(TableMessages{a.layers}, num_layers, max_k, parts, d_means, s);
 }
 
 hipError_t launch_accumulate(const CompressArgs& a, uint32_t num_wgs, hipStream_t s) {
@@ -1957,12 +1949,12 @@ hipError_t launch_wave_scan_selftest(uint32_t* io, hipStream_t s) {
 // messages are named in the kernel arguments and the partial sums live in an array of the code object,
 // of which every device holds its own copy at its own address for as long as the process lives.
 static_assert(RGC_NOALLOC_MAX_LAYERS == rgc::kInlineMessagesMax, "the header states the limit of the kernel arguments");
-static __device__ __align__(256) double scratch[rgc::kInlineMessagesMax * rgc::kMeanPartsMax];   // 512 KiB
+static __device__ __align__(256) long long scratch[rgc::kInlineMessagesMax * rgc::kMeanPartsMax * rgc::kExactWordsPerPart];   // 1.44 MiB
 
 namespace {
 constexpr int kScratchDevices = 64;
 std::mutex g_scratch_mutex;
-double* g_scratch_ptr[kScratchDevices] = {};    // device address of `scratch` on each device, once asked for
+long long* g_scratch_ptr[kScratchDevices] = {};    // device address of `scratch` on each device, once asked for
 }  // namespace
 
 extern "C" int rgc_message_means_noalloc(const float* const* values, const int32_t* const* counts,
@@ -1985,7 +1977,7 @@ extern "C" int rgc_message_means_noalloc(const float* const* values, const int32
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return rgc::fail_hip(e, "hipGetDevice");
   if (dev < 0 || dev >= kScratchDevices) return RGC_EINVAL;
-  double* ptr = nullptr;
+  long long* ptr = nullptr;
   {
     // In host code the array's name is only a handle for the symbol; its address on the current device
     // is asked for once per device and used from then on.
@@ -1994,13 +1986,14 @@ extern "C" int rgc_message_means_noalloc(const float* const* values, const int32
       void* p = nullptr;
       e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
       if (e != hipSuccess || !p) return rgc::fail_hip(e != hipSuccess ? e : hipErrorInvalidSymbol, "hipGetSymbolAddress(scratch)");
-      g_scratch_ptr[dev] = static_cast<double*>(p);
+      g_scratch_ptr[dev] = static_cast<long long*>(p);
     }
     ptr = g_scratch_ptr[dev];
   }
   // Nothing in the array has to start at zero: the second kernel reads exactly the parts the first one
   // has just written (both derive them from the same message lengths).
-  e = rgc::launch_message_means_from(src, static_cast<uint32_t>(num_layers), max_k, ptr, means,
+  const rgc::ExactParts parts = rgc::exact_parts_at(ptr, static_cast<size_t>(rgc::kInlineMessagesMax) * rgc::kMeanPartsMax);
+  e = rgc::launch_message_means_from(src, static_cast<uint32_t>(num_layers), max_k, parts, means,
                                      static_cast<hipStream_t>(hip_stream));
   if (e != hipSuccess) return rgc::fail_hip(e, "rgc_message_means_noalloc launch");
   return RGC_OK;

@@ -101,6 +101,24 @@ struct LayerState {
   uint32_t pad_[3];
 };
 
+// Where the kernels of an exactly rounded sum leave their parts (one per workgroup): the running sum
+// and the sum of its rounding errors, the flags (digits in use, non-finite terms seen) and, only where
+// the flags say so, the part's fixed-point digits.
+constexpr int kExactDigits = 20;            // 32 bits each, from 2^-298 upwards: any sum of fp32 terms or of their squares
+constexpr size_t kExactWordsPerPart = 3 + kExactDigits;   // 8-byte words of one part
+struct ExactParts {
+  double* sc;                  // [parts][2]
+  unsigned long long* flags;   // [parts]
+  long long* digits;           // [parts][kExactDigits]
+};
+inline ExactParts exact_parts_at(void* base, size_t parts) {
+  ExactParts P;
+  P.sc = static_cast<double*>(base);
+  P.flags = reinterpret_cast<unsigned long long*>(P.sc + 2 * parts);
+  P.digits = reinterpret_cast<long long*>(P.flags + parts);
+  return P;
+}
+
 struct CompressArgs {
   const LayerDesc* layers;
   LayerState* state;
@@ -131,7 +149,7 @@ struct CompressArgs {
   uint32_t reverse;      // the streaming pass takes its workgroups in descending order
   uint32_t nesterov;     // momentum correction in its Nesterov form: u = m (u + g), a = (V + u) + g
   const float* grad_scale;   // device word every gradient element is multiplied with first, or null
-  double* norm_part;     // [wave-chunks] partial sums of squares (clipping coefficient only)
+  ExactParts norm_parts; // [workgroups] parts of the sum of squares (clipping coefficient only)
 };
 
 // ---------------------------------------------------------------- threshold binary search selection
@@ -148,8 +166,8 @@ struct ThresholdArgs {
   float* thresholds;        // [layers] the caller's: written by a search, read otherwise
   int32_t* nnz;             // [layers] the caller's, or null: elements above the threshold
   const float* grad_scale;  // device word every gradient element is multiplied with first, or null
-  double* part_sum;         // [wave-chunks] partial sums of |a|
-  float* part_max;          // [wave-chunks] partial maxima of |a|
+  ExactParts sum_parts;     // [workgroups] parts of the sum of |a|
+  float* part_max;          // [workgroups] partial maxima of |a|
   uint32_t* counts;         // [wave-chunks] elements above the threshold, then first output positions
   uint32_t* listed;         // [wave-chunks] elements above the threshold (kept; more than cap: list incomplete)
   uint2* slots;             // [wave-chunks][cap] (float bits, index) of the elements above a reused threshold
@@ -223,11 +241,10 @@ hipError_t launch_probe(const CompressArgs& a, uint32_t num_wgs, hipStream_t s);
 hipError_t launch_rank(const CompressArgs& a, uint32_t num_wgs, hipStream_t s);
 hipError_t launch_emit(const CompressArgs& a, uint32_t num_wgs, hipStream_t s);
 hipError_t launch_phase(const CompressArgs& a, uint32_t num_wgs, hipStream_t s);
-constexpr uint32_t kMeanPartsMax = 1024;   // partial sums per layer at most (rgc_message_means)
-hipError_t launch_message_means(const CompressArgs& a, uint32_t num_layers, uint32_t max_k, double* d_part,
+constexpr uint32_t kMeanPartsMax = 128;    // parts per layer at most (rgc_message_means)
+hipError_t launch_message_means(const CompressArgs& a, uint32_t num_layers, uint32_t max_k, const ExactParts& parts,
                                 float* d_means, hipStream_t s);
-hipError_t launch_clip_coefficient(const CompressArgs& a, uint32_t num_wgs, uint32_t num_chunks, float threshold,
-                                   float* d_coef, hipStream_t s);
+hipError_t launch_clip_coefficient(const CompressArgs& a, uint32_t num_wgs, float threshold, float* d_coef, hipStream_t s);
 hipError_t launch_poison(LayerState* st, uint32_t num_layers, int mode, hipStream_t s);
 hipError_t launch_decompress_table(const DecompressArgs& a, hipStream_t s);
 hipError_t launch_decompress_tiles(const DecompressArgs& a, hipStream_t s);

@@ -16,7 +16,7 @@
 //            ->  count  ->  offsets  ->  emit
 //   reuse:   accumulate (+ the elements above the given threshold, listed per wave-chunk)  ->  offsets
 //            ->  emit from the lists
-#include "rgc_device.h"
+#include "rgc_exact.h"
 
 namespace rgc {
 
@@ -181,12 +181,6 @@ __device__ __forceinline__ void accumulate_groups(const LayerDesc& L, uint32_t b
   }
 }
 
-__device__ __forceinline__ double wave_sum(double x) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off);   // both partners add the same two numbers
-  return x;
-}
-
 __device__ __forceinline__ float wave_max(float x) {
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) x = fmaxf(x, __shfl_xor(x, off));
@@ -196,99 +190,109 @@ __device__ __forceinline__ float wave_max(float x) {
 }  // namespace
 
 // ------------------------------------------------------------------ accumulate (+ moments or counts)
-// kCount = false (a search follows): leaves per wave-chunk the fp64 sum and the maximum of |a|.
+// kCount = false (a search follows): leaves per workgroup its part of the exactly rounded sum of |a|
+// (rgc_exact.h) and the maximum of |a|.
 // kCount = true (the threshold is given): leaves per wave-chunk the number of |a| > threshold and, in
 // the wave-chunk's list, those elements themselves (as many as the list holds).
 template <bool kCount, bool kReverse>
 __global__ void __launch_bounds__(kBlockThreads) threshold_accumulate_kernel(ThresholdArgs A) {
+  __shared__ ExactShared sh;
+  __shared__ float wave_mx[kWavesPerBlock];
+  if constexpr (!kCount) {
+    exact_shared_init(sh);
+    __syncthreads();
+  }
   const uint32_t wg = (kReverse != (A.reverse != 0u)) ? gridDim.x - 1u - blockIdx.x : blockIdx.x;
   const uint32_t l = A.wg2layer[wg];
   const LayerDesc L = A.layers[l];
   const Place p = place_of(A, L, l, wg);
-  if (p.begin == p.end) return;
-  const float thr = kCount ? *as_global(A.thresholds + l) : 0.0f;
-  double sum = 0.0;
+  ExactAcc acc{0.0, 0.0, 0u};
   float mx = 0.0f;
-  uint32_t cnt = 0u;                      // kCount: elements above the threshold so far, the same in every lane
-  const gptr<vu2> slot = as_global(reinterpret_cast<vu2*>(A.slots + static_cast<size_t>(p.wc) * A.cap));
-  auto take = [&](const float (&a)[4], uint32_t nvalid, uint32_t idx0) {
+  if (p.begin != p.end) {
+    const float thr = kCount ? *as_global(A.thresholds + l) : 0.0f;
+    uint32_t cnt = 0u;                      // kCount: elements above the threshold so far, the same in every lane
+    const gptr<vu2> slot = as_global(reinterpret_cast<vu2*>(A.slots + static_cast<size_t>(p.wc) * A.cap));
+    auto take = [&](const float (&a)[4], uint32_t nvalid, uint32_t idx0) {
+      if constexpr (kCount) {
+        // the elements above the threshold go to the wave-chunk's list in index order (ballot ranks);
+        // a list that is full only counts on, and the emit pass reads that wave-chunk from V instead
+        bool f[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) f[j] = static_cast<uint32_t>(j) < nvalid && fabsf(a[j]) > thr;
+        const unsigned long long m0 = __ballot(f[0]), m1 = __ballot(f[1]), m2 = __ballot(f[2]), m3 = __ballot(f[3]);
+        if ((m0 | m1 | m2 | m3) == 0ull) return;
+        uint32_t pos = cnt + rank_below(m0) + rank_below(m1) + rank_below(m2) + rank_below(m3);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if (f[j]) {
+            if (pos < A.cap) slot[pos] = vu2{fbits(a[j]), idx0 + static_cast<uint32_t>(j)};
+            ++pos;
+          }
+        }
+        cnt += popc64(m0) + popc64(m1) + popc64(m2) + popc64(m3);
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if (static_cast<uint32_t>(j) < nvalid) {
+            const float mag = fabsf(a[j]);
+            exact_add_f32(acc, mag, sh.digits);
+            mx = fmaxf(mx, mag);
+          }
+        }
+      }
+    };
+    AccumRule rule;
+    rule.m = A.m;
+    rule.scale = A.grad_scale ? *as_global(A.grad_scale) : 1.0f;
+    if (L.mom == nullptr) accumulate_groups<false, false>(L, p.begin, p.end, rule, take);
+    else if (!A.nesterov) accumulate_groups<true, false>(L, p.begin, p.end, rule, take);
+    else accumulate_groups<true, true>(L, p.begin, p.end, rule, take);
     if constexpr (kCount) {
-      // the elements above the threshold go to the wave-chunk's list in index order (ballot ranks);
-      // a list that is full only counts on, and the emit pass reads that wave-chunk from V instead
-      bool f[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) f[j] = static_cast<uint32_t>(j) < nvalid && fabsf(a[j]) > thr;
-      const unsigned long long m0 = __ballot(f[0]), m1 = __ballot(f[1]), m2 = __ballot(f[2]), m3 = __ballot(f[3]);
-      if ((m0 | m1 | m2 | m3) == 0ull) return;
-      uint32_t pos = cnt + rank_below(m0) + rank_below(m1) + rank_below(m2) + rank_below(m3);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        if (f[j]) {
-          if (pos < A.cap) slot[pos] = vu2{fbits(a[j]), idx0 + static_cast<uint32_t>(j)};
-          ++pos;
-        }
-      }
-      cnt += popc64(m0) + popc64(m1) + popc64(m2) + popc64(m3);
-    } else {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        if (static_cast<uint32_t>(j) < nvalid) {
-          const float mag = fabsf(a[j]);
-          sum += static_cast<double>(mag);
-          mx = fmaxf(mx, mag);
-        }
+      if (lane_id() == 0u) {
+        A.counts[p.wc] = cnt;
+        A.listed[p.wc] = cnt;
       }
     }
-  };
-  AccumRule rule;
-  rule.m = A.m;
-  rule.scale = A.grad_scale ? *as_global(A.grad_scale) : 1.0f;
-  if (L.mom == nullptr) accumulate_groups<false, false>(L, p.begin, p.end, rule, take);
-  else if (!A.nesterov) accumulate_groups<true, false>(L, p.begin, p.end, rule, take);
-  else accumulate_groups<true, true>(L, p.begin, p.end, rule, take);
-  if constexpr (kCount) {
-    if (lane_id() == 0u) {
-      A.counts[p.wc] = cnt;
-      A.listed[p.wc] = cnt;
-    }
-  } else {
-    const double s = wave_sum(sum);
+  }
+  if constexpr (!kCount) {
     const float m = wave_max(mx);
-    if (lane_id() == 0u) {
-      A.part_sum[p.wc] = s;
-      A.part_max[p.wc] = m;
+    if (lane_id() == 0u) wave_mx[threadIdx.x >> 6] = m;
+    const ExactAcc total = exact_block_total(acc, sh);      // its barriers also order wave_mx
+    if (threadIdx.x == 0u) {
+      exact_store_part(A.sum_parts, wg, total, sh);
+      float bm = wave_mx[0];
+#pragma unroll
+      for (int w = 1; w < kWavesPerBlock; ++w) bm = fmaxf(bm, wave_mx[w]);
+      A.part_max[wg] = bm;
     }
   }
 }
 
 // ------------------------------------------------------------------ moments of a layer
-// One workgroup per layer adds the partial sums in a fixed order (thread t takes the wave-chunks
-// t, t + 256, ...; the 256 sums pairwise), takes the maximum, stores mean, max and max - mean, and
-// clears the layer's histogram for the pass that follows.
+// One workgroup per layer adds the parts of the layer's workgroups up, rounds the sum once, takes the
+// maximum, stores mean, max and max - mean, and clears the layer's histogram for the pass that follows.
 __global__ void __launch_bounds__(kBlockThreads) threshold_moments_kernel(ThresholdArgs A) {
-  __shared__ double red[kBlockThreads];
+  __shared__ ExactShared sh;
   __shared__ float redm[kBlockThreads];
+  exact_shared_init(sh);
+  __syncthreads();
   const uint32_t l = blockIdx.x;
   const LayerDesc L = A.layers[l];
-  double sum = 0.0;
+  ExactAcc acc{0.0, 0.0, 0u};
   float mx = 0.0f;
-  for (uint32_t i = threadIdx.x; i < L.wc_count; i += kBlockThreads) {
-    sum += A.part_sum[L.wc_first + i];
-    mx = fmaxf(mx, A.part_max[L.wc_first + i]);
+  for (uint32_t i = threadIdx.x; i < L.wg_count; i += kBlockThreads) {
+    exact_take_part(acc, A.sum_parts, L.wg_first + i, sh);
+    mx = fmaxf(mx, A.part_max[L.wg_first + i]);
   }
-  red[threadIdx.x] = sum;
   redm[threadIdx.x] = mx;
-  __syncthreads();
+  const ExactAcc total = exact_block_total(acc, sh);        // holds barriers
   for (uint32_t step = kBlockThreads / 2u; step >= 1u; step >>= 1) {
-    if (threadIdx.x < step) {
-      red[threadIdx.x] += red[threadIdx.x + step];
-      redm[threadIdx.x] = fmaxf(redm[threadIdx.x], redm[threadIdx.x + step]);
-    }
+    if (threadIdx.x < step) redm[threadIdx.x] = fmaxf(redm[threadIdx.x], redm[threadIdx.x + step]);
     __syncthreads();
   }
   if (threadIdx.x == 0u) {
     ThresholdMoments M;
-    M.mean = static_cast<float>(red[0] / static_cast<double>(L.n));
+    M.mean = static_cast<float>(exact_round(total, sh) / static_cast<double>(L.n));
     M.max = redm[0];
     M.span = __fsub_rn(M.max, M.mean);
     M.counts_taken = 0u;

@@ -1,7 +1,7 @@
 """GPU parity of the Alternating Signs Quantization pieces (Section 2.2) against the CPU oracle:
 selection of the k largest / k smallest elements (indices, residual and velocity bit for bit),
-the one value of each message (the average; summed in another order than the oracle's, so one fp32
-ulp is allowed), and decompression of one-value messages (bit for bit)."""
+the one value of each message (the average of the exactly rounded sum: bit for bit, whatever the order
+the kernels add in), and decompression of one-value messages (bit for bit)."""
 import numpy as np
 import pytest
 
@@ -20,8 +20,9 @@ def rgc():
     return pkg
 
 
-def ulps(a, b):
-    return abs(int(np.array(a, np.float32).view(np.int32)) - int(np.array(b, np.float32).view(np.int32)))
+def same_f32(a, b):
+    a, b = np.float32(a), np.float32(b)
+    return (np.isnan(a) and np.isnan(b)) or a.view(np.uint32) == b.view(np.uint32)
 
 
 def run_asq(rgc, oracle, V0, G_list, ks, U0=None, m=0.0, tag="", extra_flags=0):
@@ -52,7 +53,7 @@ def run_asq(rgc, oracle, V0, G_list, ks, U0=None, m=0.0, tag="", extra_flags=0):
                 assert np.array_equal(u32(U[l]), u32(Uh[l])), where + ": velocity"
             if a_ref is not None:
                 assert np.array_equal(u32(val[l]), u32(a_ref[l][oi])), where + ": values"
-            assert ulps(got_means[l], omean) <= 1, where + ": mean %r vs %r" % (got_means[l], omean)
+            assert same_f32(got_means[l], omean), where + ": mean %r vs %r" % (got_means[l], omean)
         paths.append(ctx.last_paths(len(V0)))
     ctx.close()
     return paths
@@ -103,6 +104,56 @@ def test_mean_of_a_long_message(rgc, oracle):
     ks = [rgc.rgc_k_for_density(n, 10_000) for n in sizes]
     assert ks[0] > 10 * 2048
     run_asq(rgc, oracle, V, Gs, ks, tag="asq long message")
+
+
+@pytest.mark.parametrize("law", ["cancelling", "wide", "subnormal", "nonfinite"])
+def test_means_of_hard_sums(rgc, oracle, law):
+    """The mean is that of the exactly rounded sum: values that cancel, values 250 binary orders apart,
+    subnormal values, infinities and NaNs among them, in messages that span several workgroups and in tiny ones."""
+    import torch
+    g = np.random.default_rng({"cancelling": 1, "wide": 2, "subnormal": 3, "nonfinite": 4}[law])
+    sizes = [70_001, 5_000, 257, 3]
+    V = []
+    for n in sizes:
+        if law == "cancelling":
+            h = (g.standard_normal(n // 2) * np.exp2(g.integers(-30, 90, n // 2))).astype(np.float32)
+            v = np.concatenate([h, -h, np.full(n - 2 * (n // 2), 1e-30, np.float32)])
+            g.shuffle(v)
+        elif law == "wide":
+            v = (g.standard_normal(n) * np.exp2(g.integers(-125, 125, n).astype(np.float64))).astype(np.float32)
+        elif law == "subnormal":
+            v = (g.integers(-2 ** 20, 2 ** 20, n).astype(np.float64) * 2.0 ** -149).astype(np.float32)
+            v[::3] = np.float32(g.standard_normal())
+        else:
+            v = g.standard_normal(n).astype(np.float32)
+            v[g.integers(0, n)] = np.inf
+        V.append(v.astype(np.float32))
+    if law == "nonfinite":
+        V[1][7] = -np.inf           # infinities of both signs: NaN
+        V[1][9] = np.inf
+        V[2][100] = np.nan          # a NaN beside an infinity: NaN
+        V[3][:] = [-np.inf, 1.0, -np.inf]
+    # the messages are written by hand: rgc_message_means reads the value buffers and the counts of the list
+    dev = GpuLayers(rgc, [np.zeros(n, np.float32) for n in sizes], sizes)
+    for l, n in enumerate(sizes):
+        dev.out_val[l].copy_(torch.from_numpy(V[l]))
+    dev.out_count.copy_(torch.tensor(sizes, dtype=torch.int32))
+    ctx = rgc.Context(sum(sizes), len(sizes))
+    means = torch.full((len(sizes),), 7.0, dtype=torch.float32, device=torch.device("cuda:0"))
+    print("  hard sums: %s" % law, flush=True)
+    rgc.rgc_message_means(ctx, dev.layers, means, torch.cuda.current_stream())
+    got = means.cpu().numpy()
+    naive_differs = 0
+    for l, n in enumerate(sizes):
+        # the oracle's mean of these values: a layer made of them, every element sent (k = n)
+        _, omean, oc = oracle.compress_layer_asq(np.zeros(n, np.float32), V[l].copy(), n, +1)
+        assert oc == n
+        assert same_f32(got[l], omean), "%s layer %d: %r vs %r" % (law, l, got[l], omean)
+        with np.errstate(all="ignore"):
+            naive_differs += not same_f32(np.float32(np.cumsum(V[l].astype(np.float64))[-1] / n), omean)
+    if law == "cancelling":
+        assert naive_differs > 0, "the inputs do not tell an ordered fp64 sum from the exact one"
+    ctx.close()
 
 
 def test_no_hints_gives_the_same(rgc, oracle):

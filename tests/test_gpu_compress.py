@@ -358,8 +358,8 @@ def ulp_distance(a, b):
 
 
 def test_clipping_coefficient_and_scaled_gradients(rgc, oracle):
-    """rgc_clip_coefficient against the oracle's fp64 sum (the order of additions differs: one fp32 ulp
-    is allowed), then rgc_compress_layers_scaled with that very coefficient against the oracle fed the
+    """rgc_clip_coefficient against the oracle's (both take the exactly rounded sum of the squares: bit for
+    bit), then rgc_compress_layers_scaled with that very coefficient against the oracle fed the
     same number: bit for bit, several steps, plain, momentum-corrected and Nesterov."""
     import torch
     g = np.random.default_rng(62)
@@ -382,7 +382,7 @@ def test_clipping_coefficient_and_scaled_gradients(rgc, oracle):
             rgc.rgc_clip_coefficient(ctx, layers.layers, max_norm, 16, coef, stream)
             c_gpu = float(coef.cpu().numpy()[0])
             c_ref, sq = oracle.clip_coefficient(G, max_norm, 16)
-            assert ulp_distance(c_gpu, c_ref) <= 1, (t, c_gpu, c_ref)
+            assert ulp_distance(c_gpu, c_ref) == 0, (t, c_gpu, c_ref)
             if t % 2 == 0:
                 assert c_ref == 1.0 and c_gpu == 1.0, "below the threshold nothing is scaled"
             else:
@@ -391,6 +391,48 @@ def test_clipping_coefficient_and_scaled_gradients(rgc, oracle):
             msgs = oracle_step(oracle, G, Vh, ks, Uh, m, nesterov=bool(flags & rgc.RGC_NESTEROV), grad_scale=c_gpu)
             assert_layers_equal("scaled m=%g flags=%d step %d" % (m, flags, t), ks, layers.results(), msgs, Vh, Uh)
         ctx.close()
+
+
+@pytest.mark.parametrize("law", ["wide", "tiny_beside_large", "subnormal", "infinite", "nan"])
+def test_clipping_coefficient_of_hard_norms(rgc, oracle, law):
+    """Gradients whose squares span the whole fp64-exact range of fp32 products, tiny elements beside large
+    ones (their squares fall below the last bit of a running fp64 sum), subnormal elements, and elements that
+    are not finite (norm infinite: coefficient 0; norm NaN: the comparison fails, coefficient 1)."""
+    import torch
+    g = np.random.default_rng({"wide": 11, "tiny_beside_large": 12, "subnormal": 13, "infinite": 14, "nan": 15}[law])
+    sizes = [100_003, 9_000, 300, 2]
+    G = []
+    for n in sizes:
+        if law == "wide":
+            x = g.standard_normal(n) * np.exp2(g.integers(-70, 55, n).astype(np.float64))
+        elif law == "tiny_beside_large":
+            x = g.standard_normal(n) * np.where(g.random(n) < 0.5, 1e-12, 1.0)
+        elif law == "subnormal":
+            x = g.integers(-2 ** 22, 2 ** 22, n).astype(np.float64) * 2.0 ** -149
+        else:
+            x = g.standard_normal(n)
+        G.append(x.astype(np.float32))
+    if law == "infinite":
+        G[1][5] = -np.inf
+    if law == "nan":
+        G[2][5] = np.nan
+        G[0][1] = np.inf
+    V = [np.zeros(n, np.float32) for n in sizes]
+    layers = GpuLayers(rgc, V, [1] * len(sizes))
+    layers.set_grads(G)
+    ctx = rgc.Context(sum(sizes), len(sizes))
+    coef = torch.full((1,), 7.0, dtype=torch.float32, device=torch.device("cuda:0"))
+    for max_norm, workers in ((1e-30, 4), (1.0, 16), (1e30, 1)):
+        print("  hard norms: %s max_norm %g" % (law, max_norm), flush=True)
+        rgc.rgc_clip_coefficient(ctx, layers.layers, max_norm, workers, coef, torch.cuda.current_stream())
+        c_gpu = coef.cpu().numpy()[0]
+        c_ref, sq = oracle.clip_coefficient(G, max_norm, workers)
+        assert np.float32(c_gpu).view(np.uint32) == np.float32(c_ref).view(np.uint32), (law, max_norm, c_gpu, c_ref, sq)
+    if law == "infinite":
+        assert c_gpu == 0.0
+    if law == "nan":
+        assert c_gpu == 1.0
+    ctx.close()
 
 
 def test_clipping_coefficient_full_size_vgg16(rgc, oracle):
@@ -406,5 +448,5 @@ def test_clipping_coefficient_full_size_vgg16(rgc, oracle):
     rgc.rgc_clip_coefficient(ctx, layers.layers, 1.0, 128, coef, torch.cuda.current_stream())
     c_ref, sq = oracle.clip_coefficient(G, 1.0, 128)
     c_gpu = float(coef.cpu().numpy()[0])
-    assert c_ref < 1.0 and ulp_distance(c_gpu, c_ref) <= 1, (c_gpu, c_ref, sq)
+    assert c_ref < 1.0 and ulp_distance(c_gpu, c_ref) == 0, (c_gpu, c_ref, sq)
     ctx.close()

@@ -1,8 +1,8 @@
 """GPU test of rgc_message_means_noalloc, the entry point for callers that cannot allocate: its output
-must equal rgc_message_means' bit for bit (same kernels, same order of additions), on two calls in a
-row that share the library's static scratch array, the second with a smaller input, and both must agree
-with the CPU oracle's average to the bar the other average tests use (one fp32 ulp: the oracle adds in
-index order, the kernels in a fixed tree).  Collected last on purpose."""
+must equal rgc_message_means' bit for bit (same kernels), on two calls in a row that share the
+library's static scratch array, the second with a smaller input, and both must agree with the CPU
+oracle's average bit for bit as well (the sum behind it is the exactly rounded one on both sides).
+Collected last on purpose."""
 import ctypes
 
 import numpy as np
@@ -56,7 +56,7 @@ def check_call(rgc, oracle_mean_of, dev, ctx, ks, tag):
     _, val, cnt, _, _ = dev.results()
     for l in range(L):
         assert int(cnt[l]) == ks[l]
-        assert ulps(g_[l], oracle_mean_of(val[l])) <= 1, "%s layer %d" % (tag, l)
+        assert ulps(g_[l], oracle_mean_of(val[l])) == 0, "%s layer %d" % (tag, l)
     return g_
 
 
