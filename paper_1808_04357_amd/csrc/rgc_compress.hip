@@ -1727,6 +1727,79 @@ __global__ void wave_scan_selftest_kernel(uint32_t* io) {
 // coefficient comes out whatever the tiling.  Two launches: every workgroup leaves one part of the
 // sum for its four wave-chunks of the gradient; one workgroup then adds the parts up, rounds, and
 // stores  c = norm > threshold ? threshold / norm : 1  as a float.
+//
+// The squares of one wave-chunk, fast: one error-free addition per element into s, its error added
+// to c with an ordinary addition, and the smallest and largest magnitude seen kept beside them.  The
+// ordinary additions were exact if every error is a multiple of q, the last bit of the smallest
+// square, and their sums stay below 2^53 q; a lane checks that afterwards from the exponents (the
+// errors of the at most 2^k additions of a lane are at most half a last bit of its final s each).  A
+// wave in which a lane cannot show it (elements some 2^23 apart, an element that is not finite) takes
+// its chunk again the careful way (kCareful), which needs no such condition.
+struct SquareSums {
+  ExactAcc acc{0.0, 0.0, 0u};
+  uint32_t least = 0xFFFFFFFFu;   // smallest magnitude bits - 1 over the non-zero elements
+  uint32_t most = 0u;             // largest magnitude bits
+};
+
+template <bool kCareful>
+__device__ __forceinline__ void add_square(SquareSums& S, float x, long long* digits) {
+  if constexpr (kCareful) {
+    exact_add_square(S.acc, x, digits);
+  } else {
+    const uint32_t b = fbits(x) & 0x7FFFFFFFu;
+    S.most = b > S.most ? b : S.most;
+    S.least = (b - 1u) < S.least ? (b - 1u) : S.least;        // zero wraps around and never counts
+    const double d = static_cast<double>(x);
+    double sum, err;
+    two_sum(S.acc.s, d * d, sum, err);
+    S.acc.s = sum;
+    S.acc.c += err;
+  }
+}
+
+template <bool kCareful>
+__device__ __forceinline__ void squares_of_chunk(const float* grad, uint32_t begin, uint32_t end, SquareSums& S, long long* digits) {
+  const uint32_t lane = lane_id();
+  uint32_t base = begin;
+  if ((reinterpret_cast<uintptr_t>(grad) & 15u) == 0u) {
+    // whole groups of 64 x 4 elements, eight 16-byte loads of a lane in flight
+    const gptr<const vf4> G4 = as_global(reinterpret_cast<const vf4*>(grad + begin));
+    const uint32_t nfull = (end - begin) / kGroupElems;
+    uint32_t g = 0;
+    for (; g + 8u <= nfull; g += 8u) {
+      vf4 q[8];
+#pragma unroll
+      for (uint32_t t = 0; t < 8u; ++t) q[t] = G4[(g + t) * kWaveSize + lane];
+#pragma unroll
+      for (uint32_t t = 0; t < 8u; ++t) {
+        add_square<kCareful>(S, q[t].x, digits);
+        add_square<kCareful>(S, q[t].y, digits);
+        add_square<kCareful>(S, q[t].z, digits);
+        add_square<kCareful>(S, q[t].w, digits);
+      }
+    }
+    base = begin + g * kGroupElems;
+  }
+  for_each_group(grad, false, base, end,
+                 [&](const float (&a)[4], uint32_t nvalid, uint32_t) {
+#pragma unroll
+                   for (int j = 0; j < 4; ++j) {
+                     if (static_cast<uint32_t>(j) < nvalid) add_square<kCareful>(S, a[j], digits);
+                   }
+                 });
+}
+
+// True if the fast sums of this lane are the exact ones (see above); terms: at most 2^k per lane.
+__device__ __forceinline__ bool square_sums_exact(const SquareSums& S, uint32_t k) {
+  if (S.most >= 0x7F800000u) return false;                   // an infinity or a NaN
+  if (S.least == 0xFFFFFFFFu) return true;                   // nothing but zeros
+  uint32_t fmin = (S.least + 1u) >> 23;                      // exponent field of the smallest non-zero magnitude
+  fmin = fmin ? fmin : 1u;                                   // subnormal: the same last bit as the field 1
+  const uint32_t sf = static_cast<uint32_t>(static_cast<unsigned long long>(__double_as_longlong(S.acc.s)) >> 52) & 0x7FFu;
+  // errors: multiples of q = 2^(2 (fmin - 150)), their sums at most 2^(k-1) 2^(sf - 1075); exact up to 2^53 q
+  return sf + k <= 2u * fmin + 829u;
+}
+
 __global__ void __launch_bounds__(kBlockThreads) grad_sqnorm_kernel(CompressArgs A) {
   __shared__ ExactShared sh;
   exact_shared_init(sh);
@@ -1739,40 +1812,19 @@ __global__ void __launch_bounds__(kBlockThreads) grad_sqnorm_kernel(CompressArgs
   const uint32_t l = A.wg2layer[wg];
   const LayerDesc L = A.layers[l];
   const uint32_t wc_local = (wg - L.wg_first) * kWavesPerBlock + (threadIdx.x >> 6);
-  ExactAcc acc{0.0, 0.0, 0u};
+  SquareSums S;
   if (wc_local < L.wc_count) {
     const uint32_t begin = wc_local * A.chunk;
     const uint32_t end = (L.n - begin) < A.chunk ? L.n : begin + A.chunk;
-    const uint32_t lane = lane_id();
-    uint32_t base = begin;
-    if ((reinterpret_cast<uintptr_t>(L.grad) & 15u) == 0u) {
-      // whole groups of 64 x 4 elements, eight 16-byte loads of a lane in flight
-      const gptr<const vf4> G4 = as_global(reinterpret_cast<const vf4*>(L.grad + begin));
-      const uint32_t nfull = (end - begin) / kGroupElems;
-      uint32_t g = 0;
-      for (; g + 8u <= nfull; g += 8u) {
-        vf4 q[8];
-#pragma unroll
-        for (uint32_t t = 0; t < 8u; ++t) q[t] = G4[(g + t) * kWaveSize + lane];
-#pragma unroll
-        for (uint32_t t = 0; t < 8u; ++t) {
-          exact_add_square(acc, q[t].x, sh.digits);
-          exact_add_square(acc, q[t].y, sh.digits);
-          exact_add_square(acc, q[t].z, sh.digits);
-          exact_add_square(acc, q[t].w, sh.digits);
-        }
-      }
-      base = begin + g * kGroupElems;
+    squares_of_chunk<false>(L.grad, begin, end, S, sh.digits);
+    const uint32_t per_lane = A.chunk / kWaveSize;           // elements of a lane at most (the chunk is a multiple of 256)
+    const uint32_t k = 32u - static_cast<uint32_t>(__clz(static_cast<int>(per_lane - 1u)));
+    if (__any(!square_sums_exact(S, k))) {
+      S = SquareSums{};
+      squares_of_chunk<true>(L.grad, begin, end, S, sh.digits);
     }
-    for_each_group(L.grad, false, base, end,
-                   [&](const float (&a)[4], uint32_t nvalid, uint32_t) {
-#pragma unroll
-                     for (int j = 0; j < 4; ++j) {
-                       if (static_cast<uint32_t>(j) < nvalid) exact_add_square(acc, a[j], sh.digits);
-                     }
-                   });
   }
-  const ExactAcc total = exact_block_total(acc, sh);
+  const ExactAcc total = exact_block_total(S.acc, sh);
   if (threadIdx.x == 0u) exact_store_part(A.norm_parts, wg, total, sh);
 }
 
