@@ -248,6 +248,48 @@ def measure_compress(torch, rgc, ctx, wl, stream, steps, warmup):
     return out
 
 
+def measure_step_on(torch, rgc, ctx, wl, stream, steps, dev, synth):
+    """The whole step (compression + decompression of 128 workers' messages of the same shape) on a layer set."""
+    dec = DecompressWorkload(torch, rgc, wl.sizes, 128, dev, synth)
+
+    def step():
+        wl.step(ctx, stream)
+        dec.step(ctx, stream)
+
+    for _ in range(40):
+        step()
+    ms = time_loop(torch, step, steps)
+    ms_d = time_loop(torch, lambda: dec.step(ctx, stream), steps)
+    nbytes = wl.alg_bytes + dec.alg_bytes
+    return {"ms_per_step": ms, "gradient_GBps": 4.0 * wl.total / ms / 1e6, "alg_bytes": nbytes,
+            "hbm_frac_step_algorithmic": nbytes / (ms * 1e-3) / (HBM_PEAK_GBPS * 1e9),
+            "decompress_alone_ms": ms_d, "decompress_entries": dec.entries}
+
+
+def measure_density(torch, rgc, ctx, vgg, ppm, stream, steps, dev):
+    """The compression call on the headline tensors at another density (Section 2.5: the warm-up period's):
+    message buffers of its own, residual and velocity shared with the headline workload."""
+    ks = [rgc.rgc_k_for_density(n, ppm) for n in vgg.sizes]
+    oi = [torch.empty(k, dtype=torch.int32, device=dev) for k in ks]
+    ov = [torch.empty(k, dtype=torch.float32, device=dev) for k in ks]
+    lists = [rgc.LayerList(g, vgg.V, ks, oi, ov, vgg.out_count, vgg.U) for g in vgg.G]
+    calls = [0]
+
+    def warm_step():
+        rgc.rgc_compress_layers(ctx, lists[calls[0] % len(lists)], vgg.m, 0, stream)
+        calls[0] += 1
+
+    for _ in range(16):                           # the two-pass path's hints settle within a few calls
+        warm_step()
+    misses0 = sum(r[4] for r in ctx.last_stats(len(vgg.sizes), stream))
+    ms = time_loop(torch, warm_step, min(steps, 20))
+    alg = vgg.alg_bytes_stream + 16 * sum(ks)
+    return {"sum_k": sum(ks), "ms_per_iter": ms, "alg_bytes": alg,
+            "hbm_frac_algorithmic": alg / (ms * 1e-3) / (HBM_PEAK_GBPS * 1e9),
+            "hint_misses_in_timed_calls": sum(r[4] for r in ctx.last_stats(len(vgg.sizes), stream)) - misses0,
+            "layers_on_multi_pass_path_last_call": sum(1 for p in ctx.last_paths(len(vgg.sizes), stream) if p != 0)}
+
+
 def cpu_baseline(torch, wl, dec):
     """The oracle as it stands, timed on the host over one whole step of the headline workload: one
     compress step of the layer set on one thread (about 10 s for the VGG16 set: the largest tensor
@@ -300,6 +342,12 @@ def main():
     ap.add_argument("--workload", choices=["lstm", "resnet50", "single_1Mi", "uniform_1Mi", "uniform_64Mi"],
                     help="time only the compression call on this layer set and print its block (for a profiler: "
                          "the per-kernel averages are then those of this workload)")
+    ap.add_argument("--with-step", action="store_true",
+                    help="with --workload: also time the whole step (compression + decompression of 128 workers' "
+                         "messages of the same shape) on that layer set")
+    ap.add_argument("--density-ppm", type=int,
+                    help="time only the compression call on the headline tensors at this density (parts per million; "
+                         "the warm-up period's densities of Section 2.5) and print its block (for a profiler)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain device copies of 4*138,344,128 bytes (a yardstick of known "
                          "size for rocprofv3 byte counters)")
@@ -326,12 +374,22 @@ def main():
         ctx = rgc.Context(wl.total, 256)
         out = measure_compress(torch, rgc, ctx, wl, stream, args.steps, args.warmup)
         out["workload"] = args.workload
+        if args.with_step:
+            out["step"] = measure_step_on(torch, rgc, ctx, wl, stream, args.steps, dev, synth)
         print(json.dumps(out))
         return
 
     log("generating VGG16-shaped inputs (138.3 M elements, %d gradient sets)..." % NUM_GRAD_SETS)
     t0 = time.perf_counter()
     vgg = CompressWorkload(torch, rgc, synth.config_vgg16(num_grads=NUM_GRAD_SETS), dev)
+    if args.density_ppm:
+        ctx = rgc.Context(vgg.total, 256)
+        for _ in range(20):                        # the state the densities meet in the default run: a residual in use
+            vgg.step(ctx, stream)
+        out = measure_density(torch, rgc, ctx, vgg, args.density_ppm, stream, args.steps, dev)
+        out["density_ppm"] = args.density_ppm
+        print(json.dumps(out))
+        return
     log("  %.1f s; generating 128 workers' messages..." % (time.perf_counter() - t0))
     dec = DecompressWorkload(torch, rgc, vgg.sizes, 128, dev, synth)
     ctx = rgc.Context(vgg.total, 256)
@@ -359,7 +417,7 @@ def main():
     step_bytes = vgg.alg_bytes + dec.alg_bytes
     value = 4.0 * vgg.total / ms_step / 1e6          # gradient GB/s through the whole step
     # the same step K more times, each bracketed by its own pair of events on the stream (median and minimum)
-    per_step = [float("nan")]
+    per_step = [None]
     if not args.step_only:
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
         for a, b in evs:
@@ -460,27 +518,7 @@ def main():
     if not args.step_only:
         warm_info = {}
         for ppm in (250_000, 62_500, 15_625, 4_000):
-            ks = [rgc.rgc_k_for_density(n, ppm) for n in vgg.sizes]
-            oi = [torch.empty(k, dtype=torch.int32, device=dev) for k in ks]
-            ov = [torch.empty(k, dtype=torch.float32, device=dev) for k in ks]
-            lists = [rgc.LayerList(g, vgg.V, ks, oi, ov, vgg.out_count, vgg.U) for g in vgg.G]
-            calls = [0]
-
-            def warm_step():
-                rgc.rgc_compress_layers(ctx, lists[calls[0] % len(lists)], vgg.m, 0, stream)
-                calls[0] += 1
-
-            for _ in range(16):                           # the two-pass path's hints settle within a few calls
-                warm_step()
-            misses0 = sum(r[4] for r in ctx.last_stats(len(vgg.sizes), stream))
-            ms = time_loop(torch, warm_step, min(args.steps, 20))
-            alg = vgg.alg_bytes_stream + 16 * sum(ks)
-            warm_info["%g%%" % (ppm / 1e4)] = {
-                "sum_k": sum(ks), "ms_per_iter": ms, "alg_bytes": alg,
-                "hbm_frac_algorithmic": alg / (ms * 1e-3) / (HBM_PEAK_GBPS * 1e9),
-                "hint_misses_in_timed_calls": sum(r[4] for r in ctx.last_stats(len(vgg.sizes), stream)) - misses0,
-                "layers_on_multi_pass_path_last_call": sum(1 for p in ctx.last_paths(len(vgg.sizes), stream) if p != 0)}
-            del lists, oi, ov
+            warm_info["%g%%" % (ppm / 1e4)] = measure_density(torch, rgc, ctx, vgg, ppm, stream, args.steps, dev)
         torch.cuda.empty_cache()
 
     if args.calibrate_copy:
@@ -501,22 +539,7 @@ def main():
             if name == "lstm":      # the paper selects the large layers of its recurrent models this way
                 others[name]["threshold_search"] = measure_threshold(torch, rgc, ctx, wl, stream, args.steps, dev)
                 # the whole step on this layer set too: compression + decompression of 128 workers' messages
-                ldec = DecompressWorkload(torch, rgc, wl.sizes, 128, dev, synth)
-
-                def lstm_step():
-                    wl.step(ctx, stream)
-                    ldec.step(ctx, stream)
-
-                for _ in range(40):
-                    lstm_step()
-                ms_l = time_loop(torch, lstm_step, args.steps)
-                ms_ld = time_loop(torch, lambda: ldec.step(ctx, stream), args.steps)
-                lbytes = wl.alg_bytes + ldec.alg_bytes
-                others[name]["step"] = {"ms_per_step": ms_l, "gradient_GBps": 4.0 * wl.total / ms_l / 1e6,
-                                        "alg_bytes": lbytes,
-                                        "hbm_frac_step_algorithmic": lbytes / (ms_l * 1e-3) / (HBM_PEAK_GBPS * 1e9),
-                                        "decompress_alone_ms": ms_ld, "decompress_entries": ldec.entries}
-                del ldec
+                others[name]["step"] = measure_step_on(torch, rgc, ctx, wl, stream, args.steps, dev, synth)
             del wl
             torch.cuda.empty_cache()
 

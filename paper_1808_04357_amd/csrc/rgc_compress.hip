@@ -1833,11 +1833,11 @@ __global__ void __launch_bounds__(kBlockThreads) clip_coefficient_kernel(ExactPa
   __shared__ ExactShared sh;
   exact_shared_init(sh);
   __syncthreads();
-  ExactAcc acc{0.0, 0.0, 0u};
-  for (uint32_t i = threadIdx.x; i < count; i += kBlockThreads) exact_take_part(acc, parts, i, sh);
-  const ExactAcc total = exact_block_total(acc, sh);
+  ExactPair acc;
+  exact_take_parts(acc, parts, 0u, count, sh);
+  const double sum = exact_finish(acc, sh);
   if (threadIdx.x == 0u) {
-    const double norm = sqrt(exact_round(total, sh));
+    const double norm = sqrt(sum);
     const double t = static_cast<double>(threshold);
     *coef = static_cast<float>(norm > t ? t / norm : 1.0);
   }
@@ -1922,12 +1922,10 @@ __global__ void __launch_bounds__(kBlockThreads) message_means_kernel(Messages s
   const MessageRef M = src.get(blockIdx.x);
   const uint32_t count = message_length(M);
   const uint32_t nparts = static_cast<uint32_t>((static_cast<uint64_t>(count) + part - 1u) / part);
-  ExactAcc acc{0.0, 0.0, 0u};
-  for (uint32_t i = threadIdx.x; i < nparts; i += kBlockThreads)
-    exact_take_part(acc, parts, static_cast<size_t>(blockIdx.x) * kMeanPartsMax + i, sh);
-  const ExactAcc total = exact_block_total(acc, sh);
+  ExactPair acc;
+  exact_take_parts(acc, parts, static_cast<size_t>(blockIdx.x) * kMeanPartsMax, nparts, sh);
+  const double sum = exact_finish(acc, sh);
   if (threadIdx.x == 0u) {
-    const double sum = exact_round(total, sh);
     means[blockIdx.x] = count ? static_cast<float>(sum / static_cast<double>(count)) : 0.0f;
   }
 }

@@ -146,13 +146,11 @@ __device__ __forceinline__ ExactAcc exact_block_total(ExactAcc a, ExactShared& s
     const uint32_t bf = __shfl_down(a.flags, off);
     exact_join(a, bs, bc, bf, lane < off, sh.digits);
   }
-  // a lane that spilled on behalf of others must be seen by lane 0: the bit travels with the flags
-  // only downwards, so gather it once more over the wave
-  const uint32_t any = static_cast<uint32_t>(__ballot((a.flags & kExactSpilled) != 0u) != 0ull);
+  // (the flags, the note of a spill among them, have travelled down the tree with the sums)
   if (lane == 0u) {
     sh.s[wave] = a.s;
     sh.c[wave] = a.c;
-    sh.flags[wave] = a.flags | (any ? kExactSpilled : 0u);
+    sh.flags[wave] = a.flags;
   }
   __syncthreads();
   if (threadIdx.x == 0u) {
@@ -175,23 +173,66 @@ __device__ __forceinline__ void exact_store_part(const ExactParts& P, size_t par
   }
 }
 
-// One thread takes one part into its accumulator (and the part's digits into the workgroup's).
-__device__ __forceinline__ void exact_take_part(ExactAcc& a, const ExactParts& P, size_t part, ExactShared& sh) {
+// The last kernel of a sum.  Every thread of the workgroup takes the parts first + threadIdx.x,
+// first + threadIdx.x + blockDim.x, ... below first + count, eight of them asked for at a time (one thread
+// adding up a few dozen parts is a chain of memory round trips otherwise).  The parts' running sums go to one
+// accumulator and their error sums to another: the two kinds lie some fifty binary orders apart, and one
+// accumulator for both would have to put nearly every error sum into the digits.
+struct ExactPair {
+  ExactAcc sums{0.0, 0.0, 0u};
+  ExactAcc errs{0.0, 0.0, 0u};
+};
+
+__device__ __forceinline__ void exact_take_parts(ExactPair& a, const ExactParts& P, size_t first, uint32_t count, ExactShared& sh) {
+  constexpr uint32_t kBatch = 8u;
   const gptr<const double> sc = as_global(static_cast<const double*>(P.sc));
-  const uint32_t f = static_cast<uint32_t>(as_global(static_cast<const unsigned long long*>(P.flags))[part]);
-  exact_add(a, sc[2u * part], sh.digits);
-  exact_add(a, sc[2u * part + 1u], sh.digits);
-  a.flags |= f;
-  if (f & kExactSpilled) {
-    const gptr<const long long> dg = as_global(static_cast<const long long*>(P.digits)) + part * kExactDigits;
-    for (int i = 0; i < kExactDigits; ++i) {
-      const long long v = dg[i];
-      if (v != 0ll) atomicAdd(reinterpret_cast<unsigned long long*>(&sh.digits[i]), static_cast<unsigned long long>(v));
+  const gptr<const unsigned long long> fl = as_global(static_cast<const unsigned long long*>(P.flags));
+  for (uint32_t i0 = threadIdx.x; i0 < count; i0 += kBatch * blockDim.x) {
+    double s[kBatch], c[kBatch];
+    uint32_t f[kBatch];
+#pragma unroll
+    for (uint32_t j = 0; j < kBatch; ++j) {
+      const uint32_t i = i0 + j * blockDim.x;
+      const bool in = i < count;
+      const size_t part = first + (in ? i : i0);
+      s[j] = sc[2u * part];
+      c[j] = sc[2u * part + 1u];
+      f[j] = in ? static_cast<uint32_t>(fl[part]) : 0xFFFFFFFFu;      // ~0: no such part
+    }
+#pragma unroll
+    for (uint32_t j = 0; j < kBatch; ++j) {
+      if (f[j] == 0xFFFFFFFFu) continue;
+      exact_add(a.sums, s[j], sh.digits);
+      exact_add(a.errs, c[j], sh.digits);
+      a.sums.flags |= f[j];
+      if (f[j] & kExactSpilled) {
+        const gptr<const long long> dg = as_global(static_cast<const long long*>(P.digits)) + (first + i0 + j * blockDim.x) * kExactDigits;
+        long long v[kExactDigits];                     // all asked for before the first is used
+#pragma unroll
+        for (int d = 0; d < kExactDigits; ++d) v[d] = dg[d];
+#pragma unroll
+        for (int d = 0; d < kExactDigits; ++d)
+          if (v[d] != 0ll) atomicAdd(reinterpret_cast<unsigned long long*>(&sh.digits[d]), static_cast<unsigned long long>(v[d]));
+      }
     }
   }
 }
 
 // Thread 0, after exact_block_total: the sum of everything the workgroup took, rounded once.
+__device__ __noinline__ double exact_round(const ExactAcc& total, ExactShared& sh);
+
+// Every thread brings what exact_take_parts gave it; thread 0 returns with the sum of all parts, rounded once
+// (the other threads with nothing of use).  Holds barriers.
+__device__ __forceinline__ double exact_finish(const ExactPair& mine, ExactShared& sh) {
+  const ExactAcc errs = exact_block_total(mine.errs, sh);
+  ExactAcc sums = exact_block_total(mine.sums, sh);
+  if (threadIdx.x != 0u) return 0.0;
+  if (errs.s != 0.0) exact_spill(errs.s, sh.digits);
+  if (errs.c != 0.0) exact_spill(errs.c, sh.digits);
+  sums.flags |= errs.flags;
+  return exact_round(sums, sh);
+}
+
 __device__ __noinline__ double exact_round(const ExactAcc& total, ExactShared& sh) {
   const uint32_t f = total.flags;
   if ((f & kExactNaN) || ((f & kExactPosInf) && (f & kExactNegInf))) return __longlong_as_double(0x7FF8000000000000ll);

@@ -278,21 +278,19 @@ __global__ void __launch_bounds__(kBlockThreads) threshold_moments_kernel(Thresh
   __syncthreads();
   const uint32_t l = blockIdx.x;
   const LayerDesc L = A.layers[l];
-  ExactAcc acc{0.0, 0.0, 0u};
+  ExactPair acc;
   float mx = 0.0f;
-  for (uint32_t i = threadIdx.x; i < L.wg_count; i += kBlockThreads) {
-    exact_take_part(acc, A.sum_parts, L.wg_first + i, sh);
-    mx = fmaxf(mx, A.part_max[L.wg_first + i]);
-  }
+  exact_take_parts(acc, A.sum_parts, L.wg_first, L.wg_count, sh);
+  for (uint32_t i = threadIdx.x; i < L.wg_count; i += kBlockThreads) mx = fmaxf(mx, A.part_max[L.wg_first + i]);
   redm[threadIdx.x] = mx;
-  const ExactAcc total = exact_block_total(acc, sh);        // holds barriers
+  const double sum = exact_finish(acc, sh);                 // holds barriers
   for (uint32_t step = kBlockThreads / 2u; step >= 1u; step >>= 1) {
     if (threadIdx.x < step) redm[threadIdx.x] = fmaxf(redm[threadIdx.x], redm[threadIdx.x + step]);
     __syncthreads();
   }
   if (threadIdx.x == 0u) {
     ThresholdMoments M;
-    M.mean = static_cast<float>(exact_round(total, sh) / static_cast<double>(L.n));
+    M.mean = static_cast<float>(sum / static_cast<double>(L.n));
     M.max = redm[0];
     M.span = __fsub_rn(M.max, M.mean);
     M.counts_taken = 0u;
