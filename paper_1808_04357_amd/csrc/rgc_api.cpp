@@ -39,7 +39,6 @@ namespace {
   } while (0)
 
 constexpr uint32_t kChunkSmallest = 4096;  // elements per wave-chunk for small layer sets
-constexpr uint32_t kChunkMin = 1024;
 // Candidate slots per wave-chunk = chunk / 16: sixty times the average number of candidates of a chunk at
 // density 0.1 %.  Tensors whose large values sit in a few rows (embedding gradients) fill single lists far
 // beyond the average; with chunk / 32 such a layer overflowed a list, and so missed its hint, in 20 of its first

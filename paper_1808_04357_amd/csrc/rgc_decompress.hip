@@ -364,7 +364,6 @@ __device__ void tile_generic(const DecompressArgs& A, GenericLds& S, const TileG
 // =================================================================== fast tiles
 constexpr uint32_t kFastShift = 9;
 constexpr uint32_t kFastThreads = 1u << kFastShift;   // 8 waves per tile
-constexpr uint32_t kFastR = 4;                  // entries a thread keeps in registers per tile
 constexpr uint32_t kRows = 48;                  // positions hit more than once in one tile
 constexpr uint32_t kRowStride = kBatchWorkers + 4;   // floats; the +4 spreads the rows over the LDS banks
 
