@@ -279,7 +279,7 @@ def measure_density(torch, rgc, ctx, vgg, ppm, stream, steps, dev):
         rgc.rgc_compress_layers(ctx, lists[calls[0] % len(lists)], vgg.m, 0, stream)
         calls[0] += 1
 
-    for _ in range(16):                           # the two-pass path's hints settle within a few calls
+    for _ in range(40):                           # the hints and margins of the dense layers settle within a few dozen calls
         warm_step()
     misses0 = sum(r[4] for r in ctx.last_stats(len(vgg.sizes), stream))
     ms = time_loop(torch, warm_step, min(steps, 20))

@@ -44,11 +44,9 @@ constexpr uint32_t kChunkSmallest = 4096;  // elements per wave-chunk for small 
 // beyond the average; with chunk / 32 such a layer overflowed a list, and so missed its hint, in 20 of its first
 // 50 calls, with chunk / 16 in 2.
 constexpr uint32_t kCapDiv = 16;
-// Two-pass layers (high densities) list the keys around the hinted threshold in lists of their own, a quarter of a
-// wave-chunk long (2 bytes per element of scratch, allocated when such a layer is first seen), and rank up to this
-// many members of the k-th key's coarse bin:
-constexpr uint32_t kCapDiv2 = 4;
-// the members of the k-th key's coarse bin go to a pool in which every such layer owns max(4096, n / 64) entries.
+// Dense layers (high densities) list every candidate in lists of their own, long enough for twice the number the
+// hint aims at (allocated when a plan with such a layer is first used); the members of the k-th key's coarse bin
+// go to a pool in which every such layer owns max(4096, n / 64) entries.
 
 // -DRGC_CHUNK=<elements> (a multiple of 256, >= 1024) at build time fixes the wave-chunk size for tuning
 // experiments; not defined = automatic.  (There are no run-time switches: nothing here reads the environment.)
@@ -133,7 +131,9 @@ struct CompressPlan {
   uint32_t num_chunks = 0;                 // wave-chunks over all layers
   uint64_t write_bytes = 0;                // what the streaming pass writes (V, and u where there is one)
   uint32_t max_k = 0;                      // the largest k of the list
-  bool any_two_pass = false;               // some layer takes the probe pass + second pass when it has a hint
+  bool any_dense = false;                  // some layer is streamed by collect_kernel when it has a hint
+  uint64_t list_entries = 0;               // list entries of the dense layers
+  uint64_t member_entries = 0;             // entries of the member pool they own
   uint64_t last_use = 0;
   bool valid = false;
 };
@@ -160,14 +160,15 @@ struct rgc_ctx {
   uint32_t wc_max = 0;
   uint32_t cus = 0;                        // compute units of the device (sizes the persistent decompression grids)
   DevBuf<LayerState> d_state;
-  DevBuf<uint32_t> d_hist, d_coarse, d_cand_cnt, d_wc_a, d_wc_b, d_wc_c, d_err, d_group;
+  DevBuf<uint32_t> d_hist, d_coarse, d_cand_cnt, d_wc_a, d_wc_b, d_err, d_group;
   DevBuf<unsigned long long> d_members;
   DevBuf<long long> d_norm_part;           // [workgroups] parts of the sum of squares / of |a| (ExactParts)
   DevBuf<long long> d_mean_part;           // [layers][kMeanPartsMax] parts of the sums of message values (ExactParts)
   DevBuf<ThresholdMoments> d_moments;      // [max_layers] threshold binary search: mean, max of each layer
   DevBuf<uint2> d_slots;
-  DevBuf<uint2> d_slots2;                  // the probe pass's lists of two-pass layers (first use)
-  DevBuf<unsigned long long> d_members2;   // member pool of the two-pass layers (first use)
+  DevBuf<uint2> d_slots2;                  // the lists of the dense layers (first use)
+  DevBuf<float> d_slots_u;                 // the velocity of every listed element (first use)
+  DevBuf<unsigned long long> d_members2;   // member pool of the dense layers (first use)
   DevBuf<uint32_t> d_shards;               // their sub-list counters (first use)
   CompressPlan plans[kPlanCache];
   uint64_t tick = 0;
@@ -207,7 +208,8 @@ int build_compress_plan(rgc_ctx* ctx, CompressPlan& P, const rgc_layer* layers, 
   const uint32_t kChunk = chunk_for(total_elems), kCap = kChunk / kCapDiv;
   P.chunk = kChunk;
   uint32_t wc = 0, wg = 0, grp = 0;
-  uint64_t mem = 0;                        // entries of the member pool handed out to two-pass layers
+  uint64_t mem = 0;                        // entries of the member pool handed out to dense layers
+  uint64_t lists = 0;                      // list entries handed out to them
   for (int32_t o = 0; o < L; ++o) {
     const int32_t l = order[o];
     const rgc_layer& in = layers[l];
@@ -246,24 +248,30 @@ int build_compress_plan(rgc_ctx* ctx, CompressPlan& P, const rgc_layer* layers, 
     d.margin = static_cast<uint32_t>(margin);
     uint64_t cmax = std::min<uint64_t>(2 * target, (kCap / 2) * (span / kChunk));
     d.target = static_cast<uint32_t>(std::min<uint64_t>(target, 0xFFFFFFFFu));
-    d.two_pass = 0;
+    d.dense = 0;
+    d.list_cap = 0;
+    d.list_first = 0;
+    d.pad_ = 0;
     if (!d.hintable && d.wc_count >= 2) {
-      // High densities (the warm-up period of Section 2.5): no list can hold every element from the
-      // threshold upwards, but the lists of the probe pass (kCapDiv2) can hold the keys around it.  The
-      // hint is aimed at rank k + margin and accepted up to rank k + 1.5 margin; the probe pass lists the
-      // keys from the hinted threshold up to as far above the last k-th key as the threshold lies below
-      // it: about two margins' worth of keys, which must fit half the list capacity.
-      const uint32_t kCap2 = kChunk / kCapDiv2;
+      // High densities (the warm-up period of Section 2.5): the short lists of the one-pass path cannot hold every
+      // element from the threshold upwards.  Such a layer gets lists of its own, long enough for twice the number of
+      // candidates aimed at, and its hint is aimed at rank k + margin and accepted from rank k to rank k + 2 margin.
+      // The margin is wide (on the benchmark's tensors at 25 % the count above the hinted threshold comes out within
+      // 3 % of k of the rank aimed at, 10 % now and then, and a miss costs more than a whole hint-free call): what it
+      // costs is list entries, a twenty-fourth of the layer at most (at 1.5625 % a margin of k / 2 missed on most calls).
       const uint64_t margin2 = std::max<uint64_t>(std::min<uint64_t>(2 * k, d.n / 24), 64);
-      const uint64_t band_per_chunk = (5 * margin2 / 2 * kChunk + span - 1) / span;
-      if (2 * band_per_chunk + 16 <= kCap2 && k + 2 * margin2 < d.n) {
-        d.two_pass = 1;
+      if (k + 2 * margin2 < d.n) {
+        const uint64_t aimed_per_chunk = ((k + margin2) * kChunk + span - 1) / span;
+        d.dense = 1;
+        d.list_cap = static_cast<uint32_t>(std::min<uint64_t>(kChunk, (2 * aimed_per_chunk + 64 + 63) / 64 * 64));
+        d.list_first = lists;
+        lists += static_cast<uint64_t>(d.wc_count) * d.list_cap;
         d.mem_cap = static_cast<uint32_t>(std::max<uint64_t>(4096, d.n / 64) / kMemberShards * kMemberShards);
         d.mem_first = mem;
         mem += d.mem_cap;
         d.margin = static_cast<uint32_t>(margin2);
         d.target = static_cast<uint32_t>(k + margin2);
-        cmax = k + margin2 + margin2 / 2;
+        cmax = k + 2 * margin2;
       }
     }
     d.cmax = static_cast<uint32_t>(std::min<uint64_t>(cmax, 0x7FFFFFFFu));
@@ -296,9 +304,11 @@ int build_compress_plan(rgc_ctx* ctx, CompressPlan& P, const rgc_layer* layers, 
   P.num_chunks = wc;
   P.write_bytes = 0;
   P.max_k = 0;
-  P.any_two_pass = false;
+  P.any_dense = false;
+  P.list_entries = lists;
+  P.member_entries = mem;
   for (int32_t l = 0; l < L; ++l) {
-    P.any_two_pass = P.any_two_pass || desc[l].two_pass != 0;
+    P.any_dense = P.any_dense || desc[l].dense != 0;
     P.write_bytes += static_cast<uint64_t>(layers[l].n) * (layers[l].momentum ? 8u : 4u);
     P.max_k = std::max(P.max_k, static_cast<uint32_t>(layers[l].k));
   }
@@ -386,7 +396,6 @@ int rgc_create(rgc_ctx** out, int device_id, int64_t max_total_elems, int32_t ma
   chk(c->d_cand_cnt.alloc(wc_max));
   chk(c->d_wc_a.alloc(wc_max));
   chk(c->d_wc_b.alloc(wc_max));
-  chk(c->d_wc_c.alloc(wc_max));
   {
     // every wave-chunk owns chunk / kCapDiv slots whatever the chunk size: total / kCapDiv slots
     // plus one (partly used) chunk per layer at the largest chunk size a plan may pick
@@ -429,9 +438,9 @@ int rgc_destroy(rgc_ctx* ctx) {
   ctx->d_cand_cnt.release();
   ctx->d_wc_a.release();
   ctx->d_wc_b.release();
-  ctx->d_wc_c.release();
   ctx->d_slots.release();
   ctx->d_slots2.release();
+  ctx->d_slots_u.release();
   ctx->d_members2.release();
   ctx->d_shards.release();
   ctx->d_err.release();
@@ -676,7 +685,6 @@ int rgc_compress_layers_scaled(rgc_ctx* ctx, const rgc_layer* layers, int32_t nu
   A.slots = ctx->d_slots.p;
   A.wc_a = ctx->d_wc_a.p;
   A.wc_b = ctx->d_wc_b.p;
-  A.wc_c = ctx->d_wc_c.p;
   A.errflag = ctx->d_err.p;
   A.group_done = ctx->d_group.p;
   A.chunk = plan->chunk;
@@ -684,50 +692,46 @@ int rgc_compress_layers_scaled(rgc_ctx* ctx, const rgc_layer* layers, int32_t nu
   A.use_hints = (sig_same && !no_hints) ? 1u : 0u;
   A.update_hints = no_hints ? 0u : 1u;
   A.mask_momentum = (flags & RGC_NO_MOMENTUM_MASK) ? 0u : 1u;
-  const bool two_pass = plan->any_two_pass && A.use_hints;
-  if (plan->any_two_pass && !ctx->d_slots2.p) {   // the first call that shows the context such a layer
-    const uint64_t largest = std::max<uint64_t>(16384, chunk_override());
-    hipError_t e = ctx->d_slots2.alloc(static_cast<uint64_t>(ctx->max_total) / kCapDiv2 +
-                                       (static_cast<uint64_t>(ctx->max_layers) + 1) * (largest / kCapDiv2));
-    if (e == hipSuccess) e = ctx->d_members2.alloc(static_cast<uint64_t>(ctx->max_total) / 64 + static_cast<uint64_t>(ctx->max_layers) * 4096);
-    if (e == hipSuccess) e = ctx->d_shards.alloc(static_cast<size_t>(ctx->max_layers) * kMemberShards * kShardStride);
+  const bool dense = plan->any_dense && A.use_hints;
+  if (plan->any_dense && (ctx->d_slots2.n < plan->list_entries || ctx->d_members2.n < plan->member_entries || !ctx->d_shards.p)) {
+    // the first call that shows the context a plan with such layers (or one that needs longer lists): hipFree
+    // waits for the kernels that may still use the old ones
+    hipError_t e = ctx->d_slots2.alloc(plan->list_entries);
+    if (e == hipSuccess) e = ctx->d_slots_u.alloc(plan->list_entries);
+    if (e == hipSuccess) e = ctx->d_members2.alloc(plan->member_entries);
+    if (e == hipSuccess && !ctx->d_shards.p) e = ctx->d_shards.alloc(static_cast<size_t>(ctx->max_layers) * kMemberShards * kShardStride);
     if (e != hipSuccess) {
       ctx->d_slots2.release();
+      ctx->d_slots_u.release();
       ctx->d_members2.release();
       ctx->d_shards.release();
       if (e == hipErrorOutOfMemory) { (void)hipGetLastError(); return RGC_ENOMEM; }
-      return fail_hip(e, "two-pass scratch allocation");
+      return fail_hip(e, "scratch allocation for dense layers");
     }
   }
   A.slots2 = ctx->d_slots2.p;
-  A.cap2 = A.chunk / kCapDiv2;
+  A.slots_u = ctx->d_slots_u.p;
   A.members2 = ctx->d_members2.p;
   A.shard_cnt = ctx->d_shards.p;
-  // (a call with two-pass layers ends where it began: its second pass runs against its first)
-  A.reverse = two_pass ? 0u : streaming_direction(plan, ctx->compress_calls);
+  A.reverse = streaming_direction(plan, ctx->compress_calls);
   ++ctx->compress_calls;
   ctx->compressed_since_decompress = true;
   A.nesterov = (flags & RGC_NESTEROV) ? 1u : 0u;
   A.grad_scale = grad_scale;
   A.m = momentum;
   A.launch = 1;
-  // Layers of the two-pass kind that have a hint are probed by a kernel of their own (read-only) and
-  // skipped by the streaming kernel; if their probe misses they are streamed in a second launch of the
-  // streaming kernel, and if it does not they are ranked by a kernel of their own at launch 2 and end in the emit
-  // kernel at launch 3.
+  // Dense layers that have a hint are streamed by a kernel of their own and skipped by accumulate_kernel (both
+  // decide from the same state, which neither changes before its layer is done).  They are ranked at launch 2 and
+  // written at launch 3 by lists_kernel; one whose hint misses has its residual put right at launch 2 or 3 and
+  // then takes the five passes, so such a call has up to eight launches.
   if (ctx->profiling) RGC_HIP(take_event(ctx, stream, ctx->ev_compress));
   RGC_HIP(launch_accumulate(A, plan->num_wgs, stream));
-  // (after the streaming kernel: both decide from the same state which of them has a layer, and only the
-  // probe kernel changes that state, when it misses)
-  if (two_pass) RGC_HIP(launch_probe(A, plan->num_wgs, stream));
+  if (dense) RGC_HIP(launch_collect(A, plan->num_wgs, stream));
   if (ctx->profiling) RGC_HIP(take_event(ctx, stream, ctx->ev_compress));
-  // (a two-pass layer can fall back as late as launch 3 and then needs four more launches)
-  for (int launch = 2; launch <= kLaunches + (two_pass ? 1 : 0); ++launch) {
+  for (int launch = 2; launch <= kLaunches + (dense ? 2 : 0); ++launch) {
     A.launch = static_cast<uint32_t>(launch);
-    if (two_pass && launch <= 3) RGC_HIP(launch_accumulate(A, plan->num_wgs, stream));
-    RGC_HIP(launch_phase(A, plan->num_wgs, stream));
-    if (two_pass && launch == 2) RGC_HIP(launch_rank(A, plan->num_wgs, stream));
-    if (two_pass && launch == 3) RGC_HIP(launch_emit(A, plan->num_wgs, stream));
+    RGC_HIP(launch_phase(A, plan->num_wgs, dense, stream));
+    if (dense && launch <= 3) RGC_HIP(launch_lists(A, plan->num_wgs, stream));
   }
   if (ctx->profiling) RGC_HIP(take_event(ctx, stream, ctx->ev_compress));
   if (!no_hints) {

@@ -27,11 +27,8 @@
 
 #include "../../include/rgc.h"
 
-#ifndef RGC_PROBE_GROUP
-#define RGC_PROBE_GROUP 1
-#endif
 #ifndef RGC_RECOMPUTE_UNROLL
-#define RGC_RECOMPUTE_UNROLL 4
+#define RGC_RECOMPUTE_UNROLL 2
 #endif
 
 namespace rgc {
@@ -48,7 +45,7 @@ struct Collector {
   uint32_t tau;
   uint32_t shift;
   uint32_t sign_xor, sign_filter;   // see key_of()
-  uint32_t clip;     // probe pass of a two-pass layer: candidates of the coarse bins from this one upwards are counted, not listed
+  uint32_t clip;     // dense layers: candidates of the coarse bins from this one upwards are masked by the streaming pass itself
 };
 
 // The selection key of an element with bit pattern `bits`.  Plain top-k (Section 2.1): its
@@ -86,6 +83,29 @@ __device__ __forceinline__ uint32_t coarse_bin(uint32_t key, uint32_t tau, uint3
   const uint32_t b = (key - tau) >> shift;
   return b < static_cast<uint32_t>(kCoarseBins - 1) ? b : static_cast<uint32_t>(kCoarseBins - 1);
 }
+
+// Dense layers: the clip bin as the kernels use it (whatever the state holds).
+__device__ __forceinline__ uint32_t dense_clip(uint32_t clip) {
+  return clip < static_cast<uint32_t>(kCoarseBins - 1) ? clip : static_cast<uint32_t>(kCoarseBins - 1);
+}
+// Dense layers: the smallest key whose coarse bin is the clip bin or a higher one (clip <= kCoarseBins - 1, where
+// coarse_bin() does not saturate yet); 2^31, which no key reaches, if there is none.
+__device__ __forceinline__ uint32_t dense_clip_key(uint32_t tau, uint32_t shift, uint32_t clip) {
+  const unsigned long long k = static_cast<unsigned long long>(tau) + (static_cast<unsigned long long>(clip) << shift);
+  return k < 0x80000000ull ? static_cast<uint32_t>(k) : 0x80000000u;
+}
+// Dense layers: the key from which the streaming pass masks at once, as the kernels use it (whatever the state
+// holds, only candidates are masked: they are the ones the lists can put back).
+__device__ __forceinline__ uint32_t dense_mask_key(uint32_t mask_key, uint32_t tau) { return mask_key > tau ? mask_key : tau; }
+// ... and where the next call's k-th key is expected: as far above the new threshold as this call's k-th key T lies
+// above the (undrifted) threshold tn of the same rank.
+__device__ __forceinline__ uint32_t mask_key_for(uint32_t T, uint32_t tn, uint32_t tau_new) {
+  const unsigned long long k = static_cast<unsigned long long>(tau_new) + (T >= tn ? T - tn : 0u);
+  return k < 0x80000000ull ? static_cast<uint32_t>(k) : 0x80000000u;
+}
+// Dense layers: a wave-chunk whose list could not be sure to hold another group stores this bit with the number of
+// entries it had listed by then (as a count that is beyond every capacity, so the layer's hint counts as missed).
+constexpr uint32_t kListStopped = 0x80000000u;
 
 // Consume the four accumulated values a lane holds (elements idx0 .. idx0+3, the first
 // `nvalid` of which exist).  Element order inside the wave is lane-major.
@@ -265,11 +285,13 @@ __device__ __forceinline__ uint32_t shift_for(uint32_t T, uint32_t tau) {
   return bl > kKeep ? bl - kKeep : 0u;
 }
 
-// Two-pass layers: the probe pass of the next call lists the keys from the hinted threshold tau up to as far above
-// the k-th key T of this call as tau lies below it (in coarse bins of the next call's shift).
+// Dense layers: the ranking step of the next call looks at the keys from the hinted threshold tau up to twice as far
+// above the k-th key T of this call as tau lies below it (in coarse bins of the next call's shift, as far as the
+// bins reach); what lies above that is sure to be selected.  (A k-th key that rises costs a miss, one that falls
+// only list entries, and the band costs an LDS atomic per candidate in it: hence the lopsided band.)
 __device__ __forceinline__ uint32_t clip_for(uint32_t T, uint32_t tau, uint32_t shift) {
   const uint32_t d = T >= tau ? T - tau : 0u;
-  const uint32_t b = 2u * (d >> shift) + 2u;
+  const uint32_t b = 3u * (d >> shift) + 2u;
   return b < static_cast<uint32_t>(kCoarseBins - 1) ? b : static_cast<uint32_t>(kCoarseBins - 1);
 }
 
@@ -431,7 +453,7 @@ __device__ void resolve_digit(const CompressArgs& A, uint32_t l, const LayerDesc
       st->T = T;
       st->r = new_rem;
       st->next_phase = PH_COUNT;
-      if (A.update_hints && L.two_pass && st->probe_skip != 0u) st->probe_skip -= 1u;   // one more call without a probe pass
+      if (A.update_hints && L.dense && st->dense_skip != 0u) st->dense_skip -= 1u;   // one more call without its hint
       if (A.update_hints) {
         // The hints live in the key space of the one-pass path (key_of).  With the ordered key a hint
         // exists only if the k-th key and the threshold aimed at both lie among the elements key_of()
@@ -447,6 +469,7 @@ __device__ void resolve_digit(const CompressArgs& A, uint32_t l, const LayerDesc
           st->tau = drifted_tau(tn, Th, st->T_prev, A.use_hints && st->has_prev);
           st->shift = shift_for(Th, tn);
           st->clip = clip_for(Th, tn, st->shift);
+          st->mask_key = mask_key_for(Th, tn, st->tau);
           st->hint_valid = 1u;
           st->T_prev = Th;
           st->has_prev = 1u;
@@ -462,31 +485,38 @@ __device__ void resolve_digit(const CompressArgs& A, uint32_t l, const LayerDesc
   }
 }
 
+// A dense layer's hint missed: a pass over the lists and five more passes for nothing, so the layer goes without its
+// hint for a while, twice as long after every further miss.
+__device__ __forceinline__ void dense_missed(LayerState* st) {
+  const uint32_t wait = st->dense_backoff ? 2u * st->dense_backoff : 1u;
+  st->dense_backoff = wait < kDenseBackoffMax ? wait : kDenseBackoffMax;
+  st->dense_skip = st->dense_backoff + 1u;       // (the count-down at the end of this call's own fall-back included)
+}
+
 // Hinted path, end of the streaming pass: validate the candidate lists, locate the coarse bin
 // holding the k-th key, clear the coarse histogram, schedule PH_SEL or fall back.
 // `lds` holds >= kCoarseBins words and is free for use.
 // `after_first_digit`: the lists come from PH_COLLECT of a hint-free call rather than from the streaming pass
 // of a hinted one; should they not do, the call goes on with the second digit.
-// `probe`: the lists come from the read-only probe pass of a two-pass layer; they hold only the candidates
-// of the coarse bins below the layer's clip bin (the others were counted per wave-chunk in wc_c), the k-th key must lie
-// among those, and should they not do the layer is streamed after all (PH_STREAM).
+// `dense`: the lists are those of a dense layer's streaming pass (collect_kernel), which has already masked the
+// candidates of the coarse bins from the layer's clip bin upwards: the k-th key must lie below that bin, and
+// should it not, or should anything else be off, those entries are put back first (PH_RESTORE).
 __device__ void resolve_collect(const CompressArgs& A, uint32_t l, const LayerDesc& L, LayerState* st,
                                 ResolveShared& sh, uint32_t* lds, bool after_first_digit, uint32_t cur_launch,
-                                bool probe = false) {
+                                bool dense = false) {
   const uint32_t t = threadIdx.x;
   uint32_t total = 0, bad = 0;
   for (uint32_t c0 = 0; c0 < L.wc_count; c0 += 8u * kBlockThreads) {
-    uint32_t v[8], w[8];
+    uint32_t v[8];
 #pragma unroll
     for (uint32_t j = 0; j < 8u; ++j) {
       const uint32_t c = c0 + j * kBlockThreads + t;
       v[j] = c < L.wc_count ? ld_agent(&A.cand_cnt[L.wc_first + c]) : 0u;
-      w[j] = (probe && c < L.wc_count) ? ld_agent(&A.wc_c[L.wc_first + c]) : 0u;
     }
 #pragma unroll
     for (uint32_t j = 0; j < 8u; ++j) {
-      bad |= (v[j] > (probe ? A.cap2 : A.cap)) ? 1u : 0u;
-      total += v[j] + w[j];
+      bad |= (v[j] > (dense ? L.list_cap : A.cap)) ? 1u : 0u;
+      total += v[j];
     }
   }
   uint32_t cand_total;
@@ -498,20 +528,25 @@ __device__ void resolve_collect(const CompressArgs& A, uint32_t l, const LayerDe
   // PH_SEL adds the selected counts of every kOffsetGroup wave-chunks up in wc_b: start from zero
   for (uint32_t g = t; g < (L.wc_count + kOffsetGroup - 1u) / kOffsetGroup; g += kBlockThreads)
     st_agent(&A.wc_b[L.wc_first + g], 0u);
-  if (probe && t < kMemberShards) st_agent(&A.shard_cnt[(static_cast<size_t>(l) * kMemberShards + t) * kShardStride], 0u);
+  if (dense && t < kMemberShards) st_agent(&A.shard_cnt[(static_cast<size_t>(l) * kMemberShards + t) * kShardStride], 0u);
   if (t == 0) {
-    if (probe) st->shard_overflow = 0u;
+    if (dense) {
+      st->shard_overflow = 0u;
+      st->cur_tau = st->tau;
+      st->cur_shift = st->shift;
+      st->cur_mask_key = dense_mask_key(st->mask_key, st->tau);
+    }
     st->stat_candidates = cand_total;
     st->stat_members = sh.cnt;
     const bool ok = !bad && cand_total >= k && hist_total == cand_total && sh.bin != 0xFFFFFFFFu &&
-                    sh.cnt <= (probe ? L.mem_cap / 4u : static_cast<uint32_t>(kMemberMax)) && (!probe || sh.bin < st->clip);
+                    sh.cnt <= (dense ? L.mem_cap / 4u : static_cast<uint32_t>(kMemberMax)) && (!dense || sh.bin < dense_clip(st->clip));
     if (ok) {
       const uint32_t tau = st->tau, shift = st->shift;
       st->bstar = sh.bin;
       st->k_rem = k - sh.above;
       st->nmembers = 0u;
       if (!after_first_digit) st->path = 0u;
-      st->next_phase = probe ? PH_SEL2 : PH_SEL;
+      st->next_phase = dense ? PH_SEL2 : PH_SEL;
       unsigned long long tn;
       if (sh.hbin != 0xFFFFFFFFu) {
         tn = static_cast<unsigned long long>(tau) + (static_cast<unsigned long long>(sh.hbin) << shift);
@@ -529,14 +564,11 @@ __device__ void resolve_collect(const CompressArgs& A, uint32_t l, const LayerDe
       st->tau_next = static_cast<uint32_t>(tn);
     } else if (after_first_digit) {
       st->next_phase = PH_HIST2;          // prefix and k_rem are still those of the first digit
-    } else if (probe) {
+    } else if (dense) {
       st->path = 2u;
       st->stat_misses += 1u;
-      st->next_phase = PH_STREAM;         // nothing has been written yet: the ordinary streaming pass, hint-free
-      // a wasted read-only pass: go without one for a while, twice as long after every further miss
-      const uint32_t wait = st->probe_backoff ? 2u * st->probe_backoff : 1u;
-      st->probe_backoff = wait < kProbeBackoffMax ? wait : kProbeBackoffMax;
-      st->probe_skip = st->probe_backoff + 1u;   // (the count-down of this call's own hint-free pass included)
+      st->next_phase = PH_RESTORE;        // then the multi-pass path on the restored residual
+      dense_missed(st);
     } else {
       st->path = 2u;
       st->stat_misses += 1u;
@@ -687,12 +719,8 @@ __global__ void __launch_bounds__(kBlockThreads) accumulate_kernel(CompressArgs 
   LayerState* st = A.state + l;
   // (with a sign filter a threshold of 0 would let the elements that key_of() ranks last and equal into the lists)
   const bool hinted = A.use_hints && (st->hint_valid != 0u) && !(A.sign_filter != 0u && st->tau == 0u);
-  if (A.launch == 1u) {
-    if (L.two_pass && hinted && st->probe_skip == 0u) return;   // the probe kernel has this layer
-  } else if (st->next_launch != A.launch || st->next_phase != PH_STREAM) {
-    return;                                 // second launch: only the layers whose probe missed
-  }
-  const bool collect = hinted && L.hintable && A.launch == 1u;
+  if (L.dense && hinted && st->dense_skip == 0u) return;     // collect_kernel has this layer
+  const bool collect = hinted && L.hintable;
   // the same LDS array serves as 4096-bin digit histogram (hint-free) or 1024-bin coarse one
   const uint32_t lds_bins = collect ? static_cast<uint32_t>(kCoarseBins) : static_cast<uint32_t>(kHistBins);
   for (uint32_t b = threadIdx.x; b < lds_bins; b += kBlockThreads) lds_hist[b] = 0u;
@@ -739,8 +767,8 @@ __global__ void __launch_bounds__(kBlockThreads) accumulate_kernel(CompressArgs 
     if (collect) {
       resolve_collect(A, l, L, st, sh, lds_hist, false, 1u);
     } else {
-      if (threadIdx.x == 0 && A.launch == 1u) { st->path = 1u; st->stat_candidates = 0u; st->stat_members = 0u; }
-      resolve_digit<1>(A, l, L, st, sh, lds_hist, A.launch);
+      if (threadIdx.x == 0) { st->path = 1u; st->stat_candidates = 0u; st->stat_members = 0u; }
+      resolve_digit<1>(A, l, L, st, sh, lds_hist, 1u);
     }
   }
 }
@@ -1171,103 +1199,133 @@ __global__ void __launch_bounds__(kBlockThreads) phase_late_kernel(CompressArgs 
   }
 }
 
-// =================================================================== two-pass layers (high densities)
+// =================================================================== dense layers (high densities)
 // At the densities of a warm-up period (Section 2.5: 25 %, 6.25 %, 1.5625 % before 0.1 %) the candidate
-// lists cannot hold every element from the hinted threshold upwards, and masking the sent entries out of the
-// residual one by one would dirty most cache lines of V and u.  Such a layer, once it has a hint, takes two
-// streaming passes and no pass in between:
-//  1. probe_kernel reads G, V (, u), computes the accumulated values and writes NOTHING back: candidates
-//     (key >= tau) are counted in the coarse histogram as on the one-pass path, but only those of the coarse
-//     bins below the layer's clip bin (see clip_for) go to the lists; the others are counted per wave-chunk (wc_c).  If the k-th key
-//     turns out to lie among the listed ones, PH_SEL ranks them exactly as for a one-pass layer;
-//  2. emit_kernel reads G, V (, u) again, computes the same values, and with the k-th entry known writes the
-//     masked residual, the masked velocity and the message in one go (32 instead of 52 bytes per element
-//     moved at 25 %, and every write is a streaming one).
-// A probe that misses (too few candidates, the k-th key above the listed band, a list overflow) costs the
-// read-only pass: the layer is then streamed by a second launch of accumulate_kernel and goes on hint-free.
+// lists of the one-pass path cannot hold every element from the hinted threshold upwards, and masking the
+// sent entries out of the residual one by one afterwards would dirty most cache lines of V and u a second
+// time.  Such a layer ("dense"), once it has a hint, is streamed by a kernel of its own:
+//  1. collect_kernel reads G, V (, u), computes the accumulated values and lists EVERY candidate
+//     (key >= tau) in the wave-chunk's list, in index order (lists of the layer's own, long enough for twice
+//     the expected number).  The hint also says where the k-th key is expected (mask_key): the pass writes +0
+//     into V (and u) in place of every candidate from there upwards, taking it as sent, and keeps its velocity
+//     in a second array.  The candidates up to a clip bin well above the expected k-th key ("the band") enter
+//     the coarse histogram one by one; those above it are sure to be selected, are counted per lane and added
+//     to the top bin once.
+//  2. lists_kernel, launch 2 (PH_SEL2): every wave walks its list; the members of the k-th key's coarse bin
+//     are ranked exactly by the layer's last workgroup, as on the one-pass path.
+//  3. lists_kernel, launch 3 (PH_EMIT): the message straight from the ordered lists.  What step 1 guessed
+//     wrong is put right here: a sent entry below mask_key is masked now, a masked entry that is not sent gets
+//     its value and velocity back (as many isolated writes as the k-th key lies ranks away from where it was
+//     expected, whatever the width of the band).
+// If the hint misses (too few candidates, the k-th key at or above the clip bin, a list or a member sub-list
+// that ran over), what step 1 masked is put back from the lists (PH_RESTORE: V and u are then exactly the
+// accumulated values, as after an ordinary streaming pass) and the layer goes on with the multi-pass path.
+// A wave-chunk whose list may not hold the next group stops listing AND masking there, so the lists always
+// hold what was masked.
 namespace {
 
-// The probe pass's share of consume(): the four accumulated values of a lane.
-__device__ __forceinline__ void consume_probe(const float (&a)[4], uint32_t nvalid, uint32_t idx0, Collector& c,
-                                              uint32_t& certain) {
-  uint32_t bits[4], bin[4];
-  bool cand[4], listed[4];
+// What the streaming pass of a dense layer keeps per wave-chunk beside the Collector.
+struct DenseChunk {
+  gptr<float> slot_u;   // the velocity of the listed elements that are masked at once (null: the velocity is not masked)
+  uint32_t mask_key;    // candidates with keys from here upwards are masked at once (where the k-th key is expected)
+  uint32_t clip_key;    // candidates with keys from here upwards lie in the coarse bins from the clip bin upwards: sure to be selected
+  uint32_t certain;     // how many candidates from clip_key upwards this lane has seen (they enter the histogram's top bin in one
+                        // addition per wave-chunk: one by one they would all queue up on that word)
+  bool overflow;        // the list may not hold the next group: from here on the pass neither lists nor masks
+};
+
+// The four accumulated values a lane holds (elements idx0 .. idx0+3, the first `nvalid` exist): which of them the
+// pass masks at once.  Known before any rank is, so the stores of V (and u) go out first, as in stream_chunk.
+__device__ __forceinline__ void masked_dense(const float (&a)[4], uint32_t nvalid, const Collector& c, const DenseChunk& dc,
+                                             uint32_t (&key)[4], bool (&masked)[4]) {
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    bits[j] = fbits(a[j]);
-    const uint32_t key = key_of(bits[j], c.sign_xor, c.sign_filter);
-    cand[j] = (static_cast<uint32_t>(j) < nvalid) && (key >= c.tau);
-    bin[j] = coarse_bin(key, c.tau, c.shift);
-    listed[j] = cand[j] && bin[j] < c.clip;
+    key[j] = key_of(fbits(a[j]), c.sign_xor, c.sign_filter);
+    masked[j] = !dc.overflow && (static_cast<uint32_t>(j) < nvalid) && key[j] >= dc.mask_key;
   }
-  const unsigned long long any = __ballot(cand[0] | cand[1] | cand[2] | cand[3]);
-  if (any == 0ull) return;
-  // (the candidates above the band are added to the histogram's top bin once per wave, not one by one:
-  // they would all queue up on that one word)
+}
+
+// Appends the group's candidates to the wave-chunk's list in index order (the caller has seen that 256 more
+// entries fit).  The candidates of the band (keys below clip_key) enter the coarse histogram one by one.
+__device__ __forceinline__ void list_dense(const float (&a)[4], const float (&u)[4], const uint32_t (&key)[4],
+                                           const bool (&masked)[4], uint32_t nvalid, uint32_t idx0, Collector& c,
+                                           DenseChunk& dc) {
+  bool cand[4];
 #pragma unroll
-  for (int j = 0; j < 4; ++j)
-    if (listed[j]) atomicAdd(&c.coarse[bin[j]], 1u);
-  const unsigned long long c0 = __ballot(cand[0] && !listed[0]), c1 = __ballot(cand[1] && !listed[1]),
-                           c2 = __ballot(cand[2] && !listed[2]), c3 = __ballot(cand[3] && !listed[3]);
-  certain += popc64(c0) + popc64(c1) + popc64(c2) + popc64(c3);
-  const unsigned long long m0 = __ballot(listed[0]), m1 = __ballot(listed[1]), m2 = __ballot(listed[2]),
-                           m3 = __ballot(listed[3]);
+  for (int j = 0; j < 4; ++j) cand[j] = (static_cast<uint32_t>(j) < nvalid) && (key[j] >= c.tau);
+  const unsigned long long m0 = __ballot(cand[0]), m1 = __ballot(cand[1]), m2 = __ballot(cand[2]), m3 = __ballot(cand[3]);
   if ((m0 | m1 | m2 | m3) == 0ull) return;
   uint32_t pos = c.count + rank_below(m0) + rank_below(m1) + rank_below(m2) + rank_below(m3);
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    if (listed[j]) {
-      if (pos < c.cap) c.slot[pos] = vu2{bits[j], idx0 + j};
+    if (cand[j]) {
+      c.slot[pos] = vu2{fbits(a[j]), idx0 + j};
+      if (masked[j] && dc.slot_u != nullptr) dc.slot_u[pos] = u[j];
+      if (key[j] >= dc.clip_key) ++dc.certain;
+      else atomicAdd(&c.coarse[coarse_bin(key[j], c.tau, c.shift)], 1u);
       ++pos;
     }
   }
   c.count += popc64(m0) + popc64(m1) + popc64(m2) + popc64(m3);
 }
 
-// One wave-chunk of a two-pass layer, both passes: f(a[4], u[4], nvalid, idx0, vector group?) sees the accumulated
-// values (and the updated velocity) of four consecutive elements per lane, computed exactly as the
-// streaming pass computes them, in the same element order.
-template <bool kMom, bool kNest, typename F>
-__device__ __forceinline__ void recompute_chunk(const LayerDesc& L, uint32_t begin, uint32_t end, const AccumRule m, F&& f) {
+// Streaming pass over one wave-chunk [begin, end) of a dense layer that has a hint: stream_chunk's loop, with the
+// candidates far above the hinted threshold masked on the way.
+template <bool kMom, bool kNest>
+__device__ __forceinline__ void stream_chunk_dense(const LayerDesc& L, uint32_t begin, uint32_t end, const AccumRule m,
+                                                   bool clear_mom, Collector& c, DenseChunk& dc) {
   const uint32_t lane = lane_id();
   uint32_t base = begin;
   if (L.vec_ok) {
     const uint32_t nfull = (end - begin) / kGroupElems;
     const gptr<const vf4> G4 = as_global(reinterpret_cast<const vf4*>(L.grad + begin));
-    const gptr<const vf4> V4 = as_global(reinterpret_cast<const vf4*>(L.resid + begin));
-    const gptr<const vf4> U4 = as_global(kMom ? reinterpret_cast<const vf4*>(L.mom + begin) : nullptr);
-    constexpr uint32_t kUnroll = kMom ? RGC_RECOMPUTE_UNROLL : 4u;
+    const gptr<vf4> V4 = as_global(reinterpret_cast<vf4*>(L.resid + begin));
+    const gptr<vf4> U4 = as_global(kMom ? reinterpret_cast<vf4*>(L.mom + begin) : nullptr);
+    constexpr uint32_t kUnroll = kMom ? 2u : 4u;
+    auto group = [&](const vf4& gq, const vf4& vq, const vf4& uq, uint32_t o) __attribute__((always_inline)) {
+      const float gg[4] = {gq.x, gq.y, gq.z, gq.w};
+      const float vvv[4] = {vq.x, vq.y, vq.z, vq.w};
+      float uu[4] = {0.f, 0.f, 0.f, 0.f};
+      if constexpr (kMom) { uu[0] = uq.x; uu[1] = uq.y; uu[2] = uq.z; uu[3] = uq.w; }
+      float a[4];
+      accum4<kMom, kNest>(gg, vvv, uu, m, a);
+      dc.overflow = dc.overflow || (c.count + 4u * kWaveSize > c.cap);
+      uint32_t key[4];
+      bool masked[4];
+      masked_dense(a, 4u, c, dc, key, masked);
+      V4[o] = vf4{masked[0] ? 0.0f : a[0], masked[1] ? 0.0f : a[1], masked[2] ? 0.0f : a[2], masked[3] ? 0.0f : a[3]};
+      if constexpr (kMom)
+        U4[o] = vf4{(masked[0] && clear_mom) ? 0.0f : uu[0], (masked[1] && clear_mom) ? 0.0f : uu[1],
+                    (masked[2] && clear_mom) ? 0.0f : uu[2], (masked[3] && clear_mom) ? 0.0f : uu[3]};
+      if (!dc.overflow) list_dense(a, uu, key, masked, 4u, begin + o * 4u, c, dc);
+    };
     uint32_t g = 0;
-    for (; g < nfull; g += kUnroll) {
+    for (; g + kUnroll <= nfull; g += kUnroll) {
       vf4 gv[kUnroll], vv[kUnroll], uv[kUnroll];
 #pragma unroll
       for (uint32_t t = 0; t < kUnroll; ++t) {
-        if (g + t < nfull) {
-          const uint32_t o = (g + t) * kWaveSize + lane;
-          gv[t] = __builtin_nontemporal_load(&G4[o]);
-          vv[t] = V4[o];
-          if constexpr (kMom) uv[t] = U4[o];
-        }
+        const uint32_t o = (g + t) * kWaveSize + lane;
+        gv[t] = __builtin_nontemporal_load(&G4[o]);
+        vv[t] = V4[o];
+        if constexpr (kMom) uv[t] = U4[o];
       }
 #pragma unroll
-      for (uint32_t t = 0; t < kUnroll; ++t) {
-        if (g + t < nfull) {
-          const uint32_t o = (g + t) * kWaveSize + lane;
-          const float gg[4] = {gv[t].x, gv[t].y, gv[t].z, gv[t].w};
-          const float vvv[4] = {vv[t].x, vv[t].y, vv[t].z, vv[t].w};
-          float uu[4] = {0.f, 0.f, 0.f, 0.f};
-          if constexpr (kMom) { uu[0] = uv[t].x; uu[1] = uv[t].y; uu[2] = uv[t].z; uu[3] = uv[t].w; }
-          float a[4];
-          accum4<kMom, kNest>(gg, vvv, uu, m, a);
-          f(a, uu, 4u, begin + o * 4u, true);
-        }
-      }
+      for (uint32_t t = 0; t < kUnroll; ++t) group(gv[t], vv[t], uv[t], (g + t) * kWaveSize + lane);
+    }
+    for (; g < nfull; ++g) {
+      const uint32_t o = g * kWaveSize + lane;
+      const vf4 gq = __builtin_nontemporal_load(&G4[o]);
+      const vf4 vq = V4[o];
+      vf4 uq = vf4{0.f, 0.f, 0.f, 0.f};
+      if constexpr (kMom) uq = U4[o];
+      group(gq, vq, uq, o);
     }
     base = begin + nfull * kGroupElems;
   }
+  // scalar groups: the ragged tail of an aligned layer, or every group of an unaligned one
   const gptr<const float> Gs = as_global(L.grad);
-  const gptr<const float> Vs = as_global(L.resid);
-  const gptr<const float> Us = as_global(L.mom);
+  const gptr<float> Vs = as_global(L.resid);
+  const gptr<float> Us = as_global(L.mom);
   for (; base < end; base += kGroupElems) {
     const uint32_t idx0 = base + lane * 4u;
     const uint32_t nvalid = idx0 < end ? ((end - idx0) < 4u ? (end - idx0) : 4u) : 0u;
@@ -1282,78 +1340,83 @@ __device__ __forceinline__ void recompute_chunk(const LayerDesc& L, uint32_t beg
     }
     float a[4];
     accum4<kMom, kNest>(gg, vvv, uu, m, a);
-    f(a, uu, nvalid, idx0, false);
+    dc.overflow = dc.overflow || (c.count + 4u * kWaveSize > c.cap);
+    uint32_t key[4];
+    bool masked[4];
+    masked_dense(a, nvalid, c, dc, key, masked);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (static_cast<uint32_t>(j) < nvalid) {
+        Vs[idx0 + j] = masked[j] ? 0.0f : a[j];
+        if constexpr (kMom) Us[idx0 + j] = (masked[j] && clear_mom) ? 0.0f : uu[j];
+      }
+    }
+    if (!dc.overflow) list_dense(a, uu, key, masked, nvalid, idx0, c, dc);
   }
-}
-
-template <typename F>
-__device__ __forceinline__ void recompute_chunk_any(const CompressArgs& A, const LayerDesc& L, uint32_t begin, uint32_t end, F&& f) {
-  AccumRule rule;
-  rule.m = A.m;
-  rule.scale = A.grad_scale ? *as_global(A.grad_scale) : 1.0f;
-  if (L.mom == nullptr) recompute_chunk<false, false>(L, begin, end, rule, f);
-  else if (!A.nesterov) recompute_chunk<true, false>(L, begin, end, rule, f);
-  else recompute_chunk<true, true>(L, begin, end, rule, f);
 }
 
 }  // namespace
 
-constexpr uint32_t kProbeGroup = RGC_PROBE_GROUP;
-
-__global__ void __launch_bounds__(kBlockThreads) probe_kernel(CompressArgs A) {
+// Launch 1 for the dense layers that have a hint (accumulate_kernel leaves exactly these out).
+__global__ void __launch_bounds__(kBlockThreads) collect_kernel(CompressArgs A) {
   __shared__ uint32_t lds_hist[kCoarseBins];
   __shared__ ResolveShared sh;
   const uint32_t wg = A.reverse ? gridDim.x - 1u - blockIdx.x : blockIdx.x;
   const uint32_t l = A.wg2layer[wg];
   const LayerDesc L = A.layers[l];
-  if (!L.two_pass) return;
+  if (!L.dense) return;
   LayerState* st = A.state + l;
-  // the same condition as in accumulate_kernel, which skips exactly the layers taken here
+  // the same condition as in accumulate_kernel
   const bool hinted = A.use_hints && (st->hint_valid != 0u) && !(A.sign_filter != 0u && st->tau == 0u);
-  if (!hinted || st->probe_skip != 0u) return;
-  // One workgroup in kProbeGroup does the work of kProbeGroup workgroups (their wave-chunks one after the other, one
-  // histogram for all): a workgroup's epilogue -- up to a thousand device atomics that flush the histogram, then the
-  // election, which waits for them -- is paid a quarter as often, and the bins of 16 wave-chunks overlap.
-  const uint32_t wgl = wg - L.wg_first;
-  if (wgl % kProbeGroup != 0u) return;
+  if (!hinted || st->dense_skip != 0u) return;
   for (uint32_t b = threadIdx.x; b < static_cast<uint32_t>(kCoarseBins); b += kBlockThreads) lds_hist[b] = 0u;
   __syncthreads();
-  const uint32_t tau = st->tau, shift = st->shift, clip = st->clip;
-  for (uint32_t i = 0; i < kProbeGroup; ++i) {
-    const uint32_t wc_local = (wgl + i) * kWavesPerBlock + (threadIdx.x >> 6);
-    if (wc_local >= L.wc_count) break;
+  const uint32_t wc_local = (wg - L.wg_first) * kWavesPerBlock + (threadIdx.x >> 6);
+  if (wc_local < L.wc_count) {
     const uint32_t begin = wc_local * A.chunk;
     const uint32_t end = (L.n - begin) < A.chunk ? L.n : begin + A.chunk;
+    const size_t list = L.list_first + static_cast<size_t>(wc_local) * L.list_cap;
+    const bool mom = L.mom != nullptr;
+    const bool clear_mom = mom && A.mask_momentum;
     Collector c;
-    c.slot = as_global(reinterpret_cast<vu2*>(A.slots2 + static_cast<size_t>(L.wc_first + wc_local) * A.cap2));
+    c.slot = as_global(reinterpret_cast<vu2*>(A.slots2 + list));
     c.coarse = lds_hist;
-    c.cap = A.cap2;
+    c.cap = L.list_cap;
     c.count = 0;
-    c.tau = tau;
-    c.shift = shift;
+    c.tau = st->tau;
+    c.shift = st->shift;
     c.sign_xor = A.sign_xor;
     c.sign_filter = A.sign_filter;
-    c.clip = clip;
-    uint32_t certain = 0;
-    recompute_chunk_any(A, L, begin, end, [&](const float (&a)[4], const float (&)[4], uint32_t nvalid, uint32_t idx0, bool) {
-      consume_probe(a, nvalid, idx0, c, certain);
-    });
+    c.clip = dense_clip(st->clip);
+    DenseChunk dc;
+    // (the velocity is kept only where the masking clears it)
+    dc.slot_u = clear_mom ? as_global(A.slots_u + list) : gptr<float>(nullptr);
+    dc.clip_key = dense_clip_key(c.tau, c.shift, c.clip);
+    dc.mask_key = dense_mask_key(st->mask_key, c.tau);
+    dc.certain = 0u;
+    dc.overflow = false;
+    AccumRule rule;
+    rule.m = A.m;
+    rule.scale = A.grad_scale ? *as_global(A.grad_scale) : 1.0f;
+    if (!mom) stream_chunk_dense<false, false>(L, begin, end, rule, clear_mom, c, dc);
+    else if (!A.nesterov) stream_chunk_dense<true, false>(L, begin, end, rule, clear_mom, c, dc);
+    else stream_chunk_dense<true, true>(L, begin, end, rule, clear_mom, c, dc);
+    const uint32_t certain = wave_total(wave_incl_scan(dc.certain));
     if (lane_id() == 0) {
-      st_agent(&A.cand_cnt[L.wc_first + wc_local], c.count);
-      st_agent(&A.wc_c[L.wc_first + wc_local], certain);
+      // (a list that stopped early says so, and where: nothing was listed or masked after that entry)
+      st_agent(&A.cand_cnt[L.wc_first + wc_local], dc.overflow ? (kListStopped | c.count) : c.count);
       if (certain) atomicAdd(&lds_hist[kCoarseBins - 1], certain);
     }
   }
   __syncthreads();
-  flush_hist(lds_hist, A.coarse + (static_cast<size_t>(l) * kCoarseRep + ((wgl / kProbeGroup) & (kCoarseRep - 1))) * kCoarseBins, kCoarseBins);
-  if (last_block_of_layer(&st->done, A.group_done + L.grp_first, wgl / kProbeGroup,
-                          (L.wg_count + kProbeGroup - 1u) / kProbeGroup, &sh.flag))
+  flush_hist(lds_hist, A.coarse + (static_cast<size_t>(l) * kCoarseRep + (wg & (kCoarseRep - 1))) * kCoarseBins, kCoarseBins);
+  if (last_block_of_layer(&st->done, A.group_done + L.grp_first, wg - L.wg_first, L.wg_count, &sh.flag))
     resolve_collect(A, l, L, st, sh, lds_hist, false, 1u, true);
 }
 
 namespace {
 
-// The members of a two-pass layer: kMemberShards sub-lists in global memory (region + s * shard_cap, n[s] entries),
+// The members of a dense layer: kMemberShards sub-lists in global memory (region + s * shard_cap, n[s] entries),
 // which other workgroups filled with device-scope stores.  A thread asks for eight values at a time, so that
 // their round trips overlap.
 struct MemberLists {
@@ -1453,22 +1516,13 @@ __device__ unsigned long long select_kth_largest_global(const MemberLists& M, un
   return r;
 }
 
-}  // namespace
-
-// Launch 2 of a call with two-pass layers: PH_SEL for the layers whose probe pass found the k-th key in its
-// lists.  Every wave takes its own wave-chunk's list; the layer's last workgroup ranks the members of the k-th
-// key's coarse bin (in global memory: there may be more of them than one workgroup's LDS holds), credits the
-// selected ones to their wave-chunks, scans the group sums into offsets and schedules the emit pass.
-__global__ void __launch_bounds__(kBlockThreads) rank_kernel(CompressArgs A) {
-  __shared__ ResolveShared sh;
-  __shared__ __attribute__((aligned(16))) uint32_t sel_hist[3 * 256];
-  __shared__ uint32_t shard_first[kMemberShards + 1];
-  const uint32_t wg = blockIdx.x;
-  const uint32_t l = A.wg2layer[wg];
-  LayerState* st = A.state + l;
-  if (st->next_launch != A.launch || st->next_phase != PH_SEL2) return;
-  const LayerDesc L = A.layers[l];
-  const uint32_t tau = st->tau, shift = st->shift, bstar = st->bstar;
+// Launch 2 of a call with dense layers (PH_SEL2), for the layers whose streaming pass found the k-th key below
+// its clip bin.  Every wave takes its own wave-chunk's list; the layer's last workgroup ranks the members of the
+// k-th key's coarse bin (in global memory: there may be more of them than one workgroup's LDS holds), credits the
+// selected ones to their wave-chunks, scans the group sums into offsets and schedules the output step.
+__device__ void dense_rank(const CompressArgs& A, uint32_t l, const LayerDesc& L, LayerState* st, uint32_t wg,
+                           ResolveShared& sh, uint32_t* sel_hist, uint32_t* shard_first) {
+  const uint32_t tau = st->cur_tau, shift = st->cur_shift, bstar = st->bstar;
   unsigned long long* const region = A.members2 + L.mem_first;
   const uint32_t shard_cap = L.mem_cap / kMemberShards;
   const uint32_t lane = lane_id();
@@ -1477,20 +1531,27 @@ __global__ void __launch_bounds__(kBlockThreads) rank_kernel(CompressArgs A) {
   __syncthreads();
   if (wc_local < L.wc_count) {
     const uint32_t wc = L.wc_first + wc_local;
-    const uint32_t cnt = A.cand_cnt[wc];               // (<= cap2: the probe's resolve step has checked)
-    const uint2* slot = A.slots2 + static_cast<size_t>(wc) * A.cap2;
-    // One walk through the list, eight entries of a lane on their way at a time (the list is a few hundred
-    // entries long and every round trip counts).  A lane keeps the first two members it meets; the wave then
-    // appends all its members with ONE atomic, and only a wave in which some lane met more walks again.
+    const uint2* slot = A.slots2 + L.list_first + static_cast<size_t>(wc_local) * L.list_cap;
+    // One walk through the list, eight entries of a lane on their way at a time (every round trip counts); the
+    // first eight are asked for together with the list's length (the slots exist whatever the length), the next
+    // eight while these are looked at.  A lane keeps the first two members it meets; the wave then appends all its
+    // members with ONE atomic, and only a wave in which some lane met more walks again.
+    constexpr uint32_t kBatch = 8;
+    uint2 e[kBatch];
+#pragma unroll
+    for (uint32_t j = 0; j < kBatch; ++j) {
+      const uint32_t p = j * kWaveSize + lane;
+      e[j] = p < L.list_cap ? slot[p] : make_uint2(0u, 0u);
+    }
+    const uint32_t cnt = A.cand_cnt[wc];               // (<= list_cap: the streaming pass's resolve step has checked)
     uint32_t hi = 0, nm = 0;
     unsigned long long keep0 = 0ull, keep1 = 0ull;
-    constexpr uint32_t kBatch = 8;
     for (uint32_t p0 = 0; p0 < cnt; p0 += kBatch * kWaveSize) {
-      uint2 e[kBatch];
+      uint2 nx[kBatch];
 #pragma unroll
       for (uint32_t j = 0; j < kBatch; ++j) {
-        const uint32_t p = p0 + j * kWaveSize + lane;
-        e[j] = p < cnt ? slot[p] : make_uint2(0u, 0u);
+        const uint32_t p = p0 + (kBatch + j) * kWaveSize + lane;
+        nx[j] = p < cnt ? slot[p] : make_uint2(0u, 0u);
       }
 #pragma unroll
       for (uint32_t j = 0; j < kBatch; ++j) {
@@ -1505,6 +1566,8 @@ __global__ void __launch_bounds__(kBlockThreads) rank_kernel(CompressArgs A) {
           }
         }
       }
+#pragma unroll
+      for (uint32_t j = 0; j < kBatch; ++j) e[j] = nx[j];
     }
     const uint32_t nm_incl = wave_incl_scan(nm);
     const uint32_t nm_all = wave_total(nm_incl);
@@ -1530,8 +1593,7 @@ __global__ void __launch_bounds__(kBlockThreads) rank_kernel(CompressArgs A) {
         }
       }
     }
-    // the candidates above the listed band are all selected
-    const uint32_t hi_all = wave_total(wave_incl_scan(hi)) + A.wc_c[wc];
+    const uint32_t hi_all = wave_total(wave_incl_scan(hi));
     if (lane == 0) {
       st_agent(&A.wc_a[wc], hi_all);
       if (hi_all) atomicAdd(&sh.hcnt, hi_all);
@@ -1557,15 +1619,13 @@ __global__ void __launch_bounds__(kBlockThreads) rank_kernel(CompressArgs A) {
   const uint32_t k_rem = st->k_rem;
   if (ld_agent(&st->shard_overflow) != 0u || k_rem == 0u || k_rem > m) {
     // A sub-list ran over (the members crowd in a few wave-chunks), or the lists and the histogram disagree (a bug,
-    // flagged).  Nothing of the layer has been written yet: it is streamed by the next launch and goes on hint-free.
+    // flagged).  What the streaming pass masked is put back by the next launch and the layer goes on hint-free.
     if (threadIdx.x == 0) {
       if (ld_agent(&st->shard_overflow) == 0u) atomicOr(A.errflag, 32u);
       st->path = 2u;
       st->stat_misses += 1u;
-      const uint32_t wait = st->probe_backoff ? 2u * st->probe_backoff : 1u;
-      st->probe_backoff = wait < kProbeBackoffMax ? wait : kProbeBackoffMax;
-      st->probe_skip = st->probe_backoff + 1u;
-      st->next_phase = PH_STREAM;
+      dense_missed(st);
+      st->next_phase = PH_RESTORE;
       st->next_launch = A.launch + 1u;
     }
     return;
@@ -1611,7 +1671,8 @@ __global__ void __launch_bounds__(kBlockThreads) rank_kernel(CompressArgs A) {
       st->tau = drifted_tau(tn, T, st->T_prev, st->has_prev != 0u);
       st->shift = shift_for(T, tn);
       st->clip = clip_for(T, tn, st->shift);
-      st->probe_backoff = 0u;            // the probe pass did its job
+      st->mask_key = mask_key_for(T, tn, st->tau);
+      st->dense_backoff = 0u;            // the hint did its job
       st->hint_valid = 1u;
       st->T_prev = T;
       st->has_prev = 1u;
@@ -1621,19 +1682,29 @@ __global__ void __launch_bounds__(kBlockThreads) rank_kernel(CompressArgs A) {
   }
 }
 
-// Second pass of a two-pass layer (launch 3, after PH_SEL): the composite of the k-th entry is known, so an
-// element is sent if and only if its composite (key, then lower index first) is not below it.
-__global__ void __launch_bounds__(kBlockThreads) emit_kernel(CompressArgs A) {
-  // against the direction of the probe pass: what that pass read last is still in the memory-side cache
-  const uint32_t wg = A.reverse ? blockIdx.x : gridDim.x - 1u - blockIdx.x;
-  const uint32_t l = A.wg2layer[wg];
-  LayerState* st = A.state + l;
-  if (st->next_launch != A.launch || st->next_phase != PH_EMIT) return;
-  const LayerDesc L = A.layers[l];
+// Launch 3 (PH_EMIT): the composite of the k-th entry is known, and a listed element is sent if and only if its
+// composite (key, then lower index first) is not below it.  The lists are in index order, so a wave writes its
+// wave-chunk's part of the message in one walk; of the sent entries those of the coarse bins below the clip bin
+// are still in V (and u) and are masked here, the others were masked by the streaming pass.
+__device__ void dense_emit(const CompressArgs& A, const LayerDesc& L, LayerState* st, uint32_t wg) {
   const uint32_t wc_local = (wg - L.wg_first) * kWavesPerBlock + (threadIdx.x >> 6);
   if (wc_local >= L.wc_count) return;
-  const unsigned long long thr = st->thr;
   const uint32_t lane = lane_id();
+  // everything that depends on the wave-chunk's number alone is asked for together: the list's length, its first
+  // entries (the slots exist whatever the length), the counts the output offset is made of
+  const size_t list = L.list_first + static_cast<size_t>(wc_local) * L.list_cap;
+  const gptr<const vu2> slot = as_global(reinterpret_cast<const vu2*>(A.slots2 + list));
+  const gptr<const float> slot_u = as_global(static_cast<const float*>(A.slots_u + list));
+  constexpr uint32_t kBatch = 4;
+  vu2 e[kBatch];
+#pragma unroll
+  for (uint32_t j = 0; j < kBatch; ++j) {
+    const uint32_t p = j * kWaveSize + lane;
+    e[j] = p < L.list_cap ? slot[p] : vu2{0u, 0u};
+  }
+  const uint32_t cnt = A.cand_cnt[L.wc_first + wc_local];
+  const unsigned long long thr = st->thr;
+  const uint32_t mask_key = st->cur_mask_key;
   // the first output position of this wave-chunk: the offset of its group of kOffsetGroup wave-chunks (wc_b)
   // plus the selected entries of the group's chunks before it (wc_a), as in PH_OUT_C
   uint32_t out_pos;
@@ -1645,55 +1716,93 @@ __global__ void __launch_bounds__(kBlockThreads) emit_kernel(CompressArgs A) {
     out_pos = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(excl),
                                                               static_cast<int>(__builtin_amdgcn_readfirstlane(wc_local % kOffsetGroup))));
   }
-  const uint32_t begin = wc_local * A.chunk;
-  const uint32_t end = (L.n - begin) < A.chunk ? L.n : begin + A.chunk;
   const bool clear_mom = (L.mom != nullptr) && A.mask_momentum;
-  const bool has_mom = L.mom != nullptr;
   const gptr<int32_t> out_idx = as_global(L.out_idx);
   const gptr<float> out_val = as_global(L.out_val);
   const gptr<float> resid = as_global(L.resid);
   const gptr<float> mom = as_global(L.mom);
-  recompute_chunk_any(A, L, begin, end, [&](const float (&a)[4], const float (&u)[4], uint32_t nvalid, uint32_t idx0, bool vec) {
-    bool sel[4];
+  for (uint32_t p0 = 0; p0 < cnt; p0 += kBatch * kWaveSize) {
+    vu2 nx[kBatch];                                   // the next entries are on their way while these are written
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-      sel[j] = (static_cast<uint32_t>(j) < nvalid) &&
-               composite(key_of(fbits(a[j]), A.sign_xor, A.sign_filter), idx0 + j) >= thr;
-    const unsigned long long s0 = __ballot(sel[0]), s1 = __ballot(sel[1]), s2 = __ballot(sel[2]), s3 = __ballot(sel[3]);
-    if ((s0 | s1 | s2 | s3) != 0ull) {
-      uint32_t pos = out_pos + rank_below(s0) + rank_below(s1) + rank_below(s2) + rank_below(s3);
+    for (uint32_t j = 0; j < kBatch; ++j) {
+      const uint32_t p = p0 + (kBatch + j) * kWaveSize + lane;
+      nx[j] = p < cnt ? slot[p] : vu2{0u, 0u};
+    }
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        if (sel[j]) {
-          if (pos < L.k) {   // always true when the counts are consistent
-            out_idx[pos] = static_cast<int32_t>(idx0 + j);
-            out_val[pos] = a[j];
-          }
-          ++pos;
+    for (uint32_t j = 0; j < kBatch; ++j) {
+      const uint32_t key = key_of(e[j].x, A.sign_xor, A.sign_filter);
+      const bool sel = (p0 + j * kWaveSize + lane < cnt) && composite(key, e[j].y) >= thr;
+      const unsigned long long sm = __ballot(sel);
+      const uint32_t pos = out_pos + rank_below(sm);
+      const uint32_t p = p0 + j * kWaveSize + lane;
+      if (sel && pos < L.k && e[j].y < L.n) {   // the bounds always hold when the counts are consistent
+        out_idx[pos] = static_cast<int32_t>(e[j].y);
+        out_val[pos] = __uint_as_float(e[j].x);
+        if (key < mask_key) {                   // (the streaming pass has masked the others)
+          mask_store(&resid[e[j].y]);
+          if (clear_mom) mask_store(&mom[e[j].y]);
         }
+      } else if (!sel && p < cnt && key >= mask_key && e[j].y < L.n) {
+        // masked by the streaming pass on the strength of the hint, and not sent after all: back it goes
+        // (isolated 4-byte writes like the masking ones: stored with the streaming hint for the same reason)
+        __builtin_nontemporal_store(__uint_as_float(e[j].x), &resid[e[j].y]);
+        if (clear_mom) __builtin_nontemporal_store(slot_u[p], &mom[e[j].y]);
       }
-      out_pos += popc64(s0) + popc64(s1) + popc64(s2) + popc64(s3);
+      out_pos += popc64(sm);
     }
-    float v[4], w[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      v[j] = sel[j] ? 0.0f : a[j];
-      w[j] = (sel[j] && clear_mom) ? 0.0f : u[j];
-    }
-    if (vec) {
-      *reinterpret_cast<gptr<vf4>>(resid + idx0) = vf4{v[0], v[1], v[2], v[3]};
-      if (has_mom) *reinterpret_cast<gptr<vf4>>(mom + idx0) = vf4{w[0], w[1], w[2], w[3]};
-    } else {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        if (static_cast<uint32_t>(j) < nvalid) {
-          resid[idx0 + j] = v[j];
-          if (has_mom) mom[idx0 + j] = w[j];
-        }
-      }
-    }
-  });
+    for (uint32_t j = 0; j < kBatch; ++j) e[j] = nx[j];
+  }
   if (wc_local == 0 && lane == 0) *as_global(L.out_count) = static_cast<int32_t>(L.k);
+}
+
+// PH_RESTORE: the entries the streaming pass masked (coarse bin not below the clip bin) get their accumulated value
+// and their velocity back from the lists; the layer's last workgroup then starts the multi-pass path.
+__device__ void dense_restore(const CompressArgs& A, const LayerDesc& L, LayerState* st, uint32_t wg, ResolveShared& sh) {
+  const uint32_t wc_local = (wg - L.wg_first) * kWavesPerBlock + (threadIdx.x >> 6);
+  if (wc_local < L.wc_count) {
+    const uint32_t mask_key = st->cur_mask_key;
+    const bool clear_mom = (L.mom != nullptr) && A.mask_momentum;
+    const gptr<float> resid = as_global(L.resid);
+    const gptr<float> mom = as_global(L.mom);
+    const size_t list = L.list_first + static_cast<size_t>(wc_local) * L.list_cap;
+    const gptr<const vu2> slot = as_global(reinterpret_cast<const vu2*>(A.slots2 + list));
+    const gptr<const float> slot_u = as_global(static_cast<const float*>(A.slots_u + list));
+    uint32_t cnt = A.cand_cnt[L.wc_first + wc_local] & ~kListStopped;   // (a list that stopped early: what it held by then)
+    cnt = cnt < L.list_cap ? cnt : L.list_cap;
+    for (uint32_t p = lane_id(); p < cnt; p += kWaveSize) {
+      const vu2 e = slot[p];
+      const uint32_t key = key_of(e.x, A.sign_xor, A.sign_filter);
+      if (key >= mask_key && e.y < L.n) {
+        resid[e.y] = __uint_as_float(e.x);
+        if (clear_mom) mom[e.y] = slot_u[p];
+      }
+    }
+  }
+  if (!last_block_of_layer(&st->done, A.group_done + L.grp_first, wg - L.wg_first, L.wg_count, &sh.flag)) return;
+  if (threadIdx.x == 0) {
+    st->next_phase = PH_HIST1;
+    st->next_launch = A.launch + 1u;
+  }
+}
+
+}  // namespace
+
+__global__ void __launch_bounds__(kBlockThreads) lists_kernel(CompressArgs A) {
+  __shared__ ResolveShared sh;
+  __shared__ __attribute__((aligned(16))) uint32_t sel_hist[3 * 256];
+  __shared__ uint32_t shard_first[kMemberShards + 1];
+  const uint32_t wg = blockIdx.x;
+  const uint32_t l = A.wg2layer[wg];
+  LayerState* st = A.state + l;
+  if (st->next_launch != A.launch) return;
+  const LayerDesc L = A.layers[l];
+  switch (st->next_phase) {
+    case PH_SEL2: dense_rank(A, l, L, st, wg, sh, sel_hist, shard_first); break;
+    case PH_EMIT: dense_emit(A, L, st, wg); break;
+    case PH_RESTORE: dense_restore(A, L, st, wg, sh); break;
+    default: break;                                   // the other phases belong to phase_kernel
+  }
 }
 
 // Overwrite the cached thresholds with wrong values (test hook: results must not change).
@@ -1961,23 +2070,18 @@ hipError_t launch_accumulate(const CompressArgs& a, uint32_t num_wgs, hipStream_
   return hipGetLastError();
 }
 
-hipError_t launch_probe(const CompressArgs& a, uint32_t num_wgs, hipStream_t s) {
-  hipLaunchKernelGGL(probe_kernel, dim3(num_wgs), dim3(kBlockThreads), 0, s, a);
+hipError_t launch_collect(const CompressArgs& a, uint32_t num_wgs, hipStream_t s) {
+  hipLaunchKernelGGL(collect_kernel, dim3(num_wgs), dim3(kBlockThreads), 0, s, a);
   return hipGetLastError();
 }
 
-hipError_t launch_rank(const CompressArgs& a, uint32_t num_wgs, hipStream_t s) {
-  hipLaunchKernelGGL(rank_kernel, dim3(num_wgs), dim3(kBlockThreads), 0, s, a);
+hipError_t launch_lists(const CompressArgs& a, uint32_t num_wgs, hipStream_t s) {
+  hipLaunchKernelGGL(lists_kernel, dim3(num_wgs), dim3(kBlockThreads), 0, s, a);
   return hipGetLastError();
 }
 
-hipError_t launch_emit(const CompressArgs& a, uint32_t num_wgs, hipStream_t s) {
-  hipLaunchKernelGGL(emit_kernel, dim3(num_wgs), dim3(kBlockThreads), 0, s, a);
-  return hipGetLastError();
-}
-
-hipError_t launch_phase(const CompressArgs& a, uint32_t num_wgs, hipStream_t s) {
-  if (a.launch >= kFirstLateLaunch) hipLaunchKernelGGL(phase_late_kernel, dim3(num_wgs), dim3(kBlockThreads), 0, s, a);
+hipError_t launch_phase(const CompressArgs& a, uint32_t num_wgs, bool every_phase, hipStream_t s) {
+  if (a.launch >= kFirstLateLaunch && !every_phase) hipLaunchKernelGGL(phase_late_kernel, dim3(num_wgs), dim3(kBlockThreads), 0, s, a);
   else hipLaunchKernelGGL(phase_kernel, dim3(num_wgs), dim3(kBlockThreads), 0, s, a);
   return hipGetLastError();
 }

@@ -29,15 +29,15 @@ enum Phase : uint32_t {
   PH_COUNT = 6,    // multi-pass: per wave-chunk counts of keys > T and == T
   PH_OUT_V = 7,    // multi-pass: ordered compaction from the updated residual
   PH_COLLECT = 8,  // after the first digit: candidate lists from the updated residual, then PH_SEL / PH_OUT_C
-  PH_STREAM = 9,   // two-pass layers whose probe pass missed: the ordinary streaming pass after all (launch 2)
-  PH_EMIT = 10,    // two-pass layers: the second pass writes residual, velocity and message with the threshold known
-  PH_SEL2 = 11,    // two-pass layers: PH_SEL on the probe pass's lists (rank_kernel)
+  PH_RESTORE = 9,  // dense layers whose hint missed: the entries masked on the strength of the hint go back into residual and velocity
+  PH_EMIT = 10,    // dense layers: the message from the lists, with the k-th entry known
+  PH_SEL2 = 11,    // dense layers: PH_SEL on the layer's own lists (lists_kernel)
 };
 
-// Two-pass layers: after a probe pass that missed, the layer goes without one for a number of calls that
+// Dense layers: after a call whose hint missed, the layer goes without its hint for a number of calls that
 // doubles with every further miss, up to this many.
-constexpr uint32_t kProbeBackoffMax = 64;
-// Two-pass layers: the members of the k-th key's coarse bin are appended to this many sub-lists, each with a counter
+constexpr uint32_t kDenseBackoffMax = 64;
+// Dense layers: the members of the k-th key's coarse bin are appended to this many sub-lists, each with a counter
 // of its own (thousands of waves appending through one counter take their turns at ~20 ns each).
 constexpr uint32_t kMemberShards = 16;
 constexpr uint32_t kShardStride = 64;    // words between two counters: atomics on one cache line take their turns like atomics on one word
@@ -61,11 +61,14 @@ struct LayerDesc {
   uint32_t hintable;   // one-pass layer: the candidate lists can hold every element from the hinted threshold upwards
   uint32_t margin;     // extra candidates aimed for beyond k
   uint32_t cmax;       // largest candidate total a hint may aim at
-  uint32_t target;     // rank the next call's threshold hint is aimed at (2k + margin, two-pass layers: k + margin)
-  uint32_t two_pass;   // high-density layer: a read-only probe pass lists only the keys around the hinted threshold,
-                       // the second pass applies the exact threshold (never set together with hintable)
-  uint32_t mem_cap;    // two-pass layers: entries of the layer's region of the member pool (a multiple of kMemberShards)
-  uint64_t mem_first;  // ... and where the region starts
+  uint32_t target;     // rank the next call's threshold hint is aimed at (2k + margin, dense layers: k + margin)
+  uint32_t dense;      // high-density layer (never set together with hintable): with a hint, its streaming pass lists every
+                       // candidate in lists of its own and masks those far enough above the hinted threshold at once
+  uint32_t mem_cap;    // dense layers: entries of the layer's region of the member pool (a multiple of kMemberShards)
+  uint32_t list_cap;   // dense layers: entries of one wave-chunk's list
+  uint32_t pad_;
+  uint64_t mem_first;  // dense layers: where the layer's region of the member pool starts
+  uint64_t list_first; // dense layers: where the layer's lists start (wave-chunk c of the layer: list_first + c * list_cap)
 };
 
 // Per layer state living in the context (device memory).  Everything but the hint fields is
@@ -93,12 +96,16 @@ struct LayerState {
   uint32_t stat_candidates;  // diagnostics of the last call
   uint32_t stat_members;
   uint32_t stat_misses;      // calls so far in which this layer's hint missed (never reset)
-  // two-pass layers (speed only, like the hints)
-  uint32_t clip;             // the probe pass lists the candidates of the coarse bins below this one
-  uint32_t probe_backoff;    // calls the layer went without a probe pass after the last miss
-  uint32_t probe_skip;       // calls it still goes without one
+  // dense layers (speed only, like the hints)
+  uint32_t clip;             // candidates of the coarse bins from this one upwards are sure to be selected: counted, not ranked
+  uint32_t dense_backoff;    // calls the layer went without its hint after the last miss
+  uint32_t dense_skip;       // calls it still goes without it
   uint32_t shard_overflow;   // a member sub-list ran over in this call's ranking launch
-  uint32_t pad_[3];
+  uint32_t cur_tau;          // tau, shift and mask_key as this call's streaming pass used them (the ranking step rewrites
+  uint32_t cur_shift;        // the hint for the next call before the output step has read it)
+  uint32_t cur_mask_key;
+  uint32_t mask_key;         // dense layers: where the k-th key of the next call is expected; its streaming pass masks the candidates
+                             // from here upwards at once and the output step puts right what that got wrong
 };
 
 // Where the kernels of an exactly rounded sum leave their parts (one per workgroup): the running sum
@@ -130,10 +137,9 @@ struct CompressArgs {
   uint2* slots;          // [wave-chunks][cap] (float bits, index), ascending index per chunk
   uint32_t* wc_a;        // [wave-chunks] counts, then output offsets
   uint32_t* wc_b;        // [wave-chunks] tie counts, then tie prefixes
-  uint32_t* wc_c;        // [wave-chunks] two-pass layers: candidates of the probe pass above the listed band
-  uint2* slots2;         // [wave-chunks][cap2] the probe pass's lists (allocated when a two-pass layer is first seen)
-  uint32_t cap2;         // slots per wave-chunk in slots2
-  unsigned long long* members2;  // member pool of the two-pass layers (LayerDesc::mem_first, mem_cap)
+  uint2* slots2;         // the lists of the dense layers (LayerDesc::list_first, list_cap; allocated when such a layer is first seen)
+  float* slots_u;        // the velocity of every listed element, same layout (restores a masked entry after a miss)
+  unsigned long long* members2;  // member pool of the dense layers (LayerDesc::mem_first, mem_cap)
   uint32_t* shard_cnt;   // [layers][kMemberShards][kShardStride] members appended to each sub-list, one counter per 256 bytes
   uint32_t* group_done;  // [election groups] workgroups of the group that finished the current phase
   uint32_t* errflag;     // set non-zero on an internal inconsistency
@@ -237,10 +243,10 @@ int fail_hip(hipError_t e, const char* what);
 
 // kernel launchers (defined in the .hip files)
 hipError_t launch_accumulate(const CompressArgs& a, uint32_t num_wgs, hipStream_t s);
-hipError_t launch_probe(const CompressArgs& a, uint32_t num_wgs, hipStream_t s);
-hipError_t launch_rank(const CompressArgs& a, uint32_t num_wgs, hipStream_t s);
-hipError_t launch_emit(const CompressArgs& a, uint32_t num_wgs, hipStream_t s);
-hipError_t launch_phase(const CompressArgs& a, uint32_t num_wgs, hipStream_t s);
+hipError_t launch_collect(const CompressArgs& a, uint32_t num_wgs, hipStream_t s);   // streaming pass of the dense layers
+hipError_t launch_lists(const CompressArgs& a, uint32_t num_wgs, hipStream_t s);     // their ranking, output and restoring steps
+// every_phase: the launch may meet any phase (calls with dense layers, whose fall-back starts later)
+hipError_t launch_phase(const CompressArgs& a, uint32_t num_wgs, bool every_phase, hipStream_t s);
 constexpr uint32_t kMeanPartsMax = 128;    // parts per layer at most (rgc_message_means)
 hipError_t launch_message_means(const CompressArgs& a, uint32_t num_layers, uint32_t max_k, const ExactParts& parts,
                                 float* d_means, hipStream_t s);

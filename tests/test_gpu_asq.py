@@ -159,8 +159,8 @@ def test_means_of_hard_sums(rgc, oracle, law):
 @pytest.mark.parametrize("ppm", [250_000, 62_500])
 def test_alternating_selection_at_warmup_densities(rgc, oracle, ppm):
     """The densities of a warm-up period (Section 2.5) with the alternating selection: the large layers take the
-    read-only probe pass and the second streaming pass once their hints exist, with the signed key; gradients
-    larger than the residual keep the k-th value steady, so the probes hit."""
+    hinted path of the dense layers once their hints exist, with the signed key; gradients larger than the residual
+    keep the k-th value steady, so the hints hit."""
     g = np.random.default_rng(86)
     sizes = [600_000, 200_003, 9_000]
     V = [(g.standard_normal(n) * 1e-3).astype(np.float32) for n in sizes]
@@ -168,7 +168,7 @@ def test_alternating_selection_at_warmup_densities(rgc, oracle, ppm):
     Gs = [[(g.standard_normal(n) * 5e-3).astype(np.float32) for n in sizes] for _ in range(10)]
     ks = [rgc.rgc_k_for_density(n, ppm) for n in sizes]
     paths = run_asq(rgc, oracle, V, Gs, ks, U0=U, m=0.5, tag="asq %d ppm" % ppm)
-    assert paths[-1][0] == 0 and paths[-2][0] == 0, paths      # both signs' hints lead the largest layer through the two passes
+    assert paths[-1][0] == 0 and paths[-2][0] == 0, paths      # both signs' hints lead the largest layer along its hinted path
 
 
 def test_no_hints_gives_the_same(rgc, oracle):

@@ -173,9 +173,10 @@ def test_larger_density(rgc, oracle):
 
 @pytest.mark.parametrize("ppm", [250_000, 62_500, 15_625])
 @pytest.mark.parametrize("variant", ["plain", "momentum", "nesterov_unmasked"])
-def test_warmup_densities_take_the_two_pass_path(rgc, oracle, ppm, variant):
+def test_warmup_densities_take_the_dense_path(rgc, oracle, ppm, variant):
     """Section 2.5's warm-up densities on layers of several wave-chunks: the first call is hint-free, later
-    calls probe read-only and write residual, velocity and message in the second pass; every step bit for bit."""
+    calls list every candidate while they stream, mask those above the expected k-th key at once and put right
+    what that got wrong when the message is written; every step bit for bit."""
     g = np.random.default_rng(500 + ppm % 97)
     sizes = [300_000, 70_001, 40_960, 9_000]
     # gradients larger than the residual: the k-th magnitude then hardly moves from call to call, as in
@@ -184,7 +185,7 @@ def test_warmup_densities_take_the_two_pass_path(rgc, oracle, ppm, variant):
     # (the velocity starts at its stationary scale for the same reason)
     V = [(g.laplace(size=n) * 1e-3).astype(np.float32) for n in sizes]
     U = [(g.laplace(size=n) * 1.15e-2).astype(np.float32) for n in sizes] if variant != "plain" else None
-    G_list = [[(g.laplace(size=n) * 1e-2).astype(np.float32) for n in sizes] for _ in range(8)]
+    G_list = [[(g.laplace(size=n) * 1e-2).astype(np.float32) for n in sizes] for _ in range(14)]
     ks = [rgc.rgc_k_for_density(n, ppm) for n in sizes]
     flags = (rgc.RGC_NESTEROV | rgc.RGC_NO_MOMENTUM_MASK) if variant == "nesterov_unmasked" else 0
 
@@ -196,9 +197,10 @@ def test_warmup_densities_take_the_two_pass_path(rgc, oracle, ppm, variant):
                    tag="warmup %d ppm %s" % (ppm, variant), expect_paths=expect)
 
 
-def test_two_pass_layers_with_poisoned_hints_ties_and_unaligned_tensors(rgc, oracle):
-    """The probe pass must notice a useless hint (too high, too low, random), heavy ties (the bin of the k-th
-    key does not fit the ranking) and list overflows, and the call must still give the exact result."""
+def test_dense_layers_with_poisoned_hints_ties_and_unaligned_tensors(rgc, oracle):
+    """The streaming pass of a dense layer must notice a useless hint (too high, too low, random), heavy ties (the
+    bin of the k-th key does not fit the ranking) and list overflows, put back what it masked on the strength of the
+    hint, and the call must still give the exact result."""
     g = np.random.default_rng(77)
     sizes = [200_003, 131_072, 60_000]
     ks = [rgc.rgc_k_for_density(n, 62_500) for n in sizes]
@@ -207,12 +209,13 @@ def test_two_pass_layers_with_poisoned_hints_ties_and_unaligned_tensors(rgc, ora
     G_list = [[(g.standard_normal(n) * 1e-3).astype(np.float32) for n in sizes] for _ in range(7)]
     for G in G_list:
         G[1][:] = (np.round(G[1] * 800) / 800).astype(np.float32)
-    paths = run_iterations(rgc, oracle, V, G_list, ks, poison=[0, 1, 2, 2, 0, 1], misalign=1, tag="two-pass poison")
-    assert any(p == 2 for step in paths[1:] for p in step), "poisoned hints should make the probe pass miss: %r" % (paths,)
+    paths = run_iterations(rgc, oracle, V, G_list, ks, poison=[0, 1, 2, 2, 0, 1], misalign=1, tag="dense poison")
+    assert any(p == 2 for step in paths[1:] for p in step), "poisoned hints should make the hinted pass miss: %r" % (paths,)
 
 
-def test_two_pass_clustered_values_overflow_single_lists(rgc, oracle):
-    """All large values in one stretch of the tensor: the probe pass's lists of those wave-chunks overflow."""
+def test_dense_layers_clustered_values_overflow_single_lists(rgc, oracle):
+    """All large values in one stretch of the tensor: the lists of those wave-chunks run over, the pass stops listing
+    and masking there, and what it had masked by then is put back."""
     g = np.random.default_rng(78)
     n = 400_000
     ks = [rgc.rgc_k_for_density(n, 62_500)]
@@ -220,16 +223,16 @@ def test_two_pass_clustered_values_overflow_single_lists(rgc, oracle):
     scale[100_000:130_000] = 1.0
     V = [(g.standard_normal(n).astype(np.float32) * scale)]
     G_list = [[(g.standard_normal(n).astype(np.float32) * scale * 0.1)] for _ in range(4)]
-    run_iterations(rgc, oracle, V, G_list, ks, tag="two-pass clustered")
+    run_iterations(rgc, oracle, V, G_list, ks, tag="dense clustered")
 
 
 @pytest.mark.parametrize("ppm", [250_000, 15_625])
 def test_config3_vgg16_set_full_size_warmup_density(rgc, oracle, ppm):
     """The VGG16-shaped set with the momentum correction at a warm-up density, at full size (the configuration
-    the benchmark's warm-up block times).  The threshold hints of the two-pass path need a few calls to settle
+    the benchmark's warm-up block times).  The threshold hints of the dense layers need a few calls to settle
     (the first hinted call finds the residual's k-th magnitude far from where the hint-free call left it), so
     eight calls run on the GPU alone; the oracle then starts from the residual and velocity the GPU holds and
-    the next two calls are compared bit for bit, with the large layers on the two-pass path."""
+    the next two calls are compared bit for bit, with the large layers on their hinted path."""
     cfg = synth.config_vgg16(num_grads=4)
     V0, U0, G_list, m = cfg["V"], cfg["U"], cfg["G"], cfg["momentum"]
     ks = [rgc.rgc_k_for_density(v.size, ppm) for v in V0]
@@ -249,7 +252,7 @@ def test_config3_vgg16_set_full_size_warmup_density(rgc, oracle, ppm):
         assert_layers_equal("C3 %d ppm step %d" % (ppm, t), ks, dev.results(), msgs, Vh, Uh)
         paths.append(ctx.last_paths(len(V0)))
     big = int(np.argmax([v.size for v in V0]))
-    assert any(p[big] == 0 for p in paths), "the largest layer never took the two-pass path: %r" % (paths,)
+    assert any(p[big] == 0 for p in paths), "the largest layer never took its hinted path: %r" % (paths,)
     ctx.close()
 
 
