@@ -268,7 +268,7 @@ int build_compress_plan(rgc_ctx* ctx, CompressPlan& P, const rgc_layer* layers, 
         lists += static_cast<uint64_t>(d.wc_count) * d.list_cap;
         d.mem_cap = static_cast<uint32_t>(std::max<uint64_t>(4096, d.n / 64) / kMemberShards * kMemberShards);
         d.mem_first = mem;
-        mem += d.mem_cap;
+        mem += d.mem_cap + d.mem_cap / 4;       // (the sub-lists and the list for what they cannot hold)
         d.margin = static_cast<uint32_t>(margin2);
         d.target = static_cast<uint32_t>(k + margin2);
         cmax = k + 2 * margin2;
@@ -699,7 +699,7 @@ int rgc_compress_layers_scaled(rgc_ctx* ctx, const rgc_layer* layers, int32_t nu
     hipError_t e = ctx->d_slots2.alloc(plan->list_entries);
     if (e == hipSuccess) e = ctx->d_slots_u.alloc(plan->list_entries);
     if (e == hipSuccess) e = ctx->d_members2.alloc(plan->member_entries);
-    if (e == hipSuccess && !ctx->d_shards.p) e = ctx->d_shards.alloc(static_cast<size_t>(ctx->max_layers) * kMemberShards * kShardStride);
+    if (e == hipSuccess && !ctx->d_shards.p) e = ctx->d_shards.alloc(static_cast<size_t>(ctx->max_layers) * kMemberLists * kShardStride);
     if (e != hipSuccess) {
       ctx->d_slots2.release();
       ctx->d_slots_u.release();
@@ -722,15 +722,15 @@ int rgc_compress_layers_scaled(rgc_ctx* ctx, const rgc_layer* layers, int32_t nu
   A.launch = 1;
   // Dense layers that have a hint are streamed by a kernel of their own and skipped by accumulate_kernel (both
   // decide from the same state, which neither changes before its layer is done).  They are ranked at launch 2 and
-  // written at launch 3 by lists_kernel; one whose hint misses has its residual put right at launch 2 or 3 and
-  // then takes the five passes, so such a call has up to eight launches.
+  // written at launch 3 by lists_kernel; one whose hint misses has its residual put right at launch 2, where it
+  // also starts on the five passes.
   if (ctx->profiling) RGC_HIP(take_event(ctx, stream, ctx->ev_compress));
   RGC_HIP(launch_accumulate(A, plan->num_wgs, stream));
   if (dense) RGC_HIP(launch_collect(A, plan->num_wgs, stream));
   if (ctx->profiling) RGC_HIP(take_event(ctx, stream, ctx->ev_compress));
-  for (int launch = 2; launch <= kLaunches + (dense ? 2 : 0); ++launch) {
+  for (int launch = 2; launch <= kLaunches; ++launch) {
     A.launch = static_cast<uint32_t>(launch);
-    RGC_HIP(launch_phase(A, plan->num_wgs, dense, stream));
+    RGC_HIP(launch_phase(A, plan->num_wgs, stream));
     if (dense && launch <= 3) RGC_HIP(launch_lists(A, plan->num_wgs, stream));
   }
   if (ctx->profiling) RGC_HIP(take_event(ctx, stream, ctx->ev_compress));

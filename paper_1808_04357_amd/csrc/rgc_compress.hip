@@ -528,10 +528,9 @@ __device__ void resolve_collect(const CompressArgs& A, uint32_t l, const LayerDe
   // PH_SEL adds the selected counts of every kOffsetGroup wave-chunks up in wc_b: start from zero
   for (uint32_t g = t; g < (L.wc_count + kOffsetGroup - 1u) / kOffsetGroup; g += kBlockThreads)
     st_agent(&A.wc_b[L.wc_first + g], 0u);
-  if (dense && t < kMemberShards) st_agent(&A.shard_cnt[(static_cast<size_t>(l) * kMemberShards + t) * kShardStride], 0u);
+  if (dense && t < kMemberLists) st_agent(&A.shard_cnt[(static_cast<size_t>(l) * kMemberLists + t) * kShardStride], 0u);
   if (t == 0) {
     if (dense) {
-      st->shard_overflow = 0u;
       st->cur_tau = st->tau;
       st->cur_shift = st->shift;
       st->cur_mask_key = dense_mask_key(st->mask_key, st->tau);
@@ -567,7 +566,7 @@ __device__ void resolve_collect(const CompressArgs& A, uint32_t l, const LayerDe
     } else if (dense) {
       st->path = 2u;
       st->stat_misses += 1u;
-      st->next_phase = PH_RESTORE;        // then the multi-pass path on the restored residual
+      st->next_phase = PH_RESTORE;        // the multi-pass path on the restored residual
       dense_missed(st);
     } else {
       st->path = 2u;
@@ -775,6 +774,33 @@ __global__ void __launch_bounds__(kBlockThreads) accumulate_kernel(CompressArgs 
 
 // =================================================================== launches 2..6: phases
 namespace {
+
+// PH_RESTORE, a dense layer whose hint missed: the entries its streaming pass masked on the strength of the hint
+// (keys from the expected k-th key upwards) get their accumulated value and their velocity back from the wave-chunk's
+// list; V and u are then exactly what an ordinary streaming pass leaves.  The wave goes on to the first digit's
+// histogram of the same wave-chunk at once (phase_hist<1>), which reads what it has just written.
+__device__ void dense_restore(const CompressArgs& A, const LayerDesc& L, const LayerState* st, uint32_t wc_local) {
+  if (wc_local < L.wc_count) {
+    const uint32_t mask_key = st->cur_mask_key;
+    const bool clear_mom = (L.mom != nullptr) && A.mask_momentum;
+    const gptr<float> resid = as_global(L.resid);
+    const gptr<float> mom = as_global(L.mom);
+    const size_t list = L.list_first + static_cast<size_t>(wc_local) * L.list_cap;
+    const gptr<const vu2> slot = as_global(reinterpret_cast<const vu2*>(A.slots2 + list));
+    const gptr<const float> slot_u = as_global(static_cast<const float*>(A.slots_u + list));
+    uint32_t cnt = A.cand_cnt[L.wc_first + wc_local] & ~kListStopped;   // (a list that stopped early: what it held by then)
+    cnt = cnt < L.list_cap ? cnt : L.list_cap;
+    for (uint32_t p = lane_id(); p < cnt; p += kWaveSize) {
+      const vu2 e = slot[p];
+      const uint32_t key = key_of(e.x, A.sign_xor, A.sign_filter);
+      if (key >= mask_key && e.y < L.n) {
+        resid[e.y] = __uint_as_float(e.x);
+        if (clear_mom) mom[e.y] = slot_u[p];
+      }
+    }
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the wave's stores have arrived before it reads the wave-chunk
+}
 
 template <int kLevel>
 __device__ void phase_hist(const CompressArgs& A, uint32_t l, const LayerDesc& L, LayerState* st, uint32_t wg,
@@ -1166,6 +1192,7 @@ __global__ void __launch_bounds__(kBlockThreads) phase_kernel(CompressArgs A) {
     case PH_SEL:   phase_sel(A, l, L, st, wg, sm.sortbuf, sel_hist, sh); break;
     case PH_OUT_C: phase_out_c(A, L, st, wg); break;
     case PH_HIST1: phase_hist<1>(A, l, L, st, wg, wc_local, sm.hist, sh); break;
+    case PH_RESTORE: dense_restore(A, L, st, wc_local); phase_hist<1>(A, l, L, st, wg, wc_local, sm.hist, sh); break;
     case PH_HIST2: phase_hist<2>(A, l, L, st, wg, wc_local, sm.hist, sh); break;
     case PH_HIST3: phase_hist<3>(A, l, L, st, wg, wc_local, sm.hist, sh); break;
     case PH_COUNT: phase_count(A, l, L, st, wg, wc_local, sh); break;
@@ -1217,9 +1244,10 @@ __global__ void __launch_bounds__(kBlockThreads) phase_late_kernel(CompressArgs 
 //     wrong is put right here: a sent entry below mask_key is masked now, a masked entry that is not sent gets
 //     its value and velocity back (as many isolated writes as the k-th key lies ranks away from where it was
 //     expected, whatever the width of the band).
-// If the hint misses (too few candidates, the k-th key at or above the clip bin, a list or a member sub-list
-// that ran over), what step 1 masked is put back from the lists (PH_RESTORE: V and u are then exactly the
-// accumulated values, as after an ordinary streaming pass) and the layer goes on with the multi-pass path.
+// If the hint misses (too few candidates, the k-th key at or above the clip bin, a list that ran over, more
+// members than can be ranked), what step 1 masked is put back from the lists at launch 2 (PH_RESTORE: V and u
+// are then exactly the accumulated values, as after an ordinary streaming pass), and the layer starts on the
+// multi-pass path in the same launch.
 // A wave-chunk whose list may not hold the next group stops listing AND masking there, so the lists always
 // hold what was masked.
 namespace {
@@ -1416,33 +1444,33 @@ __global__ void __launch_bounds__(kBlockThreads) collect_kernel(CompressArgs A) 
 
 namespace {
 
-// The members of a dense layer: kMemberShards sub-lists in global memory (region + s * shard_cap, n[s] entries),
-// which other workgroups filled with device-scope stores.  A thread asks for eight values at a time, so that
-// their round trips overlap.
+// The members of a dense layer: kMemberLists lists in global memory (region + s * shard_cap, n[s] entries; the last
+// one, for what the others could not hold, is longer), which other workgroups filled with device-scope stores.
+// A thread asks for one value of every list at a time, so that their round trips overlap.
 struct MemberLists {
   const unsigned long long* region;
   uint32_t shard_cap;
-  const uint32_t* first;  // [kMemberShards + 1], in LDS: running number of each sub-list's first member; [kMemberShards] = all
+  const uint32_t* first;  // [kMemberLists + 1], in LDS: running number of each list's first member; [kMemberLists] = all
 };
 
 template <typename F>
 __device__ __forceinline__ void for_each_member(const MemberLists& M, F&& f) {
-  // one step takes the i-th member of every sub-list: kMemberShards independent loads of a thread in flight
-  uint32_t n[kMemberShards], nmax = 0u;
+  // one step takes the i-th member of every list: kMemberLists independent loads of a thread in flight
+  uint32_t n[kMemberLists], nmax = 0u;
 #pragma unroll
-  for (uint32_t s = 0; s < kMemberShards; ++s) {
+  for (uint32_t s = 0; s < kMemberLists; ++s) {
     n[s] = M.first[s + 1] - M.first[s];
     nmax = n[s] > nmax ? n[s] : nmax;
   }
   for (uint32_t i = threadIdx.x; i < nmax; i += kBlockThreads) {
-    unsigned long long x[kMemberShards];
+    unsigned long long x[kMemberLists];
 #pragma unroll
-    for (uint32_t s = 0; s < kMemberShards; ++s)
+    for (uint32_t s = 0; s < kMemberLists; ++s)
       x[s] = i < n[s] ? __hip_atomic_load(&M.region[static_cast<size_t>(s) * M.shard_cap + i], __ATOMIC_RELAXED,
                                           __HIP_MEMORY_SCOPE_AGENT)
                       : 0ull;
 #pragma unroll
-    for (uint32_t s = 0; s < kMemberShards; ++s)
+    for (uint32_t s = 0; s < kMemberLists; ++s)
       if (i < n[s]) f(x[s]);
   }
 }
@@ -1524,7 +1552,7 @@ __device__ void dense_rank(const CompressArgs& A, uint32_t l, const LayerDesc& L
                            ResolveShared& sh, uint32_t* sel_hist, uint32_t* shard_first) {
   const uint32_t tau = st->cur_tau, shift = st->cur_shift, bstar = st->bstar;
   unsigned long long* const region = A.members2 + L.mem_first;
-  const uint32_t shard_cap = L.mem_cap / kMemberShards;
+  const uint32_t shard_cap = L.mem_cap / kMemberShards, spill_cap = L.mem_cap / 4u;
   const uint32_t lane = lane_id();
   const uint32_t wc_local = (wg - L.wg_first) * kWavesPerBlock + (threadIdx.x >> 6);
   if (threadIdx.x == 0) sh.hcnt = 0u;              // what this workgroup's lists add to their offset group
@@ -1572,24 +1600,34 @@ __device__ void dense_rank(const CompressArgs& A, uint32_t l, const LayerDesc& L
     const uint32_t nm_incl = wave_incl_scan(nm);
     const uint32_t nm_all = wave_total(nm_incl);
     if (nm_all != 0u) {
+      // the wave's members go to its sub-list as far as that has room, the others to the overflow list (which can
+      // hold every member the streaming pass's resolve step accepts): no sub-list is left with a gap
       const uint32_t shard = wc_local % kMemberShards;
-      uint32_t base = 0;
-      if (lane == 0) base = atomicAdd(&A.shard_cnt[(static_cast<size_t>(l) * kMemberShards + shard) * kShardStride], nm_all);
+      uint32_t base = 0, spill_base = 0;
+      if (lane == 0) {
+        base = atomicAdd(&A.shard_cnt[(static_cast<size_t>(l) * kMemberLists + shard) * kShardStride], nm_all);
+        const uint32_t from = base > shard_cap ? base : shard_cap;
+        if (base + nm_all > from)
+          spill_base = atomicAdd(&A.shard_cnt[(static_cast<size_t>(l) * kMemberLists + kMemberShards) * kShardStride], base + nm_all - from);
+      }
       base = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(base)));
-      if (base + nm_all > shard_cap) {
-        if (lane == 0) atomicOr(&st->shard_overflow, 1u);   // the layer is streamed after all (see below)
+      spill_base = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(spill_base)));
+      const uint32_t from = base > shard_cap ? base : shard_cap;
+      auto put = [&](uint32_t at, unsigned long long c) {        // `at`: position in the sub-list as if it had no end
+        unsigned long long* to = nullptr;
+        if (at < shard_cap) to = region + static_cast<size_t>(shard) * shard_cap + at;
+        else if (spill_base + (at - from) < spill_cap) to = region + L.mem_cap + spill_base + (at - from);
+        if (to != nullptr) __hip_atomic_store(to, c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      };
+      uint32_t at = base + (nm_incl - nm);
+      if (__ballot(nm > 2u) == 0ull) {
+        if (nm >= 1u) put(at, keep0);
+        if (nm >= 2u) put(at + 1u, keep1);
       } else {
-        unsigned long long* out = region + static_cast<size_t>(shard) * shard_cap + base + (nm_incl - nm);
-        if (__ballot(nm > 2u) == 0ull) {
-          if (nm >= 1u) __hip_atomic_store(out, keep0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          if (nm >= 2u) __hip_atomic_store(out + 1, keep1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        } else {
-          for (uint32_t p = lane; p < cnt; p += kWaveSize) {
-            const uint2 e = slot[p];
-            const uint32_t key = key_of(e.x, A.sign_xor, A.sign_filter);
-            if (coarse_bin(key, tau, shift) == bstar)
-              __hip_atomic_store(out++, composite(key, e.y), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          }
+        for (uint32_t p = lane; p < cnt; p += kWaveSize) {
+          const uint2 e = slot[p];
+          const uint32_t key = key_of(e.x, A.sign_xor, A.sign_filter);
+          if (coarse_bin(key, tau, shift) == bstar) put(at++, composite(key, e.y));
         }
       }
     }
@@ -1607,32 +1645,24 @@ __device__ void dense_rank(const CompressArgs& A, uint32_t l, const LayerDesc& L
 
   if (threadIdx.x == 0) {
     uint32_t run = 0;
-    for (uint32_t s = 0; s < kMemberShards; ++s) {
-      const uint32_t c = ld_agent(&A.shard_cnt[(static_cast<size_t>(l) * kMemberShards + s) * kShardStride]);
+    for (uint32_t s = 0; s < kMemberLists; ++s) {
+      const uint32_t c = ld_agent(&A.shard_cnt[(static_cast<size_t>(l) * kMemberLists + s) * kShardStride]);
+      const uint32_t cap = s < kMemberShards ? shard_cap : spill_cap;
       shard_first[s] = run;
-      run += c < shard_cap ? c : shard_cap;
+      run += c < cap ? c : cap;
     }
-    shard_first[kMemberShards] = run;
+    shard_first[kMemberLists] = run;
   }
   __syncthreads();
-  const uint32_t m = shard_first[kMemberShards];
+  const uint32_t m = shard_first[kMemberLists];
   const uint32_t k_rem = st->k_rem;
-  if (ld_agent(&st->shard_overflow) != 0u || k_rem == 0u || k_rem > m) {
-    // A sub-list ran over (the members crowd in a few wave-chunks), or the lists and the histogram disagree (a bug,
-    // flagged).  What the streaming pass masked is put back by the next launch and the layer goes on hint-free.
-    if (threadIdx.x == 0) {
-      if (ld_agent(&st->shard_overflow) == 0u) atomicOr(A.errflag, 32u);
-      st->path = 2u;
-      st->stat_misses += 1u;
-      dense_missed(st);
-      st->next_phase = PH_RESTORE;
-      st->next_launch = A.launch + 1u;
-    }
-    return;
+  if (k_rem == 0u || k_rem > m) {
+    if (threadIdx.x == 0) atomicOr(A.errflag, 32u);
+    return;   // cannot happen when the histogram and the lists agree; leave the layer unscheduled
   }
   MemberLists M{region, shard_cap, shard_first};
   unsigned long long any = 0ull;
-  for (uint32_t s = 0; s < kMemberShards; ++s)
+  for (uint32_t s = 0; s < kMemberLists; ++s)
     if (shard_first[s + 1] != shard_first[s]) { any = __hip_atomic_load(&region[static_cast<size_t>(s) * shard_cap], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); break; }
   const unsigned long long thr = select_kth_largest_global(M, any, k_rem, sel_hist, sh);
   // members not below thr are selected: credit them to their wave-chunks and to the chunks' groups
@@ -1756,42 +1786,12 @@ __device__ void dense_emit(const CompressArgs& A, const LayerDesc& L, LayerState
   if (wc_local == 0 && lane == 0) *as_global(L.out_count) = static_cast<int32_t>(L.k);
 }
 
-// PH_RESTORE: the entries the streaming pass masked (coarse bin not below the clip bin) get their accumulated value
-// and their velocity back from the lists; the layer's last workgroup then starts the multi-pass path.
-__device__ void dense_restore(const CompressArgs& A, const LayerDesc& L, LayerState* st, uint32_t wg, ResolveShared& sh) {
-  const uint32_t wc_local = (wg - L.wg_first) * kWavesPerBlock + (threadIdx.x >> 6);
-  if (wc_local < L.wc_count) {
-    const uint32_t mask_key = st->cur_mask_key;
-    const bool clear_mom = (L.mom != nullptr) && A.mask_momentum;
-    const gptr<float> resid = as_global(L.resid);
-    const gptr<float> mom = as_global(L.mom);
-    const size_t list = L.list_first + static_cast<size_t>(wc_local) * L.list_cap;
-    const gptr<const vu2> slot = as_global(reinterpret_cast<const vu2*>(A.slots2 + list));
-    const gptr<const float> slot_u = as_global(static_cast<const float*>(A.slots_u + list));
-    uint32_t cnt = A.cand_cnt[L.wc_first + wc_local] & ~kListStopped;   // (a list that stopped early: what it held by then)
-    cnt = cnt < L.list_cap ? cnt : L.list_cap;
-    for (uint32_t p = lane_id(); p < cnt; p += kWaveSize) {
-      const vu2 e = slot[p];
-      const uint32_t key = key_of(e.x, A.sign_xor, A.sign_filter);
-      if (key >= mask_key && e.y < L.n) {
-        resid[e.y] = __uint_as_float(e.x);
-        if (clear_mom) mom[e.y] = slot_u[p];
-      }
-    }
-  }
-  if (!last_block_of_layer(&st->done, A.group_done + L.grp_first, wg - L.wg_first, L.wg_count, &sh.flag)) return;
-  if (threadIdx.x == 0) {
-    st->next_phase = PH_HIST1;
-    st->next_launch = A.launch + 1u;
-  }
-}
-
 }  // namespace
 
 __global__ void __launch_bounds__(kBlockThreads) lists_kernel(CompressArgs A) {
   __shared__ ResolveShared sh;
   __shared__ __attribute__((aligned(16))) uint32_t sel_hist[3 * 256];
-  __shared__ uint32_t shard_first[kMemberShards + 1];
+  __shared__ uint32_t shard_first[kMemberLists + 1];
   const uint32_t wg = blockIdx.x;
   const uint32_t l = A.wg2layer[wg];
   LayerState* st = A.state + l;
@@ -1800,7 +1800,6 @@ __global__ void __launch_bounds__(kBlockThreads) lists_kernel(CompressArgs A) {
   switch (st->next_phase) {
     case PH_SEL2: dense_rank(A, l, L, st, wg, sh, sel_hist, shard_first); break;
     case PH_EMIT: dense_emit(A, L, st, wg); break;
-    case PH_RESTORE: dense_restore(A, L, st, wg, sh); break;
     default: break;                                   // the other phases belong to phase_kernel
   }
 }
@@ -2080,8 +2079,8 @@ hipError_t launch_lists(const CompressArgs& a, uint32_t num_wgs, hipStream_t s) 
   return hipGetLastError();
 }
 
-hipError_t launch_phase(const CompressArgs& a, uint32_t num_wgs, bool every_phase, hipStream_t s) {
-  if (a.launch >= kFirstLateLaunch && !every_phase) hipLaunchKernelGGL(phase_late_kernel, dim3(num_wgs), dim3(kBlockThreads), 0, s, a);
+hipError_t launch_phase(const CompressArgs& a, uint32_t num_wgs, hipStream_t s) {
+  if (a.launch >= kFirstLateLaunch) hipLaunchKernelGGL(phase_late_kernel, dim3(num_wgs), dim3(kBlockThreads), 0, s, a);
   else hipLaunchKernelGGL(phase_kernel, dim3(num_wgs), dim3(kBlockThreads), 0, s, a);
   return hipGetLastError();
 }

@@ -29,7 +29,8 @@ enum Phase : uint32_t {
   PH_COUNT = 6,    // multi-pass: per wave-chunk counts of keys > T and == T
   PH_OUT_V = 7,    // multi-pass: ordered compaction from the updated residual
   PH_COLLECT = 8,  // after the first digit: candidate lists from the updated residual, then PH_SEL / PH_OUT_C
-  PH_RESTORE = 9,  // dense layers whose hint missed: the entries masked on the strength of the hint go back into residual and velocity
+  PH_RESTORE = 9,  // dense layers whose hint missed: the entries masked on the strength of the hint go back into residual and
+                   // velocity, then PH_HIST1 in the same launch
   PH_EMIT = 10,    // dense layers: the message from the lists, with the k-th entry known
   PH_SEL2 = 11,    // dense layers: PH_SEL on the layer's own lists (lists_kernel)
 };
@@ -38,8 +39,10 @@ enum Phase : uint32_t {
 // doubles with every further miss, up to this many.
 constexpr uint32_t kDenseBackoffMax = 64;
 // Dense layers: the members of the k-th key's coarse bin are appended to this many sub-lists, each with a counter
-// of its own (thousands of waves appending through one counter take their turns at ~20 ns each).
+// of its own (thousands of waves appending through one counter take their turns at ~20 ns each), and what a
+// sub-list cannot hold to one more list that can hold them all.
 constexpr uint32_t kMemberShards = 16;
+constexpr uint32_t kMemberLists = kMemberShards + 1;
 constexpr uint32_t kShardStride = 64;    // words between two counters: atomics on one cache line take their turns like atomics on one word
 
 // Per call, per layer descriptor (device copy of the caller's rgc_layer plus the tiling).
@@ -64,7 +67,8 @@ struct LayerDesc {
   uint32_t target;     // rank the next call's threshold hint is aimed at (2k + margin, dense layers: k + margin)
   uint32_t dense;      // high-density layer (never set together with hintable): with a hint, its streaming pass lists every
                        // candidate in lists of its own and masks those far enough above the hinted threshold at once
-  uint32_t mem_cap;    // dense layers: entries of the layer's region of the member pool (a multiple of kMemberShards)
+  uint32_t mem_cap;    // dense layers: entries of the layer's kMemberShards sub-lists together (a multiple of kMemberShards); the
+                       // overflow list behind them holds mem_cap / 4, which is also the most members a call accepts
   uint32_t list_cap;   // dense layers: entries of one wave-chunk's list
   uint32_t pad_;
   uint64_t mem_first;  // dense layers: where the layer's region of the member pool starts
@@ -100,7 +104,6 @@ struct LayerState {
   uint32_t clip;             // candidates of the coarse bins from this one upwards are sure to be selected: counted, not ranked
   uint32_t dense_backoff;    // calls the layer went without its hint after the last miss
   uint32_t dense_skip;       // calls it still goes without it
-  uint32_t shard_overflow;   // a member sub-list ran over in this call's ranking launch
   uint32_t cur_tau;          // tau, shift and mask_key as this call's streaming pass used them (the ranking step rewrites
   uint32_t cur_shift;        // the hint for the next call before the output step has read it)
   uint32_t cur_mask_key;
@@ -140,7 +143,7 @@ struct CompressArgs {
   uint2* slots2;         // the lists of the dense layers (LayerDesc::list_first, list_cap; allocated when such a layer is first seen)
   float* slots_u;        // the velocity of every listed element, same layout (restores a masked entry after a miss)
   unsigned long long* members2;  // member pool of the dense layers (LayerDesc::mem_first, mem_cap)
-  uint32_t* shard_cnt;   // [layers][kMemberShards][kShardStride] members appended to each sub-list, one counter per 256 bytes
+  uint32_t* shard_cnt;   // [layers][kMemberLists][kShardStride] members appended to each sub-list, one counter per 256 bytes
   uint32_t* group_done;  // [election groups] workgroups of the group that finished the current phase
   uint32_t* errflag;     // set non-zero on an internal inconsistency
   uint32_t chunk;        // elements per wave-chunk (multiple of 256)
@@ -244,9 +247,8 @@ int fail_hip(hipError_t e, const char* what);
 // kernel launchers (defined in the .hip files)
 hipError_t launch_accumulate(const CompressArgs& a, uint32_t num_wgs, hipStream_t s);
 hipError_t launch_collect(const CompressArgs& a, uint32_t num_wgs, hipStream_t s);   // streaming pass of the dense layers
-hipError_t launch_lists(const CompressArgs& a, uint32_t num_wgs, hipStream_t s);     // their ranking, output and restoring steps
-// every_phase: the launch may meet any phase (calls with dense layers, whose fall-back starts later)
-hipError_t launch_phase(const CompressArgs& a, uint32_t num_wgs, bool every_phase, hipStream_t s);
+hipError_t launch_lists(const CompressArgs& a, uint32_t num_wgs, hipStream_t s);     // their ranking and output steps
+hipError_t launch_phase(const CompressArgs& a, uint32_t num_wgs, hipStream_t s);
 constexpr uint32_t kMeanPartsMax = 128;    // parts per layer at most (rgc_message_means)
 hipError_t launch_message_means(const CompressArgs& a, uint32_t num_layers, uint32_t max_k, const ExactParts& parts,
                                 float* d_means, hipStream_t s);
