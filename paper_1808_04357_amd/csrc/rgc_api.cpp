@@ -252,7 +252,7 @@ int build_compress_plan(rgc_ctx* ctx, CompressPlan& P, const rgc_layer* layers, 
     d.list_cap = 0;
     d.list_first = 0;
     d.pad_ = 0;
-    if (!d.hintable && d.wc_count >= 2) {
+    if (!d.hintable) {
       // High densities (the warm-up period of Section 2.5): the short lists of the one-pass path cannot hold every
       // element from the threshold upwards.  Such a layer gets lists of its own, long enough for twice the number of
       // candidates aimed at, and its hint is aimed at rank k + margin and accepted from rank k to rank k + 2 margin.
