@@ -22,7 +22,8 @@
  * Stream capture: the first call that shows a context a new list of layers (or of messages)
  * allocates device tables and uploads them; a repeated call with the same descriptors only
  * launches kernels (rgc_message_means, rgc_clip_coefficient and rgc_compress_layers_threshold
- * also allocate a scratch array on their first use).  After one eager call of the same function
+ * also allocate a scratch array on their first use, and so does rgc_compress_layers for layers
+ * that select more than about 2 % of their elements or more than 2^20 entries).  After one eager call of the same function
  * with the same descriptors, rgc_compress_layers (and its _scaled and _threshold forms),
  * rgc_message_means, rgc_clip_coefficient and rgc_decompress_accumulate may therefore be
  * recorded into a HIP graph on a capturing stream and replayed: all that changes
