@@ -263,7 +263,8 @@ int build_compress_plan(rgc_ctx* ctx, CompressPlan& P, const rgc_layer* layers, 
       if (k + 2 * margin2 < d.n) {
         const uint64_t aimed_per_chunk = ((k + margin2) * kChunk + span - 1) / span;
         d.dense = 1;
-        d.list_cap = static_cast<uint32_t>(std::min<uint64_t>(kChunk, (2 * aimed_per_chunk + 64 + 63) / 64 * 64));
+        // (twice the number aimed at, and the 256 slots a wave wants to see free before it lists another group)
+        d.list_cap = static_cast<uint32_t>(std::min<uint64_t>(kChunk, (2 * aimed_per_chunk + 256 + 64 + 63) / 64 * 64));
         d.list_first = lists;
         lists += static_cast<uint64_t>(d.wc_count) * d.list_cap;
         d.mem_cap = static_cast<uint32_t>(std::max<uint64_t>(4096, d.n / 64) / kMemberShards * kMemberShards);

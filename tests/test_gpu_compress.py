@@ -226,6 +226,32 @@ def test_dense_layers_clustered_values_overflow_single_lists(rgc, oracle):
     run_iterations(rgc, oracle, V, G_list, ks, tag="dense clustered")
 
 
+def test_dense_layer_whose_kth_key_is_a_long_tie(rgc, oracle):
+    """The k-th key is shared by more than a thousand elements, call after call, and they sit in five wave-chunks whose
+    members go to the same sub-list: the streaming pass masks them all (their key is the expected k-th key), the ranking
+    takes more members than that sub-list holds, the lowest indices win, and the output step puts the others back."""
+    g = np.random.default_rng(79)
+    n, k = 400_000, 25_000
+    per_step = 100
+    c = np.float32(0.25)
+    # 300 tied elements in each of the wave-chunks 5, 21, 37, 53, 69 (of 4096 elements)
+    tie = np.concatenate([np.arange(w * 4096 + 7, w * 4096 + 307) for w in (5, 21, 37, 53, 69)])
+    rest = np.setdiff1d(np.arange(n), tie)
+    large = np.sort(g.choice(rest, size=k - per_step, replace=False))   # sent on every call, and large again on the next
+    V = np.zeros(n, np.float32)
+    V[rest] = (g.standard_normal(rest.size) * 1e-2).astype(np.float32)  # well below the tied value
+    V[tie] = c
+    V[tie[::7]] = -c                                                    # the tie is one of magnitudes
+    V[large] = 0.0
+    G_list = []
+    for _ in range(9):
+        G = np.zeros(n, np.float32)
+        G[large] = (1.0 + g.random(large.size)).astype(np.float32) * g.choice([-1.0, 1.0], size=large.size).astype(np.float32)
+        G_list.append([G])
+    paths = run_iterations(rgc, oracle, [V], G_list, [k], tag="dense tie")
+    assert sum(1 for p in paths[1:] if p == [0]) >= 4, "the hinted path of the dense layer was hardly taken: %r" % (paths,)
+
+
 @pytest.mark.parametrize("ppm", [250_000, 15_625])
 def test_config3_vgg16_set_full_size_warmup_density(rgc, oracle, ppm):
     """The VGG16-shaped set with the momentum correction at a warm-up density, at full size (the configuration
