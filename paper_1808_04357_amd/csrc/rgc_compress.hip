@@ -1559,27 +1559,27 @@ __device__ void dense_rank(const CompressArgs& A, uint32_t l, const LayerDesc& L
   __syncthreads();
   if (wc_local < L.wc_count) {
     const uint32_t wc = L.wc_first + wc_local;
-    const uint2* slot = A.slots2 + L.list_first + static_cast<size_t>(wc_local) * L.list_cap;
+    const gptr<const vu2> slot = as_global(reinterpret_cast<const vu2*>(A.slots2 + L.list_first + static_cast<size_t>(wc_local) * L.list_cap));
     // One walk through the list, eight entries of a lane on their way at a time (every round trip counts); the
     // first eight are asked for together with the list's length (the slots exist whatever the length), the next
     // eight while these are looked at.  A lane keeps the first two members it meets; the wave then appends all its
     // members with ONE atomic, and only a wave in which some lane met more walks again.
     constexpr uint32_t kBatch = 8;
-    uint2 e[kBatch];
+    vu2 e[kBatch];
 #pragma unroll
     for (uint32_t j = 0; j < kBatch; ++j) {
       const uint32_t p = j * kWaveSize + lane;
-      e[j] = p < L.list_cap ? slot[p] : make_uint2(0u, 0u);
+      e[j] = p < L.list_cap ? slot[p] : vu2{0u, 0u};
     }
     const uint32_t cnt = A.cand_cnt[wc];               // (<= list_cap: the streaming pass's resolve step has checked)
     uint32_t hi = 0, nm = 0;
     unsigned long long keep0 = 0ull, keep1 = 0ull;
     for (uint32_t p0 = 0; p0 < cnt; p0 += kBatch * kWaveSize) {
-      uint2 nx[kBatch];
+      vu2 nx[kBatch];
 #pragma unroll
       for (uint32_t j = 0; j < kBatch; ++j) {
         const uint32_t p = p0 + (kBatch + j) * kWaveSize + lane;
-        nx[j] = p < cnt ? slot[p] : make_uint2(0u, 0u);
+        nx[j] = p < cnt ? slot[p] : vu2{0u, 0u};
       }
 #pragma unroll
       for (uint32_t j = 0; j < kBatch; ++j) {
@@ -1625,7 +1625,7 @@ __device__ void dense_rank(const CompressArgs& A, uint32_t l, const LayerDesc& L
         if (nm >= 2u) put(at + 1u, keep1);
       } else {
         for (uint32_t p = lane; p < cnt; p += kWaveSize) {
-          const uint2 e = slot[p];
+          const vu2 e = slot[p];
           const uint32_t key = key_of(e.x, A.sign_xor, A.sign_filter);
           if (coarse_bin(key, tau, shift) == bstar) put(at++, composite(key, e.y));
         }

@@ -32,7 +32,7 @@ def test_random_configurations(rgc, oracle):
         g = np.random.default_rng(770_000 + it)
         L = int(g.integers(1, 7))
         sizes = [int(g.choice([1, 3, 63, 64, 255, 256, 257, 1000, 4095, 4096, 8191, 8193, 33000, 100_003, 400_000, 1_500_000])) for _ in range(L)]
-        ppm = int(g.choice([100, 1000, 1000, 10_000, 100_000]))
+        ppm = int(g.choice([100, 1000, 1000, 10_000, 100_000, 250_000]))
         ks = [rgc.rgc_k_for_density(n, ppm) for n in sizes]
         mom = bool(g.integers(0, 2)); nest = mom and bool(g.integers(0, 2))
         mode = int(g.integers(0, 4))      # 0 plain,1 asq alternating, 2 threshold, 3 plain no hints
