@@ -17,6 +17,13 @@ extern "C" {
  * benchmark times a call whose hints miss. */
 int rgc_poison_hints(rgc_ctx* ctx, int mode, void* hip_stream);
 
+/* Caps the scratch that compression calls allocate on demand for layers that select a large share of
+ * their elements (their candidate lists; see rgc.h, "Stream capture"): a call that would need more than
+ * `max_bytes` does not ask for it, as if the device were short of memory, and those layers take the
+ * hint-free path.  Results do not change.  A negative value lifts the cap.  Frees what is held beyond
+ * the cap (after a device synchronisation). */
+int rgc_limit_optional_scratch(rgc_ctx* ctx, int64_t max_bytes);
+
 /* Runs a one-workgroup kernel that checks the wave64 primitives the kernels rely on (DPP
  * prefix scan, ballot ranks) against values computed on the host.  Synchronises `hip_stream`.
  * Returns RGC_OK, RGC_EINTERNAL on a mismatch, or RGC_EHIP. */

@@ -34,7 +34,7 @@ _LIB_PATH = os.path.join(_HERE, "librgc.so")
 EXPORTS = ["rgc_create", "rgc_destroy", "rgc_k_for_density", "rgc_compress_layers",
            "rgc_compress_layers_scaled", "rgc_clip_coefficient", "rgc_message_means", "rgc_message_means_noalloc",
            "rgc_compress_layers_threshold",
-           "rgc_decompress_accumulate", "rgc_reset_hints", "rgc_poison_hints", "rgc_selftest",
+           "rgc_decompress_accumulate", "rgc_reset_hints", "rgc_poison_hints", "rgc_limit_optional_scratch", "rgc_selftest",
            "rgc_last_paths", "rgc_last_stats", "rgc_last_error", "rgc_decompress_status", "rgc_profile_enable", "rgc_profile_read", "rgc_strerror"]
 
 
@@ -107,6 +107,8 @@ def load_library() -> ctypes.CDLL:
                                             ctypes.c_uint32, ctypes.c_void_p]
     L.rgc_reset_hints.restype = ctypes.c_int
     L.rgc_reset_hints.argtypes = [ctypes.c_void_p]
+    L.rgc_limit_optional_scratch.restype = ctypes.c_int
+    L.rgc_limit_optional_scratch.argtypes = [ctypes.c_void_p, ctypes.c_int64]
     L.rgc_poison_hints.restype = ctypes.c_int
     L.rgc_poison_hints.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
     L.rgc_selftest.restype = ctypes.c_int
@@ -173,6 +175,9 @@ class Context:
 
     def reset_hints(self) -> None:
         _check(self._lib.rgc_reset_hints(self._h))
+
+    def limit_optional_scratch(self, max_bytes: int) -> None:
+        _check(self._lib.rgc_limit_optional_scratch(self._h, int(max_bytes)))
 
     def poison_hints(self, mode: int, stream=None) -> None:
         _check(self._lib.rgc_poison_hints(self._h, int(mode), _stream(stream)))

@@ -172,6 +172,7 @@ struct rgc_ctx {
   DevBuf<uint32_t> d_shards;               // their sub-list counters (first use)
   CompressPlan plans[kPlanCache];
   uint64_t tick = 0;
+  int64_t optional_scratch_cap = -1;       // bytes the dense layers' lists may take (diagnostics); negative: no cap
   bool compressed_since_decompress = false;
   uint64_t compress_calls = 0;             // its parity is the direction of the next streaming pass
   uint32_t threshold_reverse = 0;          // direction of the next threshold-selection call's first pass
@@ -461,6 +462,20 @@ int rgc_reset_hints(rgc_ctx* ctx) {
   return RGC_OK;
 }
 
+int rgc_limit_optional_scratch(rgc_ctx* ctx, int64_t max_bytes) {
+  if (!ctx) return RGC_EINVAL;
+  DeviceGuard guard(ctx->device);
+  ctx->optional_scratch_cap = max_bytes;
+  const uint64_t held = ctx->d_slots2.n * (sizeof(uint2) + sizeof(float)) + ctx->d_members2.n * sizeof(unsigned long long);
+  if (max_bytes >= 0 && ctx->d_slots2.p && held > static_cast<uint64_t>(max_bytes)) {
+    RGC_HIP(hipDeviceSynchronize());
+    ctx->d_slots2.release();
+    ctx->d_slots_u.release();
+    ctx->d_members2.release();
+  }
+  return RGC_OK;
+}
+
 int rgc_poison_hints(rgc_ctx* ctx, int mode, void* hip_stream) {
   if (!ctx || mode < 0 || mode > 2) return RGC_EINVAL;
   DeviceGuard guard(ctx->device);
@@ -693,11 +708,14 @@ int rgc_compress_layers_scaled(rgc_ctx* ctx, const rgc_layer* layers, int32_t nu
   A.use_hints = (sig_same && !no_hints) ? 1u : 0u;
   A.update_hints = no_hints ? 0u : 1u;
   A.mask_momentum = (flags & RGC_NO_MOMENTUM_MASK) ? 0u : 1u;
-  const bool dense = plan->any_dense && A.use_hints;
+  // The lists of dense layers are allocated by the first call that shows the context a plan with such layers (or one
+  // that needs longer lists; hipFree waits for the kernels that may still use the old ones).  Without them (the device
+  // is short of memory) those layers simply take the hint-free path, as they would on a first call.
+  bool dense_ok = plan->any_dense;
   if (plan->any_dense && (ctx->d_slots2.n < plan->list_entries || ctx->d_members2.n < plan->member_entries || !ctx->d_shards.p)) {
-    // the first call that shows the context a plan with such layers (or one that needs longer lists): hipFree
-    // waits for the kernels that may still use the old ones
-    hipError_t e = ctx->d_slots2.alloc(plan->list_entries);
+    const uint64_t want = plan->list_entries * (sizeof(uint2) + sizeof(float)) + plan->member_entries * sizeof(unsigned long long);
+    const bool capped = ctx->optional_scratch_cap >= 0 && want > static_cast<uint64_t>(ctx->optional_scratch_cap);
+    hipError_t e = capped ? hipErrorOutOfMemory : ctx->d_slots2.alloc(plan->list_entries);
     if (e == hipSuccess) e = ctx->d_slots_u.alloc(plan->list_entries);
     if (e == hipSuccess) e = ctx->d_members2.alloc(plan->member_entries);
     if (e == hipSuccess && !ctx->d_shards.p) e = ctx->d_shards.alloc(static_cast<size_t>(ctx->max_layers) * kMemberLists * kShardStride);
@@ -706,10 +724,13 @@ int rgc_compress_layers_scaled(rgc_ctx* ctx, const rgc_layer* layers, int32_t nu
       ctx->d_slots_u.release();
       ctx->d_members2.release();
       ctx->d_shards.release();
-      if (e == hipErrorOutOfMemory) { (void)hipGetLastError(); return RGC_ENOMEM; }
-      return fail_hip(e, "scratch allocation for dense layers");
+      if (e != hipErrorOutOfMemory) return fail_hip(e, "scratch allocation for dense layers");
+      (void)hipGetLastError();
+      dense_ok = false;
     }
   }
+  A.dense_ok = dense_ok ? 1u : 0u;
+  const bool dense = dense_ok && A.use_hints;
   A.slots2 = ctx->d_slots2.p;
   A.slots_u = ctx->d_slots_u.p;
   A.members2 = ctx->d_members2.p;

@@ -718,7 +718,7 @@ __global__ void __launch_bounds__(kBlockThreads) accumulate_kernel(CompressArgs 
   LayerState* st = A.state + l;
   // (with a sign filter a threshold of 0 would let the elements that key_of() ranks last and equal into the lists)
   const bool hinted = A.use_hints && (st->hint_valid != 0u) && !(A.sign_filter != 0u && st->tau == 0u);
-  if (L.dense && hinted && st->dense_skip == 0u) return;     // collect_kernel has this layer
+  if (A.dense_ok && L.dense && hinted && st->dense_skip == 0u) return;     // collect_kernel has this layer
   const bool collect = hinted && L.hintable;
   // the same LDS array serves as 4096-bin digit histogram (hint-free) or 1024-bin coarse one
   const uint32_t lds_bins = collect ? static_cast<uint32_t>(kCoarseBins) : static_cast<uint32_t>(kHistBins);

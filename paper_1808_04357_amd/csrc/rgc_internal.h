@@ -149,6 +149,7 @@ struct CompressArgs {
   uint32_t chunk;        // elements per wave-chunk (multiple of 256)
   uint32_t cap;          // candidate slots per wave-chunk
   uint32_t use_hints;
+  uint32_t dense_ok;     // the lists of the dense layers exist: such a layer may take its hinted path (collect_kernel)
   uint32_t update_hints;
   uint32_t mask_momentum;
   float m;

@@ -226,6 +226,34 @@ def test_dense_layers_clustered_values_overflow_single_lists(rgc, oracle):
     run_iterations(rgc, oracle, V, G_list, ks, tag="dense clustered")
 
 
+def test_dense_layers_without_their_scratch_take_the_hint_free_path(rgc, oracle):
+    """The lists of the dense layers are allocated on demand; when they cannot be had (here: capped to nothing) the
+    layers take the hint-free path call after call and the results are the same; with the cap lifted the same
+    context goes on to the hinted path."""
+    g = np.random.default_rng(81)
+    sizes = [300_000, 40_960]
+    ks = [rgc.rgc_k_for_density(n, 62_500) for n in sizes]
+    V = [(g.laplace(size=n) * 1e-3).astype(np.float32) for n in sizes]
+    G_list = [[(g.laplace(size=n) * 1e-2).astype(np.float32) for n in sizes] for _ in range(10)]
+    ctx = rgc.Context(sum(sizes), len(sizes))
+    ctx.limit_optional_scratch(0)
+    dev = GpuLayers(rgc, V, ks)
+    Vh = [v.copy() for v in V]
+    paths = []
+    for t, G in enumerate(G_list):
+        if t == 4:
+            ctx.limit_optional_scratch(-1)
+        dev.set_grads(G)
+        dev.step(ctx, 0.0, 0)
+        msgs = oracle_step(oracle, G, Vh, ks)
+        assert_layers_equal("capped scratch step %d" % t, ks, dev.results(), msgs, Vh)
+        paths.append(ctx.last_paths(len(sizes)))
+    assert all(p == [1, 1] for p in paths[:4]), paths
+    assert any(p[0] == 0 for p in paths[4:]), paths
+    ctx.last_error()
+    ctx.close()
+
+
 def test_dense_layer_whose_kth_key_is_a_long_tie(rgc, oracle):
     """The k-th key is shared by more than a thousand elements, call after call, and they sit in five wave-chunks whose
     members go to the same sub-list: the streaming pass masks them all (their key is the expected k-th key), the ranking
