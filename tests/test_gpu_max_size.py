@@ -55,8 +55,9 @@ def check_selection(torch, tag, a_ref, k, out_idx, out_val, out_count, V_new):
 
 @pytest.mark.parametrize("ppm,k_expected", [(1000, 2_147_484), (100, 214_749)])
 def test_compress_largest_tensor(rgc, ppm, k_expected):
-    """Density 0.1 %: more than a million entries are selected, such a layer always takes the
-    multi-pass path.  Density 0.01 %: the hinted one-pass path runs from the second or third call on."""
+    """Density 0.1 %: more than a million entries are selected, too many for the one-pass path's ranking: the
+    layer is a dense one, with lists of its own once it has a hint.  Density 0.01 %: the hinted one-pass path runs
+    from the second or third call on."""
     import torch
     dev = torch.device("cuda:0")
     gen = torch.Generator(device=dev)
