@@ -310,6 +310,16 @@ def test_config3_vgg16_set_full_size_warmup_density(rgc, oracle, ppm):
     ctx.close()
 
 
+def test_config4_lstm_set_full_size_warmup_density(rgc, oracle):
+    """The LSTM-shaped set at full size at 6.25 %: the embedding tensor is three quarters zeros (row-sparse gradient
+    and residual), the layers are dense ones and reach their hinted path within a few calls."""
+    cfg = synth.config_lstm(num_grads=4)
+    ks = [rgc.rgc_k_for_density(v.size, 62_500) for v in cfg["V"]]
+    G_list = [cfg["G"][t % 4] for t in range(5)]
+    paths = run_iterations(rgc, oracle, cfg["V"], G_list, ks, tag="C4 62500 ppm", threads=16)
+    assert any(p.count(0) >= 5 for p in paths[1:]), "the dense layers never took their hinted path: %r" % (paths,)
+
+
 def test_config2_resnet50_set(rgc, oracle):
     cfg = synth.config_resnet50(num_grads=3)
     ks = [rgc.rgc_k_for_density(v.size) for v in cfg["V"]]
