@@ -38,6 +38,7 @@ namespace {
     if (e_ != hipSuccess) return fail_hip(e_, #call);   \
   } while (0)
 
+constexpr uint32_t kSmallCallWorkgroups = 256;   // one workgroup per compute unit
 constexpr uint32_t kChunkSmallest = 4096;  // elements per wave-chunk for small layer sets
 // Candidate slots per wave-chunk = chunk / 16: sixty times the average number of candidates of a chunk at
 // density 0.1 %.  Tensors whose large values sit in a few rows (embedding gradients) fill single lists far
@@ -739,6 +740,8 @@ int rgc_compress_layers_scaled(rgc_ctx* ctx, const rgc_layer* layers, int32_t nu
   ++ctx->compress_calls;
   ctx->compressed_since_decompress = true;
   A.nesterov = (flags & RGC_NESTEROV) ? 1u : 0u;
+  // a call that leaves most of the device idle spreads its candidate lists over as many workgroups as it has
+  A.list_group = plan->num_wgs <= kSmallCallWorkgroups ? 1u : kListGroup;
   A.grad_scale = grad_scale;
   A.m = momentum;
   A.launch = 1;

@@ -697,8 +697,6 @@ __device__ unsigned long long select_kth_largest(const unsigned long long* v, ui
   return r;
 }
 
-constexpr uint32_t kListGroup = 4;   // workgroups' worth of candidate lists one workgroup of PH_SEL / PH_OUT_C takes
-
 __device__ __forceinline__ unsigned long long composite(uint32_t key, uint32_t idx) {
   return (static_cast<unsigned long long>(key) << 32) | static_cast<unsigned long long>(0xFFFFFFFFu - idx);
 }
@@ -967,10 +965,11 @@ __device__ void phase_out_v(const CompressArgs& A, const LayerDesc& L, LayerStat
 __device__ void phase_sel(const CompressArgs& A, uint32_t l, const LayerDesc& L, LayerState* st, uint32_t wg,
                           unsigned long long* sortbuf, uint32_t* sel_hist, ResolveShared& sh) {
   // The lists are short (a few dozen entries), so this phase is a chain of dependent loads per
-  // workgroup and little else: one workgroup in kListGroup takes the lists of kListGroup
+  // workgroup and little else: one workgroup in A.list_group takes the lists of that many
   // workgroups, with the loads of all of them in flight together; the others leave at once.
   const uint32_t wgl = wg - L.wg_first;
-  if (wgl % kListGroup != 0u) return;
+  const uint32_t group = A.list_group, group_log2 = group == 1u ? 0u : kListGroupLog2;   // (1 or kListGroup)
+  if ((wgl & (group - 1u)) != 0u) return;
   const uint32_t tau = st->tau, shift = st->shift, bstar = st->bstar;
   unsigned long long* members = A.members + static_cast<size_t>(l) * kMemberMax;
   const uint32_t lane = lane_id(), wave = threadIdx.x >> 6;
@@ -981,7 +980,7 @@ __device__ void phase_sel(const CompressArgs& A, uint32_t l, const LayerDesc& L,
   for (uint32_t i = 0; i < kListGroup; ++i) {
     const uint32_t wc_local = (wgl + i) * kWavesPerBlock + wave;
     wc[i] = L.wc_first + wc_local;
-    cnt[i] = wc_local < L.wc_count ? A.cand_cnt[wc[i]] : 0xFFFFFFFFu;   // ~0: no such list
+    cnt[i] = (i < group && wc_local < L.wc_count) ? A.cand_cnt[wc[i]] : 0xFFFFFFFFu;   // ~0: no such list
   }
   // the first 64 slots of every list are asked for together with the lists' lengths, not after them
   // (the slots exist whatever the length; what lies beyond it is not looked at)
@@ -989,7 +988,7 @@ __device__ void phase_sel(const CompressArgs& A, uint32_t l, const LayerDesc& L,
 #pragma unroll
   for (uint32_t i = 0; i < kListGroup; ++i) {
     first[i] = make_uint2(0u, 0u);
-    if ((wgl + i) * kWavesPerBlock + wave < L.wc_count && lane < A.cap) first[i] = (A.slots + static_cast<size_t>(wc[i]) * A.cap)[lane];
+    if (i < group && (wgl + i) * kWavesPerBlock + wave < L.wc_count && lane < A.cap) first[i] = (A.slots + static_cast<size_t>(wc[i]) * A.cap)[lane];
   }
 #pragma unroll
   for (uint32_t i = 0; i < kListGroup; ++i) {
@@ -1021,8 +1020,8 @@ __device__ void phase_sel(const CompressArgs& A, uint32_t l, const LayerDesc& L,
   // on one address take their turns at a fraction of a microsecond each
   __syncthreads();
   if (threadIdx.x == 0 && sh.hcnt != 0u) atomicAdd(&A.wc_b[L.wc_first + (wgl * kWavesPerBlock) / kOffsetGroup], sh.hcnt);
-  if (!last_block_of_layer(&st->done, A.group_done + L.grp_first, wgl / kListGroup,
-                           (L.wg_count + kListGroup - 1u) / kListGroup, &sh.flag)) return;
+  if (!last_block_of_layer(&st->done, A.group_done + L.grp_first, wgl >> group_log2,
+                           (L.wg_count + group - 1u) >> group_log2, &sh.flag)) return;
 
   const uint32_t m = ld_agent(&st->nmembers);
   const uint32_t k_rem = st->k_rem;
@@ -1108,7 +1107,8 @@ __device__ void phase_sel(const CompressArgs& A, uint32_t l, const LayerDesc& L,
 
 __device__ void phase_out_c(const CompressArgs& A, const LayerDesc& L, LayerState* st, uint32_t wg) {
   const uint32_t wgl = wg - L.wg_first;
-  if (wgl % kListGroup != 0u) return;               // see phase_sel
+  const uint32_t group = A.list_group;              // (1 or kListGroup)
+  if ((wgl & (group - 1u)) != 0u) return;           // see phase_sel
   const unsigned long long thr = st->thr;
   const uint32_t lane = lane_id(), wave = threadIdx.x >> 6;
   const bool clear_mom = (L.mom != nullptr) && A.mask_momentum;
@@ -1132,7 +1132,7 @@ __device__ void phase_out_c(const CompressArgs& A, const LayerDesc& L, LayerStat
     cnt[i] = 0u;
     out_at[i] = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(excl),
                                                                  static_cast<int>(__builtin_amdgcn_readfirstlane(wc_local % kOffsetGroup))));
-    if (wc_local < L.wc_count) cnt[i] = A.cand_cnt[wc[i]];
+    if (i < group && wc_local < L.wc_count) cnt[i] = A.cand_cnt[wc[i]];
   }
   uint2 first[kListGroup];
 #pragma unroll
@@ -1557,13 +1557,16 @@ __device__ void dense_rank(const CompressArgs& A, uint32_t l, const LayerDesc& L
   const uint32_t wc_local = (wg - L.wg_first) * kWavesPerBlock + (threadIdx.x >> 6);
   if (threadIdx.x == 0) sh.hcnt = 0u;              // what this workgroup's lists add to their offset group
   __syncthreads();
-  if (wc_local < L.wc_count) {
-    const uint32_t wc = L.wc_first + wc_local;
-    const gptr<const vu2> slot = as_global(reinterpret_cast<const vu2*>(A.slots2 + L.list_first + static_cast<size_t>(wc_local) * L.list_cap));
+  const bool have = wc_local < L.wc_count;
+  const uint32_t wc = L.wc_first + wc_local;
+  const gptr<const vu2> slot = as_global(reinterpret_cast<const vu2*>(A.slots2 + L.list_first + static_cast<size_t>(have ? wc_local : 0u) * L.list_cap));
+  uint32_t cnt = 0, hi = 0, nm = 0;
+  unsigned long long keep0 = 0ull, keep1 = 0ull;
+  if (have) {
     // One walk through the list, eight entries of a lane on their way at a time (every round trip counts); the
     // first eight are asked for together with the list's length (the slots exist whatever the length), the next
-    // eight while these are looked at.  A lane keeps the first two members it meets; the wave then appends all its
-    // members with ONE atomic, and only a wave in which some lane met more walks again.
+    // eight while these are looked at.  A lane keeps the first two members it meets; only a wave in which some
+    // lane met more walks again.
     constexpr uint32_t kBatch = 8;
     vu2 e[kBatch];
 #pragma unroll
@@ -1571,9 +1574,7 @@ __device__ void dense_rank(const CompressArgs& A, uint32_t l, const LayerDesc& L
       const uint32_t p = j * kWaveSize + lane;
       e[j] = p < L.list_cap ? slot[p] : vu2{0u, 0u};
     }
-    const uint32_t cnt = A.cand_cnt[wc];               // (<= list_cap: the streaming pass's resolve step has checked)
-    uint32_t hi = 0, nm = 0;
-    unsigned long long keep0 = 0ull, keep1 = 0ull;
+    cnt = A.cand_cnt[wc];                              // (<= list_cap: the streaming pass's resolve step has checked)
     for (uint32_t p0 = 0; p0 < cnt; p0 += kBatch * kWaveSize) {
       vu2 nx[kBatch];
 #pragma unroll
@@ -1597,40 +1598,54 @@ __device__ void dense_rank(const CompressArgs& A, uint32_t l, const LayerDesc& L
 #pragma unroll
       for (uint32_t j = 0; j < kBatch; ++j) e[j] = nx[j];
     }
-    const uint32_t nm_incl = wave_incl_scan(nm);
-    const uint32_t nm_all = wave_total(nm_incl);
-    if (nm_all != 0u) {
-      // the wave's members go to its sub-list as far as that has room, the others to the overflow list (which can
+  }
+  // The members of the workgroup's four lists are appended to its sub-list with ONE device-scope atomic (such
+  // atomics on one address take their turns): the waves' counts meet in LDS, thread 0 reserves the room.
+  const uint32_t wave = threadIdx.x >> 6;
+  const uint32_t nm_incl = wave_incl_scan(nm);
+  const uint32_t nm_all = wave_total(nm_incl);
+  if (lane == 0) sh.scan[wave] = nm_all;
+  __syncthreads();
+  const uint32_t shard = (wg - L.wg_first) % kMemberShards;
+  if (threadIdx.x == 0) {
+    const uint32_t wg_all = sh.scan[0] + sh.scan[1] + sh.scan[2] + sh.scan[3];
+    uint32_t base = 0, spill_base = 0;
+    if (wg_all != 0u) {
+      // the members go to the sub-list as far as that has room, the others to the overflow list (which can
       // hold every member the streaming pass's resolve step accepts): no sub-list is left with a gap
-      const uint32_t shard = wc_local % kMemberShards;
-      uint32_t base = 0, spill_base = 0;
-      if (lane == 0) {
-        base = atomicAdd(&A.shard_cnt[(static_cast<size_t>(l) * kMemberLists + shard) * kShardStride], nm_all);
-        const uint32_t from = base > shard_cap ? base : shard_cap;
-        if (base + nm_all > from)
-          spill_base = atomicAdd(&A.shard_cnt[(static_cast<size_t>(l) * kMemberLists + kMemberShards) * kShardStride], base + nm_all - from);
-      }
-      base = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(base)));
-      spill_base = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(spill_base)));
+      base = atomicAdd(&A.shard_cnt[(static_cast<size_t>(l) * kMemberLists + shard) * kShardStride], wg_all);
       const uint32_t from = base > shard_cap ? base : shard_cap;
-      auto put = [&](uint32_t at, unsigned long long c) {        // `at`: position in the sub-list as if it had no end
-        unsigned long long* to = nullptr;
-        if (at < shard_cap) to = region + static_cast<size_t>(shard) * shard_cap + at;
-        else if (spill_base + (at - from) < spill_cap) to = region + L.mem_cap + spill_base + (at - from);
-        if (to != nullptr) __hip_atomic_store(to, c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      };
-      uint32_t at = base + (nm_incl - nm);
-      if (__ballot(nm > 2u) == 0ull) {
-        if (nm >= 1u) put(at, keep0);
-        if (nm >= 2u) put(at + 1u, keep1);
-      } else {
-        for (uint32_t p = lane; p < cnt; p += kWaveSize) {
-          const vu2 e = slot[p];
-          const uint32_t key = key_of(e.x, A.sign_xor, A.sign_filter);
-          if (coarse_bin(key, tau, shift) == bstar) put(at++, composite(key, e.y));
-        }
+      if (base + wg_all > from)
+        spill_base = atomicAdd(&A.shard_cnt[(static_cast<size_t>(l) * kMemberLists + kMemberShards) * kShardStride], base + wg_all - from);
+    }
+    sh.bin = base;
+    sh.above = spill_base;
+  }
+  __syncthreads();
+  if (nm_all != 0u) {
+    const uint32_t wg_base = sh.bin, spill_base = sh.above;
+    uint32_t before = 0;                               // members of the workgroup's waves before this one
+    for (uint32_t w = 0; w < wave; ++w) before += sh.scan[w];
+    const uint32_t from = wg_base > shard_cap ? wg_base : shard_cap;
+    auto put = [&](uint32_t at, unsigned long long c) {        // `at`: position in the sub-list as if it had no end
+      unsigned long long* to = nullptr;
+      if (at < shard_cap) to = region + static_cast<size_t>(shard) * shard_cap + at;
+      else if (spill_base + (at - from) < spill_cap) to = region + L.mem_cap + spill_base + (at - from);
+      if (to != nullptr) __hip_atomic_store(to, c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    };
+    uint32_t at = wg_base + before + (nm_incl - nm);
+    if (__ballot(nm > 2u) == 0ull) {
+      if (nm >= 1u) put(at, keep0);
+      if (nm >= 2u) put(at + 1u, keep1);
+    } else {
+      for (uint32_t p = lane; p < cnt; p += kWaveSize) {
+        const vu2 e = slot[p];
+        const uint32_t key = key_of(e.x, A.sign_xor, A.sign_filter);
+        if (coarse_bin(key, tau, shift) == bstar) put(at++, composite(key, e.y));
       }
     }
+  }
+  if (have) {
     const uint32_t hi_all = wave_total(wave_incl_scan(hi));
     if (lane == 0) {
       st_agent(&A.wc_a[wc], hi_all);

@@ -37,6 +37,9 @@ enum Phase : uint32_t {
 
 // Dense layers: after a call whose hint missed, the layer goes without its hint for a number of calls that
 // doubles with every further miss, up to this many.
+// Workgroups' worth of candidate lists one workgroup of PH_SEL / PH_OUT_C takes (CompressArgs::list_group:
+// kListGroup, or 1 for a call whose workgroups all fit on the device at once, where spreading the lists wins).
+constexpr uint32_t kListGroupLog2 = 2, kListGroup = 1u << kListGroupLog2;
 constexpr uint32_t kDenseBackoffMax = 64;
 // Dense layers: the members of the k-th key's coarse bin are appended to this many sub-lists, each with a counter
 // of its own (thousands of waves appending through one counter take their turns at ~20 ns each), and what a
@@ -158,6 +161,7 @@ struct CompressArgs {
   uint32_t sign_filter;  // 0: every element ranks by magnitude; ~0: elements of the other sign rank last (key 0)
   uint32_t reverse;      // the streaming pass takes its workgroups in descending order
   uint32_t nesterov;     // momentum correction in its Nesterov form: u = m (u + g), a = (V + u) + g
+  uint32_t list_group;   // workgroups' worth of candidate lists one workgroup of PH_SEL / PH_OUT_C takes (1 or 4)
   const float* grad_scale;   // device word every gradient element is multiplied with first, or null
   ExactParts norm_parts; // [workgroups] parts of the sum of squares (clipping coefficient only)
 };

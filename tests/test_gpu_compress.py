@@ -255,15 +255,16 @@ def test_dense_layers_without_their_scratch_take_the_hint_free_path(rgc, oracle)
 
 
 def test_dense_layer_whose_kth_key_is_a_long_tie(rgc, oracle):
-    """The k-th key is shared by more than a thousand elements, call after call, and they sit in five wave-chunks whose
-    members go to the same sub-list: the streaming pass masks them all (their key is the expected k-th key), the ranking
-    takes more members than that sub-list holds, the lowest indices win, and the output step puts the others back."""
+    """The k-th key is shared by more than a thousand elements, call after call, and they sit in five wave-chunks of two
+    workgroups whose members go to the same sub-list: the streaming pass masks them all (their key is the expected k-th
+    key), the ranking takes more members than that sub-list holds, the lowest indices win, and the output step puts the
+    others back."""
     g = np.random.default_rng(79)
     n, k = 400_000, 25_000
     per_step = 100
     c = np.float32(0.25)
-    # 300 tied elements in each of the wave-chunks 5, 21, 37, 53, 69 (of 4096 elements)
-    tie = np.concatenate([np.arange(w * 4096 + 7, w * 4096 + 307) for w in (5, 21, 37, 53, 69)])
+    # 300 tied elements in each of the wave-chunks 4, 5, 6, 7 and 69 (of 4096 elements): workgroups 1 and 17 of the layer
+    tie = np.concatenate([np.arange(w * 4096 + 7, w * 4096 + 307) for w in (4, 5, 6, 7, 69)])
     rest = np.setdiff1d(np.arange(n), tie)
     large = np.sort(g.choice(rest, size=k - per_step, replace=False))   # sent on every call, and large again on the next
     V = np.zeros(n, np.float32)
