@@ -115,6 +115,37 @@ def time_loop(torch, fn, steps):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
+def measure_yardstick(torch, rgc, ctx, wl, dec, stream, dev, reps):
+    """rgc_stream_yardstick on tensors of the workload's total size: u = m u + g, V += u and nothing else."""
+    g = torch.randn(wl.total, dtype=torch.float32, device=dev) * 1e-3
+    v = torch.zeros(wl.total, dtype=torch.float32, device=dev)
+    u = torch.zeros(wl.total, dtype=torch.float32, device=dev)
+    calls = [0]
+
+    def bare():
+        rgc.rgc_stream_yardstick(g, v, u, wl.m, calls[0] & 1, stream)     # alternating direction, like the compress calls
+        calls[0] += 1
+
+    for _ in range(5):
+        bare()
+    ms_b2b = time_loop(torch, bare, reps)
+    evs = []
+    for _ in range(reps):
+        dec.step(ctx, stream)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        bare()
+        b.record(stream)
+        evs.append((a, b))
+    torch.cuda.synchronize()
+    ms_after = sum(a.elapsed_time(b) for a, b in evs) / reps
+    bytes_ = 20.0 * wl.total
+    return {"kernel": "yardstick_kernel (reads G, V, u and writes V, u of the same total size; no selection work)",
+            "back_to_back_ms": ms_b2b, "back_to_back_GBps": bytes_ / ms_b2b / 1e6,
+            "after_decompress_ms": ms_after, "after_decompress_GBps": bytes_ / ms_after / 1e6,
+            "frac_of_peak_after_decompress": bytes_ / (ms_after * 1e-3) / (HBM_PEAK_GBPS * 1e9)}
+
+
 def measure_threshold(torch, rgc, ctx, wl, stream, steps, dev):
     """A call that searches the thresholds, a call that reuses them, and the paper's schedule (search every
     fifth call) on the workload's tensors; message buffers of 2k entries."""
@@ -461,6 +492,14 @@ def main():
             roofline["traffic_source"] = "profiles/hbm_traffic.json was taken with other kernel sources: not used"
     except (OSError, ValueError, KeyError):
         pass
+
+    # what the dominant kernel's traffic costs by itself on this device: the library's bare kernel of the same
+    # reads and writes (no selection work), back to back like the compress loop above and, like the kernel in
+    # the step, after a decompression call each time
+    if not args.step_only:
+        roofline["bare_kernel_same_traffic"] = measure_yardstick(torch, rgc, ctx, vgg, dec, stream, dev, min(args.steps, 30))
+        bare = roofline["bare_kernel_same_traffic"]
+        roofline["time_vs_bare_kernel"] = k_ms / bare["after_decompress_ms"]     # 1.03: 3 % more time than the traffic alone
 
     # the step before the accumulate when gradients are clipped locally (Section 2.4): one read of all gradients
     clip_info = None

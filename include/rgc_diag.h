@@ -1,6 +1,6 @@
 /* rgc_diag.h -- diagnostics, test hooks and benchmark timers of the RGC library (see rgc.h for the
  * library itself).  Nothing here changes a result; none of it belongs on a training step's path: every
- * call below except rgc_profile_enable synchronises the stream it is given.
+ * call below except rgc_profile_enable and rgc_stream_yardstick synchronises the stream it is given.
  */
 #ifndef RGC_DIAG_H_
 #define RGC_DIAG_H_
@@ -51,6 +51,17 @@ int rgc_last_stats(rgc_ctx* ctx, int64_t* out, int32_t num_layers, void* hip_str
  * number of compression / decompression calls in out_calls[0..1].  The record is then cleared. */
 int rgc_profile_enable(rgc_ctx* ctx, int enable);
 int rgc_profile_read(rgc_ctx* ctx, double* out_ms, int64_t* out_calls);
+
+/* A yardstick for the streaming pass of the compression call (Algorithm 1's accumulate with the momentum
+ * correction of Section 2.5): one kernel that reads `grad`, `residual` and `velocity` (device pointers, n fp32
+ * elements each, 16-byte aligned, the caller's) and writes  velocity = momentum * velocity + grad,
+ * residual = residual + velocity  back in place -- the 20 bytes per element of that pass and none of its
+ * selection work, with the same decomposition (one wave per 8192 consecutive elements; `reverse` != 0 walks the
+ * tensors from the far end, as every other compression call does).  A benchmark times it to learn what share of
+ * the HBM peak this mix of reads and writes reaches on the device at all.  Launches on the current device and
+ * `hip_stream`, does not synchronise, needs no context.  RGC_EINVAL: null or misaligned pointer, n < 1. */
+int rgc_stream_yardstick(const float* grad, float* residual, float* velocity, int64_t n, float momentum,
+                         int reverse, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -10,6 +10,6 @@ from .binding import (  # noqa: F401
     RGC_SELECT_LARGEST, RGC_SELECT_SMALLEST, RGC_STATUS_INDEX_ORDER, RGC_STATUS_INDEX_RANGE,
     RGC_THRESHOLD_SEARCH, RGC_VALIDATE, Context, LayerList, MessageList, RgcError, library_path,
     load_library, rgc_clip_coefficient, rgc_compress_layers, rgc_compress_layers_scaled,
-    rgc_compress_layers_threshold, rgc_decompress_accumulate, rgc_k_for_density, rgc_message_means, rgc_message_means_noalloc,
+    rgc_compress_layers_threshold, rgc_decompress_accumulate, rgc_k_for_density, rgc_message_means, rgc_message_means_noalloc, rgc_stream_yardstick,
     RGC_NOALLOC_MAX_LAYERS,
 )

@@ -35,7 +35,7 @@ EXPORTS = ["rgc_create", "rgc_destroy", "rgc_k_for_density", "rgc_compress_layer
            "rgc_compress_layers_scaled", "rgc_clip_coefficient", "rgc_message_means", "rgc_message_means_noalloc",
            "rgc_compress_layers_threshold",
            "rgc_decompress_accumulate", "rgc_reset_hints", "rgc_poison_hints", "rgc_limit_optional_scratch", "rgc_selftest",
-           "rgc_last_paths", "rgc_last_stats", "rgc_last_error", "rgc_decompress_status", "rgc_profile_enable", "rgc_profile_read", "rgc_strerror"]
+           "rgc_last_paths", "rgc_last_stats", "rgc_last_error", "rgc_decompress_status", "rgc_profile_enable", "rgc_profile_read", "rgc_stream_yardstick", "rgc_strerror"]
 
 
 class RgcError(RuntimeError):
@@ -125,6 +125,9 @@ def load_library() -> ctypes.CDLL:
     L.rgc_profile_enable.argtypes = [ctypes.c_void_p, ctypes.c_int]
     L.rgc_profile_read.restype = ctypes.c_int
     L.rgc_profile_read.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+    L.rgc_stream_yardstick.restype = ctypes.c_int
+    L.rgc_stream_yardstick.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_float,
+                                       ctypes.c_int, ctypes.c_void_p]
     L.rgc_strerror.restype = ctypes.c_char_p
     L.rgc_strerror.argtypes = [ctypes.c_int]
     _lib = L
@@ -300,6 +303,12 @@ def rgc_message_means_noalloc(values: Sequence, counts, capacity: Sequence[int],
     cp = (ctypes.c_void_p * max(L, 1))(*[base + 4 * l for l in range(L)])
     cap = (ctypes.c_int32 * max(L, 1))(*[int(c) for c in capacity])
     _check(load_library().rgc_message_means_noalloc(vp, cp, cap, L, _ptr(means), _stream(stream)))
+
+
+def rgc_stream_yardstick(grad, residual, velocity, momentum: float, reverse: bool = False, stream=None) -> None:
+    """grad, residual, velocity: float32 device tensors of one length; residual and velocity are updated in place."""
+    _check(load_library().rgc_stream_yardstick(_ptr(grad), _ptr(residual), _ptr(velocity), int(grad.numel()),
+                                               float(momentum), int(bool(reverse)), _stream(stream)))
 
 
 def rgc_clip_coefficient(ctx: Context, layers: LayerList, max_norm: float, num_workers: int, coefficient,

@@ -12,7 +12,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librgc.so")
-SOURCES = ["rgc_api.cpp", "rgc_compress.hip", "rgc_decompress.hip", "rgc_threshold.hip"]
+SOURCES = ["rgc_api.cpp", "rgc_compress.hip", "rgc_decompress.hip", "rgc_threshold.hip", "rgc_yardstick.hip"]
 HEADERS = ["rgc_internal.h", "rgc_device.h", "rgc_exact.h", os.path.join("..", "..", "include", "rgc.h"),
            os.path.join("..", "..", "include", "rgc_diag.h")]
 

@@ -518,3 +518,25 @@ def test_clipping_coefficient_full_size_vgg16(rgc, oracle):
     c_gpu = float(coef.cpu().numpy()[0])
     assert c_ref < 1.0 and ulp_distance(c_gpu, c_ref) == 0, (c_gpu, c_ref, sq)
     ctx.close()
+
+
+def test_stream_yardstick_computes_the_bare_update(rgc):
+    """The benchmark's yardstick kernel does the momentum-corrected accumulate and nothing else: compared with the two
+    fp32 operations written out in numpy (no contraction on either side), ragged lengths, both directions."""
+    import torch
+    g = np.random.default_rng(90)
+    for n in (1, 3, 4, 255, 8192, 8193, 4 * 8192 + 2, 100_003):
+        G = (g.standard_normal(n) * 1e-3).astype(np.float32)
+        V = (g.standard_normal(n) * 1e-2).astype(np.float32)
+        U = (g.standard_normal(n) * 1e-3).astype(np.float32)
+        m = np.float32(0.9)
+        dg, dv, du = (torch.from_numpy(a).cuda() for a in (G, V, U))
+        for t in range(2):
+            print("  yardstick n %d call %d" % (n, t), flush=True)
+            rgc.rgc_stream_yardstick(dg, dv, du, float(m), reverse=bool(t))
+            U = (m * U).astype(np.float32) + G
+            V = V + U
+        torch.cuda.synchronize()
+        assert np.array_equal(u32(du.cpu().numpy()), u32(U)) and np.array_equal(u32(dv.cpu().numpy()), u32(V)), n
+    with pytest.raises(rgc.RgcError):
+        rgc.rgc_stream_yardstick(dg[1:], dv[1:], du[1:], 0.9)          # not 16-byte aligned
