@@ -472,6 +472,32 @@ def main():
                     "alg_bytes": dec.alg_bytes,
                     "hbm_frac_algorithmic": dec.alg_bytes / (ms_dec * 1e-3) / (HBM_PEAK_GBPS * 1e9),
                     "table_kernel_ms": ms4[2] / max(calls[1], 1), "tile_kernel_ms": ms4[3] / max(calls[1], 1)}
+        # what writing the dense output costs by itself in the step's position: a plain fill of one tensor of the
+        # same size (PyTorch's kernel) between two compression calls, and when fills follow each other
+        fill_out = torch.empty(vgg.total, dtype=torch.float32, device=dev)
+        for _ in range(3):
+            fill_out.fill_(0.0)
+        ms_fill = time_loop(torch, lambda: fill_out.fill_(0.0), min(args.steps, 20))
+        evs = []
+        for _ in range(min(args.steps, 20)):
+            vgg.step(ctx, stream)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            fill_out.fill_(0.0)
+            b.record(stream)
+            evs.append((a, b))
+        torch.cuda.synchronize()
+
+        def step_with_fill():
+            vgg.step(ctx, stream)
+            fill_out.fill_(0.0)
+
+        ms_step_fill = time_loop(torch, step_with_fill, min(args.steps, 20))
+        dec_info["plain_fill_of_output_size"] = {"back_to_back_ms": ms_fill,
+                                                 "after_compress_ms": sum(a.elapsed_time(b) for a, b in evs) / len(evs),
+                                                 "step_with_fill_in_place_of_decompress_ms": ms_step_fill,
+                                                 "bytes": 4 * vgg.total}
+        del fill_out
     k_ms = step_ms4[0] / max(step_calls[0], 1)          # accumulate_kernel inside the timed steps
     achieved = vgg.alg_bytes_stream / (k_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": "accumulate_kernel (fused residual/momentum accumulate + candidate collect)",
