@@ -91,3 +91,26 @@ def test_product_package_does_not_import_the_oracle():
                 src = open(os.path.join(dirpath, f)).read()
                 assert "import oracle" not in src and "from oracle" not in src, f
                 assert "rgc_oracle" not in src, f
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build has no collectives: the benchmark says so instead of running a second rank."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_hbm_traffic_figures_are_stamped_with_the_current_kernel_sources():
+    """roofline.traffic comes from counter runs that cannot share a process with the timed run; the committed
+    figures carry the digest of the kernel sources they were taken with, and the benchmark drops them when the
+    sources have changed since.  This checks that the committed pair is in step."""
+    import json
+    import sys
+    sys.path.insert(0, ROOT)
+    import bench
+    with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
+        t = json.load(f)
+    assert t["kernel_source_sha256"] == bench.kernel_source_digest()
+    assert 0 < t["fetch_bytes_per_launch"] < 4e9 and 0 < t["write_bytes_per_launch"] < 4e9
