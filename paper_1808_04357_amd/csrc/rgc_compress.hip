@@ -1253,8 +1253,15 @@ __global__ void __launch_bounds__(kBlockThreads) phase_late_kernel(CompressArgs 
 namespace {
 
 // What the streaming pass of a dense layer keeps per wave-chunk beside the Collector.
+// The list entries pass through a staging area in LDS of the wave's own: appended one by one to global memory they
+// would cost up to eight sparse store instructions per group of 256 elements (and leave cache lines partly written);
+// from the staging area they go out 64 at a time, one full 512-byte store per array.
+constexpr uint32_t kStageEntries = 5u * kWaveSize;   // what a flush leaves (< 64) plus one group's candidates (<= 256)
 struct DenseChunk {
-  gptr<float> slot_u;   // the velocity of the listed elements that are masked at once (null: the velocity is not masked)
+  gptr<float> slot_u;   // the velocity of the listed elements (null: the velocity is not masked, nothing is kept)
+  vu2* stage;           // [kStageEntries] in LDS: the list's entries from number `flushed` on
+  float* stage_u;       // [kStageEntries] their velocities
+  uint32_t flushed;     // entries of the list that are in global memory already (a multiple of 64 until the end)
   uint32_t mask_key;    // candidates with keys from here upwards are masked at once (where the k-th key is expected)
   uint32_t clip_key;    // candidates with keys from here upwards lie in the coarse bins from the clip bin upwards: sure to be selected
   uint32_t certain;     // how many candidates from clip_key upwards this lane has seen (they enter the histogram's top bin in one
@@ -1273,28 +1280,57 @@ __device__ __forceinline__ void masked_dense(const float (&a)[4], uint32_t nvali
   }
 }
 
+// Writes the staged entries [0, n) (n <= 64) behind the list's flushed part.  Lanes read what other lanes of the wave
+// staged: the wave barriers keep the compiler from moving LDS accesses across them (the hardware keeps a wave's LDS
+// operations in order).
+__device__ __forceinline__ void flush_staged(Collector& c, DenseChunk& dc, uint32_t from, uint32_t n) {
+  const uint32_t lane = lane_id();
+  if (lane < n) {
+    c.slot[dc.flushed + lane] = dc.stage[from + lane];
+    if (dc.slot_u != nullptr) dc.slot_u[dc.flushed + lane] = dc.stage_u[from + lane];
+  }
+}
+
 // Appends the group's candidates to the wave-chunk's list in index order (the caller has seen that 256 more
 // entries fit).  The candidates of the band (keys below clip_key) enter the coarse histogram one by one.
 __device__ __forceinline__ void list_dense(const float (&a)[4], const float (&u)[4], const uint32_t (&key)[4],
-                                           const bool (&masked)[4], uint32_t nvalid, uint32_t idx0, Collector& c,
-                                           DenseChunk& dc) {
+                                           uint32_t nvalid, uint32_t idx0, Collector& c, DenseChunk& dc) {
   bool cand[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) cand[j] = (static_cast<uint32_t>(j) < nvalid) && (key[j] >= c.tau);
   const unsigned long long m0 = __ballot(cand[0]), m1 = __ballot(cand[1]), m2 = __ballot(cand[2]), m3 = __ballot(cand[3]);
   if ((m0 | m1 | m2 | m3) == 0ull) return;
-  uint32_t pos = c.count + rank_below(m0) + rank_below(m1) + rank_below(m2) + rank_below(m3);
+  uint32_t pos = (c.count - dc.flushed) + rank_below(m0) + rank_below(m1) + rank_below(m2) + rank_below(m3);
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     if (cand[j]) {
-      c.slot[pos] = vu2{fbits(a[j]), idx0 + j};
-      if (masked[j] && dc.slot_u != nullptr) dc.slot_u[pos] = u[j];
+      dc.stage[pos] = vu2{fbits(a[j]), idx0 + j};
+      if (dc.slot_u != nullptr) dc.stage_u[pos] = u[j];
       if (key[j] >= dc.clip_key) ++dc.certain;
       else atomicAdd(&c.coarse[coarse_bin(key[j], c.tau, c.shift)], 1u);
       ++pos;
     }
   }
   c.count += popc64(m0) + popc64(m1) + popc64(m2) + popc64(m3);
+  uint32_t pend = c.count - dc.flushed;               // wave-uniform
+  if (pend >= kWaveSize) {
+    __builtin_amdgcn_wave_barrier();
+    uint32_t from = 0;
+    do {
+      flush_staged(c, dc, from, kWaveSize);
+      from += kWaveSize;
+      dc.flushed += kWaveSize;
+      pend -= kWaveSize;
+    } while (pend >= kWaveSize);
+    // what is left moves to the front of the staging area
+    const uint32_t lane = lane_id();
+    vu2 e = vu2{0u, 0u};
+    float eu = 0.0f;
+    if (lane < pend) { e = dc.stage[from + lane]; eu = dc.stage_u[from + lane]; }
+    __builtin_amdgcn_wave_barrier();
+    if (lane < pend) { dc.stage[lane] = e; dc.stage_u[lane] = eu; }
+    __builtin_amdgcn_wave_barrier();
+  }
 }
 
 // Streaming pass over one wave-chunk [begin, end) of a dense layer that has a hint: stream_chunk's loop, with the
@@ -1325,7 +1361,7 @@ __device__ __forceinline__ void stream_chunk_dense(const LayerDesc& L, uint32_t 
       if constexpr (kMom)
         U4[o] = vf4{(masked[0] && clear_mom) ? 0.0f : uu[0], (masked[1] && clear_mom) ? 0.0f : uu[1],
                     (masked[2] && clear_mom) ? 0.0f : uu[2], (masked[3] && clear_mom) ? 0.0f : uu[3]};
-      if (!dc.overflow) list_dense(a, uu, key, masked, 4u, begin + o * 4u, c, dc);
+      if (!dc.overflow) list_dense(a, uu, key, 4u, begin + o * 4u, c, dc);
     };
     uint32_t g = 0;
     for (; g + kUnroll <= nfull; g += kUnroll) {
@@ -1379,8 +1415,12 @@ __device__ __forceinline__ void stream_chunk_dense(const LayerDesc& L, uint32_t 
         if constexpr (kMom) Us[idx0 + j] = (masked[j] && clear_mom) ? 0.0f : uu[j];
       }
     }
-    if (!dc.overflow) list_dense(a, uu, key, masked, nvalid, idx0, c, dc);
+    if (!dc.overflow) list_dense(a, uu, key, nvalid, idx0, c, dc);
   }
+  // the list's last entries (fewer than 64)
+  __builtin_amdgcn_wave_barrier();
+  flush_staged(c, dc, 0u, c.count - dc.flushed);
+  dc.flushed = c.count;
 }
 
 }  // namespace
@@ -1389,6 +1429,8 @@ __device__ __forceinline__ void stream_chunk_dense(const LayerDesc& L, uint32_t 
 __global__ void __launch_bounds__(kBlockThreads) collect_kernel(CompressArgs A) {
   __shared__ uint32_t lds_hist[kCoarseBins];
   __shared__ ResolveShared sh;
+  __shared__ vu2 stage[kWavesPerBlock][kStageEntries];
+  __shared__ float stage_u[kWavesPerBlock][kStageEntries];
   const uint32_t wg = A.reverse ? gridDim.x - 1u - blockIdx.x : blockIdx.x;
   const uint32_t l = A.wg2layer[wg];
   const LayerDesc L = A.layers[l];
@@ -1419,6 +1461,9 @@ __global__ void __launch_bounds__(kBlockThreads) collect_kernel(CompressArgs A) 
     DenseChunk dc;
     // (the velocity is kept only where the masking clears it)
     dc.slot_u = clear_mom ? as_global(A.slots_u + list) : gptr<float>(nullptr);
+    dc.stage = stage[threadIdx.x >> 6];
+    dc.stage_u = stage_u[threadIdx.x >> 6];
+    dc.flushed = 0u;
     dc.clip_key = dense_clip_key(c.tau, c.shift, c.clip);
     dc.mask_key = dense_mask_key(st->mask_key, c.tau);
     dc.certain = 0u;
